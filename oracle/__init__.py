@@ -1,0 +1,156 @@
+"""CPU oracle for the MERIT hot path -- TEST INFRASTRUCTURE ONLY.
+
+`merit_oracle.c` holds the plain nested-loop definitions (conv2d, pool2d,
+sad_search); this module compiles it with gcc into `libmerit_oracle.so` and
+wraps it with ctypes over numpy arrays.  `merit_literal.py` is a second,
+separately written evaluator that materialises the transformed tensors of
+Section III-C, Eq. 5 literally and reduces their rows (tiny inputs only).
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import
+this package.  It never imports the HIP package, and the HIP package never
+imports it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "merit_oracle.c")
+_LIB = os.path.join(_HERE, "libmerit_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain C, -O2, OpenMP over the outer loop)."""
+    if (not force and os.path.exists(_LIB)
+            and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
+        return _LIB
+    cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp",
+           "-ffp-contract=off", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build()
+    lib = ctypes.CDLL(_LIB)
+    c_int = ctypes.c_int
+    vp = ctypes.c_void_p
+    lib.ref_half_to_double.restype = ctypes.c_double
+    lib.ref_half_to_double.argtypes = [ctypes.c_uint16]
+    lib.ref_double_to_half.restype = ctypes.c_uint16
+    lib.ref_double_to_half.argtypes = [ctypes.c_double]
+    lib.ref_conv2d.restype = c_int
+    lib.ref_conv2d.argtypes = [vp, vp, vp] + [c_int] * 11
+    lib.ref_pool2d.restype = c_int
+    lib.ref_pool2d.argtypes = [vp, vp] + [c_int] * 11
+    lib.ref_sad_search.restype = c_int
+    lib.ref_sad_search.argtypes = [vp, vp, vp, vp] + [c_int] * 4
+    lib.ref_sad_surface.restype = c_int
+    lib.ref_sad_surface.argtypes = [vp, vp, vp] + [c_int] * 6
+    lib.ref_sad_candidate.restype = ctypes.c_int32
+    lib.ref_sad_candidate.argtypes = [vp, vp] + [c_int] * 7
+    lib.ref_num_threads.restype = c_int
+    lib.ref_set_num_threads.argtypes = [c_int]
+    _lib = lib
+    return lib
+
+
+def _ptr(a: np.ndarray):
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def _c(a, dtype):
+    a = np.ascontiguousarray(a)
+    if a.dtype != dtype:
+        raise TypeError(f"expected {dtype}, got {a.dtype}")
+    return a
+
+
+def num_threads() -> int:
+    return int(_load().ref_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    _load().ref_set_num_threads(int(n))
+
+
+def half_to_double(bits: int) -> float:
+    return float(_load().ref_half_to_double(int(bits)))
+
+
+def double_to_half(v: float) -> int:
+    return int(_load().ref_double_to_half(float(v)))
+
+
+def out_extent(I: int, k: int, s: int, p: int) -> int:
+    """floor((I + 2p - k) / s) + 1 -- number of window positions along one axis."""
+    return (I + 2 * p - k) // s + 1
+
+
+def conv2d(x: np.ndarray, w: np.ndarray, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
+    """x fp16 [N,Cin,H,W], w fp16 [Cout,Cin,kh,kw] -> fp16 [N,Cout,OH,OW]."""
+    x = _c(x, np.float16)
+    w = _c(w, np.float16)
+    N, Cin, H, W = x.shape
+    Cout, Cin2, kh, kw = w.shape
+    if Cin2 != Cin:
+        raise ValueError("channel mismatch")
+    sh, sw = stride
+    ph, pw = pad
+    y = np.empty((N, Cout, out_extent(H, kh, sh, ph), out_extent(W, kw, sw, pw)), np.float16)
+    rc = _load().ref_conv2d(_ptr(x), _ptr(w), _ptr(y), N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw)
+    if rc != 0:
+        raise ValueError("ref_conv2d: bad shape")
+    return y
+
+
+def pool2d(x: np.ndarray, kernel=(3, 3), stride=(2, 2), pad=(1, 1), mode="max") -> np.ndarray:
+    """x fp32 [N,C,H,W] -> fp32 [N,C,OH,OW]; mode 'max' or 'avg' (padding excluded)."""
+    x = _c(x, np.float32)
+    N, C, H, W = x.shape
+    kh, kw = kernel
+    sh, sw = stride
+    ph, pw = pad
+    y = np.empty((N, C, out_extent(H, kh, sh, ph), out_extent(W, kw, sw, pw)), np.float32)
+    rc = _load().ref_pool2d(_ptr(x), _ptr(y), N, C, H, W, kh, kw, sh, sw, ph, pw,
+                            {"max": 0, "avg": 1}[mode])
+    if rc != 0:
+        raise ValueError("ref_pool2d: bad shape")
+    return y
+
+
+def sad_search(cur: np.ndarray, ref: np.ndarray, block: int, search: int):
+    """cur, ref u8 [H,W] -> (sad int32 [nby,nbx], mv int32 [nby,nbx,2] = (dy,dx))."""
+    cur = _c(cur, np.uint8)
+    ref = _c(ref, np.uint8)
+    H, W = cur.shape
+    if ref.shape != (H, W):
+        raise ValueError("frame shape mismatch")
+    nby, nbx = H // block, W // block
+    sad = np.empty((nby, nbx), np.int32)
+    mv = np.empty((nby, nbx, 2), np.int32)
+    rc = _load().ref_sad_search(_ptr(cur), _ptr(ref), _ptr(sad), _ptr(mv), H, W, block, search)
+    if rc != 0:
+        raise ValueError("ref_sad_search: bad shape")
+    return sad, mv
+
+
+def sad_surface(cur: np.ndarray, ref: np.ndarray, block: int, search: int, by: int, bx: int):
+    """All candidate SADs of one block as int32 [(2R+1),(2R+1)] indexed [dy+R, dx+R]."""
+    cur = _c(cur, np.uint8)
+    ref = _c(ref, np.uint8)
+    H, W = cur.shape
+    n = 2 * search + 1
+    out = np.empty((n, n), np.int32)
+    rc = _load().ref_sad_surface(_ptr(cur), _ptr(ref), _ptr(out), H, W, block, search, by, bx)
+    if rc != 0:
+        raise ValueError("ref_sad_surface: bad arguments")
+    return out

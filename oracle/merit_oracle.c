@@ -1,0 +1,267 @@
+/*
+ * CPU oracle for the MERIT ranged inner-product hot path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition of what
+ * the HIP library must compute.  Nothing in the product path may call it: only
+ * the test-suite, the smoke check and the benchmark's cpu_baseline leg do.  It
+ * shares no code, header, table or helper with the HIP sources.
+ *
+ * Every operation here is an instance of the paper's row-wise reduction
+ *     Vec(C) = R(M(A), M(B), (.))                         (Section III, Eq. 1)
+ * where M(.) gathers, for output index p and accumulation index a, the input
+ * element at x_i = sum_j delta(i,d_j) (k_j s_j + o_j), k=(p,a)  (Section III-C,
+ * Eq. 5), and (.) is one of
+ *     dot product  v1^T v2                                (Section III-B, Eq. 3)
+ *     L1 distance  ||v1 - v2||_1                          (Section III-B, Eq. 4)
+ *     max / mean over the window                          (pooling; the paper
+ *         only names pooling as a max/min use, Table "isa"; the definition
+ *         used is the usual one with padding excluded)
+ * written out as nested loops over p then a, with no tiling, blocking, fusion
+ * or reordering.  Floating point accumulates in double; integers in int32.
+ *
+ * Pins: tests/test_oracle_*.py check these functions against closed forms,
+ * invariants, the literal Eq.-5 evaluator in merit_literal.py on tiny inputs,
+ * and CPU library routines (none of them derived from this file).
+ * Parity unpinned: none.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ------------------------------------------------------------------------ */
+/* IEEE-754 binary16 <-> double, written out bit by bit                     */
+/* ------------------------------------------------------------------------ */
+
+/* binary16 -> double is exact. */
+double ref_half_to_double(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int expo = (h >> 10) & 0x1f;
+    int frac = h & 0x3ff;
+    double v;
+    if (expo == 0) {
+        v = ldexp((double)frac, -24);              /* subnormal or zero */
+    } else if (expo == 31) {
+        v = frac ? NAN : INFINITY;
+    } else {
+        v = ldexp((double)(frac | 0x400), expo - 25);
+    }
+    return sign ? -v : v;
+}
+
+/* double -> binary16, round to nearest, ties to even; overflow -> inf. */
+uint16_t ref_double_to_half(double d)
+{
+    uint16_t sign = (uint16_t)(signbit(d) ? 0x8000u : 0u);
+    if (isnan(d)) return (uint16_t)(sign | 0x7e00u);
+    double a = fabs(d);
+    if (isinf(a)) return (uint16_t)(sign | 0x7c00u);
+    if (a == 0.0) return sign;
+    int e;
+    (void)frexp(a, &e);                           /* a = m * 2^e, m in [0.5,1) */
+    int expo = e - 1;                              /* a = 1.xxx * 2^expo        */
+    if (expo < -14) expo = -14;                    /* subnormal range: fixed ulp */
+    /* ulp of the target at this exponent is 2^(expo-10); scale so ulp == 1.   */
+    double scaled = ldexp(a, 10 - expo);           /* exact: power-of-two scale */
+    double r = nearbyint(scaled);                  /* default mode = ties-even  */
+    /* r is an integer in [0, 2048]. */
+    long q = (long)r;
+    if (q >= 2048) { q >>= 1; expo += 1; }        /* mantissa carried out      */
+    if (expo > 15) return (uint16_t)(sign | 0x7c00u);
+    if (q < 1024) {
+        /* subnormal (expo == -14 and no implicit bit) or zero */
+        return (uint16_t)(sign | (uint16_t)q);
+    }
+    return (uint16_t)(sign | (uint16_t)((expo + 15) << 10) | (uint16_t)(q - 1024));
+}
+
+/* ------------------------------------------------------------------------ */
+/* 2-D convolution, fp16 in / fp16 out, double accumulate                    */
+/* ------------------------------------------------------------------------ */
+/*
+ * y[n,co,oy,ox] = half( sum_{ci,ky,kx} x[n,ci,oy*sh+ky-ph, ox*sw+kx-pw] * w[co,ci,ky,kx] )
+ * Index pattern of the strided-convolution example (Section III-C, Eq. 6): the
+ * window index is added to the strided output index, the kernel is NOT
+ * flipped, weights are indexed [p1,a1,a2,a3] = [co,ci,ky,kx].  Input
+ * coordinates that fall outside the tensor contribute zero.
+ * x: [N,Cin,H,W] binary16, w: [Cout,Cin,kh,kw] binary16, y: [N,Cout,OH,OW].
+ * Returns 0, or -1 on a bad shape.
+ */
+int ref_conv2d(const uint16_t *x, const uint16_t *w, uint16_t *y,
+               int N, int Cin, int H, int W, int Cout,
+               int kh, int kw, int sh, int sw, int ph, int pw)
+{
+    if (N < 0 || Cin <= 0 || H <= 0 || W <= 0 || Cout <= 0 || kh <= 0 || kw <= 0 ||
+        sh <= 0 || sw <= 0 || ph < 0 || pw < 0) return -1;
+    if (H + 2 * ph < kh || W + 2 * pw < kw) return -1;
+    const int OH = (H + 2 * ph - kh) / sh + 1;
+    const int OW = (W + 2 * pw - kw) / sw + 1;
+    long nco;
+#pragma omp parallel for schedule(static)
+    for (nco = 0; nco < (long)N * Cout; ++nco) {
+        const int n = (int)(nco / Cout), co = (int)(nco % Cout);
+        for (int oy = 0; oy < OH; ++oy)
+            for (int ox = 0; ox < OW; ++ox) {
+                double acc = 0.0;
+                for (int ci = 0; ci < Cin; ++ci)
+                    for (int ky = 0; ky < kh; ++ky)
+                        for (int kx = 0; kx < kw; ++kx) {
+                            const int iy = oy * sh + ky - ph;
+                            const int ix = ox * sw + kx - pw;
+                            if (iy < 0 || iy >= H || ix < 0 || ix >= W) continue;
+                            const double xv = ref_half_to_double(
+                                x[(((size_t)n * Cin + ci) * H + iy) * W + ix]);
+                            const double wv = ref_half_to_double(
+                                w[(((size_t)co * Cin + ci) * kh + ky) * kw + kx]);
+                            acc += xv * wv;
+                        }
+                y[(((size_t)n * Cout + co) * OH + oy) * OW + ox] = ref_double_to_half(acc);
+            }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* 2-D pooling, fp32                                                         */
+/* ------------------------------------------------------------------------ */
+/*
+ * Window of output (oy,ox): rows oy*sh-ph .. +kh-1, columns ox*sw-pw .. +kw-1;
+ * only coordinates inside the tensor take part.
+ *   is_avg == 0: maximum of the in-range elements (scan ky-major, replace on
+ *                strict >, starting from -infinity);
+ *   is_avg != 0: their sum divided by their count, summed and divided in
+ *                double, rounded once to float.
+ * A window with no in-range element gives -inf (max) or 0 (avg).
+ */
+int ref_pool2d(const float *x, float *y, int N, int C, int H, int W,
+               int kh, int kw, int sh, int sw, int ph, int pw, int is_avg)
+{
+    if (N < 0 || C <= 0 || H <= 0 || W <= 0 || kh <= 0 || kw <= 0 ||
+        sh <= 0 || sw <= 0 || ph < 0 || pw < 0) return -1;
+    if (H + 2 * ph < kh || W + 2 * pw < kw) return -1;
+    const int OH = (H + 2 * ph - kh) / sh + 1;
+    const int OW = (W + 2 * pw - kw) / sw + 1;
+    long nc;
+#pragma omp parallel for schedule(static)
+    for (nc = 0; nc < (long)N * C; ++nc) {
+        const float *xp = x + (size_t)nc * H * W;
+        float *yp = y + (size_t)nc * OH * OW;
+        for (int oy = 0; oy < OH; ++oy)
+            for (int ox = 0; ox < OW; ++ox) {
+                float m = -INFINITY;
+                double sum = 0.0;
+                int cnt = 0;
+                for (int ky = 0; ky < kh; ++ky)
+                    for (int kx = 0; kx < kw; ++kx) {
+                        const int iy = oy * sh + ky - ph;
+                        const int ix = ox * sw + kx - pw;
+                        if (iy < 0 || iy >= H || ix < 0 || ix >= W) continue;
+                        const float v = xp[(size_t)iy * W + ix];
+                        if (v > m) m = v;
+                        sum += (double)v;
+                        ++cnt;
+                    }
+                if (is_avg)
+                    yp[(size_t)oy * OW + ox] = cnt ? (float)(sum / (double)cnt) : 0.0f;
+                else
+                    yp[(size_t)oy * OW + ox] = m;
+            }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Block-matching motion estimation: SAD + min/argmin over the search range  */
+/* ------------------------------------------------------------------------ */
+static inline int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+/*
+ * One candidate: SAD(by,bx,dy,dx) = sum_{i,j<B} | cur[by*B+i, bx*B+j]
+ *                 - ref[clamp(by*B+i+dy, 0, H-1), clamp(bx*B+j+dx, 0, W-1)] |
+ * The second tensor is displaced by the search indices exactly as in the
+ * correlation-layer example (Section III-C, Eq. 8): ref coordinate = cur
+ * coordinate + displacement.  Reference reads outside the frame are clamped
+ * to the nearest edge pixel.
+ */
+int32_t ref_sad_candidate(const uint8_t *cur, const uint8_t *ref, int H, int W, int B,
+                          int by, int bx, int dy, int dx)
+{
+    int32_t sad = 0;
+    for (int i = 0; i < B; ++i)
+        for (int j = 0; j < B; ++j) {
+            const int cy = by * B + i, cx = bx * B + j;
+            const int ry = clampi(cy + dy, 0, H - 1);
+            const int rx = clampi(cx + dx, 0, W - 1);
+            const int d = (int)cur[(size_t)cy * W + cx] - (int)ref[(size_t)ry * W + rx];
+            sad += d < 0 ? -d : d;
+        }
+    return sad;
+}
+
+/*
+ * Full search.  For every block (by,bx) scan dy = -R..R (outer), dx = -R..R
+ * (inner) and keep the first candidate with the strictly smallest SAD, i.e.
+ * ties go to the lowest raster index (dy+R)*(2R+1) + (dx+R).  This is the
+ * outer level of a two-level ranged inner product (Section III-B): the inner
+ * loop accumulates |a-b| over the block, the outer post-loop keeps the min.
+ * sad: [nby*nbx] int32, mv: [nby*nbx][2] int32 = (dy, dx).
+ */
+int ref_sad_search(const uint8_t *cur, const uint8_t *ref, int32_t *sad, int32_t *mv,
+                   int H, int W, int B, int R)
+{
+    if (H <= 0 || W <= 0 || B <= 0 || R < 0) return -1;
+    if (H % B || W % B) return -1;
+    const int nby = H / B, nbx = W / B;
+    long b;
+#pragma omp parallel for schedule(static)
+    for (b = 0; b < (long)nby * nbx; ++b) {
+        const int by = (int)(b / nbx), bx = (int)(b % nbx);
+        int32_t best = INT32_MAX;
+        int bdy = 0, bdx = 0;
+        for (int dy = -R; dy <= R; ++dy)
+            for (int dx = -R; dx <= R; ++dx) {
+                const int32_t s = ref_sad_candidate(cur, ref, H, W, B, by, bx, dy, dx);
+                if (s < best) { best = s; bdy = dy; bdx = dx; }
+            }
+        sad[b] = best;
+        mv[2 * b + 0] = bdy;
+        mv[2 * b + 1] = bdx;
+    }
+    return 0;
+}
+
+/* All (2R+1)^2 candidate SADs of one block, raster order (dy-major). */
+int ref_sad_surface(const uint8_t *cur, const uint8_t *ref, int32_t *surface,
+                    int H, int W, int B, int R, int by, int bx)
+{
+    if (H <= 0 || W <= 0 || B <= 0 || R < 0 || H % B || W % B) return -1;
+    if (by < 0 || by >= H / B || bx < 0 || bx >= W / B) return -1;
+    int k = 0;
+    for (int dy = -R; dy <= R; ++dy)
+        for (int dx = -R; dx <= R; ++dx)
+            surface[k++] = ref_sad_candidate(cur, ref, H, W, B, by, bx, dy, dx);
+    return 0;
+}
+
+/* Number of threads the parallel loops above will use. */
+int ref_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void ref_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}

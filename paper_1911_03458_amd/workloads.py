@@ -1,0 +1,190 @@
+"""Seeded synthetic input generators for the five MERIT hot-path workloads.
+
+This module holds *no* arithmetic of the method itself (no window gather, no
+reduction): it only draws the random tensors and frames that both the CPU
+oracle and the HIP path consume.  It imports neither of them.
+
+The paper's GPU experiments (Section VI-B, Table "Speedup on GPUs") ran on
+Parboil / Caffe inputs whose sizes are not stated; these generators stand in
+for them with the shapes and value distributions fixed by the build's
+configuration list:
+
+  cfg 0  block-matching ME, 64x64 u8, 8x8 blocks, search +-4
+  cfg 1  max / average pool, fp32 NCHW 16x64x112x112, 3x3 stride 2 pad 1
+  cfg 2  conv fp16 NCHW 8x64x56x56, 64 output channels, 3x3 stride 1 pad 1
+  cfg 3  block-matching ME, 1920x1088 u8, 16x16 blocks, search +-32
+  cfg 4  conv fp16 NCHW 32x3x224x224, 64 output channels, 7x7 stride 2 pad 3
+
+Every generator takes a seed; the default seed is 1911 + config index.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+import numpy as np
+
+BASE_SEED = 1911
+
+
+# --------------------------------------------------------------------------
+# descriptors
+# --------------------------------------------------------------------------
+@dataclass(frozen=True)
+class SadWorkload:
+    name: str
+    H: int
+    W: int
+    block: int
+    search: int          # R: candidates dy,dx in [-R, R]
+    noise: int           # uniform integer noise amplitude added to the displaced copy
+    texture: str         # "uniform" or "sinusoid"
+
+    @property
+    def n_blocks(self):
+        return (self.H // self.block) * (self.W // self.block)
+
+    @property
+    def n_candidates(self):
+        return (2 * self.search + 1) ** 2
+
+
+@dataclass(frozen=True)
+class PoolWorkload:
+    name: str
+    N: int
+    C: int
+    H: int
+    W: int
+    kh: int
+    kw: int
+    sh: int
+    sw: int
+    ph: int
+    pw: int
+
+    @property
+    def OH(self):
+        return (self.H + 2 * self.ph - self.kh) // self.sh + 1
+
+    @property
+    def OW(self):
+        return (self.W + 2 * self.pw - self.kw) // self.sw + 1
+
+
+@dataclass(frozen=True)
+class ConvWorkload:
+    name: str
+    N: int
+    Cin: int
+    H: int
+    W: int
+    Cout: int
+    kh: int
+    kw: int
+    sh: int
+    sw: int
+    ph: int
+    pw: int
+    x_dist: str          # "normal" or "uniform"
+
+    @property
+    def OH(self):
+        return (self.H + 2 * self.ph - self.kh) // self.sh + 1
+
+    @property
+    def OW(self):
+        return (self.W + 2 * self.pw - self.kw) // self.sw + 1
+
+
+CFG0_ME_SMALL = SadWorkload("me_64x64_b8_r4", 64, 64, 8, 4, 3, "uniform")
+CFG1_POOL = PoolWorkload("pool_16x64x112x112_k3s2p1", 16, 64, 112, 112, 3, 3, 2, 2, 1, 1)
+CFG2_CONV3 = ConvWorkload("conv_8x64x56x56_co64_k3s1p1", 8, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1, "normal")
+CFG3_ME_FHD = SadWorkload("me_1920x1088_b16_r32", 1088, 1920, 16, 32, 0, "sinusoid")
+CFG4_CONV7 = ConvWorkload("conv_32x3x224x224_co64_k7s2p3", 32, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3, "uniform")
+
+CONFIGS = [CFG0_ME_SMALL, CFG1_POOL, CFG2_CONV3, CFG3_ME_FHD, CFG4_CONV7]
+
+
+# --------------------------------------------------------------------------
+# generators
+# --------------------------------------------------------------------------
+def _texture_uniform(rng, H, W):
+    return rng.integers(0, 256, size=(H, W), dtype=np.int64)
+
+
+def _texture_sinusoid(rng, H, W):
+    """Smooth random texture: 128 + eight sinusoids of amplitude 14 + noise +-8."""
+    fx = rng.uniform(0.004, 0.06, size=8)
+    fy = rng.uniform(0.004, 0.06, size=8)
+    ph = rng.uniform(0.0, 2.0 * np.pi, size=8)
+    yy, xx = np.meshgrid(np.arange(H, dtype=np.float64),
+                         np.arange(W, dtype=np.float64), indexing="ij")
+    acc = np.full((H, W), 128.0)
+    for k in range(8):
+        acc += 14.0 * np.sin(2.0 * np.pi * (fx[k] * xx + fy[k] * yy) + ph[k])
+    tex = np.rint(acc).astype(np.int64)
+    tex += rng.integers(-8, 9, size=(H, W), dtype=np.int64)
+    return tex
+
+
+def make_sad_frames(wl: SadWorkload, seed: int | None = None):
+    """Return (cur, ref, planted) for a block-matching workload.
+
+    ref  = "frame1", the texture.
+    cur  = "frame0": every block of cur is the block of ref displaced by that
+           block's planted vector (coordinates clamped to the frame), plus
+           uniform integer noise in [-noise, noise], clipped to [0, 255].
+    planted[by, bx] = (vy, vx), drawn uniformly from [-R, R]^2.
+    """
+    if seed is None:
+        seed = BASE_SEED + CONFIGS.index(wl) if wl in CONFIGS else BASE_SEED
+    rng = np.random.default_rng(seed)
+    H, W, B, R = wl.H, wl.W, wl.block, wl.search
+    if wl.texture == "uniform":
+        tex = _texture_uniform(rng, H, W)
+    elif wl.texture == "sinusoid":
+        tex = _texture_sinusoid(rng, H, W)
+    else:
+        raise ValueError(wl.texture)
+    ref = np.clip(tex, 0, 255).astype(np.uint8)
+    nby, nbx = H // B, W // B
+    planted = rng.integers(-R, R + 1, size=(nby, nbx, 2), dtype=np.int64)
+    vy = np.repeat(np.repeat(planted[:, :, 0], B, axis=0), B, axis=1)
+    vx = np.repeat(np.repeat(planted[:, :, 1], B, axis=0), B, axis=1)
+    yy, xx = np.meshgrid(np.arange(nby * B), np.arange(nbx * B), indexing="ij")
+    sy = np.clip(yy + vy, 0, H - 1)
+    sx = np.clip(xx + vx, 0, W - 1)
+    cur = np.zeros((H, W), dtype=np.int64)
+    cur[: nby * B, : nbx * B] = ref[sy, sx].astype(np.int64)
+    if wl.noise > 0:
+        cur += rng.integers(-wl.noise, wl.noise + 1, size=(H, W), dtype=np.int64)
+    cur = np.clip(cur, 0, 255).astype(np.uint8)
+    return cur, ref, planted.astype(np.int32)
+
+
+def make_pool_input(wl: PoolWorkload, seed: int | None = None, N: int | None = None):
+    """fp32 NCHW tensor of N(0,1) values.  `N` overrides the batch (for samples)."""
+    if seed is None:
+        seed = BASE_SEED + 1
+    rng = np.random.default_rng(seed)
+    n = wl.N if N is None else N
+    return rng.standard_normal(size=(n, wl.C, wl.H, wl.W), dtype=np.float32)
+
+
+def make_conv_inputs(wl: ConvWorkload, seed: int | None = None, N: int | None = None):
+    """Return (x fp16 NCHW, w fp16 OIHW).  Weights are N(0, 1/(Cin*kh*kw))."""
+    if seed is None:
+        seed = BASE_SEED + (CONFIGS.index(wl) if wl in CONFIGS else 2)
+    rng = np.random.default_rng(seed)
+    n = wl.N if N is None else N
+    shape = (n, wl.Cin, wl.H, wl.W)
+    if wl.x_dist == "normal":
+        x = rng.standard_normal(size=shape, dtype=np.float32)
+    elif wl.x_dist == "uniform":
+        x = rng.uniform(-1.0, 1.0, size=shape).astype(np.float32)
+    else:
+        raise ValueError(wl.x_dist)
+    fan_in = wl.Cin * wl.kh * wl.kw
+    w = rng.standard_normal(size=(wl.Cout, wl.Cin, wl.kh, wl.kw), dtype=np.float32)
+    w *= np.float32(1.0 / np.sqrt(fan_in))
+    return x.astype(np.float16), w.astype(np.float16)

@@ -1,0 +1,160 @@
+"""Pins for the conv2d oracle (no GPU): closed forms, invariants, the literal
+Eq.-5 evaluator on tiny inputs, and CPU library routines as a third opinion."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import merit_literal as lit
+
+
+# ---------------------------------------------------------------- fp16 codec
+def test_half_to_double_all_patterns_match_numpy():
+    bits = np.arange(65536, dtype=np.uint16)
+    want = bits.view(np.float16).astype(np.float64)
+    got = np.array([oracle.half_to_double(int(b)) for b in bits])
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], want[~nan])
+    assert np.array_equal(np.signbit(got[~nan]), np.signbit(want[~nan]))
+
+
+def test_double_to_half_matches_numpy_rounding():
+    rng = np.random.default_rng(7)
+    vals = np.concatenate([
+        rng.standard_normal(20000),
+        rng.standard_normal(5000) * 1e-6,            # subnormal range
+        rng.standard_normal(5000) * 3e4,             # near overflow
+        np.array([0.0, -0.0, 65504.0, 65519.999, 65520.0, 1e9, -1e9, 2.0 ** -24,
+                  2.0 ** -25, 2.0 ** -25 * 1.0000001, 2.0 ** -14, np.inf, -np.inf]),
+    ])
+    # exact ties between neighbouring halves (must go to even)
+    h = rng.integers(0, 0x7bff, size=5000).astype(np.uint16)
+    lo = h.view(np.float16).astype(np.float64)
+    hi = (h + 1).astype(np.uint16).view(np.float16).astype(np.float64)
+    vals = np.concatenate([vals, 0.5 * (lo + hi), -0.5 * (lo + hi)])
+    with np.errstate(over="ignore"):
+        want = vals.astype(np.float16).view(np.uint16)
+    got = np.array([oracle.double_to_half(float(v)) for v in vals], dtype=np.uint16)
+    assert np.array_equal(got, want)
+
+
+# ---------------------------------------------------------------- invariants
+def _rand_half(rng, shape, scale=1.0):
+    return (rng.standard_normal(shape) * scale).astype(np.float16)
+
+
+def test_identity_kernel_returns_input_bit_exact():
+    rng = np.random.default_rng(1)
+    C = 5
+    x = _rand_half(rng, (2, C, 9, 11))
+    w = np.zeros((C, C, 3, 3), np.float16)
+    for c in range(C):
+        w[c, c, 1, 1] = 1.0
+    y = oracle.conv2d(x, w, (1, 1), (1, 1))
+    assert np.array_equal(y.view(np.uint16), x.view(np.uint16))
+
+
+def test_all_ones_counts_valid_taps():
+    Cin = 3
+    x = np.ones((1, Cin, 6, 7), np.float16)
+    w = np.ones((2, Cin, 3, 3), np.float16)
+    y = oracle.conv2d(x, w, (1, 1), (1, 1)).astype(np.float64)
+    want = np.full((6, 7), 9.0 * Cin)
+    want[0, :] = want[-1, :] = 6.0 * Cin
+    want[:, 0] = want[:, -1] = 6.0 * Cin
+    for cy, cx in [(0, 0), (0, -1), (-1, 0), (-1, -1)]:
+        want[cy, cx] = 4.0 * Cin
+    assert np.array_equal(y[0, 0], want) and np.array_equal(y[0, 1], want)
+
+
+def test_shifted_delta_kernel_is_a_shift_without_flip():
+    """w = delta at (ky,kx) => y[oy,ox] = x[oy+ky-p, ox+kx-p]: the window index is
+    ADDED (correlation, no kernel flip), and zeros enter from the border."""
+    rng = np.random.default_rng(2)
+    x = _rand_half(rng, (1, 1, 7, 8))
+    for ky in range(3):
+        for kx in range(3):
+            w = np.zeros((1, 1, 3, 3), np.float16)
+            w[0, 0, ky, kx] = 1.0
+            y = oracle.conv2d(x, w, (1, 1), (1, 1))[0, 0]
+            want = np.zeros((7, 8), np.float16)
+            for oy in range(7):
+                for ox in range(8):
+                    iy, ix = oy + ky - 1, ox + kx - 1
+                    if 0 <= iy < 7 and 0 <= ix < 8:
+                        want[oy, ox] = x[0, 0, iy, ix]
+            assert np.array_equal(y.view(np.uint16), want.view(np.uint16)), (ky, kx)
+
+
+def test_power_of_two_scaling_is_exact():
+    rng = np.random.default_rng(3)
+    x = _rand_half(rng, (1, 4, 8, 8))
+    w = _rand_half(rng, (3, 4, 3, 3), 0.1)
+    y1 = oracle.conv2d(x, w, (1, 1), (1, 1)).astype(np.float64)
+    y4 = oracle.conv2d(x, (w.astype(np.float32) * 4).astype(np.float16), (1, 1), (1, 1)).astype(np.float64)
+    # no value here is near the subnormal or overflow range, so scaling commutes with rounding
+    assert np.array_equal(y4, 4.0 * y1)
+
+
+def test_channel_and_output_channel_indexing():
+    """Distinct weights per (co, ci) catch a transposed OIHW operand."""
+    x = np.zeros((1, 2, 3, 3), np.float16)
+    x[0, 0, 1, 1] = 1.0
+    x[0, 1, 1, 1] = 2.0
+    w = np.zeros((3, 2, 1, 1), np.float16)
+    w[:, 0, 0, 0] = [1, 10, 100]
+    w[:, 1, 0, 0] = [3, 5, 7]
+    y = oracle.conv2d(x, w, (1, 1), (0, 0)).astype(np.float64)
+    assert y[0, :, 1, 1].tolist() == [1 + 6, 10 + 10, 100 + 14]
+    assert np.count_nonzero(y) == 3
+
+
+# -------------------------------------------------- brute force / libraries
+CASES = [
+    # N Cin H  W Cout kh kw sh sw ph pw
+    (1, 2, 5, 6, 3, 3, 3, 1, 1, 1, 1),
+    (2, 3, 9, 7, 2, 3, 3, 2, 2, 1, 1),
+    (1, 3, 11, 12, 4, 7, 7, 2, 2, 3, 3),
+    (1, 1, 6, 6, 1, 2, 3, 1, 2, 0, 1),
+    (1, 2, 8, 5, 2, 5, 1, 3, 1, 2, 0),
+]
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_matches_literal_transform_evaluator(case):
+    N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw = case
+    rng = np.random.default_rng(hash(case) % 2 ** 31)
+    x = _rand_half(rng, (N, Cin, H, W))
+    w = _rand_half(rng, (Cout, Cin, kh, kw), 0.2)
+    a = oracle.conv2d(x, w, (sh, sw), (ph, pw))
+    b = lit.conv2d(x, w, (sh, sw), (ph, pw))
+    assert a.shape == b.shape
+    # both accumulate in double but in different orders: allow one fp16 ulp
+    da = a.astype(np.float64)
+    db = b.astype(np.float64)
+    ulp = np.spacing(np.abs(db).astype(np.float16)).astype(np.float64)
+    assert np.all(np.abs(da - db) <= ulp)
+    assert np.mean(a.view(np.uint16) == b.view(np.uint16)) > 0.99
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_matches_torch_fp64_conv(case):
+    N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw = case
+    rng = np.random.default_rng(11)
+    x = _rand_half(rng, (N, Cin, H, W))
+    w = _rand_half(rng, (Cout, Cin, kh, kw), 0.2)
+    got = oracle.conv2d(x, w, (sh, sw), (ph, pw)).astype(np.float64)
+    ref = torch.nn.functional.conv2d(torch.from_numpy(x.astype(np.float64)),
+                                     torch.from_numpy(w.astype(np.float64)),
+                                     stride=(sh, sw), padding=(ph, pw)).numpy()
+    assert got.shape == ref.shape
+    ulp = np.spacing(np.abs(ref).astype(np.float16)).astype(np.float64)
+    assert np.all(np.abs(got - ref) <= 0.5 * ulp + 1e-12)
+
+
+def test_output_extent_rule():
+    # floor((I + 2p - k)/s) + 1 at the three workload shapes
+    assert oracle.out_extent(112, 3, 2, 1) == 56
+    assert oracle.out_extent(56, 3, 1, 1) == 56
+    assert oracle.out_extent(224, 7, 2, 3) == 112
