@@ -1,0 +1,216 @@
+#!/usr/bin/env python3
+"""Benchmark of the MERIT hot path on one MI355X.
+
+    python bench.py --gpus 1 --steps K --warmup W
+
+A *step* is one pass of the pooling workload (fp32 NCHW 16x64x112x112, 3x3
+stride 2 pad 1): one max-pool launch and one avg-pool launch, each reading a
+cache-cold input (the launches rotate through buffer sets larger than the
+256 MB Infinity Cache).  The JSON line carries
+
+  value        pooled output elements per second (both launches)
+  roofline     the pooling kernel against peak HBM bandwidth, algorithmic bytes
+               (input read once + output written once) / average launch duration
+  cpu_baseline the CPU oracle on the same workload, timed on the host cores
+  extra        the other four workloads (block matching, both convolutions),
+               each with its own roofline -- informational
+
+Inputs are seeded synthetic tensors already resident in HBM when timing starts.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
+MFMA_F16_PEAK_TFLOPS = 2500.0    # dense fp16 MFMA
+VALU_PEAK_TOPS = 39.3216         # 256 CU x 64 lanes x 2.4 GHz, one lane-op per lane per clock
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--sets", type=int, default=8, help="rotating buffer sets for cache-cold timing")
+    ap.add_argument("--no-extra", action="store_true", help="skip the other four workloads")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    return ap.parse_args()
+
+
+def timed_region(torch, fn, steps, warmup):
+    """Run fn(i) warmup + steps times; return (wall seconds, event milliseconds) for the steps."""
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(steps):
+        fn(warmup + i)
+    e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return t1 - t0, e0.elapsed_time(e1)
+
+
+def bench_pool(torch, mb, wl, steps, warmup, nsets):
+    c = wl.CFG1_POOL
+    x_host = torch.from_numpy(wl.make_pool_input(c))
+    x0 = x_host.to("cuda:0")
+    xs = [x0] + [x0.roll(i, dims=0).contiguous() for i in range(1, nsets)]   # distinct buffers
+    ys = [torch.empty((c.N, c.C, c.OH, c.OW), dtype=torch.float32, device="cuda:0") for _ in range(nsets)]
+    pmax = mb.merit_plan_pool2d(c.N, c.C, c.H, c.W, c.kh, c.kw, c.sh, c.sw, c.ph, c.pw, 0)
+    pavg = mb.merit_plan_pool2d(c.N, c.C, c.H, c.W, c.kh, c.kw, c.sh, c.sw, c.ph, c.pw, 1)
+
+    def step(i):
+        a = (2 * i) % nsets
+        b = (2 * i + 1) % nsets
+        mb.merit_pool2d(pmax, xs[a], ys[a])
+        mb.merit_pool2d(pavg, xs[b], ys[b])
+
+    wall, ev_ms = timed_region(torch, step, steps, warmup)
+    out_elems = c.N * c.C * c.OH * c.OW
+    alg_bytes = c.N * c.C * (c.H * c.W + c.OH * c.OW) * 4
+    launches = 2 * steps
+    avg_launch_s = ev_ms * 1e-3 / launches
+    # cache-warm figure for context: same buffers every launch
+    wall_w, ev_w = timed_region(torch, lambda i: (mb.merit_pool2d(pmax, xs[0], ys[0]),
+                                                  mb.merit_pool2d(pavg, xs[0], ys[1])), steps, warmup)
+    return {
+        "wall_s": wall, "event_ms": ev_ms, "out_elems_per_step": 2 * out_elems,
+        "alg_bytes_per_launch": alg_bytes, "avg_launch_us": avg_launch_s * 1e6,
+        "achieved_gbs": alg_bytes / avg_launch_s / 1e9,
+        "warm_avg_launch_us": ev_w * 1e3 / launches,
+        "kernel": pmax.launch_info()["kernel"], "launch": pmax.launch_info(),
+    }
+
+
+def bench_sad(torch, mb, wl, cfg, steps, warmup):
+    cur, ref, _ = wl.make_sad_frames(cfg)
+    dcur, dref = torch.from_numpy(cur).to("cuda:0"), torch.from_numpy(ref).to("cuda:0")
+    plan = mb.merit_plan_sad(cfg.H, cfg.W, cfg.block, cfg.search)
+    nby, nbx = plan.out_shape()
+    sad = torch.empty((nby, nbx), dtype=torch.int32, device="cuda:0")
+    mv = torch.empty((nby, nbx, 2), dtype=torch.int32, device="cuda:0")
+    wall, ev_ms = timed_region(torch, lambda i: mb.merit_sad_search(plan, dcur, dref, sad, mv), steps, warmup)
+    t = ev_ms * 1e-3 / steps
+    alg_bytes = 2 * cfg.H * cfg.W + nby * nbx * 12
+    absdiffs = nby * nbx * cfg.n_candidates * cfg.block * cfg.block
+    sad_lane_ops = absdiffs / 4                       # v_sad_u8: four pixels per lane-op
+    return {
+        "workload": cfg.name, "kernel": plan.launch_info()["kernel"], "avg_launch_us": t * 1e6,
+        "blocks_per_s": nby * nbx / t, "candidate_sads_per_s": nby * nbx * cfg.n_candidates / t,
+        "achieved_hbm_gbs": alg_bytes / t / 1e9, "hbm_frac": alg_bytes / t / 1e9 / HBM_PEAK_GBS,
+        "roofline": {"bound": "alu", "achieved": sad_lane_ops / t / 1e12, "peak": VALU_PEAK_TOPS,
+                     "unit": "T lane-ops/s (4-pixel SAD)", "frac": sad_lane_ops / t / 1e12 / VALU_PEAK_TOPS},
+    }
+
+
+def bench_conv(torch, mb, wl, cfg, steps, warmup, nsets):
+    x, w = wl.make_conv_inputs(cfg)
+    x0 = torch.from_numpy(x).to("cuda:0")
+    dw = torch.from_numpy(w).to("cuda:0")
+    in_bytes = x.nbytes + w.nbytes
+    out_bytes = cfg.N * cfg.Cout * cfg.OH * cfg.OW * 2
+    # rotate only when a set would otherwise stay resident in the Infinity Cache
+    ns = nsets if (in_bytes + out_bytes) > (8 << 20) else 1
+    xs = [x0] + [x0.roll(i, dims=0).contiguous() for i in range(1, ns)]
+    ys = [torch.empty((cfg.N, cfg.Cout, cfg.OH, cfg.OW), dtype=torch.float16, device="cuda:0") for _ in range(ns)]
+    plan = mb.merit_plan_conv2d(cfg.N, cfg.Cin, cfg.H, cfg.W, cfg.Cout, cfg.kh, cfg.kw, cfg.sh, cfg.sw, cfg.ph, cfg.pw)
+    wall, ev_ms = timed_region(torch, lambda i: mb.merit_conv2d(plan, xs[i % ns], dw, ys[i % ns]), steps, warmup)
+    t = ev_ms * 1e-3 / steps
+    flops = 2.0 * cfg.N * cfg.Cout * cfg.OH * cfg.OW * cfg.Cin * cfg.kh * cfg.kw
+    return {
+        "workload": cfg.name, "kernel": plan.launch_info()["kernel"], "avg_launch_us": t * 1e6,
+        "out_elems_per_s": cfg.N * cfg.Cout * cfg.OH * cfg.OW / t,
+        "achieved_tflops": flops / t / 1e12, "mfma_frac": flops / t / 1e12 / MFMA_F16_PEAK_TFLOPS,
+        "achieved_hbm_gbs": (in_bytes + out_bytes) / t / 1e9,
+        "hbm_frac": (in_bytes + out_bytes) / t / 1e9 / HBM_PEAK_GBS,
+        "rotating_sets": ns,
+    }
+
+
+def cpu_baseline(wl):
+    """The oracle as it stands, timed on the host cores: max + avg pool of the full batch."""
+    import oracle
+    c = wl.CFG1_POOL
+    x = wl.make_pool_input(c)
+    oracle.pool2d(x[:1], (c.kh, c.kw), (c.sh, c.sw), (c.ph, c.pw), "max")      # load + first touch
+    best = None
+    reps = 0
+    t_all = time.perf_counter()
+    while reps < 3 or (time.perf_counter() - t_all < 10.0 and reps < 40):
+        t0 = time.perf_counter()
+        oracle.pool2d(x, (c.kh, c.kw), (c.sh, c.sw), (c.ph, c.pw), "max")
+        oracle.pool2d(x, (c.kh, c.kw), (c.sh, c.sw), (c.ph, c.pw), "avg")
+        dt = time.perf_counter() - t0
+        best = dt if best is None else min(best, dt)
+        reps += 1
+    elems = 2 * c.N * c.C * c.OH * c.OW
+    return {"value": elems / best, "unit": "elems/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"full pooling batch (max + avg, {elems} outputs), best of {reps} passes, "
+                      f"gcc -O2 + OpenMP over (n,c) planes"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    from paper_1911_03458_amd import binding as mb
+    from paper_1911_03458_amd import workloads as wl
+    mb.lib()
+    torch.cuda.set_device(0)
+
+    pool = bench_pool(torch, mb, wl, args.steps, args.warmup, args.sets)
+    value = pool["out_elems_per_step"] * args.steps / pool["wall_s"]
+    result = {
+        "metric": "pool2d output elems/s (max + avg, cache-cold)",
+        "value": value,
+        "unit": "elems/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": pool["wall_s"] * 1e3 / args.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": wl.CFG1_POOL.name + " (max-pool launch + avg-pool launch per step)",
+                   "rotating_buffer_sets": args.sets, "kernel": pool["kernel"],
+                   "grid": pool["launch"]["grid"][0], "lds_bytes": pool["launch"]["lds_bytes"]},
+        "roofline": {"bound": "hbm", "achieved": pool["achieved_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": pool["achieved_gbs"] / HBM_PEAK_GBS, "traffic": None,
+                     "avg_launch_us": pool["avg_launch_us"], "alg_bytes_per_launch": pool["alg_bytes_per_launch"],
+                     "cache_warm_avg_launch_us": pool["warm_avg_launch_us"]},
+    }
+    if not args.no_extra:
+        k = max(20, args.steps // 4)
+        w = max(5, args.warmup // 2)
+        result["extra"] = [
+            bench_sad(torch, mb, wl, wl.CFG0_ME_SMALL, k, w),
+            bench_conv(torch, mb, wl, wl.CFG2_CONV3, k, w, args.sets),
+            bench_sad(torch, mb, wl, wl.CFG3_ME_FHD, max(10, k // 2), w),
+            bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets),
+        ]
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,177 @@
+/*
+ * merit.h -- C ABI of the MI355X (gfx950) ranged inner-product library.
+ *
+ * The library evaluates  Vec(C) = R(M(A), M(B), (.))  (paper Section III, Eq. 1):
+ * every output element p reduces, with a product function (.), the row p of the
+ * transformed tensors M(A), M(B), where
+ *
+ *     M(A)[p,a] = A[x],  x_i = sum_j delta(i, d_j) * (k_j * s_j + o_j),  k = (p,a)
+ *                                                    (Section III-C, Eq. 5).
+ *
+ * M(.) is never stored: each kernel stages the minimal covering sub-tensor of a
+ * tile (Section IV-A, Eq. 9) in LDS and expands it from there.
+ *
+ * Conventions for every entry point
+ *   - Tensor pointers are DEVICE pointers owned by the caller, dense row-major,
+ *     16-byte aligned (else MERIT_ERR_ALIGNMENT).  Nothing is copied or kept.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued and the call returns; the library never synchronises and
+ *     never allocates device memory.
+ *   - A plan is immutable host memory; it may be shared between threads and
+ *     streams.  Plans are created and destroyed without touching the GPU.
+ *   - Every function returns a merit_status; on any error nothing was launched.
+ */
+#ifndef MERIT_H
+#define MERIT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MERIT_MAX_INDEX 12   /* |p| + |a| */
+#define MERIT_MAX_DIMS  6
+
+typedef enum {
+    MERIT_OK = 0,
+    MERIT_ERR_NULL,          /* a required pointer is NULL                         */
+    MERIT_ERR_INVALID_ARG,   /* enum out of range, negative size, ...              */
+    MERIT_ERR_SHAPE,         /* ranges/shapes inconsistent with each other         */
+    MERIT_ERR_UNSUPPORTED,   /* a valid transform that no kernel here implements   */
+    MERIT_ERR_ALIGNMENT,     /* device pointer not 16-byte aligned                 */
+    MERIT_ERR_HIP            /* the HIP runtime refused the launch                 */
+} merit_status;
+
+/* Product functions (.) (Section III-B): dot product (Eq. 3); max / mean of the
+ * window (one operand; the paper names pooling only as a max/min use, Table
+ * "isa"); L1 distance (Eq. 4) followed by min/argmin over the leading
+ * accumulation indices (the outer level of a 2-level ranged inner product). */
+typedef enum {
+    MERIT_OP_CONV_DOT = 0,
+    MERIT_OP_POOL_MAX = 1,
+    MERIT_OP_POOL_AVG = 2,
+    MERIT_OP_SAD_ARGMIN = 3
+} merit_op;
+
+typedef enum { MERIT_U8 = 0, MERIT_F16 = 1, MERIT_F32 = 2 } merit_dtype;
+
+/* What an out-of-range coordinate x yields. */
+typedef enum {
+    MERIT_PAD_ZERO = 0,      /* the value 0                      (CONV_DOT)        */
+    MERIT_PAD_NEG_INF = 1,   /* -infinity                        (POOL_MAX)        */
+    MERIT_PAD_EXCLUDE = 2,   /* not part of the reduction/count  (POOL_AVG)        */
+    MERIT_PAD_CLAMP = 3      /* nearest in-range element         (SAD_ARGMIN)      */
+} merit_pad;
+
+#define MERIT_AXIS_UNUSED (-1)
+
+/* One operand's transform: for every index k_j the axis d_j it moves along
+ * (MERIT_AXIS_UNUSED if none), its stride s_j and offset o_j (Eq. 5). */
+typedef struct {
+    int32_t ndim;
+    int64_t shape [MERIT_MAX_DIMS];
+    int32_t axis  [MERIT_MAX_INDEX];
+    int64_t stride[MERIT_MAX_INDEX];
+    int64_t offset[MERIT_MAX_INDEX];
+} merit_operand;
+
+/* Plain data, caller-owned, copied by merit_plan_create.
+ * range[] lists the extents of k = (p, a): n_par parallel indices first, then
+ * n_acc accumulation indices (the NDRange of Section III-C, Eq. 6).
+ *
+ * Accepted patterns (anything else: MERIT_ERR_UNSUPPORTED)
+ *   CONV_DOT   F16 ZERO     k=(n,co,oy,ox | ci,ky,kx)  a = x[N,Cin,H,W], b = w[Cout,Cin,kh,kw]
+ *   POOL_MAX   F32 NEG_INF  k=(n,c,oy,ox | ky,kx)      a = x[N,C,H,W],   b unused (ndim 0)
+ *   POOL_AVG   F32 EXCLUDE  same
+ *   SAD_ARGMIN U8  CLAMP    k=(by,bx | dy,dx,i,j)      a = ref[H,W] (displaced by dy,dx),
+ *                                                      b = cur[H,W]
+ * with unit stride on window indices (no dilation) and output extents equal to
+ * floor((I + 2*pad - k)/s) + 1. */
+typedef struct {
+    merit_op      op;
+    merit_dtype   dtype;
+    merit_pad     pad;
+    int32_t       n_par, n_acc;
+    int64_t       range[MERIT_MAX_INDEX];
+    merit_operand a;
+    merit_operand b;
+} merit_plan_desc;
+
+typedef struct merit_plan merit_plan;   /* opaque, host memory only */
+
+/* Launch geometry a plan resolved to (for tests, profiling and roofline
+ * accounting; informational). */
+typedef struct {
+    const char *kernel;      /* name of the HIP kernel the plan dispatches to      */
+    int64_t grid[3];         /* workgroups                                         */
+    int32_t block[3];        /* threads per workgroup                              */
+    int64_t lds_bytes;       /* LDS per workgroup                                  */
+    int64_t tile[MERIT_MAX_INDEX]; /* sub-tensor (t_p, t_a) one workgroup covers   */
+} merit_launch_info;
+
+/* ---- plans ---------------------------------------------------------------- */
+
+/* Validate `desc` against the accepted patterns and derive output shape, tile
+ * and halo geometry (Eq. 9) and grid.  *out receives a new plan (free it with
+ * merit_plan_destroy).  Host only. */
+merit_status merit_plan_create(const merit_plan_desc *desc, merit_plan **out);
+merit_status merit_plan_destroy(merit_plan *plan);
+
+/* Convenience constructors: fill the descriptor for the three 2-D operations
+ * and call merit_plan_create.
+ *  conv2d: y[n,co,oy,ox] = sum x[n,ci,oy*sh+ky-ph,ox*sw+kx-pw] * w[co,ci,ky,kx]
+ *          (index pattern of Section III-C, Eq. 6: strided, no kernel flip).
+ *  pool2d: max (is_avg=0) or mean over in-range elements (is_avg=1) of the window.
+ *  sad:    frames [H,W] u8, blocks `block` x `block` (must divide H and W),
+ *          candidates dy,dx in [-range, range]; second tensor displaced by the
+ *          search indices as in Section III-C, Eq. 8. */
+merit_status merit_plan_conv2d(int N, int Cin, int H, int W, int Cout, int kh, int kw,
+                               int sh, int sw, int ph, int pw, merit_plan **out);
+merit_status merit_plan_pool2d(int N, int C, int H, int W, int kh, int kw,
+                               int sh, int sw, int ph, int pw, int is_avg, merit_plan **out);
+merit_status merit_plan_sad(int H, int W, int block, int range, merit_plan **out);
+
+/* Copy of the descriptor the plan was created from. */
+merit_status merit_plan_get_desc(const merit_plan *plan, merit_plan_desc *out);
+/* Output tensor shape: the parallel ranges ([N,Cout,OH,OW], [N,C,OH,OW], [nby,nbx]). */
+merit_status merit_plan_out_shape(const merit_plan *plan, int32_t *ndim, int64_t shape[MERIT_MAX_DIMS]);
+/* Size of the minimal sub-tensor of operand `which` (0 = a, 1 = b) that contains
+ * a tile of M(.) with extents tile[0 .. n_par+n_acc-1]:
+ * 1 + sum_j (t_j - 1) s_j delta(d_j, i) per axis i  (Section IV-A, Eq. 9). */
+merit_status merit_plan_footprint(const merit_plan *plan, int which,
+                                  const int64_t tile[MERIT_MAX_INDEX], int64_t out[MERIT_MAX_DIMS]);
+merit_status merit_plan_launch_info(const merit_plan *plan, merit_launch_info *out);
+/* Override the sub-tensor (t_p, t_a) one workgroup covers; the paper's call
+ * passes tile sizes next to the ranges (Section VI-A, Listing 3).  Entries <= 0
+ * keep the library's choice.  Honoured entries: pooling tile[2] = output rows
+ * (and tile[3] = output columns when the generic kernel is used); convolution
+ * tile[2]*tile[3] = output pixels per workgroup (128 or 256); block matching
+ * tile[1] = blocks per workgroup.  On error the plan is unchanged.  Not safe to
+ * call while another thread launches with the same plan. */
+merit_status merit_plan_set_tile(merit_plan *plan, const int64_t tile[MERIT_MAX_INDEX]);
+
+/* ---- operations ------------------------------------------------------------
+ * x_f16: [N,Cin,H,W] binary16; w_f16: [Cout,Cin,kh,kw] binary16;
+ * y_f16: [N,Cout,OH,OW] binary16.  Products accumulate in fp32 on the matrix
+ * cores and are rounded once (nearest even) to binary16.  (.) = Eq. 3. */
+merit_status merit_conv2d(const merit_plan *plan, const void *x_f16, const void *w_f16,
+                          void *y_f16, void *hip_stream);
+
+/* x_f32: [N,C,H,W]; y_f32: [N,C,OH,OW].  max: exact.  avg: fp32 sum in window
+ * scan order divided by the in-range count. */
+merit_status merit_pool2d(const merit_plan *plan, const void *x_f32, void *y_f32, void *hip_stream);
+
+/* cur_u8, ref_u8: [H,W] frames.  sad_i32: [nby*nbx] minimum SAD per block;
+ * mv_i32: [nby*nbx][2] = (dy,dx) of the minimiser with the lowest raster index
+ * (dy+R)*(2R+1)+(dx+R).  Reference reads outside the frame are clamped to the
+ * edge.  (.) = Eq. 4, reference displaced as in Eq. 8. */
+merit_status merit_sad_search(const merit_plan *plan, const void *cur_u8, const void *ref_u8,
+                              void *sad_i32, void *mv_i32, void *hip_stream);
+
+const char *merit_status_string(merit_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MERIT_H */

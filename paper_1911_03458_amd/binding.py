@@ -1,0 +1,250 @@
+"""ctypes binding of libmerit.so -- argument marshalling only.
+
+Function names mirror include/merit.h.  Tensors are torch CUDA (ROCm) tensors:
+PyTorch provides device memory and the current HIP stream, nothing else; every
+step of the computation runs in the library's kernels.  There is no fallback:
+if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+from . import build as _build
+
+MERIT_MAX_INDEX = 12
+MERIT_MAX_DIMS = 6
+MERIT_AXIS_UNUSED = -1
+
+MERIT_OK = 0
+(MERIT_ERR_NULL, MERIT_ERR_INVALID_ARG, MERIT_ERR_SHAPE, MERIT_ERR_UNSUPPORTED,
+ MERIT_ERR_ALIGNMENT, MERIT_ERR_HIP) = range(1, 7)
+MERIT_OP_CONV_DOT, MERIT_OP_POOL_MAX, MERIT_OP_POOL_AVG, MERIT_OP_SAD_ARGMIN = range(4)
+MERIT_U8, MERIT_F16, MERIT_F32 = range(3)
+MERIT_PAD_ZERO, MERIT_PAD_NEG_INF, MERIT_PAD_EXCLUDE, MERIT_PAD_CLAMP = range(4)
+
+
+class MeritError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().merit_status_string(status).decode() if _lib is not None else str(status)
+        super().__init__(f"{where}: {msg} (merit_status {status})")
+
+
+class merit_operand(ctypes.Structure):
+    _fields_ = [("ndim", ctypes.c_int32),
+                ("shape", ctypes.c_int64 * MERIT_MAX_DIMS),
+                ("axis", ctypes.c_int32 * MERIT_MAX_INDEX),
+                ("stride", ctypes.c_int64 * MERIT_MAX_INDEX),
+                ("offset", ctypes.c_int64 * MERIT_MAX_INDEX)]
+
+
+class merit_plan_desc(ctypes.Structure):
+    _fields_ = [("op", ctypes.c_int), ("dtype", ctypes.c_int), ("pad", ctypes.c_int),
+                ("n_par", ctypes.c_int32), ("n_acc", ctypes.c_int32),
+                ("range", ctypes.c_int64 * MERIT_MAX_INDEX),
+                ("a", merit_operand), ("b", merit_operand)]
+
+
+class merit_launch_info(ctypes.Structure):
+    _fields_ = [("kernel", ctypes.c_char_p),
+                ("grid", ctypes.c_int64 * 3),
+                ("block", ctypes.c_int32 * 3),
+                ("lds_bytes", ctypes.c_int64),
+                ("tile", ctypes.c_int64 * MERIT_MAX_INDEX)]
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _build.LIB_PATH
+
+
+def lib():
+    """Load libmerit.so (building it only if no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        _build.build_library(force=True)
+    L = ctypes.CDLL(path)
+    P = ctypes.c_void_p
+    c_int = ctypes.c_int
+    PP = ctypes.POINTER(P)
+    L.merit_plan_create.argtypes = [ctypes.POINTER(merit_plan_desc), PP]
+    L.merit_plan_destroy.argtypes = [P]
+    L.merit_plan_conv2d.argtypes = [c_int] * 11 + [PP]
+    L.merit_plan_pool2d.argtypes = [c_int] * 11 + [PP]
+    L.merit_plan_sad.argtypes = [c_int] * 4 + [PP]
+    L.merit_plan_get_desc.argtypes = [P, ctypes.POINTER(merit_plan_desc)]
+    L.merit_plan_out_shape.argtypes = [P, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)]
+    L.merit_plan_footprint.argtypes = [P, c_int, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]
+    L.merit_plan_launch_info.argtypes = [P, ctypes.POINTER(merit_launch_info)]
+    L.merit_plan_set_tile.argtypes = [P, ctypes.POINTER(ctypes.c_int64)]
+    L.merit_conv2d.argtypes = [P, P, P, P, P]
+    L.merit_pool2d.argtypes = [P, P, P, P]
+    L.merit_sad_search.argtypes = [P, P, P, P, P, P]
+    for name in ("merit_plan_create", "merit_plan_destroy", "merit_plan_conv2d", "merit_plan_pool2d",
+                 "merit_plan_sad", "merit_plan_get_desc", "merit_plan_out_shape", "merit_plan_footprint",
+                 "merit_plan_launch_info", "merit_plan_set_tile", "merit_conv2d", "merit_pool2d",
+                 "merit_sad_search"):
+        getattr(L, name).restype = c_int
+    L.merit_status_string.argtypes = [c_int]
+    L.merit_status_string.restype = ctypes.c_char_p
+    _lib = L
+    return L
+
+
+def _check(status: int, where: str):
+    if status != MERIT_OK:
+        raise MeritError(status, where)
+
+
+class Plan:
+    """Owner of one merit_plan handle."""
+
+    def __init__(self, handle: ctypes.c_void_p):
+        self._h = handle
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise ValueError("plan already destroyed")
+        return self._h
+
+    def destroy(self):
+        if self._h:
+            lib().merit_plan_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def desc(self) -> merit_plan_desc:
+        d = merit_plan_desc()
+        _check(lib().merit_plan_get_desc(self.handle, ctypes.byref(d)), "merit_plan_get_desc")
+        return d
+
+    def out_shape(self):
+        nd = ctypes.c_int32()
+        shp = (ctypes.c_int64 * MERIT_MAX_DIMS)()
+        _check(lib().merit_plan_out_shape(self.handle, ctypes.byref(nd), shp), "merit_plan_out_shape")
+        return tuple(shp[i] for i in range(nd.value))
+
+    def footprint(self, which: int, tile):
+        t = (ctypes.c_int64 * MERIT_MAX_INDEX)(*list(tile) + [0] * (MERIT_MAX_INDEX - len(tile)))
+        out = (ctypes.c_int64 * MERIT_MAX_DIMS)()
+        _check(lib().merit_plan_footprint(self.handle, which, t, out), "merit_plan_footprint")
+        d = self.desc()
+        nd = d.a.ndim if which == 0 else d.b.ndim
+        return tuple(out[i] for i in range(nd))
+
+    def launch_info(self) -> dict:
+        li = merit_launch_info()
+        _check(lib().merit_plan_launch_info(self.handle, ctypes.byref(li)), "merit_plan_launch_info")
+        return {"kernel": li.kernel.decode(), "grid": tuple(li.grid), "block": tuple(li.block),
+                "lds_bytes": li.lds_bytes, "tile": tuple(li.tile)}
+
+    def set_tile(self, tile):
+        t = (ctypes.c_int64 * MERIT_MAX_INDEX)(*list(tile) + [0] * (MERIT_MAX_INDEX - len(tile)))
+        _check(lib().merit_plan_set_tile(self.handle, t), "merit_plan_set_tile")
+        return self
+
+
+def merit_plan_create(desc: merit_plan_desc) -> Plan:
+    h = ctypes.c_void_p()
+    _check(lib().merit_plan_create(ctypes.byref(desc), ctypes.byref(h)), "merit_plan_create")
+    return Plan(h)
+
+
+def merit_plan_conv2d(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw) -> Plan:
+    h = ctypes.c_void_p()
+    _check(lib().merit_plan_conv2d(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, ctypes.byref(h)),
+           "merit_plan_conv2d")
+    return Plan(h)
+
+
+def merit_plan_pool2d(N, C, H, W, kh, kw, sh, sw, ph, pw, is_avg) -> Plan:
+    h = ctypes.c_void_p()
+    _check(lib().merit_plan_pool2d(N, C, H, W, kh, kw, sh, sw, ph, pw, int(bool(is_avg)), ctypes.byref(h)),
+           "merit_plan_pool2d")
+    return Plan(h)
+
+
+def merit_plan_sad(H, W, block, search) -> Plan:
+    h = ctypes.c_void_p()
+    _check(lib().merit_plan_sad(H, W, block, search, ctypes.byref(h)), "merit_plan_sad")
+    return Plan(h)
+
+
+# --------------------------------------------------------------------------
+# operations on torch device tensors
+# --------------------------------------------------------------------------
+def _dev_ptr(t, dtype, name):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name}: expected a device tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: tensor must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    import torch
+    if stream is None:
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def merit_conv2d(plan: Plan, x, w, y=None, stream=None):
+    import torch
+    if y is None:
+        y = torch.empty(plan.out_shape(), dtype=torch.float16, device=x.device)
+    if tuple(y.shape) != plan.out_shape():
+        raise ValueError("y has the wrong shape")
+    d = plan.desc()
+    if tuple(x.shape) != tuple(d.a.shape[:4]) or tuple(w.shape) != tuple(d.b.shape[:4]):
+        raise ValueError("x / w do not match the plan")
+    _check(lib().merit_conv2d(plan.handle, _dev_ptr(x, torch.float16, "x"), _dev_ptr(w, torch.float16, "w"),
+                              _dev_ptr(y, torch.float16, "y"), _stream(stream)), "merit_conv2d")
+    return y
+
+
+def merit_pool2d(plan: Plan, x, y=None, stream=None):
+    import torch
+    if y is None:
+        y = torch.empty(plan.out_shape(), dtype=torch.float32, device=x.device)
+    if tuple(y.shape) != plan.out_shape():
+        raise ValueError("y has the wrong shape")
+    if tuple(x.shape) != tuple(plan.desc().a.shape[:4]):
+        raise ValueError("x does not match the plan")
+    _check(lib().merit_pool2d(plan.handle, _dev_ptr(x, torch.float32, "x"), _dev_ptr(y, torch.float32, "y"),
+                              _stream(stream)), "merit_pool2d")
+    return y
+
+
+def merit_sad_search(plan: Plan, cur, ref, sad=None, mv=None, stream=None):
+    import torch
+    nby, nbx = plan.out_shape()
+    if sad is None:
+        sad = torch.empty((nby, nbx), dtype=torch.int32, device=cur.device)
+    if mv is None:
+        mv = torch.empty((nby, nbx, 2), dtype=torch.int32, device=cur.device)
+    d = plan.desc()
+    if tuple(cur.shape) != tuple(d.b.shape[:2]) or tuple(ref.shape) != tuple(d.a.shape[:2]):
+        raise ValueError("frames do not match the plan")
+    if tuple(sad.shape) != (nby, nbx) or tuple(mv.shape) != (nby, nbx, 2):
+        raise ValueError("outputs have the wrong shape")
+    _check(lib().merit_sad_search(plan.handle, _dev_ptr(cur, torch.uint8, "cur"), _dev_ptr(ref, torch.uint8, "ref"),
+                                  _dev_ptr(sad, torch.int32, "sad"), _dev_ptr(mv, torch.int32, "mv"),
+                                  _stream(stream)), "merit_sad_search")
+    return sad, mv

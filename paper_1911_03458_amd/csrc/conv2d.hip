@@ -1,0 +1,467 @@
+// 2-D convolution for gfx950 as an implicit GEMM on the matrix cores.
+//
+// k = (n, co, oy, ox | ci, ky, kx)                        (Section III-C, Eq. 6)
+//     M(x)[p,a] = x[n, ci, oy*sh + ky - ph, ox*sw + kx - pw]   (zero outside)
+//     M(w)[p,a] = w[co, ci, ky, kx]
+// reduced with the dot product (Section III-B, Eq. 3).  M(x) (the unrolled
+// matrix U(A) of Section III-A) is never materialised: a workgroup stages the
+// minimal covering sub-tensor of its pixel tile (Section IV-A, Eq. 9) in LDS
+// and every lane expands its windows from there with one vector LDS read per
+// MFMA operand.  Weights are the MFMA "A" operand (rows = output channels),
+// pixels the "B" operand (columns), so a lane's accumulator registers hold one
+// pixel for 16 output channels and stores run along the contiguous pixel axis
+// of NCHW.
+//
+// The accumulation order K is free (both operands use the same order), so it
+// is chosen per variant to make eight consecutive k contiguous in LDS:
+//   planar        (few input channels): K = (ci, ky | kx padded to 8); the input
+//                 tile stays planar [ci][row][col]; a lane's eight taps are one
+//                 row of the window.
+//   channel-block (many input channels): K = (ci/8, ky, kx | ci%8); the input
+//                 tile is staged as [ci/8][row][col][8 channels].
+#include "merit_internal.h"
+
+namespace merit {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ uint32_t fdiv(uint32_t n, FastDiv f)
+{
+    return __umulhi(n, f.magic);
+}
+
+union Frag {
+    uint4 u;
+    half8 h;
+    uint32_t d[4];
+};
+
+__device__ __forceinline__ floatx16 mfma16(const Frag &a, const Frag &b, floatx16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a.h, b.h, c, 0, 0, 0);
+}
+
+// Accumulator register r of lane l holds output channel 8*(r/4) + 4*(l/32) + r%4
+// (within the 32-channel block) of pixel l%32 (within the 32-pixel block).
+template <int CB, int PXW>
+__device__ __forceinline__ void store_tile(const ConvParams &p, floatx16 (&acc)[CB][PXW],
+                                           _Float16 *__restrict__ y, int n, int co_base,
+                                           const int (&m)[PXW], int lane)
+{
+    const int h = lane >> 5;
+    const int ohw = p.OH * p.OW;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int pb = 0; pb < PXW; ++pb) {
+            if (m[pb] >= ohw) continue;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int co = co_base + cb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                if (co < p.Cout)
+                    y[((size_t)n * p.Cout + co) * ohw + m[pb]] = (_Float16)acc[cb][pb][r];
+            }
+        }
+}
+
+// ---------------------------------------------------------------------------
+// planar variant
+// LDS: [ weights: CB*G2*32 x 16 B ][ 32 B of zeros ][ input: Cin*RHa*pitch halves ][ group offsets: G2 x 4 B ]
+// ---------------------------------------------------------------------------
+template <int CB, int PXW>
+__global__ __launch_bounds__(256) void merit_conv2d_planar(ConvParams p, const uint16_t *__restrict__ x,
+                                                          const uint16_t *__restrict__ w,
+                                                          _Float16 *__restrict__ y)
+{
+    extern __shared__ __align__(16) uint8_t smem[];
+    uint4 *wl = reinterpret_cast<uint4 *>(smem);
+    uint8_t *xz = smem + p.lds_w_bytes;                 // 32 zero bytes, then the tile
+    uint8_t *xl = xz + 32;
+    uint32_t *goff = reinterpret_cast<uint32_t *>(xl + p.lds_x_bytes);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6, h = lane >> 5, c32 = lane & 31;
+    const int co_base = blockIdx.y * CB * 32;
+    const int P8 = p.pitch >> 3;
+    const int ohw = p.OH * p.OW;
+
+    // ---- weights: zero-fill, then scatter w[co][g][kx] to slot kx of group g ----
+    const int nwl = CB * p.G2 * 32;
+    for (int u = tid; u < nwl; u += 256) wl[u] = make_uint4(0, 0, 0, 0);
+    if (tid < 8) reinterpret_cast<uint32_t *>(xz)[tid] = 0;
+    for (int g = tid; g < p.G2; g += 256) {
+        const int ci = (int)fdiv((uint32_t)g, p.div_kh);
+        const int ky = g - ci * p.kh;
+        goff[g] = (uint32_t)(((ci * p.RHa + ky) * p.pitch) * 2);
+    }
+    __syncthreads();
+    {
+        uint16_t *wl16 = reinterpret_cast<uint16_t *>(smem);
+        const int gk = p.G * p.kw;                       // halves per output channel
+        const int nco = min(CB * 32, p.Cout - co_base);
+        const int total = nco * gk;
+        const uint16_t *wsrc = w + (size_t)co_base * gk;
+        for (int f = tid; f < total; f += 256) {
+            const int col = f / gk;                      // local output channel
+            const int rem = f - col * gk;
+            const int g = rem / p.kw;
+            const int t = rem - g * p.kw;
+            const int cb = col >> 5, cc = col & 31;
+            wl16[(((cb * p.G2 + g) * 32 + cc) << 3) + t] = wsrc[f];
+        }
+    }
+
+    // masks that clear the slots kx >= kw of a fragment
+    uint32_t kmask[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        kmask[q] = ((2 * q < p.kw) ? 0x0000ffffu : 0u) | ((2 * q + 1 < p.kw) ? 0xffff0000u : 0u);
+
+    const int ntiles = p.N * p.tiles_per_image;
+    for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int n = (int)fdiv((uint32_t)tile, p.div_tiles);
+        const int m0 = (tile - n * p.tiles_per_image) * p.TM;
+        const int oyA = (int)fdiv((uint32_t)m0, p.div_ow);
+        const int mlast = min(m0 + p.TM, ohw) - 1;
+        const int oyB = (int)fdiv((uint32_t)mlast, p.div_ow);
+        const int yA = oyA * p.sh - p.ph;
+        const int RH = (oyB - oyA) * p.sh + p.kh;
+
+        __syncthreads();                                  // previous tile fully consumed
+        // ---- stage the input rows [yA, yA+RH) of every channel, 8 halves per unit ----
+        const int nu = p.Cin * p.RHa * P8;
+        const bool vec_ok = (p.W & 7) == 0;
+        for (int u = tid; u < nu; u += 256) {
+            const int q = (int)fdiv((uint32_t)u, p.div_pitch8);
+            const int c8 = u - q * P8;
+            const int ci = (int)fdiv((uint32_t)q, p.div_rha);
+            const int r = q - ci * p.RHa;
+            if (r >= RH) continue;
+            const int gy = yA + r;
+            const int xg0 = 8 * c8 - p.padl;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (gy >= 0 && gy < p.H) {
+                const uint16_t *row = x + (((size_t)n * p.Cin + ci) * p.H + gy) * p.W;
+                if (vec_ok && xg0 >= 0 && xg0 + 8 <= p.W) {
+                    v = *reinterpret_cast<const uint4 *>(row + xg0);
+                } else if (xg0 + 8 > 0 && xg0 < p.W) {
+                    uint32_t d[4] = {0, 0, 0, 0};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int xg = xg0 + e;
+                        if (xg >= 0 && xg < p.W) d[e >> 1] |= (uint32_t)row[xg] << (16 * (e & 1));
+                    }
+                    v = make_uint4(d[0], d[1], d[2], d[3]);
+                }
+            }
+            reinterpret_cast<uint4 *>(xl)[u] = v;
+        }
+        __syncthreads();
+
+        // ---- per-lane pixel bases ----
+        int m[PXW];
+        uint32_t pbase[PXW], shift[PXW];
+#pragma unroll
+        for (int pb = 0; pb < PXW; ++pb) {
+            m[pb] = m0 + (wave * PXW + pb) * 32 + c32;
+            const int mm = min(m[pb], ohw - 1);
+            const int oy = (int)fdiv((uint32_t)mm, p.div_ow);
+            const int ox = mm - oy * p.OW;
+            const int cs = p.padl - p.pw + ox * p.sw;       // staged column of tap kx = 0
+            pbase[pb] = (uint32_t)((((oy - oyA) * p.sh) * p.pitch + (cs & ~1)) * 2) + 32u;
+            shift[pb] = (uint32_t)(cs & 1) * 16u;
+        }
+
+        floatx16 acc[CB][PXW];
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int pb = 0; pb < PXW; ++pb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[cb][pb][r] = 0.0f;
+
+        for (int s = 0; s < p.S; ++s) {
+            const int g = 2 * s + h;
+            const bool gvalid = g < p.G;
+            const uint32_t go = goff[g];
+            Frag a[CB], b[PXW];
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) a[cb].u = wl[cb * p.G2 * 32 + s * 64 + lane];
+#pragma unroll
+            for (int pb = 0; pb < PXW; ++pb) {
+                // groups past the end read the zero block (their weights are zero too)
+                const uint32_t addr = gvalid ? pbase[pb] + go : 0u;
+                const uint32_t *src = reinterpret_cast<const uint32_t *>(xz + addr);
+                uint32_t d[5];
+#pragma unroll
+                for (int q = 0; q < 5; ++q) d[q] = src[q];
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    b[pb].d[q] = __builtin_amdgcn_alignbit(d[q + 1], d[q], shift[pb]) & kmask[q];
+            }
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int pb = 0; pb < PXW; ++pb) acc[cb][pb] = mfma16(a[cb], b[pb], acc[cb][pb]);
+        }
+        store_tile<CB, PXW>(p, acc, y, n, co_base, m, lane);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// channel-block variant
+// LDS: [ weights: S*CB*64 x 16 B ][ input: nchi*RHa*pitch x 16 B ]
+// MFMA step s = (chi', tap): lanes 0-31 take channel group chi', lanes 32-63
+// take chi' + nchi/2, so the per-step LDS offset is the same for every lane.
+// ---------------------------------------------------------------------------
+template <int T>
+__device__ __forceinline__ void stage_weights_chblock_vec(const ConvParams &p, const uint16_t *__restrict__ w,
+                                                          uint4 *wl, int co_base, int CB, int tid)
+{
+    // unit = (local output channel, channel group): 8 channels x T taps = T uint4, contiguous
+    const int half_nchi = p.nchi >> 1;
+    const int units = CB * 32 * p.nchi;
+    for (int u = tid; u < units; u += 256) {
+        const int col = u / p.nchi;
+        const int chi = u - col * p.nchi;
+        const int co = co_base + col;
+        uint32_t src[4 * T];
+        const bool ok = (co < p.Cout) && (chi * 8 + 8 <= p.Cin);
+        if (ok) {
+            const uint4 *g = reinterpret_cast<const uint4 *>(w + ((size_t)co * p.Cin + chi * 8) * T);
+#pragma unroll
+            for (int i = 0; i < T; ++i) {
+                const uint4 v = g[i];
+                src[4 * i + 0] = v.x; src[4 * i + 1] = v.y; src[4 * i + 2] = v.z; src[4 * i + 3] = v.w;
+            }
+        } else {
+            // zero-padding channel group or output channel (callers guarantee Cin % 8 == 0)
+#pragma unroll
+            for (int i = 0; i < 4 * T; ++i) src[i] = 0;
+        }
+        const int hh = chi >= half_nchi ? 1 : 0;
+        const int chip = chi - hh * half_nchi;
+        const int cb = col >> 5, cc = col & 31;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            uint32_t d[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int e0 = (2 * q) * T + t, e1 = (2 * q + 1) * T + t;   // halves (c=2q,t), (c=2q+1,t)
+                const uint32_t sel = ((e0 & 1) ? 0x00000302u : 0x00000100u) | ((e1 & 1) ? 0x07060000u : 0x05040000u);
+                d[q] = __builtin_amdgcn_perm(src[e1 >> 1], src[e0 >> 1], sel);
+            }
+            const int s = chip * T + t;
+            wl[((s * CB + cb) * 2 + hh) * 32 + cc] = make_uint4(d[0], d[1], d[2], d[3]);
+        }
+    }
+}
+
+__device__ __forceinline__ void stage_weights_chblock_scalar(const ConvParams &p, const uint16_t *__restrict__ w,
+                                                             uint4 *wl, int co_base, int CB, int tid)
+{
+    const int T = p.kh * p.kw;
+    const int half_nchi = p.nchi >> 1;
+    const int units = CB * 32 * p.nchi * T;          // one 16-byte fragment each
+    for (int u = tid; u < units; u += 256) {
+        const int t = u % T;
+        const int r = u / T;
+        const int chi = r % p.nchi;
+        const int col = r / p.nchi;
+        const int co = co_base + col;
+        uint32_t d[4] = {0, 0, 0, 0};
+        if (co < p.Cout) {
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                const int ci = chi * 8 + c;
+                if (ci < p.Cin) d[c >> 1] |= (uint32_t)w[((size_t)co * p.Cin + ci) * T + t] << (16 * (c & 1));
+            }
+        }
+        const int hh = chi >= half_nchi ? 1 : 0;
+        const int chip = chi - hh * half_nchi;
+        const int s = chip * T + t;
+        wl[((s * CB + (col >> 5)) * 2 + hh) * 32 + (col & 31)] = make_uint4(d[0], d[1], d[2], d[3]);
+    }
+}
+
+template <int CB, int PXW>
+__global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const uint16_t *__restrict__ x,
+                                                           const uint16_t *__restrict__ w,
+                                                           _Float16 *__restrict__ y)
+{
+    extern __shared__ __align__(16) uint8_t smem[];
+    uint4 *wl = reinterpret_cast<uint4 *>(smem);
+    uint4 *xl = reinterpret_cast<uint4 *>(smem + p.lds_w_bytes);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6, h = lane >> 5, c32 = lane & 31;
+    const int co_base = blockIdx.y * CB * 32;
+    const int ohw = p.OH * p.OW;
+    const int T = p.kh * p.kw;
+    const int half_nchi = p.nchi >> 1;
+
+    if (T == 9 && (p.Cin & 7) == 0) stage_weights_chblock_vec<9>(p, w, wl, co_base, CB, tid);
+    else if (T == 1 && (p.Cin & 7) == 0) stage_weights_chblock_vec<1>(p, w, wl, co_base, CB, tid);
+    else stage_weights_chblock_scalar(p, w, wl, co_base, CB, tid);
+
+    const int ntiles = p.N * p.tiles_per_image;
+    for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int n = (int)fdiv((uint32_t)tile, p.div_tiles);
+        const int m0 = (tile - n * p.tiles_per_image) * p.TM;
+        const int oyA = (int)fdiv((uint32_t)m0, p.div_ow);
+        const int mlast = min(m0 + p.TM, ohw) - 1;
+        const int oyB = (int)fdiv((uint32_t)mlast, p.div_ow);
+        const int yA = oyA * p.sh - p.ph;
+        const int RH = (oyB - oyA) * p.sh + p.kh;
+
+        __syncthreads();
+        // ---- zero the padding columns of the staged rows ----
+        const int npad = p.pitch - p.W;
+        for (int u = tid; u < p.nchi * p.RHa * npad; u += 256) {
+            const int rowi = u / npad;
+            const int c = u - rowi * npad;
+            const int col = c < p.padl ? c : p.W + c;
+            xl[rowi * p.pitch + col] = make_uint4(0, 0, 0, 0);
+        }
+        // ---- stage input: 8 channels x 8 pixels per unit, transposed in registers ----
+        if ((p.W & 7) == 0) {
+            const int W8 = p.W >> 3;
+            const int nu = p.nchi * p.RHa * W8;
+            for (int u = tid; u < nu; u += 256) {
+                const int q = (int)fdiv((uint32_t)u, p.div_w8);
+                const int x8 = u - q * W8;
+                const int chi = (int)fdiv((uint32_t)q, p.div_rha);
+                const int r = q - chi * p.RHa;
+                if (r >= RH) continue;
+                const int gy = yA + r;
+                uint32_t v[8][4];
+#pragma unroll
+                for (int c = 0; c < 8; ++c) {
+                    const int ch = chi * 8 + c;
+                    uint4 t4 = make_uint4(0, 0, 0, 0);
+                    if (ch < p.Cin && gy >= 0 && gy < p.H)
+                        t4 = *reinterpret_cast<const uint4 *>(x + (((size_t)n * p.Cin + ch) * p.H + gy) * p.W + 8 * x8);
+                    v[c][0] = t4.x; v[c][1] = t4.y; v[c][2] = t4.z; v[c][3] = t4.w;
+                }
+                uint4 *dst = xl + (chi * p.RHa + r) * p.pitch + p.padl + 8 * x8;
+#pragma unroll
+                for (int px = 0; px < 8; ++px) {
+                    const uint32_t sel = (px & 1) ? 0x07060302u : 0x05040100u;
+                    uint32_t d[4];
+#pragma unroll
+                    for (int qq = 0; qq < 4; ++qq)
+                        d[qq] = __builtin_amdgcn_perm(v[2 * qq + 1][px >> 1], v[2 * qq][px >> 1], sel);
+                    dst[px] = make_uint4(d[0], d[1], d[2], d[3]);
+                }
+            }
+        } else {
+            const int nu = p.nchi * p.RHa * p.W;
+            for (int u = tid; u < nu; u += 256) {
+                const int q = u / p.W;
+                const int xg = u - q * p.W;
+                const int chi = q / p.RHa;
+                const int r = q - chi * p.RHa;
+                if (r >= RH) continue;
+                const int gy = yA + r;
+                uint32_t d[4] = {0, 0, 0, 0};
+                if (gy >= 0 && gy < p.H) {
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) {
+                        const int ch = chi * 8 + c;
+                        if (ch < p.Cin)
+                            d[c >> 1] |= (uint32_t)x[(((size_t)n * p.Cin + ch) * p.H + gy) * p.W + xg] << (16 * (c & 1));
+                    }
+                }
+                xl[(chi * p.RHa + r) * p.pitch + p.padl + xg] = make_uint4(d[0], d[1], d[2], d[3]);
+            }
+        }
+        __syncthreads();
+
+        int m[PXW];
+        int pbase[PXW];
+#pragma unroll
+        for (int pb = 0; pb < PXW; ++pb) {
+            m[pb] = m0 + (wave * PXW + pb) * 32 + c32;
+            const int mm = min(m[pb], ohw - 1);
+            const int oy = (int)fdiv((uint32_t)mm, p.div_ow);
+            const int ox = mm - oy * p.OW;
+            // staged column of tap kx = 0 is padl - pw + ox*sw
+            pbase[pb] = ((h * half_nchi * p.RHa) + (oy - oyA) * p.sh) * p.pitch + (p.padl - p.pw) + ox * p.sw;
+        }
+
+        floatx16 acc[CB][PXW];
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int pb = 0; pb < PXW; ++pb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[cb][pb][r] = 0.0f;
+
+        int s = 0;
+        for (int chip = 0; chip < half_nchi; ++chip)
+            for (int ky = 0; ky < p.kh; ++ky) {
+                const int rowoff = (chip * p.RHa + ky) * p.pitch;
+                for (int kx = 0; kx < p.kw; ++kx, ++s) {
+                    Frag a[CB], b[PXW];
+#pragma unroll
+                    for (int cb = 0; cb < CB; ++cb) a[cb].u = wl[(s * CB + cb) * 64 + lane];
+#pragma unroll
+                    for (int pb = 0; pb < PXW; ++pb) b[pb].u = xl[pbase[pb] + rowoff + kx];
+#pragma unroll
+                    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                        for (int pb = 0; pb < PXW; ++pb) acc[cb][pb] = mfma16(a[cb], b[pb], acc[cb][pb]);
+                }
+            }
+        store_tile<CB, PXW>(p, acc, y, n, co_base, m, lane);
+    }
+}
+
+// ---------------------------------------------------------------------------
+template <typename K>
+static hipError_t launch(K kernel, const ConvParams &p, const void *x, const void *w, void *y,
+                         hipStream_t s, uint32_t gx, size_t lds_bytes)
+{
+    if (lds_bytes > 48 * 1024) {
+        // raise the kernel's dynamic-LDS limit (up to 160 KB per workgroup on gfx950)
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kernel, dim3(gx, (uint32_t)p.co_groups), dim3(256), lds_bytes, s, p,
+                       reinterpret_cast<const uint16_t *>(x), reinterpret_cast<const uint16_t *>(w),
+                       reinterpret_cast<_Float16 *>(y));
+    return hipGetLastError();
+}
+
+size_t conv_lds_bytes(const ConvParams &p)
+{
+    if (p.variant == CONV_PLANAR_SMALLC) return (size_t)p.lds_w_bytes + 32 + p.lds_x_bytes + (size_t)p.G2 * 4;
+    return (size_t)p.lds_w_bytes + p.lds_x_bytes;
+}
+
+hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, void *y, hipStream_t s)
+{
+    const int64_t ntiles = (int64_t)p.N * p.tiles_per_image;
+    if (ntiles == 0) return hipSuccess;
+    const uint32_t gx = (uint32_t)ntiles;
+    const size_t lds = conv_lds_bytes(p);
+    if (p.variant == CONV_PLANAR_SMALLC) {
+        if (p.CB == 2 && p.PXW == 2) return launch(merit_conv2d_planar<2, 2>, p, x, w, y, s, gx, lds);
+        if (p.CB == 2 && p.PXW == 1) return launch(merit_conv2d_planar<2, 1>, p, x, w, y, s, gx, lds);
+        if (p.CB == 1 && p.PXW == 2) return launch(merit_conv2d_planar<1, 2>, p, x, w, y, s, gx, lds);
+        return launch(merit_conv2d_planar<1, 1>, p, x, w, y, s, gx, lds);
+    }
+    if (p.CB == 2 && p.PXW == 2) return launch(merit_conv2d_chblock<2, 2>, p, x, w, y, s, gx, lds);
+    if (p.CB == 2 && p.PXW == 1) return launch(merit_conv2d_chblock<2, 1>, p, x, w, y, s, gx, lds);
+    if (p.CB == 1 && p.PXW == 2) return launch(merit_conv2d_chblock<1, 2>, p, x, w, y, s, gx, lds);
+    return launch(merit_conv2d_chblock<1, 1>, p, x, w, y, s, gx, lds);
+}
+
+const char *conv_kernel_name(const ConvParams &p)
+{
+    return p.variant == CONV_PLANAR_SMALLC ? "merit_conv2d_planar" : "merit_conv2d_chblock";
+}
+
+}  // namespace merit

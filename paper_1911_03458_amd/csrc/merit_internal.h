@@ -1,0 +1,113 @@
+// Internal declarations shared by the host plan code and the HIP kernels.
+// Not part of the public ABI (that is include/merit.h).
+#pragma once
+
+#include <stdint.h>
+#include <hip/hip_runtime.h>
+
+#include "merit.h"
+
+namespace merit {
+
+// ---- small integer helpers -------------------------------------------------
+
+// q = n / d as (n * magic) >> 32 with magic = floor(2^32 / d) + 1.  Exact for
+// every n with (n + d) * d < 2^32; the plan code checks that bound for each use.
+struct FastDiv {
+    uint32_t d;
+    uint32_t magic;
+};
+inline FastDiv make_fastdiv(uint32_t d)
+{
+    FastDiv f;
+    f.d = d;
+    f.magic = (uint32_t)((0x100000000ull / d) + 1ull);
+    return f;
+}
+
+// ---- pooling ---------------------------------------------------------------
+enum PoolVariant { POOL_TILE_GENERIC = 0, POOL_ROWS_K3S2P1 = 1, POOL_ROWS_K2S2P0 = 2, POOL_ROWS_K3S1P1 = 3 };
+
+struct PoolParams {
+    int NC, H, W, OH, OW;
+    int kh, kw, sh, sw, ph, pw;
+    int is_avg;
+    int variant;
+    int TH, TW;            // outputs per workgroup tile
+    int tiles_y, tiles_x;
+    int RH, RW, pitch;     // staged region (rows, cols) and LDS row pitch in floats
+    FastDiv div_tiles_x, div_tiles_y;
+    FastDiv div_rw;        // generic: staged columns
+    FastDiv div_tw;        // generic: tile columns
+    FastDiv div_p4;        // rows variant: float4 per staged row
+    FastDiv div_ow4;       // rows variant: float4 per output row
+};
+
+// ---- block matching --------------------------------------------------------
+enum SadVariant { SAD_GENERIC = 0, SAD_ROWSCAN_B16 = 1 };
+
+struct SadParams {
+    int H, W, B, R, n;     // n = 2R+1 candidates per axis
+    int nby, nbx;
+    int win;               // B + 2R: search window edge in pixels
+    int pitch;             // LDS bytes per window row (multiple of 4)
+    int variant;
+    int bpw;               // blocks per workgroup (rowscan variant)
+    int groups_x;          // workgroups per block row (rowscan variant)
+    FastDiv div_n;
+    FastDiv div_win4;      // dwords per staged window row
+    FastDiv div_nbx;
+};
+
+// ---- convolution -----------------------------------------------------------
+enum ConvVariant { CONV_PLANAR_SMALLC = 0, CONV_CHBLOCK = 1 };
+
+struct ConvParams {
+    int N, Cin, H, W, Cout, OH, OW;
+    int kh, kw, sh, sw, ph, pw;
+    int variant;
+    int TM;                // output pixels (linear, row-major within an image) per workgroup
+    int PXW;               // 32-pixel blocks per wave
+    int CB;                // 32-channel output blocks per workgroup
+    int tiles_per_image;
+    int co_groups;         // grid.y
+    int rows_out_max;      // output rows a tile can touch
+    int RHa;               // staged input rows (allocated)
+    int pitch;             // staged row pitch: halves (planar) or pixels (channel-blocked)
+    int padl;              // staged column of input x = 0
+    int G, G2;             // planar: (ci,ky) groups and padded-even count
+    int S;                 // MFMA K-steps (K = 16 each)
+    int nchi;              // channel-blocked: 8-channel groups incl. zero padding (even)
+    int lds_w_bytes;       // weights region
+    int lds_x_bytes;       // input region
+    FastDiv div_ow;
+    FastDiv div_kh;
+    FastDiv div_pitch8;    // planar staging: 16-byte units per staged row
+    FastDiv div_rha;
+    FastDiv div_g2;
+    FastDiv div_w8;        // channel-blocked staging: 8-pixel chunks per row
+    FastDiv div_tiles;
+};
+
+// ---- launchers (defined in the .hip files) --------------------------------
+hipError_t launch_pool2d(const PoolParams &p, const float *x, float *y, hipStream_t s);
+hipError_t launch_sad(const SadParams &p, const uint8_t *cur, const uint8_t *ref,
+                      int32_t *sad, int32_t *mv, hipStream_t s);
+hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, void *y, hipStream_t s);
+
+const char *pool_kernel_name(const PoolParams &p);
+const char *sad_kernel_name(const SadParams &p);
+const char *conv_kernel_name(const ConvParams &p);
+
+}  // namespace merit
+
+struct merit_plan {
+    merit_plan_desc desc;
+    int64_t tile_req[MERIT_MAX_INDEX];   // caller's tile override, 0 = library default
+    int32_t out_ndim;
+    int64_t out_shape[MERIT_MAX_DIMS];
+    merit::PoolParams pool;
+    merit::SadParams sad;
+    merit::ConvParams conv;
+    merit_launch_info info;
+};

@@ -1,0 +1,564 @@
+// Host side of the library: plan validation, derived geometry, and the C ABI.
+//
+// A plan holds the paper's transform descriptor (per index an axis d_j, stride
+// s_j and offset o_j per operand; Section III-C, Eq. 5) after it has been
+// matched against the three index patterns the kernels implement, plus the
+// tile / halo geometry derived from it with the footprint rule of Section
+// IV-A, Eq. 9.  No GPU call happens here.
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "merit_internal.h"
+
+using namespace merit;
+
+namespace merit {
+size_t conv_lds_bytes(const ConvParams &p);
+}
+
+namespace {
+
+constexpr int64_t LDS_LIMIT = 160 * 1024;       // per workgroup on gfx950
+constexpr int64_t INT_LIMIT = 1ll << 30;
+
+inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline int64_t round_up(int64_t a, int64_t b) { return cdiv(a, b) * b; }
+
+// FastDiv is exact when (nmax + d) * d < 2^32.
+inline bool fastdiv_ok(int64_t nmax, int64_t d) { return d >= 1 && (nmax + d) * d < (1ll << 32); }
+
+bool operand_is(const merit_operand &o, int n_index, const int *axis, const int64_t *stride,
+                const int64_t *offset /* may hold INT64_MIN = "don't care" */)
+{
+    for (int j = 0; j < n_index; ++j) {
+        if (o.axis[j] != axis[j]) return false;
+        if (axis[j] == MERIT_AXIS_UNUSED) continue;
+        if (stride && stride[j] != INT64_MIN && o.stride[j] != stride[j]) return false;
+        if (offset && offset[j] != INT64_MIN && o.offset[j] != offset[j]) return false;
+    }
+    return true;
+}
+
+int64_t out_extent(int64_t I, int64_t k, int64_t s, int64_t p) { return (I + 2 * p - k) / s + 1; }
+
+// ---------------------------------------------------------------- pooling ---
+merit_status derive_pool(merit_plan *pl)
+{
+    const merit_plan_desc &d = pl->desc;
+    const bool is_avg = d.op == MERIT_OP_POOL_AVG;
+    if (d.dtype != MERIT_F32) return MERIT_ERR_UNSUPPORTED;
+    if (d.pad != (is_avg ? MERIT_PAD_EXCLUDE : MERIT_PAD_NEG_INF)) return MERIT_ERR_UNSUPPORTED;
+    if (d.n_par != 4 || d.n_acc != 2) return MERIT_ERR_UNSUPPORTED;
+    if (d.a.ndim != 4 || d.b.ndim != 0) return MERIT_ERR_UNSUPPORTED;
+    const int axis[6] = {0, 1, 2, 3, 2, 3};
+    const int64_t DC = INT64_MIN;
+    const int64_t stride[6] = {1, 1, DC, DC, 1, 1};
+    const int64_t offset[6] = {0, 0, 0, 0, DC, DC};
+    if (!operand_is(d.a, 6, axis, stride, offset)) return MERIT_ERR_UNSUPPORTED;
+
+    const int64_t N = d.a.shape[0], C = d.a.shape[1], H = d.a.shape[2], W = d.a.shape[3];
+    const int64_t OH = d.range[2], OW = d.range[3], kh = d.range[4], kw = d.range[5];
+    const int64_t sh = d.a.stride[2], sw = d.a.stride[3];
+    const int64_t ph = -d.a.offset[4], pw = -d.a.offset[5];
+    if (N < 0 || C <= 0 || H <= 0 || W <= 0 || kh <= 0 || kw <= 0 || sh <= 0 || sw <= 0 || ph < 0 || pw < 0)
+        return MERIT_ERR_INVALID_ARG;
+    if (d.range[0] != N || d.range[1] != C) return MERIT_ERR_SHAPE;
+    if (H + 2 * ph < kh || W + 2 * pw < kw) return MERIT_ERR_SHAPE;
+    if (OH != out_extent(H, kh, sh, ph) || OW != out_extent(W, kw, sw, pw)) return MERIT_ERR_SHAPE;
+    if (N * C >= INT_LIMIT || H * W >= INT_LIMIT || kh > 64 || kw > 64 || sh > 64 || sw > 64)
+        return MERIT_ERR_UNSUPPORTED;
+
+    PoolParams &p = pl->pool;
+    p.NC = (int)(N * C); p.H = (int)H; p.W = (int)W; p.OH = (int)OH; p.OW = (int)OW;
+    p.kh = (int)kh; p.kw = (int)kw; p.sh = (int)sh; p.sw = (int)sw; p.ph = (int)ph; p.pw = (int)pw;
+    p.is_avg = is_avg ? 1 : 0;
+
+    // row-strip variants: full-width strips, 16-byte accesses
+    int variant = POOL_TILE_GENERIC;
+    // staged rows carry 4 fill columns on either side; the last thread of a row reads
+    // whole 16-byte chunks up to float 4*C1 past its span start
+    const int64_t C1 = (4 - pw + 3 * sw + kw + 3) / 4;
+    const bool rows_ok = (W % 4 == 0) && (OW % 4 == 0) && pw <= 4 &&
+                         ((OW - 4) * sw + 4 * C1 <= W + 8);
+    if (rows_ok) {
+        if (kh == 3 && kw == 3 && sh == 2 && sw == 2 && pw == 1) variant = POOL_ROWS_K3S2P1;
+        else if (kh == 2 && kw == 2 && sh == 2 && sw == 2 && pw == 0) variant = POOL_ROWS_K2S2P0;
+        else if (kh == 3 && kw == 3 && sh == 1 && sw == 1 && pw == 1) variant = POOL_ROWS_K3S1P1;
+    }
+    if (variant != POOL_TILE_GENERIC) {
+        const int64_t pitch = W + 8;
+        // strip height: as many output rows as keep the staged rows within ~16 KB,
+        // then balanced so that all strips of a plane are (nearly) equal
+        int64_t TH = (16 * 1024 / (pitch * 4) - kh) / sh + 1;
+        if (TH < 1) TH = 1;
+        if (TH > OH) TH = OH;
+        TH = cdiv(OH, cdiv(OH, TH));
+        if (pl->tile_req[2] > 0) TH = pl->tile_req[2] < OH ? pl->tile_req[2] : OH;
+        const int64_t RH = (TH - 1) * sh + kh;
+        if (RH * pitch * 4 > LDS_LIMIT || !fastdiv_ok(RH * (pitch / 4), pitch / 4) ||
+            !fastdiv_ok(TH * (OW / 4), OW / 4)) {
+            variant = POOL_TILE_GENERIC;
+        } else {
+            p.variant = variant;
+            p.TH = (int)TH; p.TW = (int)OW;
+            p.tiles_y = (int)cdiv(OH, TH); p.tiles_x = 1;
+            p.RH = (int)RH; p.RW = (int)pitch; p.pitch = (int)pitch;
+            p.div_p4 = make_fastdiv((uint32_t)(pitch / 4));
+            p.div_ow4 = make_fastdiv((uint32_t)(OW / 4));
+        }
+    }
+    if (variant == POOL_TILE_GENERIC) {
+        p.variant = POOL_TILE_GENERIC;
+        int64_t TW = OW < 64 ? OW : 64;
+        int64_t TH = OH < 16 ? OH : 16;
+        if (pl->tile_req[2] > 0) TH = pl->tile_req[2] < OH ? pl->tile_req[2] : OH;
+        if (pl->tile_req[3] > 0) TW = pl->tile_req[3] < OW ? pl->tile_req[3] : OW;
+        // shrink until the staged region fits comfortably
+        for (;;) {
+            const int64_t RH = (TH - 1) * sh + kh, RW = (TW - 1) * sw + kw;
+            if (RH * (RW + 1) * 4 <= 64 * 1024 || (TH == 1 && TW == 1)) break;
+            if (TH > 1) TH = (TH + 1) / 2; else TW = (TW + 1) / 2;
+        }
+        const int64_t RH = (TH - 1) * sh + kh, RW = (TW - 1) * sw + kw;
+        if (RH * (RW + 1) * 4 > LDS_LIMIT) return MERIT_ERR_UNSUPPORTED;
+        if (!fastdiv_ok(RH * RW, RW) || !fastdiv_ok(TH * TW, TW)) return MERIT_ERR_UNSUPPORTED;
+        p.TH = (int)TH; p.TW = (int)TW;
+        p.tiles_y = (int)cdiv(OH, TH); p.tiles_x = (int)cdiv(OW, TW);
+        p.RH = (int)RH; p.RW = (int)RW; p.pitch = (int)RW + 1;
+        p.div_rw = make_fastdiv((uint32_t)RW);
+        p.div_tw = make_fastdiv((uint32_t)TW);
+    }
+    const int64_t grid = (int64_t)p.NC * p.tiles_y * p.tiles_x;
+    if (grid >= (1ll << 31)) return MERIT_ERR_UNSUPPORTED;
+
+    pl->out_ndim = 4;
+    pl->out_shape[0] = N; pl->out_shape[1] = C; pl->out_shape[2] = OH; pl->out_shape[3] = OW;
+    merit_launch_info &li = pl->info;
+    li.kernel = pool_kernel_name(p);
+    li.grid[0] = grid; li.grid[1] = 1; li.grid[2] = 1;
+    li.block[0] = 256; li.block[1] = 1; li.block[2] = 1;
+    li.lds_bytes = (int64_t)p.RH * p.pitch * 4;
+    li.tile[0] = 1; li.tile[1] = 1; li.tile[2] = p.TH; li.tile[3] = p.TW; li.tile[4] = kh; li.tile[5] = kw;
+    return MERIT_OK;
+}
+
+// ----------------------------------------------------------- block matching ---
+merit_status derive_sad(merit_plan *pl)
+{
+    const merit_plan_desc &d = pl->desc;
+    if (d.dtype != MERIT_U8 || d.pad != MERIT_PAD_CLAMP) return MERIT_ERR_UNSUPPORTED;
+    if (d.n_par != 2 || d.n_acc != 4) return MERIT_ERR_UNSUPPORTED;
+    if (d.a.ndim != 2 || d.b.ndim != 2) return MERIT_ERR_UNSUPPORTED;
+    const int64_t B = d.range[4], n = d.range[2];
+    if (B <= 0 || n <= 0 || d.range[5] != B || d.range[3] != n || (n % 2) == 0) return MERIT_ERR_SHAPE;
+    const int64_t R = (n - 1) / 2;
+    const int axis_ref[6] = {0, 1, 0, 1, 0, 1};
+    const int64_t stride_ref[6] = {B, B, 1, 1, 1, 1};
+    const int64_t offset_ref[6] = {0, 0, -R, -R, 0, 0};
+    const int axis_cur[6] = {0, 1, MERIT_AXIS_UNUSED, MERIT_AXIS_UNUSED, 0, 1};
+    const int64_t stride_cur[6] = {B, B, 0, 0, 1, 1};
+    const int64_t offset_cur[6] = {0, 0, 0, 0, 0, 0};
+    if (!operand_is(d.a, 6, axis_ref, stride_ref, offset_ref)) return MERIT_ERR_UNSUPPORTED;
+    if (!operand_is(d.b, 6, axis_cur, stride_cur, offset_cur)) return MERIT_ERR_UNSUPPORTED;
+    const int64_t H = d.a.shape[0], W = d.a.shape[1];
+    if (H <= 0 || W <= 0) return MERIT_ERR_INVALID_ARG;
+    if (d.b.shape[0] != H || d.b.shape[1] != W) return MERIT_ERR_SHAPE;
+    if (H % B || W % B) return MERIT_ERR_SHAPE;
+    if (d.range[0] != H / B || d.range[1] != W / B) return MERIT_ERR_SHAPE;
+    // key packing: SAD < 2^18 and raster index < 2^14 share one u32
+    if (B % 4 || B > 32 || R > 63) return MERIT_ERR_UNSUPPORTED;
+    if (H * W >= INT_LIMIT || (H / B) * (W / B) >= INT_LIMIT) return MERIT_ERR_UNSUPPORTED;
+
+    SadParams &p = pl->sad;
+    p.H = (int)H; p.W = (int)W; p.B = (int)B; p.R = (int)R; p.n = (int)n;
+    p.nby = (int)(H / B); p.nbx = (int)(W / B);
+    p.win = (int)(B + 2 * R);
+    const int64_t cols4 = cdiv(p.win, 4);
+    p.pitch = (int)((cols4 + 1) * 4);
+    p.variant = SAD_GENERIC;
+    p.bpw = 1; p.groups_x = p.nbx;
+    if (!fastdiv_ok(n * n, n) || !fastdiv_ok((int64_t)p.win * cols4, cols4)) return MERIT_ERR_UNSUPPORTED;
+    p.div_n = make_fastdiv((uint32_t)n);
+    p.div_win4 = make_fastdiv((uint32_t)cols4);
+    p.div_nbx = make_fastdiv((uint32_t)p.nbx);
+
+    pl->out_ndim = 2;
+    pl->out_shape[0] = p.nby; pl->out_shape[1] = p.nbx;
+    merit_launch_info &li = pl->info;
+    li.kernel = sad_kernel_name(p);
+    li.grid[0] = (int64_t)p.nby * p.nbx; li.grid[1] = 1; li.grid[2] = 1;
+    li.block[0] = 256; li.block[1] = 1; li.block[2] = 1;
+    li.lds_bytes = ((int64_t)p.win * (p.pitch / 4) + 1 + B * (B / 4) + 4) * 4;
+    li.tile[0] = 1; li.tile[1] = 1; li.tile[2] = n; li.tile[3] = n; li.tile[4] = B; li.tile[5] = B;
+    return MERIT_OK;
+}
+
+// -------------------------------------------------------------- convolution ---
+merit_status derive_conv(merit_plan *pl)
+{
+    const merit_plan_desc &d = pl->desc;
+    if (d.dtype != MERIT_F16 || d.pad != MERIT_PAD_ZERO) return MERIT_ERR_UNSUPPORTED;
+    if (d.n_par != 4 || d.n_acc != 3) return MERIT_ERR_UNSUPPORTED;
+    if (d.a.ndim != 4 || d.b.ndim != 4) return MERIT_ERR_UNSUPPORTED;
+    const int64_t DC = INT64_MIN;
+    const int axis_x[7] = {0, MERIT_AXIS_UNUSED, 2, 3, 1, 2, 3};
+    const int64_t stride_x[7] = {1, 0, DC, DC, 1, 1, 1};        // unit window stride: no dilation
+    const int64_t offset_x[7] = {0, 0, 0, 0, 0, DC, DC};
+    const int axis_w[7] = {MERIT_AXIS_UNUSED, 0, MERIT_AXIS_UNUSED, MERIT_AXIS_UNUSED, 1, 2, 3};
+    const int64_t stride_w[7] = {0, 1, 0, 0, 1, 1, 1};
+    const int64_t offset_w[7] = {0, 0, 0, 0, 0, 0, 0};
+    if (!operand_is(d.a, 7, axis_x, stride_x, offset_x)) return MERIT_ERR_UNSUPPORTED;
+    if (!operand_is(d.b, 7, axis_w, stride_w, offset_w)) return MERIT_ERR_UNSUPPORTED;
+
+    const int64_t N = d.a.shape[0], Cin = d.a.shape[1], H = d.a.shape[2], W = d.a.shape[3];
+    const int64_t Cout = d.b.shape[0], kh = d.b.shape[2], kw = d.b.shape[3];
+    const int64_t sh = d.a.stride[2], sw = d.a.stride[3];
+    const int64_t ph = -d.a.offset[5], pw = -d.a.offset[6];
+    const int64_t OH = d.range[2], OW = d.range[3];
+    if (N < 0 || Cin <= 0 || H <= 0 || W <= 0 || Cout <= 0 || kh <= 0 || kw <= 0 || sh <= 0 || sw <= 0 ||
+        ph < 0 || pw < 0)
+        return MERIT_ERR_INVALID_ARG;
+    if (d.b.shape[1] != Cin || d.range[0] != N || d.range[1] != Cout || d.range[4] != Cin ||
+        d.range[5] != kh || d.range[6] != kw)
+        return MERIT_ERR_SHAPE;
+    if (H + 2 * ph < kh || W + 2 * pw < kw) return MERIT_ERR_SHAPE;
+    if (OH != out_extent(H, kh, sh, ph) || OW != out_extent(W, kw, sw, pw)) return MERIT_ERR_SHAPE;
+    if (N * Cin * H * W >= (1ll << 40) || OH * OW >= (1 << 24) || Cin > 4096 || Cout > 65535 * 32 ||
+        kh > 31 || kw > 31 || sh > 16 || sw > 16)
+        return MERIT_ERR_UNSUPPORTED;
+
+    ConvParams &p = pl->conv;
+    p.N = (int)N; p.Cin = (int)Cin; p.H = (int)H; p.W = (int)W; p.Cout = (int)Cout;
+    p.OH = (int)OH; p.OW = (int)OW; p.kh = (int)kh; p.kw = (int)kw; p.sh = (int)sh; p.sw = (int)sw;
+    p.ph = (int)ph; p.pw = (int)pw;
+
+    const int64_t ohw = OH * OW;
+    const int64_t ncb = cdiv(Cout, 32);
+    p.CB = ncb >= 2 ? 2 : 1;
+    p.co_groups = (int)cdiv(ncb, p.CB);
+
+    // try both tile sizes for a variant; prefer 256 pixels when the grid stays large
+    auto try_variant = [&](int variant, int pxw) -> bool {
+        ConvParams q = p;
+        q.variant = variant;
+        q.PXW = pxw;
+        q.TM = 4 * pxw * 32;
+        q.tiles_per_image = (int)cdiv(ohw, q.TM);
+        q.rows_out_max = (int)((q.TM + OW - 2) / OW + 1);
+        if (q.rows_out_max > OH) q.rows_out_max = (int)OH;
+        q.RHa = (int)((q.rows_out_max - 1) * sh + kh);
+        if (variant == CONV_PLANAR_SMALLC) {
+            if (kw > 8 || pw > 8) return false;
+            q.padl = 8;
+            int64_t pitch = q.padl + W;
+            const int64_t reach = q.padl - pw + (OW - 1) * sw + 10;
+            if (reach > pitch) pitch = reach;
+            q.pitch = (int)round_up(pitch, 8);
+            q.G = (int)(Cin * kh);
+            q.G2 = (int)round_up(q.G, 2);
+            q.S = q.G2 / 2;
+            q.nchi = 0;
+            q.lds_w_bytes = q.CB * q.G2 * 32 * 16;
+            q.lds_x_bytes = (int)(Cin * q.RHa * q.pitch * 2);
+            if (!fastdiv_ok((int64_t)Cin * q.RHa * (q.pitch / 8), q.pitch / 8)) return false;
+            if (!fastdiv_ok((int64_t)Cin * q.RHa, q.RHa) || !fastdiv_ok(q.G2, kh)) return false;
+            q.div_pitch8 = make_fastdiv((uint32_t)(q.pitch / 8));
+            q.div_kh = make_fastdiv((uint32_t)kh);
+            q.div_g2 = make_fastdiv((uint32_t)q.G2);
+        } else {
+            q.nchi = (int)(cdiv(Cin, 16) * 2);
+            q.padl = (int)pw;
+            int64_t pitch = q.padl + W;
+            const int64_t reach = (OW - 1) * sw + kw;
+            if (reach > pitch) pitch = reach;
+            q.pitch = (int)pitch;
+            q.G = q.G2 = 0;
+            q.S = (int)((q.nchi / 2) * kh * kw);
+            q.lds_w_bytes = q.S * q.CB * 64 * 16;
+            q.lds_x_bytes = (int)((int64_t)q.nchi * q.RHa * q.pitch * 16);
+            if ((W % 8) == 0) {
+                if (!fastdiv_ok((int64_t)q.nchi * q.RHa * (W / 8), W / 8)) return false;
+                q.div_w8 = make_fastdiv((uint32_t)(W / 8));
+            }
+            if (!fastdiv_ok((int64_t)q.nchi * q.RHa, q.RHa)) return false;
+        }
+        q.div_rha = make_fastdiv((uint32_t)q.RHa);
+        if ((int64_t)conv_lds_bytes(q) > LDS_LIMIT) return false;
+        if (!fastdiv_ok(ohw, OW) || !fastdiv_ok((int64_t)N * q.tiles_per_image, q.tiles_per_image)) return false;
+        q.div_ow = make_fastdiv((uint32_t)OW);
+        q.div_tiles = make_fastdiv((uint32_t)q.tiles_per_image);
+        p = q;
+        return true;
+    };
+
+    bool want_big = N * cdiv(ohw, 256) * p.co_groups >= 512;
+    if (pl->tile_req[2] > 0 && pl->tile_req[3] > 0) {
+        const int64_t tm = pl->tile_req[2] * pl->tile_req[3];
+        if (tm != 128 && tm != 256) return MERIT_ERR_UNSUPPORTED;
+        want_big = tm == 256;
+    }
+    const int first = want_big ? 2 : 1, second = want_big ? 1 : 2;
+    bool ok = false;
+    if (Cin < 8) ok = try_variant(CONV_PLANAR_SMALLC, first) || try_variant(CONV_PLANAR_SMALLC, second);
+    if (!ok) ok = try_variant(CONV_CHBLOCK, first) || try_variant(CONV_CHBLOCK, second);
+    if (!ok) return MERIT_ERR_UNSUPPORTED;
+    if ((int64_t)N * p.tiles_per_image >= (1ll << 31)) return MERIT_ERR_UNSUPPORTED;
+
+    pl->out_ndim = 4;
+    pl->out_shape[0] = N; pl->out_shape[1] = Cout; pl->out_shape[2] = OH; pl->out_shape[3] = OW;
+    merit_launch_info &li = pl->info;
+    li.kernel = conv_kernel_name(p);
+    li.grid[0] = (int64_t)N * p.tiles_per_image; li.grid[1] = p.co_groups; li.grid[2] = 1;
+    li.block[0] = 256; li.block[1] = 1; li.block[2] = 1;
+    li.lds_bytes = (int64_t)conv_lds_bytes(p);
+    li.tile[0] = 1; li.tile[1] = p.CB * 32; li.tile[2] = p.rows_out_max; li.tile[3] = OW;
+    li.tile[4] = Cin; li.tile[5] = kh; li.tile[6] = kw;
+    return MERIT_OK;
+}
+
+bool aligned16(const void *ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15u) == 0; }
+
+}  // namespace
+
+// ============================================================== C ABI ======
+extern "C" {
+
+merit_status merit_plan_create(const merit_plan_desc *desc, merit_plan **out)
+{
+    if (!desc || !out) return MERIT_ERR_NULL;
+    *out = nullptr;
+    if ((int)desc->op < 0 || (int)desc->op > 3 || (int)desc->dtype < 0 || (int)desc->dtype > 2 ||
+        (int)desc->pad < 0 || (int)desc->pad > 3)
+        return MERIT_ERR_INVALID_ARG;
+    if (desc->n_par < 1 || desc->n_acc < 1 || desc->n_par + desc->n_acc > MERIT_MAX_INDEX)
+        return MERIT_ERR_INVALID_ARG;
+    if (desc->a.ndim < 1 || desc->a.ndim > MERIT_MAX_DIMS || desc->b.ndim < 0 || desc->b.ndim > MERIT_MAX_DIMS)
+        return MERIT_ERR_INVALID_ARG;
+    const int nidx = desc->n_par + desc->n_acc;
+    for (int j = 0; j < nidx; ++j) {
+        if (desc->range[j] < 0) return MERIT_ERR_INVALID_ARG;
+        if (desc->a.axis[j] < MERIT_AXIS_UNUSED || desc->a.axis[j] >= desc->a.ndim) return MERIT_ERR_INVALID_ARG;
+        if (desc->b.ndim > 0 && (desc->b.axis[j] < MERIT_AXIS_UNUSED || desc->b.axis[j] >= desc->b.ndim))
+            return MERIT_ERR_INVALID_ARG;
+    }
+    merit_plan *pl = new (std::nothrow) merit_plan;
+    if (!pl) return MERIT_ERR_INVALID_ARG;
+    std::memset(pl, 0, sizeof(*pl));
+    pl->desc = *desc;
+    merit_status st;
+    switch (desc->op) {
+    case MERIT_OP_CONV_DOT: st = derive_conv(pl); break;
+    case MERIT_OP_POOL_MAX:
+    case MERIT_OP_POOL_AVG: st = derive_pool(pl); break;
+    default: st = derive_sad(pl); break;
+    }
+    if (st != MERIT_OK) {
+        delete pl;
+        return st;
+    }
+    *out = pl;
+    return MERIT_OK;
+}
+
+merit_status merit_plan_destroy(merit_plan *plan)
+{
+    if (!plan) return MERIT_ERR_NULL;
+    delete plan;
+    return MERIT_OK;
+}
+
+merit_status merit_plan_conv2d(int N, int Cin, int H, int W, int Cout, int kh, int kw, int sh, int sw,
+                               int ph, int pw, merit_plan **out)
+{
+    if (!out) return MERIT_ERR_NULL;
+    *out = nullptr;
+    if (N < 0 || Cin <= 0 || H <= 0 || W <= 0 || Cout <= 0 || kh <= 0 || kw <= 0 || sh <= 0 || sw <= 0 ||
+        ph < 0 || pw < 0)
+        return MERIT_ERR_INVALID_ARG;
+    if (H + 2 * ph < kh || W + 2 * pw < kw) return MERIT_ERR_SHAPE;
+    merit_plan_desc d;
+    std::memset(&d, 0, sizeof(d));
+    d.op = MERIT_OP_CONV_DOT; d.dtype = MERIT_F16; d.pad = MERIT_PAD_ZERO;
+    d.n_par = 4; d.n_acc = 3;
+    const int64_t OH = out_extent(H, kh, sh, ph), OW = out_extent(W, kw, sw, pw);
+    const int64_t range[7] = {N, Cout, OH, OW, Cin, kh, kw};
+    const int ax[7] = {0, MERIT_AXIS_UNUSED, 2, 3, 1, 2, 3};
+    const int64_t sx[7] = {1, 0, sh, sw, 1, 1, 1};
+    const int64_t ox[7] = {0, 0, 0, 0, 0, -ph, -pw};
+    const int aw[7] = {MERIT_AXIS_UNUSED, 0, MERIT_AXIS_UNUSED, MERIT_AXIS_UNUSED, 1, 2, 3};
+    const int64_t sw_[7] = {0, 1, 0, 0, 1, 1, 1};
+    for (int j = 0; j < 7; ++j) {
+        d.range[j] = range[j];
+        d.a.axis[j] = ax[j]; d.a.stride[j] = sx[j]; d.a.offset[j] = ox[j];
+        d.b.axis[j] = aw[j]; d.b.stride[j] = sw_[j]; d.b.offset[j] = 0;
+    }
+    d.a.ndim = 4; d.a.shape[0] = N; d.a.shape[1] = Cin; d.a.shape[2] = H; d.a.shape[3] = W;
+    d.b.ndim = 4; d.b.shape[0] = Cout; d.b.shape[1] = Cin; d.b.shape[2] = kh; d.b.shape[3] = kw;
+    return merit_plan_create(&d, out);
+}
+
+merit_status merit_plan_pool2d(int N, int C, int H, int W, int kh, int kw, int sh, int sw, int ph, int pw,
+                               int is_avg, merit_plan **out)
+{
+    if (!out) return MERIT_ERR_NULL;
+    *out = nullptr;
+    if (N < 0 || C <= 0 || H <= 0 || W <= 0 || kh <= 0 || kw <= 0 || sh <= 0 || sw <= 0 || ph < 0 || pw < 0)
+        return MERIT_ERR_INVALID_ARG;
+    if (H + 2 * ph < kh || W + 2 * pw < kw) return MERIT_ERR_SHAPE;
+    merit_plan_desc d;
+    std::memset(&d, 0, sizeof(d));
+    d.op = is_avg ? MERIT_OP_POOL_AVG : MERIT_OP_POOL_MAX;
+    d.dtype = MERIT_F32;
+    d.pad = is_avg ? MERIT_PAD_EXCLUDE : MERIT_PAD_NEG_INF;
+    d.n_par = 4; d.n_acc = 2;
+    const int64_t OH = out_extent(H, kh, sh, ph), OW = out_extent(W, kw, sw, pw);
+    const int64_t range[6] = {N, C, OH, OW, kh, kw};
+    const int ax[6] = {0, 1, 2, 3, 2, 3};
+    const int64_t sx[6] = {1, 1, sh, sw, 1, 1};
+    const int64_t ox[6] = {0, 0, 0, 0, -ph, -pw};
+    for (int j = 0; j < 6; ++j) {
+        d.range[j] = range[j];
+        d.a.axis[j] = ax[j]; d.a.stride[j] = sx[j]; d.a.offset[j] = ox[j];
+    }
+    d.a.ndim = 4; d.a.shape[0] = N; d.a.shape[1] = C; d.a.shape[2] = H; d.a.shape[3] = W;
+    d.b.ndim = 0;
+    return merit_plan_create(&d, out);
+}
+
+merit_status merit_plan_sad(int H, int W, int block, int range, merit_plan **out)
+{
+    if (!out) return MERIT_ERR_NULL;
+    *out = nullptr;
+    if (H <= 0 || W <= 0 || block <= 0 || range < 0) return MERIT_ERR_INVALID_ARG;
+    if (H % block || W % block) return MERIT_ERR_SHAPE;
+    merit_plan_desc d;
+    std::memset(&d, 0, sizeof(d));
+    d.op = MERIT_OP_SAD_ARGMIN; d.dtype = MERIT_U8; d.pad = MERIT_PAD_CLAMP;
+    d.n_par = 2; d.n_acc = 4;
+    const int64_t n = 2 * (int64_t)range + 1;
+    const int64_t rg[6] = {H / block, W / block, n, n, block, block};
+    const int a_ref[6] = {0, 1, 0, 1, 0, 1};
+    const int64_t s_ref[6] = {block, block, 1, 1, 1, 1};
+    const int64_t o_ref[6] = {0, 0, -range, -range, 0, 0};
+    const int a_cur[6] = {0, 1, MERIT_AXIS_UNUSED, MERIT_AXIS_UNUSED, 0, 1};
+    const int64_t s_cur[6] = {block, block, 0, 0, 1, 1};
+    for (int j = 0; j < 6; ++j) {
+        d.range[j] = rg[j];
+        d.a.axis[j] = a_ref[j]; d.a.stride[j] = s_ref[j]; d.a.offset[j] = o_ref[j];
+        d.b.axis[j] = a_cur[j]; d.b.stride[j] = s_cur[j]; d.b.offset[j] = 0;
+    }
+    d.a.ndim = 2; d.a.shape[0] = H; d.a.shape[1] = W;
+    d.b.ndim = 2; d.b.shape[0] = H; d.b.shape[1] = W;
+    return merit_plan_create(&d, out);
+}
+
+merit_status merit_plan_set_tile(merit_plan *plan, const int64_t tile[MERIT_MAX_INDEX])
+{
+    if (!plan || !tile) return MERIT_ERR_NULL;
+    merit_plan trial = *plan;
+    for (int j = 0; j < MERIT_MAX_INDEX; ++j) trial.tile_req[j] = tile[j];
+    merit_status st;
+    switch (trial.desc.op) {
+    case MERIT_OP_CONV_DOT: st = derive_conv(&trial); break;
+    case MERIT_OP_POOL_MAX:
+    case MERIT_OP_POOL_AVG: st = derive_pool(&trial); break;
+    default: st = derive_sad(&trial); break;
+    }
+    if (st != MERIT_OK) return st;          // the plan keeps its previous tiling
+    *plan = trial;
+    return MERIT_OK;
+}
+
+merit_status merit_plan_get_desc(const merit_plan *plan, merit_plan_desc *out)
+{
+    if (!plan || !out) return MERIT_ERR_NULL;
+    *out = plan->desc;
+    return MERIT_OK;
+}
+
+merit_status merit_plan_out_shape(const merit_plan *plan, int32_t *ndim, int64_t shape[MERIT_MAX_DIMS])
+{
+    if (!plan || !ndim || !shape) return MERIT_ERR_NULL;
+    *ndim = plan->out_ndim;
+    for (int i = 0; i < MERIT_MAX_DIMS; ++i) shape[i] = i < plan->out_ndim ? plan->out_shape[i] : 0;
+    return MERIT_OK;
+}
+
+merit_status merit_plan_footprint(const merit_plan *plan, int which, const int64_t tile[MERIT_MAX_INDEX],
+                                  int64_t out[MERIT_MAX_DIMS])
+{
+    if (!plan || !tile || !out) return MERIT_ERR_NULL;
+    if (which != 0 && which != 1) return MERIT_ERR_INVALID_ARG;
+    const merit_operand &o = which == 0 ? plan->desc.a : plan->desc.b;
+    if (o.ndim == 0) return MERIT_ERR_INVALID_ARG;
+    const int nidx = plan->desc.n_par + plan->desc.n_acc;
+    for (int j = 0; j < nidx; ++j)
+        if (tile[j] < 1 || tile[j] > plan->desc.range[j]) return MERIT_ERR_INVALID_ARG;
+    for (int i = 0; i < MERIT_MAX_DIMS; ++i) {
+        int64_t n = 0;
+        if (i < o.ndim) {
+            n = 1;
+            for (int j = 0; j < nidx; ++j)
+                if (o.axis[j] == i) n += (tile[j] - 1) * o.stride[j];
+        }
+        out[i] = n;
+    }
+    return MERIT_OK;
+}
+
+merit_status merit_plan_launch_info(const merit_plan *plan, merit_launch_info *out)
+{
+    if (!plan || !out) return MERIT_ERR_NULL;
+    *out = plan->info;
+    return MERIT_OK;
+}
+
+merit_status merit_conv2d(const merit_plan *plan, const void *x, const void *w, void *y, void *stream)
+{
+    if (!plan || !x || !w || !y) return MERIT_ERR_NULL;
+    if (plan->desc.op != MERIT_OP_CONV_DOT) return MERIT_ERR_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return MERIT_ERR_ALIGNMENT;
+    return launch_conv2d(plan->conv, x, w, y, static_cast<hipStream_t>(stream)) == hipSuccess ? MERIT_OK
+                                                                                              : MERIT_ERR_HIP;
+}
+
+merit_status merit_pool2d(const merit_plan *plan, const void *x, void *y, void *stream)
+{
+    if (!plan || !x || !y) return MERIT_ERR_NULL;
+    if (plan->desc.op != MERIT_OP_POOL_MAX && plan->desc.op != MERIT_OP_POOL_AVG) return MERIT_ERR_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(y)) return MERIT_ERR_ALIGNMENT;
+    return launch_pool2d(plan->pool, static_cast<const float *>(x), static_cast<float *>(y),
+                         static_cast<hipStream_t>(stream)) == hipSuccess
+               ? MERIT_OK
+               : MERIT_ERR_HIP;
+}
+
+merit_status merit_sad_search(const merit_plan *plan, const void *cur, const void *ref, void *sad, void *mv,
+                              void *stream)
+{
+    if (!plan || !cur || !ref || !sad || !mv) return MERIT_ERR_NULL;
+    if (plan->desc.op != MERIT_OP_SAD_ARGMIN) return MERIT_ERR_INVALID_ARG;
+    if (!aligned16(cur) || !aligned16(ref) || !aligned16(sad) || !aligned16(mv)) return MERIT_ERR_ALIGNMENT;
+    return launch_sad(plan->sad, static_cast<const uint8_t *>(cur), static_cast<const uint8_t *>(ref),
+                      static_cast<int32_t *>(sad), static_cast<int32_t *>(mv),
+                      static_cast<hipStream_t>(stream)) == hipSuccess
+               ? MERIT_OK
+               : MERIT_ERR_HIP;
+}
+
+const char *merit_status_string(merit_status s)
+{
+    switch (s) {
+    case MERIT_OK: return "ok";
+    case MERIT_ERR_NULL: return "null pointer";
+    case MERIT_ERR_INVALID_ARG: return "invalid argument";
+    case MERIT_ERR_SHAPE: return "inconsistent shape";
+    case MERIT_ERR_UNSUPPORTED: return "transform not supported by any kernel";
+    case MERIT_ERR_ALIGNMENT: return "device pointer not 16-byte aligned";
+    case MERIT_ERR_HIP: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

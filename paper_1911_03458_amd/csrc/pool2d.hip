@@ -1,0 +1,210 @@
+// 2-D max / average pooling for gfx950: one-operand ranged reduce.
+//
+// k = (n, c, oy, ox | ky, kx);  M(x)[p,a] = x[n, c, oy*sh + ky - ph, ox*sw + kx - pw]
+// (transform of Section III-C, Eq. 5), reduced over a with max or mean.  Each
+// workgroup stages the minimal covering sub-tensor of its output tile
+// (Section IV-A, Eq. 9) in LDS with coalesced loads, resolves padding there
+// (-inf for max, 0 and an analytic count for mean) and expands the windows
+// from LDS, so HBM sees every input element about once.
+#include "merit_internal.h"
+
+#include <math.h>
+
+namespace merit {
+
+__device__ __forceinline__ uint32_t fdiv(uint32_t n, FastDiv f)
+{
+    return __umulhi(n, f.magic);
+}
+
+// ---------------------------------------------------------------------------
+// Generic tile kernel: any window / stride / padding, scalar accesses.
+// ---------------------------------------------------------------------------
+template <bool AVG>
+__global__ __launch_bounds__(256) void merit_pool2d_tile(PoolParams p, const float *__restrict__ x,
+                                                        float *__restrict__ y)
+{
+    extern __shared__ __align__(16) float lds[];
+    const int tid = threadIdx.x;
+    const uint32_t wg = blockIdx.x;
+    const uint32_t per_plane = (uint32_t)(p.tiles_x * p.tiles_y);
+    const uint32_t nc = wg / per_plane;
+    const uint32_t t = wg - nc * per_plane;
+    const int tyi = (int)(t / (uint32_t)p.tiles_x);
+    const int txi = (int)(t - (uint32_t)tyi * p.tiles_x);
+    const int oy0 = tyi * p.TH, ox0 = txi * p.TW;
+    const int y0 = oy0 * p.sh - p.ph, x0 = ox0 * p.sw - p.pw;
+    const float fill = AVG ? 0.0f : -INFINITY;
+    const float *xp = x + (size_t)nc * p.H * p.W;
+
+    const int nstage = p.RH * p.RW;
+    for (int i = tid; i < nstage; i += 256) {
+        const int r = (int)fdiv((uint32_t)i, p.div_rw);
+        const int c = i - r * p.RW;
+        const int gy = y0 + r, gx = x0 + c;
+        float v = fill;
+        if (gy >= 0 && gy < p.H && gx >= 0 && gx < p.W) v = xp[(size_t)gy * p.W + gx];
+        lds[r * p.pitch + c] = v;
+    }
+    __syncthreads();
+
+    float *yp = y + (size_t)nc * p.OH * p.OW;
+    const int nout = p.TH * p.TW;
+    for (int o = tid; o < nout; o += 256) {
+        const int ty = (int)fdiv((uint32_t)o, p.div_tw);
+        const int tx = o - ty * p.TW;
+        const int oy = oy0 + ty, ox = ox0 + tx;
+        if (oy >= p.OH || ox >= p.OW) continue;
+        const float *w = lds + (ty * p.sh) * p.pitch + tx * p.sw;
+        float acc = fill;
+        for (int ky = 0; ky < p.kh; ++ky)
+            for (int kx = 0; kx < p.kw; ++kx) {
+                const float v = w[ky * p.pitch + kx];
+                if (AVG) acc += v;
+                else acc = (v > acc) ? v : acc;
+            }
+        if (AVG) {
+            const int wy0 = oy * p.sh - p.ph, wx0 = ox * p.sw - p.pw;
+            const int cy = min(wy0 + p.kh, p.H) - max(wy0, 0);
+            const int cx = min(wx0 + p.kw, p.W) - max(wx0, 0);
+            const int cnt = max(cy, 0) * max(cx, 0);
+            acc = cnt > 0 ? acc / (float)cnt : 0.0f;
+        }
+        yp[(size_t)oy * p.OW + ox] = acc;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Row-strip kernel: a workgroup owns TH full output rows of one (n,c) plane.
+// The input rows it needs are one contiguous span of the plane, copied to LDS
+// with 16-byte loads; 4 fill columns on either side and fill rows above/below
+// make the window scan branch-free.  Each thread produces four adjacent outputs
+// and stores them as one float4.  Needs W % 4 == 0, OW % 4 == 0, PW <= 4 and
+// (OW-1)*SW - PW + KW - 1 <= W + 3.
+// ---------------------------------------------------------------------------
+template <int KH, int KW, int SH, int SW, int PW, bool AVG>
+__global__ __launch_bounds__(256) void merit_pool2d_rows(PoolParams p, const float *__restrict__ x,
+                                                        float *__restrict__ y)
+{
+    extern __shared__ __align__(16) float lds[];
+    const int tid = threadIdx.x;
+    const uint32_t wg = blockIdx.x;
+    const uint32_t nc = wg / (uint32_t)p.tiles_y;
+    const int strip = (int)(wg - nc * (uint32_t)p.tiles_y);
+    const int oy0 = strip * p.TH;
+    const int nrows = min(p.TH, p.OH - oy0);
+    const int y0 = oy0 * SH - p.ph;
+    const int RH = (nrows - 1) * SH + KH;
+    const int W4 = p.W >> 2;
+    const int P4 = W4 + 2;                    // float4 per staged row: fill | data | fill
+    const float fill = AVG ? 0.0f : -INFINITY;
+    const float4 fill4 = make_float4(fill, fill, fill, fill);
+    const float *xp = x + (size_t)nc * p.H * p.W;
+    float4 *lds4 = reinterpret_cast<float4 *>(lds);
+
+    const int nstage = RH * P4;
+    for (int i = tid; i < nstage; i += 256) {
+        const int r = (int)fdiv((uint32_t)i, p.div_p4);
+        const int c4 = i - r * P4;
+        const int gy = y0 + r;
+        float4 v = fill4;
+        if (c4 >= 1 && c4 <= W4 && gy >= 0 && gy < p.H)
+            v = reinterpret_cast<const float4 *>(xp + (size_t)gy * p.W)[c4 - 1];
+        lds4[i] = v;
+    }
+    __syncthreads();
+
+    const int OW4 = p.OW >> 2;
+    const int pitch = P4 * 4;
+    float *yp = y + (size_t)nc * p.OH * p.OW;
+    const int nout = nrows * OW4;
+    for (int o = tid; o < nout; o += 256) {
+        const int ty = (int)fdiv((uint32_t)o, p.div_ow4);
+        const int q = o - ty * OW4;
+        const int oy = oy0 + ty;
+        // 16-byte aligned start of the span the four windows read: staged column of
+        // input x = 4*q*SW - 4, so tap kx of output v sits at index 4 - PW + v*SW + kx.
+        const float *base = reinterpret_cast<const float *>(
+            __builtin_assume_aligned(lds + (ty * SH) * pitch + 4 * q * SW, 16));
+        float acc[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[v] = fill;
+#pragma unroll
+        for (int ky = 0; ky < KH; ++ky) {
+            const float *row = reinterpret_cast<const float *>(
+                __builtin_assume_aligned(base + ky * pitch, 16));
+            // the four windows touch floats [4-PW, 4-PW+SPAN) of the row: read the
+            // covering 16-byte chunks
+            constexpr int SPAN = 3 * SW + KW;
+            constexpr int C0 = (4 - PW) / 4, C1 = (4 - PW + SPAN + 3) / 4;
+            float t[(C1 - C0) * 4];
+#pragma unroll
+            for (int c = C0; c < C1; ++c) {
+                const float4 f = reinterpret_cast<const float4 *>(row)[c];
+                t[(c - C0) * 4 + 0] = f.x; t[(c - C0) * 4 + 1] = f.y;
+                t[(c - C0) * 4 + 2] = f.z; t[(c - C0) * 4 + 3] = f.w;
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+#pragma unroll
+                for (int kx = 0; kx < KW; ++kx) {
+                    const float val = t[(4 - PW) - C0 * 4 + v * SW + kx];
+                    if (AVG) acc[v] += val;
+                    else acc[v] = (val > acc[v]) ? val : acc[v];
+                }
+        }
+        if (AVG) {
+            const int wy0 = oy * SH - p.ph;
+            const int cy = min(wy0 + KH, p.H) - max(wy0, 0);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int wx0 = (4 * q + v) * SW - PW;
+                const int cx = min(wx0 + KW, p.W) - max(wx0, 0);
+                acc[v] = acc[v] / (float)(cy * cx);
+            }
+        }
+        reinterpret_cast<float4 *>(yp + (size_t)oy * p.OW)[q] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    }
+}
+
+// ---------------------------------------------------------------------------
+template <typename K>
+static hipError_t launch(K kernel, const PoolParams &p, const float *x, float *y, hipStream_t s,
+                         size_t lds_bytes, uint32_t grid)
+{
+    if (grid == 0) return hipSuccess;
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), lds_bytes, s, p, x, y);
+    return hipGetLastError();
+}
+
+hipError_t launch_pool2d(const PoolParams &p, const float *x, float *y, hipStream_t s)
+{
+    const uint32_t grid = (uint32_t)((int64_t)p.NC * p.tiles_y * p.tiles_x);
+    const size_t lds_bytes = (size_t)p.RH * p.pitch * sizeof(float);
+    switch (p.variant) {
+    case POOL_ROWS_K3S2P1:
+        return p.is_avg ? launch(merit_pool2d_rows<3, 3, 2, 2, 1, true>, p, x, y, s, lds_bytes, grid)
+                        : launch(merit_pool2d_rows<3, 3, 2, 2, 1, false>, p, x, y, s, lds_bytes, grid);
+    case POOL_ROWS_K2S2P0:
+        return p.is_avg ? launch(merit_pool2d_rows<2, 2, 2, 2, 0, true>, p, x, y, s, lds_bytes, grid)
+                        : launch(merit_pool2d_rows<2, 2, 2, 2, 0, false>, p, x, y, s, lds_bytes, grid);
+    case POOL_ROWS_K3S1P1:
+        return p.is_avg ? launch(merit_pool2d_rows<3, 3, 1, 1, 1, true>, p, x, y, s, lds_bytes, grid)
+                        : launch(merit_pool2d_rows<3, 3, 1, 1, 1, false>, p, x, y, s, lds_bytes, grid);
+    default:
+        return p.is_avg ? launch(merit_pool2d_tile<true>, p, x, y, s, lds_bytes, grid)
+                        : launch(merit_pool2d_tile<false>, p, x, y, s, lds_bytes, grid);
+    }
+}
+
+const char *pool_kernel_name(const PoolParams &p)
+{
+    switch (p.variant) {
+    case POOL_ROWS_K3S2P1: return p.is_avg ? "merit_pool2d_rows<3,3,2,2,1,avg>" : "merit_pool2d_rows<3,3,2,2,1,max>";
+    case POOL_ROWS_K2S2P0: return p.is_avg ? "merit_pool2d_rows<2,2,2,2,0,avg>" : "merit_pool2d_rows<2,2,2,2,0,max>";
+    case POOL_ROWS_K3S1P1: return p.is_avg ? "merit_pool2d_rows<3,3,1,1,1,avg>" : "merit_pool2d_rows<3,3,1,1,1,max>";
+    default: return p.is_avg ? "merit_pool2d_tile<avg>" : "merit_pool2d_tile<max>";
+    }
+}
+
+}  // namespace merit

@@ -1,0 +1,166 @@
+"""Host-only checks of the C ABI: the library loads, exports every declared symbol,
+and the plan logic (validation, output shapes, footprint rule) behaves.  No GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from oracle import merit_literal as lit
+from paper_1911_03458_amd import binding as mb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "merit.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b(merit_[a-z0-9_]+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_symbol():
+    L = mb.lib()
+    names = _declared_symbols()
+    assert {"merit_plan_create", "merit_plan_destroy", "merit_conv2d", "merit_pool2d",
+            "merit_sad_search", "merit_status_string"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_status_strings():
+    L = mb.lib()
+    seen = {L.merit_status_string(i).decode() for i in range(7)}
+    assert len(seen) == 7 and "ok" in seen
+
+
+def test_struct_layout_matches_header_sizes():
+    # int32 + 6*int64 + 12*int32 + 2*12*int64, natural alignment
+    assert ctypes.sizeof(mb.merit_operand) == 8 + 48 + 48 + 96 + 96
+    assert ctypes.sizeof(mb.merit_plan_desc) == 24 + 96 + 2 * ctypes.sizeof(mb.merit_operand)
+
+
+# ------------------------------------------------------------ descriptors
+def _triples(op, n):
+    return [(op.axis[j], op.stride[j], op.offset[j]) for j in range(n)]
+
+
+def test_conv_plan_descriptor_is_the_papers_transform():
+    plan = mb.merit_plan_conv2d(2, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3)
+    d = plan.desc()
+    ranges, n_par, tx, tw = lit.conv2d_desc(2, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3)
+    assert (d.n_par, d.n_acc) == (4, 3)
+    assert tuple(d.range[:7]) == ranges
+    for got, want in ((d.a, tx), (d.b, tw)):
+        for j in range(7):
+            assert got.axis[j] == want.axis[j]
+            if want.axis[j] != lit.UNUSED:
+                assert (got.stride[j], got.offset[j]) == (want.stride[j], want.offset[j])
+    assert plan.out_shape() == (2, 64, 112, 112)
+
+
+def test_pool_and_sad_plan_descriptors():
+    plan = mb.merit_plan_pool2d(16, 64, 112, 112, 3, 3, 2, 2, 1, 1, 0)
+    d = plan.desc()
+    ranges, n_par, tx = lit.pool2d_desc(16, 64, 112, 112, 3, 3, 2, 2, 1, 1)
+    assert tuple(d.range[:6]) == ranges and d.b.ndim == 0
+    assert _triples(d.a, 6) == list(zip(tx.axis, tx.stride, tx.offset))
+    assert plan.out_shape() == (16, 64, 56, 56)
+
+    plan = mb.merit_plan_sad(1088, 1920, 16, 32)
+    d = plan.desc()
+    ranges, n_par, tref, tcur = lit.sad_desc(1088, 1920, 16, 32)
+    assert tuple(d.range[:6]) == ranges == (68, 120, 65, 65, 16, 16)
+    assert _triples(d.a, 6) == list(zip(tref.axis, tref.stride, tref.offset))
+    for j in range(6):
+        assert d.b.axis[j] == tcur.axis[j]
+    assert plan.out_shape() == (68, 120)
+
+
+# -------------------------------------------------------------- footprint
+def test_footprint_worked_example_through_the_abi():
+    """16x8 outputs of a 5x5 window need a 20x12 input sub-tensor (Section IV-A)."""
+    plan = mb.merit_plan_conv2d(1, 1, 64, 64, 1, 5, 5, 1, 1, 2, 2)
+    assert plan.footprint(0, (1, 1, 16, 8, 1, 5, 5)) == (1, 1, 20, 12)
+    assert plan.footprint(1, (1, 1, 16, 8, 1, 5, 5)) == (1, 1, 5, 5)
+
+
+@pytest.mark.parametrize("tile", [(1, 8, 4, 8, 3, 7, 7), (2, 64, 1, 112, 3, 7, 7), (1, 1, 3, 5, 1, 2, 1)])
+def test_footprint_matches_literal_evaluator(tile):
+    plan = mb.merit_plan_conv2d(2, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3)
+    ranges, n_par, tx, tw = lit.conv2d_desc(2, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3)
+    assert plan.footprint(0, tile) == lit.footprint(tile, tx, 4)
+    assert plan.footprint(1, tile) == lit.footprint(tile, tw, 4)
+
+
+def test_sad_search_window_is_block_plus_twice_range():
+    plan = mb.merit_plan_sad(1088, 1920, 16, 32)
+    assert plan.footprint(0, (1, 1, 65, 65, 16, 16)) == (80, 80)
+    assert plan.footprint(1, (1, 1, 65, 65, 16, 16)) == (16, 16)
+    # four horizontally adjacent blocks share one 80 x 128 window
+    assert plan.footprint(0, (1, 4, 65, 65, 16, 16)) == (80, 128)
+
+
+def test_launch_info_tiles_cover_the_output():
+    plan = mb.merit_plan_pool2d(16, 64, 112, 112, 3, 3, 2, 2, 1, 1, 0)
+    li = plan.launch_info()
+    th = li["tile"][2]
+    assert li["kernel"].startswith("merit_pool2d_rows")
+    assert li["grid"][0] == 16 * 64 * -(-56 // th)
+    # staged rows of a strip = footprint rule on the row axis
+    assert plan.footprint(0, (1, 1, th, 56, 3, 3))[2] == (th - 1) * 2 + 3
+    assert li["lds_bytes"] == ((th - 1) * 2 + 3) * (112 + 8) * 4 <= 160 * 1024
+    plan.set_tile((0, 0, 7))
+    assert plan.launch_info()["tile"][2] == 7 and plan.launch_info()["grid"][0] == 1024 * 8
+
+
+# ------------------------------------------------------------- validation
+def test_invalid_arguments_are_rejected():
+    with pytest.raises(mb.MeritError) as e:
+        mb.merit_plan_sad(64, 60, 8, 4)             # W not divisible by the block
+    assert e.value.status == mb.MERIT_ERR_SHAPE
+    with pytest.raises(mb.MeritError) as e:
+        mb.merit_plan_pool2d(1, 1, 0, 8, 3, 3, 2, 2, 1, 1, 0)
+    assert e.value.status == mb.MERIT_ERR_INVALID_ARG
+    with pytest.raises(mb.MeritError) as e:
+        mb.merit_plan_conv2d(1, 3, 4, 4, 8, 7, 7, 1, 1, 0, 0)   # window larger than the image
+    assert e.value.status == mb.MERIT_ERR_SHAPE
+    with pytest.raises(mb.MeritError) as e:
+        mb.merit_plan_sad(60, 60, 6, 4)             # block not a multiple of 4
+    assert e.value.status == mb.MERIT_ERR_UNSUPPORTED
+
+
+def test_generic_descriptor_patterns():
+    d = mb.merit_plan_conv2d(1, 8, 16, 16, 8, 3, 3, 1, 1, 1, 1).desc()
+    assert mb.merit_plan_create(d).out_shape() == (1, 8, 16, 16)
+    d.a.stride[5] = 2                                # dilation on the window row index
+    with pytest.raises(mb.MeritError) as e:
+        mb.merit_plan_create(d)
+    assert e.value.status == mb.MERIT_ERR_UNSUPPORTED
+    d.a.stride[5] = 1
+    d.range[2] = 17                                  # output extent that the input cannot supply
+    with pytest.raises(mb.MeritError) as e:
+        mb.merit_plan_create(d)
+    assert e.value.status == mb.MERIT_ERR_SHAPE
+    d.range[2] = 16
+    d.pad = mb.MERIT_PAD_CLAMP                       # wrong padding rule for a dot product
+    with pytest.raises(mb.MeritError) as e:
+        mb.merit_plan_create(d)
+    assert e.value.status == mb.MERIT_ERR_UNSUPPORTED
+
+
+def test_null_and_misuse_without_gpu():
+    L = mb.lib()
+    assert L.merit_plan_destroy(None) == mb.MERIT_ERR_NULL
+    plan = mb.merit_plan_pool2d(1, 1, 8, 8, 2, 2, 2, 2, 0, 0, 0)
+    # wrong op for the entry point, NULL and misaligned pointers: all rejected before any launch
+    assert L.merit_conv2d(plan.handle, 16, 16, 16, None) == mb.MERIT_ERR_INVALID_ARG
+    assert L.merit_pool2d(plan.handle, None, 16, None) == mb.MERIT_ERR_NULL
+    assert L.merit_pool2d(plan.handle, 16, 20, None) == mb.MERIT_ERR_ALIGNMENT
+
+
+def test_conv_variant_selection():
+    assert mb.merit_plan_conv2d(32, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3).launch_info()["kernel"] == "merit_conv2d_planar"
+    assert mb.merit_plan_conv2d(8, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1).launch_info()["kernel"] == "merit_conv2d_chblock"
+    li = mb.merit_plan_conv2d(8, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1).launch_info()
+    assert li["lds_bytes"] <= 160 * 1024

@@ -1,0 +1,275 @@
+"""Parity of the HIP library against the CPU oracle, element by element, through
+the C ABI.  Needs a real MI355X.
+
+Bars: SAD values and vectors bit-exact; max-pool exact; avg-pool within
+1e-5*|r| + 1e-6 (fp32 sum of at most kh*kw terms against a double sum);
+conv within 2e-2*|r| + 1e-3 (fp16 products, fp32 accumulate, against double).
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1911_03458_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def mb():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1911_03458_amd import binding
+    binding.lib()
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def guarded_empty(shape, dtype, fill):
+    """Output tensor inside a larger buffer whose margins hold a canary."""
+    n = int(np.prod(shape))
+    pad = 64
+    buf = torch.full((n + 2 * pad,), fill, dtype=dtype, device="cuda:0")
+    return buf, buf[pad:pad + n].view(shape), pad
+
+
+def check_canary(buf, pad, fill):
+    host = buf.cpu()
+    assert bool((host[:pad] == fill).all()) and bool((host[-pad:] == fill).all()), "write outside the output"
+
+
+# ------------------------------------------------------------------ pooling
+POOL_CASES = [
+    # N  C  H    W    kh kw sh sw ph pw   (rows variants: W%4==0 and OW%4==0)
+    (2, 3, 32, 32, 3, 3, 2, 2, 1, 1),
+    (1, 2, 70, 40, 3, 3, 2, 2, 1, 1),      # several strips and a ragged last strip
+    (1, 5, 16, 24, 2, 2, 2, 2, 0, 0),
+    (1, 2, 20, 12, 3, 3, 1, 1, 1, 1),
+    (1, 3, 37, 29, 3, 3, 2, 2, 1, 1),      # generic kernel: odd sizes
+    (2, 2, 33, 50, 5, 4, 3, 2, 2, 1),      # generic kernel: asymmetric window
+    (1, 1, 130, 200, 3, 3, 2, 2, 1, 1),    # wide plane, several tiles
+    (1, 1, 9, 9, 9, 9, 1, 1, 4, 4),        # window as large as the image
+    (1, 2, 4, 4, 2, 2, 2, 2, 1, 1),        # corner windows hold a single element
+]
+
+
+@pytest.mark.parametrize("case", POOL_CASES)
+@pytest.mark.parametrize("mode", ["max", "avg"])
+def test_pool_small(mb, case, mode):
+    N, C, H, W, kh, kw, sh, sw, ph, pw = case
+    rng = np.random.default_rng(abs(hash(case)) % 2 ** 31)
+    x = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    plan = mb.merit_plan_pool2d(N, C, H, W, kh, kw, sh, sw, ph, pw, mode == "avg")
+    buf, y, pad = guarded_empty(plan.out_shape(), torch.float32, 1234.5)
+    print("pool", case, mode, plan.launch_info(), flush=True)
+    mb.merit_pool2d(plan, dev(x), y)
+    torch.cuda.synchronize()
+    check_canary(buf, pad, 1234.5)
+    got = y.cpu().numpy()
+    ref = oracle.pool2d(x, (kh, kw), (sh, sw), (ph, pw), mode)
+    assert got.shape == ref.shape
+    if mode == "max":
+        assert np.array_equal(got, ref)
+    else:
+        assert np.all(np.abs(got - ref) <= 1e-5 * np.abs(ref) + 1e-6)
+
+
+@pytest.mark.parametrize("th", [1, 3, 8, 28])
+def test_pool_tile_override(mb, th):
+    rng = np.random.default_rng(th)
+    x = rng.standard_normal((1, 3, 112, 112)).astype(np.float32)
+    plan = mb.merit_plan_pool2d(1, 3, 112, 112, 3, 3, 2, 2, 1, 1, 0).set_tile((0, 0, th))
+    print("pool tile", th, plan.launch_info(), flush=True)
+    got = mb.merit_pool2d(plan, dev(x)).cpu().numpy()
+    assert np.array_equal(got, oracle.pool2d(x, (3, 3), (2, 2), (1, 1), "max"))
+
+
+@pytest.mark.parametrize("mode", ["max", "avg"])
+def test_pool_full_workload(mb, mode):
+    c = wl.CFG1_POOL
+    x = wl.make_pool_input(c)
+    plan = mb.merit_plan_pool2d(c.N, c.C, c.H, c.W, c.kh, c.kw, c.sh, c.sw, c.ph, c.pw, mode == "avg")
+    print("pool full", mode, plan.launch_info(), flush=True)
+    got = mb.merit_pool2d(plan, dev(x)).cpu().numpy()
+    ref = oracle.pool2d(x, (c.kh, c.kw), (c.sh, c.sw), (c.ph, c.pw), mode)
+    assert got.shape == (16, 64, 56, 56)
+    if mode == "max":
+        assert np.array_equal(got, ref)
+    else:
+        assert np.all(np.abs(got - ref) <= 1e-5 * np.abs(ref) + 1e-6)
+
+
+def test_pool_constant_and_negative_planes(mb):
+    x = np.full((1, 2, 16, 16), -3.0, np.float32)
+    for mode, is_avg in (("max", 0), ("avg", 1)):
+        plan = mb.merit_plan_pool2d(1, 2, 16, 16, 3, 3, 2, 2, 1, 1, is_avg)
+        assert np.all(mb.merit_pool2d(plan, dev(x)).cpu().numpy() == -3.0), mode
+
+
+def test_pool_empty_batch(mb):
+    plan = mb.merit_plan_pool2d(0, 4, 16, 16, 3, 3, 2, 2, 1, 1, 0)
+    y = mb.merit_pool2d(plan, torch.empty((0, 4, 16, 16), device="cuda:0"))
+    torch.cuda.synchronize()
+    assert tuple(y.shape) == (0, 4, 8, 8)
+
+
+# ----------------------------------------------------------- block matching
+def _sad_check(mb, cur, ref, B, R):
+    H, W = cur.shape
+    plan = mb.merit_plan_sad(H, W, B, R)
+    nby, nbx = plan.out_shape()
+    bs, sad, p1 = guarded_empty((nby, nbx), torch.int32, -77)
+    bm, mv, p2 = guarded_empty((nby, nbx, 2), torch.int32, -77)
+    mb.merit_sad_search(plan, dev(cur), dev(ref), sad, mv)
+    torch.cuda.synchronize()
+    check_canary(bs, p1, -77)
+    check_canary(bm, p2, -77)
+    osad, omv = oracle.sad_search(cur, ref, B, R)
+    assert np.array_equal(sad.cpu().numpy(), osad)
+    assert np.array_equal(mv.cpu().numpy(), omv)
+
+
+SAD_CASES = [(16, 16, 4, 2), (32, 48, 8, 4), (24, 40, 8, 3), (64, 96, 16, 8), (32, 32, 16, 5),
+             (48, 64, 16, 32), (8, 8, 8, 1), (40, 24, 4, 0), (64, 64, 32, 3)]
+
+
+@pytest.mark.parametrize("H,W,B,R", SAD_CASES)
+def test_sad_small_random(mb, H, W, B, R):
+    rng = np.random.default_rng(H * 1000 + W * 10 + R)
+    cur = rng.integers(0, 256, size=(H, W), dtype=np.uint8)
+    ref = rng.integers(0, 256, size=(H, W), dtype=np.uint8)
+    print("sad", (H, W, B, R), flush=True)
+    _sad_check(mb, cur, ref, B, R)
+    # few distinct values (including 0x00 bytes): many exact ties, exercises the tie-break
+    _sad_check(mb, cur & 0x3, ref & 0x3, B, R)
+
+
+def test_sad_degenerate_frames(mb):
+    const = np.full((32, 32), 77, np.uint8)
+    _sad_check(mb, const, const, 8, 4)                      # every candidate ties: (-R,-R)
+    rng = np.random.default_rng(9)
+    f = rng.integers(0, 256, size=(32, 32), dtype=np.uint8)
+    _sad_check(mb, f, f, 8, 4)                              # zero motion
+    _sad_check(mb, np.zeros((32, 32), np.uint8), np.full((32, 32), 255, np.uint8), 16, 4)   # max SAD
+    rows = np.tile(rng.permutation(256)[:32].astype(np.uint8), (32, 1))
+    _sad_check(mb, rows, rows, 8, 4)                        # all dy tie
+    _sad_check(mb, np.ascontiguousarray(rows.T), np.ascontiguousarray(rows.T), 8, 4)
+
+
+def test_sad_cfg0(mb):
+    cur, ref, planted = wl.make_sad_frames(wl.CFG0_ME_SMALL)
+    _sad_check(mb, cur, ref, 8, 4)
+
+
+def test_sad_full_hd_workload(mb):
+    c = wl.CFG3_ME_FHD
+    cur, ref, planted = wl.make_sad_frames(c)
+    plan = mb.merit_plan_sad(c.H, c.W, c.block, c.search)
+    print("sad full", plan.launch_info(), flush=True)
+    sad, mv = mb.merit_sad_search(plan, dev(cur), dev(ref))
+    torch.cuda.synchronize()
+    sad, mv = sad.cpu().numpy(), mv.cpu().numpy()
+    # properties that hold at any size: planted copies are exact, so the minimum is 0
+    assert sad.shape == (68, 120) and np.all(sad == 0)
+    osad, omv = oracle.sad_search(cur, ref, c.block, c.search)
+    assert np.array_equal(sad, osad)
+    assert np.array_equal(mv, omv)
+
+
+# ------------------------------------------------------------- convolution
+def _conv_check(mb, x, w, stride, pad, tile=None):
+    N, Cin, H, W = x.shape
+    Cout, _, kh, kw = w.shape
+    plan = mb.merit_plan_conv2d(N, Cin, H, W, Cout, kh, kw, *stride, *pad)
+    if tile is not None:
+        plan.set_tile(tile)
+    print("conv", x.shape, w.shape, stride, pad, plan.launch_info(), flush=True)
+    buf, y, p = guarded_empty(plan.out_shape(), torch.float16, 777.0)
+    mb.merit_conv2d(plan, dev(x), dev(w), y)
+    torch.cuda.synchronize()
+    check_canary(buf, p, 777.0)
+    got = y.cpu().numpy().astype(np.float64)
+    ref = oracle.conv2d(x, w, stride, pad).astype(np.float64)
+    assert got.shape == ref.shape
+    err = np.abs(got - ref)
+    tol = 2e-2 * np.abs(ref) + 1e-3
+    assert np.all(err <= tol), f"max excess {np.max(err - tol)} at {np.unravel_index(np.argmax(err - tol), err.shape)}"
+    return got, ref
+
+
+CONV_CASES = [
+    # N Cin H   W  Cout kh kw sh sw ph pw
+    (1, 3, 20, 24, 64, 7, 7, 2, 2, 3, 3),      # planar, stride 2
+    (2, 3, 17, 19, 40, 7, 7, 2, 2, 3, 3),      # planar, odd sizes, ragged channels
+    (1, 1, 12, 16, 8, 3, 3, 1, 1, 1, 1),       # planar, odd stride alignment
+    (1, 4, 9, 40, 33, 5, 5, 1, 2, 2, 2),       # planar, even group count, mixed strides
+    (1, 3, 30, 30, 16, 1, 8, 1, 1, 0, 4),      # planar, 8-wide window
+    (1, 16, 12, 16, 32, 3, 3, 1, 1, 1, 1),     # channel-block, vector staging
+    (2, 64, 14, 16, 64, 3, 3, 1, 1, 1, 1),     # channel-block, the 3x3 workload's shape class
+    (1, 24, 10, 12, 48, 3, 3, 2, 2, 1, 1),     # channel-block, padded channel group, stride 2
+    (1, 20, 9, 11, 10, 2, 3, 1, 1, 0, 1),      # channel-block, scalar staging everywhere
+    (1, 32, 8, 8, 96, 1, 1, 1, 1, 0, 0),       # channel-block, 1x1, three channel blocks
+    (1, 8, 40, 40, 16, 5, 5, 1, 1, 2, 2),      # channel-block, many tiles per image
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_small(mb, case):
+    N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw = case
+    rng = np.random.default_rng(abs(hash(case)) % 2 ** 31)
+    x = rng.standard_normal((N, Cin, H, W)).astype(np.float16)
+    w = (rng.standard_normal((Cout, Cin, kh, kw)) / np.sqrt(Cin * kh * kw)).astype(np.float16)
+    _conv_check(mb, x, w, (sh, sw), (ph, pw))
+
+
+@pytest.mark.parametrize("tile", [(0, 0, 4, 32), (0, 0, 8, 32)])
+def test_conv_tile_override(mb, tile):
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((1, 16, 24, 24)).astype(np.float16)
+    w = (rng.standard_normal((32, 16, 3, 3)) / 12).astype(np.float16)
+    _conv_check(mb, x, w, (1, 1), (1, 1), tile)
+
+
+def test_conv_identity_kernel_is_exact(mb):
+    rng = np.random.default_rng(4)
+    C = 16
+    x = rng.standard_normal((1, C, 12, 16)).astype(np.float16)
+    w = np.zeros((C, C, 3, 3), np.float16)
+    for c in range(C):
+        w[c, c, 1, 1] = 1.0
+    got, ref = _conv_check(mb, x, w, (1, 1), (1, 1))
+    assert np.array_equal(got, x.astype(np.float64))
+
+
+def test_conv_3x3_workload(mb):
+    c = wl.CFG2_CONV3
+    x, w = wl.make_conv_inputs(c)
+    _conv_check(mb, x, w, (c.sh, c.sw), (c.ph, c.pw))
+
+
+def test_conv_7x7_workload_sampled(mb):
+    """Full-size launch; the oracle checks three whole images of the batch."""
+    c = wl.CFG4_CONV7
+    x, w = wl.make_conv_inputs(c)
+    plan = mb.merit_plan_conv2d(c.N, c.Cin, c.H, c.W, c.Cout, c.kh, c.kw, c.sh, c.sw, c.ph, c.pw)
+    print("conv7 full", plan.launch_info(), flush=True)
+    y = mb.merit_conv2d(plan, dev(x), dev(w))
+    torch.cuda.synchronize()
+    got = y.cpu().numpy().astype(np.float64)
+    assert got.shape == (32, 64, 112, 112) and np.all(np.isfinite(got))
+    for n in (0, 17, 31):
+        ref = oracle.conv2d(x[n:n + 1], w, (c.sh, c.sw), (c.ph, c.pw)).astype(np.float64)[0]
+        err = np.abs(got[n] - ref)
+        assert np.all(err <= 2e-2 * np.abs(ref) + 1e-3), n
+
+
+def test_misaligned_pointer_is_rejected(mb):
+    plan = mb.merit_plan_pool2d(1, 1, 8, 8, 2, 2, 2, 2, 0, 0, 0)
+    x = torch.zeros(8 * 8 + 4, device="cuda:0")[1:65].view(1, 1, 8, 8)
+    with pytest.raises(mb.MeritError) as e:
+        mb.merit_pool2d(plan, x)
+    assert e.value.status == mb.MERIT_ERR_ALIGNMENT
