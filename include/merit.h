@@ -20,6 +20,8 @@
  *   - A plan is immutable host memory; it may be shared between threads and
  *     streams.  Plans are created and destroyed without touching the GPU.
  *   - Every function returns a merit_status; on any error nothing was launched.
+ *   - A plan whose output is empty (batch size 0) makes the operation a no-op
+ *     that returns MERIT_OK without looking at the tensor pointers.
  */
 #ifndef MERIT_H
 #define MERIT_H

@@ -26,11 +26,6 @@ namespace merit {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-__device__ __forceinline__ uint32_t fdiv(uint32_t n, FastDiv f)
-{
-    return __umulhi(n, f.magic);
-}
-
 union Frag {
     uint4 u;
     half8 h;

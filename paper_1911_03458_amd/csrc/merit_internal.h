@@ -21,9 +21,15 @@ inline FastDiv make_fastdiv(uint32_t d)
 {
     FastDiv f;
     f.d = d;
-    f.magic = (uint32_t)((0x100000000ull / d) + 1ull);
+    f.magic = (uint32_t)((0x100000000ull / d) + 1ull);   // d == 1 does not fit: handled in fdiv
     return f;
 }
+#ifdef __HIPCC__
+__device__ __forceinline__ uint32_t fdiv(uint32_t n, FastDiv f)
+{
+    return f.d == 1u ? n : __umulhi(n, f.magic);
+}
+#endif
 
 // ---- pooling ---------------------------------------------------------------
 enum PoolVariant { POOL_TILE_GENERIC = 0, POOL_ROWS_K3S2P1 = 1, POOL_ROWS_K2S2P0 = 2, POOL_ROWS_K3S1P1 = 3 };

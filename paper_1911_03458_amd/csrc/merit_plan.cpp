@@ -516,8 +516,10 @@ merit_status merit_plan_launch_info(const merit_plan *plan, merit_launch_info *o
 
 merit_status merit_conv2d(const merit_plan *plan, const void *x, const void *w, void *y, void *stream)
 {
-    if (!plan || !x || !w || !y) return MERIT_ERR_NULL;
+    if (!plan) return MERIT_ERR_NULL;
     if (plan->desc.op != MERIT_OP_CONV_DOT) return MERIT_ERR_INVALID_ARG;
+    if (plan->conv.N == 0) return MERIT_OK;               // empty batch: nothing to read or write
+    if (!x || !w || !y) return MERIT_ERR_NULL;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return MERIT_ERR_ALIGNMENT;
     return launch_conv2d(plan->conv, x, w, y, static_cast<hipStream_t>(stream)) == hipSuccess ? MERIT_OK
                                                                                               : MERIT_ERR_HIP;
@@ -525,8 +527,10 @@ merit_status merit_conv2d(const merit_plan *plan, const void *x, const void *w, 
 
 merit_status merit_pool2d(const merit_plan *plan, const void *x, void *y, void *stream)
 {
-    if (!plan || !x || !y) return MERIT_ERR_NULL;
+    if (!plan) return MERIT_ERR_NULL;
     if (plan->desc.op != MERIT_OP_POOL_MAX && plan->desc.op != MERIT_OP_POOL_AVG) return MERIT_ERR_INVALID_ARG;
+    if (plan->pool.NC == 0) return MERIT_OK;              // empty batch: nothing to read or write
+    if (!x || !y) return MERIT_ERR_NULL;
     if (!aligned16(x) || !aligned16(y)) return MERIT_ERR_ALIGNMENT;
     return launch_pool2d(plan->pool, static_cast<const float *>(x), static_cast<float *>(y),
                          static_cast<hipStream_t>(stream)) == hipSuccess

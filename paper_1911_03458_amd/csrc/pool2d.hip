@@ -12,11 +12,6 @@
 
 namespace merit {
 
-__device__ __forceinline__ uint32_t fdiv(uint32_t n, FastDiv f)
-{
-    return __umulhi(n, f.magic);
-}
-
 // ---------------------------------------------------------------------------
 // Generic tile kernel: any window / stride / padding, scalar accesses.
 // ---------------------------------------------------------------------------

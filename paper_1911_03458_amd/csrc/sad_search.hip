@@ -16,11 +16,6 @@
 
 namespace merit {
 
-__device__ __forceinline__ uint32_t fdiv(uint32_t n, FastDiv f)
-{
-    return __umulhi(n, f.magic);
-}
-
 constexpr int KEY_SHIFT = 14;                 // raster index < 2^14 (R <= 63)
 constexpr uint32_t KEY_MASK = (1u << KEY_SHIFT) - 1u;
 

@@ -197,7 +197,8 @@ def _conv_check(mb, x, w, stride, pad, tile=None):
     assert got.shape == ref.shape
     err = np.abs(got - ref)
     tol = 2e-2 * np.abs(ref) + 1e-3
-    assert np.all(err <= tol), f"max excess {np.max(err - tol)} at {np.unravel_index(np.argmax(err - tol), err.shape)}"
+    ok = bool(np.all(err <= tol))
+    assert ok, f"max excess {np.max(err - tol)} at {np.unravel_index(np.argmax(err - tol), err.shape)}"
     return got, ref
 
 
