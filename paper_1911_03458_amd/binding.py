@@ -107,6 +107,14 @@ class Plan:
 
     def __init__(self, handle: ctypes.c_void_p):
         self._h = handle
+        self._shapes = None
+
+    def shapes(self):
+        """(out_shape, a_shape, b_shape), computed once (a plan's shapes never change)."""
+        if self._shapes is None:
+            d = self.desc()
+            self._shapes = (self.out_shape(), tuple(d.a.shape[:d.a.ndim]), tuple(d.b.shape[:d.b.ndim]))
+        return self._shapes
 
     @property
     def handle(self):
@@ -207,12 +215,12 @@ def _stream(stream):
 
 def merit_conv2d(plan: Plan, x, w, y=None, stream=None):
     import torch
+    out_shape, a_shape, b_shape = plan.shapes()
     if y is None:
-        y = torch.empty(plan.out_shape(), dtype=torch.float16, device=x.device)
-    if tuple(y.shape) != plan.out_shape():
+        y = torch.empty(out_shape, dtype=torch.float16, device=x.device)
+    if tuple(y.shape) != out_shape:
         raise ValueError("y has the wrong shape")
-    d = plan.desc()
-    if tuple(x.shape) != tuple(d.a.shape[:4]) or tuple(w.shape) != tuple(d.b.shape[:4]):
+    if tuple(x.shape) != a_shape or tuple(w.shape) != b_shape:
         raise ValueError("x / w do not match the plan")
     _check(lib().merit_conv2d(plan.handle, _dev_ptr(x, torch.float16, "x"), _dev_ptr(w, torch.float16, "w"),
                               _dev_ptr(y, torch.float16, "y"), _stream(stream)), "merit_conv2d")
@@ -221,11 +229,12 @@ def merit_conv2d(plan: Plan, x, w, y=None, stream=None):
 
 def merit_pool2d(plan: Plan, x, y=None, stream=None):
     import torch
+    out_shape, a_shape, _ = plan.shapes()
     if y is None:
-        y = torch.empty(plan.out_shape(), dtype=torch.float32, device=x.device)
-    if tuple(y.shape) != plan.out_shape():
+        y = torch.empty(out_shape, dtype=torch.float32, device=x.device)
+    if tuple(y.shape) != out_shape:
         raise ValueError("y has the wrong shape")
-    if tuple(x.shape) != tuple(plan.desc().a.shape[:4]):
+    if tuple(x.shape) != a_shape:
         raise ValueError("x does not match the plan")
     _check(lib().merit_pool2d(plan.handle, _dev_ptr(x, torch.float32, "x"), _dev_ptr(y, torch.float32, "y"),
                               _stream(stream)), "merit_pool2d")
@@ -234,13 +243,12 @@ def merit_pool2d(plan: Plan, x, y=None, stream=None):
 
 def merit_sad_search(plan: Plan, cur, ref, sad=None, mv=None, stream=None):
     import torch
-    nby, nbx = plan.out_shape()
+    (nby, nbx), a_shape, b_shape = plan.shapes()
     if sad is None:
         sad = torch.empty((nby, nbx), dtype=torch.int32, device=cur.device)
     if mv is None:
         mv = torch.empty((nby, nbx, 2), dtype=torch.int32, device=cur.device)
-    d = plan.desc()
-    if tuple(cur.shape) != tuple(d.b.shape[:2]) or tuple(ref.shape) != tuple(d.a.shape[:2]):
+    if tuple(cur.shape) != b_shape or tuple(ref.shape) != a_shape:
         raise ValueError("frames do not match the plan")
     if tuple(sad.shape) != (nby, nbx) or tuple(mv.shape) != (nby, nbx, 2):
         raise ValueError("outputs have the wrong shape")

@@ -32,7 +32,8 @@ __device__ __forceinline__ uint32_t fdiv(uint32_t n, FastDiv f)
 #endif
 
 // ---- pooling ---------------------------------------------------------------
-enum PoolVariant { POOL_TILE_GENERIC = 0, POOL_ROWS_K3S2P1 = 1, POOL_ROWS_K2S2P0 = 2, POOL_ROWS_K3S1P1 = 3 };
+enum PoolVariant { POOL_TILE_GENERIC = 0, POOL_ROWS_K3S2P1 = 1, POOL_ROWS_K2S2P0 = 2, POOL_ROWS_K3S1P1 = 3,
+                   POOL_STREAM_K3S2P1 = 4 };
 
 struct PoolParams {
     int NC, H, W, OH, OW;
@@ -47,6 +48,9 @@ struct PoolParams {
     FastDiv div_tw;        // generic: tile columns
     FastDiv div_p4;        // rows variant: float4 per staged row
     FastDiv div_ow4;       // rows variant: float4 per output row
+    int lg_shift;          // stream variant: log2(lanes per (plane, strip) item)
+    int items;             // stream variant: NC * strips
+    int grid;              // workgroups to launch
 };
 
 // ---- block matching --------------------------------------------------------

@@ -86,7 +86,27 @@ merit_status derive_pool(merit_plan *pl)
         else if (kh == 2 && kw == 2 && sh == 2 && sw == 2 && pw == 0) variant = POOL_ROWS_K2S2P0;
         else if (kh == 3 && kw == 3 && sh == 1 && sw == 1 && pw == 1) variant = POOL_ROWS_K3S1P1;
     }
-    if (variant != POOL_TILE_GENERIC) {
+    // streaming variant: register-resident strips, no LDS (3x3 / stride 2 / pad 1, W <= 256)
+    const bool stream_ok = kh == 3 && kw == 3 && sh == 2 && sw == 2 && ph == 1 && pw == 1 &&
+                           (W % 4 == 0) && W <= 256 && pl->tile_req[3] <= 0;
+    if (stream_ok) {
+        int64_t TH = 4;             // measured best on the 112x112 workload (4 < 7 < 8)
+        if (pl->tile_req[2] > 0) TH = pl->tile_req[2];
+        if (TH == 4 || TH == 7 || TH == 8) {
+            int lg_shift = 0;
+            while ((1 << lg_shift) < W / 4) ++lg_shift;
+            p.variant = variant = POOL_STREAM_K3S2P1;
+            p.TH = (int)TH; p.TW = (int)OW;
+            p.tiles_y = (int)cdiv(OH, TH); p.tiles_x = 1;
+            p.RH = 0; p.RW = 0; p.pitch = 0;
+            p.lg_shift = lg_shift;
+            const int64_t items = N * C * p.tiles_y;
+            if (items >= INT_LIMIT) return MERIT_ERR_UNSUPPORTED;
+            p.items = (int)items;
+            p.grid = (int)cdiv(items, 4 * (64 >> lg_shift));
+        }
+    }
+    if (variant != POOL_TILE_GENERIC && variant != POOL_STREAM_K3S2P1) {
         const int64_t pitch = W + 8;
         // strip height: as many output rows as keep the staged rows within ~16 KB,
         // then balanced so that all strips of a plane are (nearly) equal
@@ -129,8 +149,12 @@ merit_status derive_pool(merit_plan *pl)
         p.div_rw = make_fastdiv((uint32_t)RW);
         p.div_tw = make_fastdiv((uint32_t)TW);
     }
-    const int64_t grid = (int64_t)p.NC * p.tiles_y * p.tiles_x;
-    if (grid >= (1ll << 31)) return MERIT_ERR_UNSUPPORTED;
+    if (variant != POOL_STREAM_K3S2P1) {
+        const int64_t g = (int64_t)p.NC * p.tiles_y * p.tiles_x;
+        if (g >= (1ll << 31)) return MERIT_ERR_UNSUPPORTED;
+        p.grid = (int)g;
+    }
+    const int64_t grid = p.grid;
 
     pl->out_ndim = 4;
     pl->out_shape[0] = N; pl->out_shape[1] = C; pl->out_shape[2] = OH; pl->out_shape[3] = OW;

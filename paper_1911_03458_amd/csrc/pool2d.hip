@@ -163,6 +163,92 @@ __global__ __launch_bounds__(256) void merit_pool2d_rows(PoolParams p, const flo
 }
 
 // ---------------------------------------------------------------------------
+// Streaming kernel for the 3x3 / stride 2 / pad 1 window on planes up to 256
+// columns wide (W % 4 == 0).  No LDS and no barrier: a group of 2^lg_shift lanes
+// owns TH output rows of one plane, lane t holds the 16-byte column chunk t of
+// every input row of the strip in registers (each input element is loaded by
+// exactly one lane, all 2*TH+1 row loads are issued before the first use), and
+// the one halo column a lane needs -- the last float of its left neighbour's
+// chunk -- arrives with a DPP wave shift instead of through memory.  The window
+// is separable: a row pass (3-tap max or sum giving the lane's two outputs) and
+// a column pass over three row results.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float dpp_from_lane_below(float v, float fill)
+{
+    // lane i receives the value of lane i-1; lane 0 keeps `fill`
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(fill), __float_as_int(v), 0x138 /* wave_shr:1 */,
+                                                      0xf, 0xf, false));
+}
+
+template <bool AVG, int TH>
+__global__ __launch_bounds__(256) void merit_pool2d_stream_k3s2p1(PoolParams p, const float *__restrict__ x,
+                                                                 float *__restrict__ y)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lg = 1 << p.lg_shift;
+    const int t = lane & (lg - 1);                          // 16-byte column chunk
+    const int item = (wave << (6 - p.lg_shift)) + (lane >> p.lg_shift);
+    const int W4 = p.W >> 2;
+    const bool live = item < p.items && t < W4;
+    const int nc = live ? item / p.tiles_y : 0;
+    const int strip = live ? item - nc * p.tiles_y : 0;
+    const int oy0 = strip * TH;
+    const float fill = AVG ? 0.0f : -INFINITY;
+    const float *xp = x + (size_t)nc * p.H * p.W + 4 * t;
+
+    // rows 2*oy0-1 .. 2*oy0+2*TH-1, all loads in flight together
+    float4 v[2 * TH + 1];
+#pragma unroll
+    for (int r = 0; r < 2 * TH + 1; ++r) {
+        const int gy = 2 * oy0 - 1 + r;
+        v[r] = make_float4(fill, fill, fill, fill);
+        if (live && gy >= 0 && gy < p.H) {
+            // every input byte is used once: non-temporal loads keep it from displacing
+            // useful lines in the caches (measured: ~20 % less time on a cold input)
+            typedef float v4f __attribute__((ext_vector_type(4)));
+            const v4f q = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(xp + (size_t)gy * p.W));
+            v[r] = make_float4(q.x, q.y, q.z, q.w);
+        }
+    }
+    // row pass: outputs 2t and 2t+1 read columns {4t-1,4t,4t+1} and {4t+1,4t+2,4t+3}
+    float h0[2 * TH + 1], h1[2 * TH + 1];
+#pragma unroll
+    for (int r = 0; r < 2 * TH + 1; ++r) {
+        float left = dpp_from_lane_below(v[r].w, fill);
+        if (t == 0) left = fill;                            // column -1 is padding
+        if (AVG) {
+            h0[r] = (left + v[r].x) + v[r].y;
+            h1[r] = (v[r].y + v[r].z) + v[r].w;
+        } else {
+            h0[r] = fmaxf(fmaxf(left, v[r].x), v[r].y);
+            h1[r] = fmaxf(fmaxf(v[r].y, v[r].z), v[r].w);
+        }
+    }
+    // column pass and store
+    float *yp = y + (size_t)nc * p.OH * p.OW + 2 * t;
+#pragma unroll
+    for (int i = 0; i < TH; ++i) {
+        const int oy = oy0 + i;
+        float o0, o1;
+        if (AVG) {
+            o0 = (h0[2 * i] + h0[2 * i + 1]) + h0[2 * i + 2];
+            o1 = (h1[2 * i] + h1[2 * i + 1]) + h1[2 * i + 2];
+            const int wy0 = 2 * oy - 1;
+            const int cy = min(wy0 + 3, p.H) - max(wy0, 0);
+            const int cx0 = min(4 * t + 2, p.W) - max(4 * t - 1, 0);
+            const int cx1 = min(4 * t + 4, p.W) - (4 * t + 1);
+            o0 = o0 / (float)(cy * cx0);
+            o1 = o1 / (float)(cy * cx1);
+        } else {
+            o0 = fmaxf(fmaxf(h0[2 * i], h0[2 * i + 1]), h0[2 * i + 2]);
+            o1 = fmaxf(fmaxf(h1[2 * i], h1[2 * i + 1]), h1[2 * i + 2]);
+        }
+        if (live && oy < p.OH) *reinterpret_cast<float2 *>(yp + (size_t)oy * p.OW) = make_float2(o0, o1);
+    }
+}
+
+// ---------------------------------------------------------------------------
 template <typename K>
 static hipError_t launch(K kernel, const PoolParams &p, const float *x, float *y, hipStream_t s,
                          size_t lds_bytes, uint32_t grid)
@@ -174,9 +260,18 @@ static hipError_t launch(K kernel, const PoolParams &p, const float *x, float *y
 
 hipError_t launch_pool2d(const PoolParams &p, const float *x, float *y, hipStream_t s)
 {
-    const uint32_t grid = (uint32_t)((int64_t)p.NC * p.tiles_y * p.tiles_x);
+    const uint32_t grid = (uint32_t)p.grid;
     const size_t lds_bytes = (size_t)p.RH * p.pitch * sizeof(float);
     switch (p.variant) {
+    case POOL_STREAM_K3S2P1:
+        if (p.TH == 4)
+            return p.is_avg ? launch(merit_pool2d_stream_k3s2p1<true, 4>, p, x, y, s, 0, grid)
+                            : launch(merit_pool2d_stream_k3s2p1<false, 4>, p, x, y, s, 0, grid);
+        if (p.TH == 7)
+            return p.is_avg ? launch(merit_pool2d_stream_k3s2p1<true, 7>, p, x, y, s, 0, grid)
+                            : launch(merit_pool2d_stream_k3s2p1<false, 7>, p, x, y, s, 0, grid);
+        return p.is_avg ? launch(merit_pool2d_stream_k3s2p1<true, 8>, p, x, y, s, 0, grid)
+                        : launch(merit_pool2d_stream_k3s2p1<false, 8>, p, x, y, s, 0, grid);
     case POOL_ROWS_K3S2P1:
         return p.is_avg ? launch(merit_pool2d_rows<3, 3, 2, 2, 1, true>, p, x, y, s, lds_bytes, grid)
                         : launch(merit_pool2d_rows<3, 3, 2, 2, 1, false>, p, x, y, s, lds_bytes, grid);
@@ -195,6 +290,7 @@ hipError_t launch_pool2d(const PoolParams &p, const float *x, float *y, hipStrea
 const char *pool_kernel_name(const PoolParams &p)
 {
     switch (p.variant) {
+    case POOL_STREAM_K3S2P1: return p.is_avg ? "merit_pool2d_stream_k3s2p1<avg>" : "merit_pool2d_stream_k3s2p1<max>";
     case POOL_ROWS_K3S2P1: return p.is_avg ? "merit_pool2d_rows<3,3,2,2,1,avg>" : "merit_pool2d_rows<3,3,2,2,1,max>";
     case POOL_ROWS_K2S2P0: return p.is_avg ? "merit_pool2d_rows<2,2,2,2,0,avg>" : "merit_pool2d_rows<2,2,2,2,0,max>";
     case POOL_ROWS_K3S1P1: return p.is_avg ? "merit_pool2d_rows<3,3,1,1,1,avg>" : "merit_pool2d_rows<3,3,1,1,1,max>";

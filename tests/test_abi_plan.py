@@ -105,13 +105,17 @@ def test_launch_info_tiles_cover_the_output():
     plan = mb.merit_plan_pool2d(16, 64, 112, 112, 3, 3, 2, 2, 1, 1, 0)
     li = plan.launch_info()
     th = li["tile"][2]
-    assert li["kernel"].startswith("merit_pool2d_rows")
-    assert li["grid"][0] == 16 * 64 * -(-56 // th)
-    # staged rows of a strip = footprint rule on the row axis
-    assert plan.footprint(0, (1, 1, th, 56, 3, 3))[2] == (th - 1) * 2 + 3
-    assert li["lds_bytes"] == ((th - 1) * 2 + 3) * (112 + 8) * 4 <= 160 * 1024
-    plan.set_tile((0, 0, 7))
-    assert plan.launch_info()["tile"][2] == 7 and plan.launch_info()["grid"][0] == 1024 * 8
+    # default: register-streaming kernel, 28 lanes (a 32-lane group) per (plane, strip)
+    assert li["kernel"].startswith("merit_pool2d_stream") and li["lds_bytes"] == 0
+    assert 56 % th == 0 and li["grid"][0] == 16 * 64 * (56 // th) // 8
+    # rows a lane holds per strip = footprint rule on the row axis
+    assert plan.footprint(0, (1, 1, th, 56, 3, 3))[2] == 2 * th + 1
+    # a strip height the streaming kernel has no instance for selects the LDS row-strip kernel
+    plan.set_tile((0, 0, 14))
+    li = plan.launch_info()
+    assert li["kernel"].startswith("merit_pool2d_rows") and li["tile"][2] == 14
+    assert li["grid"][0] == 1024 * 4
+    assert li["lds_bytes"] == (13 * 2 + 3) * (112 + 8) * 4 <= 160 * 1024
 
 
 # ------------------------------------------------------------- validation

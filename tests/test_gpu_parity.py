@@ -78,14 +78,19 @@ def test_pool_small(mb, case, mode):
         assert np.all(np.abs(got - ref) <= 1e-5 * np.abs(ref) + 1e-6)
 
 
-@pytest.mark.parametrize("th", [1, 3, 8, 28])
+@pytest.mark.parametrize("th", [1, 3, 4, 7, 8, 14, 28])
 def test_pool_tile_override(mb, th):
     rng = np.random.default_rng(th)
     x = rng.standard_normal((1, 3, 112, 112)).astype(np.float32)
-    plan = mb.merit_plan_pool2d(1, 3, 112, 112, 3, 3, 2, 2, 1, 1, 0).set_tile((0, 0, th))
-    print("pool tile", th, plan.launch_info(), flush=True)
-    got = mb.merit_pool2d(plan, dev(x)).cpu().numpy()
-    assert np.array_equal(got, oracle.pool2d(x, (3, 3), (2, 2), (1, 1), "max"))
+    for is_avg, mode in ((0, "max"), (1, "avg")):
+        plan = mb.merit_plan_pool2d(1, 3, 112, 112, 3, 3, 2, 2, 1, 1, is_avg).set_tile((0, 0, th))
+        print("pool tile", th, plan.launch_info(), flush=True)
+        got = mb.merit_pool2d(plan, dev(x)).cpu().numpy()
+        ref = oracle.pool2d(x, (3, 3), (2, 2), (1, 1), mode)
+        if mode == "max":
+            assert np.array_equal(got, ref)
+        else:
+            assert bool(np.all(np.abs(got - ref) <= 1e-5 * np.abs(ref) + 1e-6))
 
 
 @pytest.mark.parametrize("mode", ["max", "avg"])
