@@ -207,14 +207,33 @@ merit_status derive_sad(merit_plan *pl)
     p.div_win4 = make_fastdiv((uint32_t)cols4);
     p.div_nbx = make_fastdiv((uint32_t)p.nbx);
 
+    // row-scan kernel: 16x16 blocks, four blocks per workgroup, instances for R = 16 and 32;
+    // a tile request of one block per workgroup keeps the generic kernel
+    int64_t grid = (int64_t)p.nby * p.nbx;
+    int64_t lds = ((int64_t)p.win * (p.pitch / 4) + 1 + B * (B / 4) + 4) * 4;
+    int64_t tile_bx = 1;
+    if (B == 16 && (R == 16 || R == 32) && pl->tile_req[1] != 1) {
+        const int64_t c4 = cdiv(4 * 16 + 2 * R, 4);
+        if (fastdiv_ok((16 + 2 * R) * c4, c4)) {
+            p.variant = SAD_ROWSCAN_B16;
+            p.bpw = 4;
+            p.groups_x = (int)cdiv(p.nbx, 4);
+            p.pitch = (int)((c4 + 1) * 4);
+            p.div_win4 = make_fastdiv((uint32_t)c4);
+            grid = (int64_t)p.nby * p.groups_x;
+            lds = ((16 + 2 * R) * (c4 + 1) + 1) * 4;
+            tile_bx = 4;
+        }
+    }
+
     pl->out_ndim = 2;
     pl->out_shape[0] = p.nby; pl->out_shape[1] = p.nbx;
     merit_launch_info &li = pl->info;
     li.kernel = sad_kernel_name(p);
-    li.grid[0] = (int64_t)p.nby * p.nbx; li.grid[1] = 1; li.grid[2] = 1;
+    li.grid[0] = grid; li.grid[1] = 1; li.grid[2] = 1;
     li.block[0] = 256; li.block[1] = 1; li.block[2] = 1;
-    li.lds_bytes = ((int64_t)p.win * (p.pitch / 4) + 1 + B * (B / 4) + 4) * 4;
-    li.tile[0] = 1; li.tile[1] = 1; li.tile[2] = n; li.tile[3] = n; li.tile[4] = B; li.tile[5] = B;
+    li.lds_bytes = lds;
+    li.tile[0] = 1; li.tile[1] = tile_bx; li.tile[2] = n; li.tile[3] = n; li.tile[4] = B; li.tile[5] = B;
     return MERIT_OK;
 }
 

@@ -132,12 +132,176 @@ __global__ __launch_bounds__(256) void merit_sad_generic(SadParams p, const uint
 }
 
 // ---------------------------------------------------------------------------
+// Row-scan kernel for 16x16 blocks and a compile-time search range R >= 8.
+//
+// A workgroup stages the joint search window of four horizontally adjacent
+// blocks ((16+2R) rows x (64+2R) bytes); each of its four wavefronts owns one
+// block.  Lane l of a wavefront owns the column of candidates dx = l - R (all
+// dy).  The current block sits in 64 wave-uniform registers.  The wavefront
+// walks the window rows top to bottom; for window row r a lane byte-aligns its
+// 16 reference pixels once (4 x v_alignbyte) and adds them into the partial
+// SADs of the (up to) sixteen candidates dy = r - i that use this row as block
+// row i (4 x v_sad_u8 each), so a reference row is fetched and aligned once
+// for sixteen uses.  Sixteen accumulators rotate: candidate dy completes at row
+// dy + 15 and its slot restarts for dy + 16.  A lane keeps its best (sad, dy)
+// as one packed key; at the end keys are widened to (sad, raster index) and
+// reduced across the wavefront with DPP.
+// The 2R+1 columns do not fill whole wavefronts: what is left after the full
+// 64-column chunks is either run as one more (partly idle) chunk or, when it is
+// narrow, one candidate per lane.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void load_aligned16(const uint32_t *rowp, uint32_t sh, uint32_t (&r)[4])
+{
+    const uint32_t d0 = rowp[0], d1 = rowp[1], d2 = rowp[2], d3 = rowp[3], d4 = rowp[4];
+    r[0] = __builtin_amdgcn_alignbyte(d1, d0, sh);
+    r[1] = __builtin_amdgcn_alignbyte(d2, d1, sh);
+    r[2] = __builtin_amdgcn_alignbyte(d3, d2, sh);
+    r[3] = __builtin_amdgcn_alignbyte(d4, d3, sh);
+}
+
+template <int R>
+__global__ __launch_bounds__(256) void merit_sad_rowscan16(SadParams p, const uint8_t *__restrict__ cur,
+                                                          const uint8_t *__restrict__ ref,
+                                                          int32_t *__restrict__ sad, int32_t *__restrict__ mv)
+{
+    static_assert(R >= 8 && R <= 63, "steady state needs 2R >= 15");
+    constexpr int N = 2 * R + 1, ROWS = 16 + 2 * R;
+    constexpr int NLEFT0 = N % 64;
+    constexpr bool LEFT_AS_CHUNK = NLEFT0 * N > 640;
+    constexpr int NCHUNK = N / 64 + ((LEFT_AS_CHUNK && NLEFT0) ? 1 : 0);
+    constexpr int NLEFT = LEFT_AS_CHUNK ? 0 : NLEFT0;
+    constexpr int NS = 2 * R - 14, NSB = NS / 16, NSR = NS % 16;   // rows 15..2R use all 16 block rows
+
+    extern __shared__ __align__(16) uint32_t lds32[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int pitch4 = p.pitch >> 2;
+    const uint32_t g = blockIdx.x;
+    const int by = (int)(g / (uint32_t)p.groups_x);
+    const int bx0 = (int)(g - (uint32_t)by * p.groups_x) * 4;
+
+    stage_window(p, ref, lds32, by * 16 - R, bx0 * 16 - R, ROWS, pitch4 - 1, p.div_win4, pitch4, tid, 256);
+    __syncthreads();
+    const int bx = bx0 + wv;
+    if (bx >= p.nbx) return;                       // ragged last group (no barrier follows)
+
+    // current block: wave-uniform loads
+    uint32_t c[16][4];
+    {
+        const uint32_t *cp = reinterpret_cast<const uint32_t *>(cur + (size_t)(by * 16) * p.W + bx * 16);
+        const int W4 = p.W >> 2;
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) c[i][j] = cp[i * W4 + j];
+    }
+
+    uint32_t best = 0xffffffffu;                   // (sad << 14) | raster index
+#pragma unroll 1
+    for (int ch = 0; ch < NCHUNK; ++ch) {
+        const int dxi = ch * 64 + lane;
+        const int o = 16 * wv + min(dxi, N - 1);   // idle lanes repeat the last column
+        const uint32_t sh = (uint32_t)(o & 3);
+        const uint32_t *base = lds32 + (o >> 2);
+        uint32_t acc[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) acc[k] = 0;
+        uint32_t lbest = 0xffffffffu;              // (sad << 7) | (dy + R)
+
+        // one window row: block rows i in [ilo, ihi] accumulate into slot (rot - i) & 15;
+        // then candidate `fin` (if >= 0), which sits in slot (rot + 1) & 15, is complete
+        auto step = [&](const uint32_t *rowp, int ilo, int ihi, int rot, int fin) __attribute__((always_inline)) {
+            uint32_t r4[4];
+            load_aligned16(rowp, sh, r4);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                if (i < ilo || i > ihi) continue;
+                const int slot = (rot - i) & 15;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[slot] = __builtin_amdgcn_sad_u8(c[i][j], r4[j], acc[slot]);
+            }
+            if (fin >= 0) {
+                const int slot = (rot + 1) & 15;
+                const uint32_t key = (acc[slot] << 7) | (uint32_t)fin;
+                lbest = key < lbest ? key : lbest;
+                acc[slot] = 0;
+            }
+        };
+
+#pragma unroll
+        for (int r = 0; r < 15; ++r) step(base + r * pitch4, 0, r, r, -1);
+#pragma unroll 1
+        for (int k = 0; k < NSB; ++k) {
+            const uint32_t *rp = base + (15 + 16 * k) * pitch4;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) step(rp + j * pitch4, 0, 15, (15 + j) & 15, 16 * k + j);
+        }
+#pragma unroll
+        for (int j = 0; j < NSR; ++j)
+            step(base + (15 + 16 * NSB + j) * pitch4, 0, 15, (15 + j) & 15, 16 * NSB + j);
+#pragma unroll
+        for (int e = 1; e <= 15; ++e)
+            step(base + (2 * R + e) * pitch4, e, 15, (2 * R + e) & 15, 2 * R + e - 15);
+
+        if (dxi < N) {
+            const uint32_t dyi = lbest & 127u;
+            const uint32_t key = ((lbest >> 7) << KEY_SHIFT) | (dyi * (uint32_t)N + (uint32_t)dxi);
+            best = key < best ? key : best;
+        }
+    }
+
+    if (NLEFT > 0) {
+        // the last NLEFT columns, one candidate per lane
+        constexpr int NCAND = NLEFT * N;
+#pragma unroll 1
+        for (int c0 = 0; c0 < NCAND; c0 += 64) {
+            const int cand = min(c0 + lane, NCAND - 1);
+            const int dyi = cand / NLEFT;
+            const int dxi = (N / 64) * 64 + (cand - dyi * NLEFT);
+            const int o = 16 * wv + dxi;
+            const uint32_t sh = (uint32_t)(o & 3);
+            const uint32_t *base = lds32 + dyi * pitch4 + (o >> 2);
+            uint32_t a = 0;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                uint32_t r4[4];
+                load_aligned16(base + i * pitch4, sh, r4);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) a = __builtin_amdgcn_sad_u8(c[i][j], r4[j], a);
+            }
+            const uint32_t key = (a << KEY_SHIFT) | (uint32_t)(dyi * N + dxi);
+            best = key < best ? key : best;        // idle lanes recompute the last candidate
+        }
+    }
+
+    best = wave_min_u32(best);
+    if (lane == 0) {
+        const uint32_t blk = (uint32_t)by * p.nbx + bx;
+        const uint32_t cidx = best & KEY_MASK;
+        const int dyi = (int)(cidx / (uint32_t)N);
+        sad[blk] = (int32_t)(best >> KEY_SHIFT);
+        mv[2 * blk + 0] = dyi - R;
+        mv[2 * blk + 1] = (int)cidx - dyi * N - R;
+    }
+}
+
+// ---------------------------------------------------------------------------
 hipError_t launch_sad(const SadParams &p, const uint8_t *cur, const uint8_t *ref, int32_t *sad,
                       int32_t *mv, hipStream_t s)
 {
     const uint32_t nblocks = (uint32_t)(p.nby * p.nbx);
     if (nblocks == 0) return hipSuccess;
     const int pitch4 = p.pitch >> 2;
+    if (p.variant == SAD_ROWSCAN_B16) {
+        const uint32_t grid = (uint32_t)(p.nby * p.groups_x);
+        const size_t lds_bytes = (size_t)((16 + 2 * p.R) * pitch4 + 1) * 4;
+        if (p.R == 32)
+            hipLaunchKernelGGL(merit_sad_rowscan16<32>, dim3(grid), dim3(256), lds_bytes, s, p, cur, ref, sad, mv);
+        else
+            hipLaunchKernelGGL(merit_sad_rowscan16<16>, dim3(grid), dim3(256), lds_bytes, s, p, cur, ref, sad, mv);
+        return hipGetLastError();
+    }
     const size_t lds_bytes = (size_t)(p.win * pitch4 + 1 + p.B * (p.B >> 2) + 4) * 4;
     hipLaunchKernelGGL(merit_sad_generic, dim3(nblocks), dim3(256), lds_bytes, s, p, cur, ref, sad, mv);
     return hipGetLastError();
@@ -145,7 +309,7 @@ hipError_t launch_sad(const SadParams &p, const uint8_t *cur, const uint8_t *ref
 
 const char *sad_kernel_name(const SadParams &p)
 {
-    (void)p;
+    if (p.variant == SAD_ROWSCAN_B16) return p.R == 32 ? "merit_sad_rowscan16<32>" : "merit_sad_rowscan16<16>";
     return "merit_sad_generic";
 }
 

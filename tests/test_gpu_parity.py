@@ -123,9 +123,12 @@ def test_pool_empty_batch(mb):
 
 
 # ----------------------------------------------------------- block matching
-def _sad_check(mb, cur, ref, B, R):
+def _sad_check(mb, cur, ref, B, R, tile=None):
     H, W = cur.shape
     plan = mb.merit_plan_sad(H, W, B, R)
+    if tile is not None:
+        plan.set_tile(tile)
+    print("sad", (H, W, B, R), plan.launch_info(), flush=True)
     nby, nbx = plan.out_shape()
     bs, sad, p1 = guarded_empty((nby, nbx), torch.int32, -77)
     bm, mv, p2 = guarded_empty((nby, nbx, 2), torch.int32, -77)
@@ -139,7 +142,9 @@ def _sad_check(mb, cur, ref, B, R):
 
 
 SAD_CASES = [(16, 16, 4, 2), (32, 48, 8, 4), (24, 40, 8, 3), (64, 96, 16, 8), (32, 32, 16, 5),
-             (48, 64, 16, 32), (8, 8, 8, 1), (40, 24, 4, 0), (64, 64, 32, 3)]
+             (48, 64, 16, 32), (8, 8, 8, 1), (40, 24, 4, 0), (64, 64, 32, 3),
+             # row-scan kernel (16x16 blocks, R = 16 / 32): ragged last group of blocks, one block row
+             (64, 96, 16, 16), (80, 112, 16, 32), (16, 16, 16, 32), (32, 80, 16, 16)]
 
 
 @pytest.mark.parametrize("H,W,B,R", SAD_CASES)
@@ -163,6 +168,15 @@ def test_sad_degenerate_frames(mb):
     rows = np.tile(rng.permutation(256)[:32].astype(np.uint8), (32, 1))
     _sad_check(mb, rows, rows, 8, 4)                        # all dy tie
     _sad_check(mb, np.ascontiguousarray(rows.T), np.ascontiguousarray(rows.T), 8, 4)
+
+
+def test_sad_generic_kernel_on_rowscan_shape(mb):
+    """One block per workgroup selects the generic kernel for a shape the row-scan kernel covers."""
+    rng = np.random.default_rng(21)
+    cur = rng.integers(0, 256, size=(48, 64), dtype=np.uint8)
+    ref = rng.integers(0, 256, size=(48, 64), dtype=np.uint8)
+    _sad_check(mb, cur, ref, 16, 32, tile=(0, 1))
+    _sad_check(mb, cur & 0x1, ref & 0x1, 16, 32)
 
 
 def test_sad_cfg0(mb):
