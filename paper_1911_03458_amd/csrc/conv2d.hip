@@ -9,8 +9,7 @@
 // and every lane expands its windows from there with one vector LDS read per
 // MFMA operand.  Weights are the MFMA "A" operand (rows = output channels),
 // pixels the "B" operand (columns), so a lane's accumulator registers hold one
-// pixel for 16 output channels and stores run along the contiguous pixel axis
-// of NCHW.
+// pixel for 16 output channels.
 //
 // The accumulation order K is free (both operands use the same order), so it
 // is chosen per variant to make eight consecutive k contiguous in LDS:
@@ -19,11 +18,18 @@
 //                 row of the window.
 //   channel-block (many input channels): K = (ci/8, ky, kx | ci%8); the input
 //                 tile is staged as [ci/8][row][col][8 channels].
+//
+// Workgroups are persistent: each stages its weights once and then walks tiles
+// blockIdx.x, blockIdx.x + gridDim.x, ...  A tile is TM consecutive output
+// pixels (row-major within one image) times CB*32 output channels.  Results
+// leave through an LDS transpose so that global stores are 16 bytes per lane
+// along the contiguous pixel axis of NCHW.
 #include "merit_internal.h"
 
 namespace merit {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 union Frag {
@@ -37,43 +43,93 @@ __device__ __forceinline__ floatx16 mfma16(const Frag &a, const Frag &b, floatx1
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(a.h, b.h, c, 0, 0, 0);
 }
 
-// Accumulator register r of lane l holds output channel 8*(r/4) + 4*(l/32) + r%4
-// (within the 32-channel block) of pixel l%32 (within the 32-pixel block).
-template <int CB, int PXW>
-__device__ __forceinline__ void store_tile(const ConvParams &p, floatx16 (&acc)[CB][PXW],
-                                           _Float16 *__restrict__ y, int n, int co_base,
-                                           const int (&m)[PXW], int lane)
+__device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi)
 {
-    const int h = lane >> 5;
+    half2v v;
+    v.x = (_Float16)lo;       // v_cvt_f16_f32: round to nearest even
+    v.y = (_Float16)hi;
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+// ---------------------------------------------------------------------------
+// Epilogue.  Accumulator register r of lane l holds output channel
+// 8*(r/4) + 4*(l/32) + r%4 (within its 32-channel block) of pixel l%32 (within
+// its 32-pixel block).  Channel pairs (r, r+1) are packed into one dword and
+// written to LDS as outl[channel pair][pixel]; after a barrier every thread
+// reads 8 pixels x 2 channels, splits the pair and stores two 16-byte runs.
+// The row pitch TM+16 dwords puts the two lane halves (4 channels apart) on
+// disjoint banks.
+// ---------------------------------------------------------------------------
+template <int CB, int PXW>
+__device__ __forceinline__ void store_tile(const ConvParams &p, floatx16 (&acc)[CB][PXW], uint32_t *outl,
+                                           uint16_t *__restrict__ y, int n, int co_base, int m0, int tid)
+{
+    constexpr int TM = 4 * PXW * 32;
+    constexpr int OP = TM + 16;
+    const int lane = tid & 63, wave = tid >> 6, h = lane >> 5, c32 = lane & 31;
     const int ohw = p.OH * p.OW;
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-        for (int pb = 0; pb < PXW; ++pb) {
-            if (m[pb] >= ohw) continue;
+        for (int pb = 0; pb < PXW; ++pb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int co = co_base + cb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-                if (co < p.Cout)
-                    y[((size_t)n * p.Cout + co) * ohw + m[pb]] = (_Float16)acc[cb][pb][r];
+            for (int r = 0; r < 16; r += 2) {
+                const int cp = cb * 16 + 4 * (r >> 2) + 2 * h + ((r & 3) >> 1);
+                outl[cp * OP + (wave * PXW + pb) * 32 + c32] = pack_f16x2(acc[cb][pb][r], acc[cb][pb][r + 1]);
+            }
+    __syncthreads();
+    const bool vec_ok = (ohw & 7) == 0;
+    constexpr int UNITS = CB * 16 * (TM / 8);
+#pragma unroll
+    for (int u = tid; u < UNITS; u += 256) {
+        const int cp = u / (TM / 8);
+        const int px8 = u - cp * (TM / 8);
+        const int m = m0 + px8 * 8;
+        const int co = co_base + 2 * cp;
+        if (m >= ohw || co >= p.Cout) continue;
+        const uint4 a = *reinterpret_cast<const uint4 *>(outl + cp * OP + px8 * 8);
+        const uint4 b = *reinterpret_cast<const uint4 *>(outl + cp * OP + px8 * 8 + 4);
+        uint4 ev, od;
+        ev.x = __builtin_amdgcn_perm(a.y, a.x, 0x05040100u); od.x = __builtin_amdgcn_perm(a.y, a.x, 0x07060302u);
+        ev.y = __builtin_amdgcn_perm(a.w, a.z, 0x05040100u); od.y = __builtin_amdgcn_perm(a.w, a.z, 0x07060302u);
+        ev.z = __builtin_amdgcn_perm(b.y, b.x, 0x05040100u); od.z = __builtin_amdgcn_perm(b.y, b.x, 0x07060302u);
+        ev.w = __builtin_amdgcn_perm(b.w, b.z, 0x05040100u); od.w = __builtin_amdgcn_perm(b.w, b.z, 0x07060302u);
+        uint16_t *y0 = y + ((size_t)n * p.Cout + co) * ohw + m;
+        if (vec_ok) {
+            *reinterpret_cast<uint4 *>(y0) = ev;
+            if (co + 1 < p.Cout) *reinterpret_cast<uint4 *>(y0 + ohw) = od;
+        } else {
+            const uint32_t e[4] = {ev.x, ev.y, ev.z, ev.w}, o[4] = {od.x, od.y, od.z, od.w};
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                if (m + k >= ohw) break;
+                y0[k] = (uint16_t)(e[k >> 1] >> (16 * (k & 1)));
+                if (co + 1 < p.Cout) y0[ohw + k] = (uint16_t)(o[k >> 1] >> (16 * (k & 1)));
             }
         }
+    }
 }
 
 // ---------------------------------------------------------------------------
 // planar variant
-// LDS: [ weights: CB*G2*32 x 16 B ][ 32 B of zeros ][ input: Cin*RHa*pitch halves ][ group offsets: G2 x 4 B ]
+// LDS: [ weights: CB*G2*32 x 16 B ][ 32 B of zeros ][ input: Cin*RHa*pitch halves ]
+//      [ group offsets: G2 x 4 B, padded to 16 B ][ output staging ]
+// A K-group g = (ci, ky) is one window row: its kw taps occupy slots
+// front .. front+kw-1 of an 8-slot fragment (front = 0 or 1 is chosen so that the
+// fragment starts on an even staged column whenever the column stride is even);
+// unused slots are cleared in the data and zero in the weights.
 // ---------------------------------------------------------------------------
-template <int CB, int PXW>
-__global__ __launch_bounds__(256) void merit_conv2d_planar(ConvParams p, const uint16_t *__restrict__ x,
-                                                          const uint16_t *__restrict__ w,
-                                                          _Float16 *__restrict__ y)
+template <int CB, int PXW, bool ALIGNED>
+__global__ __launch_bounds__(256, 2) void merit_conv2d_planar(ConvParams p, const uint16_t *__restrict__ x,
+                                                             const uint16_t *__restrict__ w,
+                                                             uint16_t *__restrict__ y)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     uint4 *wl = reinterpret_cast<uint4 *>(smem);
     uint8_t *xz = smem + p.lds_w_bytes;                 // 32 zero bytes, then the tile
     uint8_t *xl = xz + 32;
     uint32_t *goff = reinterpret_cast<uint32_t *>(xl + p.lds_x_bytes);
+    uint32_t *outl = reinterpret_cast<uint32_t *>(smem + p.lds_o_offset);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6, h = lane >> 5, c32 = lane & 31;
@@ -81,37 +137,40 @@ __global__ __launch_bounds__(256) void merit_conv2d_planar(ConvParams p, const u
     const int P8 = p.pitch >> 3;
     const int ohw = p.OH * p.OW;
 
-    // ---- weights: zero-fill, then scatter w[co][g][kx] to slot kx of group g ----
-    const int nwl = CB * p.G2 * 32;
-    for (int u = tid; u < nwl; u += 256) wl[u] = make_uint4(0, 0, 0, 0);
-    if (tid < 8) reinterpret_cast<uint32_t *>(xz)[tid] = 0;
-    for (int g = tid; g < p.G2; g += 256) {
-        const int ci = (int)fdiv((uint32_t)g, p.div_kh);
-        const int ky = g - ci * p.kh;
-        goff[g] = (uint32_t)(((ci * p.RHa + ky) * p.pitch) * 2);
-    }
-    __syncthreads();
+    // ---- weights, once per workgroup: unit = (local output channel, group) ----
     {
-        uint16_t *wl16 = reinterpret_cast<uint16_t *>(smem);
-        const int gk = p.G * p.kw;                       // halves per output channel
-        const int nco = min(CB * 32, p.Cout - co_base);
-        const int total = nco * gk;
-        const uint16_t *wsrc = w + (size_t)co_base * gk;
-        for (int f = tid; f < total; f += 256) {
-            const int col = f / gk;                      // local output channel
-            const int rem = f - col * gk;
-            const int g = rem / p.kw;
-            const int t = rem - g * p.kw;
-            const int cb = col >> 5, cc = col & 31;
-            wl16[(((cb * p.G2 + g) * 32 + cc) << 3) + t] = wsrc[f];
+        const int units = CB * 32 * p.G2;
+        for (int u = tid; u < units; u += 256) {
+            const int col = (int)fdiv((uint32_t)u, p.div_g2);
+            const int g = u - col * p.G2;
+            const int co = co_base + col;
+            uint32_t d[4] = {0, 0, 0, 0};
+            if (co < p.Cout && g < p.G) {
+                const uint16_t *src = w + ((size_t)co * p.G + g) * p.kw;
+#pragma unroll
+                for (int t = 0; t < 8; ++t)
+                    if (t < p.kw) {
+                        const int s = t + p.front;
+                        d[s >> 1] |= (uint32_t)src[t] << (16 * (s & 1));
+                    }
+            }
+            wl[((col >> 5) * p.G2 + g) * 32 + (col & 31)] = make_uint4(d[0], d[1], d[2], d[3]);
+        }
+        if (tid < 8) reinterpret_cast<uint32_t *>(xz)[tid] = 0;
+        for (int g = tid; g < p.G2; g += 256) {
+            const int ci = (int)fdiv((uint32_t)g, p.div_kh);
+            const int ky = g - ci * p.kh;
+            goff[g] = (uint32_t)(((ci * p.RHa + ky) * p.pitch) * 2);
         }
     }
 
-    // masks that clear the slots kx >= kw of a fragment
+    // masks that clear the slots outside [front, front+kw) of a fragment
     uint32_t kmask[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
-        kmask[q] = ((2 * q < p.kw) ? 0x0000ffffu : 0u) | ((2 * q + 1 < p.kw) ? 0xffff0000u : 0u);
+    for (int q = 0; q < 4; ++q) {
+        const int s0 = 2 * q - p.front, s1 = 2 * q + 1 - p.front;
+        kmask[q] = ((s0 >= 0 && s0 < p.kw) ? 0x0000ffffu : 0u) | ((s1 >= 0 && s1 < p.kw) ? 0xffff0000u : 0u);
+    }
 
     const int ntiles = p.N * p.tiles_per_image;
     for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
@@ -155,15 +214,14 @@ __global__ __launch_bounds__(256) void merit_conv2d_planar(ConvParams p, const u
         __syncthreads();
 
         // ---- per-lane pixel bases ----
-        int m[PXW];
         uint32_t pbase[PXW], shift[PXW];
 #pragma unroll
         for (int pb = 0; pb < PXW; ++pb) {
-            m[pb] = m0 + (wave * PXW + pb) * 32 + c32;
-            const int mm = min(m[pb], ohw - 1);
+            const int m = m0 + (wave * PXW + pb) * 32 + c32;
+            const int mm = min(m, ohw - 1);
             const int oy = (int)fdiv((uint32_t)mm, p.div_ow);
             const int ox = mm - oy * p.OW;
-            const int cs = p.padl - p.pw + ox * p.sw;       // staged column of tap kx = 0
+            const int cs = p.padl - p.pw + ox * p.sw - p.front;       // staged column of slot 0
             pbase[pb] = (uint32_t)((((oy - oyA) * p.sh) * p.pitch + (cs & ~1)) * 2) + 32u;
             shift[pb] = (uint32_t)(cs & 1) * 16u;
         }
@@ -188,52 +246,56 @@ __global__ __launch_bounds__(256) void merit_conv2d_planar(ConvParams p, const u
                 // groups past the end read the zero block (their weights are zero too)
                 const uint32_t addr = gvalid ? pbase[pb] + go : 0u;
                 const uint32_t *src = reinterpret_cast<const uint32_t *>(xz + addr);
-                uint32_t d[5];
+                if (ALIGNED) {
 #pragma unroll
-                for (int q = 0; q < 5; ++q) d[q] = src[q];
+                    for (int q = 0; q < 4; ++q) b[pb].d[q] = src[q] & kmask[q];
+                } else {
+                    uint32_t d[5];
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    b[pb].d[q] = __builtin_amdgcn_alignbit(d[q + 1], d[q], shift[pb]) & kmask[q];
+                    for (int q = 0; q < 5; ++q) d[q] = src[q];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        b[pb].d[q] = __builtin_amdgcn_alignbit(d[q + 1], d[q], shift[pb]) & kmask[q];
+                }
             }
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
                 for (int pb = 0; pb < PXW; ++pb) acc[cb][pb] = mfma16(a[cb], b[pb], acc[cb][pb]);
         }
-        store_tile<CB, PXW>(p, acc, y, n, co_base, m, lane);
+        store_tile<CB, PXW>(p, acc, outl, y, n, co_base, m0, tid);
     }
 }
 
 // ---------------------------------------------------------------------------
 // channel-block variant
-// LDS: [ weights: S*CB*64 x 16 B ][ input: nchi*RHa*pitch x 16 B ]
+// LDS: [ weights: S*CB*64 x 16 B ][ input: nchi*RHa*pitch x 16 B ][ output staging ]
 // MFMA step s = (chi', tap): lanes 0-31 take channel group chi', lanes 32-63
 // take chi' + nchi/2, so the per-step LDS offset is the same for every lane.
 // ---------------------------------------------------------------------------
+
+// weights, 8 channels x T taps per unit, read as T 16-byte loads and transposed
+// in registers to T fragments of 8 channels (needs Cin % 8 == 0)
 template <int T>
 __device__ __forceinline__ void stage_weights_chblock_vec(const ConvParams &p, const uint16_t *__restrict__ w,
-                                                          uint4 *wl, int co_base, int CB, int tid)
+                                                          uint4 *wl, int co_base, int CB, int t0, int nthr)
 {
-    // unit = (local output channel, channel group): 8 channels x T taps = T uint4, contiguous
     const int half_nchi = p.nchi >> 1;
     const int units = CB * 32 * p.nchi;
-    for (int u = tid; u < units; u += 256) {
+#pragma unroll 2
+    for (int u = t0; u < units; u += nthr) {
         const int col = u / p.nchi;
         const int chi = u - col * p.nchi;
         const int co = co_base + col;
-        uint32_t src[4 * T];
         const bool ok = (co < p.Cout) && (chi * 8 + 8 <= p.Cin);
-        if (ok) {
-            const uint4 *g = reinterpret_cast<const uint4 *>(w + ((size_t)co * p.Cin + chi * 8) * T);
+        // branch-free load (a padding unit re-reads unit 0 and is zeroed below)
+        const uint4 *g = reinterpret_cast<const uint4 *>(w + (ok ? ((size_t)co * p.Cin + chi * 8) * T : 0));
+        uint32_t src[4 * T];
 #pragma unroll
-            for (int i = 0; i < T; ++i) {
-                const uint4 v = g[i];
-                src[4 * i + 0] = v.x; src[4 * i + 1] = v.y; src[4 * i + 2] = v.z; src[4 * i + 3] = v.w;
-            }
-        } else {
-            // zero-padding channel group or output channel (callers guarantee Cin % 8 == 0)
-#pragma unroll
-            for (int i = 0; i < 4 * T; ++i) src[i] = 0;
+        for (int i = 0; i < T; ++i) {
+            const uint4 v = g[i];
+            src[4 * i + 0] = ok ? v.x : 0u; src[4 * i + 1] = ok ? v.y : 0u;
+            src[4 * i + 2] = ok ? v.z : 0u; src[4 * i + 3] = ok ? v.w : 0u;
         }
         const int hh = chi >= half_nchi ? 1 : 0;
         const int chip = chi - hh * half_nchi;
@@ -254,12 +316,12 @@ __device__ __forceinline__ void stage_weights_chblock_vec(const ConvParams &p, c
 }
 
 __device__ __forceinline__ void stage_weights_chblock_scalar(const ConvParams &p, const uint16_t *__restrict__ w,
-                                                             uint4 *wl, int co_base, int CB, int tid)
+                                                             uint4 *wl, int co_base, int CB, int t0, int nthr)
 {
     const int T = p.kh * p.kw;
     const int half_nchi = p.nchi >> 1;
     const int units = CB * 32 * p.nchi * T;          // one 16-byte fragment each
-    for (int u = tid; u < units; u += 256) {
+    for (int u = t0; u < units; u += nthr) {
         const int t = u % T;
         const int r = u / T;
         const int chi = r % p.nchi;
@@ -280,27 +342,102 @@ __device__ __forceinline__ void stage_weights_chblock_scalar(const ConvParams &p
     }
 }
 
+__device__ __forceinline__ void stage_weights_chblock(const ConvParams &p, const uint16_t *__restrict__ w,
+                                                      uint4 *wl, int co_base, int CB, int t0, int nthr)
+{
+    const int T = p.kh * p.kw;
+    if (T == 9 && (p.Cin & 7) == 0) stage_weights_chblock_vec<9>(p, w, wl, co_base, CB, t0, nthr);
+    else if (T == 1 && (p.Cin & 7) == 0) stage_weights_chblock_vec<1>(p, w, wl, co_base, CB, t0, nthr);
+    else stage_weights_chblock_scalar(p, w, wl, co_base, CB, t0, nthr);
+}
+
+// input rows [yA, yA+RH) of image n as [ci/8][row][col][8 channels]
+__device__ __forceinline__ void stage_input_chblock(const ConvParams &p, const uint16_t *__restrict__ x, uint4 *xl,
+                                                    int n, int yA, int RH, int t0, int nthr)
+{
+    // zero the padding columns of the staged rows
+    const int npad = p.pitch - p.W;
+    for (int u = t0; u < p.nchi * p.RHa * npad; u += nthr) {
+        const int rowi = u / npad;
+        const int c = u - rowi * npad;
+        const int col = c < p.padl ? c : p.W + c;
+        xl[rowi * p.pitch + col] = make_uint4(0, 0, 0, 0);
+    }
+    if ((p.W & 7) == 0) {
+        // 8 channels x 8 pixels per unit, transposed in registers
+        const int W8 = p.W >> 3;
+        const int nu = p.nchi * p.RHa * W8;
+        const size_t chstride = (size_t)p.H * p.W;
+#pragma unroll 2
+        for (int u = t0; u < nu; u += nthr) {
+            const int q = (int)fdiv((uint32_t)u, p.div_w8);
+            const int x8 = u - q * W8;
+            const int chi = (int)fdiv((uint32_t)q, p.div_rha);
+            const int r = q - chi * p.RHa;
+            if (r >= RH) continue;
+            const int gy = yA + r;
+            const bool rowok = gy >= 0 && gy < p.H;
+            const uint16_t *src = x + (((size_t)n * p.Cin + chi * 8) * p.H + (rowok ? gy : 0)) * p.W + 8 * x8;
+            uint32_t v[8][4];
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                const bool ok = rowok && (chi * 8 + c < p.Cin);
+                // branch-free: a padding channel re-reads channel group row 0 and is zeroed
+                const uint4 t4 = *reinterpret_cast<const uint4 *>(ok ? src + c * chstride : x);
+                v[c][0] = ok ? t4.x : 0u; v[c][1] = ok ? t4.y : 0u; v[c][2] = ok ? t4.z : 0u; v[c][3] = ok ? t4.w : 0u;
+            }
+            uint4 *dst = xl + (chi * p.RHa + r) * p.pitch + p.padl + 8 * x8;
+#pragma unroll
+            for (int px = 0; px < 8; ++px) {
+                const uint32_t sel = (px & 1) ? 0x07060302u : 0x05040100u;
+                uint32_t d[4];
+#pragma unroll
+                for (int qq = 0; qq < 4; ++qq)
+                    d[qq] = __builtin_amdgcn_perm(v[2 * qq + 1][px >> 1], v[2 * qq][px >> 1], sel);
+                dst[px] = make_uint4(d[0], d[1], d[2], d[3]);
+            }
+        }
+    } else {
+        const int nu = p.nchi * p.RHa * p.W;
+        for (int u = t0; u < nu; u += nthr) {
+            const int q = u / p.W;
+            const int xg = u - q * p.W;
+            const int chi = q / p.RHa;
+            const int r = q - chi * p.RHa;
+            if (r >= RH) continue;
+            const int gy = yA + r;
+            uint32_t d[4] = {0, 0, 0, 0};
+            if (gy >= 0 && gy < p.H) {
+#pragma unroll
+                for (int c = 0; c < 8; ++c) {
+                    const int ch = chi * 8 + c;
+                    if (ch < p.Cin)
+                        d[c >> 1] |= (uint32_t)x[(((size_t)n * p.Cin + ch) * p.H + gy) * p.W + xg] << (16 * (c & 1));
+                }
+            }
+            xl[(chi * p.RHa + r) * p.pitch + p.padl + xg] = make_uint4(d[0], d[1], d[2], d[3]);
+        }
+    }
+}
+
 template <int CB, int PXW>
 __global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const uint16_t *__restrict__ x,
                                                            const uint16_t *__restrict__ w,
-                                                           _Float16 *__restrict__ y)
+                                                           uint16_t *__restrict__ y)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     uint4 *wl = reinterpret_cast<uint4 *>(smem);
     uint4 *xl = reinterpret_cast<uint4 *>(smem + p.lds_w_bytes);
+    uint32_t *outl = reinterpret_cast<uint32_t *>(smem + p.lds_o_offset);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6, h = lane >> 5, c32 = lane & 31;
     const int co_base = blockIdx.y * CB * 32;
     const int ohw = p.OH * p.OW;
-    const int T = p.kh * p.kw;
     const int half_nchi = p.nchi >> 1;
 
-    if (T == 9 && (p.Cin & 7) == 0) stage_weights_chblock_vec<9>(p, w, wl, co_base, CB, tid);
-    else if (T == 1 && (p.Cin & 7) == 0) stage_weights_chblock_vec<1>(p, w, wl, co_base, CB, tid);
-    else stage_weights_chblock_scalar(p, w, wl, co_base, CB, tid);
-
     const int ntiles = p.N * p.tiles_per_image;
+    bool first = true;
     for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const int n = (int)fdiv((uint32_t)tile, p.div_tiles);
         const int m0 = (tile - n * p.tiles_per_image) * p.TM;
@@ -311,74 +448,22 @@ __global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const 
         const int RH = (oyB - oyA) * p.sh + p.kh;
 
         __syncthreads();
-        // ---- zero the padding columns of the staged rows ----
-        const int npad = p.pitch - p.W;
-        for (int u = tid; u < p.nchi * p.RHa * npad; u += 256) {
-            const int rowi = u / npad;
-            const int c = u - rowi * npad;
-            const int col = c < p.padl ? c : p.W + c;
-            xl[rowi * p.pitch + col] = make_uint4(0, 0, 0, 0);
-        }
-        // ---- stage input: 8 channels x 8 pixels per unit, transposed in registers ----
-        if ((p.W & 7) == 0) {
-            const int W8 = p.W >> 3;
-            const int nu = p.nchi * p.RHa * W8;
-            for (int u = tid; u < nu; u += 256) {
-                const int q = (int)fdiv((uint32_t)u, p.div_w8);
-                const int x8 = u - q * W8;
-                const int chi = (int)fdiv((uint32_t)q, p.div_rha);
-                const int r = q - chi * p.RHa;
-                if (r >= RH) continue;
-                const int gy = yA + r;
-                uint32_t v[8][4];
-#pragma unroll
-                for (int c = 0; c < 8; ++c) {
-                    const int ch = chi * 8 + c;
-                    uint4 t4 = make_uint4(0, 0, 0, 0);
-                    if (ch < p.Cin && gy >= 0 && gy < p.H)
-                        t4 = *reinterpret_cast<const uint4 *>(x + (((size_t)n * p.Cin + ch) * p.H + gy) * p.W + 8 * x8);
-                    v[c][0] = t4.x; v[c][1] = t4.y; v[c][2] = t4.z; v[c][3] = t4.w;
-                }
-                uint4 *dst = xl + (chi * p.RHa + r) * p.pitch + p.padl + 8 * x8;
-#pragma unroll
-                for (int px = 0; px < 8; ++px) {
-                    const uint32_t sel = (px & 1) ? 0x07060302u : 0x05040100u;
-                    uint32_t d[4];
-#pragma unroll
-                    for (int qq = 0; qq < 4; ++qq)
-                        d[qq] = __builtin_amdgcn_perm(v[2 * qq + 1][px >> 1], v[2 * qq][px >> 1], sel);
-                    dst[px] = make_uint4(d[0], d[1], d[2], d[3]);
-                }
-            }
+        if (first) {
+            // first tile: half of the wavefronts fetch the weights (once per workgroup) while
+            // the other half fetches the input, so the two global-memory round trips overlap
+            if (wave < 2) stage_weights_chblock(p, w, wl, co_base, CB, tid, 128);
+            else stage_input_chblock(p, x, xl, n, yA, RH, tid - 128, 128);
+            first = false;
         } else {
-            const int nu = p.nchi * p.RHa * p.W;
-            for (int u = tid; u < nu; u += 256) {
-                const int q = u / p.W;
-                const int xg = u - q * p.W;
-                const int chi = q / p.RHa;
-                const int r = q - chi * p.RHa;
-                if (r >= RH) continue;
-                const int gy = yA + r;
-                uint32_t d[4] = {0, 0, 0, 0};
-                if (gy >= 0 && gy < p.H) {
-#pragma unroll
-                    for (int c = 0; c < 8; ++c) {
-                        const int ch = chi * 8 + c;
-                        if (ch < p.Cin)
-                            d[c >> 1] |= (uint32_t)x[(((size_t)n * p.Cin + ch) * p.H + gy) * p.W + xg] << (16 * (c & 1));
-                    }
-                }
-                xl[(chi * p.RHa + r) * p.pitch + p.padl + xg] = make_uint4(d[0], d[1], d[2], d[3]);
-            }
+            stage_input_chblock(p, x, xl, n, yA, RH, tid, 256);
         }
         __syncthreads();
 
-        int m[PXW];
         int pbase[PXW];
 #pragma unroll
         for (int pb = 0; pb < PXW; ++pb) {
-            m[pb] = m0 + (wave * PXW + pb) * 32 + c32;
-            const int mm = min(m[pb], ohw - 1);
+            const int m = m0 + (wave * PXW + pb) * 32 + c32;
+            const int mm = min(m, ohw - 1);
             const int oy = (int)fdiv((uint32_t)mm, p.div_ow);
             const int ox = mm - oy * p.OW;
             // staged column of tap kx = 0 is padl - pw + ox*sw
@@ -409,7 +494,7 @@ __global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const 
                         for (int pb = 0; pb < PXW; ++pb) acc[cb][pb] = mfma16(a[cb], b[pb], acc[cb][pb]);
                 }
             }
-        store_tile<CB, PXW>(p, acc, y, n, co_base, m, lane);
+        store_tile<CB, PXW>(p, acc, outl, y, n, co_base, m0, tid);
     }
 }
 
@@ -426,27 +511,50 @@ static hipError_t launch(K kernel, const ConvParams &p, const void *x, const voi
     }
     hipLaunchKernelGGL(kernel, dim3(gx, (uint32_t)p.co_groups), dim3(256), lds_bytes, s, p,
                        reinterpret_cast<const uint16_t *>(x), reinterpret_cast<const uint16_t *>(w),
-                       reinterpret_cast<_Float16 *>(y));
+                       reinterpret_cast<uint16_t *>(y));
     return hipGetLastError();
 }
 
 size_t conv_lds_bytes(const ConvParams &p)
 {
-    if (p.variant == CONV_PLANAR_SMALLC) return (size_t)p.lds_w_bytes + 32 + p.lds_x_bytes + (size_t)p.G2 * 4;
-    return (size_t)p.lds_w_bytes + p.lds_x_bytes;
+    return (size_t)p.lds_o_offset + p.lds_o_bytes;
+}
+
+// number of compute units of the current device (cached; 256 on MI355X)
+static int device_cu_count()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            cus = v;
+        else
+            cus = 256;
+    }
+    return cus;
 }
 
 hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, void *y, hipStream_t s)
 {
     const int64_t ntiles = (int64_t)p.N * p.tiles_per_image;
     if (ntiles == 0) return hipSuccess;
-    const uint32_t gx = (uint32_t)ntiles;
+    // persistent grid: as many workgroups as fit on the chip at once, at most one per tile
+    int64_t slots = (int64_t)device_cu_count() * p.wg_per_cu / p.co_groups;
+    if (slots < 1) slots = 1;
+    const uint32_t gx = (uint32_t)(ntiles < slots ? ntiles : slots);
     const size_t lds = conv_lds_bytes(p);
     if (p.variant == CONV_PLANAR_SMALLC) {
-        if (p.CB == 2 && p.PXW == 2) return launch(merit_conv2d_planar<2, 2>, p, x, w, y, s, gx, lds);
-        if (p.CB == 2 && p.PXW == 1) return launch(merit_conv2d_planar<2, 1>, p, x, w, y, s, gx, lds);
-        if (p.CB == 1 && p.PXW == 2) return launch(merit_conv2d_planar<1, 2>, p, x, w, y, s, gx, lds);
-        return launch(merit_conv2d_planar<1, 1>, p, x, w, y, s, gx, lds);
+        if (p.aligned) {
+            if (p.CB == 2 && p.PXW == 2) return launch(merit_conv2d_planar<2, 2, true>, p, x, w, y, s, gx, lds);
+            if (p.CB == 2 && p.PXW == 1) return launch(merit_conv2d_planar<2, 1, true>, p, x, w, y, s, gx, lds);
+            if (p.CB == 1 && p.PXW == 2) return launch(merit_conv2d_planar<1, 2, true>, p, x, w, y, s, gx, lds);
+            return launch(merit_conv2d_planar<1, 1, true>, p, x, w, y, s, gx, lds);
+        }
+        if (p.CB == 2 && p.PXW == 2) return launch(merit_conv2d_planar<2, 2, false>, p, x, w, y, s, gx, lds);
+        if (p.CB == 2 && p.PXW == 1) return launch(merit_conv2d_planar<2, 1, false>, p, x, w, y, s, gx, lds);
+        if (p.CB == 1 && p.PXW == 2) return launch(merit_conv2d_planar<1, 2, false>, p, x, w, y, s, gx, lds);
+        return launch(merit_conv2d_planar<1, 1, false>, p, x, w, y, s, gx, lds);
     }
     if (p.CB == 2 && p.PXW == 2) return launch(merit_conv2d_chblock<2, 2>, p, x, w, y, s, gx, lds);
     if (p.CB == 2 && p.PXW == 1) return launch(merit_conv2d_chblock<2, 1>, p, x, w, y, s, gx, lds);

@@ -90,6 +90,11 @@ struct ConvParams {
     int nchi;              // channel-blocked: 8-channel groups incl. zero padding (even)
     int lds_w_bytes;       // weights region
     int lds_x_bytes;       // input region
+    int lds_o_offset;      // output staging region: byte offset and size
+    int lds_o_bytes;
+    int front;             // planar: slot of tap kx = 0 inside an 8-slot fragment (0 or 1)
+    int aligned;           // planar: every fragment starts on an even staged column
+    int wg_per_cu;         // resident workgroups per compute unit the launcher sizes the grid for
     FastDiv div_ow;
     FastDiv div_kh;
     FastDiv div_pitch8;    // planar staging: 16-byte units per staged row

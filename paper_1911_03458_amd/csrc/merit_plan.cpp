@@ -294,6 +294,12 @@ merit_status derive_conv(merit_plan *pl)
         if (variant == CONV_PLANAR_SMALLC) {
             if (kw > 8 || pw > 8) return false;
             q.padl = 8;
+            // with an even column stride every window starts on the same column parity; if that
+            // parity is odd and a slot is free, start the fragment one column earlier (front = 1)
+            // so that it is dword-aligned in LDS and needs no funnel shift
+            const bool odd_start = ((q.padl - pw) & 1) != 0;
+            q.front = (sw % 2 == 0 && odd_start && kw <= 7) ? 1 : 0;
+            q.aligned = (sw % 2 == 0 && ((q.padl - pw - q.front) & 1) == 0) ? 1 : 0;
             int64_t pitch = q.padl + W;
             const int64_t reach = q.padl - pw + (OW - 1) * sw + 10;
             if (reach > pitch) pitch = reach;
@@ -308,8 +314,11 @@ merit_status derive_conv(merit_plan *pl)
             if (!fastdiv_ok((int64_t)Cin * q.RHa, q.RHa) || !fastdiv_ok(q.G2, kh)) return false;
             q.div_pitch8 = make_fastdiv((uint32_t)(q.pitch / 8));
             q.div_kh = make_fastdiv((uint32_t)kh);
+            if (!fastdiv_ok((int64_t)q.CB * 32 * q.G2, q.G2)) return false;
             q.div_g2 = make_fastdiv((uint32_t)q.G2);
+            q.lds_o_offset = (int)round_up((int64_t)q.lds_w_bytes + 32 + q.lds_x_bytes + (int64_t)q.G2 * 4, 16);
         } else {
+            q.front = 0; q.aligned = 0;
             q.nchi = (int)(cdiv(Cin, 16) * 2);
             q.padl = (int)pw;
             int64_t pitch = q.padl + W;
@@ -325,9 +334,13 @@ merit_status derive_conv(merit_plan *pl)
                 q.div_w8 = make_fastdiv((uint32_t)(W / 8));
             }
             if (!fastdiv_ok((int64_t)q.nchi * q.RHa, q.RHa)) return false;
+            q.lds_o_offset = q.lds_w_bytes + q.lds_x_bytes;
         }
+        q.lds_o_bytes = q.CB * 16 * (q.TM + 16) * 4;      // [channel pair][TM + 16] dwords
         q.div_rha = make_fastdiv((uint32_t)q.RHa);
         if ((int64_t)conv_lds_bytes(q) > LDS_LIMIT) return false;
+        q.wg_per_cu = (int)(LDS_LIMIT / (int64_t)conv_lds_bytes(q));
+        if (q.wg_per_cu > 2) q.wg_per_cu = 2;             // register budget: two workgroups per CU
         if (!fastdiv_ok(ohw, OW) || !fastdiv_ok((int64_t)N * q.tiles_per_image, q.tiles_per_image)) return false;
         q.div_ow = make_fastdiv((uint32_t)OW);
         q.div_tiles = make_fastdiv((uint32_t)q.tiles_per_image);
@@ -352,7 +365,14 @@ merit_status derive_conv(merit_plan *pl)
     pl->out_shape[0] = N; pl->out_shape[1] = Cout; pl->out_shape[2] = OH; pl->out_shape[3] = OW;
     merit_launch_info &li = pl->info;
     li.kernel = conv_kernel_name(p);
-    li.grid[0] = (int64_t)N * p.tiles_per_image; li.grid[1] = p.co_groups; li.grid[2] = 1;
+    // persistent grid; the launcher sizes it from the device's CU count (256 on MI355X)
+    {
+        int64_t slots = 256 * (int64_t)p.wg_per_cu / p.co_groups;
+        if (slots < 1) slots = 1;
+        const int64_t nt = (int64_t)N * p.tiles_per_image;
+        li.grid[0] = nt < slots ? nt : slots;
+    }
+    li.grid[1] = p.co_groups; li.grid[2] = 1;
     li.block[0] = 256; li.block[1] = 1; li.block[2] = 1;
     li.lds_bytes = (int64_t)conv_lds_bytes(p);
     li.tile[0] = 1; li.tile[1] = p.CB * 32; li.tile[2] = p.rows_out_max; li.tile[3] = OW;
