@@ -42,6 +42,9 @@ def parse_args():
     ap.add_argument("--sets", type=int, default=8, help="rotating buffer sets for cache-cold timing")
     ap.add_argument("--no-extra", action="store_true", help="skip the other four workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 256 MiB device copy 10 times (known traffic, for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings) and exit")
     return ap.parse_args()
 
 
@@ -71,11 +74,13 @@ def bench_pool(torch, mb, wl, steps, warmup, nsets):
     pmax = mb.merit_plan_pool2d(c.N, c.C, c.H, c.W, c.kh, c.kw, c.sh, c.sw, c.ph, c.pw, 0)
     pavg = mb.merit_plan_pool2d(c.N, c.C, c.H, c.W, c.kh, c.kw, c.sh, c.sw, c.ph, c.pw, 1)
 
+    # arguments marshalled once per buffer set; a call is then one C entry-point invocation
+    cmax = [mb.bind_pool2d(pmax, xs[i], ys[i]) for i in range(nsets)]
+    cavg = [mb.bind_pool2d(pavg, xs[i], ys[i]) for i in range(nsets)]
+
     def step(i):
-        a = (2 * i) % nsets
-        b = (2 * i + 1) % nsets
-        mb.merit_pool2d(pmax, xs[a], ys[a])
-        mb.merit_pool2d(pavg, xs[b], ys[b])
+        cmax[(2 * i) % nsets]()
+        cavg[(2 * i + 1) % nsets]()
 
     wall, ev_ms = timed_region(torch, step, steps, warmup)
     out_elems = c.N * c.C * c.OH * c.OW
@@ -83,8 +88,8 @@ def bench_pool(torch, mb, wl, steps, warmup, nsets):
     launches = 2 * steps
     avg_launch_s = ev_ms * 1e-3 / launches
     # cache-warm figure for context: same buffers every launch
-    wall_w, ev_w = timed_region(torch, lambda i: (mb.merit_pool2d(pmax, xs[0], ys[0]),
-                                                  mb.merit_pool2d(pavg, xs[0], ys[1])), steps, warmup)
+    wmax, wavg = mb.bind_pool2d(pmax, xs[0], ys[0]), mb.bind_pool2d(pavg, xs[0], ys[1])
+    wall_w, ev_w = timed_region(torch, lambda i: (wmax(), wavg()), steps, warmup)
     return {
         "wall_s": wall, "event_ms": ev_ms, "out_elems_per_step": 2 * out_elems,
         "alg_bytes_per_launch": alg_bytes, "avg_launch_us": avg_launch_s * 1e6,
@@ -101,7 +106,8 @@ def bench_sad(torch, mb, wl, cfg, steps, warmup):
     nby, nbx = plan.out_shape()
     sad = torch.empty((nby, nbx), dtype=torch.int32, device="cuda:0")
     mv = torch.empty((nby, nbx, 2), dtype=torch.int32, device="cuda:0")
-    wall, ev_ms = timed_region(torch, lambda i: mb.merit_sad_search(plan, dcur, dref, sad, mv), steps, warmup)
+    call = mb.bind_sad_search(plan, dcur, dref, sad, mv)
+    wall, ev_ms = timed_region(torch, lambda i: call(), steps, warmup)
     t = ev_ms * 1e-3 / steps
     alg_bytes = 2 * cfg.H * cfg.W + nby * nbx * 12
     absdiffs = nby * nbx * cfg.n_candidates * cfg.block * cfg.block
@@ -126,7 +132,8 @@ def bench_conv(torch, mb, wl, cfg, steps, warmup, nsets):
     xs = [x0] + [x0.roll(i, dims=0).contiguous() for i in range(1, ns)]
     ys = [torch.empty((cfg.N, cfg.Cout, cfg.OH, cfg.OW), dtype=torch.float16, device="cuda:0") for _ in range(ns)]
     plan = mb.merit_plan_conv2d(cfg.N, cfg.Cin, cfg.H, cfg.W, cfg.Cout, cfg.kh, cfg.kw, cfg.sh, cfg.sw, cfg.ph, cfg.pw)
-    wall, ev_ms = timed_region(torch, lambda i: mb.merit_conv2d(plan, xs[i % ns], dw, ys[i % ns]), steps, warmup)
+    calls = [mb.bind_conv2d(plan, xs[i], dw, ys[i]) for i in range(ns)]
+    wall, ev_ms = timed_region(torch, lambda i: calls[i % ns](), steps, warmup)
     t = ev_ms * 1e-3 / steps
     flops = 2.0 * cfg.N * cfg.Cout * cfg.OH * cfg.OW * cfg.Cin * cfg.kh * cfg.kw
     return {
@@ -174,6 +181,18 @@ def main():
     from paper_1911_03458_amd import workloads as wl
     mb.lib()
     torch.cuda.set_device(0)
+
+    if args.copy_calibration:
+        # one elementwise copy kernel per iteration: reads 256 MiB and writes 256 MiB
+        src = torch.empty(64 << 20, dtype=torch.float32, device="cuda:0").normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4,
+                          "launches": 10}))
+        return
 
     pool = bench_pool(torch, mb, wl, args.steps, args.warmup, args.sets)
     value = pool["out_elems_per_step"] * args.steps / pool["wall_s"]

@@ -256,3 +256,50 @@ def merit_sad_search(plan: Plan, cur, ref, sad=None, mv=None, stream=None):
                                   _dev_ptr(sad, torch.int32, "sad"), _dev_ptr(mv, torch.int32, "mv"),
                                   _stream(stream)), "merit_sad_search")
     return sad, mv
+
+
+# --------------------------------------------------------------------------
+# pre-marshalled calls: validate tensors once, then re-issue the same C call
+# with raw pointers (for tight loops where ~10 us of Python checks per call
+# would exceed the kernel's own duration)
+# --------------------------------------------------------------------------
+class BoundCall:
+    """The C entry point plus its marshalled arguments; calling it enqueues one launch."""
+
+    def __init__(self, fn, name, args, keep):
+        self._fn, self._name, self._args, self._keep = fn, name, args, keep
+
+    def __call__(self):
+        st = self._fn(*self._args)
+        if st != MERIT_OK:
+            raise MeritError(st, self._name)
+
+
+def bind_conv2d(plan: Plan, x, w, y, stream=None) -> BoundCall:
+    import torch
+    out_shape, a_shape, b_shape = plan.shapes()
+    if tuple(y.shape) != out_shape or tuple(x.shape) != a_shape or tuple(w.shape) != b_shape:
+        raise ValueError("tensors do not match the plan")
+    args = (plan.handle, _dev_ptr(x, torch.float16, "x"), _dev_ptr(w, torch.float16, "w"),
+            _dev_ptr(y, torch.float16, "y"), _stream(stream))
+    return BoundCall(lib().merit_conv2d, "merit_conv2d", args, (plan, x, w, y))
+
+
+def bind_pool2d(plan: Plan, x, y, stream=None) -> BoundCall:
+    import torch
+    out_shape, a_shape, _ = plan.shapes()
+    if tuple(y.shape) != out_shape or tuple(x.shape) != a_shape:
+        raise ValueError("tensors do not match the plan")
+    args = (plan.handle, _dev_ptr(x, torch.float32, "x"), _dev_ptr(y, torch.float32, "y"), _stream(stream))
+    return BoundCall(lib().merit_pool2d, "merit_pool2d", args, (plan, x, y))
+
+
+def bind_sad_search(plan: Plan, cur, ref, sad, mv, stream=None) -> BoundCall:
+    import torch
+    (nby, nbx), a_shape, b_shape = plan.shapes()
+    if (tuple(cur.shape) != b_shape or tuple(ref.shape) != a_shape or tuple(sad.shape) != (nby, nbx)
+            or tuple(mv.shape) != (nby, nbx, 2)):
+        raise ValueError("tensors do not match the plan")
+    args = (plan.handle, _dev_ptr(cur, torch.uint8, "cur"), _dev_ptr(ref, torch.uint8, "ref"),
+            _dev_ptr(sad, torch.int32, "sad"), _dev_ptr(mv, torch.int32, "mv"), _stream(stream))
+    return BoundCall(lib().merit_sad_search, "merit_sad_search", args, (plan, cur, ref, sad, mv))

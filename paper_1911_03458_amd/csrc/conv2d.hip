@@ -139,22 +139,42 @@ __global__ __launch_bounds__(256, 2) void merit_conv2d_planar(ConvParams p, cons
 
     // ---- weights, once per workgroup: unit = (local output channel, group) ----
     {
+        // batches of WU units: all global loads of a batch are issued before the first LDS
+        // write, so a batch costs one memory round trip
+        constexpr int WU = 6;
         const int units = CB * 32 * p.G2;
-        for (int u = tid; u < units; u += 256) {
-            const int col = (int)fdiv((uint32_t)u, p.div_g2);
-            const int g = u - col * p.G2;
-            const int co = co_base + col;
-            uint32_t d[4] = {0, 0, 0, 0};
-            if (co < p.Cout && g < p.G) {
-                const uint16_t *src = w + ((size_t)co * p.G + g) * p.kw;
+        for (int u0 = tid; u0 < units; u0 += 256 * WU) {
+            uint16_t hv[WU][8];
+            bool ok[WU];
+#pragma unroll
+            for (int k = 0; k < WU; ++k) {
+                const int u = min(u0 + 256 * k, units - 1);
+                const int col = (int)fdiv((uint32_t)u, p.div_g2);
+                const int g = u - col * p.G2;
+                const int co = co_base + col;
+                ok[k] = co < p.Cout && g < p.G;
+                const uint16_t *src = w + (ok[k] ? ((size_t)co * p.G + g) * p.kw : 0);
+#pragma unroll
+                for (int t = 0; t < 8; ++t) hv[k][t] = (t < p.kw) ? src[t] : (uint16_t)0;
+            }
+#pragma unroll
+            for (int k = 0; k < WU; ++k) {
+                const int u = u0 + 256 * k;
+                if (u >= units) break;
+                const int col = (int)fdiv((uint32_t)u, p.div_g2);
+                const int g = u - col * p.G2;
+                uint32_t d[4] = {0, 0, 0, 0};
 #pragma unroll
                 for (int t = 0; t < 8; ++t)
-                    if (t < p.kw) {
-                        const int s = t + p.front;
-                        d[s >> 1] |= (uint32_t)src[t] << (16 * (s & 1));
-                    }
+                    if (t < p.kw && ok[k]) d[t >> 1] |= (uint32_t)hv[k][t] << (16 * (t & 1));
+                if (p.front) {                             // taps start at slot 1 (kw <= 7)
+                    d[3] = (d[3] << 16) | (d[2] >> 16);
+                    d[2] = (d[2] << 16) | (d[1] >> 16);
+                    d[1] = (d[1] << 16) | (d[0] >> 16);
+                    d[0] = d[0] << 16;
+                }
+                wl[((col >> 5) * p.G2 + g) * 32 + (col & 31)] = make_uint4(d[0], d[1], d[2], d[3]);
             }
-            wl[((col >> 5) * p.G2 + g) * 32 + (col & 31)] = make_uint4(d[0], d[1], d[2], d[3]);
         }
         if (tid < 8) reinterpret_cast<uint32_t *>(xz)[tid] = 0;
         for (int g = tid; g < p.G2; g += 256) {
@@ -186,7 +206,36 @@ __global__ __launch_bounds__(256, 2) void merit_conv2d_planar(ConvParams p, cons
         // ---- stage the input rows [yA, yA+RH) of every channel, 8 halves per unit ----
         const int nu = p.Cin * p.RHa * P8;
         const bool vec_ok = (p.W & 7) == 0;
-        for (int u = tid; u < nu; u += 256) {
+        if (vec_ok) {
+            // W % 8 == 0 and padl == 8: a unit is entirely inside a row or entirely padding.
+            // Batches of XU units, loads first (one memory round trip per batch).
+            constexpr int XU = 5;
+            for (int u0 = tid; u0 < nu; u0 += 256 * XU) {
+                uint4 v[XU];
+                bool inside[XU];
+#pragma unroll
+                for (int k = 0; k < XU; ++k) {
+                    const int u = min(u0 + 256 * k, nu - 1);
+                    const int q = (int)fdiv((uint32_t)u, p.div_pitch8);
+                    const int c8 = u - q * P8;
+                    const int ci = (int)fdiv((uint32_t)q, p.div_rha);
+                    const int r = q - ci * p.RHa;
+                    const int gy = yA + r;
+                    const int xg0 = 8 * c8 - p.padl;
+                    inside[k] = r < RH && gy >= 0 && gy < p.H && xg0 >= 0 && xg0 < p.W;
+                    const uint16_t *src =
+                        inside[k] ? x + (((size_t)n * p.Cin + ci) * p.H + gy) * p.W + xg0 : x;
+                    v[k] = *reinterpret_cast<const uint4 *>(src);
+                }
+#pragma unroll
+                for (int k = 0; k < XU; ++k) {
+                    const int u = u0 + 256 * k;
+                    if (u >= nu) break;
+                    reinterpret_cast<uint4 *>(xl)[u] = inside[k] ? v[k] : make_uint4(0, 0, 0, 0);
+                }
+            }
+        }
+        for (int u = tid; u < (vec_ok ? 0 : nu); u += 256) {
             const int q = (int)fdiv((uint32_t)u, p.div_pitch8);
             const int c8 = u - q * P8;
             const int ci = (int)fdiv((uint32_t)q, p.div_rha);
@@ -282,35 +331,48 @@ __device__ __forceinline__ void stage_weights_chblock_vec(const ConvParams &p, c
 {
     const int half_nchi = p.nchi >> 1;
     const int units = CB * 32 * p.nchi;
-#pragma unroll 2
-    for (int u = t0; u < units; u += nthr) {
-        const int col = u / p.nchi;
-        const int chi = u - col * p.nchi;
-        const int co = co_base + col;
-        const bool ok = (co < p.Cout) && (chi * 8 + 8 <= p.Cin);
-        // branch-free load (a padding unit re-reads unit 0 and is zeroed below)
-        const uint4 *g = reinterpret_cast<const uint4 *>(w + (ok ? ((size_t)co * p.Cin + chi * 8) * T : 0));
-        uint32_t src[4 * T];
+    // batches of WB units: every load of a batch is issued before the first use
+    constexpr int WB = (T >= 8) ? 4 : 8;
+    for (int u0 = t0; u0 < units; u0 += nthr * WB) {
+        uint32_t src[WB][4 * T];
 #pragma unroll
-        for (int i = 0; i < T; ++i) {
-            const uint4 v = g[i];
-            src[4 * i + 0] = ok ? v.x : 0u; src[4 * i + 1] = ok ? v.y : 0u;
-            src[4 * i + 2] = ok ? v.z : 0u; src[4 * i + 3] = ok ? v.w : 0u;
-        }
-        const int hh = chi >= half_nchi ? 1 : 0;
-        const int chip = chi - hh * half_nchi;
-        const int cb = col >> 5, cc = col & 31;
+        for (int k = 0; k < WB; ++k) {
+            const int u = min(u0 + nthr * k, units - 1);
+            const int col = u / p.nchi;
+            const int chi = u - col * p.nchi;
+            const int co = co_base + col;
+            const bool ok = (co < p.Cout) && (chi * 8 + 8 <= p.Cin);
+            // branch-free load (a padding unit re-reads unit 0 and is zeroed)
+            const uint4 *g = reinterpret_cast<const uint4 *>(w + (ok ? ((size_t)co * p.Cin + chi * 8) * T : 0));
 #pragma unroll
-        for (int t = 0; t < T; ++t) {
-            uint32_t d[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int e0 = (2 * q) * T + t, e1 = (2 * q + 1) * T + t;   // halves (c=2q,t), (c=2q+1,t)
-                const uint32_t sel = ((e0 & 1) ? 0x00000302u : 0x00000100u) | ((e1 & 1) ? 0x07060000u : 0x05040000u);
-                d[q] = __builtin_amdgcn_perm(src[e1 >> 1], src[e0 >> 1], sel);
+            for (int i = 0; i < T; ++i) {
+                const uint4 v = g[i];
+                src[k][4 * i + 0] = ok ? v.x : 0u; src[k][4 * i + 1] = ok ? v.y : 0u;
+                src[k][4 * i + 2] = ok ? v.z : 0u; src[k][4 * i + 3] = ok ? v.w : 0u;
             }
-            const int s = chip * T + t;
-            wl[((s * CB + cb) * 2 + hh) * 32 + cc] = make_uint4(d[0], d[1], d[2], d[3]);
+        }
+#pragma unroll
+        for (int k = 0; k < WB; ++k) {
+            const int u = u0 + nthr * k;
+            if (u >= units) break;
+            const int col = u / p.nchi;
+            const int chi = u - col * p.nchi;
+            const int hh = chi >= half_nchi ? 1 : 0;
+            const int chip = chi - hh * half_nchi;
+            const int cb = col >> 5, cc = col & 31;
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                uint32_t d[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int e0 = (2 * q) * T + t, e1 = (2 * q + 1) * T + t;   // halves (c=2q,t), (c=2q+1,t)
+                    const uint32_t sel =
+                        ((e0 & 1) ? 0x00000302u : 0x00000100u) | ((e1 & 1) ? 0x07060000u : 0x05040000u);
+                    d[q] = __builtin_amdgcn_perm(src[k][e1 >> 1], src[k][e0 >> 1], sel);
+                }
+                const int s = chip * T + t;
+                wl[((s * CB + cb) * 2 + hh) * 32 + cc] = make_uint4(d[0], d[1], d[2], d[3]);
+            }
         }
     }
 }
@@ -368,33 +430,47 @@ __device__ __forceinline__ void stage_input_chblock(const ConvParams &p, const u
         const int W8 = p.W >> 3;
         const int nu = p.nchi * p.RHa * W8;
         const size_t chstride = (size_t)p.H * p.W;
-#pragma unroll 2
-        for (int u = t0; u < nu; u += nthr) {
-            const int q = (int)fdiv((uint32_t)u, p.div_w8);
-            const int x8 = u - q * W8;
-            const int chi = (int)fdiv((uint32_t)q, p.div_rha);
-            const int r = q - chi * p.RHa;
-            if (r >= RH) continue;
-            const int gy = yA + r;
-            const bool rowok = gy >= 0 && gy < p.H;
-            const uint16_t *src = x + (((size_t)n * p.Cin + chi * 8) * p.H + (rowok ? gy : 0)) * p.W + 8 * x8;
-            uint32_t v[8][4];
+        // batches of XB units: every load of a batch is issued before the first use
+        constexpr int XB = 3;
+        for (int u0 = t0; u0 < nu; u0 += nthr * XB) {
+            uint32_t v[XB][8][4];
 #pragma unroll
-            for (int c = 0; c < 8; ++c) {
-                const bool ok = rowok && (chi * 8 + c < p.Cin);
-                // branch-free: a padding channel re-reads channel group row 0 and is zeroed
-                const uint4 t4 = *reinterpret_cast<const uint4 *>(ok ? src + c * chstride : x);
-                v[c][0] = ok ? t4.x : 0u; v[c][1] = ok ? t4.y : 0u; v[c][2] = ok ? t4.z : 0u; v[c][3] = ok ? t4.w : 0u;
+            for (int k = 0; k < XB; ++k) {
+                const int u = min(u0 + nthr * k, nu - 1);
+                const int q = (int)fdiv((uint32_t)u, p.div_w8);
+                const int x8 = u - q * W8;
+                const int chi = (int)fdiv((uint32_t)q, p.div_rha);
+                const int r = q - chi * p.RHa;
+                const int gy = yA + r;
+                const bool rowok = r < RH && gy >= 0 && gy < p.H;
+                const uint16_t *src = x + (((size_t)n * p.Cin + chi * 8) * p.H + (rowok ? gy : 0)) * p.W + 8 * x8;
+#pragma unroll
+                for (int c = 0; c < 8; ++c) {
+                    const bool ok = rowok && (chi * 8 + c < p.Cin);
+                    // branch-free: a padding channel or row re-reads the tensor's first bytes and is zeroed
+                    const uint4 t4 = *reinterpret_cast<const uint4 *>(ok ? src + c * chstride : x);
+                    v[k][c][0] = ok ? t4.x : 0u; v[k][c][1] = ok ? t4.y : 0u;
+                    v[k][c][2] = ok ? t4.z : 0u; v[k][c][3] = ok ? t4.w : 0u;
+                }
             }
-            uint4 *dst = xl + (chi * p.RHa + r) * p.pitch + p.padl + 8 * x8;
 #pragma unroll
-            for (int px = 0; px < 8; ++px) {
-                const uint32_t sel = (px & 1) ? 0x07060302u : 0x05040100u;
-                uint32_t d[4];
+            for (int k = 0; k < XB; ++k) {
+                const int u = u0 + nthr * k;
+                if (u >= nu) break;
+                const int q = (int)fdiv((uint32_t)u, p.div_w8);
+                const int x8 = u - q * W8;
+                const int chi = (int)fdiv((uint32_t)q, p.div_rha);
+                const int r = q - chi * p.RHa;
+                uint4 *dst = xl + (chi * p.RHa + r) * p.pitch + p.padl + 8 * x8;
 #pragma unroll
-                for (int qq = 0; qq < 4; ++qq)
-                    d[qq] = __builtin_amdgcn_perm(v[2 * qq + 1][px >> 1], v[2 * qq][px >> 1], sel);
-                dst[px] = make_uint4(d[0], d[1], d[2], d[3]);
+                for (int px = 0; px < 8; ++px) {
+                    const uint32_t sel = (px & 1) ? 0x07060302u : 0x05040100u;
+                    uint32_t d[4];
+#pragma unroll
+                    for (int qq = 0; qq < 4; ++qq)
+                        d[qq] = __builtin_amdgcn_perm(v[k][2 * qq + 1][px >> 1], v[k][2 * qq][px >> 1], sel);
+                    dst[px] = make_uint4(d[0], d[1], d[2], d[3]);
+                }
             }
         }
     } else {
@@ -503,11 +579,14 @@ template <typename K>
 static hipError_t launch(K kernel, const ConvParams &p, const void *x, const void *w, void *y,
                          hipStream_t s, uint32_t gx, size_t lds_bytes)
 {
-    if (lds_bytes > 48 * 1024) {
-        // raise the kernel's dynamic-LDS limit (up to 160 KB per workgroup on gfx950)
+    // raise this kernel instance's dynamic-LDS limit to the 160 KB a gfx950 workgroup may
+    // use; done once per instance (the static lives in this template instantiation)
+    static bool raised = false;
+    if (!raised) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
+        raised = true;
     }
     hipLaunchKernelGGL(kernel, dim3(gx, (uint32_t)p.co_groups), dim3(256), lds_bytes, s, p,
                        reinterpret_cast<const uint16_t *>(x), reinterpret_cast<const uint16_t *>(w),
