@@ -148,7 +148,9 @@ merit_status merit_plan_launch_info(const merit_plan *plan, merit_launch_info *o
  * passes tile sizes next to the ranges (Section VI-A, Listing 3).  Entries <= 0
  * keep the library's choice.  Honoured entries: pooling tile[2] = output rows
  * (and tile[3] = output columns when the generic kernel is used); convolution
- * tile[2]*tile[3] = output pixels per workgroup (128 or 256); block matching
+ * tile[2] = wavefronts per workgroup (4, or 8 for few input channels) and
+ * tile[3] = consecutive output pixels per wavefront (32 or 64; 32 with 8
+ * wavefronts), i.e. tile[2]*tile[3] pixels per workgroup; block matching
  * tile[1] = blocks per workgroup.  On error the plan is unchanged.  Not safe to
  * call while another thread launches with the same plan. */
 merit_status merit_plan_set_tile(merit_plan *plan, const int64_t tile[MERIT_MAX_INDEX]);

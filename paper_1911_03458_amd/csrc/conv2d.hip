@@ -26,6 +26,8 @@
 // along the contiguous pixel axis of NCHW.
 #include "merit_internal.h"
 
+#include <type_traits>
+
 namespace merit {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
@@ -60,11 +62,12 @@ __device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi)
 // The row pitch TM+16 dwords puts the two lane halves (4 channels apart) on
 // disjoint banks.
 // ---------------------------------------------------------------------------
-template <int CB, int PXW>
+template <int CB, int PXW, int NW, bool FULL>
 __device__ __forceinline__ void store_tile(const ConvParams &p, floatx16 (&acc)[CB][PXW], uint32_t *outl,
                                            uint16_t *__restrict__ y, int n, int co_base, int m0, int tid)
 {
-    constexpr int TM = 4 * PXW * 32;
+    constexpr int TM = NW * PXW * 32;
+    constexpr int NT = NW * 64;
     constexpr int OP = TM + 16;
     const int lane = tid & 63, wave = tid >> 6, h = lane >> 5, c32 = lane & 31;
     const int ohw = p.OH * p.OW;
@@ -81,12 +84,15 @@ __device__ __forceinline__ void store_tile(const ConvParams &p, floatx16 (&acc)[
     const bool vec_ok = (ohw & 7) == 0;
     constexpr int UNITS = CB * 16 * (TM / 8);
 #pragma unroll
-    for (int u = tid; u < UNITS; u += 256) {
+    for (int u = tid; u < UNITS; u += NT) {
         const int cp = u / (TM / 8);
         const int px8 = u - cp * (TM / 8);
         const int m = m0 + px8 * 8;
         const int co = co_base + 2 * cp;
-        if (m >= ohw || co >= p.Cout) continue;
+        // FULL: every tile is complete (OH*OW % TM == 0, Cout % (CB*32) == 0, OH*OW % 8 == 0), so
+        // the stores are unconditional and the compiler can count them when it later waits for
+        // loads issued before them
+        if (!FULL && (m >= ohw || co >= p.Cout)) continue;
         const uint4 a = *reinterpret_cast<const uint4 *>(outl + cp * OP + px8 * 8);
         const uint4 b = *reinterpret_cast<const uint4 *>(outl + cp * OP + px8 * 8 + 4);
         uint4 ev, od;
@@ -95,7 +101,10 @@ __device__ __forceinline__ void store_tile(const ConvParams &p, floatx16 (&acc)[
         ev.z = __builtin_amdgcn_perm(b.y, b.x, 0x05040100u); od.z = __builtin_amdgcn_perm(b.y, b.x, 0x07060302u);
         ev.w = __builtin_amdgcn_perm(b.w, b.z, 0x05040100u); od.w = __builtin_amdgcn_perm(b.w, b.z, 0x07060302u);
         uint16_t *y0 = y + ((size_t)n * p.Cout + co) * ohw + m;
-        if (vec_ok) {
+        if (FULL) {
+            *reinterpret_cast<uint4 *>(y0) = ev;
+            *reinterpret_cast<uint4 *>(y0 + ohw) = od;
+        } else if (vec_ok) {
             *reinterpret_cast<uint4 *>(y0) = ev;
             if (co + 1 < p.Cout) *reinterpret_cast<uint4 *>(y0 + ohw) = od;
         } else {
@@ -113,14 +122,14 @@ __device__ __forceinline__ void store_tile(const ConvParams &p, floatx16 (&acc)[
 // ---------------------------------------------------------------------------
 // planar variant
 // LDS: [ weights: CB*G2*32 x 16 B ][ 32 B of zeros ][ input: Cin*RHa*pitch halves ]
-//      [ group offsets: G2 x 4 B, padded to 16 B ][ output staging ]
+//      [ output staging ]
 // A K-group g = (ci, ky) is one window row: its kw taps occupy slots
 // front .. front+kw-1 of an 8-slot fragment (front = 0 or 1 is chosen so that the
 // fragment starts on an even staged column whenever the column stride is even);
 // unused slots are cleared in the data and zero in the weights.
 // ---------------------------------------------------------------------------
-template <int CB, int PXW, bool ALIGNED>
-__global__ __launch_bounds__(256, 2) void merit_conv2d_planar(ConvParams p, const uint16_t *__restrict__ x,
+template <int CB, int PXW, int NW, bool ALIGNED, bool PREFETCH>
+__global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, const uint16_t *__restrict__ x,
                                                              const uint16_t *__restrict__ w,
                                                              uint16_t *__restrict__ y)
 {
@@ -128,9 +137,10 @@ __global__ __launch_bounds__(256, 2) void merit_conv2d_planar(ConvParams p, cons
     uint4 *wl = reinterpret_cast<uint4 *>(smem);
     uint8_t *xz = smem + p.lds_w_bytes;                 // 32 zero bytes, then the tile
     uint8_t *xl = xz + 32;
-    uint32_t *goff = reinterpret_cast<uint32_t *>(xl + p.lds_x_bytes);
     uint32_t *outl = reinterpret_cast<uint32_t *>(smem + p.lds_o_offset);
 
+    constexpr int NT = NW * 64;                          // threads per workgroup
+    constexpr bool FULL = false;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6, h = lane >> 5, c32 = lane & 31;
     const int co_base = blockIdx.y * CB * 32;
@@ -143,12 +153,12 @@ __global__ __launch_bounds__(256, 2) void merit_conv2d_planar(ConvParams p, cons
         // write, so a batch costs one memory round trip
         constexpr int WU = 6;
         const int units = CB * 32 * p.G2;
-        for (int u0 = tid; u0 < units; u0 += 256 * WU) {
+        for (int u0 = tid; u0 < units; u0 += NT * WU) {
             uint16_t hv[WU][8];
             bool ok[WU];
 #pragma unroll
             for (int k = 0; k < WU; ++k) {
-                const int u = min(u0 + 256 * k, units - 1);
+                const int u = min(u0 + NT * k, units - 1);
                 const int col = (int)fdiv((uint32_t)u, p.div_g2);
                 const int g = u - col * p.G2;
                 const int co = co_base + col;
@@ -159,7 +169,7 @@ __global__ __launch_bounds__(256, 2) void merit_conv2d_planar(ConvParams p, cons
             }
 #pragma unroll
             for (int k = 0; k < WU; ++k) {
-                const int u = u0 + 256 * k;
+                const int u = u0 + NT * k;
                 if (u >= units) break;
                 const int col = (int)fdiv((uint32_t)u, p.div_g2);
                 const int g = u - col * p.G2;
@@ -177,11 +187,6 @@ __global__ __launch_bounds__(256, 2) void merit_conv2d_planar(ConvParams p, cons
             }
         }
         if (tid < 8) reinterpret_cast<uint32_t *>(xz)[tid] = 0;
-        for (int g = tid; g < p.G2; g += 256) {
-            const int ci = (int)fdiv((uint32_t)g, p.div_kh);
-            const int ky = g - ci * p.kh;
-            goff[g] = (uint32_t)(((ci * p.RHa + ky) * p.pitch) * 2);
-        }
     }
 
     // masks that clear the slots outside [front, front+kw) of a fragment
@@ -193,72 +198,119 @@ __global__ __launch_bounds__(256, 2) void merit_conv2d_planar(ConvParams p, cons
     }
 
     const int ntiles = p.N * p.tiles_per_image;
-    for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int n = (int)fdiv((uint32_t)tile, p.div_tiles);
-        const int m0 = (tile - n * p.tiles_per_image) * p.TM;
-        const int oyA = (int)fdiv((uint32_t)m0, p.div_ow);
-        const int mlast = min(m0 + p.TM, ohw) - 1;
-        const int oyB = (int)fdiv((uint32_t)mlast, p.div_ow);
-        const int yA = oyA * p.sh - p.ph;
-        const int RH = (oyB - oyA) * p.sh + p.kh;
+    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): give every XCD
+    // a contiguous run of tiles, so that neighbouring tiles, which share halo rows, meet in
+    // one L2.
+    const int nwg = (int)gridDim.x;
+    const int lw = (nwg % 8 == 0) ? (int)(blockIdx.x % 8) * (nwg / 8) + (int)(blockIdx.x / 8) : (int)blockIdx.x;
 
-        __syncthreads();                                  // previous tile fully consumed
-        // ---- stage the input rows [yA, yA+RH) of every channel, 8 halves per unit ----
-        const int nu = p.Cin * p.RHa * P8;
-        const bool vec_ok = (p.W & 7) == 0;
-        if (vec_ok) {
-            // W % 8 == 0 and padl == 8: a unit is entirely inside a row or entirely padding.
-            // Batches of XU units, loads first (one memory round trip per batch).
-            constexpr int XU = 5;
-            for (int u0 = tid; u0 < nu; u0 += 256 * XU) {
-                uint4 v[XU];
-                bool inside[XU];
+    struct Geom {
+        int n, m0, oyA, yA, RH;
+    };
+    auto geom = [&](int tile) {
+        Geom t;
+        t.n = (int)fdiv((uint32_t)tile, p.div_tiles);
+        t.m0 = (tile - t.n * p.tiles_per_image) * p.TM;
+        t.oyA = (int)fdiv((uint32_t)t.m0, p.div_ow);
+        const int mlast = min(t.m0 + p.TM, ohw) - 1;
+        const int oyB = (int)fdiv((uint32_t)mlast, p.div_ow);
+        t.yA = t.oyA * p.sh - p.ph;
+        t.RH = (oyB - t.oyA) * p.sh + p.kh;
+        return t;
+    };
+
+    // Input staging, 8 halves per unit.  With W % 8 == 0 (and padl == 8) a unit is entirely
+    // inside a row or entirely padding, and when one batch of XU units per thread covers the
+    // tile the loads of the NEXT tile are issued before the current tile's results are
+    // stored, so their latency hides behind the epilogue.
+    const int nu = p.Cin * p.RHa * P8;
+    const bool vec_ok = (p.W & 7) == 0;
+    constexpr int XU = 5;
+    constexpr bool prefetchable = PREFETCH;               // host: W % 8 == 0 and nu <= NT * XU
+    uint4 pre[XU];
+    bool pre_in[XU];
+    // unit u = u0 + NT k -> (channel, staged row, column): independent of the tile, so the
+    // prefetch path decomposes once; u_off = (ci*H + r)*W + x relative to row yA of the image
+    int u_off[XU], u_row[XU];
+    bool u_colok[XU];
+    auto decompose = [&](int u0) {
 #pragma unroll
-                for (int k = 0; k < XU; ++k) {
-                    const int u = min(u0 + 256 * k, nu - 1);
-                    const int q = (int)fdiv((uint32_t)u, p.div_pitch8);
-                    const int c8 = u - q * P8;
-                    const int ci = (int)fdiv((uint32_t)q, p.div_rha);
-                    const int r = q - ci * p.RHa;
-                    const int gy = yA + r;
-                    const int xg0 = 8 * c8 - p.padl;
-                    inside[k] = r < RH && gy >= 0 && gy < p.H && xg0 >= 0 && xg0 < p.W;
-                    const uint16_t *src =
-                        inside[k] ? x + (((size_t)n * p.Cin + ci) * p.H + gy) * p.W + xg0 : x;
-                    v[k] = *reinterpret_cast<const uint4 *>(src);
-                }
-#pragma unroll
-                for (int k = 0; k < XU; ++k) {
-                    const int u = u0 + 256 * k;
-                    if (u >= nu) break;
-                    reinterpret_cast<uint4 *>(xl)[u] = inside[k] ? v[k] : make_uint4(0, 0, 0, 0);
-                }
-            }
-        }
-        for (int u = tid; u < (vec_ok ? 0 : nu); u += 256) {
-            const int q = (int)fdiv((uint32_t)u, p.div_pitch8);
-            const int c8 = u - q * P8;
+        for (int k = 0; k < XU; ++k) {
+            const int u = u0 + NT * k;
+            const int uc = min(u, nu - 1);
+            const int q = (int)fdiv((uint32_t)uc, p.div_pitch8);
+            const int c8 = uc - q * P8;
             const int ci = (int)fdiv((uint32_t)q, p.div_rha);
             const int r = q - ci * p.RHa;
-            if (r >= RH) continue;
-            const int gy = yA + r;
             const int xg0 = 8 * c8 - p.padl;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (gy >= 0 && gy < p.H) {
-                const uint16_t *row = x + (((size_t)n * p.Cin + ci) * p.H + gy) * p.W;
-                if (vec_ok && xg0 >= 0 && xg0 + 8 <= p.W) {
-                    v = *reinterpret_cast<const uint4 *>(row + xg0);
-                } else if (xg0 + 8 > 0 && xg0 < p.W) {
-                    uint32_t d[4] = {0, 0, 0, 0};
+            u_row[k] = r;
+            u_colok[k] = u < nu && xg0 >= 0 && xg0 < p.W;
+            u_off[k] = (ci * p.H + r) * p.W + xg0;
+        }
+    };
+    auto issue_loads = [&](const Geom &t) {
+        const uint16_t *img = x + (size_t)t.n * p.Cin * p.H * p.W;
+        const int yaw = t.yA * p.W;
+#pragma unroll
+        for (int k = 0; k < XU; ++k) {
+            const int gy = t.yA + u_row[k];
+            pre_in[k] = u_colok[k] && u_row[k] < t.RH && gy >= 0 && gy < p.H;
+            const int off = pre_in[k] ? u_off[k] + yaw : 0;           // >= 0 whenever it is used
+            pre[k] = *reinterpret_cast<const uint4 *>(img + off);
+        }
+    };
+    auto commit_loads = [&](int u0) {
+#pragma unroll
+        for (int k = 0; k < XU; ++k) {
+            const int u = u0 + NT * k;
+            if (u < nu) reinterpret_cast<uint4 *>(xl)[u] = pre_in[k] ? pre[k] : make_uint4(0, 0, 0, 0);
+        }
+    };
+
+    const uint32_t rowb = (uint32_t)p.pitch * 2u;                 // bytes per staged row
+    const uint32_t chb = (uint32_t)p.RHa * rowb;                  // bytes per staged channel
+    const uint32_t wrapb = chb - (uint32_t)p.kh * rowb;           // row kh of ci -> row 0 of ci+1
+    const bool g_odd = (p.G & 1) != 0;                            // last step: lanes 32-63 have no group
+    // which dwords of a fragment hold slots outside [front, front+kw): 1 = first, 2 = last, 3 = any
+    const int mask_mode = (kmask[0] & kmask[1] & kmask[2] & kmask[3]) == 0xffffffffu ? 0
+                          : ((kmask[1] & kmask[2] & kmask[3]) == 0xffffffffu ? 1
+                          : ((kmask[0] & kmask[1] & kmask[2]) == 0xffffffffu ? 2 : 3));
+
+    // One tile up to (not including) its stores: stage, multiply, and issue the next tile's
+    // input loads.  The caller stores the accumulators afterwards, so that in the steady
+    // state the order of memory operations is  loads(t+1), stores(t), [wait loads(t+1)] ...
+    // and the wait for the loads does not have to wait for the stores behind them.
+    floatx16 acc[CB][PXW];
+    auto tile_body = [&](const Geom &T, const Geom &Tn) {
+        __syncthreads();                                  // previous tile fully consumed
+        if (prefetchable) {
+            commit_loads(tid);
+        } else if (vec_ok) {
+            for (int u0 = tid; u0 < nu; u0 += NT * XU) {
+                decompose(u0);
+                issue_loads(T);
+                commit_loads(u0);
+            }
+        } else {
+            for (int u = tid; u < nu; u += NT) {
+                const int q = (int)fdiv((uint32_t)u, p.div_pitch8);
+                const int c8 = u - q * P8;
+                const int ci = (int)fdiv((uint32_t)q, p.div_rha);
+                const int r = q - ci * p.RHa;
+                if (r >= T.RH) continue;
+                const int gy = T.yA + r;
+                const int xg0 = 8 * c8 - p.padl;
+                uint32_t d[4] = {0, 0, 0, 0};
+                if (gy >= 0 && gy < p.H && xg0 + 8 > 0 && xg0 < p.W) {
+                    const uint16_t *row = x + (((size_t)T.n * p.Cin + ci) * p.H + gy) * p.W;
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
                         const int xg = xg0 + e;
                         if (xg >= 0 && xg < p.W) d[e >> 1] |= (uint32_t)row[xg] << (16 * (e & 1));
                     }
-                    v = make_uint4(d[0], d[1], d[2], d[3]);
                 }
+                reinterpret_cast<uint4 *>(xl)[u] = make_uint4(d[0], d[1], d[2], d[3]);
             }
-            reinterpret_cast<uint4 *>(xl)[u] = v;
         }
         __syncthreads();
 
@@ -266,54 +318,106 @@ __global__ __launch_bounds__(256, 2) void merit_conv2d_planar(ConvParams p, cons
         uint32_t pbase[PXW], shift[PXW];
 #pragma unroll
         for (int pb = 0; pb < PXW; ++pb) {
-            const int m = m0 + (wave * PXW + pb) * 32 + c32;
+            const int m = T.m0 + (wave * PXW + pb) * 32 + c32;
             const int mm = min(m, ohw - 1);
             const int oy = (int)fdiv((uint32_t)mm, p.div_ow);
             const int ox = mm - oy * p.OW;
             const int cs = p.padl - p.pw + ox * p.sw - p.front;       // staged column of slot 0
-            pbase[pb] = (uint32_t)((((oy - oyA) * p.sh) * p.pitch + (cs & ~1)) * 2) + 32u;
+            pbase[pb] = (uint32_t)((((oy - T.oyA) * p.sh) * p.pitch + (cs & ~1)) * 2) + 32u;
             shift[pb] = (uint32_t)(cs & 1) * 16u;
         }
 
-        floatx16 acc[CB][PXW];
+        // K loop.  Step s feeds group 2s to lanes 0-31 and group 2s+1 to lanes 32-63; a group
+        // g = (ci, ky) is one staged row, two rows further per step, so both halves' LDS offsets
+        // are advanced incrementally in scalar registers.  Fragments of step s+1 are fetched
+        // while the MFMAs of step s run; the first step starts from a zero accumulator.
+        uint32_t goff[2] = {0u, (p.kh == 1) ? chb : rowb};            // offsets of groups 0 and 1
+        int gky[2] = {0, (p.kh == 1) ? 0 : 1};
+        auto kloop = [&](auto mm_tag) {
+            constexpr int MM = decltype(mm_tag)::value;
+            auto load_frags = [&](int s, Frag (&a)[CB], Frag (&b)[PXW]) {
+                const uint32_t off = h ? goff[1] : goff[0];
+                const bool dead = g_odd && h && (s == p.S - 1);       // group 2s+1 == G: no such row
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb)
+                for (int cb = 0; cb < CB; ++cb) a[cb].u = wl[cb * p.G2 * 32 + s * 64 + lane];
 #pragma unroll
-            for (int pb = 0; pb < PXW; ++pb)
+                for (int pb = 0; pb < PXW; ++pb) {
+                    // a dead group reads the zero block (its weights are zero too)
+                    const uint32_t addr = dead ? 0u : pbase[pb] + off;
+                    const uint32_t *src = reinterpret_cast<const uint32_t *>(xz + addr);
+                    if (ALIGNED) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[cb][pb][r] = 0.0f;
-
-        for (int s = 0; s < p.S; ++s) {
-            const int g = 2 * s + h;
-            const bool gvalid = g < p.G;
-            const uint32_t go = goff[g];
-            Frag a[CB], b[PXW];
+                        for (int q = 0; q < 4; ++q) b[pb].d[q] = src[q];
+                    } else {
+                        uint32_t d[5];
 #pragma unroll
-            for (int cb = 0; cb < CB; ++cb) a[cb].u = wl[cb * p.G2 * 32 + s * 64 + lane];
+                        for (int q = 0; q < 5; ++q) d[q] = src[q];
 #pragma unroll
-            for (int pb = 0; pb < PXW; ++pb) {
-                // groups past the end read the zero block (their weights are zero too)
-                const uint32_t addr = gvalid ? pbase[pb] + go : 0u;
-                const uint32_t *src = reinterpret_cast<const uint32_t *>(xz + addr);
-                if (ALIGNED) {
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) b[pb].d[q] = src[q] & kmask[q];
-                } else {
-                    uint32_t d[5];
-#pragma unroll
-                    for (int q = 0; q < 5; ++q) d[q] = src[q];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        b[pb].d[q] = __builtin_amdgcn_alignbit(d[q + 1], d[q], shift[pb]) & kmask[q];
+                        for (int q = 0; q < 4; ++q) b[pb].d[q] = __builtin_amdgcn_alignbit(d[q + 1], d[q], shift[pb]);
+                    }
+                    if (MM == 1 || MM == 3) b[pb].d[0] &= kmask[0];
+                    if (MM == 3) { b[pb].d[1] &= kmask[1]; b[pb].d[2] &= kmask[2]; }
+                    if (MM == 2 || MM == 3) b[pb].d[3] &= kmask[3];
                 }
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {                         // both halves: two rows on
+                    gky[e] += 2; goff[e] += 2u * rowb;
+                    if (gky[e] >= p.kh) { gky[e] -= p.kh; goff[e] += wrapb; }
+                    if (gky[e] >= p.kh) { gky[e] -= p.kh; goff[e] += wrapb; }
+                }
+            };
+            auto mfma_all = [&](Frag (&a)[CB], Frag (&b)[PXW]) {
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                    for (int pb = 0; pb < PXW; ++pb) acc[cb][pb] = mfma16(a[cb], b[pb], acc[cb][pb]);
+            };
+            Frag a0[CB], b0[PXW], a1[CB], b1[PXW];
+            load_frags(0, a0, b0);
+            if (p.S > 1) load_frags(1, a1, b1);
+            {
+                floatx16 zero;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) zero[r] = 0.0f;
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                    for (int pb = 0; pb < PXW; ++pb) acc[cb][pb] = mfma16(a0[cb], b0[pb], zero);
             }
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-                for (int pb = 0; pb < PXW; ++pb) acc[cb][pb] = mfma16(a[cb], b[pb], acc[cb][pb]);
-        }
-        store_tile<CB, PXW>(p, acc, outl, y, n, co_base, m0, tid);
+            int s = 1;                                                // a1/b1 hold step s
+            for (; s + 2 <= p.S; s += 2) {
+                load_frags(s + 1, a0, b0);
+                mfma_all(a1, b1);
+                if (s + 2 < p.S) load_frags(s + 2, a1, b1);
+                mfma_all(a0, b0);
+            }
+            if (s < p.S) mfma_all(a1, b1);
+        };
+        if (mask_mode == 0) kloop(std::integral_constant<int, 0>{});
+        else if (mask_mode == 1) kloop(std::integral_constant<int, 1>{});
+        else if (mask_mode == 2) kloop(std::integral_constant<int, 2>{});
+        else kloop(std::integral_constant<int, 3>{});
+
+        // next tile's input loads (unconditionally: the last tile re-loads itself, which keeps
+        // the loaded registers free of copies)
+        if (prefetchable) issue_loads(Tn);
+    };
+
+    int tile = lw;                                        // < ntiles: the grid never exceeds it
+    Geom T = geom(tile);
+    Geom Tn = geom(min(tile + nwg, ntiles - 1));
+    if (prefetchable) {
+        decompose(tid);
+        issue_loads(T);
     }
+    tile_body(T, Tn);
+    for (tile += nwg; tile < ntiles; tile += nwg) {
+        store_tile<CB, PXW, NW, FULL>(p, acc, outl, y, T.n, co_base, T.m0, tid);
+        T = Tn;
+        Tn = geom(min(tile + nwg, ntiles - 1));
+        tile_body(T, Tn);
+    }
+    store_tile<CB, PXW, NW, FULL>(p, acc, outl, y, T.n, co_base, T.m0, tid);
 }
 
 // ---------------------------------------------------------------------------
@@ -570,14 +674,14 @@ __global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const 
                         for (int pb = 0; pb < PXW; ++pb) acc[cb][pb] = mfma16(a[cb], b[pb], acc[cb][pb]);
                 }
             }
-        store_tile<CB, PXW>(p, acc, outl, y, n, co_base, m0, tid);
+        store_tile<CB, PXW, 4, false>(p, acc, outl, y, n, co_base, m0, tid);
     }
 }
 
 // ---------------------------------------------------------------------------
 template <typename K>
 static hipError_t launch(K kernel, const ConvParams &p, const void *x, const void *w, void *y,
-                         hipStream_t s, uint32_t gx, size_t lds_bytes)
+                         hipStream_t s, uint32_t gx, size_t lds_bytes, uint32_t nthreads = 256)
 {
     // raise this kernel instance's dynamic-LDS limit to the 160 KB a gfx950 workgroup may
     // use; done once per instance (the static lives in this template instantiation)
@@ -588,7 +692,7 @@ static hipError_t launch(K kernel, const ConvParams &p, const void *x, const voi
         if (e != hipSuccess) return e;
         raised = true;
     }
-    hipLaunchKernelGGL(kernel, dim3(gx, (uint32_t)p.co_groups), dim3(256), lds_bytes, s, p,
+    hipLaunchKernelGGL(kernel, dim3(gx, (uint32_t)p.co_groups), dim3(nthreads), lds_bytes, s, p,
                        reinterpret_cast<const uint16_t *>(x), reinterpret_cast<const uint16_t *>(w),
                        reinterpret_cast<uint16_t *>(y));
     return hipGetLastError();
@@ -596,7 +700,7 @@ static hipError_t launch(K kernel, const ConvParams &p, const void *x, const voi
 
 size_t conv_lds_bytes(const ConvParams &p)
 {
-    return (size_t)p.lds_o_offset + p.lds_o_bytes;
+    return (size_t)p.lds_total;
 }
 
 // number of compute units of the current device (cached; 256 on MI355X)
@@ -624,16 +728,25 @@ hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, void
     const uint32_t gx = (uint32_t)(ntiles < slots ? ntiles : slots);
     const size_t lds = conv_lds_bytes(p);
     if (p.variant == CONV_PLANAR_SMALLC) {
-        if (p.aligned) {
-            if (p.CB == 2 && p.PXW == 2) return launch(merit_conv2d_planar<2, 2, true>, p, x, w, y, s, gx, lds);
-            if (p.CB == 2 && p.PXW == 1) return launch(merit_conv2d_planar<2, 1, true>, p, x, w, y, s, gx, lds);
-            if (p.CB == 1 && p.PXW == 2) return launch(merit_conv2d_planar<1, 2, true>, p, x, w, y, s, gx, lds);
-            return launch(merit_conv2d_planar<1, 1, true>, p, x, w, y, s, gx, lds);
+        // one batch of 5 staging units per thread covers a tile => next-tile prefetch
+        const int nt = p.NW * 64;
+        const bool pf = (p.W % 8 == 0) && ((int64_t)p.Cin * p.RHa * (p.pitch / 8) <= nt * 5);
+#define MERIT_PLANAR(CBv, PXv, NWv)                                                                        \
+    do {                                                                                                   \
+        if (p.aligned && pf) return launch(merit_conv2d_planar<CBv, PXv, NWv, true, true>, p, x, w, y, s, gx, lds, nt);   \
+        if (p.aligned) return launch(merit_conv2d_planar<CBv, PXv, NWv, true, false>, p, x, w, y, s, gx, lds, nt);        \
+        if (pf) return launch(merit_conv2d_planar<CBv, PXv, NWv, false, true>, p, x, w, y, s, gx, lds, nt);               \
+        return launch(merit_conv2d_planar<CBv, PXv, NWv, false, false>, p, x, w, y, s, gx, lds, nt);                      \
+    } while (0)
+        if (p.NW == 8) {
+            if (p.CB == 2) MERIT_PLANAR(2, 1, 8);
+            MERIT_PLANAR(1, 1, 8);
         }
-        if (p.CB == 2 && p.PXW == 2) return launch(merit_conv2d_planar<2, 2, false>, p, x, w, y, s, gx, lds);
-        if (p.CB == 2 && p.PXW == 1) return launch(merit_conv2d_planar<2, 1, false>, p, x, w, y, s, gx, lds);
-        if (p.CB == 1 && p.PXW == 2) return launch(merit_conv2d_planar<1, 2, false>, p, x, w, y, s, gx, lds);
-        return launch(merit_conv2d_planar<1, 1, false>, p, x, w, y, s, gx, lds);
+        if (p.CB == 2 && p.PXW == 2) MERIT_PLANAR(2, 2, 4);
+        if (p.CB == 2 && p.PXW == 1) MERIT_PLANAR(2, 1, 4);
+        if (p.CB == 1 && p.PXW == 2) MERIT_PLANAR(1, 2, 4);
+        MERIT_PLANAR(1, 1, 4);
+#undef MERIT_PLANAR
     }
     if (p.CB == 2 && p.PXW == 2) return launch(merit_conv2d_chblock<2, 2>, p, x, w, y, s, gx, lds);
     if (p.CB == 2 && p.PXW == 1) return launch(merit_conv2d_chblock<2, 1>, p, x, w, y, s, gx, lds);

@@ -78,6 +78,7 @@ struct ConvParams {
     int variant;
     int TM;                // output pixels (linear, row-major within an image) per workgroup
     int PXW;               // 32-pixel blocks per wave
+    int NW;                // wavefronts per workgroup (4 or 8)
     int CB;                // 32-channel output blocks per workgroup
     int tiles_per_image;
     int co_groups;         // grid.y
@@ -92,6 +93,7 @@ struct ConvParams {
     int lds_x_bytes;       // input region
     int lds_o_offset;      // output staging region: byte offset and size
     int lds_o_bytes;
+    int lds_total;         // LDS per workgroup
     int front;             // planar: slot of tap kx = 0 inside an 8-slot fragment (0 or 1)
     int aligned;           // planar: every fragment starts on an even staged column
     int wg_per_cu;         // resident workgroups per compute unit the launcher sizes the grid for

@@ -282,11 +282,12 @@ merit_status derive_conv(merit_plan *pl)
     p.co_groups = (int)cdiv(ncb, p.CB);
 
     // try both tile sizes for a variant; prefer 256 pixels when the grid stays large
-    auto try_variant = [&](int variant, int pxw) -> bool {
+    auto try_variant = [&](int variant, int pxw, int nw) -> bool {
         ConvParams q = p;
         q.variant = variant;
         q.PXW = pxw;
-        q.TM = 4 * pxw * 32;
+        q.NW = nw;
+        q.TM = nw * pxw * 32;
         q.tiles_per_image = (int)cdiv(ohw, q.TM);
         q.rows_out_max = (int)((q.TM + OW - 2) / OW + 1);
         if (q.rows_out_max > OH) q.rows_out_max = (int)OH;
@@ -316,7 +317,7 @@ merit_status derive_conv(merit_plan *pl)
             q.div_kh = make_fastdiv((uint32_t)kh);
             if (!fastdiv_ok((int64_t)q.CB * 32 * q.G2, q.G2)) return false;
             q.div_g2 = make_fastdiv((uint32_t)q.G2);
-            q.lds_o_offset = (int)round_up((int64_t)q.lds_w_bytes + 32 + q.lds_x_bytes + (int64_t)q.G2 * 4, 16);
+            q.lds_o_offset = (int)round_up((int64_t)q.lds_w_bytes + 32 + q.lds_x_bytes, 16);
         } else {
             q.front = 0; q.aligned = 0;
             q.nchi = (int)(cdiv(Cin, 16) * 2);
@@ -337,10 +338,17 @@ merit_status derive_conv(merit_plan *pl)
             q.lds_o_offset = q.lds_w_bytes + q.lds_x_bytes;
         }
         q.lds_o_bytes = q.CB * 16 * (q.TM + 16) * 4;      // [channel pair][TM + 16] dwords
+        {
+            const int64_t end_x = (int64_t)q.lds_w_bytes + (variant == CONV_PLANAR_SMALLC ? 32 : 0) + q.lds_x_bytes;
+            const int64_t end_o = (int64_t)q.lds_o_offset + q.lds_o_bytes;
+            q.lds_total = (int)round_up(end_x > end_o ? end_x : end_o, 16);
+        }
         q.div_rha = make_fastdiv((uint32_t)q.RHa);
         if ((int64_t)conv_lds_bytes(q) > LDS_LIMIT) return false;
         q.wg_per_cu = (int)(LDS_LIMIT / (int64_t)conv_lds_bytes(q));
-        if (q.wg_per_cu > 2) q.wg_per_cu = 2;             // register budget: two workgroups per CU
+        // register budget: three workgroups (waves per SIMD) for the planar kernel, two otherwise
+        const int reg_cap = variant == CONV_PLANAR_SMALLC ? 3 : 2;
+        if (q.wg_per_cu > reg_cap) q.wg_per_cu = reg_cap;
         if (!fastdiv_ok(ohw, OW) || !fastdiv_ok((int64_t)N * q.tiles_per_image, q.tiles_per_image)) return false;
         q.div_ow = make_fastdiv((uint32_t)OW);
         q.div_tiles = make_fastdiv((uint32_t)q.tiles_per_image);
@@ -348,16 +356,24 @@ merit_status derive_conv(merit_plan *pl)
         return true;
     };
 
-    bool want_big = N * cdiv(ohw, 256) * p.co_groups >= 512;
-    if (pl->tile_req[2] > 0 && pl->tile_req[3] > 0) {
-        const int64_t tm = pl->tile_req[2] * pl->tile_req[3];
-        if (tm != 128 && tm != 256) return MERIT_ERR_UNSUPPORTED;
-        want_big = tm == 256;
-    }
-    const int first = want_big ? 2 : 1, second = want_big ? 1 : 2;
+    // tile = (wavefronts per workgroup) x (pixels per wavefront): 4 x 32, 4 x 64 or, for the
+    // planar kernel, 8 x 32.  256-pixel tiles when that still leaves a large grid.
+    const bool want_big = N * cdiv(ohw, 256) * p.co_groups >= 512;
     bool ok = false;
-    if (Cin < 8) ok = try_variant(CONV_PLANAR_SMALLC, first) || try_variant(CONV_PLANAR_SMALLC, second);
-    if (!ok) ok = try_variant(CONV_CHBLOCK, first) || try_variant(CONV_CHBLOCK, second);
+    if (pl->tile_req[2] > 0 && pl->tile_req[3] > 0) {
+        const int64_t nw = pl->tile_req[2], ppw = pl->tile_req[3];
+        if ((nw != 4 && nw != 8) || (ppw != 32 && ppw != 64) || (nw == 8 && ppw != 32))
+            return MERIT_ERR_UNSUPPORTED;
+        if (Cin < 8) ok = try_variant(CONV_PLANAR_SMALLC, (int)(ppw / 32), (int)nw);
+        if (!ok && nw == 4) ok = try_variant(CONV_CHBLOCK, (int)(ppw / 32), 4);
+    } else {
+        if (Cin < 8)
+            ok = want_big ? (try_variant(CONV_PLANAR_SMALLC, 2, 4) || try_variant(CONV_PLANAR_SMALLC, 1, 4))
+                          : (try_variant(CONV_PLANAR_SMALLC, 1, 4) || try_variant(CONV_PLANAR_SMALLC, 2, 4));
+        if (!ok)
+            ok = want_big ? (try_variant(CONV_CHBLOCK, 2, 4) || try_variant(CONV_CHBLOCK, 1, 4))
+                          : (try_variant(CONV_CHBLOCK, 1, 4) || try_variant(CONV_CHBLOCK, 2, 4));
+    }
     if (!ok) return MERIT_ERR_UNSUPPORTED;
     if ((int64_t)N * p.tiles_per_image >= (1ll << 31)) return MERIT_ERR_UNSUPPORTED;
 
@@ -373,7 +389,7 @@ merit_status derive_conv(merit_plan *pl)
         li.grid[0] = nt < slots ? nt : slots;
     }
     li.grid[1] = p.co_groups; li.grid[2] = 1;
-    li.block[0] = 256; li.block[1] = 1; li.block[2] = 1;
+    li.block[0] = p.NW * 64; li.block[1] = 1; li.block[2] = 1;
     li.lds_bytes = (int64_t)conv_lds_bytes(p);
     li.tile[0] = 1; li.tile[1] = p.CB * 32; li.tile[2] = p.rows_out_max; li.tile[3] = OW;
     li.tile[4] = Cin; li.tile[5] = kh; li.tile[6] = kw;

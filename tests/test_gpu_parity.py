@@ -246,12 +246,20 @@ def test_conv_small(mb, case):
     _conv_check(mb, x, w, (sh, sw), (ph, pw))
 
 
-@pytest.mark.parametrize("tile", [(0, 0, 4, 32), (0, 0, 8, 32)])
+@pytest.mark.parametrize("tile", [(0, 0, 4, 32), (0, 0, 4, 64)])
 def test_conv_tile_override(mb, tile):
     rng = np.random.default_rng(3)
     x = rng.standard_normal((1, 16, 24, 24)).astype(np.float16)
     w = (rng.standard_normal((32, 16, 3, 3)) / 12).astype(np.float16)
     _conv_check(mb, x, w, (1, 1), (1, 1), tile)
+
+
+@pytest.mark.parametrize("tile", [(0, 0, 4, 32), (0, 0, 4, 64), (0, 0, 8, 32)])
+def test_conv_tile_override_few_channels(mb, tile):
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((2, 3, 40, 48)).astype(np.float16)
+    w = (rng.standard_normal((40, 3, 7, 7)) / 12).astype(np.float16)
+    _conv_check(mb, x, w, (2, 2), (3, 3), tile)
 
 
 def test_conv_identity_kernel_is_exact(mb):
