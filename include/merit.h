@@ -149,8 +149,9 @@ merit_status merit_plan_launch_info(const merit_plan *plan, merit_launch_info *o
  * keep the library's choice.  Honoured entries: pooling tile[2] = output rows
  * (and tile[3] = output columns when the generic kernel is used); convolution
  * tile[2] = wavefronts per workgroup (4, or 8 for few input channels) and
- * tile[3] = consecutive output pixels per wavefront (32 or 64; 32 with 8
- * wavefronts), i.e. tile[2]*tile[3] pixels per workgroup; block matching
+ * tile[3] = consecutive output pixels per multiplying wavefront (32 or 64),
+ * where 8 x 64 means 4 multiplying + 4 data-moving wavefronts (256 pixels per
+ * workgroup) and every other pair tile[2]*tile[3] pixels; block matching
  * tile[1] = blocks per workgroup.  On error the plan is unchanged.  Not safe to
  * call while another thread launches with the same plan. */
 merit_status merit_plan_set_tile(merit_plan *plan, const int64_t tile[MERIT_MAX_INDEX]);

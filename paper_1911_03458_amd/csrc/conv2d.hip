@@ -62,15 +62,12 @@ __device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi)
 // The row pitch TM+16 dwords puts the two lane halves (4 channels apart) on
 // disjoint banks.
 // ---------------------------------------------------------------------------
-template <int CB, int PXW, int NW, bool FULL>
-__device__ __forceinline__ void store_tile(const ConvParams &p, floatx16 (&acc)[CB][PXW], uint32_t *outl,
-                                           uint16_t *__restrict__ y, int n, int co_base, int m0, int tid)
+// part 1: accumulators -> LDS staging (channel pairs packed)
+template <int CB, int PXW, int NW>
+__device__ __forceinline__ void tile_to_lds(floatx16 (&acc)[CB][PXW], uint32_t *outl, int wave, int lane)
 {
-    constexpr int TM = NW * PXW * 32;
-    constexpr int NT = NW * 64;
-    constexpr int OP = TM + 16;
-    const int lane = tid & 63, wave = tid >> 6, h = lane >> 5, c32 = lane & 31;
-    const int ohw = p.OH * p.OW;
+    constexpr int OP = NW * PXW * 32 + 16;
+    const int h = lane >> 5, c32 = lane & 31;
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
@@ -80,18 +77,25 @@ __device__ __forceinline__ void store_tile(const ConvParams &p, floatx16 (&acc)[
                 const int cp = cb * 16 + 4 * (r >> 2) + 2 * h + ((r & 3) >> 1);
                 outl[cp * OP + (wave * PXW + pb) * 32 + c32] = pack_f16x2(acc[cb][pb][r], acc[cb][pb][r + 1]);
             }
-    __syncthreads();
+}
+
+// part 2: LDS staging -> global, by the NT threads t = 0 .. NT-1 of the storing group
+template <int CB, int TM, int NT, bool FULL>
+__device__ __forceinline__ void lds_to_global(const ConvParams &p, const uint32_t *outl, uint16_t *__restrict__ y,
+                                              int n, int co_base, int m0, int t)
+{
+    constexpr int OP = TM + 16;
+    const int ohw = p.OH * p.OW;
     const bool vec_ok = (ohw & 7) == 0;
     constexpr int UNITS = CB * 16 * (TM / 8);
 #pragma unroll
-    for (int u = tid; u < UNITS; u += NT) {
+    for (int u = t; u < UNITS; u += NT) {
         const int cp = u / (TM / 8);
         const int px8 = u - cp * (TM / 8);
         const int m = m0 + px8 * 8;
         const int co = co_base + 2 * cp;
         // FULL: every tile is complete (OH*OW % TM == 0, Cout % (CB*32) == 0, OH*OW % 8 == 0), so
-        // the stores are unconditional and the compiler can count them when it later waits for
-        // loads issued before them
+        // the stores are unconditional
         if (!FULL && (m >= ohw || co >= p.Cout)) continue;
         const uint4 a = *reinterpret_cast<const uint4 *>(outl + cp * OP + px8 * 8);
         const uint4 b = *reinterpret_cast<const uint4 *>(outl + cp * OP + px8 * 8 + 4);
@@ -117,6 +121,15 @@ __device__ __forceinline__ void store_tile(const ConvParams &p, floatx16 (&acc)[
             }
         }
     }
+}
+
+template <int CB, int PXW, int NW, bool FULL>
+__device__ __forceinline__ void store_tile(const ConvParams &p, floatx16 (&acc)[CB][PXW], uint32_t *outl,
+                                           uint16_t *__restrict__ y, int n, int co_base, int m0, int tid)
+{
+    tile_to_lds<CB, PXW, NW>(acc, outl, tid >> 6, tid & 63);
+    __syncthreads();
+    lds_to_global<CB, NW * PXW * 32, NW * 64, FULL>(p, outl, y, n, co_base, m0, tid);
 }
 
 // ---------------------------------------------------------------------------
@@ -418,6 +431,270 @@ __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, 
         tile_body(T, Tn);
     }
     store_tile<CB, PXW, NW, FULL>(p, acc, outl, y, T.n, co_base, T.m0, tid);
+}
+
+// ---------------------------------------------------------------------------
+// planar variant, wave-specialised (8 wavefronts per workgroup, one workgroup per CU)
+// LDS: [ weights ][ 32 B zeros ][ input tile A ][ input tile B ][ out staging A ][ out staging B ]
+//
+// Wavefronts 0-3 only multiply: K loop of tile i out of input buffer i%2, then the packed
+// results into out staging i%2.  They never touch global memory.
+// Wavefronts 4-7 only move data: in iteration i they write the (already loaded) input of
+// tile i+1 into buffer (i+1)%2, issue the global loads of tile i+2, and store the results
+// of tile i-1 from out staging (i-1)%2 to global memory.
+// One barrier per iteration hands the buffers over; memory latency lives in the mover
+// wavefronts and is covered by a whole K loop of the multiplier wavefronts.
+// Needs W % 8 == 0 and at most 5 staging units per mover thread.
+// ---------------------------------------------------------------------------
+template <int CB, bool ALIGNED>
+__global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, const uint16_t *__restrict__ x,
+                                                                const uint16_t *__restrict__ w,
+                                                                uint16_t *__restrict__ y)
+{
+    constexpr int PXW = 2, NWC = 4, TM = NWC * PXW * 32, NTG = 256;    // group = 4 wavefronts
+    extern __shared__ __align__(16) uint8_t smem[];
+    uint4 *wl = reinterpret_cast<uint4 *>(smem);
+    uint8_t *xz = smem + p.lds_w_bytes;                 // 32 zero bytes, then the two tiles
+    const uint32_t xstride = (uint32_t)p.lds_x_bytes;   // multiple of 16
+    uint8_t *outl0 = smem + p.lds_o_offset;
+    const uint32_t ostride = (uint32_t)p.lds_o_bytes;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6, h = lane >> 5, c32 = lane & 31;
+    const bool mover = wave >= NWC;
+    const int t = tid & (NTG - 1);                      // index inside the group
+    const int cwave = wave & (NWC - 1);
+    const int co_base = blockIdx.y * CB * 32;
+    const int P8 = p.pitch >> 3;
+    const int ohw = p.OH * p.OW;
+
+    // ---- weights, once per workgroup (all 512 threads) ----
+    {
+        constexpr int WU = 3;
+        const int units = CB * 32 * p.G2;
+        for (int u0 = tid; u0 < units; u0 += 512 * WU) {
+            uint16_t hv[WU][8];
+            bool ok[WU];
+#pragma unroll
+            for (int k = 0; k < WU; ++k) {
+                const int u = min(u0 + 512 * k, units - 1);
+                const int col = (int)fdiv((uint32_t)u, p.div_g2);
+                const int g = u - col * p.G2;
+                const int co = co_base + col;
+                ok[k] = co < p.Cout && g < p.G;
+                const uint16_t *src = w + (ok[k] ? ((size_t)co * p.G + g) * p.kw : 0);
+#pragma unroll
+                for (int tt = 0; tt < 8; ++tt) hv[k][tt] = (tt < p.kw) ? src[tt] : (uint16_t)0;
+            }
+#pragma unroll
+            for (int k = 0; k < WU; ++k) {
+                const int u = u0 + 512 * k;
+                if (u >= units) break;
+                const int col = (int)fdiv((uint32_t)u, p.div_g2);
+                const int g = u - col * p.G2;
+                uint32_t d[4] = {0, 0, 0, 0};
+#pragma unroll
+                for (int tt = 0; tt < 8; ++tt)
+                    if (tt < p.kw && ok[k]) d[tt >> 1] |= (uint32_t)hv[k][tt] << (16 * (tt & 1));
+                if (p.front) {                             // taps start at slot 1 (kw <= 7)
+                    d[3] = (d[3] << 16) | (d[2] >> 16);
+                    d[2] = (d[2] << 16) | (d[1] >> 16);
+                    d[1] = (d[1] << 16) | (d[0] >> 16);
+                    d[0] = d[0] << 16;
+                }
+                wl[((col >> 5) * p.G2 + g) * 32 + (col & 31)] = make_uint4(d[0], d[1], d[2], d[3]);
+            }
+        }
+        if (tid < 8) reinterpret_cast<uint32_t *>(xz)[tid] = 0;
+    }
+
+    uint32_t kmask[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int s0 = 2 * q - p.front, s1 = 2 * q + 1 - p.front;
+        kmask[q] = ((s0 >= 0 && s0 < p.kw) ? 0x0000ffffu : 0u) | ((s1 >= 0 && s1 < p.kw) ? 0xffff0000u : 0u);
+    }
+
+    const int ntiles = p.N * p.tiles_per_image;
+    const int nwg = (int)gridDim.x;
+    const int lw = (nwg % 8 == 0) ? (int)(blockIdx.x % 8) * (nwg / 8) + (int)(blockIdx.x / 8) : (int)blockIdx.x;
+    const int K = (ntiles - lw + nwg - 1) / nwg;          // tiles of this workgroup (>= 1)
+
+    struct Geom {
+        int n, m0, oyA, yA, RH;
+    };
+    auto geom = [&](int i) {                              // i-th tile of this workgroup, clamped
+        const int tile = lw + min(i, K - 1) * nwg;
+        Geom g;
+        g.n = (int)fdiv((uint32_t)tile, p.div_tiles);
+        g.m0 = (tile - g.n * p.tiles_per_image) * p.TM;
+        g.oyA = (int)fdiv((uint32_t)g.m0, p.div_ow);
+        const int mlast = min(g.m0 + p.TM, ohw) - 1;
+        const int oyB = (int)fdiv((uint32_t)mlast, p.div_ow);
+        g.yA = g.oyA * p.sh - p.ph;
+        g.RH = (oyB - g.oyA) * p.sh + p.kh;
+        return g;
+    };
+
+    // ---- mover state: staging units of this thread (tile-independent decomposition) ----
+    const int nu = p.Cin * p.RHa * P8;
+    constexpr int XU = 5;
+    uint4 pre[XU];
+    bool pre_in[XU];
+    int u_off[XU], u_row[XU];
+    bool u_colok[XU];
+#pragma unroll
+    for (int k = 0; k < XU; ++k) {
+        const int u = t + NTG * k;
+        const int uc = min(u, nu - 1);
+        const int q = (int)fdiv((uint32_t)uc, p.div_pitch8);
+        const int c8 = uc - q * P8;
+        const int ci = (int)fdiv((uint32_t)q, p.div_rha);
+        const int r = q - ci * p.RHa;
+        const int xg0 = 8 * c8 - p.padl;
+        u_row[k] = r;
+        u_colok[k] = u < nu && xg0 >= 0 && xg0 < p.W;
+        u_off[k] = (ci * p.H + r) * p.W + xg0;
+    }
+    auto issue_loads = [&](const Geom &g) {
+        const uint16_t *img = x + (size_t)g.n * p.Cin * p.H * p.W;
+        const int yaw = g.yA * p.W;
+#pragma unroll
+        for (int k = 0; k < XU; ++k) {
+            const int gy = g.yA + u_row[k];
+            pre_in[k] = u_colok[k] && u_row[k] < g.RH && gy >= 0 && gy < p.H;
+            const int off = pre_in[k] ? u_off[k] + yaw : 0;
+            pre[k] = *reinterpret_cast<const uint4 *>(img + off);
+        }
+    };
+    auto commit_loads = [&](uint8_t *xl) {
+#pragma unroll
+        for (int k = 0; k < XU; ++k) {
+            const int u = t + NTG * k;
+            if (u < nu) reinterpret_cast<uint4 *>(xl)[u] = pre_in[k] ? pre[k] : make_uint4(0, 0, 0, 0);
+        }
+    };
+
+    const uint32_t rowb = (uint32_t)p.pitch * 2u;
+    const uint32_t chb = (uint32_t)p.RHa * rowb;
+    const uint32_t wrapb = chb - (uint32_t)p.kh * rowb;
+    const bool g_odd = (p.G & 1) != 0;
+    const int mask_mode = (kmask[0] & kmask[1] & kmask[2] & kmask[3]) == 0xffffffffu ? 0
+                          : ((kmask[1] & kmask[2] & kmask[3]) == 0xffffffffu ? 1
+                          : ((kmask[0] & kmask[1] & kmask[2]) == 0xffffffffu ? 2 : 3));
+
+    // ---- multiplier work for one tile: K loop out of input buffer `buf`, results to `outl` ----
+    auto multiply = [&](const Geom &T, uint32_t buf, uint32_t *outl) {
+        uint32_t pbase[PXW], shift[PXW];
+#pragma unroll
+        for (int pb = 0; pb < PXW; ++pb) {
+            const int m = T.m0 + (cwave * PXW + pb) * 32 + c32;
+            const int mm = min(m, ohw - 1);
+            const int oy = (int)fdiv((uint32_t)mm, p.div_ow);
+            const int ox = mm - oy * p.OW;
+            const int cs = p.padl - p.pw + ox * p.sw - p.front;
+            pbase[pb] = (uint32_t)((((oy - T.oyA) * p.sh) * p.pitch + (cs & ~1)) * 2) + 32u + buf * xstride;
+            shift[pb] = (uint32_t)(cs & 1) * 16u;
+        }
+        floatx16 acc[CB][PXW];
+        uint32_t goff[2] = {0u, (p.kh == 1) ? chb : rowb};
+        int gky[2] = {0, (p.kh == 1) ? 0 : 1};
+        auto kloop = [&](auto mm_tag) {
+            constexpr int MM = decltype(mm_tag)::value;
+            auto load_frags = [&](int s, Frag (&a)[CB], Frag (&b)[PXW]) {
+                const uint32_t off = h ? goff[1] : goff[0];
+                const bool dead = g_odd && h && (s == p.S - 1);
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) a[cb].u = wl[cb * p.G2 * 32 + s * 64 + lane];
+#pragma unroll
+                for (int pb = 0; pb < PXW; ++pb) {
+                    const uint32_t addr = dead ? 0u : pbase[pb] + off;
+                    const uint32_t *src = reinterpret_cast<const uint32_t *>(xz + addr);
+                    if (ALIGNED) {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) b[pb].d[q] = src[q];
+                    } else {
+                        uint32_t d[5];
+#pragma unroll
+                        for (int q = 0; q < 5; ++q) d[q] = src[q];
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) b[pb].d[q] = __builtin_amdgcn_alignbit(d[q + 1], d[q], shift[pb]);
+                    }
+                    if (MM == 1 || MM == 3) b[pb].d[0] &= kmask[0];
+                    if (MM == 3) { b[pb].d[1] &= kmask[1]; b[pb].d[2] &= kmask[2]; }
+                    if (MM == 2 || MM == 3) b[pb].d[3] &= kmask[3];
+                }
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    gky[e] += 2; goff[e] += 2u * rowb;
+                    if (gky[e] >= p.kh) { gky[e] -= p.kh; goff[e] += wrapb; }
+                    if (gky[e] >= p.kh) { gky[e] -= p.kh; goff[e] += wrapb; }
+                }
+            };
+            auto mfma_all = [&](Frag (&a)[CB], Frag (&b)[PXW]) {
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                    for (int pb = 0; pb < PXW; ++pb) acc[cb][pb] = mfma16(a[cb], b[pb], acc[cb][pb]);
+            };
+            // three fragment buffers: step s multiplies buffer s % 3 while the LDS reads of
+            // steps s+1 and s+2 are in flight (a lone wavefront per SIMD has nothing else to
+            // cover the LDS latency with)
+            Frag a0[CB], b0[PXW], a1[CB], b1[PXW], a2[CB], b2[PXW];
+            floatx16 zero;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) zero[r] = 0.0f;
+            load_frags(0, a0, b0);
+            if (p.S > 1) load_frags(1, a1, b1);
+            if (p.S > 2) load_frags(2, a2, b2);
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int pb = 0; pb < PXW; ++pb) acc[cb][pb] = mfma16(a0[cb], b0[pb], zero);
+            int s = 1;                                                // a1 holds step s, a2 step s+1
+            for (; s + 3 <= p.S; s += 3) {
+                load_frags(s + 2, a0, b0);
+                mfma_all(a1, b1);
+                if (s + 3 < p.S) load_frags(s + 3, a1, b1);
+                mfma_all(a2, b2);
+                if (s + 4 < p.S) load_frags(s + 4, a2, b2);
+                mfma_all(a0, b0);
+            }
+            if (s < p.S) mfma_all(a1, b1);
+            if (s + 1 < p.S) mfma_all(a2, b2);
+        };
+        if (mask_mode == 0) kloop(std::integral_constant<int, 0>{});
+        else if (mask_mode == 1) kloop(std::integral_constant<int, 1>{});
+        else if (mask_mode == 2) kloop(std::integral_constant<int, 2>{});
+        else kloop(std::integral_constant<int, 3>{});
+        tile_to_lds<CB, PXW, NWC>(acc, outl, cwave, lane);
+    };
+
+    // ---- prologue: input of tile 0 into buffer 0, loads of tile 1 in flight ----
+    if (mover) {
+        issue_loads(geom(0));
+        commit_loads(xz + 32);
+        issue_loads(geom(1));
+    }
+    __syncthreads();
+
+    for (int i = 0; i <= K; ++i) {
+        if (mover) {
+            // order matters: the loads are the last memory operations of an iteration, so the
+            // wait in the next commit covers only them (not the stores), and they have the
+            // whole barrier wait to arrive
+            if (i + 1 < K) commit_loads(xz + 32 + ((i + 1) & 1) * xstride);   // tile i+1, loaded an iteration ago
+            if (i >= 1) {
+                const Geom P = geom(i - 1);
+                lds_to_global<CB, TM, NTG, false>(p, reinterpret_cast<const uint32_t *>(outl0 + ((i - 1) & 1) * ostride),
+                                                  y, P.n, co_base, P.m0, t);
+            }
+            issue_loads(geom(i + 2));                                          // clamped to the last tile
+        } else if (i < K) {
+            multiply(geom(i), (uint32_t)(i & 1), reinterpret_cast<uint32_t *>(outl0 + (i & 1) * ostride));
+        }
+        __syncthreads();
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -727,6 +1004,14 @@ hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, void
     if (slots < 1) slots = 1;
     const uint32_t gx = (uint32_t)(ntiles < slots ? ntiles : slots);
     const size_t lds = conv_lds_bytes(p);
+    if (p.variant == CONV_PLANAR_SMALLC && p.ws) {
+        if (p.CB == 2) {
+            if (p.aligned) return launch(merit_conv2d_planar_ws<2, true>, p, x, w, y, s, gx, lds, 512);
+            return launch(merit_conv2d_planar_ws<2, false>, p, x, w, y, s, gx, lds, 512);
+        }
+        if (p.aligned) return launch(merit_conv2d_planar_ws<1, true>, p, x, w, y, s, gx, lds, 512);
+        return launch(merit_conv2d_planar_ws<1, false>, p, x, w, y, s, gx, lds, 512);
+    }
     if (p.variant == CONV_PLANAR_SMALLC) {
         // one batch of 5 staging units per thread covers a tile => next-tile prefetch
         const int nt = p.NW * 64;
@@ -756,7 +1041,8 @@ hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, void
 
 const char *conv_kernel_name(const ConvParams &p)
 {
-    return p.variant == CONV_PLANAR_SMALLC ? "merit_conv2d_planar" : "merit_conv2d_chblock";
+    if (p.variant == CONV_PLANAR_SMALLC) return p.ws ? "merit_conv2d_planar_ws" : "merit_conv2d_planar";
+    return "merit_conv2d_chblock";
 }
 
 }  // namespace merit

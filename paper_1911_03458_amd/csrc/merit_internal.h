@@ -96,6 +96,7 @@ struct ConvParams {
     int lds_total;         // LDS per workgroup
     int front;             // planar: slot of tap kx = 0 inside an 8-slot fragment (0 or 1)
     int aligned;           // planar: every fragment starts on an even staged column
+    int ws;                // planar: wave-specialised kernel (4 multiplier + 4 mover wavefronts)
     int wg_per_cu;         // resident workgroups per compute unit the launcher sizes the grid for
     FastDiv div_ow;
     FastDiv div_kh;

@@ -282,6 +282,7 @@ merit_status derive_conv(merit_plan *pl)
     p.co_groups = (int)cdiv(ncb, p.CB);
 
     // try both tile sizes for a variant; prefer 256 pixels when the grid stays large
+    bool want_ws = pl->tile_req[2] <= 0;                  // an explicit tile request selects the plain kernels
     auto try_variant = [&](int variant, int pxw, int nw) -> bool {
         ConvParams q = p;
         q.variant = variant;
@@ -344,10 +345,22 @@ merit_status derive_conv(merit_plan *pl)
             q.lds_total = (int)round_up(end_x > end_o ? end_x : end_o, 16);
         }
         q.div_rha = make_fastdiv((uint32_t)q.RHa);
+        // wave-specialised planar kernel: 4 multiplier + 4 mover wavefronts, double-buffered
+        // input tile and output staging, one workgroup per CU
+        q.ws = 0;
+        if (variant == CONV_PLANAR_SMALLC && want_ws && pxw == 2 && nw == 4 && (W % 8) == 0 &&
+            (int64_t)Cin * q.RHa * (q.pitch / 8) <= 256 * 5) {
+            const int64_t o_off = (int64_t)q.lds_w_bytes + 32 + 2 * (int64_t)q.lds_x_bytes;
+            if (o_off + 2 * (int64_t)q.lds_o_bytes <= LDS_LIMIT) {
+                q.ws = 1;
+                q.lds_o_offset = (int)o_off;
+                q.lds_total = (int)(o_off + 2 * (int64_t)q.lds_o_bytes);
+            }
+        }
         if ((int64_t)conv_lds_bytes(q) > LDS_LIMIT) return false;
         q.wg_per_cu = (int)(LDS_LIMIT / (int64_t)conv_lds_bytes(q));
         // register budget: three workgroups (waves per SIMD) for the planar kernel, two otherwise
-        const int reg_cap = variant == CONV_PLANAR_SMALLC ? 3 : 2;
+        const int reg_cap = q.ws ? 1 : (variant == CONV_PLANAR_SMALLC ? 3 : 2);
         if (q.wg_per_cu > reg_cap) q.wg_per_cu = reg_cap;
         if (!fastdiv_ok(ohw, OW) || !fastdiv_ok((int64_t)N * q.tiles_per_image, q.tiles_per_image)) return false;
         q.div_ow = make_fastdiv((uint32_t)OW);
@@ -362,9 +375,13 @@ merit_status derive_conv(merit_plan *pl)
     bool ok = false;
     if (pl->tile_req[2] > 0 && pl->tile_req[3] > 0) {
         const int64_t nw = pl->tile_req[2], ppw = pl->tile_req[3];
-        if ((nw != 4 && nw != 8) || (ppw != 32 && ppw != 64) || (nw == 8 && ppw != 32))
-            return MERIT_ERR_UNSUPPORTED;
-        if (Cin < 8) ok = try_variant(CONV_PLANAR_SMALLC, (int)(ppw / 32), (int)nw);
+        if ((nw != 4 && nw != 8) || (ppw != 32 && ppw != 64)) return MERIT_ERR_UNSUPPORTED;
+        if (nw == 8 && ppw == 64) {
+            // 4 multiplier wavefronts x 64 pixels + 4 mover wavefronts: the wave-specialised kernel
+            want_ws = true;
+            if (Cin < 8) ok = try_variant(CONV_PLANAR_SMALLC, 2, 4) && p.ws;
+            if (!ok) return MERIT_ERR_UNSUPPORTED;
+        } else if (Cin < 8) ok = try_variant(CONV_PLANAR_SMALLC, (int)(ppw / 32), (int)nw);
         if (!ok && nw == 4) ok = try_variant(CONV_CHBLOCK, (int)(ppw / 32), 4);
     } else {
         if (Cin < 8)
@@ -389,7 +406,7 @@ merit_status derive_conv(merit_plan *pl)
         li.grid[0] = nt < slots ? nt : slots;
     }
     li.grid[1] = p.co_groups; li.grid[2] = 1;
-    li.block[0] = p.NW * 64; li.block[1] = 1; li.block[2] = 1;
+    li.block[0] = p.ws ? 512 : p.NW * 64; li.block[1] = 1; li.block[2] = 1;
     li.lds_bytes = (int64_t)conv_lds_bytes(p);
     li.tile[0] = 1; li.tile[1] = p.CB * 32; li.tile[2] = p.rows_out_max; li.tile[3] = OW;
     li.tile[4] = Cin; li.tile[5] = kh; li.tile[6] = kw;

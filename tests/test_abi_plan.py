@@ -164,7 +164,7 @@ def test_null_and_misuse_without_gpu():
 
 
 def test_conv_variant_selection():
-    assert mb.merit_plan_conv2d(32, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3).launch_info()["kernel"] == "merit_conv2d_planar"
+    assert mb.merit_plan_conv2d(32, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3).launch_info()["kernel"].startswith("merit_conv2d_planar")
     assert mb.merit_plan_conv2d(8, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1).launch_info()["kernel"] == "merit_conv2d_chblock"
     li = mb.merit_plan_conv2d(8, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1).launch_info()
     assert li["lds_bytes"] <= 160 * 1024

@@ -254,12 +254,31 @@ def test_conv_tile_override(mb, tile):
     _conv_check(mb, x, w, (1, 1), (1, 1), tile)
 
 
-@pytest.mark.parametrize("tile", [(0, 0, 4, 32), (0, 0, 4, 64), (0, 0, 8, 32)])
+@pytest.mark.parametrize("tile", [(0, 0, 4, 32), (0, 0, 4, 64), (0, 0, 8, 32), (0, 0, 8, 64)])
 def test_conv_tile_override_few_channels(mb, tile):
     rng = np.random.default_rng(5)
     x = rng.standard_normal((2, 3, 40, 48)).astype(np.float16)
     w = (rng.standard_normal((40, 3, 7, 7)) / 12).astype(np.float16)
     _conv_check(mb, x, w, (2, 2), (3, 3), tile)
+
+
+WS_CASES = [
+    # wave-specialised kernel (tile 8 x 64): one tile, several tiles per workgroup, ragged ends
+    (1, 3, 20, 24, 64, 7, 7, 2, 2, 3, 3),
+    (3, 3, 64, 72, 40, 7, 7, 2, 2, 3, 3),
+    (2, 1, 33, 40, 8, 3, 3, 1, 1, 1, 1),
+    (300, 3, 32, 32, 64, 7, 7, 2, 2, 3, 3),    # 300 tiles on 256 workgroups: 1 or 2 tiles each
+    (1, 4, 96, 160, 33, 5, 5, 1, 2, 2, 2),
+]
+
+
+@pytest.mark.parametrize("case", WS_CASES)
+def test_conv_wave_specialised(mb, case):
+    N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw = case
+    rng = np.random.default_rng(abs(hash(case)) % 2 ** 31)
+    x = rng.standard_normal((N, Cin, H, W)).astype(np.float16)
+    w = (rng.standard_normal((Cout, Cin, kh, kw)) / np.sqrt(Cin * kh * kw)).astype(np.float16)
+    _conv_check(mb, x, w, (sh, sw), (ph, pw), (0, 0, 8, 64))
 
 
 def test_conv_identity_kernel_is_exact(mb):
