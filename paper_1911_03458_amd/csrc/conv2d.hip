@@ -34,15 +34,19 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
+typedef uint32_t uint32x4 __attribute__((ext_vector_type(4)));
+
 union Frag {
     uint4 u;
     half8 h;
     uint32_t d[4];
 };
 
-__device__ __forceinline__ floatx16 mfma16(const Frag &a, const Frag &b, floatx16 c)
+// One 32x32x16 step: rows of the result are the 32 pixels of `xin`, columns the 32 output
+// channels of `wgt` (both fragments: lane l holds row/column l%32, k = 8*(l/32) .. +7).
+__device__ __forceinline__ floatx16 mfma16(const Frag &wgt, const Frag &xin, floatx16 c)
 {
-    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a.h, b.h, c, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(xin.h, wgt.h, c, 0, 0, 0);
 }
 
 __device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi)
@@ -54,28 +58,31 @@ __device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi)
 }
 
 // ---------------------------------------------------------------------------
-// Epilogue.  Accumulator register r of lane l holds output channel
-// 8*(r/4) + 4*(l/32) + r%4 (within its 32-channel block) of pixel l%32 (within
-// its 32-pixel block).  Channel pairs (r, r+1) are packed into one dword and
-// written to LDS as outl[channel pair][pixel]; after a barrier every thread
-// reads 8 pixels x 2 channels, splits the pair and stores two 16-byte runs.
-// The row pitch TM+16 dwords puts the two lane halves (4 channels apart) on
-// disjoint banks.
+// Epilogue.  Accumulator register r of lane l holds output channel l%32 (within
+// its 32-channel block) of pixel 8*(r/4) + 4*(l/32) + r%4 (within its 32-pixel
+// block): four consecutive registers are four consecutive pixels of one channel.
+// They are rounded to binary16 and written as 8 bytes to LDS, laid out
+// outl[channel][pixel]; after a barrier every thread reads runs of 8 pixels of
+// one channel and stores them as 16 bytes.  The row pitch of TM/2 + 2 dwords
+// spreads the 32 channels of a write over all banks.
 // ---------------------------------------------------------------------------
-// part 1: accumulators -> LDS staging (channel pairs packed)
+// part 1: accumulators -> LDS staging
 template <int CB, int PXW, int NW>
 __device__ __forceinline__ void tile_to_lds(floatx16 (&acc)[CB][PXW], uint32_t *outl, int wave, int lane)
 {
-    constexpr int OP = NW * PXW * 32 + 16;
+    constexpr int OP = NW * PXW * 16 + 2;
     const int h = lane >> 5, c32 = lane & 31;
+    uint32_t *row = outl + c32 * OP + wave * PXW * 16 + 2 * h;
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
         for (int pb = 0; pb < PXW; ++pb)
 #pragma unroll
-            for (int r = 0; r < 16; r += 2) {
-                const int cp = cb * 16 + 4 * (r >> 2) + 2 * h + ((r & 3) >> 1);
-                outl[cp * OP + (wave * PXW + pb) * 32 + c32] = pack_f16x2(acc[cb][pb][r], acc[cb][pb][r + 1]);
+            for (int q = 0; q < 4; ++q) {
+                uint2 v;
+                v.x = pack_f16x2(acc[cb][pb][4 * q], acc[cb][pb][4 * q + 1]);
+                v.y = pack_f16x2(acc[cb][pb][4 * q + 2], acc[cb][pb][4 * q + 3]);
+                *reinterpret_cast<uint2 *>(row + cb * 32 * OP + pb * 16 + 4 * q) = v;
             }
 }
 
@@ -84,40 +91,30 @@ template <int CB, int TM, int NT, bool FULL>
 __device__ __forceinline__ void lds_to_global(const ConvParams &p, const uint32_t *outl, uint16_t *__restrict__ y,
                                               int n, int co_base, int m0, int t)
 {
-    constexpr int OP = TM + 16;
+    constexpr int OP = TM / 2 + 2;
     const int ohw = p.OH * p.OW;
     const bool vec_ok = (ohw & 7) == 0;
-    constexpr int UNITS = CB * 16 * (TM / 8);
+    constexpr int UNITS = CB * 32 * (TM / 8);
 #pragma unroll
     for (int u = t; u < UNITS; u += NT) {
-        const int cp = u / (TM / 8);
-        const int px8 = u - cp * (TM / 8);
+        const int c = u / (TM / 8);
+        const int px8 = u - c * (TM / 8);
         const int m = m0 + px8 * 8;
-        const int co = co_base + 2 * cp;
-        // FULL: every tile is complete (OH*OW % TM == 0, Cout % (CB*32) == 0, OH*OW % 8 == 0), so
-        // the stores are unconditional
+        const int co = co_base + c;
+        // FULL: every tile is complete (OH*OW % TM == 0, Cout % (CB*32) == 0), so the stores
+        // are unconditional
         if (!FULL && (m >= ohw || co >= p.Cout)) continue;
-        const uint4 a = *reinterpret_cast<const uint4 *>(outl + cp * OP + px8 * 8);
-        const uint4 b = *reinterpret_cast<const uint4 *>(outl + cp * OP + px8 * 8 + 4);
-        uint4 ev, od;
-        ev.x = __builtin_amdgcn_perm(a.y, a.x, 0x05040100u); od.x = __builtin_amdgcn_perm(a.y, a.x, 0x07060302u);
-        ev.y = __builtin_amdgcn_perm(a.w, a.z, 0x05040100u); od.y = __builtin_amdgcn_perm(a.w, a.z, 0x07060302u);
-        ev.z = __builtin_amdgcn_perm(b.y, b.x, 0x05040100u); od.z = __builtin_amdgcn_perm(b.y, b.x, 0x07060302u);
-        ev.w = __builtin_amdgcn_perm(b.w, b.z, 0x05040100u); od.w = __builtin_amdgcn_perm(b.w, b.z, 0x07060302u);
+        const uint2 *src = reinterpret_cast<const uint2 *>(outl + c * OP + px8 * 4);   // 8-byte aligned
+        const uint2 a = src[0], b = src[1];
         uint16_t *y0 = y + ((size_t)n * p.Cout + co) * ohw + m;
-        if (FULL) {
-            *reinterpret_cast<uint4 *>(y0) = ev;
-            *reinterpret_cast<uint4 *>(y0 + ohw) = od;
-        } else if (vec_ok) {
-            *reinterpret_cast<uint4 *>(y0) = ev;
-            if (co + 1 < p.Cout) *reinterpret_cast<uint4 *>(y0 + ohw) = od;
+        if (FULL || vec_ok) {
+            *reinterpret_cast<uint4 *>(y0) = make_uint4(a.x, a.y, b.x, b.y);
         } else {
-            const uint32_t e[4] = {ev.x, ev.y, ev.z, ev.w}, o[4] = {od.x, od.y, od.z, od.w};
+            const uint32_t e[4] = {a.x, a.y, b.x, b.y};
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 if (m + k >= ohw) break;
                 y0[k] = (uint16_t)(e[k >> 1] >> (16 * (k & 1)));
-                if (co + 1 < p.Cout) y0[ohw + k] = (uint16_t)(o[k >> 1] >> (16 * (k & 1)));
             }
         }
     }
@@ -437,16 +434,19 @@ __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, 
 // planar variant, wave-specialised (8 wavefronts per workgroup, one workgroup per CU)
 // LDS: [ weights ][ 32 B zeros ][ input tile A ][ input tile B ][ out staging A ][ out staging B ]
 //
-// Wavefronts 0-3 only multiply: K loop of tile i out of input buffer i%2, then the packed
-// results into out staging i%2.  They never touch global memory.
+// Wavefronts 0-3 only multiply: K loop of tile i out of input buffer i%2, then the rounded
+// results into out staging i%2.  They never touch global memory, and they keep every weight
+// fragment in registers, so the K loop reads only input fragments from LDS.  The K loop is
+// SU steps without a branch (template parameter, S <= SU <= S+2).
 // Wavefronts 4-7 only move data: in iteration i they write the (already loaded) input of
 // tile i+1 into buffer (i+1)%2, issue the global loads of tile i+2, and store the results
 // of tile i-1 from out staging (i-1)%2 to global memory.
 // One barrier per iteration hands the buffers over; memory latency lives in the mover
 // wavefronts and is covered by a whole K loop of the multiplier wavefronts.
-// Needs W % 8 == 0 and at most 5 staging units per mover thread.
+// Needs W % 8 == 0, OH*OW % 8 == 0, tensors below 2 GiB and at most 5 staging units per
+// mover thread.
 // ---------------------------------------------------------------------------
-template <int CB, bool ALIGNED>
+template <int CB, bool ALIGNED, int SU>
 __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, const uint16_t *__restrict__ x,
                                                                 const uint16_t *__restrict__ w,
                                                                 uint16_t *__restrict__ y)
@@ -469,51 +469,68 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
     const int ohw = p.OH * p.OW;
 
     // ---- weights, once per workgroup (all 512 threads) ----
-    {
-        constexpr int WU = 3;
-        const int units = CB * 32 * p.G2;
-        for (int u0 = tid; u0 < units; u0 += 512 * WU) {
-            uint16_t hv[WU][8];
-            bool ok[WU];
-#pragma unroll
-            for (int k = 0; k < WU; ++k) {
-                const int u = min(u0 + 512 * k, units - 1);
-                const int col = (int)fdiv((uint32_t)u, p.div_g2);
-                const int g = u - col * p.G2;
-                const int co = co_base + col;
-                ok[k] = co < p.Cout && g < p.G;
-                const uint16_t *src = w + (ok[k] ? ((size_t)co * p.G + g) * p.kw : 0);
-#pragma unroll
-                for (int tt = 0; tt < 8; ++tt) hv[k][tt] = (tt < p.kw) ? src[tt] : (uint16_t)0;
-            }
-#pragma unroll
-            for (int k = 0; k < WU; ++k) {
-                const int u = u0 + 512 * k;
-                if (u >= units) break;
-                const int col = (int)fdiv((uint32_t)u, p.div_g2);
-                const int g = u - col * p.G2;
-                uint32_t d[4] = {0, 0, 0, 0};
-#pragma unroll
-                for (int tt = 0; tt < 8; ++tt)
-                    if (tt < p.kw && ok[k]) d[tt >> 1] |= (uint32_t)hv[k][tt] << (16 * (tt & 1));
-                if (p.front) {                             // taps start at slot 1 (kw <= 7)
-                    d[3] = (d[3] << 16) | (d[2] >> 16);
-                    d[2] = (d[2] << 16) | (d[1] >> 16);
-                    d[1] = (d[1] << 16) | (d[0] >> 16);
-                    d[0] = d[0] << 16;
-                }
-                wl[((col >> 5) * p.G2 + g) * 32 + (col & 31)] = make_uint4(d[0], d[1], d[2], d[3]);
-            }
-        }
-        if (tid < 8) reinterpret_cast<uint32_t *>(xz)[tid] = 0;
-    }
-
+    // The (CB*32) x G x kw block of this workgroup's output channels is contiguous in global
+    // memory (at most 3 x 512 16-byte vectors): request it before anything else, so that the
+    // first memory round trip of the kernel runs under the index set-up below.  It is parked in
+    // LDS (the out staging area is still free) and rearranged into fragments from there.
+    const int nco = min(CB * 32, p.Cout - co_base);
+    const int wrow = p.G * p.kw;                        // halves per output channel
+    const int wtotal = nco * wrow;
+    const int wvec = wtotal >> 3;
+    constexpr int WV = 3;
+    // co_base % 32 == 0 keeps the block 16-byte aligned; it holds at least one vector
+    const uint4 *wsrc = reinterpret_cast<const uint4 *>(w + (size_t)co_base * wrow);
+    const uint4 wraw0 = wsrc[min(tid, wvec - 1)];
+    const uint4 wraw1 = wsrc[min(tid + 512, wvec - 1)];
+    const uint4 wraw2 = wsrc[min(tid + 1024, wvec - 1)];
+    auto weights_park = [&]() {
+        uint16_t *rawh = reinterpret_cast<uint16_t *>(outl0);
+        if (tid < wvec) reinterpret_cast<uint4 *>(rawh)[tid] = wraw0;
+        if (tid + 512 < wvec) reinterpret_cast<uint4 *>(rawh)[tid + 512] = wraw1;
+        if (tid + 1024 < wvec) reinterpret_cast<uint4 *>(rawh)[tid + 1024] = wraw2;
+        const uint16_t *src = w + (size_t)co_base * wrow;
+        for (int e = (wvec << 3) + tid; e < wtotal; e += 512) rawh[e] = src[e];
+    };
+    // masks that clear the slots outside [front, front+kw) of a fragment
     uint32_t kmask[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int s0 = 2 * q - p.front, s1 = 2 * q + 1 - p.front;
         kmask[q] = ((s0 >= 0 && s0 < p.kw) ? 0x0000ffffu : 0u) | ((s1 >= 0 && s1 < p.kw) ? 0xffff0000u : 0u);
     }
+    auto weights_frag = [&]() {
+        // unit = (local channel, group): its kw taps start at half (col*G + g)*kw of the parked
+        // block and go to slots front .. front+kw-1.  Five dwords around them are read whole
+        // (what lies outside the block is inside LDS and masked) and shifted by one half if needed.
+        const uint32_t *rawd = reinterpret_cast<const uint32_t *>(outl0);
+        const int units = CB * 32 * p.G2;                 // at most 3 per thread
+        uint32_t d[WV][5];
+        uint32_t sh[WV];
+        int dst[WV];
+        bool ok[WV];
+#pragma unroll
+        for (int k = 0; k < WV; ++k) {                     // every LDS read before the first use
+            const int u = min(tid + 512 * k, units - 1);
+            const int col = (int)fdiv((uint32_t)u, p.div_g2);
+            const int g = u - col * p.G2;
+            ok[k] = col < nco && g < p.G;
+            const int start = (ok[k] ? (col * p.G + g) * p.kw : 0) - p.front;     // >= -1
+            dst[k] = ((col >> 5) * p.G2 + g) * 32 + (col & 31);
+            sh[k] = (uint32_t)(start & 1) * 16u;
+            const uint32_t *r = rawd + (start >> 1);
+#pragma unroll
+            for (int q = 0; q < 5; ++q) d[k][q] = r[q];
+        }
+#pragma unroll
+        for (int k = 0; k < WV; ++k) {
+            uint32_t o[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                o[q] = ok[k] ? (__builtin_amdgcn_alignbit(d[k][q + 1], d[k][q], sh[k]) & kmask[q]) : 0u;
+            if (tid + 512 * k < units) wl[dst[k]] = make_uint4(o[0], o[1], o[2], o[3]);
+        }
+        if (tid < 8) reinterpret_cast<uint32_t *>(xz)[tid] = 0;
+    };
 
     const int ntiles = p.N * p.tiles_per_image;
     const int nwg = (int)gridDim.x;
@@ -537,11 +554,18 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
     };
 
     // ---- mover state: staging units of this thread (tile-independent decomposition) ----
+    // Global memory is reached through buffer descriptors: an offset of 2^31 is past the end
+    // of either tensor, so such a load returns zeros and such a store is dropped.  Padding,
+    // halo rows outside the image and partial tiles need no branch and no select on the data.
+    constexpr uint32_t OOB = 0x80000000u;
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(x), 0, (int)((size_t)p.N * p.Cin * p.H * p.W * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t ry =
+        __builtin_amdgcn_make_buffer_rsrc(y, 0, (int)((size_t)p.N * p.Cout * ohw * 2), 0x00020000);
     const int nu = p.Cin * p.RHa * P8;
     constexpr int XU = 5;
-    uint4 pre[XU];
-    bool pre_in[XU];
-    int u_off[XU], u_row[XU];
+    uint32x4 pre[XU];
+    int u_off2[XU], u_row[XU];                            // byte offset in the image at yA = 0; staged row
     bool u_colok[XU];
 #pragma unroll
     for (int k = 0; k < XU; ++k) {
@@ -554,34 +578,72 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
         const int xg0 = 8 * c8 - p.padl;
         u_row[k] = r;
         u_colok[k] = u < nu && xg0 >= 0 && xg0 < p.W;
-        u_off[k] = (ci * p.H + r) * p.W + xg0;
+        u_off2[k] = ((ci * p.H + r) * p.W + xg0) * 2;
     }
     auto issue_loads = [&](const Geom &g) {
-        const uint16_t *img = x + (size_t)g.n * p.Cin * p.H * p.W;
-        const int yaw = g.yA * p.W;
+        const uint32_t soff = (uint32_t)g.n * (uint32_t)(p.Cin * p.H * p.W * 2);
+        const int yaw2 = g.yA * p.W * 2;
 #pragma unroll
         for (int k = 0; k < XU; ++k) {
-            const int gy = g.yA + u_row[k];
-            pre_in[k] = u_colok[k] && u_row[k] < g.RH && gy >= 0 && gy < p.H;
-            const int off = pre_in[k] ? u_off[k] + yaw : 0;
-            pre[k] = *reinterpret_cast<const uint4 *>(img + off);
+            const uint32_t gy = (uint32_t)(g.yA + u_row[k]);
+            const int ok = (int)u_colok[k] & (int)(u_row[k] < g.RH) & (int)(gy < (uint32_t)p.H);
+            const uint32_t voff = ok ? (uint32_t)(u_off2[k] + yaw2) : OOB;
+            pre[k] = __builtin_amdgcn_raw_buffer_load_b128(rx, voff, soff, 0);
         }
     };
     auto commit_loads = [&](uint8_t *xl) {
 #pragma unroll
         for (int k = 0; k < XU; ++k) {
             const int u = t + NTG * k;
-            if (u < nu) reinterpret_cast<uint4 *>(xl)[u] = pre_in[k] ? pre[k] : make_uint4(0, 0, 0, 0);
+            if (u < nu) reinterpret_cast<uint32x4 *>(xl)[u] = pre[k];
+        }
+    };
+    // results: thread t stores 8 pixels of channels t/32 + 8k, k = 0 .. CB*4-1
+    constexpr int OPW = TM / 2 + 2;                       // out staging pitch in dwords
+    const int st_c0 = t >> 5, st_px = (t & 31) * 8;
+    const uint32_t st_voff = (uint32_t)(st_c0 * ohw + st_px) * 2u;
+    const int st_nc = p.Cout - co_base - st_c0;           // channel t/32 + 8k exists iff 8k < st_nc
+    auto store_tile_ws = [&](int i) {
+        const Geom P = geom(i);
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(outl0 + (i & 1) * ostride) + st_c0 * OPW + (t & 31) * 4;
+        const uint32_t soff = (uint32_t)(((size_t)P.n * p.Cout + co_base) * ohw + P.m0) * 2u;
+        const bool mok = P.m0 + st_px < ohw;
+#pragma unroll
+        for (int k = 0; k < CB * 4; ++k) {
+            const uint2 a = *reinterpret_cast<const uint2 *>(src + k * 8 * OPW);
+            const uint2 b = *reinterpret_cast<const uint2 *>(src + k * 8 * OPW + 2);
+            uint32x4 v;
+            v.x = a.x; v.y = a.y; v.z = b.x; v.w = b.y;
+            // The whole offset goes into the vector register and the scalar offset stays 0: for
+            // a 16-byte buffer store WITH a scalar offset register the compiler leaves no gap
+            // before the next instruction that overwrites the data registers, and on this chip
+            // that instruction was seen to win the race (first dword of the run corrupted).
+            const uint32_t voff = (mok && 8 * k < st_nc) ? st_voff + soff + (uint32_t)(k * 8 * ohw * 2) : OOB;
+            __builtin_amdgcn_raw_buffer_store_b128(v, ry, voff, 0, 0);
         }
     };
 
+    // first input tile requested as early as its addresses are known
+    if (mover) issue_loads(geom(0));
+
     const uint32_t rowb = (uint32_t)p.pitch * 2u;
     const uint32_t chb = (uint32_t)p.RHa * rowb;
-    const uint32_t wrapb = chb - (uint32_t)p.kh * rowb;
-    const bool g_odd = (p.G & 1) != 0;
     const int mask_mode = (kmask[0] & kmask[1] & kmask[2] & kmask[3]) == 0xffffffffu ? 0
                           : ((kmask[1] & kmask[2] & kmask[3]) == 0xffffffffu ? 1
                           : ((kmask[0] & kmask[1] & kmask[2]) == 0xffffffffu ? 2 : 3));
+
+    // ---- multiplier state that no tile changes ----
+    // goffv[s]: byte offset, inside a staged tile, of the window row this lane reads in step s
+    // (group 2s + h = (ci, ky)); wreg: every weight fragment of the workgroup's channels, so
+    // that the K loop reads only input fragments from LDS (filled after the first barrier).
+    uint32_t goffv[SU];
+    Frag wreg[SU][CB];
+#pragma unroll
+    for (int s = 0; s < SU; ++s) {
+        const int g = min(2 * s + h, p.G - 1);
+        const int ci = (int)fdiv((uint32_t)g, p.div_kh);
+        goffv[s] = (uint32_t)ci * chb + (uint32_t)(g - ci * p.kh) * rowb;
+    }
 
     // ---- multiplier work for one tile: K loop out of input buffer `buf`, results to `outl` ----
     auto multiply = [&](const Geom &T, uint32_t buf, uint32_t *outl) {
@@ -597,71 +659,60 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
             shift[pb] = (uint32_t)(cs & 1) * 16u;
         }
         floatx16 acc[CB][PXW];
-        uint32_t goff[2] = {0u, (p.kh == 1) ? chb : rowb};
-        int gky[2] = {0, (p.kh == 1) ? 0 : 1};
         auto kloop = [&](auto mm_tag) {
             constexpr int MM = decltype(mm_tag)::value;
-            auto load_frags = [&](int s, Frag (&a)[CB], Frag (&b)[PXW]) {
-                const uint32_t off = h ? goff[1] : goff[0];
-                const bool dead = g_odd && h && (s == p.S - 1);
-#pragma unroll
-                for (int cb = 0; cb < CB; ++cb) a[cb].u = wl[cb * p.G2 * 32 + s * 64 + lane];
+            constexpr int NR = ALIGNED ? 4 : 5;
+            // raw dwords of step s; masks and the odd-column shift are applied right before
+            // the step's MFMAs, so nothing waits for a read that has just been issued
+            auto load_b = [&](int s, uint32_t (&raw)[PXW][NR]) {
 #pragma unroll
                 for (int pb = 0; pb < PXW; ++pb) {
-                    const uint32_t addr = dead ? 0u : pbase[pb] + off;
-                    const uint32_t *src = reinterpret_cast<const uint32_t *>(xz + addr);
-                    if (ALIGNED) {
+                    const uint32_t *src = reinterpret_cast<const uint32_t *>(xz + pbase[pb] + goffv[s]);
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) b[pb].d[q] = src[q];
-                    } else {
-                        uint32_t d[5];
+                    for (int q = 0; q < NR; ++q) raw[pb][q] = src[q];
+                }
+            };
+            auto fix_b = [&](int s, const uint32_t (&raw)[PXW][NR], Frag (&b)[PXW]) {
 #pragma unroll
-                        for (int q = 0; q < 5; ++q) d[q] = src[q];
+                for (int pb = 0; pb < PXW; ++pb) {
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) b[pb].d[q] = __builtin_amdgcn_alignbit(d[q + 1], d[q], shift[pb]);
-                    }
+                    for (int q = 0; q < 4; ++q)
+                        b[pb].d[q] = ALIGNED ? raw[pb][q]
+                                             : __builtin_amdgcn_alignbit(raw[pb][NR - 4 + q], raw[pb][q], shift[pb]);
                     if (MM == 1 || MM == 3) b[pb].d[0] &= kmask[0];
                     if (MM == 3) { b[pb].d[1] &= kmask[1]; b[pb].d[2] &= kmask[2]; }
                     if (MM == 2 || MM == 3) b[pb].d[3] &= kmask[3];
-                }
+                    if (s >= SU - 2) {              // the only steps that can lie past the last group
+                        const bool live = 2 * s + h < p.G;
 #pragma unroll
-                for (int e = 0; e < 2; ++e) {
-                    gky[e] += 2; goff[e] += 2u * rowb;
-                    if (gky[e] >= p.kh) { gky[e] -= p.kh; goff[e] += wrapb; }
-                    if (gky[e] >= p.kh) { gky[e] -= p.kh; goff[e] += wrapb; }
+                        for (int q = 0; q < 4; ++q) b[pb].d[q] = live ? b[pb].d[q] : 0u;
+                    }
                 }
             };
-            auto mfma_all = [&](Frag (&a)[CB], Frag (&b)[PXW]) {
-#pragma unroll
-                for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-                    for (int pb = 0; pb < PXW; ++pb) acc[cb][pb] = mfma16(a[cb], b[pb], acc[cb][pb]);
-            };
-            // three fragment buffers: step s multiplies buffer s % 3 while the LDS reads of
-            // steps s+1 and s+2 are in flight (a lone wavefront per SIMD has nothing else to
-            // cover the LDS latency with)
-            Frag a0[CB], b0[PXW], a1[CB], b1[PXW], a2[CB], b2[PXW];
+            // Exactly SU steps with no branch between them (steps past the last group multiply
+            // zeros), so the LDS reads in flight can be counted: step s multiplies buffer s % 3
+            // while the reads of steps s+1 and s+2 are outstanding.  The scheduling barriers
+            // keep the compiler from sinking the reads back to their first use.
+            uint32_t raw[3][PXW][NR];
             floatx16 zero;
 #pragma unroll
             for (int r = 0; r < 16; ++r) zero[r] = 0.0f;
-            load_frags(0, a0, b0);
-            if (p.S > 1) load_frags(1, a1, b1);
-            if (p.S > 2) load_frags(2, a2, b2);
+            load_b(0, raw[0]);
+            if (SU > 1) load_b(1, raw[1]);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int cb = 0; cb < CB; ++cb)
+            for (int s = 0; s < SU; ++s) {
+                if (s + 2 < SU) load_b(s + 2, raw[(s + 2) % 3]);
+                __builtin_amdgcn_sched_barrier(0);
+                Frag b[PXW];
+                fix_b(s, raw[s % 3], b);
 #pragma unroll
-                for (int pb = 0; pb < PXW; ++pb) acc[cb][pb] = mfma16(a0[cb], b0[pb], zero);
-            int s = 1;                                                // a1 holds step s, a2 step s+1
-            for (; s + 3 <= p.S; s += 3) {
-                load_frags(s + 2, a0, b0);
-                mfma_all(a1, b1);
-                if (s + 3 < p.S) load_frags(s + 3, a1, b1);
-                mfma_all(a2, b2);
-                if (s + 4 < p.S) load_frags(s + 4, a2, b2);
-                mfma_all(a0, b0);
+                for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                    for (int pb = 0; pb < PXW; ++pb)
+                        acc[cb][pb] = mfma16(wreg[s][cb], b[pb], s == 0 ? zero : acc[cb][pb]);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            if (s < p.S) mfma_all(a1, b1);
-            if (s + 1 < p.S) mfma_all(a2, b2);
         };
         if (mask_mode == 0) kloop(std::integral_constant<int, 0>{});
         else if (mask_mode == 1) kloop(std::integral_constant<int, 1>{});
@@ -670,31 +721,46 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
         tile_to_lds<CB, PXW, NWC>(acc, outl, cwave, lane);
     };
 
-    // ---- prologue: input of tile 0 into buffer 0, loads of tile 1 in flight ----
-    if (mover) {
-        issue_loads(geom(0));
-        commit_loads(xz + 32);
-        issue_loads(geom(1));
-    }
+    // ---- common prologue: weights global -> LDS -> fragment layout ----
+    weights_park();
     __syncthreads();
+    weights_frag();
 
-    for (int i = 0; i <= K; ++i) {
-        if (mover) {
-            // order matters: the loads are the last memory operations of an iteration, so the
-            // wait in the next commit covers only them (not the stores), and they have the
-            // whole barrier wait to arrive
-            if (i + 1 < K) commit_loads(xz + 32 + ((i + 1) & 1) * xstride);   // tile i+1, loaded an iteration ago
-            if (i >= 1) {
-                const Geom P = geom(i - 1);
-                lds_to_global<CB, TM, NTG, false>(p, reinterpret_cast<const uint32_t *>(outl0 + ((i - 1) & 1) * ostride),
-                                                  y, P.n, co_base, P.m0, t);
+    if (!mover) {
+        // ---- multiplying wavefronts: barrier b ends "tile b-1 multiplied, tile b staged" ----
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < SU; ++s)
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                const uint4 v = wl[cb * p.G2 * 32 + min(s, p.S - 1) * 64 + lane];
+                wreg[s][cb].u = (s < p.S) ? v : make_uint4(0, 0, 0, 0);
             }
-            issue_loads(geom(i + 2));                                          // clamped to the last tile
-        } else if (i < K) {
+        for (int i = 0; i < K; ++i) {
             multiply(geom(i), (uint32_t)(i & 1), reinterpret_cast<uint32_t *>(outl0 + (i & 1) * ostride));
+            __syncthreads();
         }
+        return;
+    }
+
+    // ---- data-moving wavefronts ----
+    // Per iteration: write the input of tile i+1 (loaded an iteration ago) to its buffer, issue
+    // the loads of tile i+2, store the results of tile i-1.  No memory instruction sits in a
+    // branch, so the wait in front of the next LDS write lets exactly the stores issued after
+    // those loads stay in flight: neither loads nor stores are waited for right after issue.
+    commit_loads(xz + 32);                        // tile 0, requested before the weights
+    issue_loads(geom(1));
+    __syncthreads();
+    commit_loads(xz + 32 + xstride);              // K == 1: a second copy of tile 0, never read
+    issue_loads(geom(2));
+    __syncthreads();
+    for (int i = 1; i < K; ++i) {
+        commit_loads(xz + 32 + ((i + 1) & 1) * xstride);
+        issue_loads(geom(i + 2));                 // clamped to the last tile
+        store_tile_ws(i - 1);
         __syncthreads();
     }
+    store_tile_ws(K - 1);
 }
 
 // ---------------------------------------------------------------------------
@@ -1005,12 +1071,25 @@ hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, void
     const uint32_t gx = (uint32_t)(ntiles < slots ? ntiles : slots);
     const size_t lds = conv_lds_bytes(p);
     if (p.variant == CONV_PLANAR_SMALLC && p.ws) {
-        if (p.CB == 2) {
-            if (p.aligned) return launch(merit_conv2d_planar_ws<2, true>, p, x, w, y, s, gx, lds, 512);
-            return launch(merit_conv2d_planar_ws<2, false>, p, x, w, y, s, gx, lds, 512);
+#define MERIT_PLANAR_WS(CBv, SUv)                                                                          \
+    do {                                                                                                   \
+        if (p.aligned) return launch(merit_conv2d_planar_ws<CBv, true, SUv>, p, x, w, y, s, gx, lds, 512); \
+        return launch(merit_conv2d_planar_ws<CBv, false, SUv>, p, x, w, y, s, gx, lds, 512);               \
+    } while (0)
+        switch (p.CB * 100 + p.su) {
+        case 204: MERIT_PLANAR_WS(2, 4);
+        case 206: MERIT_PLANAR_WS(2, 6);
+        case 208: MERIT_PLANAR_WS(2, 8);
+        case 211: MERIT_PLANAR_WS(2, 11);
+        case 212: MERIT_PLANAR_WS(2, 12);
+        case 104: MERIT_PLANAR_WS(1, 4);
+        case 106: MERIT_PLANAR_WS(1, 6);
+        case 108: MERIT_PLANAR_WS(1, 8);
+        case 111: MERIT_PLANAR_WS(1, 11);
+        case 112: MERIT_PLANAR_WS(1, 12);
+        default: return hipErrorInvalidValue;
         }
-        if (p.aligned) return launch(merit_conv2d_planar_ws<1, true>, p, x, w, y, s, gx, lds, 512);
-        return launch(merit_conv2d_planar_ws<1, false>, p, x, w, y, s, gx, lds, 512);
+#undef MERIT_PLANAR_WS
     }
     if (p.variant == CONV_PLANAR_SMALLC) {
         // one batch of 5 staging units per thread covers a tile => next-tile prefetch

@@ -21,13 +21,14 @@ inline FastDiv make_fastdiv(uint32_t d)
 {
     FastDiv f;
     f.d = d;
-    f.magic = (uint32_t)((0x100000000ull / d) + 1ull);   // d == 1 does not fit: handled in fdiv
+    f.magic = d == 1u ? 0u : (uint32_t)((0x100000000ull / d) + 1ull);   // d == 1 does not fit: see fdiv
     return f;
 }
 #ifdef __HIPCC__
 __device__ __forceinline__ uint32_t fdiv(uint32_t n, FastDiv f)
 {
-    return f.d == 1u ? n : __umulhi(n, f.magic);
+    // d == 1 has magic 0 and adds n instead: a select, no branch
+    return __umulhi(n, f.magic) + (f.d == 1u ? n : 0u);
 }
 #endif
 
@@ -97,6 +98,7 @@ struct ConvParams {
     int front;             // planar: slot of tap kx = 0 inside an 8-slot fragment (0 or 1)
     int aligned;           // planar: every fragment starts on an even staged column
     int ws;                // planar: wave-specialised kernel (4 multiplier + 4 mover wavefronts)
+    int su;                // wave-specialised kernel: unrolled K steps (S <= su <= S+2)
     int wg_per_cu;         // resident workgroups per compute unit the launcher sizes the grid for
     FastDiv div_ow;
     FastDiv div_kh;

@@ -338,7 +338,7 @@ merit_status derive_conv(merit_plan *pl)
             if (!fastdiv_ok((int64_t)q.nchi * q.RHa, q.RHa)) return false;
             q.lds_o_offset = q.lds_w_bytes + q.lds_x_bytes;
         }
-        q.lds_o_bytes = q.CB * 16 * (q.TM + 16) * 4;      // [channel pair][TM + 16] dwords
+        q.lds_o_bytes = q.CB * 32 * (q.TM / 2 + 2) * 4;   // [channel][TM/2 + 2] dwords
         {
             const int64_t end_x = (int64_t)q.lds_w_bytes + (variant == CONV_PLANAR_SMALLC ? 32 : 0) + q.lds_x_bytes;
             const int64_t end_o = (int64_t)q.lds_o_offset + q.lds_o_bytes;
@@ -347,12 +347,19 @@ merit_status derive_conv(merit_plan *pl)
         q.div_rha = make_fastdiv((uint32_t)q.RHa);
         // wave-specialised planar kernel: 4 multiplier + 4 mover wavefronts, double-buffered
         // input tile and output staging, one workgroup per CU
-        q.ws = 0;
+        q.ws = 0; q.su = 0;
+        // (the kernel fetches a channel's weights in 16-byte vectors: at least one per channel)
         if (variant == CONV_PLANAR_SMALLC && want_ws && pxw == 2 && nw == 4 && (W % 8) == 0 &&
-            (int64_t)Cin * q.RHa * (q.pitch / 8) <= 256 * 5) {
+            (int64_t)Cin * q.RHa * (q.pitch / 8) <= 256 * 5 && (int64_t)q.G * kw >= 8 &&
+            (OH * OW) % 8 == 0 && N * Cin * H * W * 2 < (1ll << 31) && N * Cout * OH * OW * 2 < (1ll << 31)) {
+            static const int steps[] = {4, 6, 8, 11, 12};
+            int su = 0;
+            for (int k = 0; k < 5 && !su; ++k)
+                if (q.S <= steps[k] && q.S + 2 >= steps[k]) su = steps[k];
             const int64_t o_off = (int64_t)q.lds_w_bytes + 32 + 2 * (int64_t)q.lds_x_bytes;
-            if (o_off + 2 * (int64_t)q.lds_o_bytes <= LDS_LIMIT) {
+            if (su && o_off + 2 * (int64_t)q.lds_o_bytes <= LDS_LIMIT) {
                 q.ws = 1;
+                q.su = su;
                 q.lds_o_offset = (int)o_off;
                 q.lds_total = (int)(o_off + 2 * (int64_t)q.lds_o_bytes);
             }
