@@ -438,20 +438,20 @@ __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, 
 // results into out staging i%2.  They never touch global memory, and they keep every weight
 // fragment in registers, so the K loop reads only input fragments from LDS.  The K loop is
 // SU steps without a branch (template parameter, S <= SU <= S+2).
-// Wavefronts 4-7 only move data: in iteration i they write the (already loaded) input of
-// tile i+1 into buffer (i+1)%2, issue the global loads of tile i+2, and store the results
-// of tile i-1 from out staging (i-1)%2 to global memory.
+// Wavefronts 4-5 only load: in iteration i they write the (already loaded) input of tile
+// i+1 into buffer (i+1)%2 and issue the global loads of tile i+2.  Wavefronts 6-7 only
+// store: the results of tile i-1 from out staging (i-1)%2 to global memory.
 // One barrier per iteration hands the buffers over; memory latency lives in the mover
 // wavefronts and is covered by a whole K loop of the multiplier wavefronts.
-// Needs W % 8 == 0, OH*OW % 8 == 0, tensors below 2 GiB and at most 5 staging units per
-// mover thread.
+// Needs W % 8 == 0, OH*OW % 8 == 0, tensors below 2 GiB and at most 10 staging units per
+// loading thread.
 // ---------------------------------------------------------------------------
 template <int CB, bool ALIGNED, int SU>
 __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, const uint16_t *__restrict__ x,
                                                                 const uint16_t *__restrict__ w,
                                                                 uint16_t *__restrict__ y)
 {
-    constexpr int PXW = 2, NWC = 4, TM = NWC * PXW * 32, NTG = 256;    // group = 4 wavefronts
+    constexpr int PXW = 2, NWC = 4, TM = NWC * PXW * 32, NTG = 128;    // loading / storing group = 2 wavefronts
     extern __shared__ __align__(16) uint8_t smem[];
     uint4 *wl = reinterpret_cast<uint4 *>(smem);
     uint8_t *xz = smem + p.lds_w_bytes;                 // 32 zero bytes, then the two tiles
@@ -462,7 +462,8 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6, h = lane >> 5, c32 = lane & 31;
     const bool mover = wave >= NWC;
-    const int t = tid & (NTG - 1);                      // index inside the group
+    const bool loader = wave >= NWC && wave < NWC + 2;  // wavefronts 4-5 load, 6-7 store
+    const int t = tid & (NTG - 1);                      // index inside the loading / storing group
     const int cwave = wave & (NWC - 1);
     const int co_base = blockIdx.y * CB * 32;
     const int P8 = p.pitch >> 3;
@@ -563,7 +564,7 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
     const __amdgpu_buffer_rsrc_t ry =
         __builtin_amdgcn_make_buffer_rsrc(y, 0, (int)((size_t)p.N * p.Cout * ohw * 2), 0x00020000);
     const int nu = p.Cin * p.RHa * P8;
-    constexpr int XU = 5;
+    constexpr int XU = 10;
     uint32x4 pre[XU];
     int u_off2[XU], u_row[XU];                            // byte offset in the image at yA = 0; staged row
     bool u_colok[XU];
@@ -598,33 +599,36 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
             if (u < nu) reinterpret_cast<uint32x4 *>(xl)[u] = pre[k];
         }
     };
-    // results: thread t stores 8 pixels of channels t/32 + 8k, k = 0 .. CB*4-1
+    // results: thread t stores 8 pixels of channels t/32 + 4k, k = 0 .. CB*8-1
     constexpr int OPW = TM / 2 + 2;                       // out staging pitch in dwords
     const int st_c0 = t >> 5, st_px = (t & 31) * 8;
     const uint32_t st_voff = (uint32_t)(st_c0 * ohw + st_px) * 2u;
-    const int st_nc = p.Cout - co_base - st_c0;           // channel t/32 + 8k exists iff 8k < st_nc
+    const int st_nc = p.Cout - co_base - st_c0;           // channel t/32 + 4k exists iff 4k < st_nc
     auto store_tile_ws = [&](int i) {
         const Geom P = geom(i);
         const uint32_t *src = reinterpret_cast<const uint32_t *>(outl0 + (i & 1) * ostride) + st_c0 * OPW + (t & 31) * 4;
         const uint32_t soff = (uint32_t)(((size_t)P.n * p.Cout + co_base) * ohw + P.m0) * 2u;
         const bool mok = P.m0 + st_px < ohw;
 #pragma unroll
-        for (int k = 0; k < CB * 4; ++k) {
-            const uint2 a = *reinterpret_cast<const uint2 *>(src + k * 8 * OPW);
-            const uint2 b = *reinterpret_cast<const uint2 *>(src + k * 8 * OPW + 2);
+        for (int k = 0; k < CB * 8; ++k) {
+            const uint2 a = *reinterpret_cast<const uint2 *>(src + k * 4 * OPW);
+            const uint2 b = *reinterpret_cast<const uint2 *>(src + k * 4 * OPW + 2);
             uint32x4 v;
             v.x = a.x; v.y = a.y; v.z = b.x; v.w = b.y;
             // The whole offset goes into the vector register and the scalar offset stays 0: for
             // a 16-byte buffer store WITH a scalar offset register the compiler leaves no gap
             // before the next instruction that overwrites the data registers, and on this chip
             // that instruction was seen to win the race (first dword of the run corrupted).
-            const uint32_t voff = (mok && 8 * k < st_nc) ? st_voff + soff + (uint32_t)(k * 8 * ohw * 2) : OOB;
-            __builtin_amdgcn_raw_buffer_store_b128(v, ry, voff, 0, 0);
+            const uint32_t voff = (mok && 4 * k < st_nc) ? st_voff + soff + (uint32_t)(k * 4 * ohw * 2) : OOB;
+            // cache policy "sc0 nt": results are written once and not read again by this kernel;
+            // streaming them keeps the L2 from collecting dirty lines that the end of the
+            // kernel then has to write back all at once
+            __builtin_amdgcn_raw_buffer_store_b128(v, ry, voff, 0, 3);
         }
     };
 
     // first input tile requested as early as its addresses are known
-    if (mover) issue_loads(geom(0));
+    if (loader) issue_loads(geom(0));
 
     const uint32_t rowb = (uint32_t)p.pitch * 2u;
     const uint32_t chb = (uint32_t)p.RHa * rowb;
@@ -690,27 +694,37 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
                 }
             };
             // Exactly SU steps with no branch between them (steps past the last group multiply
-            // zeros), so the LDS reads in flight can be counted: step s multiplies buffer s % 3
-            // while the reads of steps s+1 and s+2 are outstanding.  The scheduling barriers
-            // keep the compiler from sinking the reads back to their first use.
+            // zeros), so the LDS reads in flight can be counted.  Step s issues the reads of
+            // step s+2, prepares the fragments of step s+1 (read two steps ago) and multiplies
+            // those of step s; the group barriers spread the reads and the vector arithmetic
+            // between the four MFMAs, which each keep the matrix pipe busy for 32 cycles.
             uint32_t raw[3][PXW][NR];
+            Frag bb[2][PXW];
             floatx16 zero;
 #pragma unroll
             for (int r = 0; r < 16; ++r) zero[r] = 0.0f;
             load_b(0, raw[0]);
             if (SU > 1) load_b(1, raw[1]);
+            fix_b(0, raw[0], bb[0]);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int s = 0; s < SU; ++s) {
                 if (s + 2 < SU) load_b(s + 2, raw[(s + 2) % 3]);
-                __builtin_amdgcn_sched_barrier(0);
-                Frag b[PXW];
-                fix_b(s, raw[s % 3], b);
+                if (s + 1 < SU) fix_b(s + 1, raw[(s + 1) % 3], bb[(s + 1) & 1]);
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
                     for (int pb = 0; pb < PXW; ++pb)
-                        acc[cb][pb] = mfma16(wreg[s][cb], b[pb], s == 0 ? zero : acc[cb][pb]);
+                        acc[cb][pb] = mfma16(wreg[s][cb], bb[s & 1][pb], s == 0 ? zero : acc[cb][pb]);
+                // MFMA | address arithmetic + reads | MFMA | reads | MFMA | fragment fix-up | MFMA...
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, PXW * (ALIGNED ? 1 : 2), 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, PXW * (ALIGNED ? 1 : 2), 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 32, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, CB * PXW, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
@@ -744,19 +758,27 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
     }
 
     // ---- data-moving wavefronts ----
-    // Per iteration: write the input of tile i+1 (loaded an iteration ago) to its buffer, issue
-    // the loads of tile i+2, store the results of tile i-1.  No memory instruction sits in a
-    // branch, so the wait in front of the next LDS write lets exactly the stores issued after
-    // those loads stay in flight: neither loads nor stores are waited for right after issue.
-    commit_loads(xz + 32);                        // tile 0, requested before the weights
-    issue_loads(geom(1));
+    // Loading wavefronts, per iteration: write the input of tile i+1 (requested an iteration ago)
+    // to its buffer, request tile i+2.  Storing wavefronts: write the results of tile i-1 to
+    // global memory.  The two kinds have separate memory counters, so a wait for loaded data
+    // never also waits for stores; the storing wavefronts never wait for memory at all.
+    if (loader) {
+        commit_loads(xz + 32);                    // tile 0, requested before the weights
+        issue_loads(geom(1));
+        __syncthreads();
+        commit_loads(xz + 32 + xstride);          // K == 1: a second copy of tile 0, never read
+        issue_loads(geom(2));
+        __syncthreads();
+        for (int i = 1; i < K; ++i) {
+            commit_loads(xz + 32 + ((i + 1) & 1) * xstride);
+            issue_loads(geom(i + 2));             // clamped to the last tile
+            __syncthreads();
+        }
+        return;
+    }
     __syncthreads();
-    commit_loads(xz + 32 + xstride);              // K == 1: a second copy of tile 0, never read
-    issue_loads(geom(2));
     __syncthreads();
     for (int i = 1; i < K; ++i) {
-        commit_loads(xz + 32 + ((i + 1) & 1) * xstride);
-        issue_loads(geom(i + 2));                 // clamped to the last tile
         store_tile_ws(i - 1);
         __syncthreads();
     }

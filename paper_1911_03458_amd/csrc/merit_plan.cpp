@@ -350,7 +350,7 @@ merit_status derive_conv(merit_plan *pl)
         q.ws = 0; q.su = 0;
         // (the kernel fetches a channel's weights in 16-byte vectors: at least one per channel)
         if (variant == CONV_PLANAR_SMALLC && want_ws && pxw == 2 && nw == 4 && (W % 8) == 0 &&
-            (int64_t)Cin * q.RHa * (q.pitch / 8) <= 256 * 5 && (int64_t)q.G * kw >= 8 &&
+            (int64_t)Cin * q.RHa * (q.pitch / 8) <= 128 * 10 && (int64_t)q.G * kw >= 8 &&
             (OH * OW) % 8 == 0 && N * Cin * H * W * 2 < (1ll << 31) && N * Cout * OH * OW * 2 < (1ll << 31)) {
             static const int steps[] = {4, 6, 8, 11, 12};
             int su = 0;
