@@ -108,7 +108,10 @@ __device__ __forceinline__ void lds_to_global(const ConvParams &p, const uint32_
         const uint2 a = src[0], b = src[1];
         uint16_t *y0 = y + ((size_t)n * p.Cout + co) * ohw + m;
         if (FULL || vec_ok) {
-            *reinterpret_cast<uint4 *>(y0) = make_uint4(a.x, a.y, b.x, b.y);
+            // streaming store: written once, not read again here
+            uint32x4 v;
+            v.x = a.x; v.y = a.y; v.z = b.x; v.w = b.y;
+            __builtin_nontemporal_store(v, reinterpret_cast<uint32x4 *>(y0));
         } else {
             const uint32_t e[4] = {a.x, a.y, b.x, b.y};
 #pragma unroll

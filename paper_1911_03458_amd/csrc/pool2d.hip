@@ -12,6 +12,8 @@
 
 namespace merit {
 
+typedef float v4f __attribute__((ext_vector_type(4)));
+
 // ---------------------------------------------------------------------------
 // Generic tile kernel: any window / stride / padding, scalar accesses.
 // ---------------------------------------------------------------------------
@@ -206,7 +208,6 @@ __global__ __launch_bounds__(256) void merit_pool2d_stream_k3s2p1(PoolParams p, 
         if (live && gy >= 0 && gy < p.H) {
             // every input byte is used once: non-temporal loads keep it from displacing
             // useful lines in the caches (measured: ~20 % less time on a cold input)
-            typedef float v4f __attribute__((ext_vector_type(4)));
             const v4f q = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(xp + (size_t)gy * p.W));
             v[r] = make_float4(q.x, q.y, q.z, q.w);
         }
