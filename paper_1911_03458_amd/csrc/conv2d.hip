@@ -455,6 +455,15 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
                                                                 uint16_t *__restrict__ y)
 {
     constexpr int PXW = 2, NWC = 4, TM = NWC * PXW * 32, NTG = 128;    // loading / storing group = 2 wavefronts
+    {
+        // Touch every 64-byte line of the argument block with the first scalar loads, so the
+        // later ones (issued where their values are needed) hit the scalar cache instead of
+        // each paying a trip to memory.
+        typedef const uint32_t __attribute__((address_space(4))) *kernarg_ptr;
+        kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
+        const uint32_t warm = ka[16] ^ ka[32] ^ ka[48];
+        asm volatile("" ::"s"(warm));
+    }
     extern __shared__ __align__(16) uint8_t smem[];
     uint4 *wl = reinterpret_cast<uint4 *>(smem);
     uint8_t *xz = smem + p.lds_w_bytes;                 // 32 zero bytes, then the two tiles
@@ -566,23 +575,30 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
         const_cast<uint16_t *>(x), 0, (int)((size_t)p.N * p.Cin * p.H * p.W * 2), 0x00020000);
     const __amdgpu_buffer_rsrc_t ry =
         __builtin_amdgcn_make_buffer_rsrc(y, 0, (int)((size_t)p.N * p.Cout * ohw * 2), 0x00020000);
-    const int nu = p.Cin * p.RHa * P8;
+    // Loading thread t owns 16-byte column chunk t % 2^lgc of the staged rows
+    // q = t / 2^lgc + (128 >> lgc) k  (q = ci*RHa + r; 2^lgc >= chunks per row), so that a
+    // thread's column tests are shared by all its units and only q needs a division.
     constexpr int XU = 10;
     uint32x4 pre[XU];
-    int u_off2[XU], u_row[XU];                            // byte offset in the image at yA = 0; staged row
-    bool u_colok[XU];
+    int u_off2[XU], u_row[XU], u_lds[XU];                 // byte offset in the image at yA = 0; staged row
+    bool u_live[XU];
+    const int lgc = p.lg_chunks;
+    const int ld_c8 = t & ((1 << lgc) - 1);
+    const int ld_xg0 = 8 * ld_c8 - p.padl;
+    const bool ld_colok = ld_xg0 >= 0 && ld_xg0 < p.W;    // else: padding columns, zero-filled
+    if (loader) {
+        const int nq = p.Cin * p.RHa;
 #pragma unroll
-    for (int k = 0; k < XU; ++k) {
-        const int u = t + NTG * k;
-        const int uc = min(u, nu - 1);
-        const int q = (int)fdiv((uint32_t)uc, p.div_pitch8);
-        const int c8 = uc - q * P8;
-        const int ci = (int)fdiv((uint32_t)q, p.div_rha);
-        const int r = q - ci * p.RHa;
-        const int xg0 = 8 * c8 - p.padl;
-        u_row[k] = r;
-        u_colok[k] = u < nu && xg0 >= 0 && xg0 < p.W;
-        u_off2[k] = ((ci * p.H + r) * p.W + xg0) * 2;
+        for (int k = 0; k < XU; ++k) {
+            const int q = (t >> lgc) + (NTG >> lgc) * k;
+            const int qc = min(q, nq - 1);
+            const int ci = (int)fdiv((uint32_t)qc, p.div_rha);
+            const int r = qc - ci * p.RHa;
+            u_row[k] = r;
+            u_live[k] = q < nq && ld_c8 < P8;
+            u_off2[k] = ((ci * p.H + r) * p.W + ld_xg0) * 2;
+            u_lds[k] = (qc * P8 + min(ld_c8, P8 - 1)) * 16;
+        }
     }
     auto issue_loads = [&](const Geom &g) {
         const uint32_t soff = (uint32_t)g.n * (uint32_t)(p.Cin * p.H * p.W * 2);
@@ -590,17 +606,15 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
 #pragma unroll
         for (int k = 0; k < XU; ++k) {
             const uint32_t gy = (uint32_t)(g.yA + u_row[k]);
-            const int ok = (int)u_colok[k] & (int)(u_row[k] < g.RH) & (int)(gy < (uint32_t)p.H);
+            const int ok = (int)ld_colok & (int)(u_row[k] < g.RH) & (int)(gy < (uint32_t)p.H);
             const uint32_t voff = ok ? (uint32_t)(u_off2[k] + yaw2) : OOB;
             pre[k] = __builtin_amdgcn_raw_buffer_load_b128(rx, voff, soff, 0);
         }
     };
     auto commit_loads = [&](uint8_t *xl) {
 #pragma unroll
-        for (int k = 0; k < XU; ++k) {
-            const int u = t + NTG * k;
-            if (u < nu) reinterpret_cast<uint32x4 *>(xl)[u] = pre[k];
-        }
+        for (int k = 0; k < XU; ++k)
+            if (u_live[k]) *reinterpret_cast<uint32x4 *>(xl + u_lds[k]) = pre[k];
     };
     // results: thread t stores 8 pixels of channels t/32 + 4k, k = 0 .. CB*8-1
     constexpr int OPW = TM / 2 + 2;                       // out staging pitch in dwords

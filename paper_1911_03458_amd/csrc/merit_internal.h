@@ -99,6 +99,7 @@ struct ConvParams {
     int aligned;           // planar: every fragment starts on an even staged column
     int ws;                // planar: wave-specialised kernel (4 multiplier + 4 mover wavefronts)
     int su;                // wave-specialised kernel: unrolled K steps (S <= su <= S+2)
+    int lg_chunks;         // wave-specialised kernel: log2 of the 16-byte chunks per staged row, rounded up
     int wg_per_cu;         // resident workgroups per compute unit the launcher sizes the grid for
     FastDiv div_ow;
     FastDiv div_kh;

@@ -347,10 +347,12 @@ merit_status derive_conv(merit_plan *pl)
         q.div_rha = make_fastdiv((uint32_t)q.RHa);
         // wave-specialised planar kernel: 4 multiplier + 4 mover wavefronts, double-buffered
         // input tile and output staging, one workgroup per CU
-        q.ws = 0; q.su = 0;
+        q.ws = 0; q.su = 0; q.lg_chunks = 0;
         // (the kernel fetches a channel's weights in 16-byte vectors: at least one per channel)
-        if (variant == CONV_PLANAR_SMALLC && want_ws && pxw == 2 && nw == 4 && (W % 8) == 0 &&
-            (int64_t)Cin * q.RHa * (q.pitch / 8) <= 128 * 10 && (int64_t)q.G * kw >= 8 &&
+        int lgc = 0;
+        while ((1 << lgc) < q.pitch / 8) ++lgc;
+        if (variant == CONV_PLANAR_SMALLC && want_ws && pxw == 2 && nw == 4 && (W % 8) == 0 && lgc <= 7 &&
+            (((int64_t)Cin * q.RHa) << lgc) <= 128 * 10 && (int64_t)q.G * kw >= 8 &&
             (OH * OW) % 8 == 0 && N * Cin * H * W * 2 < (1ll << 31) && N * Cout * OH * OW * 2 < (1ll << 31)) {
             static const int steps[] = {4, 6, 8, 11, 12};
             int su = 0;
@@ -360,6 +362,7 @@ merit_status derive_conv(merit_plan *pl)
             if (su && o_off + 2 * (int64_t)q.lds_o_bytes <= LDS_LIMIT) {
                 q.ws = 1;
                 q.su = su;
+                q.lg_chunks = lgc;
                 q.lds_o_offset = (int)o_off;
                 q.lds_total = (int)(o_off + 2 * (int64_t)q.lds_o_bytes);
             }

@@ -268,6 +268,7 @@ WS_CASES = [
     (3, 3, 64, 72, 40, 7, 7, 2, 2, 3, 3),
     (2, 1, 33, 40, 8, 3, 3, 1, 1, 1, 1),
     (300, 3, 32, 32, 64, 7, 7, 2, 2, 3, 3),    # 300 tiles on 256 workgroups: 1 or 2 tiles each
+    (1100, 3, 32, 32, 64, 7, 7, 2, 2, 3, 3),   # 4 or 5 tiles each: both LDS buffers reused
     (1, 4, 96, 160, 33, 5, 5, 1, 2, 2, 2),
 ]
 
@@ -278,6 +279,9 @@ def test_conv_wave_specialised(mb, case):
     rng = np.random.default_rng(abs(hash(case)) % 2 ** 31)
     x = rng.standard_normal((N, Cin, H, W)).astype(np.float16)
     w = (rng.standard_normal((Cout, Cin, kh, kw)) / np.sqrt(Cin * kh * kw)).astype(np.float16)
+    plan = mb.merit_plan_conv2d(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw)
+    plan.set_tile((0, 0, 8, 64))
+    assert plan.launch_info()["kernel"] == "merit_conv2d_planar_ws"
     _conv_check(mb, x, w, (sh, sw), (ph, pw), (0, 0, 8, 64))
 
 
@@ -296,6 +300,28 @@ def test_conv_3x3_workload(mb):
     c = wl.CFG2_CONV3
     x, w = wl.make_conv_inputs(c)
     _conv_check(mb, x, w, (c.sh, c.sw), (c.ph, c.pw))
+
+
+def test_conv_7x7_workload_kernels_agree(mb):
+    """Every output of the full-size launch, from the wave-specialised kernel and from the
+    one-role kernel (same products, same order): guards the hand-over of the LDS buffers
+    between wavefronts, which a sampled comparison could miss."""
+    c = wl.CFG4_CONV7
+    x, w = wl.make_conv_inputs(c)
+    dx, dw = dev(x), dev(w)
+    outs = []
+    for tile in (None, (0, 0, 4, 64)):
+        plan = mb.merit_plan_conv2d(c.N, c.Cin, c.H, c.W, c.Cout, c.kh, c.kw, c.sh, c.sw, c.ph, c.pw)
+        if tile:
+            plan.set_tile(tile)
+        outs.append((plan.launch_info()["kernel"], mb.merit_conv2d(plan, dx, dw)))
+    assert outs[0][0] == "merit_conv2d_planar_ws" and outs[1][0] == "merit_conv2d_planar"
+    for rep in range(3):                                  # repeated: a race shows up sporadically
+        plan = mb.merit_plan_conv2d(c.N, c.Cin, c.H, c.W, c.Cout, c.kh, c.kw, c.sh, c.sw, c.ph, c.pw)
+        again = mb.merit_conv2d(plan, dx, dw)
+        assert torch.equal(again, outs[0][1]), rep
+    a, b = outs[0][1].float(), outs[1][1].float()
+    assert bool(torch.all((a - b).abs() <= 2e-3 * b.abs() + 1e-3))
 
 
 def test_conv_7x7_workload_sampled(mb):
