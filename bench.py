@@ -168,6 +168,14 @@ def cpu_baseline(wl):
                       f"gcc -O2 + OpenMP over (n,c) planes"}
 
 
+# HBM-side bytes per pooling launch from two rocprofv3 --pmc runs of this file (FETCH_SIZE, then
+# WRITE_SIZE, KiB per dispatch), each scaled by what the same counter reads for a plain 256 MiB
+# device copy (--copy-calibration): FETCH_SIZE 26979.7 x 2.000, WRITE_SIZE 12544.2 x 1.000
+# (profiles/pool2d_stream_k3s2p1_max__pool_16x64x112x112_k3s2p1.txt).  A stored measurement:
+# counters cannot be read from inside this process.
+POOL_TRAFFIC_BYTES = 68.09e6
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -213,7 +221,8 @@ def main():
                    "rotating_buffer_sets": args.sets, "kernel": pool["kernel"],
                    "grid": pool["launch"]["grid"][0], "lds_bytes": pool["launch"]["lds_bytes"]},
         "roofline": {"bound": "hbm", "achieved": pool["achieved_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": pool["achieved_gbs"] / HBM_PEAK_GBS, "traffic": None,
+                     "frac": pool["achieved_gbs"] / HBM_PEAK_GBS, "traffic": POOL_TRAFFIC_BYTES,
+                     "traffic_unit": "bytes per launch",
                      "avg_launch_us": pool["avg_launch_us"], "alg_bytes_per_launch": pool["alg_bytes_per_launch"],
                      "cache_warm_avg_launch_us": pool["warm_avg_launch_us"]},
     }
