@@ -49,6 +49,8 @@ def _load():
     lib.ref_double_to_half.argtypes = [ctypes.c_double]
     lib.ref_conv2d.restype = c_int
     lib.ref_conv2d.argtypes = [vp, vp, vp] + [c_int] * 11
+    lib.ref_conv2d_relu.restype = c_int
+    lib.ref_conv2d_relu.argtypes = [vp, vp, vp] + [c_int] * 11
     lib.ref_pool2d.restype = c_int
     lib.ref_pool2d.argtypes = [vp, vp] + [c_int] * 11
     lib.ref_sad_search.restype = c_int
@@ -95,8 +97,9 @@ def out_extent(I: int, k: int, s: int, p: int) -> int:
     return (I + 2 * p - k) // s + 1
 
 
-def conv2d(x: np.ndarray, w: np.ndarray, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
-    """x fp16 [N,Cin,H,W], w fp16 [Cout,Cin,kh,kw] -> fp16 [N,Cout,OH,OW]."""
+def conv2d(x: np.ndarray, w: np.ndarray, stride=(1, 1), pad=(0, 0), relu=False) -> np.ndarray:
+    """x fp16 [N,Cin,H,W], w fp16 [Cout,Cin,kh,kw] -> fp16 [N,Cout,OH,OW]; relu: the
+    product function max(v1.v2, 0) of Section III-B instead of the plain dot product."""
     x = _c(x, np.float16)
     w = _c(w, np.float16)
     N, Cin, H, W = x.shape
@@ -106,7 +109,8 @@ def conv2d(x: np.ndarray, w: np.ndarray, stride=(1, 1), pad=(0, 0)) -> np.ndarra
     sh, sw = stride
     ph, pw = pad
     y = np.empty((N, Cout, out_extent(H, kh, sh, ph), out_extent(W, kw, sw, pw)), np.float16)
-    rc = _load().ref_conv2d(_ptr(x), _ptr(w), _ptr(y), N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw)
+    fn = _load().ref_conv2d_relu if relu else _load().ref_conv2d
+    rc = fn(_ptr(x), _ptr(w), _ptr(y), N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw)
     if rc != 0:
         raise ValueError("ref_conv2d: bad shape")
     return y

@@ -91,9 +91,9 @@ uint16_t ref_double_to_half(double d)
  * x: [N,Cin,H,W] binary16, w: [Cout,Cin,kh,kw] binary16, y: [N,Cout,OH,OW].
  * Returns 0, or -1 on a bad shape.
  */
-int ref_conv2d(const uint16_t *x, const uint16_t *w, uint16_t *y,
-               int N, int Cin, int H, int W, int Cout,
-               int kh, int kw, int sh, int sw, int ph, int pw)
+static int conv2d_postloop(const uint16_t *x, const uint16_t *w, uint16_t *y,
+                           int N, int Cin, int H, int W, int Cout,
+                           int kh, int kw, int sh, int sw, int ph, int pw, int relu)
 {
     if (N < 0 || Cin <= 0 || H <= 0 || W <= 0 || Cout <= 0 || kh <= 0 || kw <= 0 ||
         sh <= 0 || sw <= 0 || ph < 0 || pw < 0) return -1;
@@ -119,10 +119,30 @@ int ref_conv2d(const uint16_t *x, const uint16_t *w, uint16_t *y,
                                 w[(((size_t)co * Cin + ci) * kh + ky) * kw + kx]);
                             acc += xv * wv;
                         }
+                if (relu && !(acc > 0.0)) acc = 0.0;       /* PostLoop: max(act, 0) */
                 y[(((size_t)n * Cout + co) * OH + oy) * OW + ox] = ref_double_to_half(acc);
             }
     }
     return 0;
+}
+
+int ref_conv2d(const uint16_t *x, const uint16_t *w, uint16_t *y,
+               int N, int Cin, int H, int W, int Cout,
+               int kh, int kw, int sh, int sw, int ph, int pw)
+{
+    return conv2d_postloop(x, w, y, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, 0);
+}
+
+/*
+ * The same ranged inner product with the second product function of Section
+ * III-B, max(v1^T v2, 0) (the fused ReLU layer; Listing 1's PostLoop): the
+ * double sum is clipped at zero, then rounded once to binary16.
+ */
+int ref_conv2d_relu(const uint16_t *x, const uint16_t *w, uint16_t *y,
+                    int N, int Cin, int H, int W, int Cout,
+                    int kh, int kw, int sh, int sw, int ph, int pw)
+{
+    return conv2d_postloop(x, w, y, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, 1);
 }
 
 /* ------------------------------------------------------------------------ */

@@ -158,3 +158,59 @@ def test_output_extent_rule():
     assert oracle.out_extent(112, 3, 2, 1) == 56
     assert oracle.out_extent(56, 3, 1, 1) == 56
     assert oracle.out_extent(224, 7, 2, 3) == 112
+
+
+# ------------------------------------------- product function max(v1.v2, 0) (Section III-B)
+def test_relu_identity_kernel_clips_the_input_at_zero():
+    """Identity weights: the fused-ReLU product returns max(x, 0), with +0 for every
+    non-positive input (a dropped clip or a clip of the wrong sign fails here)."""
+    rng = np.random.default_rng(21)
+    C = 4
+    x = _rand_half(rng, (2, C, 7, 9))
+    x[0, 0, 0, :3] = [-0.0, 0.0, -6.1e-5]                    # signed zero, negative subnormal
+    w = np.zeros((C, C, 3, 3), np.float16)
+    for c in range(C):
+        w[c, c, 1, 1] = 1.0
+    y = oracle.conv2d(x, w, (1, 1), (1, 1), relu=True)
+    want = np.where(x > 0, x, np.float16(0.0))
+    assert np.array_equal(y.view(np.uint16), want.view(np.uint16))
+    assert not np.signbit(y).any()
+
+
+def test_relu_closed_forms_on_constant_tensors():
+    """Ones times +1 weights: the valid-tap count; times -1 weights: zero everywhere."""
+    Cin = 3
+    x = np.ones((1, Cin, 6, 7), np.float16)
+    for sign, scale in ((1.0, 1.0), (-1.0, 0.0)):
+        w = np.full((2, Cin, 3, 3), sign, np.float16)
+        y = oracle.conv2d(x, w, (1, 1), (1, 1), relu=True).astype(np.float64)
+        assert y[0, 0, 0, 0] == scale * Cin * 4 and y[0, 1, 0, 3] == scale * Cin * 6
+        assert y[0, 0, 2, 3] == scale * Cin * 9
+
+
+def test_relu_clips_before_the_single_rounding():
+    """A sum just below zero must give +0, not the rounded negative; a sum in the binary16
+    subnormal range must survive (clip first, round once)."""
+    x = np.array([[[[1.0, 1.0]]]], np.float16).reshape(1, 2, 1, 1)
+    w = np.array([[2.0 ** -14, -(2.0 ** -14) - 2.0 ** -24]], np.float16).reshape(1, 2, 1, 1)
+    y = oracle.conv2d(x, w, relu=True)
+    assert y.view(np.uint16)[0, 0, 0, 0] == 0                 # -2^-24 -> +0
+    y = oracle.conv2d(x, -w, relu=True)
+    assert float(y[0, 0, 0, 0]) == 2.0 ** -24
+
+
+@pytest.mark.parametrize("stride,pad", [((1, 1), (1, 1)), ((2, 2), (3, 3)), ((2, 1), (0, 2))])
+def test_relu_matches_literal_evaluator_and_torch(stride, pad):
+    rng = np.random.default_rng(33)
+    k = 7 if pad == (3, 3) else 3
+    x = _rand_half(rng, (2, 3, 9, 10))
+    w = _rand_half(rng, (4, 3, k, k), 0.3)
+    got = oracle.conv2d(x, w, stride, pad, relu=True)
+    assert np.array_equal(got.view(np.uint16), lit.conv2d(x, w, stride, pad, relu=True).view(np.uint16))
+    ref = torch.relu(torch.nn.functional.conv2d(torch.from_numpy(x.astype(np.float64)),
+                                                torch.from_numpy(w.astype(np.float64)),
+                                                stride=stride, padding=pad)).numpy()
+    assert np.allclose(got.astype(np.float64), ref, rtol=2e-3, atol=1e-3)
+    plain = oracle.conv2d(x, w, stride, pad).astype(np.float64)
+    assert np.array_equal(got.astype(np.float64), np.maximum(plain, 0.0))
+    assert (plain < 0).any() and (plain > 0).any()
