@@ -40,7 +40,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--sets", type=int, default=8, help="rotating buffer sets for cache-cold timing")
-    ap.add_argument("--no-extra", action="store_true", help="skip the other four workloads")
+    ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB device copy 10 times (known traffic, for scaling "
@@ -121,7 +121,7 @@ def bench_sad(torch, mb, wl, cfg, steps, warmup):
     }
 
 
-def bench_conv(torch, mb, wl, cfg, steps, warmup, nsets):
+def bench_conv(torch, mb, wl, cfg, steps, warmup, nsets, relu=False):
     x, w = wl.make_conv_inputs(cfg)
     x0 = torch.from_numpy(x).to("cuda:0")
     dw = torch.from_numpy(w).to("cuda:0")
@@ -131,13 +131,15 @@ def bench_conv(torch, mb, wl, cfg, steps, warmup, nsets):
     ns = nsets if (in_bytes + out_bytes) > (8 << 20) else 1
     xs = [x0] + [x0.roll(i, dims=0).contiguous() for i in range(1, ns)]
     ys = [torch.empty((cfg.N, cfg.Cout, cfg.OH, cfg.OW), dtype=torch.float16, device="cuda:0") for _ in range(ns)]
-    plan = mb.merit_plan_conv2d(cfg.N, cfg.Cin, cfg.H, cfg.W, cfg.Cout, cfg.kh, cfg.kw, cfg.sh, cfg.sw, cfg.ph, cfg.pw)
+    make = mb.merit_plan_conv2d_relu if relu else mb.merit_plan_conv2d
+    plan = make(cfg.N, cfg.Cin, cfg.H, cfg.W, cfg.Cout, cfg.kh, cfg.kw, cfg.sh, cfg.sw, cfg.ph, cfg.pw)
     calls = [mb.bind_conv2d(plan, xs[i], dw, ys[i]) for i in range(ns)]
     wall, ev_ms = timed_region(torch, lambda i: calls[i % ns](), steps, warmup)
     t = ev_ms * 1e-3 / steps
     flops = 2.0 * cfg.N * cfg.Cout * cfg.OH * cfg.OW * cfg.Cin * cfg.kh * cfg.kw
     return {
-        "workload": cfg.name, "kernel": plan.launch_info()["kernel"], "avg_launch_us": t * 1e6,
+        "workload": cfg.name + (" + fused ReLU" if relu else ""), "kernel": plan.launch_info()["kernel"],
+        "avg_launch_us": t * 1e6,
         "out_elems_per_s": cfg.N * cfg.Cout * cfg.OH * cfg.OW / t,
         "achieved_tflops": flops / t / 1e12, "mfma_frac": flops / t / 1e12 / MFMA_F16_PEAK_TFLOPS,
         "achieved_hbm_gbs": (in_bytes + out_bytes) / t / 1e9,
@@ -234,6 +236,7 @@ def main():
             bench_conv(torch, mb, wl, wl.CFG2_CONV3, k, w, args.sets),
             bench_sad(torch, mb, wl, wl.CFG3_ME_FHD, max(10, k // 2), w),
             bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets),
+            bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets, relu=True),
         ]
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(wl)

@@ -48,12 +48,15 @@ typedef enum {
 /* Product functions (.) (Section III-B): dot product (Eq. 3); max / mean of the
  * window (one operand; the paper names pooling only as a max/min use, Table
  * "isa"); L1 distance (Eq. 4) followed by min/argmin over the leading
- * accumulation indices (the outer level of a 2-level ranged inner product). */
+ * accumulation indices (the outer level of a 2-level ranged inner product);
+ * the clipped dot product max(v1^T v2, 0), the fused ReLU layer (second
+ * definition of (.) in Section III-B; PostLoop of Listing 1). */
 typedef enum {
     MERIT_OP_CONV_DOT = 0,
     MERIT_OP_POOL_MAX = 1,
     MERIT_OP_POOL_AVG = 2,
-    MERIT_OP_SAD_ARGMIN = 3
+    MERIT_OP_SAD_ARGMIN = 3,
+    MERIT_OP_CONV_DOT_RELU = 4
 } merit_op;
 
 typedef enum { MERIT_U8 = 0, MERIT_F16 = 1, MERIT_F32 = 2 } merit_dtype;
@@ -84,6 +87,7 @@ typedef struct {
  *
  * Accepted patterns (anything else: MERIT_ERR_UNSUPPORTED)
  *   CONV_DOT   F16 ZERO     k=(n,co,oy,ox | ci,ky,kx)  a = x[N,Cin,H,W], b = w[Cout,Cin,kh,kw]
+ *   CONV_DOT_RELU           same
  *   POOL_MAX   F32 NEG_INF  k=(n,c,oy,ox | ky,kx)      a = x[N,C,H,W],   b unused (ndim 0)
  *   POOL_AVG   F32 EXCLUDE  same
  *   SAD_ARGMIN U8  CLAMP    k=(by,bx | dy,dx,i,j)      a = ref[H,W] (displaced by dy,dx),
@@ -130,6 +134,10 @@ merit_status merit_plan_destroy(merit_plan *plan);
  *          search indices as in Section III-C, Eq. 8. */
 merit_status merit_plan_conv2d(int N, int Cin, int H, int W, int Cout, int kh, int kw,
                                int sh, int sw, int ph, int pw, merit_plan **out);
+/* The same transform with the product function max(v1^T v2, 0) (Section III-B):
+ * y = max(sum, 0), clipped before the one rounding to binary16; never -0. */
+merit_status merit_plan_conv2d_relu(int N, int Cin, int H, int W, int Cout, int kh, int kw,
+                                    int sh, int sw, int ph, int pw, merit_plan **out);
 merit_status merit_plan_pool2d(int N, int C, int H, int W, int kh, int kw,
                                int sh, int sw, int ph, int pw, int is_avg, merit_plan **out);
 merit_status merit_plan_sad(int H, int W, int block, int range, merit_plan **out);
@@ -159,7 +167,8 @@ merit_status merit_plan_set_tile(merit_plan *plan, const int64_t tile[MERIT_MAX_
 /* ---- operations ------------------------------------------------------------
  * x_f16: [N,Cin,H,W] binary16; w_f16: [Cout,Cin,kh,kw] binary16;
  * y_f16: [N,Cout,OH,OW] binary16.  Products accumulate in fp32 on the matrix
- * cores and are rounded once (nearest even) to binary16.  (.) = Eq. 3. */
+ * cores and are rounded once (nearest even) to binary16.  (.) = Eq. 3, or its
+ * clipped form for a CONV_DOT_RELU plan. */
 merit_status merit_conv2d(const merit_plan *plan, const void *x_f16, const void *w_f16,
                           void *y_f16, void *hip_stream);
 

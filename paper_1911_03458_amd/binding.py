@@ -19,7 +19,7 @@ MERIT_AXIS_UNUSED = -1
 MERIT_OK = 0
 (MERIT_ERR_NULL, MERIT_ERR_INVALID_ARG, MERIT_ERR_SHAPE, MERIT_ERR_UNSUPPORTED,
  MERIT_ERR_ALIGNMENT, MERIT_ERR_HIP) = range(1, 7)
-MERIT_OP_CONV_DOT, MERIT_OP_POOL_MAX, MERIT_OP_POOL_AVG, MERIT_OP_SAD_ARGMIN = range(4)
+MERIT_OP_CONV_DOT, MERIT_OP_POOL_MAX, MERIT_OP_POOL_AVG, MERIT_OP_SAD_ARGMIN, MERIT_OP_CONV_DOT_RELU = range(5)
 MERIT_U8, MERIT_F16, MERIT_F32 = range(3)
 MERIT_PAD_ZERO, MERIT_PAD_NEG_INF, MERIT_PAD_EXCLUDE, MERIT_PAD_CLAMP = range(4)
 
@@ -76,6 +76,7 @@ def lib():
     L.merit_plan_create.argtypes = [ctypes.POINTER(merit_plan_desc), PP]
     L.merit_plan_destroy.argtypes = [P]
     L.merit_plan_conv2d.argtypes = [c_int] * 11 + [PP]
+    L.merit_plan_conv2d_relu.argtypes = [c_int] * 11 + [PP]
     L.merit_plan_pool2d.argtypes = [c_int] * 11 + [PP]
     L.merit_plan_sad.argtypes = [c_int] * 4 + [PP]
     L.merit_plan_get_desc.argtypes = [P, ctypes.POINTER(merit_plan_desc)]
@@ -86,7 +87,8 @@ def lib():
     L.merit_conv2d.argtypes = [P, P, P, P, P]
     L.merit_pool2d.argtypes = [P, P, P, P]
     L.merit_sad_search.argtypes = [P, P, P, P, P, P]
-    for name in ("merit_plan_create", "merit_plan_destroy", "merit_plan_conv2d", "merit_plan_pool2d",
+    for name in ("merit_plan_create", "merit_plan_destroy", "merit_plan_conv2d", "merit_plan_conv2d_relu",
+                 "merit_plan_pool2d",
                  "merit_plan_sad", "merit_plan_get_desc", "merit_plan_out_shape", "merit_plan_footprint",
                  "merit_plan_launch_info", "merit_plan_set_tile", "merit_conv2d", "merit_pool2d",
                  "merit_sad_search"):
@@ -174,6 +176,13 @@ def merit_plan_conv2d(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw) -> Plan:
     h = ctypes.c_void_p()
     _check(lib().merit_plan_conv2d(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, ctypes.byref(h)),
            "merit_plan_conv2d")
+    return Plan(h)
+
+
+def merit_plan_conv2d_relu(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw) -> Plan:
+    h = ctypes.c_void_p()
+    _check(lib().merit_plan_conv2d_relu(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, ctypes.byref(h)),
+           "merit_plan_conv2d_relu")
     return Plan(h)
 
 

@@ -67,8 +67,16 @@ __device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi)
 // spreads the 32 channels of a write over all banks.
 // ---------------------------------------------------------------------------
 // part 1: accumulators -> LDS staging
+// max(v, +0) on two packed binary16 values (v_pk_max_f16: -0 and negative values give +0)
+__device__ __forceinline__ uint32_t relu_f16x2(uint32_t v)
+{
+    const half2v z = {(_Float16)0.0f, (_Float16)0.0f};
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(half2v, v), z));
+}
+
 template <int CB, int PXW, int NW>
-__device__ __forceinline__ void tile_to_lds(floatx16 (&acc)[CB][PXW], uint32_t *outl, int wave, int lane)
+__device__ __forceinline__ void tile_to_lds(floatx16 (&acc)[CB][PXW], uint32_t *outl, int wave, int lane,
+                                            bool relu)
 {
     constexpr int OP = NW * PXW * 16 + 2;
     const int h = lane >> 5, c32 = lane & 31;
@@ -82,6 +90,10 @@ __device__ __forceinline__ void tile_to_lds(floatx16 (&acc)[CB][PXW], uint32_t *
                 uint2 v;
                 v.x = pack_f16x2(acc[cb][pb][4 * q], acc[cb][pb][4 * q + 1]);
                 v.y = pack_f16x2(acc[cb][pb][4 * q + 2], acc[cb][pb][4 * q + 3]);
+                if (relu) {        // clipping the rounded value = rounding the clipped value
+                    v.x = relu_f16x2(v.x);
+                    v.y = relu_f16x2(v.y);
+                }
                 *reinterpret_cast<uint2 *>(row + cb * 32 * OP + pb * 16 + 4 * q) = v;
             }
 }
@@ -127,7 +139,7 @@ template <int CB, int PXW, int NW, bool FULL>
 __device__ __forceinline__ void store_tile(const ConvParams &p, floatx16 (&acc)[CB][PXW], uint32_t *outl,
                                            uint16_t *__restrict__ y, int n, int co_base, int m0, int tid)
 {
-    tile_to_lds<CB, PXW, NW>(acc, outl, tid >> 6, tid & 63);
+    tile_to_lds<CB, PXW, NW>(acc, outl, tid >> 6, tid & 63, p.relu != 0);
     __syncthreads();
     lds_to_global<CB, NW * PXW * 32, NW * 64, FULL>(p, outl, y, n, co_base, m0, tid);
 }
@@ -749,7 +761,7 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
         else if (mask_mode == 1) kloop(std::integral_constant<int, 1>{});
         else if (mask_mode == 2) kloop(std::integral_constant<int, 2>{});
         else kloop(std::integral_constant<int, 3>{});
-        tile_to_lds<CB, PXW, NWC>(acc, outl, cwave, lane);
+        tile_to_lds<CB, PXW, NWC>(acc, outl, cwave, lane, p.relu != 0);
     };
 
     // ---- common prologue: weights global -> LDS -> fragment layout ----

@@ -97,6 +97,7 @@ struct ConvParams {
     int lds_total;         // LDS per workgroup
     int front;             // planar: slot of tap kx = 0 inside an 8-slot fragment (0 or 1)
     int aligned;           // planar: every fragment starts on an even staged column
+    int relu;              // product function max(v1.v2, 0): results clipped at zero before rounding
     int ws;                // planar: wave-specialised kernel (4 multiplier + 4 mover wavefronts)
     int su;                // wave-specialised kernel: unrolled K steps (S <= su <= S+2)
     int lg_chunks;         // wave-specialised kernel: log2 of the 16-byte chunks per staged row, rounded up

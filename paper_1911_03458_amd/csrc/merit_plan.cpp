@@ -273,6 +273,7 @@ merit_status derive_conv(merit_plan *pl)
 
     ConvParams &p = pl->conv;
     p.N = (int)N; p.Cin = (int)Cin; p.H = (int)H; p.W = (int)W; p.Cout = (int)Cout;
+    p.relu = d.op == MERIT_OP_CONV_DOT_RELU ? 1 : 0;
     p.OH = (int)OH; p.OW = (int)OW; p.kh = (int)kh; p.kw = (int)kw; p.sh = (int)sh; p.sw = (int)sw;
     p.ph = (int)ph; p.pw = (int)pw;
 
@@ -434,7 +435,7 @@ merit_status merit_plan_create(const merit_plan_desc *desc, merit_plan **out)
 {
     if (!desc || !out) return MERIT_ERR_NULL;
     *out = nullptr;
-    if ((int)desc->op < 0 || (int)desc->op > 3 || (int)desc->dtype < 0 || (int)desc->dtype > 2 ||
+    if ((int)desc->op < 0 || (int)desc->op > 4 || (int)desc->dtype < 0 || (int)desc->dtype > 2 ||
         (int)desc->pad < 0 || (int)desc->pad > 3)
         return MERIT_ERR_INVALID_ARG;
     if (desc->n_par < 1 || desc->n_acc < 1 || desc->n_par + desc->n_acc > MERIT_MAX_INDEX)
@@ -454,7 +455,8 @@ merit_status merit_plan_create(const merit_plan_desc *desc, merit_plan **out)
     pl->desc = *desc;
     merit_status st;
     switch (desc->op) {
-    case MERIT_OP_CONV_DOT: st = derive_conv(pl); break;
+    case MERIT_OP_CONV_DOT:
+    case MERIT_OP_CONV_DOT_RELU: st = derive_conv(pl); break;
     case MERIT_OP_POOL_MAX:
     case MERIT_OP_POOL_AVG: st = derive_pool(pl); break;
     default: st = derive_sad(pl); break;
@@ -474,8 +476,10 @@ merit_status merit_plan_destroy(merit_plan *plan)
     return MERIT_OK;
 }
 
-merit_status merit_plan_conv2d(int N, int Cin, int H, int W, int Cout, int kh, int kw, int sh, int sw,
-                               int ph, int pw, merit_plan **out)
+}  // extern "C"
+
+static merit_status plan_conv2d_op(merit_op op, int N, int Cin, int H, int W, int Cout, int kh, int kw, int sh,
+                                   int sw, int ph, int pw, merit_plan **out)
 {
     if (!out) return MERIT_ERR_NULL;
     *out = nullptr;
@@ -485,7 +489,7 @@ merit_status merit_plan_conv2d(int N, int Cin, int H, int W, int Cout, int kh, i
     if (H + 2 * ph < kh || W + 2 * pw < kw) return MERIT_ERR_SHAPE;
     merit_plan_desc d;
     std::memset(&d, 0, sizeof(d));
-    d.op = MERIT_OP_CONV_DOT; d.dtype = MERIT_F16; d.pad = MERIT_PAD_ZERO;
+    d.op = op; d.dtype = MERIT_F16; d.pad = MERIT_PAD_ZERO;
     d.n_par = 4; d.n_acc = 3;
     const int64_t OH = out_extent(H, kh, sh, ph), OW = out_extent(W, kw, sw, pw);
     const int64_t range[7] = {N, Cout, OH, OW, Cin, kh, kw};
@@ -502,6 +506,20 @@ merit_status merit_plan_conv2d(int N, int Cin, int H, int W, int Cout, int kh, i
     d.a.ndim = 4; d.a.shape[0] = N; d.a.shape[1] = Cin; d.a.shape[2] = H; d.a.shape[3] = W;
     d.b.ndim = 4; d.b.shape[0] = Cout; d.b.shape[1] = Cin; d.b.shape[2] = kh; d.b.shape[3] = kw;
     return merit_plan_create(&d, out);
+}
+
+extern "C" {
+
+merit_status merit_plan_conv2d(int N, int Cin, int H, int W, int Cout, int kh, int kw, int sh, int sw,
+                               int ph, int pw, merit_plan **out)
+{
+    return plan_conv2d_op(MERIT_OP_CONV_DOT, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, out);
+}
+
+merit_status merit_plan_conv2d_relu(int N, int Cin, int H, int W, int Cout, int kh, int kw, int sh, int sw,
+                                    int ph, int pw, merit_plan **out)
+{
+    return plan_conv2d_op(MERIT_OP_CONV_DOT_RELU, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, out);
 }
 
 merit_status merit_plan_pool2d(int N, int C, int H, int W, int kh, int kw, int sh, int sw, int ph, int pw,
@@ -566,7 +584,8 @@ merit_status merit_plan_set_tile(merit_plan *plan, const int64_t tile[MERIT_MAX_
     for (int j = 0; j < MERIT_MAX_INDEX; ++j) trial.tile_req[j] = tile[j];
     merit_status st;
     switch (trial.desc.op) {
-    case MERIT_OP_CONV_DOT: st = derive_conv(&trial); break;
+    case MERIT_OP_CONV_DOT:
+    case MERIT_OP_CONV_DOT_RELU: st = derive_conv(&trial); break;
     case MERIT_OP_POOL_MAX:
     case MERIT_OP_POOL_AVG: st = derive_pool(&trial); break;
     default: st = derive_sad(&trial); break;
@@ -623,7 +642,7 @@ merit_status merit_plan_launch_info(const merit_plan *plan, merit_launch_info *o
 merit_status merit_conv2d(const merit_plan *plan, const void *x, const void *w, void *y, void *stream)
 {
     if (!plan) return MERIT_ERR_NULL;
-    if (plan->desc.op != MERIT_OP_CONV_DOT) return MERIT_ERR_INVALID_ARG;
+    if (plan->desc.op != MERIT_OP_CONV_DOT && plan->desc.op != MERIT_OP_CONV_DOT_RELU) return MERIT_ERR_INVALID_ARG;
     if (plan->conv.N == 0) return MERIT_OK;               // empty batch: nothing to read or write
     if (!x || !w || !y) return MERIT_ERR_NULL;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return MERIT_ERR_ALIGNMENT;

@@ -59,6 +59,20 @@ def test_conv_plan_descriptor_is_the_papers_transform():
     assert plan.out_shape() == (2, 64, 112, 112)
 
 
+def test_relu_plan_differs_only_in_the_product_function():
+    a = mb.merit_plan_conv2d(2, 3, 32, 32, 8, 7, 7, 2, 2, 3, 3)
+    b = mb.merit_plan_conv2d_relu(2, 3, 32, 32, 8, 7, 7, 2, 2, 3, 3)
+    da, db = a.desc(), b.desc()
+    assert (da.op, db.op) == (mb.MERIT_OP_CONV_DOT, mb.MERIT_OP_CONV_DOT_RELU)
+    assert tuple(da.range) == tuple(db.range) and a.out_shape() == b.out_shape()
+    assert a.launch_info() == b.launch_info()
+    # the generic constructor accepts the same descriptor
+    assert mb.merit_plan_create(db).desc().op == mb.MERIT_OP_CONV_DOT_RELU
+    db.pad = mb.MERIT_PAD_CLAMP
+    with pytest.raises(mb.MeritError):
+        mb.merit_plan_create(db)
+
+
 def test_pool_and_sad_plan_descriptors():
     plan = mb.merit_plan_pool2d(16, 64, 112, 112, 3, 3, 2, 2, 1, 1, 0)
     d = plan.desc()

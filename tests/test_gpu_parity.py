@@ -200,10 +200,11 @@ def test_sad_full_hd_workload(mb):
 
 
 # ------------------------------------------------------------- convolution
-def _conv_check(mb, x, w, stride, pad, tile=None):
+def _conv_check(mb, x, w, stride, pad, tile=None, relu=False):
     N, Cin, H, W = x.shape
     Cout, _, kh, kw = w.shape
-    plan = mb.merit_plan_conv2d(N, Cin, H, W, Cout, kh, kw, *stride, *pad)
+    make = mb.merit_plan_conv2d_relu if relu else mb.merit_plan_conv2d
+    plan = make(N, Cin, H, W, Cout, kh, kw, *stride, *pad)
     if tile is not None:
         plan.set_tile(tile)
     print("conv", x.shape, w.shape, stride, pad, plan.launch_info(), flush=True)
@@ -212,8 +213,10 @@ def _conv_check(mb, x, w, stride, pad, tile=None):
     torch.cuda.synchronize()
     check_canary(buf, p, 777.0)
     got = y.cpu().numpy().astype(np.float64)
-    ref = oracle.conv2d(x, w, stride, pad).astype(np.float64)
+    ref = oracle.conv2d(x, w, stride, pad, relu=relu).astype(np.float64)
     assert got.shape == ref.shape
+    if relu:                                       # clipped at +0: no negative value, no -0
+        assert not np.signbit(got).any()
     err = np.abs(got - ref)
     tol = 2e-2 * np.abs(ref) + 1e-3
     ok = bool(np.all(err <= tol))
@@ -283,6 +286,58 @@ def test_conv_wave_specialised(mb, case):
     plan.set_tile((0, 0, 8, 64))
     assert plan.launch_info()["kernel"] == "merit_conv2d_planar_ws"
     _conv_check(mb, x, w, (sh, sw), (ph, pw), (0, 0, 8, 64))
+
+
+RELU_CASES = [
+    # the fused-ReLU product function on each kernel: wave-specialised planar, planar, channel-block
+    ((300, 3, 32, 32, 64, 7, 7, 2, 2, 3, 3), (0, 0, 8, 64), "merit_conv2d_planar_ws"),
+    ((2, 3, 17, 19, 40, 7, 7, 2, 2, 3, 3), None, "merit_conv2d_planar"),
+    ((1, 16, 12, 16, 32, 3, 3, 1, 1, 1, 1), None, "merit_conv2d_chblock"),
+    ((2, 64, 28, 28, 64, 3, 3, 1, 1, 1, 1), None, "merit_conv2d_chblock"),
+]
+
+
+@pytest.mark.parametrize("case,tile,kernel", RELU_CASES)
+def test_conv_relu_product_function(mb, case, tile, kernel):
+    N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw = case
+    plan = mb.merit_plan_conv2d_relu(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw)
+    if tile is not None:
+        plan.set_tile(tile)
+    assert plan.launch_info()["kernel"] == kernel
+    rng = np.random.default_rng(abs(hash(case)) % 2 ** 31)
+    x = rng.standard_normal((N, Cin, H, W)).astype(np.float16)
+    w = (rng.standard_normal((Cout, Cin, kh, kw)) / np.sqrt(Cin * kh * kw)).astype(np.float16)
+    got, ref = _conv_check(mb, x, w, (sh, sw), (ph, pw), tile, relu=True)
+    assert (ref == 0).mean() > 0.3 and (ref > 0).mean() > 0.3      # both branches exercised
+
+
+def test_conv_relu_identity_kernel_clips_exactly(mb):
+    rng = np.random.default_rng(5)
+    C = 16
+    x = rng.standard_normal((1, C, 12, 16)).astype(np.float16)
+    x[0, 0, 0, :2] = [-0.0, -6.1e-5]
+    w = np.zeros((C, C, 3, 3), np.float16)
+    for c in range(C):
+        w[c, c, 1, 1] = 1.0
+    got, ref = _conv_check(mb, x, w, (1, 1), (1, 1), relu=True)
+    assert np.array_equal(got, np.maximum(x.astype(np.float64), 0.0))
+
+
+def test_conv_7x7_workload_relu_sampled(mb):
+    """Full-size launch with the clipped product function; the oracle checks one image."""
+    c = wl.CFG4_CONV7
+    x, w = wl.make_conv_inputs(c)
+    plan = mb.merit_plan_conv2d_relu(c.N, c.Cin, c.H, c.W, c.Cout, c.kh, c.kw, c.sh, c.sw, c.ph, c.pw)
+    assert plan.launch_info()["kernel"] == "merit_conv2d_planar_ws"
+    y = mb.merit_conv2d(plan, dev(x), dev(w))
+    n = 13
+    got = y[n].cpu().numpy().astype(np.float64)
+    ref = oracle.conv2d(x[n:n + 1], w, (c.sh, c.sw), (c.ph, c.pw), relu=True)[0].astype(np.float64)
+    assert not np.signbit(got).any()
+    assert np.all(np.abs(got - ref) <= 2e-2 * np.abs(ref) + 1e-3)
+    plain = mb.merit_conv2d(mb.merit_plan_conv2d(c.N, c.Cin, c.H, c.W, c.Cout, c.kh, c.kw, c.sh, c.sw, c.ph, c.pw),
+                            dev(x), dev(w))
+    assert torch.equal(y, torch.clamp_min(plain, 0.0) + 0.0)      # same products, clipped; "+ 0.0" folds -0
 
 
 def test_conv_identity_kernel_is_exact(mb):
