@@ -51,6 +51,8 @@ def _load():
     lib.ref_conv2d.argtypes = [vp, vp, vp] + [c_int] * 11
     lib.ref_conv2d_relu.restype = c_int
     lib.ref_conv2d_relu.argtypes = [vp, vp, vp] + [c_int] * 11
+    lib.ref_conv2d_dilated.restype = c_int
+    lib.ref_conv2d_dilated.argtypes = [vp, vp, vp] + [c_int] * 14
     lib.ref_pool2d.restype = c_int
     lib.ref_pool2d.argtypes = [vp, vp] + [c_int] * 11
     lib.ref_sad_search.restype = c_int
@@ -97,9 +99,10 @@ def out_extent(I: int, k: int, s: int, p: int) -> int:
     return (I + 2 * p - k) // s + 1
 
 
-def conv2d(x: np.ndarray, w: np.ndarray, stride=(1, 1), pad=(0, 0), relu=False) -> np.ndarray:
+def conv2d(x: np.ndarray, w: np.ndarray, stride=(1, 1), pad=(0, 0), relu=False, dilation=(1, 1)) -> np.ndarray:
     """x fp16 [N,Cin,H,W], w fp16 [Cout,Cin,kh,kw] -> fp16 [N,Cout,OH,OW]; relu: the
-    product function max(v1.v2, 0) of Section III-B instead of the plain dot product."""
+    product function max(v1.v2, 0) of Section III-B instead of the plain dot product;
+    dilation: input rows / columns per step of the window indices (Section III-C)."""
     x = _c(x, np.float16)
     w = _c(w, np.float16)
     N, Cin, H, W = x.shape
@@ -108,9 +111,15 @@ def conv2d(x: np.ndarray, w: np.ndarray, stride=(1, 1), pad=(0, 0), relu=False) 
         raise ValueError("channel mismatch")
     sh, sw = stride
     ph, pw = pad
-    y = np.empty((N, Cout, out_extent(H, kh, sh, ph), out_extent(W, kw, sw, pw)), np.float16)
-    fn = _load().ref_conv2d_relu if relu else _load().ref_conv2d
-    rc = fn(_ptr(x), _ptr(w), _ptr(y), N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw)
+    dh, dw = dilation
+    y = np.empty((N, Cout, out_extent(H, (kh - 1) * dh + 1, sh, ph), out_extent(W, (kw - 1) * dw + 1, sw, pw)),
+                 np.float16)
+    if (dh, dw) == (1, 1):
+        fn = _load().ref_conv2d_relu if relu else _load().ref_conv2d
+        rc = fn(_ptr(x), _ptr(w), _ptr(y), N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw)
+    else:
+        rc = _load().ref_conv2d_dilated(_ptr(x), _ptr(w), _ptr(y), N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw,
+                                        dh, dw, 1 if relu else 0)
     if rc != 0:
         raise ValueError("ref_conv2d: bad shape")
     return y

@@ -87,13 +87,14 @@ def footprint(tile: Sequence[int], t: Transform, ndim: int):
 # --------------------------------------------------------------------------
 # the three operations as (ranges, transforms)
 # --------------------------------------------------------------------------
-def conv2d_desc(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw):
-    """k = (n, co, oy, ox | ci, ky, kx), after the strided example of Eq. 6."""
-    OH = (H + 2 * ph - kh) // sh + 1
-    OW = (W + 2 * pw - kw) // sw + 1
+def conv2d_desc(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh=1, dw=1):
+    """k = (n, co, oy, ox | ci, ky, kx), after the strided example of Eq. 6; the window
+    indices step dh rows / dw columns (the dilated example that follows it)."""
+    OH = (H + 2 * ph - ((kh - 1) * dh + 1)) // sh + 1
+    OW = (W + 2 * pw - ((kw - 1) * dw + 1)) // sw + 1
     ranges = (N, Cout, OH, OW, Cin, kh, kw)
     tx = Transform(axis=(0, UNUSED, 2, 3, 1, 2, 3),
-                   stride=(1, 0, sh, sw, 1, 1, 1),
+                   stride=(1, 0, sh, sw, 1, dh, dw),
                    offset=(0, 0, 0, 0, 0, -ph, -pw))
     tw = Transform(axis=(UNUSED, 0, UNUSED, UNUSED, 1, 2, 3),
                    stride=(0, 1, 0, 0, 1, 1, 1),
@@ -129,10 +130,10 @@ def sad_desc(H, W, B, R):
 # --------------------------------------------------------------------------
 # row-wise reductions R(M(A), M(B), (.))
 # --------------------------------------------------------------------------
-def conv2d(x: np.ndarray, w: np.ndarray, stride=(1, 1), pad=(0, 0), relu=False) -> np.ndarray:
+def conv2d(x: np.ndarray, w: np.ndarray, stride=(1, 1), pad=(0, 0), relu=False, dilation=(1, 1)) -> np.ndarray:
     N, Cin, H, W = x.shape
     Cout, _, kh, kw = w.shape
-    ranges, n_par, tx, tw = conv2d_desc(N, Cin, H, W, Cout, kh, kw, *stride, *pad)
+    ranges, n_par, tx, tw = conv2d_desc(N, Cin, H, W, Cout, kh, kw, *stride, *pad, *dilation)
     MA, _ = transform(x.astype(np.float64), ranges, tx, n_par, "zero")
     MB, _ = transform(w.astype(np.float64), ranges, tw, n_par, "zero")
     rows = np.einsum("pa,pa->p", MA, MB)                    # v1^T v2 per row

@@ -93,13 +93,14 @@ uint16_t ref_double_to_half(double d)
  */
 static int conv2d_postloop(const uint16_t *x, const uint16_t *w, uint16_t *y,
                            int N, int Cin, int H, int W, int Cout,
-                           int kh, int kw, int sh, int sw, int ph, int pw, int relu)
+                           int kh, int kw, int sh, int sw, int ph, int pw, int dh, int dw, int relu)
 {
     if (N < 0 || Cin <= 0 || H <= 0 || W <= 0 || Cout <= 0 || kh <= 0 || kw <= 0 ||
-        sh <= 0 || sw <= 0 || ph < 0 || pw < 0) return -1;
-    if (H + 2 * ph < kh || W + 2 * pw < kw) return -1;
-    const int OH = (H + 2 * ph - kh) / sh + 1;
-    const int OW = (W + 2 * pw - kw) / sw + 1;
+        sh <= 0 || sw <= 0 || ph < 0 || pw < 0 || dh <= 0 || dw <= 0) return -1;
+    const int eh = (kh - 1) * dh + 1, ew = (kw - 1) * dw + 1;   /* extent of the dilated window */
+    if (H + 2 * ph < eh || W + 2 * pw < ew) return -1;
+    const int OH = (H + 2 * ph - eh) / sh + 1;
+    const int OW = (W + 2 * pw - ew) / sw + 1;
     long nco;
 #pragma omp parallel for schedule(static)
     for (nco = 0; nco < (long)N * Cout; ++nco) {
@@ -110,8 +111,8 @@ static int conv2d_postloop(const uint16_t *x, const uint16_t *w, uint16_t *y,
                 for (int ci = 0; ci < Cin; ++ci)
                     for (int ky = 0; ky < kh; ++ky)
                         for (int kx = 0; kx < kw; ++kx) {
-                            const int iy = oy * sh + ky - ph;
-                            const int ix = ox * sw + kx - pw;
+                            const int iy = oy * sh + ky * dh - ph;
+                            const int ix = ox * sw + kx * dw - pw;
                             if (iy < 0 || iy >= H || ix < 0 || ix >= W) continue;
                             const double xv = ref_half_to_double(
                                 x[(((size_t)n * Cin + ci) * H + iy) * W + ix]);
@@ -130,7 +131,7 @@ int ref_conv2d(const uint16_t *x, const uint16_t *w, uint16_t *y,
                int N, int Cin, int H, int W, int Cout,
                int kh, int kw, int sh, int sw, int ph, int pw)
 {
-    return conv2d_postloop(x, w, y, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, 0);
+    return conv2d_postloop(x, w, y, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, 1, 1, 0);
 }
 
 /*
@@ -142,7 +143,21 @@ int ref_conv2d_relu(const uint16_t *x, const uint16_t *w, uint16_t *y,
                     int N, int Cin, int H, int W, int Cout,
                     int kh, int kw, int sh, int sw, int ph, int pw)
 {
-    return conv2d_postloop(x, w, y, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, 1);
+    return conv2d_postloop(x, w, y, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, 1, 1, 1);
+}
+
+/*
+ * Dilated form (Section III-C, the example after Eq. 6: I[a1, p2 + 2 a2, p3 + 2 a3]):
+ * window index ky moves dh input rows, kx moves dw input columns,
+ *   x[n, ci, oy*sh + ky*dh - ph, ox*sw + kx*dw - pw];
+ * output extent floor((I + 2 pad - ((k-1) d + 1)) / s) + 1.  relu != 0 selects the clipped
+ * product function.
+ */
+int ref_conv2d_dilated(const uint16_t *x, const uint16_t *w, uint16_t *y,
+                       int N, int Cin, int H, int W, int Cout,
+                       int kh, int kw, int sh, int sw, int ph, int pw, int dh, int dw, int relu)
+{
+    return conv2d_postloop(x, w, y, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw, relu);
 }
 
 /* ------------------------------------------------------------------------ */

@@ -214,3 +214,49 @@ def test_relu_matches_literal_evaluator_and_torch(stride, pad):
     plain = oracle.conv2d(x, w, stride, pad).astype(np.float64)
     assert np.array_equal(got.astype(np.float64), np.maximum(plain, 0.0))
     assert (plain < 0).any() and (plain > 0).any()
+
+
+# ------------------------------------------- dilated window (Section III-C, after Eq. 6)
+def _stuff(w, dh, dw):
+    """The dilated kernel written out: zeros between the taps."""
+    Cout, Cin, kh, kw = w.shape
+    ws = np.zeros((Cout, Cin, (kh - 1) * dh + 1, (kw - 1) * dw + 1), w.dtype)
+    ws[:, :, ::dh, ::dw] = w
+    return ws
+
+
+@pytest.mark.parametrize("dil,stride,pad", [((2, 2), (1, 1), (2, 2)), ((3, 1), (2, 1), (1, 0)), ((1, 4), (1, 2), (0, 5))])
+def test_dilated_equals_plain_conv_with_zero_stuffed_kernel(dil, stride, pad):
+    """Dilation pinned to the already pinned plain convolution: same products, extra zeros."""
+    rng = np.random.default_rng(41)
+    x = _rand_half(rng, (2, 3, 13, 15))
+    w = _rand_half(rng, (4, 3, 3, 3), 0.3)
+    for relu in (False, True):
+        got = oracle.conv2d(x, w, stride, pad, relu=relu, dilation=dil)
+        want = oracle.conv2d(x, _stuff(w, *dil), stride, pad, relu=relu)
+        assert got.shape == want.shape
+        assert np.array_equal(got.view(np.uint16), want.view(np.uint16))
+
+
+def test_dilated_index_expression_of_the_paper():
+    """x = p + 2a with no padding: a one-hot kernel at tap (a2, a3) returns the input shifted
+    by (2 a2, 2 a3), bit-exactly."""
+    rng = np.random.default_rng(42)
+    x = _rand_half(rng, (1, 1, 12, 14))
+    for a2, a3 in ((0, 0), (1, 2), (2, 1)):
+        w = np.zeros((1, 1, 3, 3), np.float16)
+        w[0, 0, a2, a3] = 1.0
+        y = oracle.conv2d(x, w, dilation=(2, 2))
+        assert y.shape == (1, 1, 8, 10)
+        assert np.array_equal(y.view(np.uint16), x[:, :, 2 * a2:2 * a2 + 8, 2 * a3:2 * a3 + 10].view(np.uint16))
+
+
+def test_dilated_matches_literal_evaluator_and_torch():
+    rng = np.random.default_rng(43)
+    x = _rand_half(rng, (1, 4, 11, 12))
+    w = _rand_half(rng, (3, 4, 3, 2), 0.3)
+    got = oracle.conv2d(x, w, (2, 1), (2, 3), dilation=(2, 3))
+    assert np.array_equal(got.view(np.uint16), lit.conv2d(x, w, (2, 1), (2, 3), dilation=(2, 3)).view(np.uint16))
+    ref = torch.nn.functional.conv2d(torch.from_numpy(x.astype(np.float64)), torch.from_numpy(w.astype(np.float64)),
+                                     stride=(2, 1), padding=(2, 3), dilation=(2, 3)).numpy()
+    assert np.allclose(got.astype(np.float64), ref, rtol=2e-3, atol=1e-3)
