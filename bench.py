@@ -131,8 +131,12 @@ def bench_conv(torch, mb, wl, cfg, steps, warmup, nsets, relu=False):
     ns = nsets if (in_bytes + out_bytes) > (8 << 20) else 1
     xs = [x0] + [x0.roll(i, dims=0).contiguous() for i in range(1, ns)]
     ys = [torch.empty((cfg.N, cfg.Cout, cfg.OH, cfg.OW), dtype=torch.float16, device="cuda:0") for _ in range(ns)]
-    make = mb.merit_plan_conv2d_relu if relu else mb.merit_plan_conv2d
-    plan = make(cfg.N, cfg.Cin, cfg.H, cfg.W, cfg.Cout, cfg.kh, cfg.kw, cfg.sh, cfg.sw, cfg.ph, cfg.pw)
+    if (cfg.dh, cfg.dw) != (1, 1):
+        plan = mb.merit_plan_conv2d_dilated(cfg.N, cfg.Cin, cfg.H, cfg.W, cfg.Cout, cfg.kh, cfg.kw, cfg.sh, cfg.sw,
+                                            cfg.ph, cfg.pw, cfg.dh, cfg.dw, int(relu))
+    else:
+        make = mb.merit_plan_conv2d_relu if relu else mb.merit_plan_conv2d
+        plan = make(cfg.N, cfg.Cin, cfg.H, cfg.W, cfg.Cout, cfg.kh, cfg.kw, cfg.sh, cfg.sw, cfg.ph, cfg.pw)
     calls = [mb.bind_conv2d(plan, xs[i], dw, ys[i]) for i in range(ns)]
     wall, ev_ms = timed_region(torch, lambda i: calls[i % ns](), steps, warmup)
     t = ev_ms * 1e-3 / steps
@@ -237,6 +241,7 @@ def main():
             bench_sad(torch, mb, wl, wl.CFG3_ME_FHD, max(10, k // 2), w),
             bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets),
             bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets, relu=True),
+            bench_conv(torch, mb, wl, wl.CFG_DILATED, k, w, args.sets),
         ]
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(wl)

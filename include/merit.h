@@ -92,8 +92,9 @@ typedef struct {
  *   POOL_AVG   F32 EXCLUDE  same
  *   SAD_ARGMIN U8  CLAMP    k=(by,bx | dy,dx,i,j)      a = ref[H,W] (displaced by dy,dx),
  *                                                      b = cur[H,W]
- * with unit stride on window indices (no dilation) and output extents equal to
- * floor((I + 2*pad - k)/s) + 1. */
+ * with output extents equal to floor((I + 2*pad - e)/s) + 1, e = (k-1)*d + 1.  The
+ * strides d of the window indices ky, kx must be 1 for pooling; for the CONV ops they are
+ * the dilation (Section III-C, the example after Eq. 6), up to 16. */
 typedef struct {
     merit_op      op;
     merit_dtype   dtype;
@@ -138,6 +139,11 @@ merit_status merit_plan_conv2d(int N, int Cin, int H, int W, int Cout, int kh, i
  * y = max(sum, 0), clipped before the one rounding to binary16; never -0. */
 merit_status merit_plan_conv2d_relu(int N, int Cin, int H, int W, int Cout, int kh, int kw,
                                     int sh, int sw, int ph, int pw, merit_plan **out);
+/* Dilated window: x[n,ci,oy*sh+ky*dh-ph,ox*sw+kx*dw-pw] (Section III-C, after Eq. 6);
+ * relu != 0 selects the clipped product function. */
+merit_status merit_plan_conv2d_dilated(int N, int Cin, int H, int W, int Cout, int kh, int kw,
+                                       int sh, int sw, int ph, int pw, int dh, int dw, int relu,
+                                       merit_plan **out);
 merit_status merit_plan_pool2d(int N, int C, int H, int W, int kh, int kw,
                                int sh, int sw, int ph, int pw, int is_avg, merit_plan **out);
 merit_status merit_plan_sad(int H, int W, int block, int range, merit_plan **out);

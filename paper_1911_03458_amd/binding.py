@@ -77,6 +77,7 @@ def lib():
     L.merit_plan_destroy.argtypes = [P]
     L.merit_plan_conv2d.argtypes = [c_int] * 11 + [PP]
     L.merit_plan_conv2d_relu.argtypes = [c_int] * 11 + [PP]
+    L.merit_plan_conv2d_dilated.argtypes = [c_int] * 14 + [PP]
     L.merit_plan_pool2d.argtypes = [c_int] * 11 + [PP]
     L.merit_plan_sad.argtypes = [c_int] * 4 + [PP]
     L.merit_plan_get_desc.argtypes = [P, ctypes.POINTER(merit_plan_desc)]
@@ -88,6 +89,7 @@ def lib():
     L.merit_pool2d.argtypes = [P, P, P, P]
     L.merit_sad_search.argtypes = [P, P, P, P, P, P]
     for name in ("merit_plan_create", "merit_plan_destroy", "merit_plan_conv2d", "merit_plan_conv2d_relu",
+                 "merit_plan_conv2d_dilated",
                  "merit_plan_pool2d",
                  "merit_plan_sad", "merit_plan_get_desc", "merit_plan_out_shape", "merit_plan_footprint",
                  "merit_plan_launch_info", "merit_plan_set_tile", "merit_conv2d", "merit_pool2d",
@@ -183,6 +185,13 @@ def merit_plan_conv2d_relu(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw) -> Plan:
     h = ctypes.c_void_p()
     _check(lib().merit_plan_conv2d_relu(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, ctypes.byref(h)),
            "merit_plan_conv2d_relu")
+    return Plan(h)
+
+
+def merit_plan_conv2d_dilated(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw, relu=0) -> Plan:
+    h = ctypes.c_void_p()
+    _check(lib().merit_plan_conv2d_dilated(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw, int(relu),
+                                           ctypes.byref(h)), "merit_plan_conv2d_dilated")
     return Plan(h)
 
 

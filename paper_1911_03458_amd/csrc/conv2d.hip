@@ -1019,7 +1019,7 @@ __global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const 
         const int mlast = min(m0 + p.TM, ohw) - 1;
         const int oyB = (int)fdiv((uint32_t)mlast, p.div_ow);
         const int yA = oyA * p.sh - p.ph;
-        const int RH = (oyB - oyA) * p.sh + p.kh;
+        const int RH = (oyB - oyA) * p.sh + (p.kh - 1) * p.dh + 1;
 
         __syncthreads();
         if (first) {
@@ -1055,13 +1055,13 @@ __global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const 
         int s = 0;
         for (int chip = 0; chip < half_nchi; ++chip)
             for (int ky = 0; ky < p.kh; ++ky) {
-                const int rowoff = (chip * p.RHa + ky) * p.pitch;
+                const int rowoff = (chip * p.RHa + ky * p.dh) * p.pitch;
                 for (int kx = 0; kx < p.kw; ++kx, ++s) {
                     Frag a[CB], b[PXW];
 #pragma unroll
                     for (int cb = 0; cb < CB; ++cb) a[cb].u = wl[(s * CB + cb) * 64 + lane];
 #pragma unroll
-                    for (int pb = 0; pb < PXW; ++pb) b[pb].u = xl[pbase[pb] + rowoff + kx];
+                    for (int pb = 0; pb < PXW; ++pb) b[pb].u = xl[pbase[pb] + rowoff + kx * p.dw];
 #pragma unroll
                     for (int cb = 0; cb < CB; ++cb)
 #pragma unroll

@@ -76,6 +76,7 @@ enum ConvVariant { CONV_PLANAR_SMALLC = 0, CONV_CHBLOCK = 1 };
 struct ConvParams {
     int N, Cin, H, W, Cout, OH, OW;
     int kh, kw, sh, sw, ph, pw;
+    int dh, dw;            // input rows / columns per step of the window indices (dilation)
     int variant;
     int TM;                // output pixels (linear, row-major within an image) per workgroup
     int PXW;               // 32-pixel blocks per wave

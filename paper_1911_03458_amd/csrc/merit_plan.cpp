@@ -246,7 +246,7 @@ merit_status derive_conv(merit_plan *pl)
     if (d.a.ndim != 4 || d.b.ndim != 4) return MERIT_ERR_UNSUPPORTED;
     const int64_t DC = INT64_MIN;
     const int axis_x[7] = {0, MERIT_AXIS_UNUSED, 2, 3, 1, 2, 3};
-    const int64_t stride_x[7] = {1, 0, DC, DC, 1, 1, 1};        // unit window stride: no dilation
+    const int64_t stride_x[7] = {1, 0, DC, DC, 1, DC, DC};      // window strides = dilation
     const int64_t offset_x[7] = {0, 0, 0, 0, 0, DC, DC};
     const int axis_w[7] = {MERIT_AXIS_UNUSED, 0, MERIT_AXIS_UNUSED, MERIT_AXIS_UNUSED, 1, 2, 3};
     const int64_t stride_w[7] = {0, 1, 0, 0, 1, 1, 1};
@@ -257,25 +257,28 @@ merit_status derive_conv(merit_plan *pl)
     const int64_t N = d.a.shape[0], Cin = d.a.shape[1], H = d.a.shape[2], W = d.a.shape[3];
     const int64_t Cout = d.b.shape[0], kh = d.b.shape[2], kw = d.b.shape[3];
     const int64_t sh = d.a.stride[2], sw = d.a.stride[3];
+    const int64_t dh = d.a.stride[5], dw = d.a.stride[6];
     const int64_t ph = -d.a.offset[5], pw = -d.a.offset[6];
     const int64_t OH = d.range[2], OW = d.range[3];
     if (N < 0 || Cin <= 0 || H <= 0 || W <= 0 || Cout <= 0 || kh <= 0 || kw <= 0 || sh <= 0 || sw <= 0 ||
-        ph < 0 || pw < 0)
+        ph < 0 || pw < 0 || dh <= 0 || dw <= 0)
         return MERIT_ERR_INVALID_ARG;
+    const int64_t eh = (kh - 1) * dh + 1, ew = (kw - 1) * dw + 1;      // extent of the dilated window
     if (d.b.shape[1] != Cin || d.range[0] != N || d.range[1] != Cout || d.range[4] != Cin ||
         d.range[5] != kh || d.range[6] != kw)
         return MERIT_ERR_SHAPE;
-    if (H + 2 * ph < kh || W + 2 * pw < kw) return MERIT_ERR_SHAPE;
-    if (OH != out_extent(H, kh, sh, ph) || OW != out_extent(W, kw, sw, pw)) return MERIT_ERR_SHAPE;
+    if (H + 2 * ph < eh || W + 2 * pw < ew) return MERIT_ERR_SHAPE;
+    if (OH != out_extent(H, eh, sh, ph) || OW != out_extent(W, ew, sw, pw)) return MERIT_ERR_SHAPE;
     if (N * Cin * H * W >= (1ll << 40) || OH * OW >= (1 << 24) || Cin > 4096 || Cout > 65535 * 32 ||
-        kh > 31 || kw > 31 || sh > 16 || sw > 16)
+        kh > 31 || kw > 31 || sh > 16 || sw > 16 || dh > 16 || dw > 16)
         return MERIT_ERR_UNSUPPORTED;
+    const bool dilated = dh != 1 || dw != 1;
 
     ConvParams &p = pl->conv;
     p.N = (int)N; p.Cin = (int)Cin; p.H = (int)H; p.W = (int)W; p.Cout = (int)Cout;
     p.relu = d.op == MERIT_OP_CONV_DOT_RELU ? 1 : 0;
     p.OH = (int)OH; p.OW = (int)OW; p.kh = (int)kh; p.kw = (int)kw; p.sh = (int)sh; p.sw = (int)sw;
-    p.ph = (int)ph; p.pw = (int)pw;
+    p.ph = (int)ph; p.pw = (int)pw; p.dh = (int)dh; p.dw = (int)dw;
 
     const int64_t ohw = OH * OW;
     const int64_t ncb = cdiv(Cout, 32);
@@ -293,9 +296,9 @@ merit_status derive_conv(merit_plan *pl)
         q.tiles_per_image = (int)cdiv(ohw, q.TM);
         q.rows_out_max = (int)((q.TM + OW - 2) / OW + 1);
         if (q.rows_out_max > OH) q.rows_out_max = (int)OH;
-        q.RHa = (int)((q.rows_out_max - 1) * sh + kh);
+        q.RHa = (int)((q.rows_out_max - 1) * sh + eh);
         if (variant == CONV_PLANAR_SMALLC) {
-            if (kw > 8 || pw > 8) return false;
+            if (kw > 8 || pw > 8 || dilated) return false;       // its fragments are runs of adjacent taps
             q.padl = 8;
             // with an even column stride every window starts on the same column parity; if that
             // parity is odd and a slot is free, start the fragment one column earlier (front = 1)
@@ -325,7 +328,7 @@ merit_status derive_conv(merit_plan *pl)
             q.nchi = (int)(cdiv(Cin, 16) * 2);
             q.padl = (int)pw;
             int64_t pitch = q.padl + W;
-            const int64_t reach = (OW - 1) * sw + kw;
+            const int64_t reach = (OW - 1) * sw + ew;
             if (reach > pitch) pitch = reach;
             q.pitch = (int)pitch;
             q.G = q.G2 = 0;
@@ -479,22 +482,23 @@ merit_status merit_plan_destroy(merit_plan *plan)
 }  // extern "C"
 
 static merit_status plan_conv2d_op(merit_op op, int N, int Cin, int H, int W, int Cout, int kh, int kw, int sh,
-                                   int sw, int ph, int pw, merit_plan **out)
+                                   int sw, int ph, int pw, int dh, int dw, merit_plan **out)
 {
     if (!out) return MERIT_ERR_NULL;
     *out = nullptr;
     if (N < 0 || Cin <= 0 || H <= 0 || W <= 0 || Cout <= 0 || kh <= 0 || kw <= 0 || sh <= 0 || sw <= 0 ||
-        ph < 0 || pw < 0)
+        ph < 0 || pw < 0 || dh <= 0 || dw <= 0)
         return MERIT_ERR_INVALID_ARG;
-    if (H + 2 * ph < kh || W + 2 * pw < kw) return MERIT_ERR_SHAPE;
+    const int64_t eh = ((int64_t)kh - 1) * dh + 1, ew = ((int64_t)kw - 1) * dw + 1;
+    if (H + 2 * ph < eh || W + 2 * pw < ew) return MERIT_ERR_SHAPE;
     merit_plan_desc d;
     std::memset(&d, 0, sizeof(d));
     d.op = op; d.dtype = MERIT_F16; d.pad = MERIT_PAD_ZERO;
     d.n_par = 4; d.n_acc = 3;
-    const int64_t OH = out_extent(H, kh, sh, ph), OW = out_extent(W, kw, sw, pw);
+    const int64_t OH = out_extent(H, eh, sh, ph), OW = out_extent(W, ew, sw, pw);
     const int64_t range[7] = {N, Cout, OH, OW, Cin, kh, kw};
     const int ax[7] = {0, MERIT_AXIS_UNUSED, 2, 3, 1, 2, 3};
-    const int64_t sx[7] = {1, 0, sh, sw, 1, 1, 1};
+    const int64_t sx[7] = {1, 0, sh, sw, 1, dh, dw};
     const int64_t ox[7] = {0, 0, 0, 0, 0, -ph, -pw};
     const int aw[7] = {MERIT_AXIS_UNUSED, 0, MERIT_AXIS_UNUSED, MERIT_AXIS_UNUSED, 1, 2, 3};
     const int64_t sw_[7] = {0, 1, 0, 0, 1, 1, 1};
@@ -513,13 +517,20 @@ extern "C" {
 merit_status merit_plan_conv2d(int N, int Cin, int H, int W, int Cout, int kh, int kw, int sh, int sw,
                                int ph, int pw, merit_plan **out)
 {
-    return plan_conv2d_op(MERIT_OP_CONV_DOT, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, out);
+    return plan_conv2d_op(MERIT_OP_CONV_DOT, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, 1, 1, out);
 }
 
 merit_status merit_plan_conv2d_relu(int N, int Cin, int H, int W, int Cout, int kh, int kw, int sh, int sw,
                                     int ph, int pw, merit_plan **out)
 {
-    return plan_conv2d_op(MERIT_OP_CONV_DOT_RELU, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, out);
+    return plan_conv2d_op(MERIT_OP_CONV_DOT_RELU, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, 1, 1, out);
+}
+
+merit_status merit_plan_conv2d_dilated(int N, int Cin, int H, int W, int Cout, int kh, int kw, int sh, int sw,
+                                       int ph, int pw, int dh, int dw, int relu, merit_plan **out)
+{
+    return plan_conv2d_op(relu ? MERIT_OP_CONV_DOT_RELU : MERIT_OP_CONV_DOT, N, Cin, H, W, Cout, kh, kw, sh, sw, ph,
+                          pw, dh, dw, out);
 }
 
 merit_status merit_plan_pool2d(int N, int C, int H, int W, int kh, int kw, int sh, int sw, int ph, int pw,

@@ -86,14 +86,16 @@ class ConvWorkload:
     ph: int
     pw: int
     x_dist: str          # "normal" or "uniform"
+    dh: int = 1          # dilation: input rows / columns per window step
+    dw: int = 1
 
     @property
     def OH(self):
-        return (self.H + 2 * self.ph - self.kh) // self.sh + 1
+        return (self.H + 2 * self.ph - ((self.kh - 1) * self.dh + 1)) // self.sh + 1
 
     @property
     def OW(self):
-        return (self.W + 2 * self.pw - self.kw) // self.sw + 1
+        return (self.W + 2 * self.pw - ((self.kw - 1) * self.dw + 1)) // self.sw + 1
 
 
 CFG0_ME_SMALL = SadWorkload("me_64x64_b8_r4", 64, 64, 8, 4, 3, "uniform")
@@ -103,6 +105,10 @@ CFG3_ME_FHD = SadWorkload("me_1920x1088_b16_r32", 1088, 1920, 16, 32, 0, "sinuso
 CFG4_CONV7 = ConvWorkload("conv_32x3x224x224_co64_k7s2p3", 32, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3, "uniform")
 
 CONFIGS = [CFG0_ME_SMALL, CFG1_POOL, CFG2_CONV3, CFG3_ME_FHD, CFG4_CONV7]
+
+# Beyond the five configurations: the dilated layer of the paper's table of further workloads
+# (output 64 x 64 x 32; channel count and batch are not given there: 32 in, batch 8 here).
+CFG_DILATED = ConvWorkload("conv_8x32x64x64_co32_k3s1p2_d2", 8, 32, 64, 64, 32, 3, 3, 1, 1, 2, 2, "normal", 2, 2)
 
 
 # --------------------------------------------------------------------------
@@ -174,7 +180,7 @@ def make_pool_input(wl: PoolWorkload, seed: int | None = None, N: int | None = N
 def make_conv_inputs(wl: ConvWorkload, seed: int | None = None, N: int | None = None):
     """Return (x fp16 NCHW, w fp16 OIHW).  Weights are N(0, 1/(Cin*kh*kw))."""
     if seed is None:
-        seed = BASE_SEED + (CONFIGS.index(wl) if wl in CONFIGS else 2)
+        seed = BASE_SEED + (CONFIGS.index(wl) if wl in CONFIGS else 5)
     rng = np.random.default_rng(seed)
     n = wl.N if N is None else N
     shape = (n, wl.Cin, wl.H, wl.W)

@@ -73,6 +73,20 @@ def test_relu_plan_differs_only_in_the_product_function():
         mb.merit_plan_create(db)
 
 
+def test_dilated_plan_is_the_papers_expression():
+    """I[a1, p2 + 2 a2, p3 + 2 a3] (Section III-C): stride 2 on the window indices."""
+    plan = mb.merit_plan_conv2d_dilated(1, 32, 64, 64, 32, 3, 3, 1, 1, 2, 2, 2, 2, 0)
+    d = plan.desc()
+    ranges, n_par, tx, tw = lit.conv2d_desc(1, 32, 64, 64, 32, 3, 3, 1, 1, 2, 2, 2, 2)
+    assert tuple(d.range[:7]) == ranges and plan.out_shape() == (1, 32, 64, 64)
+    assert (d.a.stride[5], d.a.stride[6], d.a.offset[5], d.a.offset[6]) == (2, 2, -2, -2)
+    assert plan.launch_info()["kernel"] == "merit_conv2d_chblock"
+    assert plan.footprint(0, (1, 1, 8, 8, 32, 3, 3)) == lit.footprint((1, 1, 8, 8, 32, 3, 3), tx, 4)
+    # few input channels: the adjacent-tap kernels do not apply, the channel-block one does
+    assert mb.merit_plan_conv2d_dilated(2, 3, 32, 32, 8, 3, 3, 1, 1, 2, 2, 2, 2, 1).launch_info()["kernel"] == \
+        "merit_conv2d_chblock"
+
+
 def test_pool_and_sad_plan_descriptors():
     plan = mb.merit_plan_pool2d(16, 64, 112, 112, 3, 3, 2, 2, 1, 1, 0)
     d = plan.desc()
@@ -151,11 +165,21 @@ def test_invalid_arguments_are_rejected():
 def test_generic_descriptor_patterns():
     d = mb.merit_plan_conv2d(1, 8, 16, 16, 8, 3, 3, 1, 1, 1, 1).desc()
     assert mb.merit_plan_create(d).out_shape() == (1, 8, 16, 16)
-    d.a.stride[5] = 2                                # dilation on the window row index
+    d.a.stride[5] = 2                                # dilation on the window row index ...
     with pytest.raises(mb.MeritError) as e:
         mb.merit_plan_create(d)
-    assert e.value.status == mb.MERIT_ERR_UNSUPPORTED
+    assert e.value.status == mb.MERIT_ERR_SHAPE      # ... shrinks the output: (16 + 2 - 5) + 1
+    d.range[2] = 14
+    plan = mb.merit_plan_create(d)
+    assert plan.out_shape() == (1, 8, 14, 16) and plan.launch_info()["kernel"] == "merit_conv2d_chblock"
+    assert plan.footprint(0, (1, 1, 4, 4, 8, 3, 3))[2:] == (8, 6)   # rows 1 + 3 + 2*2, columns 1 + 3 + 2
     d.a.stride[5] = 1
+    d.range[2] = 16
+    dp = mb.merit_plan_pool2d(1, 1, 16, 16, 3, 3, 2, 2, 1, 1, 0).desc()
+    dp.a.stride[4] = 2                               # pooling windows are not dilated here
+    with pytest.raises(mb.MeritError) as e:
+        mb.merit_plan_create(dp)
+    assert e.value.status == mb.MERIT_ERR_UNSUPPORTED
     d.range[2] = 17                                  # output extent that the input cannot supply
     with pytest.raises(mb.MeritError) as e:
         mb.merit_plan_create(d)

@@ -200,11 +200,14 @@ def test_sad_full_hd_workload(mb):
 
 
 # ------------------------------------------------------------- convolution
-def _conv_check(mb, x, w, stride, pad, tile=None, relu=False):
+def _conv_check(mb, x, w, stride, pad, tile=None, relu=False, dilation=(1, 1)):
     N, Cin, H, W = x.shape
     Cout, _, kh, kw = w.shape
-    make = mb.merit_plan_conv2d_relu if relu else mb.merit_plan_conv2d
-    plan = make(N, Cin, H, W, Cout, kh, kw, *stride, *pad)
+    if dilation != (1, 1):
+        plan = mb.merit_plan_conv2d_dilated(N, Cin, H, W, Cout, kh, kw, *stride, *pad, *dilation, int(relu))
+    else:
+        make = mb.merit_plan_conv2d_relu if relu else mb.merit_plan_conv2d
+        plan = make(N, Cin, H, W, Cout, kh, kw, *stride, *pad)
     if tile is not None:
         plan.set_tile(tile)
     print("conv", x.shape, w.shape, stride, pad, plan.launch_info(), flush=True)
@@ -213,7 +216,7 @@ def _conv_check(mb, x, w, stride, pad, tile=None, relu=False):
     torch.cuda.synchronize()
     check_canary(buf, p, 777.0)
     got = y.cpu().numpy().astype(np.float64)
-    ref = oracle.conv2d(x, w, stride, pad, relu=relu).astype(np.float64)
+    ref = oracle.conv2d(x, w, stride, pad, relu=relu, dilation=dilation).astype(np.float64)
     assert got.shape == ref.shape
     if relu:                                       # clipped at +0: no negative value, no -0
         assert not np.signbit(got).any()
@@ -338,6 +341,37 @@ def test_conv_7x7_workload_relu_sampled(mb):
     plain = mb.merit_conv2d(mb.merit_plan_conv2d(c.N, c.Cin, c.H, c.W, c.Cout, c.kh, c.kw, c.sh, c.sw, c.ph, c.pw),
                             dev(x), dev(w))
     assert torch.equal(y, torch.clamp_min(plain, 0.0) + 0.0)      # same products, clipped; "+ 0.0" folds -0
+
+
+DILATED_CASES = [
+    # N Cin H   W  Cout kh kw sh sw ph pw dh dw relu
+    (1, 32, 64, 64, 32, 3, 3, 1, 1, 2, 2, 2, 2, 0),   # the dilated layer of the paper's table: 64x64x32 out
+    (2, 16, 21, 19, 40, 3, 3, 1, 1, 2, 2, 2, 2, 1),   # odd sizes, ragged channels, clipped product
+    (1, 64, 30, 34, 64, 3, 3, 2, 1, 3, 0, 3, 1, 0),   # mixed dilation and stride
+    (2, 3, 33, 40, 8, 3, 3, 1, 1, 2, 2, 2, 2, 0),     # few input channels (padded to 16)
+    (1, 8, 18, 24, 16, 2, 5, 1, 2, 0, 4, 4, 2, 0),    # even window, wide dilation
+]
+
+
+@pytest.mark.parametrize("case", DILATED_CASES)
+def test_conv_dilated(mb, case):
+    N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw, relu = case
+    rng = np.random.default_rng(abs(hash(case)) % 2 ** 31)
+    x = rng.standard_normal((N, Cin, H, W)).astype(np.float16)
+    w = (rng.standard_normal((Cout, Cin, kh, kw)) / np.sqrt(Cin * kh * kw)).astype(np.float16)
+    _conv_check(mb, x, w, (sh, sw), (ph, pw), relu=bool(relu), dilation=(dh, dw))
+
+
+def test_conv_dilated_one_hot_tap_shifts_the_input_exactly(mb):
+    """x = p + 2a (Section III-C): a one-hot kernel returns the input shifted by twice the tap."""
+    rng = np.random.default_rng(6)
+    C = 16
+    x = rng.standard_normal((1, C, 20, 24)).astype(np.float16)
+    w = np.zeros((C, C, 3, 3), np.float16)
+    for c in range(C):
+        w[c, c, 2, 1] = 1.0
+    got, ref = _conv_check(mb, x, w, (1, 1), (0, 0), dilation=(2, 2))
+    assert np.array_equal(got, x[:, :, 4:4 + 16, 2:2 + 20].astype(np.float64))
 
 
 def test_conv_identity_kernel_is_exact(mb):
