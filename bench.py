@@ -239,6 +239,7 @@ def main():
             bench_sad(torch, mb, wl, wl.CFG0_ME_SMALL, k, w),
             bench_conv(torch, mb, wl, wl.CFG2_CONV3, k, w, args.sets),
             bench_sad(torch, mb, wl, wl.CFG3_ME_FHD, max(10, k // 2), w),
+            bench_sad(torch, mb, wl, wl.CFG_ME_720P, k, w),
             bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets),
             bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets, relu=True),
             bench_conv(torch, mb, wl, wl.CFG_DILATED, k, w, args.sets),

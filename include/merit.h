@@ -166,7 +166,8 @@ merit_status merit_plan_launch_info(const merit_plan *plan, merit_launch_info *o
  * tile[3] = consecutive output pixels per multiplying wavefront (32 or 64),
  * where 8 x 64 means 4 multiplying + 4 data-moving wavefronts (256 pixels per
  * workgroup) and every other pair tile[2]*tile[3] pixels; block matching
- * tile[1] = blocks per workgroup.  On error the plan is unchanged.  Not safe to
+ * tile[1] = blocks per workgroup (1, 4 or 8; a value the shape has no kernel for
+ * keeps the library's choice).  On error the plan is unchanged.  Not safe to
  * call while another thread launches with the same plan. */
 merit_status merit_plan_set_tile(merit_plan *plan, const int64_t tile[MERIT_MAX_INDEX]);
 

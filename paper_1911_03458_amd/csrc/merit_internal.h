@@ -55,7 +55,7 @@ struct PoolParams {
 };
 
 // ---- block matching --------------------------------------------------------
-enum SadVariant { SAD_GENERIC = 0, SAD_ROWSCAN_B16 = 1 };
+enum SadVariant { SAD_GENERIC = 0, SAD_ROWSCAN_B16 = 1, SAD_ROWSCAN_PAIR = 2 };
 
 struct SadParams {
     int H, W, B, R, n;     // n = 2R+1 candidates per axis

@@ -226,6 +226,23 @@ merit_status derive_sad(merit_plan *pl)
         }
     }
 
+    // two blocks per wavefront, eight per workgroup: 8x8 blocks with R = 8 or 16, 16x16 blocks
+    // with R = 16 (a tile request of four blocks per workgroup keeps the one-block-per-wavefront
+    // kernel there)
+    if (((B == 8 && (R == 8 || R == 16)) || (B == 16 && R == 16)) && pl->tile_req[1] != 1 && pl->tile_req[1] != 4) {
+        const int64_t c4 = cdiv(8 * B + 2 * R, 4);
+        if (fastdiv_ok((B + 2 * R) * c4, c4)) {
+            p.variant = SAD_ROWSCAN_PAIR;
+            p.bpw = 8;
+            p.groups_x = (int)cdiv(p.nbx, 8);
+            p.pitch = (int)((c4 + 1) * 4);
+            p.div_win4 = make_fastdiv((uint32_t)c4);
+            grid = (int64_t)p.nby * p.groups_x;
+            lds = ((B + 2 * R) * (c4 + 1) + 1) * 4;
+            tile_bx = 8;
+        }
+    }
+
     pl->out_ndim = 2;
     pl->out_shape[0] = p.nby; pl->out_shape[1] = p.nbx;
     merit_launch_info &li = pl->info;

@@ -287,6 +287,156 @@ __global__ __launch_bounds__(256) void merit_sad_rowscan16(SadParams p, const ui
 }
 
 // ---------------------------------------------------------------------------
+// Row-scan kernel, two blocks per wavefront: for search ranges whose 2R+1 candidate columns
+// fill only half a wavefront (R <= 19), each 32-lane half owns one block, so a workgroup
+// covers eight horizontally adjacent blocks.  The walk over the window rows is the one
+// described above with B block rows and B rotating accumulators; the current block lives
+// in vector registers (it differs between the halves).  Columns beyond the 32nd are run
+// one candidate per lane.  B = 8 or 16.
+// ---------------------------------------------------------------------------
+template <int B4>
+__device__ __forceinline__ void load_aligned_row(const uint32_t *rowp, uint32_t sh, uint32_t (&r)[B4])
+{
+    uint32_t d[B4 + 1];
+#pragma unroll
+    for (int j = 0; j <= B4; ++j) d[j] = rowp[j];
+#pragma unroll
+    for (int j = 0; j < B4; ++j) r[j] = __builtin_amdgcn_alignbyte(d[j + 1], d[j], sh);
+}
+
+// min over each 32-lane half of a wavefront; valid in lanes 31 and 63
+__device__ __forceinline__ uint32_t half_wave_min_u32(uint32_t v)
+{
+    v = dpp_min_step<0xB1, 0xf>(v);    // quad_perm [1,0,3,2]
+    v = dpp_min_step<0x4E, 0xf>(v);    // quad_perm [2,3,0,1]
+    v = dpp_min_step<0x141, 0xf>(v);   // row_half_mirror
+    v = dpp_min_step<0x140, 0xf>(v);   // row_mirror: every lane holds its row's min
+    v = dpp_min_step<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
+    return v;
+}
+
+template <int B, int R>
+__global__ __launch_bounds__(256) void merit_sad_rowscan_pair(SadParams p, const uint8_t *__restrict__ cur,
+                                                             const uint8_t *__restrict__ ref,
+                                                             int32_t *__restrict__ sad, int32_t *__restrict__ mv)
+{
+    static_assert(B == 8 || B == 16, "accumulator rotation needs a power of two");
+    static_assert(2 * R >= B - 1 && 2 * R + 1 <= 40, "steady state needs 2R >= B-1; at most 8 extra columns");
+    constexpr int N = 2 * R + 1, ROWS = B + 2 * R, B4 = B / 4;
+    constexpr int NMAIN = N < 32 ? N : 32;          // candidate columns that are lane columns
+    constexpr int NLEFT = N - NMAIN;                // the rest: one candidate per lane
+    constexpr int NS = 2 * R - B + 2, NSB = NS / B, NSR = NS % B;   // rows B-1 .. 2R use all B block rows
+
+    extern __shared__ __align__(16) uint32_t lds32[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, l32 = lane & 31, hb = lane >> 5;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int pitch4 = p.pitch >> 2;
+    const uint32_t g = blockIdx.x;
+    const int by = (int)(g / (uint32_t)p.groups_x);
+    const int bx0 = (int)(g - (uint32_t)by * p.groups_x) * 8;
+
+    stage_window(p, ref, lds32, by * B - R, bx0 * B - R, ROWS, pitch4 - 1, p.div_win4, pitch4, tid, 256);
+    __syncthreads();
+    const int bxl = 2 * wv + hb;                    // block inside the workgroup's window
+    const int bx = bx0 + bxl;
+    const bool live = bx < p.nbx;                   // ragged last group: the half computes, nothing is written
+
+    uint32_t c[B][B4];
+    {
+        const uint32_t *cp = reinterpret_cast<const uint32_t *>(cur + (size_t)(by * B) * p.W + min(bx, p.nbx - 1) * B);
+        const int W4 = p.W >> 2;
+#pragma unroll
+        for (int i = 0; i < B; ++i)
+#pragma unroll
+            for (int j = 0; j < B4; ++j) c[i][j] = cp[i * W4 + j];
+    }
+
+    uint32_t best = 0xffffffffu;                    // (sad << 14) | raster index
+    {
+        const int dxi = l32;
+        const int o = B * bxl + min(dxi, NMAIN - 1);          // idle lanes repeat the last column
+        const uint32_t sh = (uint32_t)(o & 3);
+        const uint32_t *base = lds32 + (o >> 2);
+        uint32_t acc[B];
+#pragma unroll
+        for (int k = 0; k < B; ++k) acc[k] = 0;
+        uint32_t lbest = 0xffffffffu;               // (sad << 7) | (dy + R)
+
+        auto step = [&](const uint32_t *rowp, int ilo, int ihi, int rot, int fin) __attribute__((always_inline)) {
+            uint32_t r4[B4];
+            load_aligned_row<B4>(rowp, sh, r4);
+#pragma unroll
+            for (int i = 0; i < B; ++i) {
+                if (i < ilo || i > ihi) continue;
+                const int slot = (rot - i) & (B - 1);
+#pragma unroll
+                for (int j = 0; j < B4; ++j) acc[slot] = __builtin_amdgcn_sad_u8(c[i][j], r4[j], acc[slot]);
+            }
+            if (fin >= 0) {
+                const int slot = (rot + 1) & (B - 1);
+                const uint32_t key = (acc[slot] << 7) | (uint32_t)fin;
+                lbest = key < lbest ? key : lbest;
+                acc[slot] = 0;
+            }
+        };
+
+#pragma unroll
+        for (int r = 0; r < B - 1; ++r) step(base + r * pitch4, 0, r, r, -1);
+#pragma unroll 1
+        for (int k = 0; k < NSB; ++k) {
+            const uint32_t *rp = base + (B - 1 + B * k) * pitch4;
+#pragma unroll
+            for (int j = 0; j < B; ++j) step(rp + j * pitch4, 0, B - 1, (B - 1 + j) & (B - 1), B * k + j);
+        }
+#pragma unroll
+        for (int j = 0; j < NSR; ++j)
+            step(base + (B - 1 + B * NSB + j) * pitch4, 0, B - 1, (B - 1 + j) & (B - 1), B * NSB + j);
+#pragma unroll
+        for (int e = 1; e <= B - 1; ++e)
+            step(base + (2 * R + e) * pitch4, e, B - 1, (2 * R + e) & (B - 1), 2 * R + e - (B - 1));
+
+        if (dxi < NMAIN) {
+            const uint32_t dyi = lbest & 127u;
+            best = ((lbest >> 7) << KEY_SHIFT) | (dyi * (uint32_t)N + (uint32_t)dxi);
+        }
+    }
+
+    if (NLEFT > 0) {
+        constexpr int NCAND = NLEFT * N;
+#pragma unroll 1
+        for (int c0 = 0; c0 < NCAND; c0 += 32) {
+            const int cand = min(c0 + l32, NCAND - 1);         // idle lanes recompute the last candidate
+            const int dyi = cand / NLEFT;
+            const int dxi = NMAIN + (cand - dyi * NLEFT);
+            const int o = B * bxl + dxi;
+            const uint32_t sh = (uint32_t)(o & 3);
+            const uint32_t *base = lds32 + dyi * pitch4 + (o >> 2);
+            uint32_t a = 0;
+#pragma unroll
+            for (int i = 0; i < B; ++i) {
+                uint32_t r4[B4];
+                load_aligned_row<B4>(base + i * pitch4, sh, r4);
+#pragma unroll
+                for (int j = 0; j < B4; ++j) a = __builtin_amdgcn_sad_u8(c[i][j], r4[j], a);
+            }
+            const uint32_t key = (a << KEY_SHIFT) | (uint32_t)(dyi * N + dxi);
+            best = key < best ? key : best;
+        }
+    }
+
+    best = half_wave_min_u32(best);
+    if (l32 == 31 && live) {
+        const uint32_t blk = (uint32_t)by * p.nbx + bx;
+        const uint32_t cidx = best & KEY_MASK;
+        const int dyi = (int)(cidx / (uint32_t)N);
+        sad[blk] = (int32_t)(best >> KEY_SHIFT);
+        mv[2 * blk + 0] = dyi - R;
+        mv[2 * blk + 1] = (int)cidx - dyi * N - R;
+    }
+}
+
+// ---------------------------------------------------------------------------
 hipError_t launch_sad(const SadParams &p, const uint8_t *cur, const uint8_t *ref, int32_t *sad,
                       int32_t *mv, hipStream_t s)
 {
@@ -302,6 +452,19 @@ hipError_t launch_sad(const SadParams &p, const uint8_t *cur, const uint8_t *ref
             hipLaunchKernelGGL(merit_sad_rowscan16<16>, dim3(grid), dim3(256), lds_bytes, s, p, cur, ref, sad, mv);
         return hipGetLastError();
     }
+    if (p.variant == SAD_ROWSCAN_PAIR) {
+        const uint32_t grid = (uint32_t)(p.nby * p.groups_x);
+        const size_t lds_bytes = (size_t)((p.B + 2 * p.R) * pitch4 + 1) * 4;
+        if (p.B == 8 && p.R == 16)
+            hipLaunchKernelGGL((merit_sad_rowscan_pair<8, 16>), dim3(grid), dim3(256), lds_bytes, s, p, cur, ref, sad, mv);
+        else if (p.B == 8 && p.R == 8)
+            hipLaunchKernelGGL((merit_sad_rowscan_pair<8, 8>), dim3(grid), dim3(256), lds_bytes, s, p, cur, ref, sad, mv);
+        else if (p.B == 16 && p.R == 16)
+            hipLaunchKernelGGL((merit_sad_rowscan_pair<16, 16>), dim3(grid), dim3(256), lds_bytes, s, p, cur, ref, sad, mv);
+        else
+            return hipErrorInvalidValue;
+        return hipGetLastError();
+    }
     const size_t lds_bytes = (size_t)(p.win * pitch4 + 1 + p.B * (p.B >> 2) + 4) * 4;
     hipLaunchKernelGGL(merit_sad_generic, dim3(nblocks), dim3(256), lds_bytes, s, p, cur, ref, sad, mv);
     return hipGetLastError();
@@ -310,6 +473,8 @@ hipError_t launch_sad(const SadParams &p, const uint8_t *cur, const uint8_t *ref
 const char *sad_kernel_name(const SadParams &p)
 {
     if (p.variant == SAD_ROWSCAN_B16) return p.R == 32 ? "merit_sad_rowscan16<32>" : "merit_sad_rowscan16<16>";
+    if (p.variant == SAD_ROWSCAN_PAIR)
+        return p.B == 16 ? "merit_sad_rowscan_pair<16,16>" : (p.R == 16 ? "merit_sad_rowscan_pair<8,16>" : "merit_sad_rowscan_pair<8,8>");
     return "merit_sad_generic";
 }
 

@@ -106,8 +106,10 @@ CFG4_CONV7 = ConvWorkload("conv_32x3x224x224_co64_k7s2p3", 32, 3, 224, 224, 64, 
 
 CONFIGS = [CFG0_ME_SMALL, CFG1_POOL, CFG2_CONV3, CFG3_ME_FHD, CFG4_CONV7]
 
-# Beyond the five configurations: the dilated layer of the paper's table of further workloads
+# Beyond the five configurations: the motion-estimation row of the paper's table of further
+# workloads (720p, 8x8 blocks; the search range is not given there: +-16 here), and the dilated layer of the paper's table of further workloads
 # (output 64 x 64 x 32; channel count and batch are not given there: 32 in, batch 8 here).
+CFG_ME_720P = SadWorkload("me_1280x720_b8_r16", 720, 1280, 8, 16, 0, "sinusoid")
 CFG_DILATED = ConvWorkload("conv_8x32x64x64_co32_k3s1p2_d2", 8, 32, 64, 64, 32, 3, 3, 1, 1, 2, 2, "normal", 2, 2)
 
 
@@ -143,7 +145,7 @@ def make_sad_frames(wl: SadWorkload, seed: int | None = None):
     planted[by, bx] = (vy, vx), drawn uniformly from [-R, R]^2.
     """
     if seed is None:
-        seed = BASE_SEED + CONFIGS.index(wl) if wl in CONFIGS else BASE_SEED
+        seed = BASE_SEED + (CONFIGS.index(wl) if wl in CONFIGS else 6)
     rng = np.random.default_rng(seed)
     H, W, B, R = wl.H, wl.W, wl.block, wl.search
     if wl.texture == "uniform":

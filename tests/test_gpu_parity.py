@@ -144,7 +144,9 @@ def _sad_check(mb, cur, ref, B, R, tile=None):
 SAD_CASES = [(16, 16, 4, 2), (32, 48, 8, 4), (24, 40, 8, 3), (64, 96, 16, 8), (32, 32, 16, 5),
              (48, 64, 16, 32), (8, 8, 8, 1), (40, 24, 4, 0), (64, 64, 32, 3),
              # row-scan kernel (16x16 blocks, R = 16 / 32): ragged last group of blocks, one block row
-             (64, 96, 16, 16), (80, 112, 16, 32), (16, 16, 16, 32), (32, 80, 16, 16)]
+             (64, 96, 16, 16), (80, 112, 16, 32), (16, 16, 16, 32), (32, 80, 16, 16),
+             # two blocks per wavefront (8x8 blocks, R = 8 / 16): full and ragged groups of eight blocks
+             (32, 64, 8, 16), (24, 88, 8, 16), (8, 8, 8, 16), (40, 72, 8, 8), (16, 136, 8, 8)]
 
 
 @pytest.mark.parametrize("H,W,B,R", SAD_CASES)
@@ -177,6 +179,43 @@ def test_sad_generic_kernel_on_rowscan_shape(mb):
     ref = rng.integers(0, 256, size=(48, 64), dtype=np.uint8)
     _sad_check(mb, cur, ref, 16, 32, tile=(0, 1))
     _sad_check(mb, cur & 0x1, ref & 0x1, 16, 32)
+
+
+def test_sad_pair_kernel(mb):
+    """The two-blocks-per-wavefront kernel: the default for 8x8 blocks and for 16x16 blocks
+    with R = 16 (four blocks per workgroup keep the one-block-per-wavefront kernel there);
+    ties and clamping included."""
+    assert mb.merit_plan_sad(720, 1280, 8, 16).launch_info()["kernel"] == "merit_sad_rowscan_pair<8,16>"
+    assert mb.merit_plan_sad(64, 64, 16, 16).launch_info()["kernel"] == "merit_sad_rowscan_pair<16,16>"
+    rng = np.random.default_rng(22)
+    cur = rng.integers(0, 256, size=(48, 208), dtype=np.uint8)
+    ref = rng.integers(0, 256, size=(48, 208), dtype=np.uint8)
+    _sad_check(mb, cur, ref, 16, 16)
+    _sad_check(mb, cur & 0x1, ref & 0x1, 16, 16)
+    plan = mb.merit_plan_sad(48, 208, 16, 16)
+    plan.set_tile((0, 4))
+    assert plan.launch_info()["kernel"] == "merit_sad_rowscan16<16>"
+    _sad_check(mb, cur, ref, 16, 16, tile=(0, 4))
+    _sad_check(mb, cur & 0x1, ref & 0x1, 16, 16, tile=(0, 4))
+    _sad_check(mb, cur, ref, 8, 16, tile=(0, 1))            # generic kernel on the same frames
+    const = np.full((16, 64), 200, np.uint8)
+    _sad_check(mb, const, const, 8, 16)                     # every candidate ties: (-R,-R)
+    rows = np.tile(rng.permutation(256)[:64].astype(np.uint8), (16, 1))
+    _sad_check(mb, rows, rows, 8, 16)                       # all dy tie
+    _sad_check(mb, np.ascontiguousarray(rows[:, :16].T.repeat(4, 1)), np.ascontiguousarray(rows[:, :16].T.repeat(4, 1)), 8, 8)
+
+
+def test_sad_720p_workload(mb):
+    c = wl.CFG_ME_720P
+    cur, ref, planted = wl.make_sad_frames(c)
+    plan = mb.merit_plan_sad(c.H, c.W, c.block, c.search)
+    print("sad 720p", plan.launch_info(), flush=True)
+    sad, mv = mb.merit_sad_search(plan, dev(cur), dev(ref))
+    sad, mv = sad.cpu().numpy(), mv.cpu().numpy()
+    assert sad.shape == (90, 160) and np.all(sad == 0)      # planted copies are exact
+    osad, omv = oracle.sad_search(cur, ref, c.block, c.search)
+    assert np.array_equal(sad, osad)
+    assert np.array_equal(mv, omv)
 
 
 def test_sad_cfg0(mb):
