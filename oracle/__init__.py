@@ -51,6 +51,8 @@ def _load():
     lib.ref_conv2d.argtypes = [vp, vp, vp] + [c_int] * 11
     lib.ref_conv2d_relu.restype = c_int
     lib.ref_conv2d_relu.argtypes = [vp, vp, vp] + [c_int] * 11
+    lib.ref_correlation.restype = c_int
+    lib.ref_correlation.argtypes = [vp, vp, vp] + [c_int] * 6
     lib.ref_conv2d_dilated.restype = c_int
     lib.ref_conv2d_dilated.argtypes = [vp, vp, vp] + [c_int] * 14
     lib.ref_pool2d.restype = c_int
@@ -122,6 +124,21 @@ def conv2d(x: np.ndarray, w: np.ndarray, stride=(1, 1), pad=(0, 0), relu=False, 
                                         dh, dw, 1 if relu else 0)
     if rc != 0:
         raise ValueError("ref_conv2d: bad shape")
+    return y
+
+
+def correlation(x1: np.ndarray, x2: np.ndarray, search: int, stride: int = 1) -> np.ndarray:
+    """Correlation layer (Section III-C, Eq. 8): x1, x2 fp16 [N,C,H,W] -> fp16 [N,H,W,n,n],
+    n = 2*search + 1, displacement (p3 - search)*stride rows, (p4 - search)*stride columns."""
+    x1 = _c(x1, np.float16)
+    x2 = _c(x2, np.float16)
+    if x1.shape != x2.shape or x1.ndim != 4:
+        raise ValueError("shape mismatch")
+    N, C, H, W = x1.shape
+    n = 2 * search + 1
+    y = np.empty((N, H, W, n, n), np.float16)
+    if _load().ref_correlation(_ptr(x1), _ptr(x2), _ptr(y), N, C, H, W, search, stride) != 0:
+        raise ValueError("ref_correlation: bad shape")
     return y
 
 

@@ -157,6 +157,25 @@ def pool2d(x: np.ndarray, kernel=(3, 3), stride=(2, 2), pad=(1, 1), mode="max") 
     return rows.reshape(ranges[:4]).astype(np.float32)
 
 
+def correlation_desc(N, C, H, W, R, sd):
+    """k = (b, p1, p2, p3, p4 | a1), Eq. 8: the second tensor moves with p1 + p3 and p2 + p4
+    (two indices on one axis); displacements centred: offset -R*sd, stride sd."""
+    n = 2 * R + 1
+    ranges = (N, H, W, n, n, C)
+    t1 = Transform(axis=(0, 2, 3, UNUSED, UNUSED, 1), stride=(1, 1, 1, 0, 0, 1), offset=(0,) * 6)
+    t2 = Transform(axis=(0, 2, 3, 2, 3, 1), stride=(1, 1, 1, sd, sd, 1), offset=(0, 0, 0, -R * sd, -R * sd, 0))
+    return ranges, 5, t1, t2
+
+
+def correlation(x1: np.ndarray, x2: np.ndarray, search: int, stride: int = 1) -> np.ndarray:
+    N, C, H, W = x1.shape
+    ranges, n_par, t1, t2 = correlation_desc(N, C, H, W, search, stride)
+    M1, _ = transform(x1.astype(np.float64), ranges, t1, n_par, "zero")
+    M2, _ = transform(x2.astype(np.float64), ranges, t2, n_par, "zero")
+    rows = np.einsum("pa,pa->p", M1, M2)
+    return rows.reshape(ranges[:5]).astype(np.float16)
+
+
 def sad_search(cur: np.ndarray, ref: np.ndarray, block: int, search: int):
     H, W = cur.shape
     ranges, n_par, tref, tcur = sad_desc(H, W, block, search)

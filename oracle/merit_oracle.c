@@ -269,6 +269,44 @@ int ref_sad_search(const uint8_t *cur, const uint8_t *ref, int32_t *sad, int32_t
     return 0;
 }
 
+/* ------------------------------------------------------------------------ */
+/* Correlation layer, fp16 in / fp16 out                                      */
+/* ------------------------------------------------------------------------ */
+/*
+ * Section III-C, Eq. 8:  M(I1)[p1,p2,p3,p4,a1] = I1[a1,p1,p2],
+ *                        M(I2)[p1,p2,p3,p4,a1] = I2[a1,p1+p3,p2+p4],
+ * reduced over the channel index a1 with the dot product (Eq. 3).  Here the two
+ * displacement indices run over n = 2R+1 values each, centred and with a
+ * stride: displacement (p3 - R)*sd rows, (p4 - R)*sd columns; a second-tensor
+ * coordinate outside the image contributes 0.  No normalisation by the channel
+ * count.  x1, x2: [N,C,H,W] binary16; y: [N,H,W,n,n] binary16 (the index order
+ * (p1,p2,p3,p4) of the equation).  Exact products, double accumulation, one
+ * rounding.  Returns 0, or -1 on a bad shape.
+ */
+int ref_correlation(const uint16_t *x1, const uint16_t *x2, uint16_t *y,
+                    int N, int C, int H, int W, int R, int sd)
+{
+    if (N < 0 || C <= 0 || H <= 0 || W <= 0 || R < 0 || sd <= 0) return -1;
+    const int n = 2 * R + 1;
+    long row;
+#pragma omp parallel for schedule(static)
+    for (row = 0; row < (long)N * H; ++row) {
+        const int b = (int)(row / H), p1 = (int)(row % H);
+        for (int p2 = 0; p2 < W; ++p2)
+            for (int p3 = 0; p3 < n; ++p3)
+                for (int p4 = 0; p4 < n; ++p4) {
+                    const int yy = p1 + (p3 - R) * sd, xx = p2 + (p4 - R) * sd;
+                    double acc = 0.0;
+                    if (yy >= 0 && yy < H && xx >= 0 && xx < W)
+                        for (int c = 0; c < C; ++c)
+                            acc += ref_half_to_double(x1[(((size_t)b * C + c) * H + p1) * W + p2]) *
+                                   ref_half_to_double(x2[(((size_t)b * C + c) * H + yy) * W + xx]);
+                    y[((((size_t)b * H + p1) * W + p2) * n + p3) * n + p4] = ref_double_to_half(acc);
+                }
+    }
+    return 0;
+}
+
 /* All (2R+1)^2 candidate SADs of one block, raster order (dy-major). */
 int ref_sad_surface(const uint8_t *cur, const uint8_t *ref, int32_t *surface,
                     int H, int W, int B, int R, int by, int bx)
