@@ -152,6 +152,26 @@ def bench_conv(torch, mb, wl, cfg, steps, warmup, nsets, relu=False):
     }
 
 
+def bench_corr(torch, mb, wl, cfg, steps, warmup):
+    x1, x2 = wl.make_correlation_inputs(cfg)
+    d1, d2 = torch.from_numpy(x1).to("cuda:0"), torch.from_numpy(x2).to("cuda:0")
+    plan = mb.merit_plan_correlation(cfg.N, cfg.C, cfg.H, cfg.W, cfg.search, cfg.stride)
+    y = torch.empty(plan.out_shape(), dtype=torch.float16, device="cuda:0")
+    call = mb.bind_correlation(plan, d1, d2, y)
+    wall, ev_ms = timed_region(torch, lambda i: call(), steps, warmup)
+    t = ev_ms * 1e-3 / steps
+    n = 2 * cfg.search + 1
+    alg_bytes = x1.nbytes + x2.nbytes + y.numel() * 2
+    flops = 2.0 * cfg.N * cfg.H * cfg.W * n * n * cfg.C          # zero-padded positions included
+    return {
+        "workload": cfg.name, "kernel": plan.launch_info()["kernel"], "avg_launch_us": t * 1e6,
+        "out_elems_per_s": y.numel() / t, "achieved_tflops": flops / t / 1e12,
+        "achieved_hbm_gbs": alg_bytes / t / 1e9, "hbm_frac": alg_bytes / t / 1e9 / HBM_PEAK_GBS,
+        "roofline": {"bound": "alu", "achieved": flops / 4 / t / 1e12, "peak": VALU_PEAK_TOPS,
+                     "unit": "T lane-ops/s (v_dot2: 2 MACs)", "frac": flops / 4 / t / 1e12 / VALU_PEAK_TOPS},
+    }
+
+
 def cpu_baseline(wl):
     """The oracle as it stands, timed on the host cores: max + avg pool of the full batch."""
     import oracle
@@ -243,6 +263,7 @@ def main():
             bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets),
             bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets, relu=True),
             bench_conv(torch, mb, wl, wl.CFG_DILATED, k, w, args.sets),
+            bench_corr(torch, mb, wl, wl.CFG_CORRELATION, k, w),
         ]
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(wl)

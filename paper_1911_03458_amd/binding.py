@@ -19,7 +19,8 @@ MERIT_AXIS_UNUSED = -1
 MERIT_OK = 0
 (MERIT_ERR_NULL, MERIT_ERR_INVALID_ARG, MERIT_ERR_SHAPE, MERIT_ERR_UNSUPPORTED,
  MERIT_ERR_ALIGNMENT, MERIT_ERR_HIP) = range(1, 7)
-MERIT_OP_CONV_DOT, MERIT_OP_POOL_MAX, MERIT_OP_POOL_AVG, MERIT_OP_SAD_ARGMIN, MERIT_OP_CONV_DOT_RELU = range(5)
+(MERIT_OP_CONV_DOT, MERIT_OP_POOL_MAX, MERIT_OP_POOL_AVG, MERIT_OP_SAD_ARGMIN, MERIT_OP_CONV_DOT_RELU,
+ MERIT_OP_CORR_DOT) = range(6)
 MERIT_U8, MERIT_F16, MERIT_F32 = range(3)
 MERIT_PAD_ZERO, MERIT_PAD_NEG_INF, MERIT_PAD_EXCLUDE, MERIT_PAD_CLAMP = range(4)
 
@@ -80,6 +81,8 @@ def lib():
     L.merit_plan_conv2d_dilated.argtypes = [c_int] * 14 + [PP]
     L.merit_plan_pool2d.argtypes = [c_int] * 11 + [PP]
     L.merit_plan_sad.argtypes = [c_int] * 4 + [PP]
+    L.merit_plan_correlation.argtypes = [c_int] * 6 + [PP]
+    L.merit_correlation.argtypes = [P, P, P, P, P]
     L.merit_plan_get_desc.argtypes = [P, ctypes.POINTER(merit_plan_desc)]
     L.merit_plan_out_shape.argtypes = [P, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)]
     L.merit_plan_footprint.argtypes = [P, c_int, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]
@@ -91,7 +94,7 @@ def lib():
     for name in ("merit_plan_create", "merit_plan_destroy", "merit_plan_conv2d", "merit_plan_conv2d_relu",
                  "merit_plan_conv2d_dilated",
                  "merit_plan_pool2d",
-                 "merit_plan_sad", "merit_plan_get_desc", "merit_plan_out_shape", "merit_plan_footprint",
+                 "merit_plan_sad", "merit_plan_correlation", "merit_correlation", "merit_plan_get_desc", "merit_plan_out_shape", "merit_plan_footprint",
                  "merit_plan_launch_info", "merit_plan_set_tile", "merit_conv2d", "merit_pool2d",
                  "merit_sad_search"):
         getattr(L, name).restype = c_int
@@ -276,6 +279,24 @@ def merit_sad_search(plan: Plan, cur, ref, sad=None, mv=None, stream=None):
     return sad, mv
 
 
+def merit_plan_correlation(N, C, H, W, R, sd=1) -> Plan:
+    h = ctypes.c_void_p()
+    _check(lib().merit_plan_correlation(N, C, H, W, R, sd, ctypes.byref(h)), "merit_plan_correlation")
+    return Plan(h)
+
+
+def merit_correlation(plan: Plan, x1, x2, y=None, stream=None):
+    import torch
+    out_shape, a_shape, b_shape = plan.shapes()
+    if y is None:
+        y = torch.empty(out_shape, dtype=torch.float16, device=x1.device)
+    if tuple(x1.shape) != a_shape or tuple(x2.shape) != b_shape or tuple(y.shape) != out_shape:
+        raise ValueError("tensors do not match the plan")
+    _check(lib().merit_correlation(plan.handle, _dev_ptr(x1, torch.float16, "x1"), _dev_ptr(x2, torch.float16, "x2"),
+                                   _dev_ptr(y, torch.float16, "y"), _stream(stream)), "merit_correlation")
+    return y
+
+
 # --------------------------------------------------------------------------
 # pre-marshalled calls: validate tensors once, then re-issue the same C call
 # with raw pointers (for tight loops where ~10 us of Python checks per call
@@ -321,3 +342,13 @@ def bind_sad_search(plan: Plan, cur, ref, sad, mv, stream=None) -> BoundCall:
     args = (plan.handle, _dev_ptr(cur, torch.uint8, "cur"), _dev_ptr(ref, torch.uint8, "ref"),
             _dev_ptr(sad, torch.int32, "sad"), _dev_ptr(mv, torch.int32, "mv"), _stream(stream))
     return BoundCall(lib().merit_sad_search, "merit_sad_search", args, (plan, cur, ref, sad, mv))
+
+
+def bind_correlation(plan: Plan, x1, x2, y, stream=None) -> BoundCall:
+    import torch
+    out_shape, a_shape, b_shape = plan.shapes()
+    if tuple(x1.shape) != a_shape or tuple(x2.shape) != b_shape or tuple(y.shape) != out_shape:
+        raise ValueError("tensors do not match the plan")
+    args = (plan.handle, _dev_ptr(x1, torch.float16, "x1"), _dev_ptr(x2, torch.float16, "x2"),
+            _dev_ptr(y, torch.float16, "y"), _stream(stream))
+    return BoundCall(lib().merit_correlation, "merit_correlation", args, (plan, x1, x2, y))

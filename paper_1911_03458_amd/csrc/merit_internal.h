@@ -122,6 +122,20 @@ const char *pool_kernel_name(const PoolParams &p);
 const char *sad_kernel_name(const SadParams &p);
 const char *conv_kernel_name(const ConvParams &p);
 
+// ---- correlation layer -----------------------------------------------------
+struct CorrParams {
+    int N, C, H, W, R, sd, n;   // n = 2R+1 displacements per axis, sd = displacement stride
+    int nchi;                   // channel groups of 8 (C padded)
+    int chg;                    // channel groups staged per pass
+    int xchunks;                // 64-pixel chunks per image row
+    int cols2;                  // staged columns of the second tensor per chunk (multiple of 8)
+    int lead;                   // columns staged left of the chunk's first pixel (multiple of 8, >= R*sd)
+    FastDiv div_n, div_xchunks, div_h;
+};
+
+hipError_t launch_correlation(const CorrParams &p, const void *x1, const void *x2, void *y, hipStream_t s);
+size_t corr_lds_bytes(const CorrParams &p);
+
 }  // namespace merit
 
 struct merit_plan {
@@ -132,5 +146,6 @@ struct merit_plan {
     merit::PoolParams pool;
     merit::SadParams sad;
     merit::ConvParams conv;
+    merit::CorrParams corr;
     merit_launch_info info;
 };

@@ -444,6 +444,63 @@ merit_status derive_conv(merit_plan *pl)
     return MERIT_OK;
 }
 
+// -------------------------------------------------------- correlation layer ---
+merit_status derive_corr(merit_plan *pl)
+{
+    const merit_plan_desc &d = pl->desc;
+    if (d.dtype != MERIT_F16 || d.pad != MERIT_PAD_ZERO) return MERIT_ERR_UNSUPPORTED;
+    if (d.n_par != 5 || d.n_acc != 1) return MERIT_ERR_UNSUPPORTED;
+    if (d.a.ndim != 4 || d.b.ndim != 4) return MERIT_ERR_UNSUPPORTED;
+    const int64_t n = d.range[3];
+    if (n <= 0 || (n % 2) == 0 || d.range[4] != n) return MERIT_ERR_SHAPE;
+    const int64_t R = (n - 1) / 2;
+    const int64_t sd = d.b.stride[3];
+    if (sd <= 0) return MERIT_ERR_INVALID_ARG;
+    const int axis_1[6] = {0, 2, 3, MERIT_AXIS_UNUSED, MERIT_AXIS_UNUSED, 1};
+    const int64_t stride_1[6] = {1, 1, 1, 0, 0, 1};
+    const int64_t offset_1[6] = {0, 0, 0, 0, 0, 0};
+    const int axis_2[6] = {0, 2, 3, 2, 3, 1};
+    const int64_t stride_2[6] = {1, 1, 1, sd, sd, 1};
+    const int64_t offset_2[6] = {0, 0, 0, -R * sd, -R * sd, 0};
+    if (!operand_is(d.a, 6, axis_1, stride_1, offset_1)) return MERIT_ERR_UNSUPPORTED;
+    if (!operand_is(d.b, 6, axis_2, stride_2, offset_2)) return MERIT_ERR_UNSUPPORTED;
+    const int64_t N = d.a.shape[0], C = d.a.shape[1], H = d.a.shape[2], W = d.a.shape[3];
+    if (N < 0 || C <= 0 || H <= 0 || W <= 0) return MERIT_ERR_INVALID_ARG;
+    for (int i = 0; i < 4; ++i)
+        if (d.b.shape[i] != d.a.shape[i]) return MERIT_ERR_SHAPE;
+    if (d.range[0] != N || d.range[1] != H || d.range[2] != W || d.range[5] != C) return MERIT_ERR_SHAPE;
+    // the kernel stages 8-pixel units and gives a wavefront at most 8 column displacements
+    if ((W % 8) != 0 || R > 15 || sd > 8 || C > 65536) return MERIT_ERR_UNSUPPORTED;
+    if (N * C * H * W >= INT_LIMIT || N * H * W * n * n >= INT_LIMIT) return MERIT_ERR_UNSUPPORTED;
+
+    CorrParams &p = pl->corr;
+    p.N = (int)N; p.C = (int)C; p.H = (int)H; p.W = (int)W; p.R = (int)R; p.sd = (int)sd; p.n = (int)n;
+    p.nchi = (int)cdiv(C, 8);
+    p.xchunks = (int)cdiv(W, 64);
+    p.lead = (int)round_up(R * sd, 8);
+    p.cols2 = (int)round_up(64 + p.lead + R * sd, 8);
+    const int64_t per_group = (64 + (int64_t)p.cols2) * 16;
+    int64_t chg = (80 * 1024) / per_group;                 // two workgroups per CU share its 160 KB of LDS
+    if (chg < 1) chg = 1;
+    p.chg = (int)(chg < p.nchi ? chg : p.nchi);
+    const int64_t grid = N * H * n * p.xchunks;
+    if (grid >= INT_LIMIT || !fastdiv_ok(grid, p.xchunks) || !fastdiv_ok(grid, n) || !fastdiv_ok(grid, H))
+        return MERIT_ERR_UNSUPPORTED;
+    p.div_xchunks = make_fastdiv((uint32_t)p.xchunks);
+    p.div_n = make_fastdiv((uint32_t)n);
+    p.div_h = make_fastdiv((uint32_t)H);
+
+    pl->out_ndim = 5;
+    pl->out_shape[0] = N; pl->out_shape[1] = H; pl->out_shape[2] = W; pl->out_shape[3] = n; pl->out_shape[4] = n;
+    merit_launch_info &li = pl->info;
+    li.kernel = "merit_corr_dot";
+    li.grid[0] = grid; li.grid[1] = 1; li.grid[2] = 1;
+    li.block[0] = 256; li.block[1] = 1; li.block[2] = 1;
+    li.lds_bytes = (int64_t)corr_lds_bytes(p);
+    li.tile[0] = 1; li.tile[1] = 1; li.tile[2] = W < 64 ? W : 64; li.tile[3] = 1; li.tile[4] = n; li.tile[5] = C;
+    return MERIT_OK;
+}
+
 bool aligned16(const void *ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15u) == 0; }
 
 }  // namespace
@@ -455,7 +512,7 @@ merit_status merit_plan_create(const merit_plan_desc *desc, merit_plan **out)
 {
     if (!desc || !out) return MERIT_ERR_NULL;
     *out = nullptr;
-    if ((int)desc->op < 0 || (int)desc->op > 4 || (int)desc->dtype < 0 || (int)desc->dtype > 2 ||
+    if ((int)desc->op < 0 || (int)desc->op > 5 || (int)desc->dtype < 0 || (int)desc->dtype > 2 ||
         (int)desc->pad < 0 || (int)desc->pad > 3)
         return MERIT_ERR_INVALID_ARG;
     if (desc->n_par < 1 || desc->n_acc < 1 || desc->n_par + desc->n_acc > MERIT_MAX_INDEX)
@@ -479,6 +536,7 @@ merit_status merit_plan_create(const merit_plan_desc *desc, merit_plan **out)
     case MERIT_OP_CONV_DOT_RELU: st = derive_conv(pl); break;
     case MERIT_OP_POOL_MAX:
     case MERIT_OP_POOL_AVG: st = derive_pool(pl); break;
+    case MERIT_OP_CORR_DOT: st = derive_corr(pl); break;
     default: st = derive_sad(pl); break;
     }
     if (st != MERIT_OK) {
@@ -616,6 +674,7 @@ merit_status merit_plan_set_tile(merit_plan *plan, const int64_t tile[MERIT_MAX_
     case MERIT_OP_CONV_DOT_RELU: st = derive_conv(&trial); break;
     case MERIT_OP_POOL_MAX:
     case MERIT_OP_POOL_AVG: st = derive_pool(&trial); break;
+    case MERIT_OP_CORR_DOT: st = derive_corr(&trial); break;
     default: st = derive_sad(&trial); break;
     }
     if (st != MERIT_OK) return st;          // the plan keeps its previous tiling
@@ -702,6 +761,43 @@ merit_status merit_sad_search(const merit_plan *plan, const void *cur, const voi
                       static_cast<hipStream_t>(stream)) == hipSuccess
                ? MERIT_OK
                : MERIT_ERR_HIP;
+}
+
+merit_status merit_plan_correlation(int N, int C, int H, int W, int R, int sd, merit_plan **out)
+{
+    if (!out) return MERIT_ERR_NULL;
+    *out = nullptr;
+    if (N < 0 || C <= 0 || H <= 0 || W <= 0 || R < 0 || sd <= 0) return MERIT_ERR_INVALID_ARG;
+    merit_plan_desc d;
+    std::memset(&d, 0, sizeof(d));
+    d.op = MERIT_OP_CORR_DOT; d.dtype = MERIT_F16; d.pad = MERIT_PAD_ZERO;
+    d.n_par = 5; d.n_acc = 1;
+    const int64_t n = 2 * (int64_t)R + 1;
+    const int64_t range[6] = {N, H, W, n, n, C};
+    const int a1[6] = {0, 2, 3, MERIT_AXIS_UNUSED, MERIT_AXIS_UNUSED, 1};
+    const int64_t s1[6] = {1, 1, 1, 0, 0, 1};
+    const int a2[6] = {0, 2, 3, 2, 3, 1};
+    const int64_t s2[6] = {1, 1, 1, sd, sd, 1};
+    const int64_t o2[6] = {0, 0, 0, -(int64_t)R * sd, -(int64_t)R * sd, 0};
+    for (int j = 0; j < 6; ++j) {
+        d.range[j] = range[j];
+        d.a.axis[j] = a1[j]; d.a.stride[j] = s1[j]; d.a.offset[j] = 0;
+        d.b.axis[j] = a2[j]; d.b.stride[j] = s2[j]; d.b.offset[j] = o2[j];
+    }
+    d.a.ndim = 4; d.a.shape[0] = N; d.a.shape[1] = C; d.a.shape[2] = H; d.a.shape[3] = W;
+    d.b.ndim = 4; d.b.shape[0] = N; d.b.shape[1] = C; d.b.shape[2] = H; d.b.shape[3] = W;
+    return merit_plan_create(&d, out);
+}
+
+merit_status merit_correlation(const merit_plan *plan, const void *x1, const void *x2, void *y, void *stream)
+{
+    if (!plan) return MERIT_ERR_NULL;
+    if (plan->desc.op != MERIT_OP_CORR_DOT) return MERIT_ERR_INVALID_ARG;
+    if (plan->corr.N == 0) return MERIT_OK;               // empty batch: nothing to read or write
+    if (!x1 || !x2 || !y) return MERIT_ERR_NULL;
+    if (!aligned16(x1) || !aligned16(x2) || !aligned16(y)) return MERIT_ERR_ALIGNMENT;
+    return launch_correlation(plan->corr, x1, x2, y, static_cast<hipStream_t>(stream)) == hipSuccess ? MERIT_OK
+                                                                                                   : MERIT_ERR_HIP;
 }
 
 const char *merit_status_string(merit_status s)

@@ -109,8 +109,25 @@ CONFIGS = [CFG0_ME_SMALL, CFG1_POOL, CFG2_CONV3, CFG3_ME_FHD, CFG4_CONV7]
 # Beyond the five configurations: the motion-estimation row of the paper's table of further
 # workloads (720p, 8x8 blocks; the search range is not given there: +-16 here), and the dilated layer of the paper's table of further workloads
 # (output 64 x 64 x 32; channel count and batch are not given there: 32 in, batch 8 here).
+CFG_CORRELATION = None   # defined below (needs its dataclass)
 CFG_ME_720P = SadWorkload("me_1280x720_b8_r16", 720, 1280, 8, 16, 0, "sinusoid")
 CFG_DILATED = ConvWorkload("conv_8x32x64x64_co32_k3s1p2_d2", 8, 32, 64, 64, 32, 3, 3, 1, 1, 2, 2, "normal", 2, 2)
+
+
+@dataclass(frozen=True)
+class CorrWorkload:
+    name: str
+    N: int
+    C: int
+    H: int
+    W: int
+    search: int          # R: displacement indices p3, p4 in [0, 2R]
+    stride: int          # displacement stride
+
+
+# The correlation row of the paper's table of further workloads: output 64 x 64 x 11 x 11
+# (channel count and displacement stride are not given there: 256 channels, stride 2 here).
+CFG_CORRELATION = CorrWorkload("corr_1x256x64x64_r5_s2", 1, 256, 64, 64, 5, 2)
 
 
 # --------------------------------------------------------------------------
@@ -196,3 +213,13 @@ def make_conv_inputs(wl: ConvWorkload, seed: int | None = None, N: int | None = 
     w = rng.standard_normal(size=(wl.Cout, wl.Cin, wl.kh, wl.kw), dtype=np.float32)
     w *= np.float32(1.0 / np.sqrt(fan_in))
     return x.astype(np.float16), w.astype(np.float16)
+
+
+def make_correlation_inputs(wl: CorrWorkload, seed: int | None = None):
+    """Two fp16 feature maps [N,C,H,W]: the second is the first shifted by a few pixels plus
+    noise (so that the correlation has structure), both scaled to keep sums O(1)."""
+    rng = np.random.default_rng(BASE_SEED + 7 if seed is None else seed)
+    a = rng.standard_normal(size=(wl.N, wl.C, wl.H, wl.W)).astype(np.float32)
+    b = np.roll(a, shift=(2, -4), axis=(2, 3)) + 0.5 * rng.standard_normal(size=a.shape).astype(np.float32)
+    s = np.float32(1.0 / np.sqrt(wl.C))
+    return (a * s).astype(np.float16), b.astype(np.float16)

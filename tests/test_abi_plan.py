@@ -87,6 +87,35 @@ def test_dilated_plan_is_the_papers_expression():
         "merit_conv2d_chblock"
 
 
+def test_correlation_plan_is_eq8():
+    """M(I2) = I2[a1, p1 + p3, p2 + p4] (Section III-C, Eq. 8): two indices on one axis."""
+    plan = mb.merit_plan_correlation(1, 256, 64, 64, 5, 2)
+    d = plan.desc()
+    ranges, n_par, t1, t2 = lit.correlation_desc(1, 256, 64, 64, 5, 2)
+    assert (d.op, d.n_par, d.n_acc) == (mb.MERIT_OP_CORR_DOT, 5, 1)
+    assert tuple(d.range[:6]) == ranges == (1, 64, 64, 11, 11, 256)
+    assert _triples(d.b, 6) == list(zip(t2.axis, t2.stride, t2.offset))
+    for j in range(6):
+        assert d.a.axis[j] == t1.axis[j]
+    assert plan.out_shape() == (1, 64, 64, 11, 11)                  # the paper's 64 x 64 x 11 x 11
+    # footprint of a (1 row x 64 pixels x 1 x 11 displacements) tile of the second tensor
+    assert plan.footprint(1, (1, 1, 64, 1, 11, 256)) == lit.footprint((1, 1, 64, 1, 11, 256), t2, 4)
+    assert plan.footprint(1, (1, 1, 64, 1, 11, 256))[3] == 64 + 10 * 2
+    li = plan.launch_info()
+    assert li["kernel"] == "merit_corr_dot" and li["grid"][0] == 64 * 11 and li["lds_bytes"] <= 160 * 1024
+    assert mb.merit_plan_create(d).out_shape() == (1, 64, 64, 11, 11)
+    d.b.offset[3] = -9                                              # not centred: no kernel
+    with pytest.raises(mb.MeritError) as e:
+        mb.merit_plan_create(d)
+    assert e.value.status == mb.MERIT_ERR_UNSUPPORTED
+    with pytest.raises(mb.MeritError) as e:
+        mb.merit_plan_correlation(1, 8, 16, 20, 2, 1)               # W not a multiple of 8
+    assert e.value.status == mb.MERIT_ERR_UNSUPPORTED
+    L = mb.lib()
+    assert L.merit_correlation(plan.handle, None, 16, 16, None) == mb.MERIT_ERR_NULL
+    assert L.merit_conv2d(plan.handle, 16, 16, 16, None) == mb.MERIT_ERR_INVALID_ARG
+
+
 def test_pool_and_sad_plan_descriptors():
     plan = mb.merit_plan_pool2d(16, 64, 112, 112, 3, 3, 2, 2, 1, 1, 0)
     d = plan.desc()

@@ -238,6 +238,60 @@ def test_sad_full_hd_workload(mb):
     assert np.array_equal(mv, omv)
 
 
+# ------------------------------------------------------- correlation layer
+CORR_CASES = [
+    # N  C   H   W   R  sd
+    (1, 8, 8, 8, 1, 1),
+    (2, 20, 9, 24, 2, 1),        # channels not a multiple of 8
+    (1, 64, 12, 72, 5, 2),       # two pixel chunks, the second ragged
+    (1, 130, 6, 64, 3, 3),       # two channel passes
+    (1, 16, 10, 16, 0, 1),       # zero range: the per-pixel dot product
+    (1, 32, 5, 40, 15, 1),       # widest range: 31 displacements, 8 per wavefront
+]
+
+
+@pytest.mark.parametrize("case", CORR_CASES)
+def test_correlation(mb, case):
+    N, C, H, W, R, sd = case
+    rng = np.random.default_rng(abs(hash(case)) % 2 ** 31)
+    x1 = (rng.standard_normal((N, C, H, W)) / np.sqrt(C)).astype(np.float16)
+    x2 = rng.standard_normal((N, C, H, W)).astype(np.float16)
+    plan = mb.merit_plan_correlation(N, C, H, W, R, sd)
+    print("corr", case, plan.launch_info(), flush=True)
+    buf, y, pad = guarded_empty(plan.out_shape(), torch.float16, 777.0)
+    mb.merit_correlation(plan, dev(x1), dev(x2), y)
+    torch.cuda.synchronize()
+    check_canary(buf, pad, 777.0)
+    got = y.cpu().numpy().astype(np.float64)
+    ref = oracle.correlation(x1, x2, R, sd).astype(np.float64)
+    assert np.all(np.abs(got - ref) <= 2e-2 * np.abs(ref) + 1e-3)
+    if R > 0:                                                       # displaced above the first row: exact zeros
+        assert np.all(got[:, 0, :, 0, :] == 0) and np.all(ref[:, 0, :, 0, :] == 0)
+
+
+def test_correlation_delta_images(mb):
+    """One-hot tensors answer at exactly one pixel and displacement."""
+    H, W, R, sd = 16, 24, 3, 2
+    x1 = np.zeros((1, 8, H, W), np.float16)
+    x2 = np.zeros((1, 8, H, W), np.float16)
+    x1[0, 5, 6, 7] = 2.0
+    x2[0, 5, 10, 3] = 3.0                                           # displacement (+4, -4) = (+2, -2) * sd
+    y = mb.merit_correlation(mb.merit_plan_correlation(1, 8, H, W, R, sd), dev(x1), dev(x2)).cpu().numpy()
+    want = np.zeros((1, H, W, 7, 7), np.float16)
+    want[0, 6, 7, R + 2, R - 2] = 6.0
+    assert np.array_equal(y, want)
+
+
+def test_correlation_paper_shape(mb):
+    c = wl.CFG_CORRELATION
+    x1, x2 = wl.make_correlation_inputs(c)
+    plan = mb.merit_plan_correlation(c.N, c.C, c.H, c.W, c.search, c.stride)
+    y = mb.merit_correlation(plan, dev(x1), dev(x2)).cpu().numpy().astype(np.float64)
+    ref = oracle.correlation(x1, x2, c.search, c.stride).astype(np.float64)
+    assert y.shape == (1, 64, 64, 11, 11)
+    assert np.all(np.abs(y - ref) <= 2e-2 * np.abs(ref) + 1e-3)
+
+
 # ------------------------------------------------------------- convolution
 def _conv_check(mb, x, w, stride, pad, tile=None, relu=False, dilation=(1, 1)):
     N, Cin, H, W = x.shape
