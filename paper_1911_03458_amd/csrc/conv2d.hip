@@ -57,6 +57,17 @@ __device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, v);
 }
 
+// Touch every 64-byte line of the kernel's argument block (ConvParams + three pointers) with
+// the first scalar loads, so that the later ones, issued where their values are needed, hit
+// the scalar cache instead of each paying a trip to memory.
+__device__ __forceinline__ void touch_kernarg_lines()
+{
+    typedef const uint32_t __attribute__((address_space(4))) *kernarg_ptr;
+    kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
+    const uint32_t warm = ka[16] ^ ka[32] ^ ka[48];
+    asm volatile("" ::"s"(warm));
+}
+
 // ---------------------------------------------------------------------------
 // Epilogue.  Accumulator register r of lane l holds output channel l%32 (within
 // its 32-channel block) of pixel 8*(r/4) + 4*(l/32) + r%4 (within its 32-pixel
@@ -467,15 +478,7 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
                                                                 uint16_t *__restrict__ y)
 {
     constexpr int PXW = 2, NWC = 4, TM = NWC * PXW * 32, NTG = 128;    // loading / storing group = 2 wavefronts
-    {
-        // Touch every 64-byte line of the argument block with the first scalar loads, so the
-        // later ones (issued where their values are needed) hit the scalar cache instead of
-        // each paying a trip to memory.
-        typedef const uint32_t __attribute__((address_space(4))) *kernarg_ptr;
-        kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
-        const uint32_t warm = ka[16] ^ ka[32] ^ ka[48];
-        asm volatile("" ::"s"(warm));
-    }
+    touch_kernarg_lines();
     extern __shared__ __align__(16) uint8_t smem[];
     uint4 *wl = reinterpret_cast<uint4 *>(smem);
     uint8_t *xz = smem + p.lds_w_bytes;                 // 32 zero bytes, then the two tiles
@@ -821,6 +824,16 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
 // take chi' + nchi/2, so the per-step LDS offset is the same for every lane.
 // ---------------------------------------------------------------------------
 
+// LDS bank spreading for the staging writes (the XOR layout of Section IV-B).  Input: inside
+// every aligned run of 8 staged columns the position is XORed with the run's index (a staging
+// thread writes one run of 8 pixels, its neighbours the adjacent runs 128 bytes apart).
+// Weights: a fragment's channel slot is XORed with its channel-group index (neighbouring
+// staging threads hold different channel groups of the same output channel, whose fragments
+// lie a multiple of 1 KB apart).  The K loop applies the same maps when it reads.
+// (columns of the last, partial run of a row keep their place: `lim` = pitch rounded down to 8)
+__device__ __forceinline__ int xsw(int col, int lim) { return col < lim ? col ^ ((col >> 3) & 7) : col; }
+__device__ __forceinline__ int wsw(int cc, int chi) { return cc ^ (chi & 7); }
+
 // weights, 8 channels x T taps per unit, read as T 16-byte loads and transposed
 // in registers to T fragments of 8 channels (needs Cin % 8 == 0)
 template <int T>
@@ -836,7 +849,7 @@ __device__ __forceinline__ void stage_weights_chblock_vec(const ConvParams &p, c
 #pragma unroll
         for (int k = 0; k < WB; ++k) {
             const int u = min(u0 + nthr * k, units - 1);
-            const int col = u / p.nchi;
+            const int col = (int)fdiv((uint32_t)u, p.div_nchi);
             const int chi = u - col * p.nchi;
             const int co = co_base + col;
             const bool ok = (co < p.Cout) && (chi * 8 + 8 <= p.Cin);
@@ -853,7 +866,7 @@ __device__ __forceinline__ void stage_weights_chblock_vec(const ConvParams &p, c
         for (int k = 0; k < WB; ++k) {
             const int u = u0 + nthr * k;
             if (u >= units) break;
-            const int col = u / p.nchi;
+            const int col = (int)fdiv((uint32_t)u, p.div_nchi);
             const int chi = u - col * p.nchi;
             const int hh = chi >= half_nchi ? 1 : 0;
             const int chip = chi - hh * half_nchi;
@@ -869,7 +882,7 @@ __device__ __forceinline__ void stage_weights_chblock_vec(const ConvParams &p, c
                     d[q] = __builtin_amdgcn_perm(src[k][e1 >> 1], src[k][e0 >> 1], sel);
                 }
                 const int s = chip * T + t;
-                wl[((s * CB + cb) * 2 + hh) * 32 + cc] = make_uint4(d[0], d[1], d[2], d[3]);
+                wl[((s * CB + cb) * 2 + hh) * 32 + wsw(cc, chi)] = make_uint4(d[0], d[1], d[2], d[3]);
             }
         }
     }
@@ -898,7 +911,7 @@ __device__ __forceinline__ void stage_weights_chblock_scalar(const ConvParams &p
         const int hh = chi >= half_nchi ? 1 : 0;
         const int chip = chi - hh * half_nchi;
         const int s = chip * T + t;
-        wl[((s * CB + (col >> 5)) * 2 + hh) * 32 + (col & 31)] = make_uint4(d[0], d[1], d[2], d[3]);
+        wl[((s * CB + (col >> 5)) * 2 + hh) * 32 + wsw(col & 31, chi)] = make_uint4(d[0], d[1], d[2], d[3]);
     }
 }
 
@@ -921,7 +934,7 @@ __device__ __forceinline__ void stage_input_chblock(const ConvParams &p, const u
         const int rowi = u / npad;
         const int c = u - rowi * npad;
         const int col = c < p.padl ? c : p.W + c;
-        xl[rowi * p.pitch + col] = make_uint4(0, 0, 0, 0);
+        xl[rowi * p.pitch + xsw(col, p.pitch & ~7)] = make_uint4(0, 0, 0, 0);
     }
     if ((p.W & 7) == 0) {
         // 8 channels x 8 pixels per unit, transposed in registers
@@ -959,7 +972,8 @@ __device__ __forceinline__ void stage_input_chblock(const ConvParams &p, const u
                 const int x8 = u - q * W8;
                 const int chi = (int)fdiv((uint32_t)q, p.div_rha);
                 const int r = q - chi * p.RHa;
-                uint4 *dst = xl + (chi * p.RHa + r) * p.pitch + p.padl + 8 * x8;
+                uint4 *dst = xl + (chi * p.RHa + r) * p.pitch;
+                const int col0 = p.padl + 8 * x8;
 #pragma unroll
                 for (int px = 0; px < 8; ++px) {
                     const uint32_t sel = (px & 1) ? 0x07060302u : 0x05040100u;
@@ -967,7 +981,7 @@ __device__ __forceinline__ void stage_input_chblock(const ConvParams &p, const u
 #pragma unroll
                     for (int qq = 0; qq < 4; ++qq)
                         d[qq] = __builtin_amdgcn_perm(v[k][2 * qq + 1][px >> 1], v[k][2 * qq][px >> 1], sel);
-                    dst[px] = make_uint4(d[0], d[1], d[2], d[3]);
+                    dst[xsw(col0 + px, p.pitch & ~7)] = make_uint4(d[0], d[1], d[2], d[3]);
                 }
             }
         }
@@ -989,7 +1003,7 @@ __device__ __forceinline__ void stage_input_chblock(const ConvParams &p, const u
                         d[c >> 1] |= (uint32_t)x[(((size_t)n * p.Cin + ch) * p.H + gy) * p.W + xg] << (16 * (c & 1));
                 }
             }
-            xl[(chi * p.RHa + r) * p.pitch + p.padl + xg] = make_uint4(d[0], d[1], d[2], d[3]);
+            xl[(chi * p.RHa + r) * p.pitch + xsw(p.padl + xg, p.pitch & ~7)] = make_uint4(d[0], d[1], d[2], d[3]);
         }
     }
 }
@@ -999,6 +1013,7 @@ __global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const 
                                                            const uint16_t *__restrict__ w,
                                                            uint16_t *__restrict__ y)
 {
+    touch_kernarg_lines();
     extern __shared__ __align__(16) uint8_t smem[];
     uint4 *wl = reinterpret_cast<uint4 *>(smem);
     uint4 *xl = reinterpret_cast<uint4 *>(smem + p.lds_w_bytes);
@@ -1033,15 +1048,16 @@ __global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const 
         }
         __syncthreads();
 
-        int pbase[PXW];
+        int pbase[PXW], pcol[PXW];                  // staged row offset and column of tap kx = 0
+        const int lim8 = p.pitch & ~7;
 #pragma unroll
         for (int pb = 0; pb < PXW; ++pb) {
             const int m = m0 + (wave * PXW + pb) * 32 + c32;
             const int mm = min(m, ohw - 1);
             const int oy = (int)fdiv((uint32_t)mm, p.div_ow);
             const int ox = mm - oy * p.OW;
-            // staged column of tap kx = 0 is padl - pw + ox*sw
-            pbase[pb] = ((h * half_nchi * p.RHa) + (oy - oyA) * p.sh) * p.pitch + (p.padl - p.pw) + ox * p.sw;
+            pbase[pb] = ((h * half_nchi * p.RHa) + (oy - oyA) * p.sh) * p.pitch;
+            pcol[pb] = (p.padl - p.pw) + ox * p.sw;
         }
 
         floatx16 acc[CB][PXW];
@@ -1052,22 +1068,56 @@ __global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const 
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[cb][pb][r] = 0.0f;
 
-        int s = 0;
-        for (int chip = 0; chip < half_nchi; ++chip)
-            for (int ky = 0; ky < p.kh; ++ky) {
-                const int rowoff = (chip * p.RHa + ky * p.dh) * p.pitch;
-                for (int kx = 0; kx < p.kw; ++kx, ++s) {
-                    Frag a[CB], b[PXW];
+        // K loop.  Step s = (chip, ky, kx), kx fastest; a lone wavefront per SIMD issues about one
+        // instruction per 4-5 cycles, so what counts is instructions per step (two MFMAs = 64
+        // cycles).  3x3 windows get the nine steps of a channel-group pair unrolled: weight
+        // fragments at immediate offsets, the three swizzled tap columns computed once per tile.
+        if (p.kh == 3 && p.kw == 3) {
+            int xc[PXW][3];
 #pragma unroll
-                    for (int cb = 0; cb < CB; ++cb) a[cb].u = wl[(s * CB + cb) * 64 + lane];
+            for (int pb = 0; pb < PXW; ++pb)
 #pragma unroll
-                    for (int pb = 0; pb < PXW; ++pb) b[pb].u = xl[pbase[pb] + rowoff + kx * p.dw];
+                for (int kx = 0; kx < 3; ++kx) xc[pb][kx] = pbase[pb] + xsw(pcol[pb] + kx * p.dw, lim8);
+            for (int chip = 0; chip < half_nchi; ++chip) {
+                const uint4 *wa = wl + (chip * 9 * CB) * 64 + h * 32 + wsw(c32, chip + h * half_nchi);
 #pragma unroll
-                    for (int cb = 0; cb < CB; ++cb)
+                for (int ky = 0; ky < 3; ++ky) {
+                    const int rowoff = (chip * p.RHa + ky * p.dh) * p.pitch;
 #pragma unroll
-                        for (int pb = 0; pb < PXW; ++pb) acc[cb][pb] = mfma16(a[cb], b[pb], acc[cb][pb]);
+                    for (int kx = 0; kx < 3; ++kx) {
+                        Frag a[CB], b[PXW];
+#pragma unroll
+                        for (int cb = 0; cb < CB; ++cb) a[cb].u = wa[((ky * 3 + kx) * CB + cb) * 64];
+#pragma unroll
+                        for (int pb = 0; pb < PXW; ++pb) b[pb].u = xl[xc[pb][kx] + rowoff];
+#pragma unroll
+                        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                            for (int pb = 0; pb < PXW; ++pb) acc[cb][pb] = mfma16(a[cb], b[pb], acc[cb][pb]);
+                    }
                 }
             }
+        } else {
+            int s = 0;
+            for (int chip = 0; chip < half_nchi; ++chip) {
+                const int wslot = h * 32 + wsw(c32, chip + h * half_nchi);
+                for (int ky = 0; ky < p.kh; ++ky) {
+                    const int rowoff = (chip * p.RHa + ky * p.dh) * p.pitch;
+                    for (int kx = 0; kx < p.kw; ++kx, ++s) {
+                        Frag a[CB], b[PXW];
+#pragma unroll
+                        for (int cb = 0; cb < CB; ++cb) a[cb].u = wl[(s * CB + cb) * 64 + wslot];
+#pragma unroll
+                        for (int pb = 0; pb < PXW; ++pb)
+                            b[pb].u = xl[pbase[pb] + rowoff + xsw(pcol[pb] + kx * p.dw, lim8)];
+#pragma unroll
+                        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                            for (int pb = 0; pb < PXW; ++pb) acc[cb][pb] = mfma16(a[cb], b[pb], acc[cb][pb]);
+                    }
+                }
+            }
+        }
         store_tile<CB, PXW, 4, false>(p, acc, outl, y, n, co_base, m0, tid);
     }
 }

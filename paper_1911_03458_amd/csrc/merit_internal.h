@@ -109,6 +109,7 @@ struct ConvParams {
     FastDiv div_rha;
     FastDiv div_g2;
     FastDiv div_w8;        // channel-blocked staging: 8-pixel chunks per row
+    FastDiv div_nchi;      // channel-blocked staging: channel groups per output channel
     FastDiv div_tiles;
 };
 

@@ -357,6 +357,8 @@ merit_status derive_conv(merit_plan *pl)
                 q.div_w8 = make_fastdiv((uint32_t)(W / 8));
             }
             if (!fastdiv_ok((int64_t)q.nchi * q.RHa, q.RHa)) return false;
+            if (!fastdiv_ok((int64_t)q.CB * 32 * q.nchi, q.nchi)) return false;
+            q.div_nchi = make_fastdiv((uint32_t)q.nchi);
             q.lds_o_offset = q.lds_w_bytes + q.lds_x_bytes;
         }
         q.lds_o_bytes = q.CB * 32 * (q.TM / 2 + 2) * 4;   // [channel][TM/2 + 2] dwords
