@@ -51,6 +51,8 @@ def _load():
     lib.ref_conv2d.argtypes = [vp, vp, vp] + [c_int] * 11
     lib.ref_conv2d_relu.restype = c_int
     lib.ref_conv2d_relu.argtypes = [vp, vp, vp] + [c_int] * 11
+    lib.ref_conv2d_depthwise.restype = c_int
+    lib.ref_conv2d_depthwise.argtypes = [vp, vp, vp] + [c_int] * 10
     lib.ref_correlation.restype = c_int
     lib.ref_correlation.argtypes = [vp, vp, vp] + [c_int] * 6
     lib.ref_conv2d_dilated.restype = c_int
@@ -124,6 +126,22 @@ def conv2d(x: np.ndarray, w: np.ndarray, stride=(1, 1), pad=(0, 0), relu=False, 
                                         dh, dw, 1 if relu else 0)
     if rc != 0:
         raise ValueError("ref_conv2d: bad shape")
+    return y
+
+
+def conv2d_depthwise(x: np.ndarray, w: np.ndarray, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
+    """x fp16 [N,C,H,W], w fp16 [C,kh,kw] (one kernel per channel) -> fp16 [N,C,OH,OW]."""
+    x = _c(x, np.float16)
+    w = _c(w, np.float16)
+    N, C, H, W = x.shape
+    if w.ndim != 3 or w.shape[0] != C:
+        raise ValueError("channel mismatch")
+    _, kh, kw = w.shape
+    sh, sw = stride
+    ph, pw = pad
+    y = np.empty((N, C, out_extent(H, kh, sh, ph), out_extent(W, kw, sw, pw)), np.float16)
+    if _load().ref_conv2d_depthwise(_ptr(x), _ptr(w), _ptr(y), N, C, H, W, kh, kw, sh, sw, ph, pw) != 0:
+        raise ValueError("ref_conv2d_depthwise: bad shape")
     return y
 
 

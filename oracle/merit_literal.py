@@ -157,6 +157,25 @@ def pool2d(x: np.ndarray, kernel=(3, 3), stride=(2, 2), pad=(1, 1), mode="max") 
     return rows.reshape(ranges[:4]).astype(np.float32)
 
 
+def depthwise_desc(N, C, H, W, kh, kw, sh, sw, ph, pw):
+    """k = (n, c, oy, ox | ky, kx): the input as in pooling, the weights w[c, ky, kx]."""
+    OH = (H + 2 * ph - kh) // sh + 1
+    OW = (W + 2 * pw - kw) // sw + 1
+    ranges = (N, C, OH, OW, kh, kw)
+    tx = Transform(axis=(0, 1, 2, 3, 2, 3), stride=(1, 1, sh, sw, 1, 1), offset=(0, 0, 0, 0, -ph, -pw))
+    tw = Transform(axis=(UNUSED, 0, UNUSED, UNUSED, 1, 2), stride=(0, 1, 0, 0, 1, 1), offset=(0,) * 6)
+    return ranges, 4, tx, tw
+
+
+def conv2d_depthwise(x: np.ndarray, w: np.ndarray, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
+    N, C, H, W = x.shape
+    _, kh, kw = w.shape
+    ranges, n_par, tx, tw = depthwise_desc(N, C, H, W, kh, kw, *stride, *pad)
+    MA, _ = transform(x.astype(np.float64), ranges, tx, n_par, "zero")
+    MB, _ = transform(w.astype(np.float64), ranges, tw, n_par, "zero")
+    return np.einsum("pa,pa->p", MA, MB).reshape(ranges[:4]).astype(np.float16)
+
+
 def correlation_desc(N, C, H, W, R, sd):
     """k = (b, p1, p2, p3, p4 | a1), Eq. 8: the second tensor moves with p1 + p3 and p2 + p4
     (two indices on one axis); displacements centred: offset -R*sd, stride sd."""

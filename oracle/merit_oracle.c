@@ -160,6 +160,42 @@ int ref_conv2d_dilated(const uint16_t *x, const uint16_t *w, uint16_t *y,
     return conv2d_postloop(x, w, y, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw, relu);
 }
 
+/*
+ * Depthwise convolution: every channel is convolved with its own kh x kw kernel
+ * (the dot product over the window indices only; the channel index is parallel):
+ *   y[n,c,oy,ox] = fp16( sum_{ky,kx} x[n,c,oy*sh+ky-ph,ox*sw+kx-pw] * w[c,ky,kx] ),
+ * zeros outside the image.  x: [N,C,H,W], w: [C,kh,kw], y: [N,C,OH,OW], binary16;
+ * double accumulation, one rounding.  Returns 0, or -1 on a bad shape.
+ */
+int ref_conv2d_depthwise(const uint16_t *x, const uint16_t *w, uint16_t *y,
+                         int N, int C, int H, int W, int kh, int kw, int sh, int sw, int ph, int pw)
+{
+    if (N < 0 || C <= 0 || H <= 0 || W <= 0 || kh <= 0 || kw <= 0 || sh <= 0 || sw <= 0 ||
+        ph < 0 || pw < 0) return -1;
+    if (H + 2 * ph < kh || W + 2 * pw < kw) return -1;
+    const int OH = (H + 2 * ph - kh) / sh + 1;
+    const int OW = (W + 2 * pw - kw) / sw + 1;
+    long nc;
+#pragma omp parallel for schedule(static)
+    for (nc = 0; nc < (long)N * C; ++nc) {
+        const int c = (int)(nc % C);
+        for (int oy = 0; oy < OH; ++oy)
+            for (int ox = 0; ox < OW; ++ox) {
+                double acc = 0.0;
+                for (int ky = 0; ky < kh; ++ky)
+                    for (int kx = 0; kx < kw; ++kx) {
+                        const int iy = oy * sh + ky - ph;
+                        const int ix = ox * sw + kx - pw;
+                        if (iy < 0 || iy >= H || ix < 0 || ix >= W) continue;
+                        acc += ref_half_to_double(x[((size_t)nc * H + iy) * W + ix]) *
+                               ref_half_to_double(w[((size_t)c * kh + ky) * kw + kx]);
+                    }
+                y[((size_t)nc * OH + oy) * OW + ox] = ref_double_to_half(acc);
+            }
+    }
+    return 0;
+}
+
 /* ------------------------------------------------------------------------ */
 /* 2-D pooling, fp32                                                         */
 /* ------------------------------------------------------------------------ */
