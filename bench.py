@@ -152,6 +152,32 @@ def bench_conv(torch, mb, wl, cfg, steps, warmup, nsets, relu=False):
     }
 
 
+def bench_depthwise(torch, mb, wl, cfg, steps, warmup, nsets):
+    x, w = wl.make_depthwise_inputs(cfg)
+    x0 = torch.from_numpy(x).to("cuda:0")
+    dw = torch.from_numpy(w).to("cuda:0")
+    plan = mb.merit_plan_conv2d_depthwise(cfg.N, cfg.C, cfg.H, cfg.W, cfg.kh, cfg.kw, cfg.sh, cfg.sw, cfg.ph, cfg.pw)
+    out_shape = plan.out_shape()
+    n_out = 1
+    for e in out_shape:
+        n_out *= int(e)
+    alg_bytes = x.nbytes + w.nbytes + n_out * 2
+    ns = nsets if alg_bytes > (8 << 20) else 1
+    xs = [x0] + [x0.roll(i, dims=0).contiguous() for i in range(1, ns)]
+    ys = [torch.empty(out_shape, dtype=torch.float16, device="cuda:0") for _ in range(ns)]
+    calls = [mb.bind_conv2d_depthwise(plan, xs[i], dw, ys[i]) for i in range(ns)]
+    wall, ev_ms = timed_region(torch, lambda i: calls[i % ns](), steps, warmup)
+    t = ev_ms * 1e-3 / steps
+    return {
+        "workload": cfg.name, "kernel": plan.launch_info()["kernel"], "avg_launch_us": t * 1e6,
+        "out_elems_per_s": n_out / t,
+        "achieved_hbm_gbs": alg_bytes / t / 1e9, "hbm_frac": alg_bytes / t / 1e9 / HBM_PEAK_GBS,
+        "rotating_sets": ns,
+        "roofline": {"bound": "hbm", "achieved": alg_bytes / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": alg_bytes / t / 1e9 / HBM_PEAK_GBS},
+    }
+
+
 def bench_corr(torch, mb, wl, cfg, steps, warmup):
     x1, x2 = wl.make_correlation_inputs(cfg)
     d1, d2 = torch.from_numpy(x1).to("cuda:0"), torch.from_numpy(x2).to("cuda:0")
@@ -264,6 +290,7 @@ def main():
             bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets, relu=True),
             bench_conv(torch, mb, wl, wl.CFG_DILATED, k, w, args.sets),
             bench_corr(torch, mb, wl, wl.CFG_CORRELATION, k, w),
+            bench_depthwise(torch, mb, wl, wl.CFG_DEPTHWISE, k, w, args.sets),
         ]
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(wl)

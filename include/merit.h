@@ -57,7 +57,8 @@ typedef enum {
     MERIT_OP_POOL_AVG = 2,
     MERIT_OP_SAD_ARGMIN = 3,
     MERIT_OP_CONV_DOT_RELU = 4,
-    MERIT_OP_CORR_DOT = 5     /* dot product over channels of two displaced tensors (Eq. 8) */
+    MERIT_OP_CORR_DOT = 5,    /* dot product over channels of two displaced tensors (Eq. 8) */
+    MERIT_OP_DWCONV_DOT = 6   /* dot product over the window only: one kernel per channel   */
 } merit_op;
 
 typedef enum { MERIT_U8 = 0, MERIT_F16 = 1, MERIT_F32 = 2 } merit_dtype;
@@ -93,6 +94,7 @@ typedef struct {
  *   POOL_AVG   F32 EXCLUDE  same
  *   SAD_ARGMIN U8  CLAMP    k=(by,bx | dy,dx,i,j)      a = ref[H,W] (displaced by dy,dx),
  *                                                      b = cur[H,W]
+ *   DWCONV_DOT F16 ZERO     k=(n,c,oy,ox | ky,kx)      a = x[N,C,H,W], b = w[C,kh,kw]
  *   CORR_DOT   F16 ZERO     k=(n,p1,p2,p3,p4 | c)      a = x1[N,C,H,W] at (p1,p2),
  *                                                      b = x2[N,C,H,W] at (p1+(p3-R)*sd, p2+(p4-R)*sd)
  * with output extents equal to floor((I + 2*pad - e)/s) + 1, e = (k-1)*d + 1.  The
@@ -150,6 +152,10 @@ merit_status merit_plan_conv2d_dilated(int N, int Cin, int H, int W, int Cout, i
 merit_status merit_plan_pool2d(int N, int C, int H, int W, int kh, int kw,
                                int sh, int sw, int ph, int pw, int is_avg, merit_plan **out);
 merit_status merit_plan_sad(int H, int W, int block, int range, merit_plan **out);
+/* Depthwise convolution (the depthwise row of the paper's table of further workloads):
+ * y[n,c,oy,ox] = sum_{ky,kx} x[n,c,oy*sh+ky-ph,ox*sw+kx-pw] * w[c,ky,kx]. */
+merit_status merit_plan_conv2d_depthwise(int N, int C, int H, int W, int kh, int kw, int sh, int sw,
+                                         int ph, int pw, merit_plan **out);
 /* Correlation layer (Section III-C, Eq. 8): y[n,p1,p2,p3,p4] = sum_c x1[n,c,p1,p2] *
  * x2[n,c,p1+(p3-R)*sd,p2+(p4-R)*sd], p3,p4 in [0, 2R]; 0 outside the image; no
  * normalisation by the channel count.  W must be a multiple of 8, R <= 15, sd <= 8. */
@@ -197,6 +203,11 @@ merit_status merit_pool2d(const merit_plan *plan, const void *x_f32, void *y_f32
  * edge.  (.) = Eq. 4, reference displaced as in Eq. 8. */
 merit_status merit_sad_search(const merit_plan *plan, const void *cur_u8, const void *ref_u8,
                               void *sad_i32, void *mv_i32, void *hip_stream);
+
+/* x_f16: [N,C,H,W], w_f16: [C,kh,kw], y_f16: [N,C,OH,OW], binary16.  Exact fp16 products,
+ * fp32 accumulation in window scan order, one rounding. */
+merit_status merit_conv2d_depthwise(const merit_plan *plan, const void *x_f16, const void *w_f16,
+                                    void *y_f16, void *hip_stream);
 
 /* x1_f16, x2_f16: [N,C,H,W] binary16; y_f16: [N,H,W,2R+1,2R+1] binary16 (the index order
  * (p1,p2,p3,p4) of Eq. 8).  Exact fp16 products, fp32 accumulation, one rounding. */

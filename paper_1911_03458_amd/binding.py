@@ -20,7 +20,7 @@ MERIT_OK = 0
 (MERIT_ERR_NULL, MERIT_ERR_INVALID_ARG, MERIT_ERR_SHAPE, MERIT_ERR_UNSUPPORTED,
  MERIT_ERR_ALIGNMENT, MERIT_ERR_HIP) = range(1, 7)
 (MERIT_OP_CONV_DOT, MERIT_OP_POOL_MAX, MERIT_OP_POOL_AVG, MERIT_OP_SAD_ARGMIN, MERIT_OP_CONV_DOT_RELU,
- MERIT_OP_CORR_DOT) = range(6)
+ MERIT_OP_CORR_DOT, MERIT_OP_DWCONV_DOT) = range(7)
 MERIT_U8, MERIT_F16, MERIT_F32 = range(3)
 MERIT_PAD_ZERO, MERIT_PAD_NEG_INF, MERIT_PAD_EXCLUDE, MERIT_PAD_CLAMP = range(4)
 
@@ -82,6 +82,8 @@ def lib():
     L.merit_plan_pool2d.argtypes = [c_int] * 11 + [PP]
     L.merit_plan_sad.argtypes = [c_int] * 4 + [PP]
     L.merit_plan_correlation.argtypes = [c_int] * 6 + [PP]
+    L.merit_plan_conv2d_depthwise.argtypes = [c_int] * 10 + [PP]
+    L.merit_conv2d_depthwise.argtypes = [P, P, P, P, P]
     L.merit_correlation.argtypes = [P, P, P, P, P]
     L.merit_plan_get_desc.argtypes = [P, ctypes.POINTER(merit_plan_desc)]
     L.merit_plan_out_shape.argtypes = [P, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)]
@@ -94,7 +96,8 @@ def lib():
     for name in ("merit_plan_create", "merit_plan_destroy", "merit_plan_conv2d", "merit_plan_conv2d_relu",
                  "merit_plan_conv2d_dilated",
                  "merit_plan_pool2d",
-                 "merit_plan_sad", "merit_plan_correlation", "merit_correlation", "merit_plan_get_desc", "merit_plan_out_shape", "merit_plan_footprint",
+                 "merit_plan_sad", "merit_plan_correlation", "merit_correlation", "merit_plan_conv2d_depthwise",
+                 "merit_conv2d_depthwise", "merit_plan_get_desc", "merit_plan_out_shape", "merit_plan_footprint",
                  "merit_plan_launch_info", "merit_plan_set_tile", "merit_conv2d", "merit_pool2d",
                  "merit_sad_search"):
         getattr(L, name).restype = c_int
@@ -279,6 +282,25 @@ def merit_sad_search(plan: Plan, cur, ref, sad=None, mv=None, stream=None):
     return sad, mv
 
 
+def merit_plan_conv2d_depthwise(N, C, H, W, kh, kw, sh, sw, ph, pw) -> Plan:
+    h = ctypes.c_void_p()
+    _check(lib().merit_plan_conv2d_depthwise(N, C, H, W, kh, kw, sh, sw, ph, pw, ctypes.byref(h)),
+           "merit_plan_conv2d_depthwise")
+    return Plan(h)
+
+
+def merit_conv2d_depthwise(plan: Plan, x, w, y=None, stream=None):
+    import torch
+    out_shape, a_shape, b_shape = plan.shapes()
+    if y is None:
+        y = torch.empty(out_shape, dtype=torch.float16, device=x.device)
+    if tuple(x.shape) != a_shape or tuple(w.shape) != b_shape or tuple(y.shape) != out_shape:
+        raise ValueError("tensors do not match the plan")
+    _check(lib().merit_conv2d_depthwise(plan.handle, _dev_ptr(x, torch.float16, "x"), _dev_ptr(w, torch.float16, "w"),
+                                        _dev_ptr(y, torch.float16, "y"), _stream(stream)), "merit_conv2d_depthwise")
+    return y
+
+
 def merit_plan_correlation(N, C, H, W, R, sd=1) -> Plan:
     h = ctypes.c_void_p()
     _check(lib().merit_plan_correlation(N, C, H, W, R, sd, ctypes.byref(h)), "merit_plan_correlation")
@@ -352,3 +374,13 @@ def bind_correlation(plan: Plan, x1, x2, y, stream=None) -> BoundCall:
     args = (plan.handle, _dev_ptr(x1, torch.float16, "x1"), _dev_ptr(x2, torch.float16, "x2"),
             _dev_ptr(y, torch.float16, "y"), _stream(stream))
     return BoundCall(lib().merit_correlation, "merit_correlation", args, (plan, x1, x2, y))
+
+
+def bind_conv2d_depthwise(plan: Plan, x, w, y, stream=None) -> BoundCall:
+    import torch
+    out_shape, a_shape, b_shape = plan.shapes()
+    if tuple(x.shape) != a_shape or tuple(w.shape) != b_shape or tuple(y.shape) != out_shape:
+        raise ValueError("tensors do not match the plan")
+    args = (plan.handle, _dev_ptr(x, torch.float16, "x"), _dev_ptr(w, torch.float16, "w"),
+            _dev_ptr(y, torch.float16, "y"), _stream(stream))
+    return BoundCall(lib().merit_conv2d_depthwise, "merit_conv2d_depthwise", args, (plan, x, w, y))

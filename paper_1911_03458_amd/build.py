@@ -10,7 +10,7 @@ ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libmerit.so")
 
-SOURCES = ["merit_plan.cpp", "pool2d.hip", "sad_search.hip", "conv2d.hip", "corr.hip"]
+SOURCES = ["merit_plan.cpp", "pool2d.hip", "sad_search.hip", "conv2d.hip", "corr.hip", "dwconv.hip"]
 HEADERS = [os.path.join(CSRC, "merit_internal.h"), os.path.join(ROOT, "include", "merit.h")]
 
 

@@ -134,6 +134,24 @@ struct CorrParams {
     FastDiv div_n, div_xchunks, div_h;
 };
 
+// ---- depthwise convolution -----------------------------------------------------
+enum DwVariant { DW_TILE_GENERIC = 0, DW_ROWS_K3S1P1 = 1 };
+
+struct DwParams {
+    int NC, C, H, W, OH, OW;
+    int kh, kw, sh, sw, ph, pw;
+    int variant;
+    int TH, tiles_y;       // output rows per workgroup, workgroups per plane
+    int pitch;             // generic: staged halves per row (W + 2*pw); rows variant: 16-byte chunks per row
+    int lds_w_offset;      // generic: byte offset of the float weights
+    int lds_bytes;
+    FastDiv div_tiles_y, div_c, div_pitch;
+    FastDiv div_ow;        // generic: OW; rows variant: W/8
+};
+
+hipError_t launch_dwconv(const DwParams &p, const void *x, const void *w, void *y, hipStream_t s);
+const char *dwconv_kernel_name(const DwParams &p);
+
 hipError_t launch_correlation(const CorrParams &p, const void *x1, const void *x2, void *y, hipStream_t s);
 size_t corr_lds_bytes(const CorrParams &p);
 
@@ -148,5 +166,6 @@ struct merit_plan {
     merit::SadParams sad;
     merit::ConvParams conv;
     merit::CorrParams corr;
+    merit::DwParams dw;
     merit_launch_info info;
 };

@@ -446,6 +446,83 @@ merit_status derive_conv(merit_plan *pl)
     return MERIT_OK;
 }
 
+// ----------------------------------------------------- depthwise convolution ---
+merit_status derive_dw(merit_plan *pl)
+{
+    const merit_plan_desc &d = pl->desc;
+    if (d.dtype != MERIT_F16 || d.pad != MERIT_PAD_ZERO) return MERIT_ERR_UNSUPPORTED;
+    if (d.n_par != 4 || d.n_acc != 2) return MERIT_ERR_UNSUPPORTED;
+    if (d.a.ndim != 4 || d.b.ndim != 3) return MERIT_ERR_UNSUPPORTED;
+    const int64_t DC = INT64_MIN;
+    const int axis_x[6] = {0, 1, 2, 3, 2, 3};
+    const int64_t stride_x[6] = {1, 1, DC, DC, 1, 1};
+    const int64_t offset_x[6] = {0, 0, 0, 0, DC, DC};
+    const int axis_w[6] = {MERIT_AXIS_UNUSED, 0, MERIT_AXIS_UNUSED, MERIT_AXIS_UNUSED, 1, 2};
+    const int64_t stride_w[6] = {0, 1, 0, 0, 1, 1};
+    const int64_t offset_w[6] = {0, 0, 0, 0, 0, 0};
+    if (!operand_is(d.a, 6, axis_x, stride_x, offset_x)) return MERIT_ERR_UNSUPPORTED;
+    if (!operand_is(d.b, 6, axis_w, stride_w, offset_w)) return MERIT_ERR_UNSUPPORTED;
+    const int64_t N = d.a.shape[0], C = d.a.shape[1], H = d.a.shape[2], W = d.a.shape[3];
+    const int64_t OH = d.range[2], OW = d.range[3], kh = d.range[4], kw = d.range[5];
+    const int64_t sh = d.a.stride[2], sw = d.a.stride[3];
+    const int64_t ph = -d.a.offset[4], pw = -d.a.offset[5];
+    if (N < 0 || C <= 0 || H <= 0 || W <= 0 || kh <= 0 || kw <= 0 || sh <= 0 || sw <= 0 || ph < 0 || pw < 0)
+        return MERIT_ERR_INVALID_ARG;
+    if (d.range[0] != N || d.range[1] != C || d.b.shape[0] != C || d.b.shape[1] != kh || d.b.shape[2] != kw)
+        return MERIT_ERR_SHAPE;
+    if (H + 2 * ph < kh || W + 2 * pw < kw) return MERIT_ERR_SHAPE;
+    if (OH != out_extent(H, kh, sh, ph) || OW != out_extent(W, kw, sw, pw)) return MERIT_ERR_SHAPE;
+    if (N * C >= INT_LIMIT || H * W >= INT_LIMIT || kh > 31 || kw > 31 || sh > 16 || sw > 16)
+        return MERIT_ERR_UNSUPPORTED;
+
+    DwParams &p = pl->dw;
+    p.NC = (int)(N * C); p.C = (int)C; p.H = (int)H; p.W = (int)W; p.OH = (int)OH; p.OW = (int)OW;
+    p.kh = (int)kh; p.kw = (int)kw; p.sh = (int)sh; p.sw = (int)sw; p.ph = (int)ph; p.pw = (int)pw;
+    if (kh == 3 && kw == 3 && sh == 1 && sw == 1 && ph == 1 && pw == 1 && (W % 8) == 0 && W <= 4096 &&
+        pl->tile_req[2] <= 0) {
+        p.variant = DW_ROWS_K3S1P1;
+        int64_t TH = 4096 / W;                       // about two 8-pixel units per thread
+        if (TH < 1) TH = 1;
+        if (TH > OH) TH = OH;
+        p.TH = (int)TH;
+        p.pitch = (int)(W / 8 + 2);
+        p.lds_w_offset = 0;
+        p.lds_bytes = (int)((TH + 2) * p.pitch * 16);
+        p.div_ow = make_fastdiv((uint32_t)(W / 8));
+    } else {
+        p.variant = DW_TILE_GENERIC;
+        p.pitch = (int)(W + 2 * pw);
+        int64_t TH = pl->tile_req[2] > 0 ? pl->tile_req[2] : (4096 / OW > 0 ? 4096 / OW : 1);
+        if (TH > OH) TH = OH;
+        while (TH > 1 && ((TH - 1) * sh + kh) * p.pitch * 2 > 48 * 1024) TH = (TH + 1) / 2;
+        const int64_t RH = (TH - 1) * sh + kh;
+        if (RH * p.pitch * 2 > 96 * 1024) return MERIT_ERR_UNSUPPORTED;      // very wide rows: no column tiling here
+        p.TH = (int)TH;
+        p.lds_w_offset = (int)round_up(RH * p.pitch * 2, 16);
+        p.lds_bytes = (int)(p.lds_w_offset + kh * kw * 4);
+        if (!fastdiv_ok(RH * p.pitch, p.pitch) || !fastdiv_ok(TH * OW, OW)) return MERIT_ERR_UNSUPPORTED;
+        p.div_ow = make_fastdiv((uint32_t)OW);
+    }
+    p.tiles_y = (int)cdiv(OH, p.TH);
+    const int64_t grid = (int64_t)p.NC * p.tiles_y;
+    if (grid >= INT_LIMIT || !fastdiv_ok(grid, p.tiles_y) || !fastdiv_ok(p.NC, C) ||
+        !fastdiv_ok((int64_t)(p.TH + 2 + kh * 16) * p.pitch, p.pitch))
+        return MERIT_ERR_UNSUPPORTED;
+    p.div_tiles_y = make_fastdiv((uint32_t)p.tiles_y);
+    p.div_c = make_fastdiv((uint32_t)C);
+    p.div_pitch = make_fastdiv((uint32_t)p.pitch);
+
+    pl->out_ndim = 4;
+    pl->out_shape[0] = N; pl->out_shape[1] = C; pl->out_shape[2] = OH; pl->out_shape[3] = OW;
+    merit_launch_info &li = pl->info;
+    li.kernel = dwconv_kernel_name(p);
+    li.grid[0] = grid; li.grid[1] = 1; li.grid[2] = 1;
+    li.block[0] = 256; li.block[1] = 1; li.block[2] = 1;
+    li.lds_bytes = p.lds_bytes;
+    li.tile[0] = 1; li.tile[1] = 1; li.tile[2] = p.TH; li.tile[3] = OW; li.tile[4] = kh; li.tile[5] = kw;
+    return MERIT_OK;
+}
+
 // -------------------------------------------------------- correlation layer ---
 merit_status derive_corr(merit_plan *pl)
 {
@@ -514,7 +591,7 @@ merit_status merit_plan_create(const merit_plan_desc *desc, merit_plan **out)
 {
     if (!desc || !out) return MERIT_ERR_NULL;
     *out = nullptr;
-    if ((int)desc->op < 0 || (int)desc->op > 5 || (int)desc->dtype < 0 || (int)desc->dtype > 2 ||
+    if ((int)desc->op < 0 || (int)desc->op > 6 || (int)desc->dtype < 0 || (int)desc->dtype > 2 ||
         (int)desc->pad < 0 || (int)desc->pad > 3)
         return MERIT_ERR_INVALID_ARG;
     if (desc->n_par < 1 || desc->n_acc < 1 || desc->n_par + desc->n_acc > MERIT_MAX_INDEX)
@@ -539,6 +616,7 @@ merit_status merit_plan_create(const merit_plan_desc *desc, merit_plan **out)
     case MERIT_OP_POOL_MAX:
     case MERIT_OP_POOL_AVG: st = derive_pool(pl); break;
     case MERIT_OP_CORR_DOT: st = derive_corr(pl); break;
+    case MERIT_OP_DWCONV_DOT: st = derive_dw(pl); break;
     default: st = derive_sad(pl); break;
     }
     if (st != MERIT_OK) {
@@ -677,6 +755,7 @@ merit_status merit_plan_set_tile(merit_plan *plan, const int64_t tile[MERIT_MAX_
     case MERIT_OP_POOL_MAX:
     case MERIT_OP_POOL_AVG: st = derive_pool(&trial); break;
     case MERIT_OP_CORR_DOT: st = derive_corr(&trial); break;
+    case MERIT_OP_DWCONV_DOT: st = derive_dw(&trial); break;
     default: st = derive_sad(&trial); break;
     }
     if (st != MERIT_OK) return st;          // the plan keeps its previous tiling
@@ -763,6 +842,45 @@ merit_status merit_sad_search(const merit_plan *plan, const void *cur, const voi
                       static_cast<hipStream_t>(stream)) == hipSuccess
                ? MERIT_OK
                : MERIT_ERR_HIP;
+}
+
+merit_status merit_plan_conv2d_depthwise(int N, int C, int H, int W, int kh, int kw, int sh, int sw, int ph, int pw,
+                                         merit_plan **out)
+{
+    if (!out) return MERIT_ERR_NULL;
+    *out = nullptr;
+    if (N < 0 || C <= 0 || H <= 0 || W <= 0 || kh <= 0 || kw <= 0 || sh <= 0 || sw <= 0 || ph < 0 || pw < 0)
+        return MERIT_ERR_INVALID_ARG;
+    if (H + 2 * ph < kh || W + 2 * pw < kw) return MERIT_ERR_SHAPE;
+    merit_plan_desc d;
+    std::memset(&d, 0, sizeof(d));
+    d.op = MERIT_OP_DWCONV_DOT; d.dtype = MERIT_F16; d.pad = MERIT_PAD_ZERO;
+    d.n_par = 4; d.n_acc = 2;
+    const int64_t OH = out_extent(H, kh, sh, ph), OW = out_extent(W, kw, sw, pw);
+    const int64_t range[6] = {N, C, OH, OW, kh, kw};
+    const int ax[6] = {0, 1, 2, 3, 2, 3};
+    const int64_t sx[6] = {1, 1, sh, sw, 1, 1};
+    const int64_t ox[6] = {0, 0, 0, 0, -ph, -pw};
+    const int aw[6] = {MERIT_AXIS_UNUSED, 0, MERIT_AXIS_UNUSED, MERIT_AXIS_UNUSED, 1, 2};
+    const int64_t sw_[6] = {0, 1, 0, 0, 1, 1};
+    for (int j = 0; j < 6; ++j) {
+        d.range[j] = range[j];
+        d.a.axis[j] = ax[j]; d.a.stride[j] = sx[j]; d.a.offset[j] = ox[j];
+        d.b.axis[j] = aw[j]; d.b.stride[j] = sw_[j]; d.b.offset[j] = 0;
+    }
+    d.a.ndim = 4; d.a.shape[0] = N; d.a.shape[1] = C; d.a.shape[2] = H; d.a.shape[3] = W;
+    d.b.ndim = 3; d.b.shape[0] = C; d.b.shape[1] = kh; d.b.shape[2] = kw;
+    return merit_plan_create(&d, out);
+}
+
+merit_status merit_conv2d_depthwise(const merit_plan *plan, const void *x, const void *w, void *y, void *stream)
+{
+    if (!plan) return MERIT_ERR_NULL;
+    if (plan->desc.op != MERIT_OP_DWCONV_DOT) return MERIT_ERR_INVALID_ARG;
+    if (plan->dw.NC == 0) return MERIT_OK;                // empty batch: nothing to read or write
+    if (!x || !w || !y) return MERIT_ERR_NULL;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return MERIT_ERR_ALIGNMENT;
+    return launch_dwconv(plan->dw, x, w, y, static_cast<hipStream_t>(stream)) == hipSuccess ? MERIT_OK : MERIT_ERR_HIP;
 }
 
 merit_status merit_plan_correlation(int N, int C, int H, int W, int R, int sd, merit_plan **out)

@@ -115,6 +115,26 @@ CFG_DILATED = ConvWorkload("conv_8x32x64x64_co32_k3s1p2_d2", 8, 32, 64, 64, 32, 
 
 
 @dataclass(frozen=True)
+class DepthwiseWorkload:
+    name: str
+    N: int
+    C: int
+    H: int
+    W: int
+    kh: int
+    kw: int
+    sh: int
+    sw: int
+    ph: int
+    pw: int
+
+
+# The depthwise row of the paper's table of further workloads: output 64 x 64 x 32 per image
+# (window and batch are not given there: the 3x3 / stride 1 / pad 1 MobileNet layer, batch 32).
+CFG_DEPTHWISE = DepthwiseWorkload("dwconv_32x32x64x64_k3s1p1", 32, 32, 64, 64, 3, 3, 1, 1, 1, 1)
+
+
+@dataclass(frozen=True)
 class CorrWorkload:
     name: str
     N: int
@@ -223,3 +243,11 @@ def make_correlation_inputs(wl: CorrWorkload, seed: int | None = None):
     b = np.roll(a, shift=(2, -4), axis=(2, 3)) + 0.5 * rng.standard_normal(size=a.shape).astype(np.float32)
     s = np.float32(1.0 / np.sqrt(wl.C))
     return (a * s).astype(np.float16), b.astype(np.float16)
+
+
+def make_depthwise_inputs(wl: DepthwiseWorkload, seed: int | None = None):
+    """x fp16 [N,C,H,W] ~ N(0,1); w fp16 [C,kh,kw] ~ N(0, 1/(kh*kw))."""
+    rng = np.random.default_rng(BASE_SEED + 8 if seed is None else seed)
+    x = rng.standard_normal(size=(wl.N, wl.C, wl.H, wl.W), dtype=np.float32)
+    w = rng.standard_normal(size=(wl.C, wl.kh, wl.kw), dtype=np.float32) / np.float32(np.sqrt(wl.kh * wl.kw))
+    return x.astype(np.float16), w.astype(np.float16)

@@ -87,6 +87,27 @@ def test_dilated_plan_is_the_papers_expression():
         "merit_conv2d_chblock"
 
 
+def test_depthwise_plan():
+    plan = mb.merit_plan_conv2d_depthwise(32, 32, 64, 64, 3, 3, 1, 1, 1, 1)
+    d = plan.desc()
+    ranges, n_par, tx, tw = lit.depthwise_desc(32, 32, 64, 64, 3, 3, 1, 1, 1, 1)
+    assert (d.op, d.n_par, d.n_acc) == (mb.MERIT_OP_DWCONV_DOT, 4, 2)
+    assert tuple(d.range[:6]) == ranges and plan.out_shape() == (32, 32, 64, 64)
+    assert _triples(d.a, 6) == list(zip(tx.axis, tx.stride, tx.offset))
+    for j in range(6):
+        assert d.b.axis[j] == tw.axis[j]
+    li = plan.launch_info()
+    assert li["kernel"] == "merit_dwconv_rows_k3s1p1" and li["grid"][0] == 32 * 32 * (64 // li["tile"][2])
+    assert plan.footprint(0, (1, 1, li["tile"][2], 64, 3, 3))[2:] == (li["tile"][2] + 2, 66)
+    plan.set_tile((0, 0, 8))
+    assert plan.launch_info()["kernel"] == "merit_dwconv_tile"
+    assert mb.merit_plan_conv2d_depthwise(1, 3, 9, 11, 5, 3, 2, 1, 2, 0).launch_info()["kernel"] == "merit_dwconv_tile"
+    d.b.shape[0] = 31                                                # one kernel per channel
+    with pytest.raises(mb.MeritError) as e:
+        mb.merit_plan_create(d)
+    assert e.value.status == mb.MERIT_ERR_SHAPE
+
+
 def test_correlation_plan_is_eq8():
     """M(I2) = I2[a1, p1 + p3, p2 + p4] (Section III-C, Eq. 8): two indices on one axis."""
     plan = mb.merit_plan_correlation(1, 256, 64, 64, 5, 2)

@@ -238,6 +238,62 @@ def test_sad_full_hd_workload(mb):
     assert np.array_equal(mv, omv)
 
 
+# -------------------------------------------------- depthwise convolution
+DW_CASES = [
+    # N  C   H   W  kh kw sh sw ph pw tile
+    (1, 3, 9, 16, 3, 3, 1, 1, 1, 1, None),       # row kernel, one strip
+    (2, 5, 70, 64, 3, 3, 1, 1, 1, 1, None),      # row kernel, two strips, the second ragged
+    (1, 2, 12, 136, 3, 3, 1, 1, 1, 1, None),     # row kernel, wide rows
+    (2, 5, 70, 64, 3, 3, 1, 1, 1, 1, (0, 0, 16)),  # generic kernel on the same shape
+    (1, 4, 11, 13, 3, 3, 2, 2, 1, 1, None),      # generic: stride 2, odd sizes
+    (2, 3, 17, 10, 5, 3, 1, 2, 2, 0, None),      # generic: rectangular window, mixed stride / padding
+    (1, 1, 8, 8, 1, 1, 1, 1, 0, 0, None),        # pointwise scale
+]
+
+
+@pytest.mark.parametrize("case", DW_CASES)
+def test_depthwise(mb, case):
+    N, C, H, W, kh, kw, sh, sw, ph, pw, tile = case
+    rng = np.random.default_rng(abs(hash(case[:10])) % 2 ** 31)
+    x = rng.standard_normal((N, C, H, W)).astype(np.float16)
+    w = (rng.standard_normal((C, kh, kw)) / np.sqrt(kh * kw)).astype(np.float16)
+    plan = mb.merit_plan_conv2d_depthwise(N, C, H, W, kh, kw, sh, sw, ph, pw)
+    if tile is not None:
+        plan.set_tile(tile)
+    print("dwconv", case, plan.launch_info(), flush=True)
+    buf, y, pad = guarded_empty(plan.out_shape(), torch.float16, 777.0)
+    mb.merit_conv2d_depthwise(plan, dev(x), dev(w), y)
+    torch.cuda.synchronize()
+    check_canary(buf, pad, 777.0)
+    got = y.cpu().numpy().astype(np.float64)
+    ref = oracle.conv2d_depthwise(x, w, (sh, sw), (ph, pw)).astype(np.float64)
+    assert got.shape == ref.shape
+    assert np.all(np.abs(got - ref) <= 2e-2 * np.abs(ref) + 1e-3)
+
+
+def test_depthwise_one_hot_taps_are_exact(mb):
+    rng = np.random.default_rng(7)
+    x = rng.standard_normal((1, 2, 16, 24)).astype(np.float16)
+    w = np.zeros((2, 3, 3), np.float16)
+    w[0, 0, 2] = 1.0
+    w[1, 1, 1] = 1.0
+    y = mb.merit_conv2d_depthwise(mb.merit_plan_conv2d_depthwise(1, 2, 16, 24, 3, 3, 1, 1, 1, 1), dev(x), dev(w))
+    y = y.cpu().numpy()
+    want = np.zeros((16, 24), np.float16)
+    want[1:, :-1] = x[0, 0, :-1, 1:]
+    assert np.array_equal(y[0, 1], x[0, 1]) and np.array_equal(y[0, 0], want)
+
+
+def test_depthwise_workload(mb):
+    c = wl.CFG_DEPTHWISE
+    x, w = wl.make_depthwise_inputs(c)
+    plan = mb.merit_plan_conv2d_depthwise(c.N, c.C, c.H, c.W, c.kh, c.kw, c.sh, c.sw, c.ph, c.pw)
+    assert plan.launch_info()["kernel"] == "merit_dwconv_rows_k3s1p1"
+    y = mb.merit_conv2d_depthwise(plan, dev(x), dev(w)).cpu().numpy().astype(np.float64)
+    ref = oracle.conv2d_depthwise(x, w, (c.sh, c.sw), (c.ph, c.pw)).astype(np.float64)
+    assert np.all(np.abs(y - ref) <= 2e-2 * np.abs(ref) + 1e-3)
+
+
 # ------------------------------------------------------- correlation layer
 CORR_CASES = [
     # N  C   H   W   R  sd
