@@ -129,6 +129,14 @@ def conv2d(x: np.ndarray, w: np.ndarray, stride=(1, 1), pad=(0, 0), relu=False, 
     return y
 
 
+def conv2d_pool(x: np.ndarray, w: np.ndarray, stride=(1, 1), pad=(0, 0), relu=True) -> np.ndarray:
+    """Convolution (optionally with the clipped product function) followed by 3x3 / stride 2 /
+    pad 1 max pooling of its binary16 results: two ranged inner products in a row, each as
+    defined above (the maximum of binary16 values is exact, so nothing else is rounded)."""
+    y = conv2d(x, w, stride, pad, relu=relu)
+    return pool2d(y.astype(np.float32), (3, 3), (2, 2), (1, 1), "max").astype(np.float16)
+
+
 def conv2d_depthwise(x: np.ndarray, w: np.ndarray, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
     """x fp16 [N,C,H,W], w fp16 [C,kh,kw] (one kernel per channel) -> fp16 [N,C,OH,OW]."""
     x = _c(x, np.float16)

@@ -260,3 +260,26 @@ def test_dilated_matches_literal_evaluator_and_torch():
     ref = torch.nn.functional.conv2d(torch.from_numpy(x.astype(np.float64)), torch.from_numpy(w.astype(np.float64)),
                                      stride=(2, 1), padding=(2, 3), dilation=(2, 3)).numpy()
     assert np.allclose(got.astype(np.float64), ref, rtol=2e-3, atol=1e-3)
+
+
+# ------------------------------------------- convolution followed by 3x3 / s2 / p1 max pooling
+def test_conv_pool_closed_form_and_library():
+    """Ones * ones: conv gives the valid-tap count, whose 3x3 maximum is the full count
+    Cin*9 everywhere for a 3x3 / s1 / p1 conv on >= 3x3 interiors; random data against the
+    CPU library's relu -> max_pool2d."""
+    x = np.ones((1, 2, 8, 8), np.float16)
+    w = np.ones((3, 2, 3, 3), np.float16)
+    y = oracle.conv2d_pool(x, w, (1, 1), (1, 1), relu=True).astype(np.float64)
+    assert y.shape == (1, 3, 4, 4)
+    assert y[0, 0, 0, 0] == 2 * 9 and np.all(y[0, :, 1:, 1:] == 18) and y[0, 2, 0, 3] == 18
+    rng = np.random.default_rng(71)
+    x = _rand_half(rng, (2, 3, 16, 16))
+    w = _rand_half(rng, (4, 3, 7, 7), 0.1)
+    got = oracle.conv2d_pool(x, w, (2, 2), (3, 3), relu=True).astype(np.float64)
+    t = torch.nn.functional.conv2d(torch.from_numpy(x.astype(np.float64)), torch.from_numpy(w.astype(np.float64)),
+                                   stride=2, padding=3)
+    ref = torch.nn.functional.max_pool2d(torch.relu(t), 3, 2, 1).numpy()
+    assert got.shape == ref.shape == (2, 4, 4, 4)
+    assert np.allclose(got, ref, rtol=2e-3, atol=1e-3)
+    plain = oracle.conv2d_pool(x, w, (2, 2), (3, 3), relu=False).astype(np.float64)
+    assert np.array_equal(np.maximum(plain, 0.0), got)        # ReLU and max commute
