@@ -121,17 +121,22 @@ def bench_sad(torch, mb, wl, cfg, steps, warmup):
     }
 
 
-def bench_conv(torch, mb, wl, cfg, steps, warmup, nsets, relu=False):
+def bench_conv(torch, mb, wl, cfg, steps, warmup, nsets, relu=False, pool=False):
     x, w = wl.make_conv_inputs(cfg)
     x0 = torch.from_numpy(x).to("cuda:0")
     dw = torch.from_numpy(w).to("cuda:0")
     in_bytes = x.nbytes + w.nbytes
-    out_bytes = cfg.N * cfg.Cout * cfg.OH * cfg.OW * 2
+    # fused 3x3/s2/p1 max pooling: only the pooled tensor is written
+    oh, ow = (cfg.OH // 2, cfg.OW // 2) if pool else (cfg.OH, cfg.OW)
+    out_bytes = cfg.N * cfg.Cout * oh * ow * 2
     # rotate only when a set would otherwise stay resident in the Infinity Cache
     ns = nsets if (in_bytes + out_bytes) > (8 << 20) else 1
     xs = [x0] + [x0.roll(i, dims=0).contiguous() for i in range(1, ns)]
-    ys = [torch.empty((cfg.N, cfg.Cout, cfg.OH, cfg.OW), dtype=torch.float16, device="cuda:0") for _ in range(ns)]
-    if (cfg.dh, cfg.dw) != (1, 1):
+    ys = [torch.empty((cfg.N, cfg.Cout, oh, ow), dtype=torch.float16, device="cuda:0") for _ in range(ns)]
+    if pool:
+        plan = mb.merit_plan_conv2d_pool(cfg.N, cfg.Cin, cfg.H, cfg.W, cfg.Cout, cfg.kh, cfg.kw, cfg.sh, cfg.sw,
+                                         cfg.ph, cfg.pw, int(relu))
+    elif (cfg.dh, cfg.dw) != (1, 1):
         plan = mb.merit_plan_conv2d_dilated(cfg.N, cfg.Cin, cfg.H, cfg.W, cfg.Cout, cfg.kh, cfg.kw, cfg.sh, cfg.sw,
                                             cfg.ph, cfg.pw, cfg.dh, cfg.dw, int(relu))
     else:
@@ -142,9 +147,10 @@ def bench_conv(torch, mb, wl, cfg, steps, warmup, nsets, relu=False):
     t = ev_ms * 1e-3 / steps
     flops = 2.0 * cfg.N * cfg.Cout * cfg.OH * cfg.OW * cfg.Cin * cfg.kh * cfg.kw
     return {
-        "workload": cfg.name + (" + fused ReLU" if relu else ""), "kernel": plan.launch_info()["kernel"],
+        "workload": cfg.name + (" + fused ReLU" if relu else "") + (" + fused 3x3/s2/p1 max pooling" if pool else ""),
+        "kernel": plan.launch_info()["kernel"],
         "avg_launch_us": t * 1e6,
-        "out_elems_per_s": cfg.N * cfg.Cout * cfg.OH * cfg.OW / t,
+        "out_elems_per_s": cfg.N * cfg.Cout * oh * ow / t,
         "achieved_tflops": flops / t / 1e12, "mfma_frac": flops / t / 1e12 / MFMA_F16_PEAK_TFLOPS,
         "achieved_hbm_gbs": (in_bytes + out_bytes) / t / 1e9,
         "hbm_frac": (in_bytes + out_bytes) / t / 1e9 / HBM_PEAK_GBS,
@@ -288,6 +294,7 @@ def main():
             bench_sad(torch, mb, wl, wl.CFG_ME_720P, k, w),
             bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets),
             bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets, relu=True),
+            bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets, relu=True, pool=True),
             bench_conv(torch, mb, wl, wl.CFG_DILATED, k, w, args.sets),
             bench_corr(torch, mb, wl, wl.CFG_CORRELATION, k, w),
             bench_depthwise(torch, mb, wl, wl.CFG_DEPTHWISE, k, w, args.sets),

@@ -58,7 +58,12 @@ typedef enum {
     MERIT_OP_SAD_ARGMIN = 3,
     MERIT_OP_CONV_DOT_RELU = 4,
     MERIT_OP_CORR_DOT = 5,    /* dot product over channels of two displaced tensors (Eq. 8) */
-    MERIT_OP_DWCONV_DOT = 6   /* dot product over the window only: one kernel per channel   */
+    MERIT_OP_DWCONV_DOT = 6,  /* dot product over the window only: one kernel per channel   */
+    /* convolution (plain / clipped product) whose binary16 result goes through a 3x3, stride 2,
+     * padding 1 max pooling before it leaves the chip: the fused "CONV+Pool" layers of the
+     * per-layer network table in Section VI-C.  The descriptor is the convolution's. */
+    MERIT_OP_CONV_DOT_POOLMAX = 7,
+    MERIT_OP_CONV_DOT_RELU_POOLMAX = 8
 } merit_op;
 
 typedef enum { MERIT_U8 = 0, MERIT_F16 = 1, MERIT_F32 = 2 } merit_dtype;
@@ -149,6 +154,14 @@ merit_status merit_plan_conv2d_relu(int N, int Cin, int H, int W, int Cout, int 
 merit_status merit_plan_conv2d_dilated(int N, int Cin, int H, int W, int Cout, int kh, int kw,
                                        int sh, int sw, int ph, int pw, int dh, int dw, int relu,
                                        merit_plan **out);
+/* Convolution, optional clipping (relu != 0), then max pooling with a 3x3 window, stride 2,
+ * padding 1 (-inf outside) of the binary16 convolution result, as one kernel: the convolution
+ * output never reaches memory (the fused "CONV+Pool" layers of the per-layer table in
+ * Section VI-C).  Output [N,Cout,OH/2,OW/2].  Built on the kernel for few input channels:
+ * Cin < 8, W % 8 == 0, OH even, OW % 16 == 0 and OW <= 128; anything else is
+ * MERIT_ERR_UNSUPPORTED (run merit_conv2d and merit_pool2d one after the other). */
+merit_status merit_plan_conv2d_pool(int N, int Cin, int H, int W, int Cout, int kh, int kw,
+                                    int sh, int sw, int ph, int pw, int relu, merit_plan **out);
 merit_status merit_plan_pool2d(int N, int C, int H, int W, int kh, int kw,
                                int sh, int sw, int ph, int pw, int is_avg, merit_plan **out);
 merit_status merit_plan_sad(int H, int W, int block, int range, merit_plan **out);
@@ -164,7 +177,7 @@ merit_status merit_plan_correlation(int N, int C, int H, int W, int R, int sd, m
 /* Copy of the descriptor the plan was created from. */
 merit_status merit_plan_get_desc(const merit_plan *plan, merit_plan_desc *out);
 /* Output tensor shape: the parallel ranges ([N,Cout,OH,OW], [N,C,OH,OW], [nby,nbx],
- * [N,H,W,2R+1,2R+1]). */
+ * [N,H,W,2R+1,2R+1]); [N,Cout,OH/2,OW/2] for a fused convolution + pooling plan. */
 merit_status merit_plan_out_shape(const merit_plan *plan, int32_t *ndim, int64_t shape[MERIT_MAX_DIMS]);
 /* Size of the minimal sub-tensor of operand `which` (0 = a, 1 = b) that contains
  * a tile of M(.) with extents tile[0 .. n_par+n_acc-1]:
@@ -189,7 +202,9 @@ merit_status merit_plan_set_tile(merit_plan *plan, const int64_t tile[MERIT_MAX_
  * x_f16: [N,Cin,H,W] binary16; w_f16: [Cout,Cin,kh,kw] binary16;
  * y_f16: [N,Cout,OH,OW] binary16.  Products accumulate in fp32 on the matrix
  * cores and are rounded once (nearest even) to binary16.  (.) = Eq. 3, or its
- * clipped form for a CONV_DOT_RELU plan. */
+ * clipped form for a CONV_DOT_RELU plan.  For a plan from merit_plan_conv2d_pool
+ * y_f16 is the pooled tensor [N,Cout,OH/2,OW/2]: the exact maximum of the rounded
+ * convolution results in each window. */
 merit_status merit_conv2d(const merit_plan *plan, const void *x_f16, const void *w_f16,
                           void *y_f16, void *hip_stream);
 

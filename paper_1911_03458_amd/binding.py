@@ -20,7 +20,7 @@ MERIT_OK = 0
 (MERIT_ERR_NULL, MERIT_ERR_INVALID_ARG, MERIT_ERR_SHAPE, MERIT_ERR_UNSUPPORTED,
  MERIT_ERR_ALIGNMENT, MERIT_ERR_HIP) = range(1, 7)
 (MERIT_OP_CONV_DOT, MERIT_OP_POOL_MAX, MERIT_OP_POOL_AVG, MERIT_OP_SAD_ARGMIN, MERIT_OP_CONV_DOT_RELU,
- MERIT_OP_CORR_DOT, MERIT_OP_DWCONV_DOT) = range(7)
+ MERIT_OP_CORR_DOT, MERIT_OP_DWCONV_DOT, MERIT_OP_CONV_DOT_POOLMAX, MERIT_OP_CONV_DOT_RELU_POOLMAX) = range(9)
 MERIT_U8, MERIT_F16, MERIT_F32 = range(3)
 MERIT_PAD_ZERO, MERIT_PAD_NEG_INF, MERIT_PAD_EXCLUDE, MERIT_PAD_CLAMP = range(4)
 
@@ -79,6 +79,7 @@ def lib():
     L.merit_plan_conv2d.argtypes = [c_int] * 11 + [PP]
     L.merit_plan_conv2d_relu.argtypes = [c_int] * 11 + [PP]
     L.merit_plan_conv2d_dilated.argtypes = [c_int] * 14 + [PP]
+    L.merit_plan_conv2d_pool.argtypes = [c_int] * 12 + [PP]
     L.merit_plan_pool2d.argtypes = [c_int] * 11 + [PP]
     L.merit_plan_sad.argtypes = [c_int] * 4 + [PP]
     L.merit_plan_correlation.argtypes = [c_int] * 6 + [PP]
@@ -94,7 +95,7 @@ def lib():
     L.merit_pool2d.argtypes = [P, P, P, P]
     L.merit_sad_search.argtypes = [P, P, P, P, P, P]
     for name in ("merit_plan_create", "merit_plan_destroy", "merit_plan_conv2d", "merit_plan_conv2d_relu",
-                 "merit_plan_conv2d_dilated",
+                 "merit_plan_conv2d_dilated", "merit_plan_conv2d_pool",
                  "merit_plan_pool2d",
                  "merit_plan_sad", "merit_plan_correlation", "merit_correlation", "merit_plan_conv2d_depthwise",
                  "merit_conv2d_depthwise", "merit_plan_get_desc", "merit_plan_out_shape", "merit_plan_footprint",
@@ -198,6 +199,13 @@ def merit_plan_conv2d_dilated(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw
     h = ctypes.c_void_p()
     _check(lib().merit_plan_conv2d_dilated(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw, int(relu),
                                            ctypes.byref(h)), "merit_plan_conv2d_dilated")
+    return Plan(h)
+
+
+def merit_plan_conv2d_pool(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, relu=1) -> Plan:
+    h = ctypes.c_void_p()
+    _check(lib().merit_plan_conv2d_pool(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, int(relu), ctypes.byref(h)),
+           "merit_plan_conv2d_pool")
     return Plan(h)
 
 

@@ -4,6 +4,7 @@ from __future__ import annotations
 import os
 import shutil
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
@@ -33,16 +34,27 @@ def build_library(force: bool = True, extra_flags=()) -> str:
     """Compile every HIP source for gfx950 into one shared library."""
     if not force and not is_stale():
         return LIB_PATH
-    cmd = [hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-           # keep hipcc from forming packed-fp32 VALU ops
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wall", "-Wno-unused-command-line-argument",
-           "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           *extra_flags,
-           "-o", LIB_PATH] + [os.path.join(CSRC, s) for s in SOURCES]
-    proc = subprocess.run(cmd, capture_output=True, text=True)
+    common = [hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+              # keep hipcc from forming packed-fp32 VALU ops
+              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+              "-Wall", "-Wno-unused-command-line-argument",
+              "-I", os.path.join(ROOT, "include"), "-I", CSRC, *extra_flags]
+    # one object per source, compiled side by side (the convolution file dominates), then one link
+    objdir = os.path.join(_HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    objs = [os.path.join(objdir, os.path.splitext(s)[0] + ".o") for s in SOURCES]
+
+    def compile_one(job):
+        src, obj = job
+        return subprocess.run(common + ["-c", os.path.join(CSRC, src), "-o", obj], capture_output=True, text=True)
+
+    with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1)) as pool:
+        for proc in pool.map(compile_one, zip(SOURCES, objs)):
+            if proc.returncode != 0:
+                raise RuntimeError("hipcc failed:\n" + proc.stdout + proc.stderr)
+    proc = subprocess.run(common + ["-shared", "-o", LIB_PATH] + objs, capture_output=True, text=True)
     if proc.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + proc.stdout + proc.stderr)
+        raise RuntimeError("hipcc (link) failed:\n" + proc.stdout + proc.stderr)
     return LIB_PATH
 
 

@@ -471,8 +471,46 @@ __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, 
 // wavefronts and is covered by a whole K loop of the multiplier wavefronts.
 // Needs W % 8 == 0, OH*OW % 8 == 0, tensors below 2 GiB and at most 10 staging units per
 // loading thread.
+//
+// POOL: the convolution feeds a 3x3 / stride 2 / padding 1 max pooling and only the pooled
+// tensor is written (the fused CONV+Pool layers of the per-layer table in Section VI-C).
+// A workgroup owns a band of PB pooled rows of one image; its tile i is the pair of
+// convolution rows 2r, 2r+1 with r = band*PB - 1 + i (two whole rows of OW <= 128 pixels in
+// the 256-pixel tile).  Pooled row r needs rows 2r-1, 2r, 2r+1: the storing wavefronts take
+// the element-wise maximum of both rows of a tile and the previous tile's second row (carried
+// in registers: every unit of 8 pooled pixels belongs to one thread for the whole band), then
+// the 3-maxima along the row at stride 2, and store 8 pooled pixels per unit.  Tile 0 of a
+// band only fills the carry (-inf above the image).  All maxima are v_pk_maximum3_f16.
 // ---------------------------------------------------------------------------
-template <int CB, bool ALIGNED, int SU>
+// elementwise maximum of three binary16 pairs: one v_pk_maximum3_f16
+__device__ __forceinline__ uint32_t pkmax3_f16x2(uint32_t a, uint32_t b, uint32_t c)
+{
+    return __builtin_bit_cast(
+        uint32_t, __builtin_elementwise_maximum(
+                      __builtin_elementwise_maximum(__builtin_bit_cast(half2v, a), __builtin_bit_cast(half2v, b)),
+                      __builtin_bit_cast(half2v, c)));
+}
+
+// column-wise 3-maxima of one row at stride 2: d[k] = columns 2k, 2k+1 of the unit (binary16
+// pairs), left = the pair before d[0]; result = 8 pooled pixels m_k = max(col 2k-1, 2k, 2k+1),
+// two at a time: { m_2j, m_2j+1 } = max( {col 4j, col 4j+2}, {col 4j+1, col 4j+3}, {col 4j-1, col 4j+1} )
+__device__ __forceinline__ uint32x4 row_max3_s2(uint32_t left, const uint32_t (&d)[8])
+{
+    uint32_t o[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t before = j == 0 ? left : d[2 * j - 1];
+        const uint32_t ev = __builtin_amdgcn_perm(d[2 * j + 1], d[2 * j], 0x05040100u);
+        const uint32_t od = __builtin_amdgcn_perm(d[2 * j + 1], d[2 * j], 0x07060302u);
+        const uint32_t pv = __builtin_amdgcn_perm(d[2 * j], before, 0x07060302u);
+        o[j] = pkmax3_f16x2(ev, od, pv);
+    }
+    uint32x4 r;
+    r.x = o[0]; r.y = o[1]; r.z = o[2]; r.w = o[3];
+    return r;
+}
+
+template <int CB, bool ALIGNED, int SU, bool POOL>
 __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, const uint16_t *__restrict__ x,
                                                                 const uint16_t *__restrict__ w,
                                                                 uint16_t *__restrict__ y)
@@ -563,12 +601,26 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
     const int ntiles = p.N * p.tiles_per_image;
     const int nwg = (int)gridDim.x;
     const int lw = (nwg % 8 == 0) ? (int)(blockIdx.x % 8) * (nwg / 8) + (int)(blockIdx.x / 8) : (int)blockIdx.x;
-    const int K = (ntiles - lw + nwg - 1) / nwg;          // tiles of this workgroup (>= 1)
+    // POOL: workgroup lw = (image, band); tile i = convolution row pair rp0 + i
+    const int band_n = POOL ? (int)fdiv((uint32_t)lw, p.div_nb) : 0;
+    const int band = POOL ? lw - band_n * p.NB : 0;
+    const int rp0 = band * p.PB - 1;
+    const int K = POOL ? min(p.PB, p.PH - band * p.PB) + 1
+                       : (ntiles - lw + nwg - 1) / nwg;   // tiles of this workgroup (>= 1)
 
     struct Geom {
         int n, m0, oyA, yA, RH;
     };
     auto geom = [&](int i) {                              // i-th tile of this workgroup, clamped
+        if constexpr (POOL) {
+            Geom g;
+            g.n = band_n;
+            g.m0 = 0;
+            g.oyA = 2 * (rp0 + min(i, K - 1));            // -2 for the tile above the image: all zeros
+            g.yA = g.oyA * p.sh - p.ph;
+            g.RH = p.sh + p.kh;
+            return g;
+        }
         const int tile = lw + min(i, K - 1) * nwg;
         Geom g;
         g.n = (int)fdiv((uint32_t)tile, p.div_tiles);
@@ -588,8 +640,8 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
     constexpr uint32_t OOB = 0x80000000u;
     const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint16_t *>(x), 0, (int)((size_t)p.N * p.Cin * p.H * p.W * 2), 0x00020000);
-    const __amdgpu_buffer_rsrc_t ry =
-        __builtin_amdgcn_make_buffer_rsrc(y, 0, (int)((size_t)p.N * p.Cout * ohw * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(
+        y, 0, (int)((size_t)p.N * p.Cout * (POOL ? p.PH * p.PW : ohw) * 2), 0x00020000);
     // Loading thread t owns 16-byte column chunk t % 2^lgc of the staged rows
     // q = t / 2^lgc + (128 >> lgc) k  (q = ci*RHa + r; 2^lgc >= chunks per row), so that a
     // thread's column tests are shared by all its units and only q needs a division.
@@ -659,6 +711,65 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
         }
     };
 
+    // POOL: thread t owns the units u = t + 128k (u = channel * pw8 + 8-pixel unit of the pooled row)
+    constexpr int PU = 2 * CB;                            // CB*32 channels x at most 8 units / 128 threads
+    constexpr uint32_t NEG = 0xFC00FC00u;                 // two binary16 -inf
+    int pl_src[PU];                                       // dword of the unit's first column pair in a staged tile
+    uint32_t pl_y[PU];                                    // byte offset of the unit inside an image's pooled rows
+    bool pl_live[PU], pl_left[PU];
+    uint32_t carry[PU][9];                                // previous tile's second row: 8 pairs + the pair before
+    if constexpr (POOL) {
+        const int units = CB * 32 * p.pw8;
+#pragma unroll
+        for (int k = 0; k < PU; ++k) {
+            const int u = t + NTG * k;
+            const int uc = min(u, units - 1);
+            const int c = (int)fdiv((uint32_t)uc, p.div_pw8);
+            const int ux = uc - c * p.pw8;
+            pl_src[k] = c * OPW + 8 * ux;
+            pl_y[k] = (uint32_t)(c * p.PH * p.PW + 8 * ux) * 2u;
+            pl_live[k] = u < units && c < p.Cout - co_base;
+            pl_left[k] = ux > 0;
+#pragma unroll
+            for (int q = 0; q < 9; ++q) carry[k][q] = NEG;
+        }
+    }
+    auto pool_tile_ws = [&](int i) {
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(outl0 + (i & 1) * ostride);
+        const int py = rp0 + i;                           // pooled row this tile completes (i >= 1)
+        const uint32_t soff = (uint32_t)((((size_t)band_n * p.Cout + co_base) * p.PH + max(py, 0)) * p.PW) * 2u;
+        const bool above = py < 0;                        // the tile above the image: its rows count as -inf
+        const int rowd = p.OW >> 1;                       // dwords per convolution row
+#pragma unroll
+        for (int k = 0; k < PU; ++k) {
+            const uint32_t *ra = src + pl_src[k];
+            const uint32_t *rb = ra + rowd;
+            uint32_t a[8], b[8];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint2 va = *reinterpret_cast<const uint2 *>(ra + 2 * q);
+                const uint2 vb = *reinterpret_cast<const uint2 *>(rb + 2 * q);
+                a[2 * q] = va.x; a[2 * q + 1] = va.y;
+                b[2 * q] = vb.x; b[2 * q + 1] = vb.y;
+            }
+            const int lo = pl_left[k] ? -1 : 0;           // column -1 is padding (-inf)
+            const uint32_t la_raw = ra[lo], lb_raw = rb[lo];
+            const uint32_t la = pl_left[k] ? la_raw : NEG;
+            const uint32_t lb = pl_left[k] ? lb_raw : NEG;
+            uint32_t m[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) m[q] = pkmax3_f16x2(a[q], b[q], carry[k][q]);
+            const uint32_t ml = pkmax3_f16x2(la, lb, carry[k][8]);
+            const uint32x4 v = row_max3_s2(ml, m);
+#pragma unroll
+            for (int q = 0; q < 8; ++q) carry[k][q] = above ? NEG : b[q];
+            carry[k][8] = above ? NEG : lb;
+            // whole offset in the vector register, scalar offset 0 (see store_tile_ws)
+            const uint32_t voff = (i >= 1 && pl_live[k]) ? pl_y[k] + soff : OOB;
+            __builtin_amdgcn_raw_buffer_store_b128(v, ry, voff, 0, 3);
+        }
+    };
+
     // first input tile requested as early as its addresses are known
     if (loader) issue_loads(geom(0));
 
@@ -686,12 +797,21 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
         uint32_t pbase[PXW], shift[PXW];
 #pragma unroll
         for (int pb = 0; pb < PXW; ++pb) {
-            const int m = T.m0 + (cwave * PXW + pb) * 32 + c32;
-            const int mm = min(m, ohw - 1);
-            const int oy = (int)fdiv((uint32_t)mm, p.div_ow);
-            const int ox = mm - oy * p.OW;
+            int oyl, ox;                                  // output row inside the staged tile, column
+            if constexpr (POOL) {
+                // two whole rows; pixels past them repeat the last one (never pooled)
+                const int idx = min((cwave * PXW + pb) * 32 + c32, 2 * p.OW - 1);
+                oyl = idx >= p.OW ? 1 : 0;
+                ox = idx - oyl * p.OW;
+            } else {
+                const int m = T.m0 + (cwave * PXW + pb) * 32 + c32;
+                const int mm = min(m, ohw - 1);
+                const int oy = (int)fdiv((uint32_t)mm, p.div_ow);
+                ox = mm - oy * p.OW;
+                oyl = oy - T.oyA;
+            }
             const int cs = p.padl - p.pw + ox * p.sw - p.front;
-            pbase[pb] = (uint32_t)((((oy - T.oyA) * p.sh) * p.pitch + (cs & ~1)) * 2) + 32u + buf * xstride;
+            pbase[pb] = (uint32_t)(((oyl * p.sh) * p.pitch + (cs & ~1)) * 2) + 32u + buf * xstride;
             shift[pb] = (uint32_t)(cs & 1) * 16u;
         }
         floatx16 acc[CB][PXW];
@@ -810,11 +930,19 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
     }
     __syncthreads();
     __syncthreads();
-    for (int i = 1; i < K; ++i) {
-        store_tile_ws(i - 1);
-        __syncthreads();
+    if constexpr (POOL) {
+        for (int i = 1; i < K; ++i) {
+            pool_tile_ws(i - 1);
+            __syncthreads();
+        }
+        pool_tile_ws(K - 1);
+    } else {
+        for (int i = 1; i < K; ++i) {
+            store_tile_ws(i - 1);
+            __syncthreads();
+        }
+        store_tile_ws(K - 1);
     }
-    store_tile_ws(K - 1);
 }
 
 // ---------------------------------------------------------------------------
@@ -1174,8 +1302,13 @@ hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, void
     if (p.variant == CONV_PLANAR_SMALLC && p.ws) {
 #define MERIT_PLANAR_WS(CBv, SUv)                                                                          \
     do {                                                                                                   \
-        if (p.aligned) return launch(merit_conv2d_planar_ws<CBv, true, SUv>, p, x, w, y, s, gx, lds, 512); \
-        return launch(merit_conv2d_planar_ws<CBv, false, SUv>, p, x, w, y, s, gx, lds, 512);               \
+        if (p.pool) {                                                                                      \
+            const uint32_t gp = (uint32_t)((int64_t)p.N * p.NB);                                           \
+            if (p.aligned) return launch(merit_conv2d_planar_ws<CBv, true, SUv, true>, p, x, w, y, s, gp, lds, 512);  \
+            return launch(merit_conv2d_planar_ws<CBv, false, SUv, true>, p, x, w, y, s, gp, lds, 512);     \
+        }                                                                                                  \
+        if (p.aligned) return launch(merit_conv2d_planar_ws<CBv, true, SUv, false>, p, x, w, y, s, gx, lds, 512); \
+        return launch(merit_conv2d_planar_ws<CBv, false, SUv, false>, p, x, w, y, s, gx, lds, 512);        \
     } while (0)
         switch (p.CB * 100 + p.su) {
         case 204: MERIT_PLANAR_WS(2, 4);
@@ -1221,6 +1354,7 @@ hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, void
 
 const char *conv_kernel_name(const ConvParams &p)
 {
+    if (p.variant == CONV_PLANAR_SMALLC && p.ws && p.pool) return "merit_conv2d_planar_ws_pool";
     if (p.variant == CONV_PLANAR_SMALLC) return p.ws ? "merit_conv2d_planar_ws" : "merit_conv2d_planar";
     return "merit_conv2d_chblock";
 }

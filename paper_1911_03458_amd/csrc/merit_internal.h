@@ -103,6 +103,11 @@ struct ConvParams {
     int su;                // wave-specialised kernel: unrolled K steps (S <= su <= S+2)
     int lg_chunks;         // wave-specialised kernel: log2 of the 16-byte chunks per staged row, rounded up
     int wg_per_cu;         // resident workgroups per compute unit the launcher sizes the grid for
+    // convolution followed by 3x3 / stride 2 / padding 1 max pooling, fused (wave-specialised kernel only)
+    int pool;              // 1: the workgroup pools its results in LDS and writes the pooled tensor
+    int PH, PW;            // pooled output extent (OH/2, OW/2)
+    int PB, NB;            // pooled rows per workgroup (band), bands per image
+    int pw8;               // 8-pixel units per pooled row (PW/8)
     FastDiv div_ow;
     FastDiv div_kh;
     FastDiv div_pitch8;    // planar staging: 16-byte units per staged row
@@ -111,6 +116,8 @@ struct ConvParams {
     FastDiv div_w8;        // channel-blocked staging: 8-pixel chunks per row
     FastDiv div_nchi;      // channel-blocked staging: channel groups per output channel
     FastDiv div_tiles;
+    FastDiv div_nb;        // fused pooling: bands per image
+    FastDiv div_pw8;       // fused pooling: units per pooled row
 };
 
 // ---- launchers (defined in the .hip files) --------------------------------

@@ -293,7 +293,12 @@ merit_status derive_conv(merit_plan *pl)
 
     ConvParams &p = pl->conv;
     p.N = (int)N; p.Cin = (int)Cin; p.H = (int)H; p.W = (int)W; p.Cout = (int)Cout;
-    p.relu = d.op == MERIT_OP_CONV_DOT_RELU ? 1 : 0;
+    p.relu = (d.op == MERIT_OP_CONV_DOT_RELU || d.op == MERIT_OP_CONV_DOT_RELU_POOLMAX) ? 1 : 0;
+    const bool pool = d.op == MERIT_OP_CONV_DOT_POOLMAX || d.op == MERIT_OP_CONV_DOT_RELU_POOLMAX;
+    p.pool = pool ? 1 : 0;
+    p.PH = p.PW = p.PB = p.NB = p.pw8 = 0;
+    // fused pooling: a workgroup's 256-pixel tile is two whole output rows, pooled 8 columns at a time
+    if (pool && (OH % 2 != 0 || OW % 16 != 0 || 2 * OW > 256)) return MERIT_ERR_UNSUPPORTED;
     p.OH = (int)OH; p.OW = (int)OW; p.kh = (int)kh; p.kw = (int)kw; p.sh = (int)sh; p.sw = (int)sw;
     p.ph = (int)ph; p.pw = (int)pw; p.dh = (int)dh; p.dw = (int)dw;
 
@@ -313,6 +318,7 @@ merit_status derive_conv(merit_plan *pl)
         q.tiles_per_image = (int)cdiv(ohw, q.TM);
         q.rows_out_max = (int)((q.TM + OW - 2) / OW + 1);
         if (q.rows_out_max > OH) q.rows_out_max = (int)OH;
+        if (pool) q.rows_out_max = 2;
         q.RHa = (int)((q.rows_out_max - 1) * sh + eh);
         if (variant == CONV_PLANAR_SMALLC) {
             if (kw > 8 || pw > 8 || dilated) return false;       // its fragments are runs of adjacent taps
@@ -376,7 +382,8 @@ merit_status derive_conv(merit_plan *pl)
         while ((1 << lgc) < q.pitch / 8) ++lgc;
         if (variant == CONV_PLANAR_SMALLC && want_ws && pxw == 2 && nw == 4 && (W % 8) == 0 && lgc <= 7 &&
             (((int64_t)Cin * q.RHa) << lgc) <= 128 * 10 && (int64_t)q.G * kw >= 8 &&
-            (OH * OW) % 8 == 0 && N * Cin * H * W * 2 < (1ll << 31) && N * Cout * OH * OW * 2 < (1ll << 31)) {
+            (OH * OW) % 8 == 0 && N * Cin * H * W * 2 < (1ll << 31) &&
+            N * Cout * OH * OW * 2 / (pool ? 4 : 1) < (1ll << 31)) {
             static const int steps[] = {4, 6, 8, 11, 12};
             int su = 0;
             for (int k = 0; k < 5 && !su; ++k)
@@ -406,7 +413,28 @@ merit_status derive_conv(merit_plan *pl)
     // planar kernel, 8 x 32.  256-pixel tiles when that still leaves a large grid.
     const bool want_big = N * cdiv(ohw, 256) * p.co_groups >= 512;
     bool ok = false;
-    if (pl->tile_req[2] > 0 && pl->tile_req[3] > 0) {
+    if (pool) {
+        // only the wave-specialised kernel pools; a tile request must name it (8 x 64) or nothing
+        if (pl->tile_req[2] > 0 && pl->tile_req[3] > 0 && (pl->tile_req[2] != 8 || pl->tile_req[3] != 64))
+            return MERIT_ERR_UNSUPPORTED;
+        want_ws = true;
+        ok = Cin < 8 && try_variant(CONV_PLANAR_SMALLC, 2, 4) && p.ws;
+        if (!ok) return MERIT_ERR_UNSUPPORTED;
+        p.PH = (int)(OH / 2); p.PW = (int)(OW / 2); p.pw8 = p.PW / 8;
+        // bands of pooled rows: about one workgroup per compute unit, but at least 4 rows per
+        // band (every band recomputes one convolution row pair above its first pooled row)
+        int64_t nb = 256 / (N * p.co_groups > 0 ? N * p.co_groups : 1);
+        const int64_t nb_max = p.PH >= 4 ? p.PH / 4 : 1;
+        if (nb > nb_max) nb = nb_max;
+        if (nb < 1) nb = 1;
+        p.PB = (int)cdiv(p.PH, nb);
+        p.NB = (int)cdiv(p.PH, p.PB);
+        if (!fastdiv_ok((int64_t)N * p.NB, p.NB) || !fastdiv_ok((int64_t)128 * 2 * p.CB, p.pw8))
+            return MERIT_ERR_UNSUPPORTED;
+        p.div_nb = make_fastdiv((uint32_t)p.NB);
+        p.div_pw8 = make_fastdiv((uint32_t)p.pw8);
+        if ((int64_t)N * p.NB >= (1ll << 31)) return MERIT_ERR_UNSUPPORTED;
+    } else if (pl->tile_req[2] > 0 && pl->tile_req[3] > 0) {
         const int64_t nw = pl->tile_req[2], ppw = pl->tile_req[3];
         if ((nw != 4 && nw != 8) || (ppw != 32 && ppw != 64)) return MERIT_ERR_UNSUPPORTED;
         if (nw == 8 && ppw == 64) {
@@ -429,6 +457,7 @@ merit_status derive_conv(merit_plan *pl)
 
     pl->out_ndim = 4;
     pl->out_shape[0] = N; pl->out_shape[1] = Cout; pl->out_shape[2] = OH; pl->out_shape[3] = OW;
+    if (pool) { pl->out_shape[2] = p.PH; pl->out_shape[3] = p.PW; }
     merit_launch_info &li = pl->info;
     li.kernel = conv_kernel_name(p);
     // persistent grid; the launcher sizes it from the device's CU count (256 on MI355X)
@@ -437,12 +466,14 @@ merit_status derive_conv(merit_plan *pl)
         if (slots < 1) slots = 1;
         const int64_t nt = (int64_t)N * p.tiles_per_image;
         li.grid[0] = nt < slots ? nt : slots;
+        if (pool) li.grid[0] = (int64_t)N * p.NB;          // one workgroup per band, not persistent
     }
     li.grid[1] = p.co_groups; li.grid[2] = 1;
     li.block[0] = p.ws ? 512 : p.NW * 64; li.block[1] = 1; li.block[2] = 1;
     li.lds_bytes = (int64_t)conv_lds_bytes(p);
     li.tile[0] = 1; li.tile[1] = p.CB * 32; li.tile[2] = p.rows_out_max; li.tile[3] = OW;
     li.tile[4] = Cin; li.tile[5] = kh; li.tile[6] = kw;
+    if (pool) li.tile[2] = 2 * (p.PB + 1);                 // convolution rows a band computes
     return MERIT_OK;
 }
 
@@ -591,7 +622,7 @@ merit_status merit_plan_create(const merit_plan_desc *desc, merit_plan **out)
 {
     if (!desc || !out) return MERIT_ERR_NULL;
     *out = nullptr;
-    if ((int)desc->op < 0 || (int)desc->op > 6 || (int)desc->dtype < 0 || (int)desc->dtype > 2 ||
+    if ((int)desc->op < 0 || (int)desc->op > 8 || (int)desc->dtype < 0 || (int)desc->dtype > 2 ||
         (int)desc->pad < 0 || (int)desc->pad > 3)
         return MERIT_ERR_INVALID_ARG;
     if (desc->n_par < 1 || desc->n_acc < 1 || desc->n_par + desc->n_acc > MERIT_MAX_INDEX)
@@ -612,7 +643,9 @@ merit_status merit_plan_create(const merit_plan_desc *desc, merit_plan **out)
     merit_status st;
     switch (desc->op) {
     case MERIT_OP_CONV_DOT:
-    case MERIT_OP_CONV_DOT_RELU: st = derive_conv(pl); break;
+    case MERIT_OP_CONV_DOT_RELU:
+    case MERIT_OP_CONV_DOT_POOLMAX:
+    case MERIT_OP_CONV_DOT_RELU_POOLMAX: st = derive_conv(pl); break;
     case MERIT_OP_POOL_MAX:
     case MERIT_OP_POOL_AVG: st = derive_pool(pl); break;
     case MERIT_OP_CORR_DOT: st = derive_corr(pl); break;
@@ -688,6 +721,13 @@ merit_status merit_plan_conv2d_dilated(int N, int Cin, int H, int W, int Cout, i
                           pw, dh, dw, out);
 }
 
+merit_status merit_plan_conv2d_pool(int N, int Cin, int H, int W, int Cout, int kh, int kw, int sh, int sw,
+                                    int ph, int pw, int relu, merit_plan **out)
+{
+    return plan_conv2d_op(relu ? MERIT_OP_CONV_DOT_RELU_POOLMAX : MERIT_OP_CONV_DOT_POOLMAX, N, Cin, H, W, Cout,
+                          kh, kw, sh, sw, ph, pw, 1, 1, out);
+}
+
 merit_status merit_plan_pool2d(int N, int C, int H, int W, int kh, int kw, int sh, int sw, int ph, int pw,
                                int is_avg, merit_plan **out)
 {
@@ -751,7 +791,9 @@ merit_status merit_plan_set_tile(merit_plan *plan, const int64_t tile[MERIT_MAX_
     merit_status st;
     switch (trial.desc.op) {
     case MERIT_OP_CONV_DOT:
-    case MERIT_OP_CONV_DOT_RELU: st = derive_conv(&trial); break;
+    case MERIT_OP_CONV_DOT_RELU:
+    case MERIT_OP_CONV_DOT_POOLMAX:
+    case MERIT_OP_CONV_DOT_RELU_POOLMAX: st = derive_conv(&trial); break;
     case MERIT_OP_POOL_MAX:
     case MERIT_OP_POOL_AVG: st = derive_pool(&trial); break;
     case MERIT_OP_CORR_DOT: st = derive_corr(&trial); break;
@@ -810,7 +852,9 @@ merit_status merit_plan_launch_info(const merit_plan *plan, merit_launch_info *o
 merit_status merit_conv2d(const merit_plan *plan, const void *x, const void *w, void *y, void *stream)
 {
     if (!plan) return MERIT_ERR_NULL;
-    if (plan->desc.op != MERIT_OP_CONV_DOT && plan->desc.op != MERIT_OP_CONV_DOT_RELU) return MERIT_ERR_INVALID_ARG;
+    if (plan->desc.op != MERIT_OP_CONV_DOT && plan->desc.op != MERIT_OP_CONV_DOT_RELU &&
+        plan->desc.op != MERIT_OP_CONV_DOT_POOLMAX && plan->desc.op != MERIT_OP_CONV_DOT_RELU_POOLMAX)
+        return MERIT_ERR_INVALID_ARG;
     if (plan->conv.N == 0) return MERIT_OK;               // empty batch: nothing to read or write
     if (!x || !w || !y) return MERIT_ERR_NULL;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return MERIT_ERR_ALIGNMENT;

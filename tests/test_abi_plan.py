@@ -87,6 +87,37 @@ def test_dilated_plan_is_the_papers_expression():
         "merit_conv2d_chblock"
 
 
+def test_fused_pooling_plan():
+    """Convolution + clipping + 3x3/s2/p1 max pooling as one launch: the descriptor is the
+    convolution's, the output shape the pooled tensor's."""
+    plan = mb.merit_plan_conv2d_pool(32, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3, 1)
+    conv = mb.merit_plan_conv2d_relu(32, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3)
+    d = plan.desc()
+    assert d.op == mb.MERIT_OP_CONV_DOT_RELU_POOLMAX and tuple(d.range) == tuple(conv.desc().range)
+    assert conv.out_shape() == (32, 64, 112, 112) and plan.out_shape() == (32, 64, 56, 56)
+    li = plan.launch_info()
+    assert li["kernel"] == "merit_conv2d_planar_ws_pool" and li["block"][0] == 512
+    # 32 images x 8 bands of 7 pooled rows; a band computes 8 convolution row pairs
+    assert li["grid"][:2] == (256, 1) and li["tile"][2] == 16
+    assert li["lds_bytes"] <= 160 * 1024
+    assert mb.merit_plan_conv2d_pool(32, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3, 0).desc().op == \
+        mb.MERIT_OP_CONV_DOT_POOLMAX
+    assert mb.merit_plan_create(d).out_shape() == (32, 64, 56, 56)
+    plan.set_tile((0, 0, 8, 64))                           # the kernel it already uses
+    with pytest.raises(mb.MeritError):
+        plan.set_tile((0, 0, 4, 32))
+    # few bands for a single image: at least 4 pooled rows each
+    one = mb.merit_plan_conv2d_pool(1, 3, 44, 32, 64, 3, 3, 1, 1, 1, 1, 1).launch_info()
+    assert one["grid"][0] == 5 and one["tile"][2] == 12
+    for bad in ((2, 3, 62, 62, 8, 7, 7, 2, 2, 3, 3),        # 31 x 31 result: odd height
+                (2, 3, 64, 48, 8, 7, 7, 2, 2, 3, 3),        # 24 columns: not a multiple of 16
+                (2, 3, 32, 256, 8, 3, 3, 1, 1, 1, 1),       # a row pair does not fit a tile
+                (2, 16, 32, 32, 8, 3, 3, 1, 1, 1, 1)):      # many input channels: other kernel family
+        with pytest.raises(mb.MeritError) as e:
+            mb.merit_plan_conv2d_pool(*bad, 1)
+        assert e.value.status == mb.MERIT_ERR_UNSUPPORTED
+
+
 def test_depthwise_plan():
     plan = mb.merit_plan_conv2d_depthwise(32, 32, 64, 64, 3, 3, 1, 1, 1, 1)
     d = plan.desc()

@@ -492,6 +492,75 @@ def test_conv_7x7_workload_relu_sampled(mb):
     assert torch.equal(y, torch.clamp_min(plain, 0.0) + 0.0)      # same products, clipped; "+ 0.0" folds -0
 
 
+POOLFUSE_CASES = [
+    # N Cin H   W  Cout kh kw sh sw ph pw relu
+    (2, 3, 64, 64, 64, 7, 7, 2, 2, 3, 3, 1),    # 4 bands of 4 pooled rows per image
+    (3, 3, 40, 64, 40, 3, 3, 1, 1, 1, 1, 0),    # ragged channels, no clipping, odd window alignment
+    (1, 3, 44, 32, 64, 3, 3, 1, 1, 1, 1, 1),    # last band shorter than the others
+    (2, 1, 16, 128, 32, 5, 5, 1, 1, 2, 2, 0),   # widest row pair (2 x 128 = the whole tile), one channel block
+    (300, 3, 32, 32, 64, 7, 7, 2, 2, 3, 3, 1),  # more images than compute units: one band per image
+    (1, 2, 8, 16, 8, 3, 3, 1, 1, 1, 1, 1),      # smallest: one unit per pooled row
+]
+
+
+def _window_max_abs(a):
+    """max |a| over the 3x3 / stride 2 / padding 1 window of every pooled position."""
+    return oracle.pool2d(np.abs(a).astype(np.float32), (3, 3), (2, 2), (1, 1), "max").astype(np.float64)
+
+
+@pytest.mark.parametrize("case", POOLFUSE_CASES)
+def test_conv_pool_fused(mb, case):
+    N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, relu = case
+    rng = np.random.default_rng(abs(hash(case)) % 2 ** 31)
+    x = rng.standard_normal((N, Cin, H, W)).astype(np.float16)
+    w = (rng.standard_normal((Cout, Cin, kh, kw)) / np.sqrt(Cin * kh * kw)).astype(np.float16)
+    plan = mb.merit_plan_conv2d_pool(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, relu)
+    info = plan.launch_info()
+    print("conv+pool", case, info, flush=True)
+    assert info["kernel"] == "merit_conv2d_planar_ws_pool"
+    buf, y, p = guarded_empty(plan.out_shape(), torch.float16, 777.0)
+    mb.merit_conv2d(plan, dev(x), dev(w), y)
+    torch.cuda.synchronize()
+    check_canary(buf, p, 777.0)
+    got = y.cpu().numpy().astype(np.float64)
+    # (1) against the oracle: max is 1-Lipschitz, so the convolution's tolerance carries over with
+    # the largest magnitude in the window in place of the element's own
+    conv_ref = oracle.conv2d(x, w, (sh, sw), (ph, pw), relu=bool(relu))
+    ref = oracle.conv2d_pool(x, w, (sh, sw), (ph, pw), relu=bool(relu)).astype(np.float64)
+    assert got.shape == ref.shape
+    tol = 2e-2 * _window_max_abs(conv_ref) + 1e-3
+    err = np.abs(got - ref)
+    assert np.all(err <= tol), f"max excess {np.max(err - tol)} at {np.unravel_index(np.argmax(err - tol), err.shape)}"
+    # (2) exactly the pooled maximum of what the unfused kernel rounds to
+    make = mb.merit_plan_conv2d_relu if relu else mb.merit_plan_conv2d
+    plain = mb.merit_conv2d(make(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw), dev(x), dev(w)).cpu().numpy()
+    exact = oracle.pool2d(plain.astype(np.float32), (3, 3), (2, 2), (1, 1), "max").astype(np.float64)
+    assert np.array_equal(got, exact)
+
+
+def test_conv_pool_fused_7x7_workload(mb):
+    """Full-size launch of the 7x7 stride-2 layer with clipping and pooling fused; the oracle
+    checks two images, the library's own unfused result (pooled on the device) all of them."""
+    c = wl.CFG4_CONV7
+    x, w = wl.make_conv_inputs(c)
+    plan = mb.merit_plan_conv2d_pool(c.N, c.Cin, c.H, c.W, c.Cout, c.kh, c.kw, c.sh, c.sw, c.ph, c.pw, 1)
+    info = plan.launch_info()
+    assert info["kernel"] == "merit_conv2d_planar_ws_pool" and info["grid"][0] == 256
+    assert plan.out_shape() == (32, 64, 56, 56)
+    y = mb.merit_conv2d(plan, dev(x), dev(w))
+    torch.cuda.synchronize()
+    for n in (0, 21):
+        got = y[n].cpu().numpy().astype(np.float64)
+        conv_ref = oracle.conv2d(x[n:n + 1], w, (c.sh, c.sw), (c.ph, c.pw), relu=True)
+        ref = oracle.conv2d_pool(x[n:n + 1], w, (c.sh, c.sw), (c.ph, c.pw), relu=True)[0].astype(np.float64)
+        tol = 2e-2 * _window_max_abs(conv_ref)[0] + 1e-3
+        assert np.all(np.abs(got - ref) <= tol)
+    plain = mb.merit_conv2d(mb.merit_plan_conv2d_relu(c.N, c.Cin, c.H, c.W, c.Cout, c.kh, c.kw, c.sh, c.sw, c.ph,
+                                                      c.pw), dev(x), dev(w))
+    pooled = torch.nn.functional.max_pool2d(plain.float(), 3, 2, 1).half()
+    assert torch.equal(y, pooled)
+
+
 DILATED_CASES = [
     # N Cin H   W  Cout kh kw sh sw ph pw dh dw relu
     (1, 32, 64, 64, 32, 3, 3, 1, 1, 2, 2, 2, 2, 0),   # the dilated layer of the paper's table: 64x64x32 out
