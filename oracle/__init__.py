@@ -57,6 +57,8 @@ def _load():
     lib.ref_correlation.argtypes = [vp, vp, vp] + [c_int] * 6
     lib.ref_conv2d_dilated.restype = c_int
     lib.ref_conv2d_dilated.argtypes = [vp, vp, vp] + [c_int] * 14
+    lib.ref_conv2d_residual.restype = c_int
+    lib.ref_conv2d_residual.argtypes = [vp, vp, vp, vp] + [c_int] * 12
     lib.ref_pool2d.restype = c_int
     lib.ref_pool2d.argtypes = [vp, vp] + [c_int] * 11
     lib.ref_sad_search.restype = c_int
@@ -126,6 +128,28 @@ def conv2d(x: np.ndarray, w: np.ndarray, stride=(1, 1), pad=(0, 0), relu=False, 
                                         dh, dw, 1 if relu else 0)
     if rc != 0:
         raise ValueError("ref_conv2d: bad shape")
+    return y
+
+
+def conv2d_residual(x: np.ndarray, w: np.ndarray, r: np.ndarray, stride=(1, 1), pad=(0, 0), relu=False) -> np.ndarray:
+    """Residual layer (Section III-B, remark after Listing 1): r fp16 [N,Cout,OH,OW] is added to
+    the exact sum in PostLoop, before the optional clip and the one rounding to fp16."""
+    x = _c(x, np.float16)
+    w = _c(w, np.float16)
+    r = _c(r, np.float16)
+    N, Cin, H, W = x.shape
+    Cout, Cin2, kh, kw = w.shape
+    if Cin2 != Cin:
+        raise ValueError("channel mismatch")
+    sh, sw = stride
+    ph, pw = pad
+    shape = (N, Cout, out_extent(H, kh, sh, ph), out_extent(W, kw, sw, pw))
+    if r.shape != shape:
+        raise ValueError("residual tensor must have the output's shape")
+    y = np.empty(shape, np.float16)
+    if _load().ref_conv2d_residual(_ptr(x), _ptr(w), _ptr(r), _ptr(y), N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw,
+                                   1 if relu else 0) != 0:
+        raise ValueError("ref_conv2d_residual: bad shape")
     return y
 
 

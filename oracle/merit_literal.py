@@ -130,13 +130,16 @@ def sad_desc(H, W, B, R):
 # --------------------------------------------------------------------------
 # row-wise reductions R(M(A), M(B), (.))
 # --------------------------------------------------------------------------
-def conv2d(x: np.ndarray, w: np.ndarray, stride=(1, 1), pad=(0, 0), relu=False, dilation=(1, 1)) -> np.ndarray:
+def conv2d(x: np.ndarray, w: np.ndarray, stride=(1, 1), pad=(0, 0), relu=False, dilation=(1, 1),
+           residual=None) -> np.ndarray:
     N, Cin, H, W = x.shape
     Cout, _, kh, kw = w.shape
     ranges, n_par, tx, tw = conv2d_desc(N, Cin, H, W, Cout, kh, kw, *stride, *pad, *dilation)
     MA, _ = transform(x.astype(np.float64), ranges, tx, n_par, "zero")
     MB, _ = transform(w.astype(np.float64), ranges, tw, n_par, "zero")
     rows = np.einsum("pa,pa->p", MA, MB)                    # v1^T v2 per row
+    if residual is not None:                                # a loaded tensor added in PostLoop: row p gets r[p]
+        rows = rows + residual.astype(np.float64).reshape(-1)
     if relu:
         rows = np.maximum(rows, 0.0)                        # max(v1^T v2, 0), Section III-B
     return rows.reshape(ranges[:4]).astype(np.float16)

@@ -91,7 +91,7 @@ uint16_t ref_double_to_half(double d)
  * x: [N,Cin,H,W] binary16, w: [Cout,Cin,kh,kw] binary16, y: [N,Cout,OH,OW].
  * Returns 0, or -1 on a bad shape.
  */
-static int conv2d_postloop(const uint16_t *x, const uint16_t *w, uint16_t *y,
+static int conv2d_postloop(const uint16_t *x, const uint16_t *w, const uint16_t *res, uint16_t *y,
                            int N, int Cin, int H, int W, int Cout,
                            int kh, int kw, int sh, int sw, int ph, int pw, int dh, int dw, int relu)
 {
@@ -120,8 +120,10 @@ static int conv2d_postloop(const uint16_t *x, const uint16_t *w, uint16_t *y,
                                 w[(((size_t)co * Cin + ci) * kh + ky) * kw + kx]);
                             acc += xv * wv;
                         }
+                const size_t o = (((size_t)n * Cout + co) * OH + oy) * OW + ox;
+                if (res) acc += ref_half_to_double(res[o]);  /* PostLoop: a loaded tensor added to act */
                 if (relu && !(acc > 0.0)) acc = 0.0;       /* PostLoop: max(act, 0) */
-                y[(((size_t)n * Cout + co) * OH + oy) * OW + ox] = ref_double_to_half(acc);
+                y[o] = ref_double_to_half(acc);
             }
     }
     return 0;
@@ -131,7 +133,7 @@ int ref_conv2d(const uint16_t *x, const uint16_t *w, uint16_t *y,
                int N, int Cin, int H, int W, int Cout,
                int kh, int kw, int sh, int sw, int ph, int pw)
 {
-    return conv2d_postloop(x, w, y, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, 1, 1, 0);
+    return conv2d_postloop(x, w, NULL, y, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, 1, 1, 0);
 }
 
 /*
@@ -143,7 +145,7 @@ int ref_conv2d_relu(const uint16_t *x, const uint16_t *w, uint16_t *y,
                     int N, int Cin, int H, int W, int Cout,
                     int kh, int kw, int sh, int sw, int ph, int pw)
 {
-    return conv2d_postloop(x, w, y, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, 1, 1, 1);
+    return conv2d_postloop(x, w, NULL, y, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, 1, 1, 1);
 }
 
 /*
@@ -157,7 +159,23 @@ int ref_conv2d_dilated(const uint16_t *x, const uint16_t *w, uint16_t *y,
                        int N, int Cin, int H, int W, int Cout,
                        int kh, int kw, int sh, int sw, int ph, int pw, int dh, int dw, int relu)
 {
-    return conv2d_postloop(x, w, y, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw, relu);
+    return conv2d_postloop(x, w, NULL, y, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw, relu);
+}
+
+/*
+ * Residual layer (Section III-B, the remark after Listing 1: a second tensor loaded and
+ * added to the accumulator in PostLoop): r has the output's shape [N,Cout,OH,OW],
+ *   y = fp16( sum + r )            relu == 0
+ *   y = fp16( max(sum + r, 0) )    relu != 0   (the addition precedes the clip, as it
+ *                                               precedes the max in Listing 1's PostLoop)
+ * The addition is made in double on the exact sum: one rounding in all.
+ */
+int ref_conv2d_residual(const uint16_t *x, const uint16_t *w, const uint16_t *r, uint16_t *y,
+                        int N, int Cin, int H, int W, int Cout,
+                        int kh, int kw, int sh, int sw, int ph, int pw, int relu)
+{
+    if (!r) return -1;
+    return conv2d_postloop(x, w, r, y, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, 1, 1, relu);
 }
 
 /*

@@ -216,6 +216,70 @@ def test_relu_matches_literal_evaluator_and_torch(stride, pad):
     assert (plain < 0).any() and (plain > 0).any()
 
 
+# ------------------------------------------- residual layer (Section III-B, remark after Listing 1)
+def test_residual_special_cases_reduce_to_known_results():
+    rng = np.random.default_rng(41)
+    x = _rand_half(rng, (2, 3, 8, 9))
+    w = _rand_half(rng, (5, 3, 3, 3), 0.3)
+    plain = oracle.conv2d(x, w, (1, 1), (1, 1))
+    zero = np.zeros(plain.shape, np.float16)
+    # r = 0: the convolution itself, bit for bit, with and without the clip
+    assert np.array_equal(oracle.conv2d_residual(x, w, zero, (1, 1), (1, 1)).view(np.uint16), plain.view(np.uint16))
+    assert np.array_equal(oracle.conv2d_residual(x, w, zero, (1, 1), (1, 1), relu=True),
+                          oracle.conv2d(x, w, (1, 1), (1, 1), relu=True))
+    # w = 0: the added tensor itself (clipped when asked)
+    r = _rand_half(rng, plain.shape)
+    assert np.array_equal(oracle.conv2d_residual(x, np.zeros_like(w), r, (1, 1), (1, 1)), r)
+    assert np.array_equal(oracle.conv2d_residual(x, np.zeros_like(w), r, (1, 1), (1, 1), relu=True),
+                          np.maximum(r, np.float16(0)))
+    # identity kernel: fp16(x + r), one rounding of the exact sum; a subtraction or a dropped term fails
+    C = 3
+    wi = np.zeros((C, C, 3, 3), np.float16)
+    for c in range(C):
+        wi[c, c, 1, 1] = 1.0
+    r = _rand_half(rng, x.shape)
+    want = (x.astype(np.float64) + r.astype(np.float64)).astype(np.float16)
+    assert np.array_equal(oracle.conv2d_residual(x, wi, r, (1, 1), (1, 1)).view(np.uint16), want.view(np.uint16))
+
+
+def test_residual_is_added_before_the_clip_and_the_single_rounding():
+    # sum = 2049 (a binary16 tie: alone it rounds to 2048), r = 1: the exact 2050 is representable.
+    # Rounding the sum first and adding then gives 2048.
+    x = np.array([2048.0, 1.0], np.float16).reshape(1, 2, 1, 1)
+    w = np.ones((1, 2, 1, 1), np.float16)
+    r = np.ones((1, 1, 1, 1), np.float16)
+    assert float(oracle.conv2d(x, w)[0, 0, 0, 0]) == 2048.0
+    assert float(oracle.conv2d_residual(x, w, r)[0, 0, 0, 0]) == 2050.0
+    # sum = -3, r = +2: clip after the addition gives 0; clipping the sum first would give 2
+    x = np.array([-3.0], np.float16).reshape(1, 1, 1, 1)
+    w = np.ones((1, 1, 1, 1), np.float16)
+    r = np.full((1, 1, 1, 1), 2.0, np.float16)
+    assert float(oracle.conv2d_residual(x, w, r, relu=True)[0, 0, 0, 0]) == 0.0
+    assert float(oracle.conv2d_residual(x, w, r)[0, 0, 0, 0]) == -1.0
+    # sum = +3, r = -5 -> -2 -> clipped; sum = 3, r = -1 -> 2
+    assert float(oracle.conv2d_residual(-x, w, np.full((1, 1, 1, 1), -5.0, np.float16), relu=True)[0, 0, 0, 0]) == 0.0
+    assert float(oracle.conv2d_residual(-x, w, np.full((1, 1, 1, 1), -1.0, np.float16), relu=True)[0, 0, 0, 0]) == 2.0
+
+
+@pytest.mark.parametrize("stride,pad,relu", [((1, 1), (1, 1), True), ((2, 2), (3, 3), False), ((2, 1), (0, 2), True)])
+def test_residual_matches_literal_evaluator_and_torch(stride, pad, relu):
+    rng = np.random.default_rng(43)
+    k = 7 if pad == (3, 3) else 3
+    x = _rand_half(rng, (2, 3, 9, 10))
+    w = _rand_half(rng, (4, 3, k, k), 0.3)
+    shape = oracle.conv2d(x, w, stride, pad).shape
+    r = _rand_half(rng, shape)
+    got = oracle.conv2d_residual(x, w, r, stride, pad, relu=relu)
+    want = lit.conv2d(x, w, stride, pad, relu=relu, residual=r)
+    assert np.array_equal(got.view(np.uint16), want.view(np.uint16))
+    ref = torch.nn.functional.conv2d(torch.from_numpy(x.astype(np.float64)), torch.from_numpy(w.astype(np.float64)),
+                                     stride=stride, padding=pad) + torch.from_numpy(r.astype(np.float64))
+    ref = (torch.relu(ref) if relu else ref).numpy()
+    assert np.allclose(got.astype(np.float64), ref, rtol=2e-3, atol=1e-3)
+    with pytest.raises(ValueError):
+        oracle.conv2d_residual(x, w, r[:, :1], stride, pad)
+
+
 # ------------------------------------------- dilated window (Section III-C, after Eq. 6)
 def _stuff(w, dh, dw):
     """The dilated kernel written out: zeros between the taps."""
