@@ -121,7 +121,7 @@ def bench_sad(torch, mb, wl, cfg, steps, warmup):
     }
 
 
-def bench_conv(torch, mb, wl, cfg, steps, warmup, nsets, relu=False, pool=False):
+def bench_conv(torch, mb, wl, cfg, steps, warmup, nsets, relu=False, pool=False, residual=False):
     x, w = wl.make_conv_inputs(cfg)
     x0 = torch.from_numpy(x).to("cuda:0")
     dw = torch.from_numpy(w).to("cuda:0")
@@ -129,11 +129,21 @@ def bench_conv(torch, mb, wl, cfg, steps, warmup, nsets, relu=False, pool=False)
     # fused 3x3/s2/p1 max pooling: only the pooled tensor is written
     oh, ow = (cfg.OH // 2, cfg.OW // 2) if pool else (cfg.OH, cfg.OW)
     out_bytes = cfg.N * cfg.Cout * oh * ow * 2
+    if residual:                                   # the added tensor is read once
+        in_bytes += out_bytes
     # rotate only when a set would otherwise stay resident in the Infinity Cache
     ns = nsets if (in_bytes + out_bytes) > (8 << 20) else 1
     xs = [x0] + [x0.roll(i, dims=0).contiguous() for i in range(1, ns)]
     ys = [torch.empty((cfg.N, cfg.Cout, oh, ow), dtype=torch.float16, device="cuda:0") for _ in range(ns)]
-    if pool:
+    rs = None
+    if residual:
+        import numpy as np
+        plan = mb.merit_plan_conv2d_residual(cfg.N, cfg.Cin, cfg.H, cfg.W, cfg.Cout, cfg.kh, cfg.kw, cfg.sh, cfg.sw,
+                                             cfg.ph, cfg.pw, int(relu))
+        r0 = torch.from_numpy(np.random.default_rng(wl.BASE_SEED + 77).standard_normal(
+            (cfg.N, cfg.Cout, oh, ow)).astype(np.float16)).to("cuda:0")
+        rs = [r0] + [r0.roll(i, dims=0).contiguous() for i in range(1, ns)]
+    elif pool:
         plan = mb.merit_plan_conv2d_pool(cfg.N, cfg.Cin, cfg.H, cfg.W, cfg.Cout, cfg.kh, cfg.kw, cfg.sh, cfg.sw,
                                          cfg.ph, cfg.pw, int(relu))
     elif (cfg.dh, cfg.dw) != (1, 1):
@@ -142,12 +152,16 @@ def bench_conv(torch, mb, wl, cfg, steps, warmup, nsets, relu=False, pool=False)
     else:
         make = mb.merit_plan_conv2d_relu if relu else mb.merit_plan_conv2d
         plan = make(cfg.N, cfg.Cin, cfg.H, cfg.W, cfg.Cout, cfg.kh, cfg.kw, cfg.sh, cfg.sw, cfg.ph, cfg.pw)
-    calls = [mb.bind_conv2d(plan, xs[i], dw, ys[i]) for i in range(ns)]
+    if residual:
+        calls = [mb.bind_conv2d_residual(plan, xs[i], dw, rs[i], ys[i]) for i in range(ns)]
+    else:
+        calls = [mb.bind_conv2d(plan, xs[i], dw, ys[i]) for i in range(ns)]
     wall, ev_ms = timed_region(torch, lambda i: calls[i % ns](), steps, warmup)
     t = ev_ms * 1e-3 / steps
     flops = 2.0 * cfg.N * cfg.Cout * cfg.OH * cfg.OW * cfg.Cin * cfg.kh * cfg.kw
     return {
-        "workload": cfg.name + (" + fused ReLU" if relu else "") + (" + fused 3x3/s2/p1 max pooling" if pool else ""),
+        "workload": cfg.name + (" + residual tensor" if residual else "") + (" + fused ReLU" if relu else "")
+        + (" + fused 3x3/s2/p1 max pooling" if pool else ""),
         "kernel": plan.launch_info()["kernel"],
         "avg_launch_us": t * 1e6,
         "out_elems_per_s": cfg.N * cfg.Cout * oh * ow / t,
@@ -295,6 +309,7 @@ def main():
             bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets),
             bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets, relu=True),
             bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets, relu=True, pool=True),
+            bench_conv(torch, mb, wl, wl.CFG2_CONV3, k, w, args.sets, relu=True, residual=True),
             bench_conv(torch, mb, wl, wl.CFG_DILATED, k, w, args.sets),
             bench_corr(torch, mb, wl, wl.CFG_CORRELATION, k, w),
             bench_depthwise(torch, mb, wl, wl.CFG_DEPTHWISE, k, w, args.sets),

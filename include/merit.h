@@ -63,7 +63,13 @@ typedef enum {
      * padding 1 max pooling before it leaves the chip: the fused "CONV+Pool" layers of the
      * per-layer network table in Section VI-C.  The descriptor is the convolution's. */
     MERIT_OP_CONV_DOT_POOLMAX = 7,
-    MERIT_OP_CONV_DOT_RELU_POOLMAX = 8
+    MERIT_OP_CONV_DOT_RELU_POOLMAX = 8,
+    /* residual layer: a tensor of the output's shape is loaded and added to the accumulated sum
+     * in PostLoop (Section III-B, the remark after Listing 1), then the optional clip, then the
+     * one rounding.  The descriptor is the convolution's; the third tensor is an argument of
+     * merit_conv2d_residual. */
+    MERIT_OP_CONV_DOT_ADD = 9,
+    MERIT_OP_CONV_DOT_ADD_RELU = 10
 } merit_op;
 
 typedef enum { MERIT_U8 = 0, MERIT_F16 = 1, MERIT_F32 = 2 } merit_dtype;
@@ -162,6 +168,11 @@ merit_status merit_plan_conv2d_dilated(int N, int Cin, int H, int W, int Cout, i
  * MERIT_ERR_UNSUPPORTED (run merit_conv2d and merit_pool2d one after the other). */
 merit_status merit_plan_conv2d_pool(int N, int Cin, int H, int W, int Cout, int kh, int kw,
                                     int sh, int sw, int ph, int pw, int relu, merit_plan **out);
+/* Residual layer (Section III-B, remark after Listing 1): y = x (*) w + r, or
+ * max(x (*) w + r, 0) when relu != 0; r has the output's shape.  Run with
+ * merit_conv2d_residual. */
+merit_status merit_plan_conv2d_residual(int N, int Cin, int H, int W, int Cout, int kh, int kw,
+                                        int sh, int sw, int ph, int pw, int relu, merit_plan **out);
 merit_status merit_plan_pool2d(int N, int C, int H, int W, int kh, int kw,
                                int sh, int sw, int ph, int pw, int is_avg, merit_plan **out);
 merit_status merit_plan_sad(int H, int W, int block, int range, merit_plan **out);
@@ -207,6 +218,14 @@ merit_status merit_plan_set_tile(merit_plan *plan, const int64_t tile[MERIT_MAX_
  * convolution results in each window. */
 merit_status merit_conv2d(const merit_plan *plan, const void *x_f16, const void *w_f16,
                           void *y_f16, void *hip_stream);
+
+/* Residual layer: as merit_conv2d, with r_f16 [N,Cout,OH,OW] binary16 added to the fp32 sums
+ * before the clip (if the plan has one) and the one rounding to binary16.  r_f16 may be
+ * y_f16 itself (every element is read before it is overwritten, by the workgroup that owns
+ * it); any other overlap of y with x, w or r is undefined.  The plan must come from
+ * merit_plan_conv2d_residual (or a CONV_DOT_ADD / CONV_DOT_ADD_RELU descriptor). */
+merit_status merit_conv2d_residual(const merit_plan *plan, const void *x_f16, const void *w_f16,
+                                   const void *r_f16, void *y_f16, void *hip_stream);
 
 /* x_f32: [N,C,H,W]; y_f32: [N,C,OH,OW].  max: exact.  avg: fp32 sum in window
  * scan order divided by the in-range count. */

@@ -20,7 +20,8 @@ MERIT_OK = 0
 (MERIT_ERR_NULL, MERIT_ERR_INVALID_ARG, MERIT_ERR_SHAPE, MERIT_ERR_UNSUPPORTED,
  MERIT_ERR_ALIGNMENT, MERIT_ERR_HIP) = range(1, 7)
 (MERIT_OP_CONV_DOT, MERIT_OP_POOL_MAX, MERIT_OP_POOL_AVG, MERIT_OP_SAD_ARGMIN, MERIT_OP_CONV_DOT_RELU,
- MERIT_OP_CORR_DOT, MERIT_OP_DWCONV_DOT, MERIT_OP_CONV_DOT_POOLMAX, MERIT_OP_CONV_DOT_RELU_POOLMAX) = range(9)
+ MERIT_OP_CORR_DOT, MERIT_OP_DWCONV_DOT, MERIT_OP_CONV_DOT_POOLMAX, MERIT_OP_CONV_DOT_RELU_POOLMAX,
+ MERIT_OP_CONV_DOT_ADD, MERIT_OP_CONV_DOT_ADD_RELU) = range(11)
 MERIT_U8, MERIT_F16, MERIT_F32 = range(3)
 MERIT_PAD_ZERO, MERIT_PAD_NEG_INF, MERIT_PAD_EXCLUDE, MERIT_PAD_CLAMP = range(4)
 
@@ -80,6 +81,8 @@ def lib():
     L.merit_plan_conv2d_relu.argtypes = [c_int] * 11 + [PP]
     L.merit_plan_conv2d_dilated.argtypes = [c_int] * 14 + [PP]
     L.merit_plan_conv2d_pool.argtypes = [c_int] * 12 + [PP]
+    L.merit_plan_conv2d_residual.argtypes = [c_int] * 12 + [PP]
+    L.merit_conv2d_residual.argtypes = [P, P, P, P, P, P]
     L.merit_plan_pool2d.argtypes = [c_int] * 11 + [PP]
     L.merit_plan_sad.argtypes = [c_int] * 4 + [PP]
     L.merit_plan_correlation.argtypes = [c_int] * 6 + [PP]
@@ -95,7 +98,8 @@ def lib():
     L.merit_pool2d.argtypes = [P, P, P, P]
     L.merit_sad_search.argtypes = [P, P, P, P, P, P]
     for name in ("merit_plan_create", "merit_plan_destroy", "merit_plan_conv2d", "merit_plan_conv2d_relu",
-                 "merit_plan_conv2d_dilated", "merit_plan_conv2d_pool",
+                 "merit_plan_conv2d_dilated", "merit_plan_conv2d_pool", "merit_plan_conv2d_residual",
+                 "merit_conv2d_residual",
                  "merit_plan_pool2d",
                  "merit_plan_sad", "merit_plan_correlation", "merit_correlation", "merit_plan_conv2d_depthwise",
                  "merit_conv2d_depthwise", "merit_plan_get_desc", "merit_plan_out_shape", "merit_plan_footprint",
@@ -209,6 +213,13 @@ def merit_plan_conv2d_pool(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, relu=1) -
     return Plan(h)
 
 
+def merit_plan_conv2d_residual(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, relu=0) -> Plan:
+    h = ctypes.c_void_p()
+    _check(lib().merit_plan_conv2d_residual(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, int(relu), ctypes.byref(h)),
+           "merit_plan_conv2d_residual")
+    return Plan(h)
+
+
 def merit_plan_pool2d(N, C, H, W, kh, kw, sh, sw, ph, pw, is_avg) -> Plan:
     h = ctypes.c_void_p()
     _check(lib().merit_plan_pool2d(N, C, H, W, kh, kw, sh, sw, ph, pw, int(bool(is_avg)), ctypes.byref(h)),
@@ -256,6 +267,21 @@ def merit_conv2d(plan: Plan, x, w, y=None, stream=None):
         raise ValueError("x / w do not match the plan")
     _check(lib().merit_conv2d(plan.handle, _dev_ptr(x, torch.float16, "x"), _dev_ptr(w, torch.float16, "w"),
                               _dev_ptr(y, torch.float16, "y"), _stream(stream)), "merit_conv2d")
+    return y
+
+
+def merit_conv2d_residual(plan: Plan, x, w, r, y=None, stream=None):
+    import torch
+    out_shape, a_shape, b_shape = plan.shapes()
+    if y is None:
+        y = torch.empty(out_shape, dtype=torch.float16, device=x.device)
+    if tuple(y.shape) != out_shape or tuple(r.shape) != out_shape:
+        raise ValueError("y / r have the wrong shape")
+    if tuple(x.shape) != a_shape or tuple(w.shape) != b_shape:
+        raise ValueError("x / w do not match the plan")
+    _check(lib().merit_conv2d_residual(plan.handle, _dev_ptr(x, torch.float16, "x"), _dev_ptr(w, torch.float16, "w"),
+                                       _dev_ptr(r, torch.float16, "r"), _dev_ptr(y, torch.float16, "y"),
+                                       _stream(stream)), "merit_conv2d_residual")
     return y
 
 
@@ -352,6 +378,17 @@ def bind_conv2d(plan: Plan, x, w, y, stream=None) -> BoundCall:
     args = (plan.handle, _dev_ptr(x, torch.float16, "x"), _dev_ptr(w, torch.float16, "w"),
             _dev_ptr(y, torch.float16, "y"), _stream(stream))
     return BoundCall(lib().merit_conv2d, "merit_conv2d", args, (plan, x, w, y))
+
+
+def bind_conv2d_residual(plan: Plan, x, w, r, y, stream=None) -> BoundCall:
+    import torch
+    out_shape, a_shape, b_shape = plan.shapes()
+    if (tuple(y.shape) != out_shape or tuple(r.shape) != out_shape or tuple(x.shape) != a_shape
+            or tuple(w.shape) != b_shape):
+        raise ValueError("tensors do not match the plan")
+    args = (plan.handle, _dev_ptr(x, torch.float16, "x"), _dev_ptr(w, torch.float16, "w"),
+            _dev_ptr(r, torch.float16, "r"), _dev_ptr(y, torch.float16, "y"), _stream(stream))
+    return BoundCall(lib().merit_conv2d_residual, "merit_conv2d_residual", args, (plan, x, w, r, y))
 
 
 def bind_pool2d(plan: Plan, x, y, stream=None) -> BoundCall:

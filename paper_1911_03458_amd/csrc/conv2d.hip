@@ -57,14 +57,14 @@ __device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, v);
 }
 
-// Touch every 64-byte line of the kernel's argument block (ConvParams + three pointers) with
+// Touch every 64-byte line of the kernel's argument block (ConvParams + four pointers) with
 // the first scalar loads, so that the later ones, issued where their values are needed, hit
 // the scalar cache instead of each paying a trip to memory.
 __device__ __forceinline__ void touch_kernarg_lines()
 {
     typedef const uint32_t __attribute__((address_space(4))) *kernarg_ptr;
     kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
-    const uint32_t warm = ka[16] ^ ka[32] ^ ka[48];
+    const uint32_t warm = ka[16] ^ ka[32] ^ ka[48] ^ ka[64];
     asm volatile("" ::"s"(warm));
 }
 
@@ -85,13 +85,41 @@ __device__ __forceinline__ uint32_t relu_f16x2(uint32_t v)
     return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(half2v, v), z));
 }
 
+// add = true: the staging area already holds a tensor of the output's shape in the same
+// layout (see stage_residual); it is added to the fp32 sums before the clip and the one
+// rounding (the residual layer of Section III-B: a loaded tensor added in PostLoop).  Every
+// lane reads exactly the 8 bytes it then overwrites.
 template <int CB, int PXW, int NW>
 __device__ __forceinline__ void tile_to_lds(floatx16 (&acc)[CB][PXW], uint32_t *outl, int wave, int lane,
-                                            bool relu)
+                                            bool relu, bool add = false)
 {
     constexpr int OP = NW * PXW * 16 + 2;
     const int h = lane >> 5, c32 = lane & 31;
     uint32_t *row = outl + c32 * OP + wave * PXW * 16 + 2 * h;
+    if (add) {
+        // all reads first: one LDS round trip for the tile
+        uint2 rr[CB][PXW][4];
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int pb = 0; pb < PXW; ++pb)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    rr[cb][pb][q] = *reinterpret_cast<const uint2 *>(row + cb * 32 * OP + pb * 16 + 4 * q);
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int pb = 0; pb < PXW; ++pb)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const half2v r0 = __builtin_bit_cast(half2v, rr[cb][pb][q].x);
+                    const half2v r1 = __builtin_bit_cast(half2v, rr[cb][pb][q].y);
+                    acc[cb][pb][4 * q] += (float)r0[0];
+                    acc[cb][pb][4 * q + 1] += (float)r0[1];
+                    acc[cb][pb][4 * q + 2] += (float)r1[0];
+                    acc[cb][pb][4 * q + 3] += (float)r1[1];
+                }
+    }
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
@@ -146,11 +174,57 @@ __device__ __forceinline__ void lds_to_global(const ConvParams &p, const uint32_
     }
 }
 
+// Residual layer: the tile of the added tensor r (the output's shape) global -> staging area,
+// in the layout and with the thread-to-unit map of lds_to_global.  Called between the two
+// barriers that frame a tile's input staging: the previous tile's results have left the area,
+// and the barrier before the K loop publishes it.  Every load is issued before the first
+// LDS write (one memory round trip); units outside the tensor leave the area untouched
+// (their sums are never stored).
+template <int CB, int TM, int NT>
+__device__ __forceinline__ void stage_residual(const ConvParams &p, uint32_t *outl, const uint16_t *__restrict__ r,
+                                               int n, int co_base, int m0, int t)
+{
+    constexpr int OP = TM / 2 + 2;
+    const int ohw = p.OH * p.OW;
+    constexpr int UNITS = CB * 32 * (TM / 8);
+    constexpr int PER = UNITS / NT;                       // TM/8 and NT are powers of two >= 32
+    if ((ohw & 7) == 0) {
+        uint32x4 v[PER];
+        bool ok[PER];
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            const int u = t + NT * k;
+            const int c = u / (TM / 8);
+            const int m = m0 + (u - c * (TM / 8)) * 8;
+            ok[k] = m < ohw && co_base + c < p.Cout;
+            const size_t off = ok[k] ? ((size_t)n * p.Cout + co_base + c) * ohw + m : 0;
+            v[k] = *reinterpret_cast<const uint32x4 *>(r + off);
+        }
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            const int u = t + NT * k;
+            const int c = u / (TM / 8);
+            uint2 *dst = reinterpret_cast<uint2 *>(outl + c * OP + (u - c * (TM / 8)) * 4);
+            if (ok[k]) {
+                dst[0] = make_uint2(v[k].x, v[k].y);
+                dst[1] = make_uint2(v[k].z, v[k].w);
+            }
+        }
+    } else {
+        uint16_t *outh = reinterpret_cast<uint16_t *>(outl);
+        for (int e = t; e < CB * 32 * TM; e += NT) {
+            const int c = e / TM, px = e - c * TM;
+            if (m0 + px < ohw && co_base + c < p.Cout)
+                outh[c * OP * 2 + px] = r[((size_t)n * p.Cout + co_base + c) * ohw + m0 + px];
+        }
+    }
+}
+
 template <int CB, int PXW, int NW, bool FULL>
 __device__ __forceinline__ void store_tile(const ConvParams &p, floatx16 (&acc)[CB][PXW], uint32_t *outl,
                                            uint16_t *__restrict__ y, int n, int co_base, int m0, int tid)
 {
-    tile_to_lds<CB, PXW, NW>(acc, outl, tid >> 6, tid & 63, p.relu != 0);
+    tile_to_lds<CB, PXW, NW>(acc, outl, tid >> 6, tid & 63, p.relu != 0, p.residual != 0);
     __syncthreads();
     lds_to_global<CB, NW * PXW * 32, NW * 64, FULL>(p, outl, y, n, co_base, m0, tid);
 }
@@ -167,6 +241,7 @@ __device__ __forceinline__ void store_tile(const ConvParams &p, floatx16 (&acc)[
 template <int CB, int PXW, int NW, bool ALIGNED, bool PREFETCH>
 __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, const uint16_t *__restrict__ x,
                                                              const uint16_t *__restrict__ w,
+                                                             const uint16_t *__restrict__ res,
                                                              uint16_t *__restrict__ y)
 {
     extern __shared__ __align__(16) uint8_t smem[];
@@ -319,6 +394,7 @@ __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, 
     floatx16 acc[CB][PXW];
     auto tile_body = [&](const Geom &T, const Geom &Tn) {
         __syncthreads();                                  // previous tile fully consumed
+        if (p.residual) stage_residual<CB, NW * PXW * 32, NT>(p, outl, res, T.n, co_base, T.m0, tid);
         if (prefetchable) {
             commit_loads(tid);
         } else if (vec_ok) {
@@ -513,6 +589,7 @@ __device__ __forceinline__ uint32x4 row_max3_s2(uint32_t left, const uint32_t (&
 template <int CB, bool ALIGNED, int SU, bool POOL>
 __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, const uint16_t *__restrict__ x,
                                                                 const uint16_t *__restrict__ w,
+                                                                const uint16_t *__restrict__ /* no residual layer here */,
                                                                 uint16_t *__restrict__ y)
 {
     constexpr int PXW = 2, NWC = 4, TM = NWC * PXW * 32, NTG = 128;    // loading / storing group = 2 wavefronts
@@ -1139,6 +1216,7 @@ __device__ __forceinline__ void stage_input_chblock(const ConvParams &p, const u
 template <int CB, int PXW>
 __global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const uint16_t *__restrict__ x,
                                                            const uint16_t *__restrict__ w,
+                                                           const uint16_t *__restrict__ res,
                                                            uint16_t *__restrict__ y)
 {
     touch_kernarg_lines();
@@ -1174,6 +1252,7 @@ __global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const 
         } else {
             stage_input_chblock(p, x, xl, n, yA, RH, tid, 256);
         }
+        if (p.residual) stage_residual<CB, 4 * PXW * 32, 256>(p, outl, res, n, co_base, m0, tid);
         __syncthreads();
 
         int pbase[PXW], pcol[PXW];                  // staged row offset and column of tap kx = 0
@@ -1252,7 +1331,7 @@ __global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const 
 
 // ---------------------------------------------------------------------------
 template <typename K>
-static hipError_t launch(K kernel, const ConvParams &p, const void *x, const void *w, void *y,
+static hipError_t launch(K kernel, const ConvParams &p, const void *x, const void *w, const void *r, void *y,
                          hipStream_t s, uint32_t gx, size_t lds_bytes, uint32_t nthreads = 256)
 {
     // raise this kernel instance's dynamic-LDS limit to the 160 KB a gfx950 workgroup may
@@ -1266,7 +1345,7 @@ static hipError_t launch(K kernel, const ConvParams &p, const void *x, const voi
     }
     hipLaunchKernelGGL(kernel, dim3(gx, (uint32_t)p.co_groups), dim3(nthreads), lds_bytes, s, p,
                        reinterpret_cast<const uint16_t *>(x), reinterpret_cast<const uint16_t *>(w),
-                       reinterpret_cast<uint16_t *>(y));
+                       reinterpret_cast<const uint16_t *>(r), reinterpret_cast<uint16_t *>(y));
     return hipGetLastError();
 }
 
@@ -1290,7 +1369,7 @@ static int device_cu_count()
     return cus;
 }
 
-hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, void *y, hipStream_t s)
+hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, const void *r, void *y, hipStream_t s)
 {
     const int64_t ntiles = (int64_t)p.N * p.tiles_per_image;
     if (ntiles == 0) return hipSuccess;
@@ -1304,11 +1383,11 @@ hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, void
     do {                                                                                                   \
         if (p.pool) {                                                                                      \
             const uint32_t gp = (uint32_t)((int64_t)p.N * p.NB);                                           \
-            if (p.aligned) return launch(merit_conv2d_planar_ws<CBv, true, SUv, true>, p, x, w, y, s, gp, lds, 512);  \
-            return launch(merit_conv2d_planar_ws<CBv, false, SUv, true>, p, x, w, y, s, gp, lds, 512);     \
+            if (p.aligned) return launch(merit_conv2d_planar_ws<CBv, true, SUv, true>, p, x, w, r, y, s, gp, lds, 512);  \
+            return launch(merit_conv2d_planar_ws<CBv, false, SUv, true>, p, x, w, r, y, s, gp, lds, 512);     \
         }                                                                                                  \
-        if (p.aligned) return launch(merit_conv2d_planar_ws<CBv, true, SUv, false>, p, x, w, y, s, gx, lds, 512); \
-        return launch(merit_conv2d_planar_ws<CBv, false, SUv, false>, p, x, w, y, s, gx, lds, 512);        \
+        if (p.aligned) return launch(merit_conv2d_planar_ws<CBv, true, SUv, false>, p, x, w, r, y, s, gx, lds, 512); \
+        return launch(merit_conv2d_planar_ws<CBv, false, SUv, false>, p, x, w, r, y, s, gx, lds, 512);        \
     } while (0)
         switch (p.CB * 100 + p.su) {
         case 204: MERIT_PLANAR_WS(2, 4);
@@ -1331,10 +1410,10 @@ hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, void
         const bool pf = (p.W % 8 == 0) && ((int64_t)p.Cin * p.RHa * (p.pitch / 8) <= nt * 5);
 #define MERIT_PLANAR(CBv, PXv, NWv)                                                                        \
     do {                                                                                                   \
-        if (p.aligned && pf) return launch(merit_conv2d_planar<CBv, PXv, NWv, true, true>, p, x, w, y, s, gx, lds, nt);   \
-        if (p.aligned) return launch(merit_conv2d_planar<CBv, PXv, NWv, true, false>, p, x, w, y, s, gx, lds, nt);        \
-        if (pf) return launch(merit_conv2d_planar<CBv, PXv, NWv, false, true>, p, x, w, y, s, gx, lds, nt);               \
-        return launch(merit_conv2d_planar<CBv, PXv, NWv, false, false>, p, x, w, y, s, gx, lds, nt);                      \
+        if (p.aligned && pf) return launch(merit_conv2d_planar<CBv, PXv, NWv, true, true>, p, x, w, r, y, s, gx, lds, nt);   \
+        if (p.aligned) return launch(merit_conv2d_planar<CBv, PXv, NWv, true, false>, p, x, w, r, y, s, gx, lds, nt);        \
+        if (pf) return launch(merit_conv2d_planar<CBv, PXv, NWv, false, true>, p, x, w, r, y, s, gx, lds, nt);               \
+        return launch(merit_conv2d_planar<CBv, PXv, NWv, false, false>, p, x, w, r, y, s, gx, lds, nt);                      \
     } while (0)
         if (p.NW == 8) {
             if (p.CB == 2) MERIT_PLANAR(2, 1, 8);
@@ -1346,10 +1425,10 @@ hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, void
         MERIT_PLANAR(1, 1, 4);
 #undef MERIT_PLANAR
     }
-    if (p.CB == 2 && p.PXW == 2) return launch(merit_conv2d_chblock<2, 2>, p, x, w, y, s, gx, lds);
-    if (p.CB == 2 && p.PXW == 1) return launch(merit_conv2d_chblock<2, 1>, p, x, w, y, s, gx, lds);
-    if (p.CB == 1 && p.PXW == 2) return launch(merit_conv2d_chblock<1, 2>, p, x, w, y, s, gx, lds);
-    return launch(merit_conv2d_chblock<1, 1>, p, x, w, y, s, gx, lds);
+    if (p.CB == 2 && p.PXW == 2) return launch(merit_conv2d_chblock<2, 2>, p, x, w, r, y, s, gx, lds);
+    if (p.CB == 2 && p.PXW == 1) return launch(merit_conv2d_chblock<2, 1>, p, x, w, r, y, s, gx, lds);
+    if (p.CB == 1 && p.PXW == 2) return launch(merit_conv2d_chblock<1, 2>, p, x, w, r, y, s, gx, lds);
+    return launch(merit_conv2d_chblock<1, 1>, p, x, w, r, y, s, gx, lds);
 }
 
 const char *conv_kernel_name(const ConvParams &p)

@@ -99,6 +99,7 @@ struct ConvParams {
     int front;             // planar: slot of tap kx = 0 inside an 8-slot fragment (0 or 1)
     int aligned;           // planar: every fragment starts on an even staged column
     int relu;              // product function max(v1.v2, 0): results clipped at zero before rounding
+    int residual;          // a tensor of the output's shape is added to the sums before clip and rounding
     int ws;                // planar: wave-specialised kernel (4 multiplier + 4 mover wavefronts)
     int su;                // wave-specialised kernel: unrolled K steps (S <= su <= S+2)
     int lg_chunks;         // wave-specialised kernel: log2 of the 16-byte chunks per staged row, rounded up
@@ -124,7 +125,7 @@ struct ConvParams {
 hipError_t launch_pool2d(const PoolParams &p, const float *x, float *y, hipStream_t s);
 hipError_t launch_sad(const SadParams &p, const uint8_t *cur, const uint8_t *ref,
                       int32_t *sad, int32_t *mv, hipStream_t s);
-hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, void *y, hipStream_t s);
+hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, const void *r, void *y, hipStream_t s);
 
 const char *pool_kernel_name(const PoolParams &p);
 const char *sad_kernel_name(const SadParams &p);

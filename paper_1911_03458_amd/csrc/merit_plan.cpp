@@ -293,7 +293,9 @@ merit_status derive_conv(merit_plan *pl)
 
     ConvParams &p = pl->conv;
     p.N = (int)N; p.Cin = (int)Cin; p.H = (int)H; p.W = (int)W; p.Cout = (int)Cout;
-    p.relu = (d.op == MERIT_OP_CONV_DOT_RELU || d.op == MERIT_OP_CONV_DOT_RELU_POOLMAX) ? 1 : 0;
+    p.relu = (d.op == MERIT_OP_CONV_DOT_RELU || d.op == MERIT_OP_CONV_DOT_RELU_POOLMAX ||
+              d.op == MERIT_OP_CONV_DOT_ADD_RELU) ? 1 : 0;
+    p.residual = (d.op == MERIT_OP_CONV_DOT_ADD || d.op == MERIT_OP_CONV_DOT_ADD_RELU) ? 1 : 0;
     const bool pool = d.op == MERIT_OP_CONV_DOT_POOLMAX || d.op == MERIT_OP_CONV_DOT_RELU_POOLMAX;
     p.pool = pool ? 1 : 0;
     p.PH = p.PW = p.PB = p.NB = p.pw8 = 0;
@@ -308,7 +310,9 @@ merit_status derive_conv(merit_plan *pl)
     p.co_groups = (int)cdiv(ncb, p.CB);
 
     // try both tile sizes for a variant; prefer 256 pixels when the grid stays large
-    bool want_ws = pl->tile_req[2] <= 0;                  // an explicit tile request selects the plain kernels
+    // an explicit tile request selects the plain kernels; so does the residual layer (the added
+    // tensor is staged by the wavefronts that also multiply)
+    bool want_ws = pl->tile_req[2] <= 0 && !p.residual;
     auto try_variant = [&](int variant, int pxw, int nw) -> bool {
         ConvParams q = p;
         q.variant = variant;
@@ -439,6 +443,7 @@ merit_status derive_conv(merit_plan *pl)
         if ((nw != 4 && nw != 8) || (ppw != 32 && ppw != 64)) return MERIT_ERR_UNSUPPORTED;
         if (nw == 8 && ppw == 64) {
             // 4 multiplier wavefronts x 64 pixels + 4 mover wavefronts: the wave-specialised kernel
+            if (p.residual) return MERIT_ERR_UNSUPPORTED;
             want_ws = true;
             if (Cin < 8) ok = try_variant(CONV_PLANAR_SMALLC, 2, 4) && p.ws;
             if (!ok) return MERIT_ERR_UNSUPPORTED;
@@ -622,7 +627,7 @@ merit_status merit_plan_create(const merit_plan_desc *desc, merit_plan **out)
 {
     if (!desc || !out) return MERIT_ERR_NULL;
     *out = nullptr;
-    if ((int)desc->op < 0 || (int)desc->op > 8 || (int)desc->dtype < 0 || (int)desc->dtype > 2 ||
+    if ((int)desc->op < 0 || (int)desc->op > 10 || (int)desc->dtype < 0 || (int)desc->dtype > 2 ||
         (int)desc->pad < 0 || (int)desc->pad > 3)
         return MERIT_ERR_INVALID_ARG;
     if (desc->n_par < 1 || desc->n_acc < 1 || desc->n_par + desc->n_acc > MERIT_MAX_INDEX)
@@ -645,7 +650,9 @@ merit_status merit_plan_create(const merit_plan_desc *desc, merit_plan **out)
     case MERIT_OP_CONV_DOT:
     case MERIT_OP_CONV_DOT_RELU:
     case MERIT_OP_CONV_DOT_POOLMAX:
-    case MERIT_OP_CONV_DOT_RELU_POOLMAX: st = derive_conv(pl); break;
+    case MERIT_OP_CONV_DOT_RELU_POOLMAX:
+    case MERIT_OP_CONV_DOT_ADD:
+    case MERIT_OP_CONV_DOT_ADD_RELU: st = derive_conv(pl); break;
     case MERIT_OP_POOL_MAX:
     case MERIT_OP_POOL_AVG: st = derive_pool(pl); break;
     case MERIT_OP_CORR_DOT: st = derive_corr(pl); break;
@@ -728,6 +735,13 @@ merit_status merit_plan_conv2d_pool(int N, int Cin, int H, int W, int Cout, int 
                           kh, kw, sh, sw, ph, pw, 1, 1, out);
 }
 
+merit_status merit_plan_conv2d_residual(int N, int Cin, int H, int W, int Cout, int kh, int kw, int sh, int sw,
+                                        int ph, int pw, int relu, merit_plan **out)
+{
+    return plan_conv2d_op(relu ? MERIT_OP_CONV_DOT_ADD_RELU : MERIT_OP_CONV_DOT_ADD, N, Cin, H, W, Cout, kh, kw, sh,
+                          sw, ph, pw, 1, 1, out);
+}
+
 merit_status merit_plan_pool2d(int N, int C, int H, int W, int kh, int kw, int sh, int sw, int ph, int pw,
                                int is_avg, merit_plan **out)
 {
@@ -793,7 +807,9 @@ merit_status merit_plan_set_tile(merit_plan *plan, const int64_t tile[MERIT_MAX_
     case MERIT_OP_CONV_DOT:
     case MERIT_OP_CONV_DOT_RELU:
     case MERIT_OP_CONV_DOT_POOLMAX:
-    case MERIT_OP_CONV_DOT_RELU_POOLMAX: st = derive_conv(&trial); break;
+    case MERIT_OP_CONV_DOT_RELU_POOLMAX:
+    case MERIT_OP_CONV_DOT_ADD:
+    case MERIT_OP_CONV_DOT_ADD_RELU: st = derive_conv(&trial); break;
     case MERIT_OP_POOL_MAX:
     case MERIT_OP_POOL_AVG: st = derive_pool(&trial); break;
     case MERIT_OP_CORR_DOT: st = derive_corr(&trial); break;
@@ -858,8 +874,23 @@ merit_status merit_conv2d(const merit_plan *plan, const void *x, const void *w, 
     if (plan->conv.N == 0) return MERIT_OK;               // empty batch: nothing to read or write
     if (!x || !w || !y) return MERIT_ERR_NULL;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return MERIT_ERR_ALIGNMENT;
-    return launch_conv2d(plan->conv, x, w, y, static_cast<hipStream_t>(stream)) == hipSuccess ? MERIT_OK
-                                                                                              : MERIT_ERR_HIP;
+    return launch_conv2d(plan->conv, x, w, nullptr, y, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? MERIT_OK
+               : MERIT_ERR_HIP;
+}
+
+merit_status merit_conv2d_residual(const merit_plan *plan, const void *x, const void *w, const void *r, void *y,
+                                   void *stream)
+{
+    if (!plan) return MERIT_ERR_NULL;
+    if (plan->desc.op != MERIT_OP_CONV_DOT_ADD && plan->desc.op != MERIT_OP_CONV_DOT_ADD_RELU)
+        return MERIT_ERR_INVALID_ARG;
+    if (plan->conv.N == 0) return MERIT_OK;               // empty batch: nothing to read or write
+    if (!x || !w || !r || !y) return MERIT_ERR_NULL;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(r) || !aligned16(y)) return MERIT_ERR_ALIGNMENT;
+    return launch_conv2d(plan->conv, x, w, r, y, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? MERIT_OK
+               : MERIT_ERR_HIP;
 }
 
 merit_status merit_pool2d(const merit_plan *plan, const void *x, void *y, void *stream)

@@ -118,6 +118,26 @@ def test_fused_pooling_plan():
         assert e.value.status == mb.MERIT_ERR_UNSUPPORTED
 
 
+def test_residual_plan():
+    """The residual layer keeps the convolution's descriptor; only the multiply-and-store kernels
+    take the added tensor, so the planner never picks the wave-specialised one."""
+    args = (32, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3)
+    plan = mb.merit_plan_conv2d_residual(*args, 1)
+    conv = mb.merit_plan_conv2d(*args)
+    assert plan.desc().op == mb.MERIT_OP_CONV_DOT_ADD_RELU and tuple(plan.desc().range) == tuple(conv.desc().range)
+    assert mb.merit_plan_conv2d_residual(*args, 0).desc().op == mb.MERIT_OP_CONV_DOT_ADD
+    assert plan.out_shape() == conv.out_shape()
+    assert conv.launch_info()["kernel"] == "merit_conv2d_planar_ws"
+    assert plan.launch_info()["kernel"] == "merit_conv2d_planar"
+    with pytest.raises(mb.MeritError):
+        plan.set_tile((0, 0, 8, 64))
+    plan.set_tile((0, 0, 4, 64))
+    assert plan.launch_info()["kernel"] == "merit_conv2d_planar"
+    res = mb.merit_plan_conv2d_residual(8, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1, 1)
+    assert res.launch_info() == mb.merit_plan_conv2d(8, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1).launch_info()
+    assert mb.merit_plan_create(res.desc()).desc().op == mb.MERIT_OP_CONV_DOT_ADD_RELU
+
+
 def test_depthwise_plan():
     plan = mb.merit_plan_conv2d_depthwise(32, 32, 64, 64, 3, 3, 1, 1, 1, 1)
     d = plan.desc()

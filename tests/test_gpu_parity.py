@@ -561,6 +561,88 @@ def test_conv_pool_fused_7x7_workload(mb):
     assert torch.equal(y, pooled)
 
 
+RESIDUAL_CASES = [
+    # N Cin H   W  Cout kh kw sh sw ph pw relu   (one per kernel and staging path)
+    (2, 64, 28, 28, 64, 3, 3, 1, 1, 1, 1, 1),   # channel-block, the residual block's shape class
+    (1, 16, 12, 16, 40, 3, 3, 1, 1, 1, 1, 0),   # channel-block, ragged channels, no clip
+    (1, 20, 9, 11, 10, 2, 3, 1, 1, 0, 1, 1),    # channel-block, OH*OW % 8 != 0: scalar staging of r
+    (2, 3, 32, 32, 64, 7, 7, 2, 2, 3, 3, 1),    # planar with prefetch
+    (2, 3, 17, 19, 40, 7, 7, 2, 2, 3, 3, 0),    # planar, odd sizes
+    (40, 3, 64, 64, 64, 7, 7, 2, 2, 3, 3, 1),   # planar, several tiles per workgroup
+]
+
+
+def _residual_check(mb, case, tile=None, in_place=False):
+    N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, relu = case
+    rng = np.random.default_rng(abs(hash(case)) % 2 ** 31)
+    x = rng.standard_normal((N, Cin, H, W)).astype(np.float16)
+    w = (rng.standard_normal((Cout, Cin, kh, kw)) / np.sqrt(Cin * kh * kw)).astype(np.float16)
+    plan = mb.merit_plan_conv2d_residual(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, relu)
+    if tile is not None:
+        plan.set_tile(tile)
+    r = rng.standard_normal(plan.out_shape()).astype(np.float16)
+    print("conv+residual", case, plan.launch_info(), flush=True)
+    buf, y, p = guarded_empty(plan.out_shape(), torch.float16, 777.0)
+    if in_place:
+        y.copy_(dev(r))
+        mb.merit_conv2d_residual(plan, dev(x), dev(w), y, y)
+    else:
+        mb.merit_conv2d_residual(plan, dev(x), dev(w), dev(r), y)
+    torch.cuda.synchronize()
+    check_canary(buf, p, 777.0)
+    got = y.cpu().numpy().astype(np.float64)
+    ref = oracle.conv2d_residual(x, w, r, (sh, sw), (ph, pw), relu=bool(relu)).astype(np.float64)
+    # one rounding of (sum + r): the convolution's bar holds on the result itself, also where
+    # the two terms cancel
+    err = np.abs(got - ref)
+    tol = 2e-2 * np.abs(ref) + 1e-3
+    assert np.all(err <= tol), f"max excess {np.max(err - tol)} at {np.unravel_index(np.argmax(err - tol), err.shape)}"
+    if relu:
+        assert not np.signbit(got).any()
+    return got, ref
+
+
+@pytest.mark.parametrize("case", RESIDUAL_CASES)
+def test_conv_residual(mb, case):
+    _residual_check(mb, case)
+
+
+def test_conv_residual_in_place_and_big_tiles(mb):
+    _residual_check(mb, RESIDUAL_CASES[0], in_place=True)
+    _residual_check(mb, RESIDUAL_CASES[0], tile=(0, 0, 4, 64))
+    _residual_check(mb, RESIDUAL_CASES[3], tile=(0, 0, 4, 64), in_place=True)
+    _residual_check(mb, RESIDUAL_CASES[3], tile=(0, 0, 8, 32))
+
+
+def test_conv_residual_single_rounding(mb):
+    """sum = 2049 is a binary16 tie (alone it rounds to 2048); with r = 1 the exact 2050 is
+    representable, and r = -2048 leaves exactly 1: both need the addition before the rounding."""
+    Cin = 16
+    x = np.zeros((1, Cin, 8, 8), np.float16)
+    x[0, 0], x[0, 1] = 2048.0, 1.0
+    w = np.zeros((32, Cin, 1, 1), np.float16)
+    w[:, 0], w[:, 1] = 1.0, 1.0
+    plan = mb.merit_plan_conv2d_residual(1, Cin, 8, 8, 32, 1, 1, 1, 1, 0, 0, 0)
+    r = np.ones(plan.out_shape(), np.float16)
+    r[0, :, 4:] = -2048.0
+    y = mb.merit_conv2d_residual(plan, dev(x), dev(w), dev(r)).cpu().numpy().astype(np.float64)
+    assert np.all(y[0, :, :4] == 2050.0) and np.all(y[0, :, 4:] == 1.0)
+    assert np.array_equal(y, oracle.conv2d_residual(x, w, r).astype(np.float64))
+
+
+def test_conv_residual_3x3_workload(mb):
+    """The 3x3 / 64-channel layer as a residual block's second convolution, full size."""
+    c = wl.CFG2_CONV3
+    x, w = wl.make_conv_inputs(c)
+    plan = mb.merit_plan_conv2d_residual(c.N, c.Cin, c.H, c.W, c.Cout, c.kh, c.kw, c.sh, c.sw, c.ph, c.pw, 1)
+    assert plan.launch_info()["kernel"] == "merit_conv2d_chblock"
+    r = np.random.default_rng(wl.BASE_SEED + 77).standard_normal(plan.out_shape()).astype(np.float16)
+    y = mb.merit_conv2d_residual(plan, dev(x), dev(w), dev(r)).cpu().numpy().astype(np.float64)
+    ref = oracle.conv2d_residual(x, w, r, (c.sh, c.sw), (c.ph, c.pw), relu=True).astype(np.float64)
+    assert np.all(np.abs(y - ref) <= 2e-2 * np.abs(ref) + 1e-3)
+    assert (ref == 0).mean() > 0.2 and (ref > 0).mean() > 0.2
+
+
 DILATED_CASES = [
     # N Cin H   W  Cout kh kw sh sw ph pw dh dw relu
     (1, 32, 64, 64, 32, 3, 3, 1, 1, 2, 2, 2, 2, 0),   # the dilated layer of the paper's table: 64x64x32 out
