@@ -208,13 +208,15 @@ def pool2d(x: np.ndarray, kernel=(3, 3), stride=(2, 2), pad=(1, 1), mode="max") 
 
 
 def sad_search(cur: np.ndarray, ref: np.ndarray, block: int, search: int):
-    """cur, ref u8 [H,W] -> (sad int32 [nby,nbx], mv int32 [nby,nbx,2] = (dy,dx))."""
+    """cur, ref u8 [H,W] -> (sad int32 [nby,nbx], mv int32 [nby,nbx,2] = (dy,dx));
+    nby = ceil(H / block), nbx = ceil(W / block): blocks that reach past the edge read both
+    frames with clamped coordinates."""
     cur = _c(cur, np.uint8)
     ref = _c(ref, np.uint8)
     H, W = cur.shape
     if ref.shape != (H, W):
         raise ValueError("frame shape mismatch")
-    nby, nbx = H // block, W // block
+    nby, nbx = -(-H // block), -(-W // block)
     sad = np.empty((nby, nbx), np.int32)
     mv = np.empty((nby, nbx, 2), np.int32)
     rc = _load().ref_sad_search(_ptr(cur), _ptr(ref), _ptr(sad), _ptr(mv), H, W, block, search)

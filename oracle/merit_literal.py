@@ -117,7 +117,7 @@ def sad_desc(H, W, B, R):
     """k = (by, bx | dy, dx, i, j): the reference frame is displaced by the
     search indices (the index pattern of the correlation layer, Eq. 8)."""
     n = 2 * R + 1
-    ranges = (H // B, W // B, n, n, B, B)
+    ranges = (-(-H // B), -(-W // B), n, n, B, B)           # blocks past the edge read clamped
     tref = Transform(axis=(0, 1, 0, 1, 0, 1),
                      stride=(B, B, 1, 1, 1, 1),
                      offset=(0, 0, -R, -R, 0, 0))

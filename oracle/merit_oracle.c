@@ -269,12 +269,16 @@ int ref_pool2d(const float *x, float *y, int N, int C, int H, int W,
 static inline int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
 /*
- * One candidate: SAD(by,bx,dy,dx) = sum_{i,j<B} | cur[by*B+i, bx*B+j]
+ * One candidate: SAD(by,bx,dy,dx) = sum_{i,j<B} | cur[clamp(by*B+i), clamp(bx*B+j)]
  *                 - ref[clamp(by*B+i+dy, 0, H-1), clamp(bx*B+j+dx, 0, W-1)] |
  * The second tensor is displaced by the search indices exactly as in the
  * correlation-layer example (Section III-C, Eq. 8): ref coordinate = cur
- * coordinate + displacement.  Reference reads outside the frame are clamped
- * to the nearest edge pixel.
+ * coordinate + displacement.  Reads outside a frame are clamped to the nearest
+ * edge pixel, in both frames: a frame whose height or width is not a multiple of
+ * B has ceil(H/B) x ceil(W/B) blocks, and the last ones reach past the edge
+ * (both frames extended by border replication, the same as padding them to a
+ * multiple of B that way first).  For frames B divides, no current-frame read is
+ * ever clamped.
  */
 int32_t ref_sad_candidate(const uint8_t *cur, const uint8_t *ref, int H, int W, int B,
                           int by, int bx, int dy, int dx)
@@ -285,7 +289,8 @@ int32_t ref_sad_candidate(const uint8_t *cur, const uint8_t *ref, int H, int W, 
             const int cy = by * B + i, cx = bx * B + j;
             const int ry = clampi(cy + dy, 0, H - 1);
             const int rx = clampi(cx + dx, 0, W - 1);
-            const int d = (int)cur[(size_t)cy * W + cx] - (int)ref[(size_t)ry * W + rx];
+            const int d = (int)cur[(size_t)clampi(cy, 0, H - 1) * W + clampi(cx, 0, W - 1)] -
+                          (int)ref[(size_t)ry * W + rx];
             sad += d < 0 ? -d : d;
         }
     return sad;
@@ -303,8 +308,7 @@ int ref_sad_search(const uint8_t *cur, const uint8_t *ref, int32_t *sad, int32_t
                    int H, int W, int B, int R)
 {
     if (H <= 0 || W <= 0 || B <= 0 || R < 0) return -1;
-    if (H % B || W % B) return -1;
-    const int nby = H / B, nbx = W / B;
+    const int nby = (H + B - 1) / B, nbx = (W + B - 1) / B;
     long b;
 #pragma omp parallel for schedule(static)
     for (b = 0; b < (long)nby * nbx; ++b) {
@@ -365,8 +369,8 @@ int ref_correlation(const uint16_t *x1, const uint16_t *x2, uint16_t *y,
 int ref_sad_surface(const uint8_t *cur, const uint8_t *ref, int32_t *surface,
                     int H, int W, int B, int R, int by, int bx)
 {
-    if (H <= 0 || W <= 0 || B <= 0 || R < 0 || H % B || W % B) return -1;
-    if (by < 0 || by >= H / B || bx < 0 || bx >= W / B) return -1;
+    if (H <= 0 || W <= 0 || B <= 0 || R < 0) return -1;
+    if (by < 0 || by >= (H + B - 1) / B || bx < 0 || bx >= (W + B - 1) / B) return -1;
     int k = 0;
     for (int dy = -R; dy <= R; ++dy)
         for (int dx = -R; dx <= R; ++dx)

@@ -88,7 +88,8 @@ def test_triangle_lower_bound_and_surface_minimum():
             assert abs(cb.sum() - rb.sum()) <= s[3, 3] == np.abs(cb - rb).sum()
 
 
-@pytest.mark.parametrize("H,W,B,R", [(16, 16, 4, 2), (8, 24, 8, 3), (12, 8, 4, 1), (16, 32, 16, 2)])
+@pytest.mark.parametrize("H,W,B,R", [(16, 16, 4, 2), (8, 24, 8, 3), (12, 8, 4, 1), (16, 32, 16, 2),
+                                     (13, 24, 8, 3), (16, 21, 8, 2), (9, 10, 4, 1)])
 def test_matches_literal_transform_evaluator(H, W, B, R):
     rng = np.random.default_rng(H * W + B + R)
     cur = rng.integers(0, 256, size=(H, W), dtype=np.uint8)
@@ -99,6 +100,35 @@ def test_matches_literal_transform_evaluator(H, W, B, R):
         b_sad, b_mv = lit.sad_search(c, r, B, R)
         assert np.array_equal(a_sad, b_sad)
         assert np.array_equal(a_mv, b_mv)
+
+
+@pytest.mark.parametrize("H,W,B,R", [(27, 40, 8, 3), (32, 45, 16, 4), (30, 29, 8, 2), (5, 7, 8, 1)])
+def test_frames_the_block_does_not_divide_equal_edge_padded_frames(H, W, B, R):
+    """Blocks that reach past the edge read both frames with clamped coordinates: the same
+    as replicating the border out to a multiple of the block first (numpy's edge padding) and
+    running the search the block divides.  A clamp missing on either frame, or the clamp
+    applied before the displacement is added, fails here."""
+    rng = np.random.default_rng(H * 100 + W)
+    cur = rng.integers(0, 256, size=(H, W), dtype=np.uint8)
+    ref = rng.integers(0, 256, size=(H, W), dtype=np.uint8)
+    Hp, Wp = -(-H // B) * B, -(-W // B) * B
+    pad = ((0, Hp - H), (0, Wp - W))
+    sad, mv = oracle.sad_search(cur, ref, B, R)
+    psad, pmv = oracle.sad_search(np.pad(cur, pad, mode="edge"), np.pad(ref, pad, mode="edge"), B, R)
+    assert sad.shape == (Hp // B, Wp // B)
+    assert np.array_equal(sad, psad) and np.array_equal(mv, pmv)
+    # one partial block by brute force
+    by, bx = sad.shape[0] - 1, sad.shape[1] - 1
+    surf = oracle.sad_surface(cur, ref, B, R, by, bx)
+    ys = np.clip(np.arange(by * B, by * B + B), 0, H - 1)
+    xs = np.clip(np.arange(bx * B, bx * B + B), 0, W - 1)
+    cb = cur[np.ix_(ys, xs)].astype(np.int64)
+    for dy in (-R, 0, R):
+        for dx in (-R, 1):
+            ry = np.clip(np.arange(by * B, by * B + B) + dy, 0, H - 1)
+            rx = np.clip(np.arange(bx * B, bx * B + B) + dx, 0, W - 1)
+            assert surf[dy + R, dx + R] == np.abs(cb - ref[np.ix_(ry, rx)].astype(np.int64)).sum()
+    assert sad[by, bx] == surf.min()
 
 
 def test_cfg0_planted_vectors_and_noise_bound():
