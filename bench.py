@@ -306,6 +306,7 @@ def main():
             bench_conv(torch, mb, wl, wl.CFG2_CONV3, k, w, args.sets),
             bench_sad(torch, mb, wl, wl.CFG3_ME_FHD, max(10, k // 2), w),
             bench_sad(torch, mb, wl, wl.CFG_ME_720P, k, w),
+            bench_sad(torch, mb, wl, wl.CFG_ME_1080P, max(10, k // 2), w),
             bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets),
             bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets, relu=True),
             bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets, relu=True, pool=True),

@@ -146,7 +146,9 @@ merit_status merit_plan_destroy(merit_plan *plan);
  *  conv2d: y[n,co,oy,ox] = sum x[n,ci,oy*sh+ky-ph,ox*sw+kx-pw] * w[co,ci,ky,kx]
  *          (index pattern of Section III-C, Eq. 6: strided, no kernel flip).
  *  pool2d: max (is_avg=0) or mean over in-range elements (is_avg=1) of the window.
- *  sad:    frames [H,W] u8, blocks `block` x `block` (must divide H and W),
+ *  sad:    frames [H,W] u8, ceil(H/block) x ceil(W/block) blocks of `block` x `block`
+ *          pixels (blocks that reach past the frame edge read both frames with
+ *          clamped coordinates, i.e. the border replicated),
  *          candidates dy,dx in [-range, range]; second tensor displaced by the
  *          search indices as in Section III-C, Eq. 8. */
 merit_status merit_plan_conv2d(int N, int Cin, int H, int W, int Cout, int kh, int kw,

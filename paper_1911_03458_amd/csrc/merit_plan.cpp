@@ -188,15 +188,15 @@ merit_status derive_sad(merit_plan *pl)
     const int64_t H = d.a.shape[0], W = d.a.shape[1];
     if (H <= 0 || W <= 0) return MERIT_ERR_INVALID_ARG;
     if (d.b.shape[0] != H || d.b.shape[1] != W) return MERIT_ERR_SHAPE;
-    if (H % B || W % B) return MERIT_ERR_SHAPE;
-    if (d.range[0] != H / B || d.range[1] != W / B) return MERIT_ERR_SHAPE;
+    // blocks that reach past the edge (B does not divide H or W) read both frames clamped
+    if (d.range[0] != cdiv(H, B) || d.range[1] != cdiv(W, B)) return MERIT_ERR_SHAPE;
     // key packing: SAD < 2^18 and raster index < 2^14 share one u32
     if (B % 4 || B > 32 || R > 63) return MERIT_ERR_UNSUPPORTED;
-    if (H * W >= INT_LIMIT || (H / B) * (W / B) >= INT_LIMIT) return MERIT_ERR_UNSUPPORTED;
+    if (H * W >= INT_LIMIT || cdiv(H, B) * cdiv(W, B) >= INT_LIMIT) return MERIT_ERR_UNSUPPORTED;
 
     SadParams &p = pl->sad;
     p.H = (int)H; p.W = (int)W; p.B = (int)B; p.R = (int)R; p.n = (int)n;
-    p.nby = (int)(H / B); p.nbx = (int)(W / B);
+    p.nby = (int)cdiv(H, B); p.nbx = (int)cdiv(W, B);
     p.win = (int)(B + 2 * R);
     const int64_t cols4 = cdiv(p.win, 4);
     p.pitch = (int)((cols4 + 1) * 4);
@@ -212,7 +212,9 @@ merit_status derive_sad(merit_plan *pl)
     int64_t grid = (int64_t)p.nby * p.nbx;
     int64_t lds = ((int64_t)p.win * (p.pitch / 4) + 1 + B * (B / 4) + 4) * 4;
     int64_t tile_bx = 1;
-    if (B == 16 && (R == 16 || R == 32) && pl->tile_req[1] != 1) {
+    // (the row-scan kernels fetch the current block in aligned dwords: B must divide W; any H)
+    const bool rowscan_ok = W % B == 0;
+    if (rowscan_ok && B == 16 && (R == 16 || R == 32) && pl->tile_req[1] != 1) {
         const int64_t c4 = cdiv(4 * 16 + 2 * R, 4);
         if (fastdiv_ok((16 + 2 * R) * c4, c4)) {
             p.variant = SAD_ROWSCAN_B16;
@@ -229,7 +231,8 @@ merit_status derive_sad(merit_plan *pl)
     // two blocks per wavefront, eight per workgroup: 8x8 blocks with R = 8 or 16, 16x16 blocks
     // with R = 16 (a tile request of four blocks per workgroup keeps the one-block-per-wavefront
     // kernel there)
-    if (((B == 8 && (R == 8 || R == 16)) || (B == 16 && R == 16)) && pl->tile_req[1] != 1 && pl->tile_req[1] != 4) {
+    if (rowscan_ok && ((B == 8 && (R == 8 || R == 16)) || (B == 16 && R == 16)) && pl->tile_req[1] != 1 &&
+        pl->tile_req[1] != 4) {
         const int64_t c4 = cdiv(8 * B + 2 * R, 4);
         if (fastdiv_ok((B + 2 * R) * c4, c4)) {
             p.variant = SAD_ROWSCAN_PAIR;
@@ -775,13 +778,12 @@ merit_status merit_plan_sad(int H, int W, int block, int range, merit_plan **out
     if (!out) return MERIT_ERR_NULL;
     *out = nullptr;
     if (H <= 0 || W <= 0 || block <= 0 || range < 0) return MERIT_ERR_INVALID_ARG;
-    if (H % block || W % block) return MERIT_ERR_SHAPE;
     merit_plan_desc d;
     std::memset(&d, 0, sizeof(d));
     d.op = MERIT_OP_SAD_ARGMIN; d.dtype = MERIT_U8; d.pad = MERIT_PAD_CLAMP;
     d.n_par = 2; d.n_acc = 4;
     const int64_t n = 2 * (int64_t)range + 1;
-    const int64_t rg[6] = {H / block, W / block, n, n, block, block};
+    const int64_t rg[6] = {cdiv(H, block), cdiv(W, block), n, n, block, block};
     const int a_ref[6] = {0, 1, 0, 1, 0, 1};
     const int64_t s_ref[6] = {block, block, 1, 1, 1, 1};
     const int64_t o_ref[6] = {0, 0, -range, -range, 0, 0};

@@ -90,9 +90,22 @@ __global__ __launch_bounds__(256) void merit_sad_generic(SadParams p, const uint
 
     stage_window(p, ref, win32, by * p.B - p.R, bx * p.B - p.R, p.win, (p.win + 3) >> 2,
                  p.div_win4, pitch4, tid, 256);
+    // current block; pixels past the frame edge (frames the block does not divide) repeat the
+    // edge pixel, as the reference window does
+    const bool cur_vec = (p.W & 3) == 0;
     for (int i = tid; i < p.B * B4; i += 256) {
         const int r = i / B4, c4 = i - r * B4;
-        cur32[i] = *reinterpret_cast<const uint32_t *>(cur + (size_t)(by * p.B + r) * p.W + bx * p.B + 4 * c4);
+        const uint8_t *row = cur + (size_t)min(by * p.B + r, p.H - 1) * p.W;
+        const int gx = bx * p.B + 4 * c4;
+        uint32_t v;
+        if (cur_vec && gx + 3 < p.W) {
+            v = *reinterpret_cast<const uint32_t *>(row + gx);
+        } else {
+            v = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) v |= (uint32_t)row[min(gx + b, p.W - 1)] << (8 * b);
+        }
+        cur32[i] = v;
     }
     __syncthreads();
 
@@ -189,12 +202,15 @@ __global__ __launch_bounds__(256) void merit_sad_rowscan16(SadParams p, const ui
     // current block: wave-uniform loads
     uint32_t c[16][4];
     {
-        const uint32_t *cp = reinterpret_cast<const uint32_t *>(cur + (size_t)(by * 16) * p.W + bx * 16);
+        // rows past the last one (H % 16 != 0) repeat it
+        const uint32_t *cp = reinterpret_cast<const uint32_t *>(cur + bx * 16);
         const int W4 = p.W >> 2;
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
+        for (int i = 0; i < 16; ++i) {
+            const int row = min(by * 16 + i, p.H - 1);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) c[i][j] = cp[i * W4 + j];
+            for (int j = 0; j < 4; ++j) c[i][j] = cp[row * W4 + j];
+        }
     }
 
     uint32_t best = 0xffffffffu;                   // (sad << 14) | raster index
@@ -344,12 +360,15 @@ __global__ __launch_bounds__(256) void merit_sad_rowscan_pair(SadParams p, const
 
     uint32_t c[B][B4];
     {
-        const uint32_t *cp = reinterpret_cast<const uint32_t *>(cur + (size_t)(by * B) * p.W + min(bx, p.nbx - 1) * B);
+        // rows past the last one (H % B != 0) repeat it
+        const uint32_t *cp = reinterpret_cast<const uint32_t *>(cur + min(bx, p.nbx - 1) * B);
         const int W4 = p.W >> 2;
 #pragma unroll
-        for (int i = 0; i < B; ++i)
+        for (int i = 0; i < B; ++i) {
+            const int row = min(by * B + i, p.H - 1);
 #pragma unroll
-            for (int j = 0; j < B4; ++j) c[i][j] = cp[i * W4 + j];
+            for (int j = 0; j < B4; ++j) c[i][j] = cp[row * W4 + j];
+        }
     }
 
     uint32_t best = 0xffffffffu;                    // (sad << 14) | raster index

@@ -111,6 +111,8 @@ CONFIGS = [CFG0_ME_SMALL, CFG1_POOL, CFG2_CONV3, CFG3_ME_FHD, CFG4_CONV7]
 # (output 64 x 64 x 32; channel count and batch are not given there: 32 in, batch 8 here).
 CFG_CORRELATION = None   # defined below (needs its dataclass)
 CFG_ME_720P = SadWorkload("me_1280x720_b8_r16", 720, 1280, 8, 16, 0, "sinusoid")
+# full HD at its real height: 1080 = 67.5 blocks of 16, the last block row reaches past the frame
+CFG_ME_1080P = SadWorkload("me_1920x1080_b16_r32", 1080, 1920, 16, 32, 0, "uniform")
 CFG_DILATED = ConvWorkload("conv_8x32x64x64_co32_k3s1p2_d2", 8, 32, 64, 64, 32, 3, 3, 1, 1, 2, 2, "normal", 2, 2)
 
 
@@ -192,15 +194,14 @@ def make_sad_frames(wl: SadWorkload, seed: int | None = None):
     else:
         raise ValueError(wl.texture)
     ref = np.clip(tex, 0, 255).astype(np.uint8)
-    nby, nbx = H // B, W // B
+    nby, nbx = -(-H // B), -(-W // B)               # blocks past the edge are cropped below
     planted = rng.integers(-R, R + 1, size=(nby, nbx, 2), dtype=np.int64)
     vy = np.repeat(np.repeat(planted[:, :, 0], B, axis=0), B, axis=1)
     vx = np.repeat(np.repeat(planted[:, :, 1], B, axis=0), B, axis=1)
     yy, xx = np.meshgrid(np.arange(nby * B), np.arange(nbx * B), indexing="ij")
     sy = np.clip(yy + vy, 0, H - 1)
     sx = np.clip(xx + vx, 0, W - 1)
-    cur = np.zeros((H, W), dtype=np.int64)
-    cur[: nby * B, : nbx * B] = ref[sy, sx].astype(np.int64)
+    cur = ref[sy, sx].astype(np.int64)[:H, :W]
     if wl.noise > 0:
         cur += rng.integers(-wl.noise, wl.noise + 1, size=(H, W), dtype=np.int64)
     cur = np.clip(cur, 0, 255).astype(np.uint8)

@@ -223,6 +223,47 @@ def test_sad_cfg0(mb):
     _sad_check(mb, cur, ref, 8, 4)
 
 
+RAGGED_SAD_CASES = [
+    # H   W   B  R  tile      kernel                       (frames the block does not divide)
+    (30, 29, 8, 2, None, "merit_sad_generic"),              # both extents ragged, W not a multiple of 4
+    (27, 40, 8, 3, None, "merit_sad_generic"),              # ragged height only
+    (32, 44, 8, 8, None, "merit_sad_generic"),              # ragged width keeps the row-scan kernels out
+    (5, 7, 8, 1, None, "merit_sad_generic"),                # frame smaller than one block
+    (36, 64, 8, 8, None, "merit_sad_rowscan_pair<8,8>"),    # last block row: 4 of 8 rows inside
+    (41, 96, 16, 16, None, "merit_sad_rowscan_pair<16,16>"),  # last block row: 9 of 16 rows inside
+    (41, 96, 16, 16, (0, 4), "merit_sad_rowscan16<16>"),
+    (56, 80, 16, 32, None, "merit_sad_rowscan16<32>"),
+]
+
+
+@pytest.mark.parametrize("H,W,B,R,tile,kernel", RAGGED_SAD_CASES)
+def test_sad_frames_the_block_does_not_divide(mb, H, W, B, R, tile, kernel):
+    rng = np.random.default_rng(H * 1000 + W * 10 + R)
+    ref = rng.integers(0, 256, size=(H, W), dtype=np.uint8)
+    cur = np.roll(ref, (1, -2), axis=(0, 1))                 # a real minimum away from the origin
+    cur[::3] = rng.integers(0, 256, size=cur[::3].shape, dtype=np.uint8)
+    plan = mb.merit_plan_sad(H, W, B, R)
+    if tile is not None:
+        plan.set_tile(tile)
+    assert plan.launch_info()["kernel"] == kernel
+    _sad_check(mb, cur, ref, B, R, tile)
+    _sad_check(mb, cur & 3, ref & 3, B, R, tile)             # many ties
+
+
+def test_sad_1080p_workload(mb):
+    """Full HD at its real height (67.5 block rows): every block against the oracle."""
+    c = wl.CFG_ME_1080P
+    cur, ref, planted = wl.make_sad_frames(c)
+    plan = mb.merit_plan_sad(c.H, c.W, c.block, c.search)
+    assert plan.launch_info()["kernel"] == "merit_sad_rowscan16<32>" and plan.out_shape() == (68, 120)
+    sad, mv = mb.merit_sad_search(plan, dev(cur), dev(ref))
+    torch.cuda.synchronize()
+    sad, mv = sad.cpu().numpy(), mv.cpu().numpy()
+    assert np.all(sad[:67] == 0)                             # planted copies are exact inside the frame
+    osad, omv = oracle.sad_search(cur, ref, c.block, c.search)
+    assert np.array_equal(sad, osad) and np.array_equal(mv, omv)
+
+
 def test_sad_full_hd_workload(mb):
     c = wl.CFG3_ME_FHD
     cur, ref, planted = wl.make_sad_frames(c)
