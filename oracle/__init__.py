@@ -57,6 +57,8 @@ def _load():
     lib.ref_correlation.argtypes = [vp, vp, vp] + [c_int] * 6
     lib.ref_conv2d_dilated.restype = c_int
     lib.ref_conv2d_dilated.argtypes = [vp, vp, vp] + [c_int] * 14
+    lib.ref_sepfilter.restype = c_int
+    lib.ref_sepfilter.argtypes = [vp, vp, vp, vp] + [c_int] * 4
     lib.ref_conv2d_residual.restype = c_int
     lib.ref_conv2d_residual.argtypes = [vp, vp, vp, vp] + [c_int] * 12
     lib.ref_pool2d.restype = c_int
@@ -204,6 +206,21 @@ def pool2d(x: np.ndarray, kernel=(3, 3), stride=(2, 2), pad=(1, 1), mode="max") 
                             {"max": 0, "avg": 1}[mode])
     if rc != 0:
         raise ValueError("ref_pool2d: bad shape")
+    return y
+
+
+def sepfilter(x: np.ndarray, kx: np.ndarray, ky: np.ndarray) -> np.ndarray:
+    """Separable filter: x fp32 [N,H,W], kx (along W) and ky (along H) fp32 [k] -> fp32 [N,H,W];
+    window offset -k//2, no flip, coordinates clamped to the image."""
+    x = _c(x, np.float32)
+    kx = _c(kx, np.float32)
+    ky = _c(ky, np.float32)
+    if x.ndim != 3 or kx.ndim != 1 or ky.shape != kx.shape:
+        raise ValueError("sepfilter: x must be [N,H,W], kx and ky vectors of one length")
+    N, H, W = x.shape
+    y = np.empty_like(x)
+    if _load().ref_sepfilter(_ptr(x), _ptr(kx), _ptr(ky), _ptr(y), N, H, W, kx.shape[0]) != 0:
+        raise ValueError("ref_sepfilter: bad shape")
     return y
 
 

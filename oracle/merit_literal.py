@@ -212,3 +212,27 @@ def sad_search(cur: np.ndarray, ref: np.ndarray, block: int, search: int):
     sad = l1[np.arange(nby * nbx), idx].astype(np.int32).reshape(nby, nbx)
     mv = np.stack([idx // n - search, idx % n - search], axis=1).astype(np.int32)
     return sad, mv.reshape(nby, nbx, 2)
+
+
+# --------------------------------------------------------------------------
+# separable filter: two 1-D ranged inner products in a row
+# --------------------------------------------------------------------------
+def sepfilter_desc(N, H, W, k):
+    """Row pass k = (n, p1, p2 | a2) on the image, column pass k = (n, p1, p2 | a1) on its
+    result; window offset -k//2 as in the bilateral-filter call of Section VI-A."""
+    ranges = (N, H, W, k)
+    t_row = Transform(axis=(0, 1, 2, 2), stride=(1, 1, 1, 1), offset=(0, 0, 0, -(k // 2)))
+    t_col = Transform(axis=(0, 1, 2, 1), stride=(1, 1, 1, 1), offset=(0, 0, 0, -(k // 2)))
+    t_ker = Transform(axis=(UNUSED, UNUSED, UNUSED, 0), stride=(0, 0, 0, 1), offset=(0, 0, 0, 0))
+    return ranges, 3, t_row, t_col, t_ker
+
+
+def sepfilter(x: np.ndarray, kx: np.ndarray, ky: np.ndarray) -> np.ndarray:
+    N, H, W = x.shape
+    ranges, n_par, t_row, t_col, t_ker = sepfilter_desc(N, H, W, len(kx))
+    MA, _ = transform(x.astype(np.float64), ranges, t_row, n_par, "clamp")
+    MB, _ = transform(kx.astype(np.float64), ranges, t_ker, n_par, "clamp")
+    t = np.einsum("pa,pa->p", MA, MB).reshape(N, H, W)
+    MA, _ = transform(t, ranges, t_col, n_par, "clamp")
+    MB, _ = transform(ky.astype(np.float64), ranges, t_ker, n_par, "clamp")
+    return np.einsum("pa,pa->p", MA, MB).reshape(N, H, W).astype(np.float32)

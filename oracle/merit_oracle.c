@@ -378,6 +378,43 @@ int ref_sad_surface(const uint8_t *cur, const uint8_t *ref, int32_t *surface,
     return 0;
 }
 
+/* ------------------------------------------------------------------------ */
+/* Separable filter, fp32                                                     */
+/* ------------------------------------------------------------------------ */
+/*
+ * Two 1-D ranged inner products in a row (dot product, Section III-B Eq. 3), the window
+ * centred as in the bilateral-filter call of Section VI-A (offset -k/2 on the window index):
+ *   t[n,p1,p2] = sum_{a2<k} kx[a2] * x[n, p1, p2 + a2 - k/2]
+ *   y[n,p1,p2] = sum_{a1<k} ky[a1] * t[n, p1 + a1 - k/2, p2]
+ * k/2 is the integer quotient (an even k reaches one tap further back than forward); the
+ * kernels are not flipped; coordinates outside the image are clamped to the nearest edge
+ * pixel.  x, y: [N,H,W] float; kx, ky: [k] float.  Accumulated in double without rounding t,
+ * rounded once to float.  Returns 0, or -1 on a bad shape.
+ */
+int ref_sepfilter(const float *x, const float *kx, const float *ky, float *y, int N, int H, int W, int k)
+{
+    if (N < 0 || H <= 0 || W <= 0 || k <= 0) return -1;
+    const int c = k / 2;
+    long row;
+#pragma omp parallel for schedule(static)
+    for (row = 0; row < (long)N * H; ++row) {
+        const int n = (int)(row / H), p1 = (int)(row % H);
+        const float *img = x + (size_t)n * H * W;
+        for (int p2 = 0; p2 < W; ++p2) {
+            double acc = 0.0;
+            for (int a1 = 0; a1 < k; ++a1) {
+                const int yy = clampi(p1 + a1 - c, 0, H - 1);
+                double t = 0.0;
+                for (int a2 = 0; a2 < k; ++a2)
+                    t += (double)kx[a2] * (double)img[(size_t)yy * W + clampi(p2 + a2 - c, 0, W - 1)];
+                acc += (double)ky[a1] * t;
+            }
+            y[(size_t)row * W + p2] = (float)acc;
+        }
+    }
+    return 0;
+}
+
 /* Number of threads the parallel loops above will use. */
 int ref_num_threads(void)
 {
