@@ -198,6 +198,30 @@ def bench_depthwise(torch, mb, wl, cfg, steps, warmup, nsets):
     }
 
 
+def bench_sepfilter(torch, mb, wl, cfg, steps, warmup, nsets):
+    x, kx, ky = wl.make_sepfilter_inputs(cfg)
+    x0 = torch.from_numpy(x).to("cuda:0")
+    dkx, dky = torch.from_numpy(kx).to("cuda:0"), torch.from_numpy(ky).to("cuda:0")
+    plan = mb.merit_plan_sepfilter(cfg.N, cfg.H, cfg.W, cfg.k)
+    alg_bytes = 2 * x.nbytes + 2 * kx.nbytes
+    ns = nsets if alg_bytes > (8 << 20) else 1
+    xs = [x0] + [x0.roll(i, dims=0).contiguous() for i in range(1, ns)]
+    ys = [torch.empty_like(x0) for _ in range(ns)]
+    calls = [mb.bind_sepfilter(plan, xs[i], dkx, dky, ys[i]) for i in range(ns)]
+    wall, ev_ms = timed_region(torch, lambda i: calls[i % ns](), steps, warmup)
+    t = ev_ms * 1e-3 / steps
+    fmas = 2.0 * cfg.k * cfg.N * cfg.H * cfg.W          # k per pass and pixel
+    return {
+        "workload": cfg.name, "kernel": plan.launch_info()["kernel"], "avg_launch_us": t * 1e6,
+        "out_elems_per_s": cfg.N * cfg.H * cfg.W / t,
+        "achieved_hbm_gbs": alg_bytes / t / 1e9, "hbm_frac": alg_bytes / t / 1e9 / HBM_PEAK_GBS,
+        "achieved_fp32_tflops": 2 * fmas / t / 1e12,
+        "rotating_sets": ns,
+        "roofline": {"bound": "hbm", "achieved": alg_bytes / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": alg_bytes / t / 1e9 / HBM_PEAK_GBS},
+    }
+
+
 def bench_corr(torch, mb, wl, cfg, steps, warmup):
     x1, x2 = wl.make_correlation_inputs(cfg)
     d1, d2 = torch.from_numpy(x1).to("cuda:0"), torch.from_numpy(x2).to("cuda:0")
@@ -314,6 +338,8 @@ def main():
             bench_conv(torch, mb, wl, wl.CFG_DILATED, k, w, args.sets),
             bench_corr(torch, mb, wl, wl.CFG_CORRELATION, k, w),
             bench_depthwise(torch, mb, wl, wl.CFG_DEPTHWISE, k, w, args.sets),
+            bench_sepfilter(torch, mb, wl, wl.CFG_SEP_K3, k, w, args.sets),
+            bench_sepfilter(torch, mb, wl, wl.CFG_SEP_K30, max(10, k // 2), w, args.sets),
         ]
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(wl)

@@ -69,7 +69,13 @@ typedef enum {
      * one rounding.  The descriptor is the convolution's; the third tensor is an argument of
      * merit_conv2d_residual. */
     MERIT_OP_CONV_DOT_ADD = 9,
-    MERIT_OP_CONV_DOT_ADD_RELU = 10
+    MERIT_OP_CONV_DOT_ADD_RELU = 10,
+    /* separable filter: a k x k window whose taps are the outer product of two vectors, run as
+     * two 1-D dot-product passes (along the width, then along the height).  Descriptor:
+     * k = (n, p1, p2 | a1, a2), a = the image [N,H,W] with the window indices on axes 1 and 2
+     * at offset -k/2 (the bilateral-filter call of Section VI-A); b = the vector of length k
+     * indexed by a2; the vector indexed by a1 is a further argument of merit_sepfilter. */
+    MERIT_OP_SEPFILTER_DOT = 11
 } merit_op;
 
 typedef enum { MERIT_U8 = 0, MERIT_F16 = 1, MERIT_F32 = 2 } merit_dtype;
@@ -177,6 +183,11 @@ merit_status merit_plan_conv2d_residual(int N, int Cin, int H, int W, int Cout, 
                                         int sh, int sw, int ph, int pw, int relu, merit_plan **out);
 merit_status merit_plan_pool2d(int N, int C, int H, int W, int kh, int kw,
                                int sh, int sw, int ph, int pw, int is_avg, merit_plan **out);
+/* Separable filter (a row of the paper's GPU speed-up table, Section VI-B) on N images of
+ * H x W fp32 pixels with two tap vectors of length k <= 64:
+ *   y[n,p1,p2] = sum_{a1,a2<k} ky[a1] kx[a2] x[n, p1 + a1 - k/2, p2 + a2 - k/2],
+ * taps not flipped, coordinates clamped to the image (border replicated). */
+merit_status merit_plan_sepfilter(int N, int H, int W, int k, merit_plan **out);
 merit_status merit_plan_sad(int H, int W, int block, int range, merit_plan **out);
 /* Depthwise convolution (the depthwise row of the paper's table of further workloads):
  * y[n,c,oy,ox] = sum_{ky,kx} x[n,c,oy*sh+ky-ph,ox*sw+kx-pw] * w[c,ky,kx]. */
@@ -207,7 +218,8 @@ merit_status merit_plan_launch_info(const merit_plan *plan, merit_launch_info *o
  * where 8 x 64 means 4 multiplying + 4 data-moving wavefronts (256 pixels per
  * workgroup) and every other pair tile[2]*tile[3] pixels; block matching
  * tile[1] = blocks per workgroup (1, 4 or 8; a value the shape has no kernel for
- * keeps the library's choice).  On error the plan is unchanged.  Not safe to
+ * keeps the library's choice); separable filter tile[1] = output rows per workgroup
+ * (32 or 64).  On error the plan is unchanged.  Not safe to
  * call while another thread launches with the same plan. */
 merit_status merit_plan_set_tile(merit_plan *plan, const int64_t tile[MERIT_MAX_INDEX]);
 
@@ -232,6 +244,12 @@ merit_status merit_conv2d_residual(const merit_plan *plan, const void *x_f16, co
 /* x_f32: [N,C,H,W]; y_f32: [N,C,OH,OW].  max: exact.  avg: fp32 sum in window
  * scan order divided by the in-range count. */
 merit_status merit_pool2d(const merit_plan *plan, const void *x_f32, void *y_f32, void *hip_stream);
+
+/* x_f32, y_f32: [N,H,W]; kx_f32 (taps along the width), ky_f32 (along the height): [k], device
+ * memory.  fp32 multiply-adds in tap order, the row pass first; its result stays on chip in
+ * fp32.  y must not overlap x. */
+merit_status merit_sepfilter(const merit_plan *plan, const void *x_f32, const void *kx_f32,
+                             const void *ky_f32, void *y_f32, void *hip_stream);
 
 /* cur_u8, ref_u8: [H,W] frames.  sad_i32: [nby*nbx] minimum SAD per block;
  * mv_i32: [nby*nbx][2] = (dy,dx) of the minimiser with the lowest raster index

@@ -160,6 +160,21 @@ struct DwParams {
 hipError_t launch_dwconv(const DwParams &p, const void *x, const void *w, void *y, hipStream_t s);
 const char *dwconv_kernel_name(const DwParams &p);
 
+// ---- separable filter --------------------------------------------------------------
+struct SepParams {
+    int N, H, W, k;
+    int c;                 // window offset: tap a reads coordinate p + a - c, c = k/2
+    int G;                 // tap groups of 4 (k rounded up)
+    int TH;                // output rows per workgroup (32 or 64); 64 columns
+    int tiles_y, tiles_x;
+    int PI, PM;            // LDS row pitch (floats) of the staged input and of the row-pass result
+    int lds_bytes;
+    FastDiv div_tiles_x, div_tiles_y, div_pi, div_rh;
+};
+
+hipError_t launch_sepfilter(const SepParams &p, const float *x, const float *kx, const float *ky, float *y,
+                            hipStream_t s);
+
 hipError_t launch_correlation(const CorrParams &p, const void *x1, const void *x2, void *y, hipStream_t s);
 size_t corr_lds_bytes(const CorrParams &p);
 
@@ -175,5 +190,6 @@ struct merit_plan {
     merit::ConvParams conv;
     merit::CorrParams corr;
     merit::DwParams dw;
+    merit::SepParams sep;
     merit_launch_info info;
 };

@@ -252,3 +252,33 @@ def make_depthwise_inputs(wl: DepthwiseWorkload, seed: int | None = None):
     x = rng.standard_normal(size=(wl.N, wl.C, wl.H, wl.W), dtype=np.float32)
     w = rng.standard_normal(size=(wl.C, wl.kh, wl.kw), dtype=np.float32) / np.float32(np.sqrt(wl.kh * wl.kw))
     return x.astype(np.float16), w.astype(np.float16)
+
+
+# --------------------------------------------------------------------------
+# separable filter (a row of the paper's GPU speed-up table: k = 3 and k = 30; the image
+# size is not given there: four full-HD fp32 planes here, normalised Gaussian taps)
+# --------------------------------------------------------------------------
+@dataclass(frozen=True)
+class SepWorkload:
+    name: str
+    N: int
+    H: int
+    W: int
+    k: int
+
+
+CFG_SEP_K3 = SepWorkload("sepfilter_4x1080x1920_k3", 4, 1080, 1920, 3)
+CFG_SEP_K30 = SepWorkload("sepfilter_4x1080x1920_k30", 4, 1080, 1920, 30)
+
+
+def make_sepfilter_inputs(wl: SepWorkload, seed: int | None = None, N: int | None = None):
+    """(x fp32 [N,H,W] uniform in [0,255], kx, ky fp32 [k]: Gaussians of sigma k/6 and k/4, sum 1)."""
+    rng = np.random.default_rng(BASE_SEED + 9 if seed is None else seed)
+    n = wl.N if N is None else N
+    x = rng.uniform(0.0, 255.0, size=(n, wl.H, wl.W)).astype(np.float32)
+    a = np.arange(wl.k, dtype=np.float64) - wl.k // 2
+    taps = []
+    for sigma in (max(wl.k / 6.0, 0.5), max(wl.k / 4.0, 0.5)):
+        g = np.exp(-0.5 * (a / sigma) ** 2)
+        taps.append((g / g.sum()).astype(np.float32))
+    return x, taps[0], taps[1]

@@ -138,6 +138,34 @@ def test_residual_plan():
     assert mb.merit_plan_create(res.desc()).desc().op == mb.MERIT_OP_CONV_DOT_ADD_RELU
 
 
+def test_sepfilter_plan():
+    plan = mb.merit_plan_sepfilter(4, 1080, 1920, 30)
+    d = plan.desc()
+    ranges, n_par, t_row, t_col, t_ker = lit.sepfilter_desc(4, 1080, 1920, 30)
+    assert (d.op, d.n_par, d.n_acc, d.dtype, d.pad) == (mb.MERIT_OP_SEPFILTER_DOT, 3, 2, mb.MERIT_F32,
+                                                      mb.MERIT_PAD_CLAMP)
+    assert tuple(d.range[:5]) == (4, 1080, 1920, 30, 30) and plan.out_shape() == (4, 1080, 1920)
+    # the window indices sit on the image axes at offset -k/2, as in the two 1-D passes
+    assert (d.a.axis[3], d.a.offset[3]) == (t_col.axis[3], t_col.offset[3]) == (1, -15)
+    assert (d.a.axis[4], d.a.offset[4]) == (t_row.axis[3], t_row.offset[3]) == (2, -15)
+    li = plan.launch_info()
+    assert li["kernel"] == "merit_sepfilter_tile" and li["tile"][1:3] == (64, 64)
+    assert li["grid"][0] == 4 * 17 * 30 and li["lds_bytes"] <= 160 * 1024
+    # Eq. 9: a 64 x 64 tile of outputs with a 30 x 30 window covers 93 x 93 pixels
+    assert plan.footprint(0, (1, 64, 64, 30, 30)) == (1, 93, 93)
+    small = mb.merit_plan_sepfilter(1, 40, 70, 3)
+    assert small.launch_info()["tile"][1] == 32
+    small.set_tile((0, 64))
+    assert small.launch_info()["tile"][1] == 64
+    with pytest.raises(mb.MeritError):
+        small.set_tile((0, 48))
+    with pytest.raises(mb.MeritError) as e:
+        mb.merit_plan_sepfilter(1, 40, 70, 65)
+    assert e.value.status == mb.MERIT_ERR_UNSUPPORTED
+    with pytest.raises(mb.MeritError):
+        mb.merit_plan_sepfilter(1, 0, 70, 3)
+
+
 def test_depthwise_plan():
     plan = mb.merit_plan_conv2d_depthwise(32, 32, 64, 64, 3, 3, 1, 1, 1, 1)
     d = plan.desc()

@@ -776,3 +776,73 @@ def test_misaligned_pointer_is_rejected(mb):
     with pytest.raises(mb.MeritError) as e:
         mb.merit_pool2d(plan, x)
     assert e.value.status == mb.MERIT_ERR_ALIGNMENT
+
+
+# -------------------------------------------------- separable filter
+SEP_CASES = [
+    # N  H    W    k  tile rows
+    (1, 40, 70, 3, None),        # ragged tiles in both directions
+    (2, 33, 129, 5, None),       # one column past two tiles
+    (1, 64, 64, 1, None),        # single tap: a scaled copy
+    (1, 17, 23, 4, None),        # even window: one tap further back than forward
+    (1, 100, 130, 30, None),     # the long window of the paper's table, 64-row tiles
+    (1, 100, 130, 30, 32),       # the same on 32-row tiles
+    (1, 9, 9, 64, None),         # window much larger than the image: everything clamps
+    (3, 32, 64, 9, 64),          # tile taller than the image
+]
+
+
+def _sep_tol(x, kx, ky):
+    # fp32 multiply-adds, 2k of them per output, each rounding at most 2^-24 of the running
+    # magnitude, which sum|kx| sum|ky| max|x| bounds
+    return 1e-5 * float(np.abs(kx).sum() * np.abs(ky).sum() * np.abs(x).max()) + 1e-30
+
+
+@pytest.mark.parametrize("N,H,W,k,tile", SEP_CASES)
+def test_sepfilter(mb, N, H, W, k, tile):
+    rng = np.random.default_rng(N * 1000 + H * 10 + k)
+    x = rng.standard_normal((N, H, W)).astype(np.float32)
+    kx = rng.standard_normal(k).astype(np.float32)
+    ky = rng.standard_normal(k).astype(np.float32)
+    plan = mb.merit_plan_sepfilter(N, H, W, k)
+    if tile is not None:
+        plan.set_tile((0, tile))
+    print("sepfilter", (N, H, W, k), plan.launch_info(), flush=True)
+    buf, y, p = guarded_empty((N, H, W), torch.float32, 777.0)
+    mb.merit_sepfilter(plan, dev(x), dev(kx), dev(ky), y)
+    torch.cuda.synchronize()
+    check_canary(buf, p, 777.0)
+    got = y.cpu().numpy().astype(np.float64)
+    ref = oracle.sepfilter(x, kx, ky).astype(np.float64)
+    err = np.abs(got - ref)
+    assert np.all(err <= _sep_tol(x, kx, ky)), f"max err {err.max()} at {np.unravel_index(err.argmax(), err.shape)}"
+
+
+def test_sepfilter_impulse_is_exact(mb):
+    """Small-integer taps and one impulse: every product is exact in fp32, so the result must
+    equal the oracle bit for bit, and shows the unflipped, -k/2-centred window."""
+    H, W, k = 70, 75, 6
+    x = np.zeros((1, H, W), np.float32)
+    x[0, 33, 64] = 1.0                                       # next to a tile boundary
+    x[0, 0, 0] = 2.0                                         # in the corner: clamped copies pile up
+    kx = (np.arange(k) + 1).astype(np.float32)
+    ky = (10 * (np.arange(k) + 1)).astype(np.float32)
+    y = mb.merit_sepfilter(mb.merit_plan_sepfilter(1, H, W, k), dev(x), dev(kx), dev(ky)).cpu().numpy()
+    assert np.array_equal(y, oracle.sepfilter(x, kx, ky))
+    assert y[0, 33 - 0 + 3, 64 - 5 + 3] == ky[0] * kx[5]
+
+
+def test_sepfilter_workloads_sampled(mb):
+    """Full-size launches (k = 3 and k = 30); the oracle checks one image's band of rows that
+    spans a tile boundary and both image edges."""
+    for c in (wl.CFG_SEP_K3, wl.CFG_SEP_K30):
+        x, kx, ky = wl.make_sepfilter_inputs(c)
+        plan = mb.merit_plan_sepfilter(c.N, c.H, c.W, c.k)
+        y = mb.merit_sepfilter(plan, dev(x), dev(kx), dev(ky))
+        torch.cuda.synchronize()
+        n = 2
+        ref = oracle.sepfilter(x[n:n + 1], kx, ky)[0].astype(np.float64)
+        got = y[n].cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(got - ref) <= _sep_tol(x, kx, ky))
+        # a normalised positive window keeps the range and (up to the borders) the mean
+        assert got.min() >= 0.0 and got.max() <= 255.0 + 1e-3
