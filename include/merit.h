@@ -184,7 +184,7 @@ merit_status merit_plan_conv2d_residual(int N, int Cin, int H, int W, int Cout, 
 merit_status merit_plan_pool2d(int N, int C, int H, int W, int kh, int kw,
                                int sh, int sw, int ph, int pw, int is_avg, merit_plan **out);
 /* Separable filter (a row of the paper's GPU speed-up table, Section VI-B) on N images of
- * H x W fp32 pixels with two tap vectors of length k <= 64:
+ * H x W fp32 pixels with two tap vectors of length k <= 32:
  *   y[n,p1,p2] = sum_{a1,a2<k} ky[a1] kx[a2] x[n, p1 + a1 - k/2, p2 + a2 - k/2],
  * taps not flipped, coordinates clamped to the image (border replicated). */
 merit_status merit_plan_sepfilter(int N, int H, int W, int k, merit_plan **out);
@@ -218,8 +218,9 @@ merit_status merit_plan_launch_info(const merit_plan *plan, merit_launch_info *o
  * where 8 x 64 means 4 multiplying + 4 data-moving wavefronts (256 pixels per
  * workgroup) and every other pair tile[2]*tile[3] pixels; block matching
  * tile[1] = blocks per workgroup (1, 4 or 8; a value the shape has no kernel for
- * keeps the library's choice); separable filter tile[1] = output rows per workgroup
- * (32 or 64).  On error the plan is unchanged.  Not safe to
+ * keeps the library's choice); separable filter tile[1] = staged rows per workgroup
+ * at most (output rows = that minus k - 1, rounded down to a multiple of 4).  On error
+ * the plan is unchanged.  Not safe to
  * call while another thread launches with the same plan. */
 merit_status merit_plan_set_tile(merit_plan *plan, const int64_t tile[MERIT_MAX_INDEX]);
 

@@ -164,12 +164,12 @@ const char *dwconv_kernel_name(const DwParams &p);
 struct SepParams {
     int N, H, W, k;
     int c;                 // window offset: tap a reads coordinate p + a - c, c = k/2
-    int G;                 // tap groups of 4 (k rounded up)
-    int TH;                // output rows per workgroup (32 or 64); 64 columns
+    int c4;                // c rounded up to 4: the staged columns start at x0 - c4
+    int TH;                // output rows per workgroup (a multiple of 4); 64 columns
     int tiles_y, tiles_x;
     int PI, PM;            // LDS row pitch (floats) of the staged input and of the row-pass result
     int lds_bytes;
-    FastDiv div_tiles_x, div_tiles_y, div_pi, div_rh;
+    FastDiv div_tiles_x, div_tiles_y, div_rh;
 };
 
 hipError_t launch_sepfilter(const SepParams &p, const float *x, const float *kx, const float *ky, float *y,

@@ -277,33 +277,35 @@ merit_status derive_sep(merit_plan *pl)
     if (!operand_is(d.b, 5, axis_k, stride_k, offset_k)) return MERIT_ERR_UNSUPPORTED;
     if (d.range[0] != N || d.range[1] != H || d.range[2] != W || d.range[3] != k || d.range[4] != k)
         return MERIT_ERR_SHAPE;
-    if (k > 64 || H * W >= INT_LIMIT || N * H * W >= (1ll << 40)) return MERIT_ERR_UNSUPPORTED;
+    if (k > 32 || H * W >= INT_LIMIT || N * H * W >= (1ll << 40)) return MERIT_ERR_UNSUPPORTED;
 
     SepParams &p = pl->sep;
     p.N = (int)N; p.H = (int)H; p.W = (int)W; p.k = (int)k; p.c = (int)c;
-    p.G = (int)cdiv(k, 4);
-    const int64_t kpad = 4 * p.G;
-    // taller tiles for long windows: the row pass also runs on the k-1 halo rows of a tile
-    int64_t TH = kpad <= 8 ? 32 : 64;
-    if (pl->tile_req[1] > 0) {
-        if (pl->tile_req[1] != 32 && pl->tile_req[1] != 64) return MERIT_ERR_UNSUPPORTED;
-        TH = pl->tile_req[1];
+    p.c4 = (int)round_up(c, 4);
+    // staged rows RH = TH + k - 1: about 64, more for long windows (whose halo rows the row pass
+    // also computes); TH a multiple of 4 (the column pass works on 4 x 4 patches)
+    int64_t rows = k <= 16 ? 64 : (k <= 32 ? 96 : 128);
+    if (pl->tile_req[1] > 0) {                            // staged rows per workgroup, at most
+        if (pl->tile_req[1] < k + 3 || pl->tile_req[1] > 256) return MERIT_ERR_UNSUPPORTED;
+        rows = pl->tile_req[1];
     }
+    const int64_t TH = (rows - k + 1) / 4 * 4;
+    const int64_t RH = TH + k - 1;
     p.TH = (int)TH;
     p.tiles_y = (int)cdiv(H, TH);
     p.tiles_x = (int)cdiv(W, 64);
-    p.PI = (int)(round_up(64 + kpad, 8) + 4);            // pitches of 4 mod 8 floats: see the kernel
+    // a row-pass unit reads ceil((d + 8 + k - 1) / 4) 16-byte groups from column 8 cg on
+    const int64_t nwr = cdiv((p.c4 - c) + 8 + k - 1, 4);
+    p.PI = (int)(round_up(56 + 4 * nwr, 8) + 4);          // pitches of 4 mod 8 floats: see the kernel
     p.PM = 64 + 4;
-    const int64_t RH = TH + kpad;
-    p.lds_bytes = (int)((RH * (p.PI + p.PM) + 2 * kpad) * 4);
+    p.lds_bytes = (int)((RH * (p.PI + p.PM) + 8 * cdiv(k, 4)) * 4);
     if (p.lds_bytes > LDS_LIMIT) return MERIT_ERR_UNSUPPORTED;
     const int64_t grid = N * p.tiles_y * p.tiles_x;
     if (grid >= INT_LIMIT || !fastdiv_ok(grid, p.tiles_x) || !fastdiv_ok(N * p.tiles_y, p.tiles_y) ||
-        !fastdiv_ok(RH * p.PI, p.PI) || !fastdiv_ok(8 * RH, RH))
+        !fastdiv_ok(8 * RH, RH))
         return MERIT_ERR_UNSUPPORTED;
     p.div_tiles_x = make_fastdiv((uint32_t)p.tiles_x);
     p.div_tiles_y = make_fastdiv((uint32_t)p.tiles_y);
-    p.div_pi = make_fastdiv((uint32_t)p.PI);
     p.div_rh = make_fastdiv((uint32_t)RH);
 
     pl->out_ndim = 3;

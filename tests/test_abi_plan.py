@@ -153,14 +153,17 @@ def test_sepfilter_plan():
     assert li["grid"][0] == 4 * 17 * 30 and li["lds_bytes"] <= 160 * 1024
     # Eq. 9: a 64 x 64 tile of outputs with a 30 x 30 window covers 93 x 93 pixels
     assert plan.footprint(0, (1, 64, 64, 30, 30)) == (1, 93, 93)
+    # output rows: a multiple of 4 that keeps the staged rows (output rows + k - 1) within the request
     small = mb.merit_plan_sepfilter(1, 40, 70, 3)
-    assert small.launch_info()["tile"][1] == 32
-    small.set_tile((0, 64))
-    assert small.launch_info()["tile"][1] == 64
+    assert small.launch_info()["tile"][1] == 60
+    small.set_tile((0, 32))
+    assert small.launch_info()["tile"][1] == 28
     with pytest.raises(mb.MeritError):
-        small.set_tile((0, 48))
+        small.set_tile((0, 5))                              # no room for four output rows
+    with pytest.raises(mb.MeritError):
+        plan.set_tile((0, 32))                              # not above the 30-tap window
     with pytest.raises(mb.MeritError) as e:
-        mb.merit_plan_sepfilter(1, 40, 70, 65)
+        mb.merit_plan_sepfilter(1, 40, 70, 33)
     assert e.value.status == mb.MERIT_ERR_UNSUPPORTED
     with pytest.raises(mb.MeritError):
         mb.merit_plan_sepfilter(1, 0, 70, 3)

@@ -780,15 +780,16 @@ def test_misaligned_pointer_is_rejected(mb):
 
 # -------------------------------------------------- separable filter
 SEP_CASES = [
-    # N  H    W    k  tile rows
-    (1, 40, 70, 3, None),        # ragged tiles in both directions
-    (2, 33, 129, 5, None),       # one column past two tiles
+    # N  H    W    k  staged rows
+    (1, 40, 70, 3, 32),          # ragged tiles in both directions
+    (2, 133, 129, 5, None),      # one column past two tiles, three tiles down
     (1, 64, 64, 1, None),        # single tap: a scaled copy
     (1, 17, 23, 4, None),        # even window: one tap further back than forward
     (1, 100, 130, 30, None),     # the long window of the paper's table, 64-row tiles
-    (1, 100, 130, 30, 32),       # the same on 32-row tiles
-    (1, 9, 9, 64, None),         # window much larger than the image: everything clamps
-    (3, 32, 64, 9, 64),          # tile taller than the image
+    (1, 100, 130, 30, 64),       # the same on 32-row tiles
+    (1, 9, 9, 32, None),         # window much larger than the image: everything clamps
+    (2, 50, 66, 7, None),        # width not a multiple of 4: scalar staging and stores
+    (3, 32, 64, 9, 128),         # tile taller than the image
 ]
 
 
