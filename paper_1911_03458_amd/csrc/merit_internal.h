@@ -169,6 +169,7 @@ struct SepParams {
     int tiles_y, tiles_x;
     int PI, PM;            // LDS row pitch (floats) of the staged input and of the row-pass result
     int lds_bytes;
+    int wg_per_cu;         // persistent workgroups per compute unit
     FastDiv div_tiles_x, div_tiles_y, div_rh;
 };
 

@@ -284,9 +284,9 @@ merit_status derive_sep(merit_plan *pl)
     p.c4 = (int)round_up(c, 4);
     // staged rows RH = TH + k - 1: about 64, more for long windows (whose halo rows the row pass
     // also computes); TH a multiple of 4 (the column pass works on 4 x 4 patches)
-    int64_t rows = k <= 16 ? 64 : (k <= 32 ? 96 : 128);
+    int64_t rows = k <= 16 ? 64 : 96;                     // the kernel keeps rows / 32 row-pass units per thread
     if (pl->tile_req[1] > 0) {                            // staged rows per workgroup, at most
-        if (pl->tile_req[1] < k + 3 || pl->tile_req[1] > 256) return MERIT_ERR_UNSUPPORTED;
+        if (pl->tile_req[1] < k + 3 || pl->tile_req[1] > rows) return MERIT_ERR_UNSUPPORTED;
         rows = pl->tile_req[1];
     }
     const int64_t TH = (rows - k + 1) / 4 * 4;
@@ -297,8 +297,8 @@ merit_status derive_sep(merit_plan *pl)
     // a row-pass unit reads ceil((d + 8 + k - 1) / 4) 16-byte groups from column 8 cg on
     const int64_t nwr = cdiv((p.c4 - c) + 8 + k - 1, 4);
     p.PI = (int)(round_up(56 + 4 * nwr, 8) + 4);          // pitches of 4 mod 8 floats: see the kernel
-    p.PM = 64 + 4;
-    p.lds_bytes = (int)((RH * (p.PI + p.PM) + 8 * cdiv(k, 4)) * 4);
+    p.PM = p.PI;                                          // the row-pass result replaces the staged input
+    p.lds_bytes = (int)((RH * p.PI + 8 * cdiv(k, 4)) * 4);
     if (p.lds_bytes > LDS_LIMIT) return MERIT_ERR_UNSUPPORTED;
     const int64_t grid = N * p.tiles_y * p.tiles_x;
     if (grid >= INT_LIMIT || !fastdiv_ok(grid, p.tiles_x) || !fastdiv_ok(N * p.tiles_y, p.tiles_y) ||
@@ -312,7 +312,10 @@ merit_status derive_sep(merit_plan *pl)
     pl->out_shape[0] = N; pl->out_shape[1] = H; pl->out_shape[2] = W;
     merit_launch_info &li = pl->info;
     li.kernel = "merit_sepfilter_tile";
-    li.grid[0] = grid; li.grid[1] = 1; li.grid[2] = 1;
+    // persistent grid: the launcher sizes it from the device's CU count (256 on MI355X)
+    p.wg_per_cu = (int)(LDS_LIMIT / p.lds_bytes);
+    if (p.wg_per_cu > 8) p.wg_per_cu = 8;
+    li.grid[0] = grid < 256 * p.wg_per_cu ? grid : 256 * p.wg_per_cu; li.grid[1] = 1; li.grid[2] = 1;
     li.block[0] = 256; li.block[1] = 1; li.block[2] = 1;
     li.lds_bytes = p.lds_bytes;
     li.tile[0] = 1; li.tile[1] = TH; li.tile[2] = 64; li.tile[3] = k; li.tile[4] = k;

@@ -150,7 +150,7 @@ def test_sepfilter_plan():
     assert (d.a.axis[4], d.a.offset[4]) == (t_row.axis[3], t_row.offset[3]) == (2, -15)
     li = plan.launch_info()
     assert li["kernel"] == "merit_sepfilter_tile" and li["tile"][1:3] == (64, 64)
-    assert li["grid"][0] == 4 * 17 * 30 and li["lds_bytes"] <= 160 * 1024
+    assert li["grid"][0] == 1024 and li["lds_bytes"] <= 160 * 1024       # persistent: 4 workgroups (37 KB each) per CU for 2040 tiles
     # Eq. 9: a 64 x 64 tile of outputs with a 30 x 30 window covers 93 x 93 pixels
     assert plan.footprint(0, (1, 64, 64, 30, 30)) == (1, 93, 93)
     # output rows: a multiple of 4 that keeps the staged rows (output rows + k - 1) within the request
