@@ -57,6 +57,8 @@ def _load():
     lib.ref_correlation.argtypes = [vp, vp, vp] + [c_int] * 6
     lib.ref_conv2d_dilated.restype = c_int
     lib.ref_conv2d_dilated.argtypes = [vp, vp, vp] + [c_int] * 14
+    lib.ref_bilateral.restype = c_int
+    lib.ref_bilateral.argtypes = [vp, vp, vp, vp] + [c_int] * 4 + [ctypes.c_double]
     lib.ref_sepfilter.restype = c_int
     lib.ref_sepfilter.argtypes = [vp, vp, vp, vp] + [c_int] * 4
     lib.ref_conv2d_residual.restype = c_int
@@ -221,6 +223,22 @@ def sepfilter(x: np.ndarray, kx: np.ndarray, ky: np.ndarray) -> np.ndarray:
     y = np.empty_like(x)
     if _load().ref_sepfilter(_ptr(x), _ptr(kx), _ptr(ky), _ptr(y), N, H, W, kx.shape[0]) != 0:
         raise ValueError("ref_sepfilter: bad shape")
+    return y
+
+
+def bilateral(x: np.ndarray, gx: np.ndarray, gy: np.ndarray, norm: float) -> np.ndarray:
+    """Bilateral filter (Section VI-A, Listings 2 and 3): x fp32 [N,H,W]; gx, gy: spatial lookup
+    tables fp32 [k]; norm: the range constant (weight exp(d*d*norm) for a pixel difference d).
+    Window offset -k//2, coordinates clamped to the image."""
+    x = _c(x, np.float32)
+    gx = _c(gx, np.float32)
+    gy = _c(gy, np.float32)
+    if x.ndim != 3 or gx.ndim != 1 or gy.shape != gx.shape:
+        raise ValueError("bilateral: x must be [N,H,W], gx and gy vectors of one length")
+    N, H, W = x.shape
+    y = np.empty_like(x)
+    if _load().ref_bilateral(_ptr(x), _ptr(gx), _ptr(gy), _ptr(y), N, H, W, gx.shape[0], float(norm)) != 0:
+        raise ValueError("ref_bilateral: bad shape")
     return y
 
 
