@@ -222,6 +222,29 @@ def bench_sepfilter(torch, mb, wl, cfg, steps, warmup, nsets):
     }
 
 
+def bench_bilateral(torch, mb, wl, cfg, steps, warmup):
+    x, g = wl.make_bilateral_inputs(cfg)
+    dx, dg = torch.from_numpy(x).to("cuda:0"), torch.from_numpy(g).to("cuda:0")
+    y = torch.empty_like(dx)
+    plan = mb.merit_plan_bilateral(cfg.N, cfg.H, cfg.W, cfg.k)
+    call = mb.bind_bilateral(plan, dx, dg, dg, cfg.norm, y)
+    wall, ev_ms = timed_region(torch, lambda i: call(), steps, warmup)
+    t = ev_ms * 1e-3 / steps
+    taps = float(cfg.N * cfg.H * cfg.W * cfg.k * cfg.k)
+    # per tap: subtract, two multiplies, the exponential (a quarter-rate instruction: 4 slots),
+    # multiply by the table entry, add, fused multiply-add = 10 issue slots of the plain fp32 rate
+    slots = 10.0 * taps
+    peak = VALU_PEAK_TOPS
+    alg_bytes = 2 * x.nbytes
+    return {
+        "workload": cfg.name, "kernel": plan.launch_info()["kernel"], "avg_launch_us": t * 1e6,
+        "out_elems_per_s": cfg.N * cfg.H * cfg.W / t, "taps_per_s": taps / t,
+        "achieved_hbm_gbs": alg_bytes / t / 1e9, "hbm_frac": alg_bytes / t / 1e9 / HBM_PEAK_GBS,
+        "roofline": {"bound": "alu", "achieved": slots / t / 1e12, "peak": peak,
+                     "unit": "T lane-ops/s (plain-rate fp32 issue slots)", "frac": slots / t / 1e12 / peak},
+    }
+
+
 def bench_corr(torch, mb, wl, cfg, steps, warmup):
     x1, x2 = wl.make_correlation_inputs(cfg)
     d1, d2 = torch.from_numpy(x1).to("cuda:0"), torch.from_numpy(x2).to("cuda:0")
@@ -340,6 +363,7 @@ def main():
             bench_depthwise(torch, mb, wl, wl.CFG_DEPTHWISE, k, w, args.sets),
             bench_sepfilter(torch, mb, wl, wl.CFG_SEP_K3, k, w, args.sets),
             bench_sepfilter(torch, mb, wl, wl.CFG_SEP_K30, max(10, k // 2), w, args.sets),
+            bench_bilateral(torch, mb, wl, wl.CFG_BILATERAL, max(10, k // 2), w),
         ]
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(wl)

@@ -75,7 +75,12 @@ typedef enum {
      * k = (n, p1, p2 | a1, a2), a = the image [N,H,W] with the window indices on axes 1 and 2
      * at offset -k/2 (the bilateral-filter call of Section VI-A); b = the vector of length k
      * indexed by a2; the vector indexed by a1 is a further argument of merit_sepfilter. */
-    MERIT_OP_SEPFILTER_DOT = 11
+    MERIT_OP_SEPFILTER_DOT = 11,
+    /* bilateral filter: the strategy class of Section VI-A (Listing 2) on the k x k window of
+     * Listing 3; descriptor as for the separable filter (image window at offset -k/2, b = the
+     * spatial lookup table indexed by a2; the table indexed by a1 and the range constant are
+     * arguments of merit_bilateral) */
+    MERIT_OP_BILATERAL = 12
 } merit_op;
 
 typedef enum { MERIT_U8 = 0, MERIT_F16 = 1, MERIT_F32 = 2 } merit_dtype;
@@ -188,6 +193,10 @@ merit_status merit_plan_pool2d(int N, int C, int H, int W, int kh, int kw,
  *   y[n,p1,p2] = sum_{a1,a2<k} ky[a1] kx[a2] x[n, p1 + a1 - k/2, p2 + a2 - k/2],
  * taps not flipped, coordinates clamped to the image (border replicated). */
 merit_status merit_plan_sepfilter(int N, int H, int W, int k, merit_plan **out);
+/* Bilateral filter (Section VI-A, Listings 2 and 3) on N images of H x W fp32 pixels, window
+ * k x k (k <= 32) at offset -k/2, coordinates clamped to the image:
+ *   y = sum w v / sum w,  w = exp((center - v)^2 * norm) * gy[a1] * gx[a2]. */
+merit_status merit_plan_bilateral(int N, int H, int W, int k, merit_plan **out);
 merit_status merit_plan_sad(int H, int W, int block, int range, merit_plan **out);
 /* Depthwise convolution (the depthwise row of the paper's table of further workloads):
  * y[n,c,oy,ox] = sum_{ky,kx} x[n,c,oy*sh+ky-ph,ox*sw+kx-pw] * w[c,ky,kx]. */
@@ -251,6 +260,13 @@ merit_status merit_pool2d(const merit_plan *plan, const void *x_f32, void *y_f32
  * fp32.  y must not overlap x. */
 merit_status merit_sepfilter(const merit_plan *plan, const void *x_f32, const void *kx_f32,
                              const void *ky_f32, void *y_f32, void *hip_stream);
+
+/* x_f32, y_f32: [N,H,W]; gx_f32, gy_f32: the spatial lookup tables [k] (device memory), all
+ * entries > 0; norm: the range constant of the strategy class (-1/(2 sigma_r^2) for a Gaussian
+ * range term), passed by value like the listing's Constant.  fp32 arithmetic, the exponential
+ * as 2^(d*d*norm*log2 e) with the hardware's base-2 exponential.  y must not overlap x. */
+merit_status merit_bilateral(const merit_plan *plan, const void *x_f32, const void *gx_f32,
+                             const void *gy_f32, double norm, void *y_f32, void *hip_stream);
 
 /* cur_u8, ref_u8: [H,W] frames.  sad_i32: [nby*nbx] minimum SAD per block;
  * mv_i32: [nby*nbx][2] = (dy,dx) of the minimiser with the lowest raster index

@@ -21,7 +21,8 @@ MERIT_OK = 0
  MERIT_ERR_ALIGNMENT, MERIT_ERR_HIP) = range(1, 7)
 (MERIT_OP_CONV_DOT, MERIT_OP_POOL_MAX, MERIT_OP_POOL_AVG, MERIT_OP_SAD_ARGMIN, MERIT_OP_CONV_DOT_RELU,
  MERIT_OP_CORR_DOT, MERIT_OP_DWCONV_DOT, MERIT_OP_CONV_DOT_POOLMAX, MERIT_OP_CONV_DOT_RELU_POOLMAX,
- MERIT_OP_CONV_DOT_ADD, MERIT_OP_CONV_DOT_ADD_RELU, MERIT_OP_SEPFILTER_DOT) = range(12)
+ MERIT_OP_CONV_DOT_ADD, MERIT_OP_CONV_DOT_ADD_RELU, MERIT_OP_SEPFILTER_DOT,
+ MERIT_OP_BILATERAL) = range(13)
 MERIT_U8, MERIT_F16, MERIT_F32 = range(3)
 MERIT_PAD_ZERO, MERIT_PAD_NEG_INF, MERIT_PAD_EXCLUDE, MERIT_PAD_CLAMP = range(4)
 
@@ -84,6 +85,8 @@ def lib():
     L.merit_plan_conv2d_residual.argtypes = [c_int] * 12 + [PP]
     L.merit_plan_sepfilter.argtypes = [c_int] * 4 + [PP]
     L.merit_sepfilter.argtypes = [P, P, P, P, P, P]
+    L.merit_plan_bilateral.argtypes = [c_int] * 4 + [PP]
+    L.merit_bilateral.argtypes = [P, P, P, P, ctypes.c_double, P, P]
     L.merit_conv2d_residual.argtypes = [P, P, P, P, P, P]
     L.merit_plan_pool2d.argtypes = [c_int] * 11 + [PP]
     L.merit_plan_sad.argtypes = [c_int] * 4 + [PP]
@@ -102,6 +105,7 @@ def lib():
     for name in ("merit_plan_create", "merit_plan_destroy", "merit_plan_conv2d", "merit_plan_conv2d_relu",
                  "merit_plan_conv2d_dilated", "merit_plan_conv2d_pool", "merit_plan_conv2d_residual",
                  "merit_conv2d_residual", "merit_plan_sepfilter", "merit_sepfilter",
+                 "merit_plan_bilateral", "merit_bilateral",
                  "merit_plan_pool2d",
                  "merit_plan_sad", "merit_plan_correlation", "merit_correlation", "merit_plan_conv2d_depthwise",
                  "merit_conv2d_depthwise", "merit_plan_get_desc", "merit_plan_out_shape", "merit_plan_footprint",
@@ -364,6 +368,36 @@ def merit_sepfilter(plan: Plan, x, kx, ky, y=None, stream=None):
 def bind_sepfilter(plan: Plan, x, kx, ky, y, stream=None) -> BoundCall:
     return BoundCall(lib().merit_sepfilter, "merit_sepfilter", _sep_args(plan, x, kx, ky, y, stream),
                      (plan, x, kx, ky, y))
+
+
+def merit_plan_bilateral(N, H, W, k) -> Plan:
+    h = ctypes.c_void_p()
+    _check(lib().merit_plan_bilateral(N, H, W, k, ctypes.byref(h)), "merit_plan_bilateral")
+    return Plan(h)
+
+
+def _bilateral_args(plan, x, gx, gy, norm, y, stream):
+    import torch
+    out_shape, a_shape, b_shape = plan.shapes()
+    if tuple(x.shape) != a_shape or tuple(y.shape) != out_shape or tuple(gx.shape) != b_shape \
+            or tuple(gy.shape) != b_shape:
+        raise ValueError("tensors do not match the plan")
+    return (plan.handle, _dev_ptr(x, torch.float32, "x"), _dev_ptr(gx, torch.float32, "gx"),
+            _dev_ptr(gy, torch.float32, "gy"), ctypes.c_double(float(norm)), _dev_ptr(y, torch.float32, "y"),
+            _stream(stream))
+
+
+def merit_bilateral(plan: Plan, x, gx, gy, norm, y=None, stream=None):
+    import torch
+    if y is None:
+        y = torch.empty(plan.out_shape(), dtype=torch.float32, device=x.device)
+    _check(lib().merit_bilateral(*_bilateral_args(plan, x, gx, gy, norm, y, stream)), "merit_bilateral")
+    return y
+
+
+def bind_bilateral(plan: Plan, x, gx, gy, norm, y, stream=None) -> BoundCall:
+    return BoundCall(lib().merit_bilateral, "merit_bilateral", _bilateral_args(plan, x, gx, gy, norm, y, stream),
+                     (plan, x, gx, gy, y))
 
 
 def merit_plan_correlation(N, C, H, W, R, sd=1) -> Plan:

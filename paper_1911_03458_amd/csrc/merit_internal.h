@@ -176,6 +176,20 @@ struct SepParams {
 hipError_t launch_sepfilter(const SepParams &p, const float *x, const float *kx, const float *ky, float *y,
                             hipStream_t s);
 
+// ---- bilateral filter ----------------------------------------------------------------
+struct BilatParams {
+    int N, H, W, k;
+    int c, c4;             // window offset k/2; the staged columns start at x0 - c4 (c rounded up to 4)
+    int tiles_y, tiles_x;  // 16 x 64 output tiles
+    int PI;                // LDS row pitch in floats (a multiple of 4)
+    int lds_bytes;
+    float norm_log2e;      // range constant times log2(e): exp(d*d*norm) = 2^(d*d*norm_log2e); set per call
+    FastDiv div_tiles_x, div_tiles_y, div_p4;
+};
+
+hipError_t launch_bilateral(const BilatParams &p, const float *x, const float *gx, const float *gy, float *y,
+                            hipStream_t s);
+
 hipError_t launch_correlation(const CorrParams &p, const void *x1, const void *x2, void *y, hipStream_t s);
 size_t corr_lds_bytes(const CorrParams &p);
 
@@ -192,5 +206,6 @@ struct merit_plan {
     merit::CorrParams corr;
     merit::DwParams dw;
     merit::SepParams sep;
+    merit::BilatParams bil;
     merit_launch_info info;
 };

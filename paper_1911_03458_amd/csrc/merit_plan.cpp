@@ -322,6 +322,56 @@ merit_status derive_sep(merit_plan *pl)
     return MERIT_OK;
 }
 
+// --------------------------------------------------------- bilateral filter ---
+merit_status derive_bilateral(merit_plan *pl)
+{
+    const merit_plan_desc &d = pl->desc;
+    if (d.dtype != MERIT_F32 || d.pad != MERIT_PAD_CLAMP) return MERIT_ERR_UNSUPPORTED;
+    if (d.n_par != 3 || d.n_acc != 2) return MERIT_ERR_UNSUPPORTED;
+    if (d.a.ndim != 3 || d.b.ndim != 1) return MERIT_ERR_UNSUPPORTED;
+    const int64_t N = d.a.shape[0], H = d.a.shape[1], W = d.a.shape[2], k = d.b.shape[0];
+    if (N < 0 || H <= 0 || W <= 0 || k <= 0) return MERIT_ERR_INVALID_ARG;
+    const int64_t c = k / 2;
+    const int axis_x[5] = {0, 1, 2, 1, 2};
+    const int64_t stride_x[5] = {1, 1, 1, 1, 1};
+    const int64_t offset_x[5] = {0, 0, 0, -c, -c};
+    const int axis_k[5] = {MERIT_AXIS_UNUSED, MERIT_AXIS_UNUSED, MERIT_AXIS_UNUSED, MERIT_AXIS_UNUSED, 0};
+    const int64_t stride_k[5] = {0, 0, 0, 0, 1};
+    const int64_t offset_k[5] = {0, 0, 0, 0, 0};
+    if (!operand_is(d.a, 5, axis_x, stride_x, offset_x)) return MERIT_ERR_UNSUPPORTED;
+    if (!operand_is(d.b, 5, axis_k, stride_k, offset_k)) return MERIT_ERR_UNSUPPORTED;
+    if (d.range[0] != N || d.range[1] != H || d.range[2] != W || d.range[3] != k || d.range[4] != k)
+        return MERIT_ERR_SHAPE;
+    if (k > 32 || H * W >= INT_LIMIT || N * H * W >= (1ll << 40)) return MERIT_ERR_UNSUPPORTED;
+
+    BilatParams &p = pl->bil;
+    p.N = (int)N; p.H = (int)H; p.W = (int)W; p.k = (int)k; p.c = (int)c;
+    p.c4 = (int)round_up(c, 4);
+    p.tiles_y = (int)cdiv(H, 16);
+    p.tiles_x = (int)cdiv(W, 64);
+    p.PI = (int)round_up(64 + p.c4 + (k - 1 - c), 4);
+    const int64_t RH = 16 + k - 1;
+    p.lds_bytes = (int)((RH * p.PI + 2 * k) * 4);
+    p.norm_log2e = 0.0f;
+    const int64_t grid = N * p.tiles_y * p.tiles_x;
+    if (grid >= INT_LIMIT || !fastdiv_ok(grid, p.tiles_x) || !fastdiv_ok(N * p.tiles_y, p.tiles_y) ||
+        !fastdiv_ok(RH * p.PI, p.PI / 4))
+        return MERIT_ERR_UNSUPPORTED;
+    p.div_tiles_x = make_fastdiv((uint32_t)p.tiles_x);
+    p.div_tiles_y = make_fastdiv((uint32_t)p.tiles_y);
+    p.div_p4 = make_fastdiv((uint32_t)(p.PI / 4));
+
+    pl->out_ndim = 3;
+    pl->out_shape[0] = N; pl->out_shape[1] = H; pl->out_shape[2] = W;
+    merit_launch_info &li = pl->info;
+    li.kernel = "merit_bilateral_tile";
+    li.grid[0] = grid; li.grid[1] = 1; li.grid[2] = 1;
+    li.block[0] = 256; li.block[1] = 1; li.block[2] = 1;
+    li.lds_bytes = p.lds_bytes;
+    li.tile[0] = 1; li.tile[1] = 16; li.tile[2] = 64; li.tile[3] = k; li.tile[4] = k;
+    return MERIT_OK;
+}
+
 // -------------------------------------------------------------- convolution ---
 merit_status derive_conv(merit_plan *pl)
 {
@@ -695,7 +745,7 @@ merit_status merit_plan_create(const merit_plan_desc *desc, merit_plan **out)
 {
     if (!desc || !out) return MERIT_ERR_NULL;
     *out = nullptr;
-    if ((int)desc->op < 0 || (int)desc->op > 11 || (int)desc->dtype < 0 || (int)desc->dtype > 2 ||
+    if ((int)desc->op < 0 || (int)desc->op > 12 || (int)desc->dtype < 0 || (int)desc->dtype > 2 ||
         (int)desc->pad < 0 || (int)desc->pad > 3)
         return MERIT_ERR_INVALID_ARG;
     if (desc->n_par < 1 || desc->n_acc < 1 || desc->n_par + desc->n_acc > MERIT_MAX_INDEX)
@@ -726,6 +776,7 @@ merit_status merit_plan_create(const merit_plan_desc *desc, merit_plan **out)
     case MERIT_OP_CORR_DOT: st = derive_corr(pl); break;
     case MERIT_OP_DWCONV_DOT: st = derive_dw(pl); break;
     case MERIT_OP_SEPFILTER_DOT: st = derive_sep(pl); break;
+    case MERIT_OP_BILATERAL: st = derive_bilateral(pl); break;
     default: st = derive_sad(pl); break;
     }
     if (st != MERIT_OK) {
@@ -839,14 +890,48 @@ merit_status merit_plan_pool2d(int N, int C, int H, int W, int kh, int kw, int s
     return merit_plan_create(&d, out);
 }
 
+static merit_status plan_window_filter(merit_op op, int N, int H, int W, int k, merit_plan **out);
+
 merit_status merit_plan_sepfilter(int N, int H, int W, int k, merit_plan **out)
+{
+    return plan_window_filter(MERIT_OP_SEPFILTER_DOT, N, H, W, k, out);
+}
+
+merit_status merit_plan_bilateral(int N, int H, int W, int k, merit_plan **out)
+{
+    return plan_window_filter(MERIT_OP_BILATERAL, N, H, W, k, out);
+}
+
+merit_status merit_bilateral(const merit_plan *plan, const void *x, const void *gx, const void *gy, double norm,
+                             void *y, void *stream)
+{
+    if (!plan) return MERIT_ERR_NULL;
+    if (plan->desc.op != MERIT_OP_BILATERAL) return MERIT_ERR_INVALID_ARG;
+    if (!(norm == norm) || norm * 1.4426950408889634 > 3.0e38 || norm * 1.4426950408889634 < -3.0e38)
+        return MERIT_ERR_INVALID_ARG;
+    if (plan->bil.N == 0) return MERIT_OK;                // empty batch: nothing to read or write
+    if (!x || !gx || !gy || !y) return MERIT_ERR_NULL;
+    if (!aligned16(x) || !aligned16(y) || ((uintptr_t)gx & 3) || ((uintptr_t)gy & 3)) return MERIT_ERR_ALIGNMENT;
+    merit::BilatParams p = plan->bil;                     // the plan stays shareable between threads
+    p.norm_log2e = (float)(norm * 1.4426950408889634);
+    return launch_bilateral(p, static_cast<const float *>(x), static_cast<const float *>(gx),
+                            static_cast<const float *>(gy), static_cast<float *>(y),
+                            static_cast<hipStream_t>(stream)) == hipSuccess
+               ? MERIT_OK
+               : MERIT_ERR_HIP;
+}
+
+}  // extern "C"
+
+// k = (n, p1, p2 | a1, a2): the image window at offset -k/2 on both axes, a vector of length k on a2
+static merit_status plan_window_filter(merit_op op, int N, int H, int W, int k, merit_plan **out)
 {
     if (!out) return MERIT_ERR_NULL;
     *out = nullptr;
     if (N < 0 || H <= 0 || W <= 0 || k <= 0) return MERIT_ERR_INVALID_ARG;
     merit_plan_desc d;
     std::memset(&d, 0, sizeof(d));
-    d.op = MERIT_OP_SEPFILTER_DOT; d.dtype = MERIT_F32; d.pad = MERIT_PAD_CLAMP;
+    d.op = op; d.dtype = MERIT_F32; d.pad = MERIT_PAD_CLAMP;
     d.n_par = 3; d.n_acc = 2;
     const int64_t range[5] = {N, H, W, k, k};
     const int ax[5] = {0, 1, 2, 1, 2};
@@ -860,6 +945,8 @@ merit_status merit_plan_sepfilter(int N, int H, int W, int k, merit_plan **out)
     d.b.ndim = 1; d.b.shape[0] = k;
     return merit_plan_create(&d, out);
 }
+
+extern "C" {
 
 merit_status merit_sepfilter(const merit_plan *plan, const void *x, const void *kx, const void *ky, void *y,
                              void *stream)
@@ -920,6 +1007,7 @@ merit_status merit_plan_set_tile(merit_plan *plan, const int64_t tile[MERIT_MAX_
     case MERIT_OP_CORR_DOT: st = derive_corr(&trial); break;
     case MERIT_OP_DWCONV_DOT: st = derive_dw(&trial); break;
     case MERIT_OP_SEPFILTER_DOT: st = derive_sep(&trial); break;
+    case MERIT_OP_BILATERAL: st = derive_bilateral(&trial); break;
     default: st = derive_sad(&trial); break;
     }
     if (st != MERIT_OK) return st;          // the plan keeps its previous tiling

@@ -282,3 +282,39 @@ def make_sepfilter_inputs(wl: SepWorkload, seed: int | None = None, N: int | Non
         g = np.exp(-0.5 * (a / sigma) ** 2)
         taps.append((g / g.sum()).astype(np.float32))
     return x, taps[0], taps[1]
+
+
+# --------------------------------------------------------------------------
+# bilateral filter (Section VI-A, Listings 2 and 3; the image size and the constants are not
+# given there: one full-HD fp32 plane, a 9 x 9 window, sigma_s = 3, sigma_r = 25 on a 0..255
+# range here).  The image is smooth regions with steps plus noise, so that both regimes of
+# the range term (weights near 1 and weights near 0) occur.
+# --------------------------------------------------------------------------
+@dataclass(frozen=True)
+class BilateralWorkload:
+    name: str
+    N: int
+    H: int
+    W: int
+    k: int
+    sigma_s: float
+    sigma_r: float
+
+    @property
+    def norm(self) -> float:
+        return -1.0 / (2.0 * self.sigma_r * self.sigma_r)
+
+
+CFG_BILATERAL = BilateralWorkload("bilateral_1x1080x1920_k9", 1, 1080, 1920, 9, 3.0, 25.0)
+
+
+def make_bilateral_inputs(wl: BilateralWorkload, seed: int | None = None, N: int | None = None):
+    """(x fp32 [N,H,W] in [0,255], g fp32 [k]: the spatial lookup table, used for both axes)."""
+    rng = np.random.default_rng(BASE_SEED + 10 if seed is None else seed)
+    n = wl.N if N is None else N
+    coarse = rng.integers(0, 4, size=(n, -(-wl.H // 40), -(-wl.W // 40))) * 60.0 + 30.0    # piecewise constant
+    x = np.repeat(np.repeat(coarse, 40, axis=1), 40, axis=2)[:, :wl.H, :wl.W]
+    x = np.clip(x + rng.normal(0.0, 8.0, size=x.shape), 0.0, 255.0).astype(np.float32)
+    a = np.arange(wl.k, dtype=np.float64) - wl.k // 2
+    g = np.exp(-0.5 * (a / wl.sigma_s) ** 2).astype(np.float32)
+    return x, g

@@ -169,6 +169,21 @@ def test_sepfilter_plan():
         mb.merit_plan_sepfilter(1, 0, 70, 3)
 
 
+def test_bilateral_plan():
+    plan = mb.merit_plan_bilateral(1, 1080, 1920, 9)
+    d = plan.desc()
+    assert (d.op, d.n_par, d.n_acc, d.dtype, d.pad) == (mb.MERIT_OP_BILATERAL, 3, 2, mb.MERIT_F32, mb.MERIT_PAD_CLAMP)
+    assert tuple(d.range[:5]) == (1, 1080, 1920, 9, 9) and plan.out_shape() == (1, 1080, 1920)
+    assert (d.a.offset[3], d.a.offset[4]) == (-4, -4)            # Listing 3: {0,-k/2,1}, {1,-k/2,1}
+    li = plan.launch_info()
+    assert li["kernel"] == "merit_bilateral_tile" and li["tile"][1:3] == (16, 64)      # the listing's 16-row tiles
+    assert li["grid"][0] == 68 * 30
+    assert plan.footprint(0, (1, 16, 64, 9, 9)) == (1, 24, 72)
+    with pytest.raises(mb.MeritError) as e:
+        mb.merit_plan_bilateral(1, 64, 64, 33)
+    assert e.value.status == mb.MERIT_ERR_UNSUPPORTED
+
+
 def test_depthwise_plan():
     plan = mb.merit_plan_conv2d_depthwise(32, 32, 64, 64, 3, 3, 1, 1, 1, 1)
     d = plan.desc()

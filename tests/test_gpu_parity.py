@@ -847,3 +847,65 @@ def test_sepfilter_workloads_sampled(mb):
         assert np.all(np.abs(got - ref) <= _sep_tol(x, kx, ky))
         # a normalised positive window keeps the range and (up to the borders) the mean
         assert got.min() >= 0.0 and got.max() <= 255.0 + 1e-3
+
+
+# -------------------------------------------------- bilateral filter
+BILATERAL_CASES = [
+    # N  H   W   k  sigma_r
+    (1, 40, 70, 5, 20.0),        # ragged tiles
+    (2, 33, 129, 9, 25.0),       # one column past two tiles
+    (1, 16, 64, 1, 10.0),        # single tap: the input itself
+    (1, 23, 30, 4, 40.0),        # even window, width not a multiple of 4
+    (1, 50, 66, 31, 30.0),       # window larger than a tile
+    (1, 20, 64, 7, 2.0),         # sharp range term: most weights underflow
+]
+
+
+def _bilateral_tol(x, k):
+    # weights carry a relative error of a few 1e-6 (two fp32 products in the exponent, the
+    # hardware exponential), which moves a weighted mean by at most twice that times the range
+    # of the window; k*k fp32 additions add k*k * 2^-24 of it
+    return (2e-5 + 1.2e-7 * k * k) * float(x.max() - x.min()) + 1e-30
+
+
+@pytest.mark.parametrize("N,H,W,k,sigma_r", BILATERAL_CASES)
+def test_bilateral(mb, N, H, W, k, sigma_r):
+    rng = np.random.default_rng(N * 1000 + H * 10 + k)
+    x = (rng.integers(0, 3, size=(N, H, W)) * 80.0 + rng.normal(0, 6.0, size=(N, H, W))).astype(np.float32)
+    gx = np.exp(-0.5 * ((np.arange(k) - k // 2) / max(k / 4.0, 0.5)) ** 2).astype(np.float32)
+    gy = rng.uniform(0.3, 1.0, k).astype(np.float32)         # a different table per axis
+    norm = -1.0 / (2 * sigma_r * sigma_r)
+    plan = mb.merit_plan_bilateral(N, H, W, k)
+    print("bilateral", (N, H, W, k), plan.launch_info(), flush=True)
+    buf, y, p = guarded_empty((N, H, W), torch.float32, 777.0)
+    mb.merit_bilateral(plan, dev(x), dev(gx), dev(gy), norm, y)
+    torch.cuda.synchronize()
+    check_canary(buf, p, 777.0)
+    got = y.cpu().numpy().astype(np.float64)
+    ref = oracle.bilateral(x, gx, gy, norm).astype(np.float64)
+    err = np.abs(got - ref)
+    assert np.all(err <= _bilateral_tol(x, k)), f"max err {err.max()} at {np.unravel_index(err.argmax(), err.shape)}"
+
+
+def test_bilateral_without_range_term_is_the_normalised_separable_filter(mb):
+    """norm = 0: both kernels of the library must agree (up to fp32 rounding)."""
+    rng = np.random.default_rng(12)
+    x = rng.uniform(0, 255, (1, 45, 80)).astype(np.float32)
+    g = np.exp(-0.5 * ((np.arange(7) - 3) / 2.0) ** 2).astype(np.float32)
+    yb = mb.merit_bilateral(mb.merit_plan_bilateral(1, 45, 80, 7), dev(x), dev(g), dev(g), 0.0).cpu().numpy()
+    ys = mb.merit_sepfilter(mb.merit_plan_sepfilter(1, 45, 80, 7), dev(x), dev(g), dev(g)).cpu().numpy()
+    assert np.allclose(yb, ys / float(g.sum()) ** 2, rtol=1e-5, atol=1e-3)
+
+
+def test_bilateral_workload_sampled(mb):
+    """Full-size launch; the oracle checks the whole (single) image."""
+    c = wl.CFG_BILATERAL
+    x, g = wl.make_bilateral_inputs(c)
+    y = mb.merit_bilateral(mb.merit_plan_bilateral(c.N, c.H, c.W, c.k), dev(x), dev(g), dev(g), c.norm)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy().astype(np.float64)
+    ref = oracle.bilateral(x, g, g, c.norm).astype(np.float64)
+    assert np.all(np.abs(got - ref) <= _bilateral_tol(x, c.k))
+    assert got.min() >= x.min() and got.max() <= x.max()
+    # it denoises: closer to the noise-free steps than the input on flat areas
+    assert np.abs(np.diff(got, axis=2)).mean() < 0.5 * np.abs(np.diff(x.astype(np.float64), axis=2)).mean()
