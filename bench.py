@@ -231,9 +231,9 @@ def bench_bilateral(torch, mb, wl, cfg, steps, warmup):
     wall, ev_ms = timed_region(torch, lambda i: call(), steps, warmup)
     t = ev_ms * 1e-3 / steps
     taps = float(cfg.N * cfg.H * cfg.W * cfg.k * cfg.k)
-    # per tap: subtract, two multiplies, the exponential (a quarter-rate instruction: 4 slots),
-    # multiply by the table entry, add, fused multiply-add = 10 issue slots of the plain fp32 rate
-    slots = 10.0 * taps
+    # per tap: two fused multiply-adds (scaled difference, exponent), the exponential (a
+    # quarter-rate instruction: 4 slots), add, fused multiply-add = 8 issue slots of the plain rate
+    slots = 8.0 * taps
     peak = VALU_PEAK_TOPS
     alg_bytes = 2 * x.nbytes
     return {

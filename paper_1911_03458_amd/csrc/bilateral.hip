@@ -12,15 +12,19 @@
 // there, from column x0 - c4 (k/2 rounded up to 4), so that for W % 4 == 0 the staging is
 // aligned 16-byte loads without a branch.  A thread makes four outputs of one column, four
 // rows apart: lanes run along the row (conflict-free 4-byte LDS reads) and the four
-// independent chains hide the latency of the exponential.  exp(d*d*norm) is computed as
-// 2^(d*d*norm*log2(e)) with the constants multiplied on the host; gy[a1] is applied once per
-// window row to the row's partial sums.
+// independent chains hide the latency of the exponential.  Five vector instructions per tap:
+// with s = sqrt(|norm| log2 e), the scaled difference d' = center*s - v*s is one fused
+// multiply-add, the weight exp(d*d*norm) * gx[a2] = 2^(-+ d'*d' + log2 gx[a2]) one more and
+// the base-2 exponential, then wsum += w and wxsum += w*v; gy[a1] is applied once per window
+// row to the row's partial sums.  (A spatial table entry of 0 gives log2 = -inf and weight 0.)
 #include "merit_internal.h"
 
 namespace merit {
 
 typedef float float4v __attribute__((ext_vector_type(4)));
 
+// NEG: the range constant is <= 0 (the usual decaying range term)
+template <bool NEG>
 __global__ __launch_bounds__(256) void merit_bilateral_tile(BilatParams p, const float *__restrict__ x,
                                                            const float *__restrict__ gx,
                                                            const float *__restrict__ gy, float *__restrict__ y)
@@ -41,7 +45,7 @@ __global__ __launch_bounds__(256) void merit_bilateral_tile(BilatParams p, const
     const float *img = x + (size_t)n * p.H * p.W;
 
     if (tid < p.k) {
-        wxl[tid] = gx[tid];
+        wxl[tid] = __builtin_amdgcn_logf(gx[tid]);        // log2
         wyl[tid] = gy[tid];
     }
     // staging: every element is a real (clamped) pixel
@@ -87,10 +91,11 @@ __global__ __launch_bounds__(256) void merit_bilateral_tile(BilatParams p, const
     // col + a2 - c + c4
     const int col = tid & 63, row0 = tid >> 6;
     const int dcol = col + p.c4 - p.c;
-    float cen[4], wsum[4], wxsum[4];
+    float cen[4], wsum[4], wxsum[4];                      // cen: centre pixel times s
+    const float sc = p.scale;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        cen[j] = in[(row0 + 4 * j + p.c) * p.PI + dcol + p.c];
+        cen[j] = in[(row0 + 4 * j + p.c) * p.PI + dcol + p.c] * sc;
         wsum[j] = 0.0f;
         wxsum[j] = 0.0f;
     }
@@ -100,12 +105,12 @@ __global__ __launch_bounds__(256) void merit_bilateral_tile(BilatParams p, const
         float rs[4] = {0.0f, 0.0f, 0.0f, 0.0f}, rxs[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll 2
         for (int a2 = 0; a2 < p.k; ++a2) {
-            const float gxv = wxl[a2];
+            const float lgx = wxl[a2];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const float v = rowp[4 * j * p.PI + a2];
-                const float d = cen[j] - v;
-                const float w = __builtin_amdgcn_exp2f(d * d * p.norm_log2e) * gxv;
+                const float d = fmaf(-v, sc, cen[j]);
+                const float w = __builtin_amdgcn_exp2f(NEG ? fmaf(-d, d, lgx) : fmaf(d, d, lgx));
                 rs[j] += w;
                 rxs[j] = fmaf(w, v, rxs[j]);
             }
@@ -130,7 +135,12 @@ hipError_t launch_bilateral(const BilatParams &p, const float *x, const float *g
 {
     const int64_t grid = (int64_t)p.N * p.tiles_y * p.tiles_x;
     if (grid == 0) return hipSuccess;
-    hipLaunchKernelGGL(merit_bilateral_tile, dim3((uint32_t)grid), dim3(256), (size_t)p.lds_bytes, s, p, x, gx, gy, y);
+    if (p.neg)
+        hipLaunchKernelGGL(merit_bilateral_tile<true>, dim3((uint32_t)grid), dim3(256), (size_t)p.lds_bytes, s, p, x,
+                           gx, gy, y);
+    else
+        hipLaunchKernelGGL(merit_bilateral_tile<false>, dim3((uint32_t)grid), dim3(256), (size_t)p.lds_bytes, s, p,
+                           x, gx, gy, y);
     return hipGetLastError();
 }
 

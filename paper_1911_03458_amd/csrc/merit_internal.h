@@ -183,7 +183,8 @@ struct BilatParams {
     int tiles_y, tiles_x;  // 16 x 64 output tiles
     int PI;                // LDS row pitch in floats (a multiple of 4)
     int lds_bytes;
-    float norm_log2e;      // range constant times log2(e): exp(d*d*norm) = 2^(d*d*norm_log2e); set per call
+    float scale;           // sqrt(|norm| log2 e): exp(d*d*norm) = 2^(-+ (d*scale)^2); set per call
+    int neg;               // norm <= 0; set per call
     FastDiv div_tiles_x, div_tiles_y, div_p4;
 };
 

@@ -6,6 +6,7 @@
 // tile / halo geometry derived from it with the footprint rule of Section
 // IV-A, Eq. 9.  No GPU call happens here.
 #include <cstdlib>
+#include <cmath>
 #include <cstring>
 #include <new>
 
@@ -352,7 +353,7 @@ merit_status derive_bilateral(merit_plan *pl)
     p.PI = (int)round_up(64 + p.c4 + (k - 1 - c), 4);
     const int64_t RH = 16 + k - 1;
     p.lds_bytes = (int)((RH * p.PI + 2 * k) * 4);
-    p.norm_log2e = 0.0f;
+    p.scale = 0.0f; p.neg = 1;
     const int64_t grid = N * p.tiles_y * p.tiles_x;
     if (grid >= INT_LIMIT || !fastdiv_ok(grid, p.tiles_x) || !fastdiv_ok(N * p.tiles_y, p.tiles_y) ||
         !fastdiv_ok(RH * p.PI, p.PI / 4))
@@ -913,7 +914,8 @@ merit_status merit_bilateral(const merit_plan *plan, const void *x, const void *
     if (!x || !gx || !gy || !y) return MERIT_ERR_NULL;
     if (!aligned16(x) || !aligned16(y) || ((uintptr_t)gx & 3) || ((uintptr_t)gy & 3)) return MERIT_ERR_ALIGNMENT;
     merit::BilatParams p = plan->bil;                     // the plan stays shareable between threads
-    p.norm_log2e = (float)(norm * 1.4426950408889634);
+    p.neg = norm <= 0.0 ? 1 : 0;
+    p.scale = (float)std::sqrt(std::fabs(norm) * 1.4426950408889634);
     return launch_bilateral(p, static_cast<const float *>(x), static_cast<const float *>(gx),
                             static_cast<const float *>(gy), static_cast<float *>(y),
                             static_cast<hipStream_t>(stream)) == hipSuccess

@@ -887,6 +887,18 @@ def test_bilateral(mb, N, H, W, k, sigma_r):
     assert np.all(err <= _bilateral_tol(x, k)), f"max err {err.max()} at {np.unravel_index(err.argmax(), err.shape)}"
 
 
+def test_bilateral_positive_constant(mb):
+    """The constant is used as given (the listing passes a positive one): weights grow with the
+    difference."""
+    rng = np.random.default_rng(31)
+    x = rng.uniform(0, 100, (1, 30, 70)).astype(np.float32)
+    g = np.exp(-0.5 * ((np.arange(5) - 2) / 1.5) ** 2).astype(np.float32)
+    y = mb.merit_bilateral(mb.merit_plan_bilateral(1, 30, 70, 5), dev(x), dev(g), dev(g), 2e-4).cpu().numpy()
+    ref = oracle.bilateral(x, g, g, 2e-4)
+    assert np.all(np.abs(y.astype(np.float64) - ref) <= _bilateral_tol(x, 5))
+    assert np.abs(ref - oracle.bilateral(x, g, g, -2e-4)).max() > 1.0       # the sign matters
+
+
 def test_bilateral_without_range_term_is_the_normalised_separable_filter(mb):
     """norm = 0: both kernels of the library must agree (up to fp32 rounding)."""
     rng = np.random.default_rng(12)
