@@ -222,9 +222,9 @@ __device__ __forceinline__ void stage_residual(const ConvParams &p, uint32_t *ou
 
 template <int CB, int PXW, int NW, bool FULL>
 __device__ __forceinline__ void store_tile(const ConvParams &p, floatx16 (&acc)[CB][PXW], uint32_t *outl,
-                                           uint16_t *__restrict__ y, int n, int co_base, int m0, int tid)
+                                           uint16_t *__restrict__ y, int n, int co_base, int m0, int tid, bool add)
 {
-    tile_to_lds<CB, PXW, NW>(acc, outl, tid >> 6, tid & 63, p.relu != 0, p.residual != 0);
+    tile_to_lds<CB, PXW, NW>(acc, outl, tid >> 6, tid & 63, p.relu != 0, add);
     __syncthreads();
     lds_to_global<CB, NW * PXW * 32, NW * 64, FULL>(p, outl, y, n, co_base, m0, tid);
 }
@@ -524,12 +524,12 @@ __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, 
     }
     tile_body(T, Tn);
     for (tile += nwg; tile < ntiles; tile += nwg) {
-        store_tile<CB, PXW, NW, FULL>(p, acc, outl, y, T.n, co_base, T.m0, tid);
+        store_tile<CB, PXW, NW, FULL>(p, acc, outl, y, T.n, co_base, T.m0, tid, p.residual != 0);
         T = Tn;
         Tn = geom(min(tile + nwg, ntiles - 1));
         tile_body(T, Tn);
     }
-    store_tile<CB, PXW, NW, FULL>(p, acc, outl, y, T.n, co_base, T.m0, tid);
+    store_tile<CB, PXW, NW, FULL>(p, acc, outl, y, T.n, co_base, T.m0, tid, p.residual != 0);
 }
 
 // ---------------------------------------------------------------------------
@@ -1213,7 +1213,8 @@ __device__ __forceinline__ void stage_input_chblock(const ConvParams &p, const u
     }
 }
 
-template <int CB, int PXW>
+// RES: residual layer (a separate instance, so that the plain one carries no test for it)
+template <int CB, int PXW, bool RES>
 __global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const uint16_t *__restrict__ x,
                                                            const uint16_t *__restrict__ w,
                                                            const uint16_t *__restrict__ res,
@@ -1252,7 +1253,7 @@ __global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const 
         } else {
             stage_input_chblock(p, x, xl, n, yA, RH, tid, 256);
         }
-        if (p.residual) stage_residual<CB, 4 * PXW * 32, 256>(p, outl, res, n, co_base, m0, tid);
+        if (RES) stage_residual<CB, 4 * PXW * 32, 256>(p, outl, res, n, co_base, m0, tid);
         __syncthreads();
 
         int pbase[PXW], pcol[PXW];                  // staged row offset and column of tap kx = 0
@@ -1325,7 +1326,7 @@ __global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const 
                 }
             }
         }
-        store_tile<CB, PXW, 4, false>(p, acc, outl, y, n, co_base, m0, tid);
+        store_tile<CB, PXW, 4, false>(p, acc, outl, y, n, co_base, m0, tid, RES);
     }
 }
 
@@ -1425,10 +1426,16 @@ hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, cons
         MERIT_PLANAR(1, 1, 4);
 #undef MERIT_PLANAR
     }
-    if (p.CB == 2 && p.PXW == 2) return launch(merit_conv2d_chblock<2, 2>, p, x, w, r, y, s, gx, lds);
-    if (p.CB == 2 && p.PXW == 1) return launch(merit_conv2d_chblock<2, 1>, p, x, w, r, y, s, gx, lds);
-    if (p.CB == 1 && p.PXW == 2) return launch(merit_conv2d_chblock<1, 2>, p, x, w, r, y, s, gx, lds);
-    return launch(merit_conv2d_chblock<1, 1>, p, x, w, r, y, s, gx, lds);
+#define MERIT_CHBLOCK(CBv, PXv)                                                                   \
+    do {                                                                                          \
+        if (p.residual) return launch(merit_conv2d_chblock<CBv, PXv, true>, p, x, w, r, y, s, gx, lds); \
+        return launch(merit_conv2d_chblock<CBv, PXv, false>, p, x, w, r, y, s, gx, lds);          \
+    } while (0)
+    if (p.CB == 2 && p.PXW == 2) MERIT_CHBLOCK(2, 2);
+    if (p.CB == 2 && p.PXW == 1) MERIT_CHBLOCK(2, 1);
+    if (p.CB == 1 && p.PXW == 2) MERIT_CHBLOCK(1, 2);
+    MERIT_CHBLOCK(1, 1);
+#undef MERIT_CHBLOCK
 }
 
 const char *conv_kernel_name(const ConvParams &p)
