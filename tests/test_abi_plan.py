@@ -362,6 +362,30 @@ def test_null_and_misuse_without_gpu():
     assert L.merit_conv2d(plan.handle, 16, 16, 16, None) == mb.MERIT_ERR_INVALID_ARG
     assert L.merit_pool2d(plan.handle, None, 16, None) == mb.MERIT_ERR_NULL
     assert L.merit_pool2d(plan.handle, 16, 20, None) == mb.MERIT_ERR_ALIGNMENT
+    # the entry points of the widened operations reject the same things in the same order
+    import ctypes
+    res = mb.merit_plan_conv2d_residual(1, 16, 8, 8, 32, 3, 3, 1, 1, 1, 1, 1)
+    assert L.merit_conv2d(res.handle, 16, 16, 16, None) == mb.MERIT_ERR_INVALID_ARG        # needs the added tensor
+    assert L.merit_conv2d_residual(res.handle, 16, 16, None, 16, None) == mb.MERIT_ERR_NULL
+    assert L.merit_conv2d_residual(res.handle, 16, 16, 24, 16, None) == mb.MERIT_ERR_ALIGNMENT
+    assert L.merit_conv2d_residual(plan.handle, 16, 16, 16, 16, None) == mb.MERIT_ERR_INVALID_ARG
+    fused = mb.merit_plan_conv2d_pool(1, 3, 32, 32, 8, 3, 3, 1, 1, 1, 1, 1)
+    assert L.merit_conv2d(fused.handle, 16, None, 16, None) == mb.MERIT_ERR_NULL
+    sep = mb.merit_plan_sepfilter(1, 8, 8, 3)
+    assert L.merit_sepfilter(sep.handle, 16, None, 4, 16, None) == mb.MERIT_ERR_NULL
+    assert L.merit_sepfilter(sep.handle, 16, 6, 4, 16, None) == mb.MERIT_ERR_ALIGNMENT     # taps: 4-byte aligned
+    assert L.merit_sepfilter(sep.handle, 24, 4, 4, 16, None) == mb.MERIT_ERR_ALIGNMENT     # image: 16-byte aligned
+    assert L.merit_sepfilter(plan.handle, 16, 4, 4, 16, None) == mb.MERIT_ERR_INVALID_ARG
+    bil = mb.merit_plan_bilateral(1, 8, 8, 3)
+    norm = ctypes.c_double(-0.01)
+    assert L.merit_bilateral(bil.handle, 16, 4, None, norm, 16, None) == mb.MERIT_ERR_NULL
+    assert L.merit_bilateral(bil.handle, 16, 4, 4, ctypes.c_double(float("nan")), 16, None) == mb.MERIT_ERR_INVALID_ARG
+    assert L.merit_bilateral(sep.handle, 16, 4, 4, norm, 16, None) == mb.MERIT_ERR_INVALID_ARG
+    dw = mb.merit_plan_conv2d_depthwise(1, 4, 8, 8, 3, 3, 1, 1, 1, 1)
+    assert L.merit_conv2d_depthwise(dw.handle, 16, 16, None, None) == mb.MERIT_ERR_NULL
+    # an empty batch is a no-op, whatever the pointers
+    assert L.merit_sepfilter(mb.merit_plan_sepfilter(0, 8, 8, 3).handle, None, None, None, None, None) == mb.MERIT_OK
+    assert L.merit_bilateral(mb.merit_plan_bilateral(0, 8, 8, 3).handle, None, None, None, norm, None, None) == mb.MERIT_OK
 
 
 def test_conv_variant_selection():
