@@ -726,10 +726,31 @@ def test_conv_identity_kernel_is_exact(mb):
     assert np.array_equal(got, x.astype(np.float64))
 
 
+def _ulp_distance(a16, b16):
+    """Distance in binary16 units in the last place (values mapped to ordered integers)."""
+    def ordered(h):
+        u = np.ascontiguousarray(h, np.float16).view(np.uint16).astype(np.int32)
+        return np.where(u & 0x8000, -(u & 0x7FFF), u)
+    return np.abs(ordered(a16) - ordered(b16))
+
+
+def _report_ulps(name, got16, ref16):
+    """Next to the tolerance test: how far the kernel's fp32 accumulation and single rounding
+    end up from the oracle's double sum rounded once.  Away from cancellations the two differ
+    by at most one binary16 unit in the last place; near zero a difference of 1e-6 is many
+    units, which is what the absolute term of the tolerance is for."""
+    d = _ulp_distance(got16, ref16)
+    big = np.abs(ref16.astype(np.float64)) >= 2.0 ** -6
+    print(f"{name}: ulp distance max {d.max()}, 99.9th percentile {np.percentile(d, 99.9):.1f}, "
+          f"max where |ref| >= 2^-6: {d[big].max()}, equal {np.mean(d == 0):.4f}", flush=True)
+    assert d[big].max() <= 1 and np.percentile(d, 99.9) <= 1
+
+
 def test_conv_3x3_workload(mb):
     c = wl.CFG2_CONV3
     x, w = wl.make_conv_inputs(c)
-    _conv_check(mb, x, w, (c.sh, c.sw), (c.ph, c.pw))
+    got, ref = _conv_check(mb, x, w, (c.sh, c.sw), (c.ph, c.pw))
+    _report_ulps("conv 3x3 workload", got.astype(np.float16), ref.astype(np.float16))
 
 
 def test_conv_7x7_workload_kernels_agree(mb):
@@ -768,6 +789,7 @@ def test_conv_7x7_workload_sampled(mb):
         ref = oracle.conv2d(x[n:n + 1], w, (c.sh, c.sw), (c.ph, c.pw)).astype(np.float64)[0]
         err = np.abs(got[n] - ref)
         assert np.all(err <= 2e-2 * np.abs(ref) + 1e-3), n
+        _report_ulps(f"conv 7x7 workload, image {n}", got[n].astype(np.float16), ref.astype(np.float16))
 
 
 def test_misaligned_pointer_is_rejected(mb):
