@@ -32,6 +32,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
 MFMA_F16_PEAK_TFLOPS = 2500.0    # dense fp16 MFMA
 VALU_PEAK_TOPS = 39.3216         # 256 CU x 64 lanes x 2.4 GHz, one lane-op per lane per clock
+FP32_FMA_PEAK_TOPS = 78.6432     # fp32 vector: 157.3 TFLOP/s = 256 CU x 128 fused multiply-adds x 2.4 GHz
 
 
 def parse_args():
@@ -42,6 +43,9 @@ def parse_args():
     ap.add_argument("--sets", type=int, default=8, help="rotating buffer sets for cache-cold timing")
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--peaks", action="store_true",
+                    help="only run the peak probes (streaming copy, MFMA / FMA / SAD / exp2 instruction "
+                         "loops) and print the measured-achievable peaks beside the data-sheet ones")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB device copy 10 times (known traffic, for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings) and exit")
@@ -63,6 +67,36 @@ def timed_region(torch, fn, steps, warmup):
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     return t1 - t0, e0.elapsed_time(e1)
+
+
+def measure_peaks(torch, mb):
+    """What the chip sustains with kernels that do nothing else (include/merit_probe.h)."""
+    out = {}
+    # memory stream: 1 GiB copied (read + written = 2 GiB of traffic), rotating over two buffer pairs
+    n = 256 << 20
+    bufs = [(torch.empty(n, dtype=torch.float32, device="cuda:0").normal_(),
+             torch.empty(n, dtype=torch.float32, device="cuda:0")) for _ in range(2)]
+    wall, ms = timed_region(torch, lambda i: mb.merit_probe_copy(*bufs[i % 2]), 20, 4)
+    assert torch.equal(bufs[0][0], bufs[0][1])
+    out["hbm_copy"] = {"measured": 2 * n * 4 / (ms * 1e-3 / 20) / 1e9, "datasheet": HBM_PEAK_GBS, "unit": "GB/s",
+                       "what": "16-byte streaming loads + stores, 1 GiB in, 1 GiB out"}
+    del bufs
+    wgs, iters = 256 * 8, 4096                       # 8 workgroups of 4 wavefronts per CU: 8 wavefronts per SIMD
+    sink = torch.empty(wgs * 256, dtype=torch.int32, device="cuda:0")
+    kinds = [("mfma_f16", mb.MERIT_PROBE_MFMA_F16, 32768.0 / 1e12, MFMA_F16_PEAK_TFLOPS, "TFLOP/s",
+              "v_mfma_f32_32x32x16_f16, 8 independent accumulators per wavefront"),
+             ("fma_f32", mb.MERIT_PROBE_FMA_F32, 64.0 / 1e12, FP32_FMA_PEAK_TOPS, "T lane-ops/s",
+              "v_fma_f32 (not packed), 8 independent chains per lane; data sheet = 157.3 TFLOP/s fp32 vector"),
+             ("sad_u8", mb.MERIT_PROBE_SAD_U8, 64.0 / 1e12, VALU_PEAK_TOPS, "T lane-ops/s",
+              "v_sad_u8, 8 independent accumulators per lane"),
+             ("exp2_f32", mb.MERIT_PROBE_EXP2_F32, 64.0 / 1e12, FP32_FMA_PEAK_TOPS / 4, "T lane-ops/s",
+              "v_exp_f32, 8 independent chains per lane; data-sheet figure = a quarter of the fp32 rate")]
+    for name, which, per_instr, sheet, unit, what in kinds:
+        it = iters // 4 if which == mb.MERIT_PROBE_MFMA_F16 else iters
+        wall, ms = timed_region(torch, lambda i: mb.merit_probe_alu(which, wgs, it, sink), 10, 2)
+        instrs = wgs * 4 * it * 8
+        out[name] = {"measured": instrs * per_instr / (ms * 1e-3 / 10), "datasheet": sheet, "unit": unit, "what": what}
+    return out
 
 
 def bench_pool(torch, mb, wl, steps, warmup, nsets):
@@ -211,11 +245,10 @@ def bench_sepfilter(torch, mb, wl, cfg, steps, warmup, nsets):
     wall, ev_ms = timed_region(torch, lambda i: calls[i % ns](), steps, warmup)
     t = ev_ms * 1e-3 / steps
     fmas = 2.0 * cfg.k * cfg.N * cfg.H * cfg.W          # k per pass and pixel
-    # one fused multiply-add per lane and clock without packed fp32: long windows are bound by
-    # the vector ALU, short ones by memory
-    if fmas / (VALU_PEAK_TOPS * 1e12) > alg_bytes / (HBM_PEAK_GBS * 1e9):
-        roof = {"bound": "alu", "achieved": fmas / t / 1e12, "peak": VALU_PEAK_TOPS,
-                "unit": "T lane-ops/s (fp32 fused multiply-adds)", "frac": fmas / t / 1e12 / VALU_PEAK_TOPS}
+    # whichever published peak the workload needs longer at binds: memory up to k = 39 here
+    if fmas / (FP32_FMA_PEAK_TOPS * 1e12) > alg_bytes / (HBM_PEAK_GBS * 1e9):
+        roof = {"bound": "alu", "achieved": 2 * fmas / t / 1e12, "peak": 2 * FP32_FMA_PEAK_TOPS,
+                "unit": "TFLOP/s (fp32 vector)", "frac": fmas / t / 1e12 / FP32_FMA_PEAK_TOPS}
     else:
         roof = {"bound": "hbm", "achieved": alg_bytes / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": alg_bytes / t / 1e9 / HBM_PEAK_GBS}
@@ -238,17 +271,18 @@ def bench_bilateral(torch, mb, wl, cfg, steps, warmup):
     wall, ev_ms = timed_region(torch, lambda i: call(), steps, warmup)
     t = ev_ms * 1e-3 / steps
     taps = float(cfg.N * cfg.H * cfg.W * cfg.k * cfg.k)
-    # per tap: two fused multiply-adds (scaled difference, exponent), the exponential (a
-    # quarter-rate instruction: 4 slots), add, fused multiply-add = 8 issue slots of the plain rate
+    # per tap: two fused multiply-adds (scaled difference, exponent), add, fused multiply-add and
+    # the exponential, a quarter-rate instruction counted as 4: 8 fp32 vector-ALU slots, priced
+    # against the published fp32 vector peak (157.3 TFLOP/s = 78.6 T slots/s)
     slots = 8.0 * taps
-    peak = VALU_PEAK_TOPS
+    peak = FP32_FMA_PEAK_TOPS
     alg_bytes = 2 * x.nbytes
     return {
         "workload": cfg.name, "kernel": plan.launch_info()["kernel"], "avg_launch_us": t * 1e6,
         "out_elems_per_s": cfg.N * cfg.H * cfg.W / t, "taps_per_s": taps / t,
         "achieved_hbm_gbs": alg_bytes / t / 1e9, "hbm_frac": alg_bytes / t / 1e9 / HBM_PEAK_GBS,
         "roofline": {"bound": "alu", "achieved": slots / t / 1e12, "peak": peak,
-                     "unit": "T lane-ops/s (plain-rate fp32 issue slots)", "frac": slots / t / 1e12 / peak},
+                     "unit": "T slots/s (fp32 vector-ALU issue slots, exp2 = 4)", "frac": slots / t / 1e12 / peak},
     }
 
 
@@ -315,6 +349,10 @@ def main():
     from paper_1911_03458_amd import workloads as wl
     mb.lib()
     torch.cuda.set_device(0)
+
+    if args.peaks:
+        print(json.dumps({"peaks": measure_peaks(torch, mb)}))
+        return
 
     if args.copy_calibration:
         # one elementwise copy kernel per iteration: reads 256 MiB and writes 256 MiB

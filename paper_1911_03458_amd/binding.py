@@ -85,6 +85,8 @@ def lib():
     L.merit_plan_conv2d_residual.argtypes = [c_int] * 12 + [PP]
     L.merit_plan_sepfilter.argtypes = [c_int] * 4 + [PP]
     L.merit_sepfilter.argtypes = [P, P, P, P, P, P]
+    L.merit_probe_copy.argtypes = [P, P, ctypes.c_size_t, P]
+    L.merit_probe_alu.argtypes = [c_int, c_int, c_int, P, P]
     L.merit_plan_bilateral.argtypes = [c_int] * 4 + [PP]
     L.merit_bilateral.argtypes = [P, P, P, P, ctypes.c_double, P, P]
     L.merit_conv2d_residual.argtypes = [P, P, P, P, P, P]
@@ -105,7 +107,7 @@ def lib():
     for name in ("merit_plan_create", "merit_plan_destroy", "merit_plan_conv2d", "merit_plan_conv2d_relu",
                  "merit_plan_conv2d_dilated", "merit_plan_conv2d_pool", "merit_plan_conv2d_residual",
                  "merit_conv2d_residual", "merit_plan_sepfilter", "merit_sepfilter",
-                 "merit_plan_bilateral", "merit_bilateral",
+                 "merit_plan_bilateral", "merit_bilateral", "merit_probe_copy", "merit_probe_alu",
                  "merit_plan_pool2d",
                  "merit_plan_sad", "merit_plan_correlation", "merit_correlation", "merit_plan_conv2d_depthwise",
                  "merit_conv2d_depthwise", "merit_plan_get_desc", "merit_plan_out_shape", "merit_plan_footprint",
@@ -398,6 +400,26 @@ def merit_bilateral(plan: Plan, x, gx, gy, norm, y=None, stream=None):
 def bind_bilateral(plan: Plan, x, gx, gy, norm, y, stream=None) -> BoundCall:
     return BoundCall(lib().merit_bilateral, "merit_bilateral", _bilateral_args(plan, x, gx, gy, norm, y, stream),
                      (plan, x, gx, gy, y))
+
+
+(MERIT_PROBE_MFMA_F16, MERIT_PROBE_FMA_F32, MERIT_PROBE_SAD_U8, MERIT_PROBE_EXP2_F32) = range(4)
+
+
+def merit_probe_copy(src, dst, stream=None):
+    """Streaming copy of one device tensor into another of the same size (peak probe)."""
+    if src.numel() * src.element_size() != dst.numel() * dst.element_size():
+        raise ValueError("sizes differ")
+    _check(lib().merit_probe_copy(_dev_ptr(src, src.dtype, "src"), _dev_ptr(dst, dst.dtype, "dst"),
+                                  src.numel() * src.element_size(), _stream(stream)), "merit_probe_copy")
+
+
+def merit_probe_alu(which, workgroups, iters, sink, stream=None):
+    """Instruction-rate probe: workgroups x 4 wavefronts x iters x 8 instructions of one kind."""
+    import torch
+    if sink.numel() < workgroups * 256:
+        raise ValueError("sink too small")
+    _check(lib().merit_probe_alu(which, workgroups, iters, _dev_ptr(sink, torch.int32, "sink"), _stream(stream)),
+           "merit_probe_alu")
 
 
 def merit_plan_correlation(N, C, H, W, R, sd=1) -> Plan:

@@ -35,6 +35,7 @@ __global__ __launch_bounds__(256) void merit_sepfilter_tile(SepParams p, const f
     constexpr int C = K / 2, C4 = (C + 3) / 4 * 4, D = C4 - C;    // staged column 0 = image column x0 - C4
     constexpr int NWR = (D + 8 + K - 1 + 3) / 4;                  // 16-byte groups a row-pass unit reads
     constexpr int K4 = (K + 3) / 4;
+    constexpr int PR = 4;                                         // rows of a column-pass patch
     extern __shared__ __align__(16) float smem[];
     const int RH = p.TH + K - 1;                          // staged rows
     float *in = smem;                                     // [RH][PI]; later the row-pass result
@@ -62,18 +63,17 @@ __global__ __launch_bounds__(256) void merit_sepfilter_tile(SepParams p, const f
     // Staging: every element is a real (clamped) pixel.  A thread owns one 4-column group of
     // the staged rows r = tid / LPR + (256 / LPR) j; SB rows per batch, every load of a batch
     // issued before the first LDS write (one memory round trip per batch).
-    constexpr int SB = 8;
-    const int P4 = p.PI >> 2, W4 = p.W >> 2;
+    constexpr int SB = K <= 16 ? 8 : 12;                  // 8 rows per step: 64 or 96 staged rows at most
+    const int P4 = p.PI >> 2, W4 = p.W >> 2;              // P4 <= 32 for every K <= 32
     const bool vec = (p.W & 3) == 0;
-    const int lg = P4 <= 32 ? 5 : 6;                      // lanes per staged row: 32 or 64
+    constexpr int lg = 5;                                 // lanes per staged row
     const int cg = tid & ((1 << lg) - 1);
     const bool live = cg < P4;
-    const int rstep = 256 >> lg;
-    // Windows up to 16 taps stage at most 64 rows, one batch: then a workgroup requests its next
-    // tile before it computes the current one, so that loads, arithmetic and stores of the
-    // workgroups of a compute unit overlap instead of all running in the same phase.
-    constexpr bool PF = K <= 16;
-    const bool pf = PF && vec;
+    constexpr int rstep = 256 >> lg;
+    // One batch covers a tile, so a workgroup requests its next tile before it computes the
+    // current one: loads, arithmetic and stores of the workgroups of a compute unit overlap
+    // instead of all running in the same phase.
+    const bool pf = vec;
     float4v pre[SB];
     auto issue = [&](const Tile &T, int r0) {
         const int g4 = ((T.x0 - C4) >> 2) + cg;           // image 4-column group (may be outside)
@@ -115,11 +115,6 @@ __global__ __launch_bounds__(256) void merit_sepfilter_tile(SepParams p, const f
         const int x0 = T.x0, y0 = T.y0;
         if (pf) {
             commit(T, tid >> lg);
-        } else if (vec) {
-            for (int r0 = tid >> lg; r0 < RH; r0 += rstep * SB) {
-                issue(T, r0);
-                commit(T, r0);
-            }
         } else {
             const float *img = x + (size_t)T.n * p.H * p.W;
             const int total = RH * p.PI;
@@ -185,15 +180,16 @@ __global__ __launch_bounds__(256) void merit_sepfilter_tile(SepParams p, const f
         }
         __syncthreads();
 
-        // column pass: unit = 4 rows x 4 columns, column groups fastest: 16-byte LDS reads and
-        // 16-byte stores.  Row q of the K + 3 rows a unit reads feeds output row i with tap q - i.
+        // column pass: unit = PR rows x 4 columns, column groups fastest: 16-byte LDS reads and
+        // 16-byte stores.  Row q of the K + PR - 1 rows a unit reads feeds output row i with tap
+        // q - i.
         float *out = y + (size_t)T.n * p.H * p.W;
-        for (int u = tid; u < (p.TH / 4) * (TW / 4); u += 256) {
+        for (int u = tid; u < (p.TH / PR) * (TW / 4); u += 256) {
             const int rg = u >> 4, c4 = u & 15;
-            const float *src = mid + (4 * rg) * p.PI + 4 * c4;
-            float4v o[4];
+            const float *src = mid + (PR * rg) * p.PI + 4 * c4;
+            float4v o[PR];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) o[i] = (float4v){0.0f, 0.0f, 0.0f, 0.0f};
+            for (int i = 0; i < PR; ++i) o[i] = (float4v){0.0f, 0.0f, 0.0f, 0.0f};
             float wt[4 * K4];
 #pragma unroll
             for (int g = 0; g < K4; ++g) {
@@ -201,10 +197,10 @@ __global__ __launch_bounds__(256) void merit_sepfilter_tile(SepParams p, const f
                 wt[4 * g] = w.x; wt[4 * g + 1] = w.y; wt[4 * g + 2] = w.z; wt[4 * g + 3] = w.w;
             }
 #pragma unroll
-            for (int q = 0; q < K + 3; ++q) {
+            for (int q = 0; q < K + PR - 1; ++q) {
                 const float4v v = *reinterpret_cast<const float4v *>(src + q * p.PI);
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
+                for (int i = 0; i < PR; ++i)
                     if (q - i >= 0 && q - i < K) {
                         o[i].x = fmaf(wt[q - i], v.x, o[i].x);
                         o[i].y = fmaf(wt[q - i], v.y, o[i].y);
@@ -214,8 +210,8 @@ __global__ __launch_bounds__(256) void merit_sepfilter_tile(SepParams p, const f
             }
             const int gx = x0 + 4 * c4;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int gy = y0 + 4 * rg + i;
+            for (int i = 0; i < PR; ++i) {
+                const int gy = y0 + PR * rg + i;
                 if (gy >= p.H) continue;
                 float *dst = out + (size_t)gy * p.W + gx;
                 if (vec) {

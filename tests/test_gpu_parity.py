@@ -943,3 +943,30 @@ def test_bilateral_workload_sampled(mb):
     assert got.min() >= x.min() and got.max() <= x.max()
     # it denoises: closer to the noise-free steps than the input on flat areas
     assert np.abs(np.diff(got, axis=2)).mean() < 0.5 * np.abs(np.diff(x.astype(np.float64), axis=2)).mean()
+
+
+# -------------------------------------------------- peak probes
+def test_probe_copy_and_alu_loops(mb):
+    src = torch.arange(4 * 1000 + 4, dtype=torch.float32, device="cuda:0")       # not a multiple of the step
+    buf, dst, p = guarded_empty((src.numel(),), torch.float32, 777.0)
+    mb.merit_probe_copy(src, dst)
+    torch.cuda.synchronize()
+    check_canary(buf, p, 777.0)
+    assert torch.equal(dst, src)
+    sink = torch.full((3 * 256,), -1, dtype=torch.int32, device="cuda:0")
+    for which in (mb.MERIT_PROBE_MFMA_F16, mb.MERIT_PROBE_FMA_F32, mb.MERIT_PROBE_SAD_U8, mb.MERIT_PROBE_EXP2_F32):
+        sink.fill_(-1)
+        mb.merit_probe_alu(which, 3, 5, sink)
+        torch.cuda.synchronize()
+        assert not bool((sink == -1).all())
+    # v_sad_u8 chain c after 5 steps: c + 5 * sum_bytes |(p + c) - q|, p = lane seed, q = p ^ 0x5a5a5a5a
+    mb.merit_probe_alu(mb.MERIT_PROBE_SAD_U8, 1, 5, sink)
+    torch.cuda.synchronize()
+    t = 7
+    pz = (t * 2654435761 + 0) & 0xFFFFFFFF
+    q = pz ^ 0x5A5A5A5A
+    want = 0
+    for c in range(8):
+        a = (pz + c) & 0xFFFFFFFF
+        want += c + 5 * sum(abs(((a >> (8 * b)) & 255) - ((q >> (8 * b)) & 255)) for b in range(4))
+    assert int(sink[t].item()) & 0xFFFFFFFF == want & 0xFFFFFFFF
