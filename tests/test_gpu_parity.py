@@ -812,6 +812,11 @@ SEP_CASES = [
     (1, 9, 9, 32, None),         # window much larger than the image: everything clamps
     (2, 50, 66, 7, None),        # width not a multiple of 4: scalar staging and stores
     (3, 32, 64, 9, 64),          # tile taller than the image
+    (2, 37, 300, 3, None),       # several column tiles, the last ragged
+    (1, 50, 1032, 9, None),      # seventeen column tiles
+    (1, 9, 12, 8, None),         # three column groups: everything near an edge
+    (3, 16, 256, 6, None),       # exactly four column tiles
+    (1, 5, 4, 5, None),          # a single column group, window wider than the image
 ]
 
 
@@ -853,6 +858,16 @@ def test_sepfilter_impulse_is_exact(mb):
     y = mb.merit_sepfilter(mb.merit_plan_sepfilter(1, H, W, k), dev(x), dev(kx), dev(ky)).cpu().numpy()
     assert np.array_equal(y, oracle.sepfilter(x, kx, ky))
     assert y[0, 33 - 0 + 3, 64 - 5 + 3] == ky[0] * kx[5]
+    # the same on a width that is a multiple of 4 (aligned 16-byte staging), impulses at a tile
+    # boundary (column 255 | 256) and in the corners
+    W = 520
+    x = np.zeros((1, H, W), np.float32)
+    x[0, 33, 255] = 1.0
+    x[0, 40, 256] = 3.0
+    x[0, 0, 0] = 2.0
+    x[0, H - 1, W - 1] = 5.0
+    y = mb.merit_sepfilter(mb.merit_plan_sepfilter(1, H, W, k), dev(x), dev(kx), dev(ky)).cpu().numpy()
+    assert np.array_equal(y, oracle.sepfilter(x, kx, ky))
 
 
 def test_sepfilter_workloads_sampled(mb):
