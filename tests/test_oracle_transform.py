@@ -86,3 +86,56 @@ def test_transformed_tensor_sizes():
     MB, _ = lit.transform(Bmat, (m, n, kk), tb, 2, "zero")
     assert MA.shape == MB.shape == (m * n, kk)
     assert np.allclose((MA * MB).sum(axis=1).reshape(m, n), Amat @ Bmat)
+
+
+def test_dilated_index_expression():
+    """I[a1, p2 + 2 a2, p3 + 2 a3]: the window indices move two input pixels per step."""
+    g = _read("dilated_index.txt")
+    assert g["row"][0] == ["p2", "1", "a2", "2"] and g["column"][0] == ["p3", "1", "a3", "2"]
+    ranges, n_par, tx, tw = lit.conv2d_desc(1, 3, 20, 22, 4, 3, 3, 1, 1, 0, 0, 2, 2)
+    x = lit.coordinates(ranges, tx, 4)
+    k = np.indices(ranges)
+    assert np.array_equal(x[1], k[4])
+    assert np.array_equal(x[2], k[2] + 2 * k[5]) and np.array_equal(x[3], k[3] + 2 * k[6])
+    assert ranges[2:4] == (20 - 4, 22 - 4)                  # extent of the dilated window: 2 (k - 1) + 1
+
+
+def test_correlation_index_expression():
+    """Eq. 8 with the displacement indices centred (p3 - R) and strided as the workload needs;
+    at R = 0 offsets and stride 1 it is the printed expression."""
+    g = _read("correlation_index.txt")
+    assert ["row", "p1", "p3"] in g["i2"] and ["column", "p2", "p4"] in g["i2"] and ["row", "p1"] in g["i1"]
+    ranges, n_par, t1, t2 = lit.correlation_desc(1, 4, 6, 7, 2, 1)
+    k = np.indices(ranges)                                  # (n, p1, p2, p3, p4 | a1)
+    x1 = lit.coordinates(ranges, t1, 4)
+    x2 = lit.coordinates(ranges, t2, 4)
+    assert np.array_equal(x1[1], k[5]) and np.array_equal(x1[2], k[1]) and np.array_equal(x1[3], k[2])
+    assert np.array_equal(x2[1], k[5])
+    assert np.array_equal(x2[2], k[1] + k[3] - 2) and np.array_equal(x2[3], k[2] + k[4] - 2)
+
+
+def test_bilateral_call_descriptor():
+    """Listing 3: window indices on the two image axes at offset -k/2, stride 1; 16 x 16 tiles."""
+    g = _read("bilateral_call.txt")
+    assert g["acc"] == [["0", "-k/2", "1"], ["1", "-k/2", "1"]] and g["tile"][0] == ["16", "16"]
+    k = 5
+    ranges, n_par, t_row, t_col, t_ker = lit.sepfilter_desc(1, 9, 10, k)
+    # the row pass carries the a2 triple {1,-k/2,1}, the column pass the a1 triple {0,-k/2,1}
+    # (image axes 1 and 2 here: axis 0 is the batch)
+    assert (t_col.axis[3], t_col.offset[3], t_col.stride[3]) == (1, -(k // 2), 1)
+    assert (t_row.axis[3], t_row.offset[3], t_row.stride[3]) == (2, -(k // 2), 1)
+    # a 16 x 16 tile of outputs with the k x k window covers (16 + k - 1)^2 pixels (Eq. 9)
+    both = lit.Transform(axis=(0, 1, 2, 1, 2), stride=(1,) * 5, offset=(0, 0, 0, -(k // 2), -(k // 2)))
+    assert lit.footprint((1, 16, 16, k, k), both, 3) == (1, 16 + k - 1, 16 + k - 1)
+
+
+def test_workload_table_shapes_are_the_synthetic_workloads():
+    from paper_1911_03458_amd import workloads as wl
+    g = _read("workload_table.txt")
+    assert [int(v) for v in g["dilated"][0]] == [wl.CFG_DILATED.OH, wl.CFG_DILATED.OW, wl.CFG_DILATED.Cout]
+    c = wl.CFG_CORRELATION
+    assert [int(v) for v in g["correlation"][0]] == [c.H, c.W, 2 * c.search + 1, 2 * c.search + 1]
+    d = wl.CFG_DEPTHWISE
+    assert [int(v) for v in g["depthwise"][0]] == [d.H, d.W, d.C]
+    m = wl.CFG_ME_720P
+    assert g["motion_estimation"][0] == ["720p", "8", "8"] and (m.H, m.W, m.block) == (720, 1280, 8)
