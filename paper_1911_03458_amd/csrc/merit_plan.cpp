@@ -352,7 +352,7 @@ merit_status derive_bilateral(merit_plan *pl)
     p.tiles_x = (int)cdiv(W, 64);
     p.PI = (int)round_up(64 + p.c4 + (k - 1 - c), 4);
     const int64_t RH = 16 + k - 1;
-    p.lds_bytes = (int)((RH * p.PI + 2 * k) * 4);
+    p.lds_bytes = (int)((RH * p.PI + 2 * k + 4) * 4);     // + one 16-byte group: whole-group reads of the last row
     p.scale = 0.0f; p.neg = 1;
     const int64_t grid = N * p.tiles_y * p.tiles_x;
     if (grid >= INT_LIMIT || !fastdiv_ok(grid, p.tiles_x) || !fastdiv_ok(N * p.tiles_y, p.tiles_y) ||
@@ -365,7 +365,7 @@ merit_status derive_bilateral(merit_plan *pl)
     pl->out_ndim = 3;
     pl->out_shape[0] = N; pl->out_shape[1] = H; pl->out_shape[2] = W;
     merit_launch_info &li = pl->info;
-    li.kernel = "merit_bilateral_tile";
+    li.kernel = k <= 16 ? "merit_bilateral_rows" : "merit_bilateral_tile";   // four outputs along a row / down a column
     li.grid[0] = grid; li.grid[1] = 1; li.grid[2] = 1;
     li.block[0] = 256; li.block[1] = 1; li.block[2] = 1;
     li.lds_bytes = p.lds_bytes;

@@ -181,7 +181,8 @@ def test_bilateral_plan():
     assert tuple(d.range[:5]) == (1, 1080, 1920, 9, 9) and plan.out_shape() == (1, 1080, 1920)
     assert (d.a.offset[3], d.a.offset[4]) == (-4, -4)            # Listing 3: {0,-k/2,1}, {1,-k/2,1}
     li = plan.launch_info()
-    assert li["kernel"] == "merit_bilateral_tile" and li["tile"][1:3] == (16, 64)      # the listing's 16-row tiles
+    assert li["kernel"] == "merit_bilateral_rows" and li["tile"][1:3] == (16, 64)      # the listing's 16-row tiles
+    assert mb.merit_plan_bilateral(1, 64, 64, 21).launch_info()["kernel"] == "merit_bilateral_tile"
     assert li["grid"][0] == 68 * 30
     assert plan.footprint(0, (1, 16, 64, 9, 9)) == (1, 24, 72)
     with pytest.raises(mb.MeritError) as e:
