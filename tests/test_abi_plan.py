@@ -399,3 +399,44 @@ def test_conv_variant_selection():
     assert mb.merit_plan_conv2d(8, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1).launch_info()["kernel"] == "merit_conv2d_chblock"
     li = mb.merit_plan_conv2d(8, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1).launch_info()
     assert li["lds_bytes"] <= 160 * 1024
+
+
+def test_plans_for_extreme_shapes_are_sane_or_refused():
+    """Planning is host arithmetic only: very large or degenerate shapes must come back as a plan
+    whose launch fits the chip (grid > 0, LDS <= 160 KB) or as a clean refusal, never anything else."""
+    def ok(make, *a):
+        try:
+            plan = make(*a)
+        except mb.MeritError as e:
+            assert e.status in (mb.MERIT_ERR_UNSUPPORTED, mb.MERIT_ERR_SHAPE, mb.MERIT_ERR_INVALID_ARG), (a, e.status)
+            return None
+        li = plan.launch_info()
+        assert 0 <= li["lds_bytes"] <= 160 * 1024, (a, li)
+        assert all(g >= 0 for g in li["grid"]) and li["block"][0] in (256, 512), (a, li)
+        n_out = 1
+        for e in plan.out_shape():
+            n_out *= e
+        assert (n_out == 0) == (li["grid"][0] == 0) or li["grid"][0] > 0, (a, li)
+        return plan
+    for a in [(1 << 16, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3),         # 4 GiB of input: no 32-bit buffer offsets
+              (1, 3, 4096, 4096, 64, 7, 7, 2, 2, 3, 3),             # very wide rows
+              (1, 4096, 8, 8, 4096, 3, 3, 1, 1, 1, 1),              # many channels, tiny image
+              (1, 64, 1024, 1024, 64, 3, 3, 1, 1, 1, 1),            # staged rows beyond LDS?
+              (0, 3, 32, 32, 8, 3, 3, 1, 1, 1, 1),                  # empty batch
+              (2, 5, 7, 9, 3, 7, 9, 3, 2, 3, 4)]:                   # window as large as the padded image
+        ok(mb.merit_plan_conv2d, *a)
+        ok(mb.merit_plan_conv2d_relu, *a)
+        ok(lambda *b: mb.merit_plan_conv2d_residual(*b, 1), *a)
+        ok(lambda *b: mb.merit_plan_conv2d_pool(*b, 1), *a)
+    for a in [(1 << 14, 256, 112, 112, 3, 3, 2, 2, 1, 1, 0), (1, 1, 1, 1, 3, 3, 2, 2, 1, 1, 1),
+              (4, 4, 8192, 8192, 2, 2, 2, 2, 0, 0, 0), (0, 8, 16, 16, 3, 3, 2, 2, 1, 1, 0)]:
+        ok(mb.merit_plan_pool2d, *a)
+    for a in [(4320, 7680, 16, 32), (16, 16, 16, 63), (17, 33, 32, 0), (8, 8, 8, 64), (1, 1, 4, 1)]:
+        ok(mb.merit_plan_sad, *a)
+    for a in [(1 << 12, 1080, 1920, 3), (1, 1, 1, 32), (1, 100000, 8, 5), (0, 64, 64, 9)]:
+        ok(mb.merit_plan_sepfilter, *a)
+        ok(mb.merit_plan_bilateral, *a)
+    for a in [(64, 1024, 64, 64, 15, 8), (1, 1, 8, 8, 0, 1), (1, 256, 64, 60, 5, 2)]:
+        ok(mb.merit_plan_correlation, *a)
+    for a in [(1 << 10, 1024, 112, 112, 3, 3, 1, 1, 1, 1), (1, 1, 3, 8192, 5, 5, 2, 2, 2, 2)]:
+        ok(mb.merit_plan_conv2d_depthwise, *a)
