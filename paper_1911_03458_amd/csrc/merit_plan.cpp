@@ -714,7 +714,7 @@ merit_status derive_corr(merit_plan *pl)
     p.lead = (int)round_up(R * sd, 8);
     p.cols2 = (int)round_up(64 + p.lead + R * sd, 8);
     const int64_t per_group = (64 + (int64_t)p.cols2) * 16;
-    int64_t chg = (80 * 1024) / per_group;                 // two workgroups per CU share its 160 KB of LDS
+    int64_t chg = (40 * 1024) / per_group;                 // four workgroups per CU share its 160 KB of LDS (measured best)
     if (chg < 1) chg = 1;
     p.chg = (int)(chg < p.nchi ? chg : p.nchi);
     const int64_t grid = N * H * n * p.xchunks;
