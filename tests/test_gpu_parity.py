@@ -985,3 +985,31 @@ def test_probe_copy_and_alu_loops(mb):
         a = (pz + c) & 0xFFFFFFFF
         want += c + 5 * sum(abs(((a >> (8 * b)) & 255) - ((q >> (8 * b)) & 255)) for b in range(4))
     assert int(sink[t].item()) & 0xFFFFFFFF == want & 0xFFFFFFFF
+
+
+# -------------------------------------------------- streams
+def test_launches_follow_the_given_stream(mb):
+    """Every entry point enqueues on the stream it is handed (default priority) and returns:
+    work queued behind a producer on a side stream sees the producer's output, and the plan can
+    be shared by two streams."""
+    side = torch.cuda.Stream()
+    c = wl.CFG1_POOL
+    x = wl.make_pool_input(c, N=2)
+    plan = mb.merit_plan_pool2d(2, c.C, c.H, c.W, c.kh, c.kw, c.sh, c.sw, c.ph, c.pw, 0)
+    dx = torch.empty(x.shape, dtype=torch.float32, device="cuda:0")
+    host = torch.empty(x.shape, dtype=torch.float32, pin_memory=True)      # freshly allocated pinned memory
+    host.copy_(torch.from_numpy(x))
+    with torch.cuda.stream(side):
+        dx.copy_(host, non_blocking=True)                   # producer on the side stream
+        y_side = mb.merit_pool2d(plan, dx, stream=side)     # consumer behind it, same stream
+        sep = mb.merit_plan_sepfilter(2 * c.C, c.H, c.W, 3)
+        taps = torch.tensor([0.25, 0.5, 0.25], device="cuda:0")
+        z_side = mb.merit_sepfilter(sep, dx.view(2 * c.C, c.H, c.W), taps, taps, stream=side)
+    side.synchronize()
+    y_main = mb.merit_pool2d(plan, dx)                      # the same plan on the current stream
+    torch.cuda.synchronize()
+    ref = oracle.pool2d(x, (c.kh, c.kw), (c.sh, c.sw), (c.ph, c.pw), "max")
+    assert np.array_equal(y_side.cpu().numpy(), ref) and np.array_equal(y_main.cpu().numpy(), ref)
+    zr = oracle.sepfilter(x.reshape(2 * c.C, c.H, c.W), np.array([0.25, 0.5, 0.25], np.float32),
+                          np.array([0.25, 0.5, 0.25], np.float32))
+    assert np.allclose(z_side.cpu().numpy(), zr, rtol=0, atol=1e-5 * float(np.abs(x).max()))
