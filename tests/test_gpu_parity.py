@@ -1013,3 +1013,41 @@ def test_launches_follow_the_given_stream(mb):
     zr = oracle.sepfilter(x.reshape(2 * c.C, c.H, c.W), np.array([0.25, 0.5, 0.25], np.float32),
                           np.array([0.25, 0.5, 0.25], np.float32))
     assert np.allclose(z_side.cpu().numpy(), zr, rtol=0, atol=1e-5 * float(np.abs(x).max()))
+
+
+def test_launches_can_be_captured_in_a_graph(mb):
+    """The entry points neither allocate nor synchronise, so a stream capture records them
+    (after one eager call per kernel instance, which raises that instance's LDS limit).  The
+    graph is replayed several times with eager work in between and every replay is checked."""
+    rng = np.random.default_rng(77)
+    shape = (2, 8, 30, 36)
+    pmax = mb.merit_plan_pool2d(*shape, 3, 3, 2, 2, 1, 1, 0)
+    pavg = mb.merit_plan_pool2d(*shape, 3, 3, 2, 2, 1, 1, 1)
+    conv = mb.merit_plan_conv2d_relu(2, 16, 30, 36, 32, 3, 3, 1, 1, 1, 1)
+    x = torch.zeros(shape, dtype=torch.float32, device="cuda:0")
+    xh = torch.zeros((2, 16, 30, 36), dtype=torch.float16, device="cuda:0")
+    w = rng.standard_normal((32, 16, 3, 3)).astype(np.float16) / 12
+    dw = dev(w)
+    ymax = torch.empty(pmax.out_shape(), dtype=torch.float32, device="cuda:0")
+    yavg = torch.empty(pavg.out_shape(), dtype=torch.float32, device="cuda:0")
+    yc = torch.empty(conv.out_shape(), dtype=torch.float16, device="cuda:0")
+    mb.merit_pool2d(pmax, x, ymax); mb.merit_pool2d(pavg, x, yavg); mb.merit_conv2d(conv, xh, dw, yc)   # eager first
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        mb.merit_pool2d(pmax, x, ymax)
+        mb.merit_pool2d(pavg, x, yavg)
+        mb.merit_conv2d(conv, xh, dw, yc)
+    for rep in range(3):
+        xv = rng.standard_normal(shape).astype(np.float32)
+        xc = rng.standard_normal((2, 16, 30, 36)).astype(np.float16)
+        x.copy_(torch.from_numpy(xv)); xh.copy_(torch.from_numpy(xc))          # eager work between replays
+        ymax.fill_(-7.0); yavg.fill_(-7.0); yc.fill_(-7.0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(ymax.cpu().numpy(), oracle.pool2d(xv, (3, 3), (2, 2), (1, 1), "max")), rep
+        ra = oracle.pool2d(xv, (3, 3), (2, 2), (1, 1), "avg")
+        assert np.all(np.abs(yavg.cpu().numpy() - ra) <= 1e-5 * np.abs(ra) + 1e-6), rep
+        rc = oracle.conv2d(xc, w, (1, 1), (1, 1), relu=True).astype(np.float64)
+        assert np.all(np.abs(yc.cpu().numpy().astype(np.float64) - rc) <= 2e-2 * np.abs(rc) + 1e-3), rep
