@@ -94,14 +94,25 @@ __global__ __launch_bounds__(256) void merit_dwconv_rows_k3s1p1(DwParams p, cons
 #pragma unroll
     for (int i = 0; i < 9; ++i) wk[i] = h2f(w[(size_t)c * 9 + i]);
 
-    for (int i = tid; i < RH * pitch8; i += 256) {
-        const int r = (int)fdiv((uint32_t)i, p.div_pitch);
-        const int c8 = i - r * pitch8;                      // 0 and W8+1 are the zero chunks
-        const int gy = oy0 - 1 + r;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (gy >= 0 && gy < p.H && c8 >= 1 && c8 <= W8)
-            v = *reinterpret_cast<const uint4 *>(xp + (size_t)gy * p.W + 8 * (c8 - 1));
-        xl[i] = v;
+    // batches of SB chunks per thread, every load issued before the first LDS write (one memory
+    // round trip per batch); a chunk outside the plane re-reads the plane's first bytes and is zeroed
+    constexpr int SB = 4;
+    const int total = RH * pitch8;
+    for (int i0 = tid; i0 < total; i0 += 256 * SB) {
+        uint4 v[SB];
+        bool in[SB];
+#pragma unroll
+        for (int b = 0; b < SB; ++b) {
+            const int i = min(i0 + 256 * b, total - 1);
+            const int r = (int)fdiv((uint32_t)i, p.div_pitch);
+            const int c8 = i - r * pitch8;                  // 0 and W8+1 are the zero chunks
+            const int gy = oy0 - 1 + r;
+            in[b] = gy >= 0 && gy < p.H && c8 >= 1 && c8 <= W8;
+            v[b] = *reinterpret_cast<const uint4 *>(in[b] ? xp + (size_t)gy * p.W + 8 * (c8 - 1) : xp);
+        }
+#pragma unroll
+        for (int b = 0; b < SB; ++b)
+            if (i0 + 256 * b < total) xl[i0 + 256 * b] = in[b] ? v[b] : make_uint4(0, 0, 0, 0);
     }
     __syncthreads();
 
