@@ -213,8 +213,8 @@ merit_status derive_sad(merit_plan *pl)
     int64_t grid = (int64_t)p.nby * p.nbx;
     int64_t lds = ((int64_t)p.win * (p.pitch / 4) + 1 + B * (B / 4) + 4) * 4;
     int64_t tile_bx = 1;
-    // (the row-scan kernels fetch the current block in aligned dwords: B must divide W; any H)
-    const bool rowscan_ok = W % B == 0;
+    // (the row-scan kernels fetch the current block in aligned dwords: W % 4 == 0; any H)
+    const bool rowscan_ok = W % 4 == 0;
     if (rowscan_ok && B == 16 && (R == 16 || R == 32) && pl->tile_req[1] != 1) {
         const int64_t c4 = cdiv(4 * 16 + 2 * R, 4);
         if (fastdiv_ok((16 + 2 * R) * c4, c4)) {

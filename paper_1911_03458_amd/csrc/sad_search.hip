@@ -202,14 +202,28 @@ __global__ __launch_bounds__(256) void merit_sad_rowscan16(SadParams p, const ui
     // current block: wave-uniform loads
     uint32_t c[16][4];
     {
-        // rows past the last one (H % 16 != 0) repeat it
-        const uint32_t *cp = reinterpret_cast<const uint32_t *>(cur + bx * 16);
+        // rows past the last one (H % 16 != 0) repeat it; dwords past the end of a row
+        // (W % 16 != 0, W % 4 == 0) are four copies of its last pixel
+        const uint32_t *cp = reinterpret_cast<const uint32_t *>(cur);
         const int W4 = p.W >> 2;
+        if ((p.W & 15) == 0) {                       // whole blocks per row: the plain loads
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int row = min(by * 16 + i, p.H - 1);
+            for (int i = 0; i < 16; ++i) {
+                const int row = min(by * 16 + i, p.H - 1);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) c[i][j] = cp[row * W4 + j];
+                for (int j = 0; j < 4; ++j) c[i][j] = cp[row * W4 + bx * 4 + j];
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int row = min(by * 16 + i, p.H - 1);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int d = bx * 4 + j;
+                    const uint32_t v = cp[row * W4 + min(d, W4 - 1)];
+                    c[i][j] = d < W4 ? v : (v >> 24) * 0x01010101u;
+                }
+            }
         }
     }
 
@@ -360,14 +374,28 @@ __global__ __launch_bounds__(256) void merit_sad_rowscan_pair(SadParams p, const
 
     uint32_t c[B][B4];
     {
-        // rows past the last one (H % B != 0) repeat it
-        const uint32_t *cp = reinterpret_cast<const uint32_t *>(cur + min(bx, p.nbx - 1) * B);
+        // rows past the last one (H % B != 0) repeat it; dwords past the end of a row
+        // (W % B != 0, W % 4 == 0) are four copies of its last pixel
+        const uint32_t *cp = reinterpret_cast<const uint32_t *>(cur);
         const int W4 = p.W >> 2;
+        const int d0 = min(bx, p.nbx - 1) * B4;
+        if ((p.W & (B - 1)) == 0) {                  // whole blocks per row: the plain loads
 #pragma unroll
-        for (int i = 0; i < B; ++i) {
-            const int row = min(by * B + i, p.H - 1);
+            for (int i = 0; i < B; ++i) {
+                const int row = min(by * B + i, p.H - 1);
 #pragma unroll
-            for (int j = 0; j < B4; ++j) c[i][j] = cp[row * W4 + j];
+                for (int j = 0; j < B4; ++j) c[i][j] = cp[row * W4 + d0 + j];
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < B; ++i) {
+                const int row = min(by * B + i, p.H - 1);
+#pragma unroll
+                for (int j = 0; j < B4; ++j) {
+                    const uint32_t v = cp[row * W4 + min(d0 + j, W4 - 1)];
+                    c[i][j] = d0 + j < W4 ? v : (v >> 24) * 0x01010101u;
+                }
+            }
         }
     }
 

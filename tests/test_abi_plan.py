@@ -300,16 +300,17 @@ def test_launch_info_tiles_cover_the_output():
 
 
 def test_block_matching_plan_for_frames_the_block_does_not_divide():
-    """ceil(H/B) x ceil(W/B) blocks; the row-scan kernels need whole blocks per row of dwords
-    (B divides W) but any height; otherwise the one-block-per-workgroup kernel runs."""
+    """ceil(H/B) x ceil(W/B) blocks; the row-scan kernels need rows of whole dwords
+    (W % 4 == 0) but any height; otherwise the one-block-per-workgroup kernel runs."""
     full_hd = mb.merit_plan_sad(1080, 1920, 16, 32)             # 1080 = 67.5 blocks
     assert full_hd.out_shape() == (68, 120)
     assert tuple(full_hd.desc().range[:2]) == (68, 120)
     li = full_hd.launch_info()
     assert li["kernel"] == "merit_sad_rowscan16<32>" and li["grid"][0] == 68 * 30
     odd_w = mb.merit_plan_sad(64, 60, 8, 4)
-    assert odd_w.out_shape() == (8, 8) and odd_w.launch_info()["kernel"] == "merit_sad_generic"
-    assert mb.merit_plan_sad(90, 100, 16, 16).launch_info()["kernel"] == "merit_sad_generic"   # 100 = 6.25 blocks
+    assert odd_w.out_shape() == (8, 8) and odd_w.launch_info()["kernel"] == "merit_sad_generic"   # no kernel for R = 4
+    assert mb.merit_plan_sad(90, 100, 16, 16).launch_info()["kernel"].startswith("merit_sad_rowscan_pair")  # 6.25 blocks
+    assert mb.merit_plan_sad(90, 98, 16, 16).launch_info()["kernel"] == "merit_sad_generic"    # rows of 24.5 dwords
     assert mb.merit_plan_sad(90, 96, 16, 16).launch_info()["kernel"].startswith("merit_sad_rowscan_pair")
     d = odd_w.desc()
     d.range[1] = 7                                              # the floor: a block column missing

@@ -227,7 +227,11 @@ RAGGED_SAD_CASES = [
     # H   W   B  R  tile      kernel                       (frames the block does not divide)
     (30, 29, 8, 2, None, "merit_sad_generic"),              # both extents ragged, W not a multiple of 4
     (27, 40, 8, 3, None, "merit_sad_generic"),              # ragged height only
-    (32, 44, 8, 8, None, "merit_sad_generic"),              # ragged width keeps the row-scan kernels out
+    (32, 46, 8, 8, None, "merit_sad_generic"),              # rows that are not whole dwords keep the row-scan kernels out
+    (32, 44, 8, 8, None, "merit_sad_rowscan_pair<8,8>"),    # last block column: 4 of 8 columns inside
+    (50, 100, 16, 16, None, "merit_sad_rowscan_pair<16,16>"),  # 6.25 x 3.125 blocks
+    (50, 100, 16, 16, (0, 4), "merit_sad_rowscan16<16>"),
+    (40, 72, 16, 32, None, "merit_sad_rowscan16<32>"),      # 4.5 block columns
     (5, 7, 8, 1, None, "merit_sad_generic"),                # frame smaller than one block
     (36, 64, 8, 8, None, "merit_sad_rowscan_pair<8,8>"),    # last block row: 4 of 8 rows inside
     (41, 96, 16, 16, None, "merit_sad_rowscan_pair<16,16>"),  # last block row: 9 of 16 rows inside
