@@ -139,6 +139,7 @@ struct CorrParams {
     int xchunks;                // 64-pixel chunks per image row
     int cols2;                  // staged columns of the second tensor per chunk (multiple of 8)
     int lead;                   // columns staged left of the chunk's first pixel (multiple of 8, >= R*sd)
+    int xq, xr;                 // grid / 8 and grid % 8: hardware workgroup id -> one contiguous band of work per XCD
     FastDiv div_n, div_xchunks, div_h;
 };
 

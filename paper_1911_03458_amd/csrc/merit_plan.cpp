@@ -720,6 +720,7 @@ merit_status derive_corr(merit_plan *pl)
     const int64_t grid = N * H * n * p.xchunks;
     if (grid >= INT_LIMIT || !fastdiv_ok(grid, p.xchunks) || !fastdiv_ok(grid, n) || !fastdiv_ok(grid, H))
         return MERIT_ERR_UNSUPPORTED;
+    p.xq = (int)(grid / 8); p.xr = (int)(grid % 8);
     p.div_xchunks = make_fastdiv((uint32_t)p.xchunks);
     p.div_n = make_fastdiv((uint32_t)n);
     p.div_h = make_fastdiv((uint32_t)H);
