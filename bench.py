@@ -301,8 +301,10 @@ def bench_corr(torch, mb, wl, cfg, steps, warmup):
         "workload": cfg.name, "kernel": plan.launch_info()["kernel"], "avg_launch_us": t * 1e6,
         "out_elems_per_s": y.numel() / t, "achieved_tflops": flops / t / 1e12,
         "achieved_hbm_gbs": alg_bytes / t / 1e9, "hbm_frac": alg_bytes / t / 1e9 / HBM_PEAK_GBS,
-        "roofline": {"bound": "alu", "achieved": flops / 4 / t / 1e12, "peak": VALU_PEAK_TOPS,
-                     "unit": "T lane-ops/s (v_dot2: 2 MACs)", "frac": flops / 4 / t / 1e12 / VALU_PEAK_TOPS},
+        "mfma_frac": flops / t / 1e12 / MFMA_F16_PEAK_TFLOPS,
+        # both ideal times are far below a launch (bytes: 0.65 us, flops: 0.1 us); the larger one is quoted
+        "roofline": {"bound": "hbm", "achieved": alg_bytes / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": alg_bytes / t / 1e9 / HBM_PEAK_GBS},
     }
 
 

@@ -132,15 +132,25 @@ const char *sad_kernel_name(const SadParams &p);
 const char *conv_kernel_name(const ConvParams &p);
 
 // ---- correlation layer -----------------------------------------------------
+// One staging unit = 8 pixels x 8 channels.  One unit per thread and pass measured best: fewer
+// registers (five wavefronts per SIMD) beat fewer, larger passes.
+constexpr int CORR_XB = 1;            // staging units a thread holds in registers per pass
+constexpr int CORR_LDS_KB = 40;       // LDS per workgroup at most: four workgroups and more per CU
 struct CorrParams {
     int N, C, H, W, R, sd, n;   // n = 2R+1 displacements per axis, sd = displacement stride
     int nchi;                   // channel groups of 8 (C padded)
-    int chg;                    // channel groups staged per pass
+    int chg;                    // channel groups staged per pass (a multiple of 4 = one MFMA reduction step)
     int xchunks;                // 64-pixel chunks per image row
     int cols2;                  // staged columns of the second tensor per chunk (multiple of 8)
     int lead;                   // columns staged left of the chunk's first pixel (multiple of 8, >= R*sd)
     int xq, xr;                 // grid / 8 and grid % 8: hardware workgroup id -> one contiguous band of work per XCD
-    FastDiv div_n, div_xchunks, div_h;
+    // staged rows are stored by residue class of the column modulo sd: position = class * pitch + column / sd
+    int pitch1, P1;             // first tensor: positions per class (ceil(64/sd)), positions per channel group
+    int pitch2, P2;             // second tensor: ceil(cols2/sd), sd * pitch2
+    int nsb, nblk;              // 16-pixel blocks per class, blocks per chunk (sd * nsb <= 8)
+    int nb;                     // 16-column blocks of the second tensor per pixel block: ceil((16 + 2R) / 16)
+    FastDiv div_n, div_xchunks, div_h, div_sd;
+    FastDiv div_perg, div_perg_last;   // staging units per channel group: full chunks, the last chunk of a row
 };
 
 // ---- depthwise convolution -----------------------------------------------------

@@ -713,10 +713,25 @@ merit_status derive_corr(merit_plan *pl)
     p.xchunks = (int)cdiv(W, 64);
     p.lead = (int)round_up(R * sd, 8);
     p.cols2 = (int)round_up(64 + p.lead + R * sd, 8);
-    const int64_t per_group = (64 + (int64_t)p.cols2) * 16;
-    int64_t chg = (40 * 1024) / per_group;                 // four workgroups per CU share its 160 KB of LDS (measured best)
-    if (chg < 1) chg = 1;
-    p.chg = (int)(chg < p.nchi ? chg : p.nchi);
+    // staged rows ordered by residue class of the column modulo sd (the 16 pixels of an MFMA block are adjacent)
+    p.pitch1 = (int)cdiv(64, sd); p.P1 = (int)(sd * p.pitch1);
+    p.pitch2 = (int)cdiv(p.cols2, sd); p.P2 = (int)(sd * p.pitch2);
+    p.nsb = (int)cdiv(p.pitch1, 16); p.nblk = (int)(sd * p.nsb);
+    p.nb = (int)cdiv(16 + 2 * R, 16);
+    // channel groups per pass: whole reduction steps of 4 groups, at most two staging units per
+    // thread, and about 40 KB so that four workgroups share a CU's LDS (measured best)
+    const int64_t per_g_full = 8 + p.cols2 / 8;
+    const int64_t per_group = ((int64_t)p.P1 + p.P2) * 16;
+    int64_t chg = (CORR_LDS_KB * 1024) / per_group;
+    if (chg > 256 * CORR_XB / per_g_full) chg = 256 * CORR_XB / per_g_full;
+    chg = chg / 4 * 4;
+    if (chg < 4) chg = 4;
+    const int64_t nchi4 = round_up(p.nchi, 4);
+    p.chg = (int)(chg < nchi4 ? chg : nchi4);
+    if (p.chg * per_g_full > 256 * CORR_XB || p.chg * per_group > LDS_LIMIT) return MERIT_ERR_UNSUPPORTED;
+    p.div_sd = make_fastdiv((uint32_t)sd);
+    p.div_perg = make_fastdiv((uint32_t)per_g_full);
+    p.div_perg_last = make_fastdiv((uint32_t)((W % 64) / 8 + p.cols2 / 8));
     const int64_t grid = N * H * n * p.xchunks;
     if (grid >= INT_LIMIT || !fastdiv_ok(grid, p.xchunks) || !fastdiv_ok(grid, n) || !fastdiv_ok(grid, H))
         return MERIT_ERR_UNSUPPORTED;
@@ -728,7 +743,7 @@ merit_status derive_corr(merit_plan *pl)
     pl->out_ndim = 5;
     pl->out_shape[0] = N; pl->out_shape[1] = H; pl->out_shape[2] = W; pl->out_shape[3] = n; pl->out_shape[4] = n;
     merit_launch_info &li = pl->info;
-    li.kernel = "merit_corr_dot";
+    li.kernel = "merit_corr_mfma";
     li.grid[0] = grid; li.grid[1] = 1; li.grid[2] = 1;
     li.block[0] = 256; li.block[1] = 1; li.block[2] = 1;
     li.lds_bytes = (int64_t)corr_lds_bytes(p);

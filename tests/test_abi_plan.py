@@ -226,7 +226,7 @@ def test_correlation_plan_is_eq8():
     assert plan.footprint(1, (1, 1, 64, 1, 11, 256)) == lit.footprint((1, 1, 64, 1, 11, 256), t2, 4)
     assert plan.footprint(1, (1, 1, 64, 1, 11, 256))[3] == 64 + 10 * 2
     li = plan.launch_info()
-    assert li["kernel"] == "merit_corr_dot" and li["grid"][0] == 64 * 11 and li["lds_bytes"] <= 160 * 1024
+    assert li["kernel"] == "merit_corr_mfma" and li["grid"][0] == 64 * 11 and li["lds_bytes"] <= 160 * 1024
     assert mb.merit_plan_create(d).out_shape() == (1, 64, 64, 11, 11)
     d.b.offset[3] = -9                                              # not centred: no kernel
     with pytest.raises(mb.MeritError) as e:

@@ -347,7 +347,13 @@ CORR_CASES = [
     (1, 64, 12, 72, 5, 2),       # two pixel chunks, the second ragged
     (1, 130, 6, 64, 3, 3),       # two channel passes
     (1, 16, 10, 16, 0, 1),       # zero range: the per-pixel dot product
-    (1, 32, 5, 40, 15, 1),       # widest range: 31 displacements, 8 per wavefront
+    (1, 32, 5, 40, 15, 1),       # widest range: 31 displacements, three column blocks per pixel block
+    (1, 40, 7, 128, 8, 1),       # two column blocks exactly (16 + 2R = 32); channel groups padded to 8
+    (1, 24, 20, 64, 9, 2),       # three column blocks with two residue classes
+    (2, 72, 9, 80, 2, 4),        # four residue classes
+    (1, 16, 30, 64, 4, 5),       # classes of unequal size (13, 13, 13, 13, 12): five pixel blocks
+    (1, 48, 44, 72, 2, 8),       # eight classes: two pixel blocks per wavefront
+    (1, 264, 23, 64, 5, 3),      # three channel passes, classes of 22, 21, 21 pixels in two blocks each
 ]
 
 
