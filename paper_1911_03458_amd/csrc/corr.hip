@@ -107,11 +107,9 @@ __global__ __launch_bounds__(256, 4) void merit_corr_mfma(CorrParams p, const ui
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    // Consecutive hardware workgroup ids go to the 8 XCDs in turn, each with an L2 of its own.
-    // XCD x takes the x-th contiguous eighth of the work list, i.e. a band of image rows: its
-    // L2 then fetches that band and its halo rows of the second tensor, not both whole tensors.
-    const uint32_t xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3;
-    uint32_t g = xcd * (uint32_t)p.xq + min(xcd, (uint32_t)p.xr) + slot;
+    // each XCD takes a band of image rows: its L2 then fetches that band and its halo rows of
+    // the second tensor, not both whole tensors
+    uint32_t g = xcd_band_item(blockIdx.x, p.xq, p.xr);
     // work item -> (b, p1, p3, pixel chunk), chunk fastest
     const uint32_t q0 = fdiv(g, p.div_xchunks);
     const int xc = (int)(g - q0 * (uint32_t)p.xchunks);

@@ -30,6 +30,16 @@ __device__ __forceinline__ uint32_t fdiv(uint32_t n, FastDiv f)
     // d == 1 has magic 0 and adds n instead: a select, no branch
     return __umulhi(n, f.magic) + (f.d == 1u ? n : 0u);
 }
+
+// Consecutive hardware workgroup ids go to the 8 XCDs in turn, each with an L2 of its own.
+// With xq = grid / 8 and xr = grid % 8, XCD x gets the x-th contiguous run of the work list
+// (a band of image rows for row-major lists), so its L2 fetches that band and its halo once
+// instead of a share of every row.  A bijection of [0, grid) for any grid.
+__device__ __forceinline__ uint32_t xcd_band_item(uint32_t hw_id, int xq, int xr)
+{
+    const uint32_t xcd = hw_id & 7u, slot = hw_id >> 3;
+    return xcd * (uint32_t)xq + min(xcd, (uint32_t)xr) + slot;
+}
 #endif
 
 // ---- pooling ---------------------------------------------------------------
@@ -65,6 +75,7 @@ struct SadParams {
     int variant;
     int bpw;               // blocks per workgroup (rowscan variant)
     int groups_x;          // workgroups per block row (rowscan variant)
+    int xq, xr;            // grid / 8, grid % 8 (see xcd_band_item)
     FastDiv div_n;
     FastDiv div_win4;      // dwords per staged window row
     FastDiv div_nbx;

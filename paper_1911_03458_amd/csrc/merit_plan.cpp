@@ -247,6 +247,7 @@ merit_status derive_sad(merit_plan *pl)
         }
     }
 
+    p.xq = (int)(grid / 8); p.xr = (int)(grid % 8);
     pl->out_ndim = 2;
     pl->out_shape[0] = p.nby; pl->out_shape[1] = p.nbx;
     merit_launch_info &li = pl->info;

@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256) void merit_sad_generic(SadParams p, const uint
     uint32_t *cur32 = lds32 + p.win * pitch4 + 1;             // [B][B4]
     uint32_t *red = cur32 + p.B * B4;                         // [4]
 
-    const uint32_t blk = blockIdx.x;
+    const uint32_t blk = xcd_band_item(blockIdx.x, p.xq, p.xr);   // a band of block rows per XCD
     const int by = (int)(blk / (uint32_t)p.nbx);
     const int bx = (int)(blk - (uint32_t)by * p.nbx);
 
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256) void merit_sad_rowscan16(SadParams p, const ui
     const int lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int pitch4 = p.pitch >> 2;
-    const uint32_t g = blockIdx.x;
+    const uint32_t g = xcd_band_item(blockIdx.x, p.xq, p.xr);     // a band of block rows per XCD
     const int by = (int)(g / (uint32_t)p.groups_x);
     const int bx0 = (int)(g - (uint32_t)by * p.groups_x) * 4;
 
@@ -362,7 +362,7 @@ __global__ __launch_bounds__(256) void merit_sad_rowscan_pair(SadParams p, const
     const int lane = tid & 63, l32 = lane & 31, hb = lane >> 5;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int pitch4 = p.pitch >> 2;
-    const uint32_t g = blockIdx.x;
+    const uint32_t g = xcd_band_item(blockIdx.x, p.xq, p.xr);     // a band of block rows per XCD
     const int by = (int)(g / (uint32_t)p.groups_x);
     const int bx0 = (int)(g - (uint32_t)by * p.groups_x) * 8;
 
