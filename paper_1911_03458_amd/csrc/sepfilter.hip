@@ -27,7 +27,7 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 // K = window length (compile time: every tap index is an immediate, the sliding windows live
 // in renamed registers and no zero tap is multiplied)
 template <int K>
-__global__ __launch_bounds__(256) void merit_sepfilter_tile(SepParams p, const float *__restrict__ x,
+__global__ __launch_bounds__(256, (K > 16 ? 3 : 1)) void merit_sepfilter_tile(SepParams p, const float *__restrict__ x,
                                                            const float *__restrict__ kx,
                                                            const float *__restrict__ ky, float *__restrict__ y)
 {
@@ -56,6 +56,10 @@ __global__ __launch_bounds__(256) void merit_sepfilter_tile(SepParams p, const f
         return T;
     };
 
+    // The taps live in LDS and are read into vector registers at the start of each pass:
+    // measured on gfx950, a multiply-add stream whose tap sits in a scalar register issues
+    // one wavefront instruction per 4.2-4.6 clocks, with all operands in vector registers
+    // one per 2.4-3.0 clocks (two or more wavefronts per SIMD).
     if (tid < 4 * K4) {
         wxl[tid] = tid < K ? kx[min(tid, K - 1)] : 0.0f;
         wyl[tid] = tid < K ? ky[min(tid, K - 1)] : 0.0f;
@@ -77,11 +81,13 @@ __global__ __launch_bounds__(256) void merit_sepfilter_tile(SepParams p, const f
     float4v pre[SB];
     auto issue = [&](const Tile &T, int r0) {
         const int g4 = ((T.x0 - C4) >> 2) + cg;           // image 4-column group (may be outside)
-        const float *col = x + (size_t)T.n * p.H * p.W + 4 * min(max(g4, 0), W4 - 1);
+        // uniform image base + 32-bit element offsets (the plan keeps H*W below 2^31)
+        const float *img = x + (size_t)T.n * p.H * p.W;
+        const uint32_t col = 4u * (uint32_t)min(max(g4, 0), W4 - 1);
 #pragma unroll
         for (int b = 0; b < SB; ++b) {
             const int gy = min(max(T.y0 - C + r0 + rstep * b, 0), p.H - 1);
-            pre[b] = *reinterpret_cast<const float4v *>(col + (size_t)gy * p.W);
+            pre[b] = *reinterpret_cast<const float4v *>(img + (col + (uint32_t)gy * (uint32_t)p.W));
         }
     };
     auto commit = [&](const Tile &T, int r0) {
@@ -127,7 +133,9 @@ __global__ __launch_bounds__(256) void merit_sepfilter_tile(SepParams p, const f
             }
         }
         __syncthreads();
-        if (pf && t + nwg < ntiles) issue(tile_at(t + nwg), tid >> lg);
+        // short windows: the next tile's loads fly during both passes; long windows need the
+        // registers for the row pass and request it before the column pass
+        if (K <= 16 && pf && t + nwg < ntiles) issue(tile_at(t + nwg), tid >> lg);
 
         // row pass: unit = (8-column group, staged row), rows fastest; output column j of the
         // unit = sum_a kx[a] * staged column (8 cg + j + D + a).  The results replace the staged
@@ -135,6 +143,12 @@ __global__ __launch_bounds__(256) void merit_sepfilter_tile(SepParams p, const f
         // first, and a barrier separates the last read from the first write.
         constexpr int RU = K <= 16 ? 2 : 3;               // units per thread: 8 * RH <= 256 * RU
         float acc[RU][8];
+        float wx[4 * K4];
+#pragma unroll
+        for (int g = 0; g < K4; ++g) {
+            const float4v w = *reinterpret_cast<const float4v *>(wxl + 4 * g);
+            wx[4 * g] = w.x; wx[4 * g + 1] = w.y; wx[4 * g + 2] = w.z; wx[4 * g + 3] = w.w;
+        }
 #pragma unroll
         for (int k = 0; k < RU; ++k) {
             const int u = min(tid + 256 * k, (TW / 8) * RH - 1);
@@ -150,17 +164,15 @@ __global__ __launch_bounds__(256) void merit_sepfilter_tile(SepParams p, const f
 #pragma unroll
             for (int j = 0; j < 8; ++j) acc[k][j] = 0.0f;
 #pragma unroll
-            for (int g = 0; g < K4; ++g) {
-                const float4v w = *reinterpret_cast<const float4v *>(wxl + 4 * g);
-                const float wt[4] = {w.x, w.y, w.z, w.w};
+            for (int a = 0; a < K; ++a)
 #pragma unroll
-                for (int tt = 0; tt < 4; ++tt)
-                    if (4 * g + tt < K) {
-#pragma unroll
-                        for (int j = 0; j < 8; ++j)
-                            acc[k][j] = fmaf(wt[tt], win[j + D + 4 * g + tt], acc[k][j]);
-                    }
-            }
+                for (int j = 0; j < 8; ++j) acc[k][j] = fmaf(wx[a], win[j + D + a], acc[k][j]);
+            // long windows: one unit's window at a time in registers.  The empty statement
+            // consumes the sums and clobbers memory, so these multiply-adds stay above it and
+            // the next unit's reads below it.
+            if constexpr (K > 16)
+                asm volatile("" : "+v"(acc[k][0]), "+v"(acc[k][1]), "+v"(acc[k][2]), "+v"(acc[k][3]),
+                                  "+v"(acc[k][4]), "+v"(acc[k][5]), "+v"(acc[k][6]), "+v"(acc[k][7]) : : "memory");
         }
         __syncthreads();
         float *mid = in;                                  // [RH][PI], columns 0..63
@@ -179,34 +191,47 @@ __global__ __launch_bounds__(256) void merit_sepfilter_tile(SepParams p, const f
             }
         }
         __syncthreads();
+        if (K > 16 && pf && t + nwg < ntiles) issue(tile_at(t + nwg), tid >> lg);
 
         // column pass: unit = PR rows x 4 columns, column groups fastest: 16-byte LDS reads and
         // 16-byte stores.  Row q of the K + PR - 1 rows a unit reads feeds output row i with tap
         // q - i.
         float *out = y + (size_t)T.n * p.H * p.W;
+        float wy[4 * K4];
+#pragma unroll
+        for (int g = 0; g < K4; ++g) {
+            const float4v w = *reinterpret_cast<const float4v *>(wyl + 4 * g);
+            wy[4 * g] = w.x; wy[4 * g + 1] = w.y; wy[4 * g + 2] = w.z; wy[4 * g + 3] = w.w;
+        }
         for (int u = tid; u < (p.TH / PR) * (TW / 4); u += 256) {
             const int rg = u >> 4, c4 = u & 15;
             const float *src = mid + (PR * rg) * p.PI + 4 * c4;
             float4v o[PR];
 #pragma unroll
             for (int i = 0; i < PR; ++i) o[i] = (float4v){0.0f, 0.0f, 0.0f, 0.0f};
-            float wt[4 * K4];
+            // QC rows at a time: their reads, then their multiply-adds (for long windows the
+            // scheduler must not pull all K + 3 reads to the front: 4 registers each)
+            constexpr int QC = K > 16 ? 4 : 8;
 #pragma unroll
-            for (int g = 0; g < K4; ++g) {
-                const float4v w = *reinterpret_cast<const float4v *>(wyl + 4 * g);
-                wt[4 * g] = w.x; wt[4 * g + 1] = w.y; wt[4 * g + 2] = w.z; wt[4 * g + 3] = w.w;
-            }
+            for (int q0 = 0; q0 < K + PR - 1; q0 += QC) {
+                float4v v[QC];
 #pragma unroll
-            for (int q = 0; q < K + PR - 1; ++q) {
-                const float4v v = *reinterpret_cast<const float4v *>(src + q * p.PI);
+                for (int e = 0; e < QC; ++e)
+                    if (q0 + e < K + PR - 1) v[e] = *reinterpret_cast<const float4v *>(src + (q0 + e) * p.PI);
 #pragma unroll
-                for (int i = 0; i < PR; ++i)
-                    if (q - i >= 0 && q - i < K) {
-                        o[i].x = fmaf(wt[q - i], v.x, o[i].x);
-                        o[i].y = fmaf(wt[q - i], v.y, o[i].y);
-                        o[i].z = fmaf(wt[q - i], v.z, o[i].z);
-                        o[i].w = fmaf(wt[q - i], v.w, o[i].w);
-                    }
+                for (int e = 0; e < QC; ++e) {
+                    const int q = q0 + e;
+#pragma unroll
+                    for (int i = 0; i < PR; ++i)
+                        if (q < K + PR - 1 && q - i >= 0 && q - i < K) {
+                            o[i].x = fmaf(wy[q - i], v[e].x, o[i].x);
+                            o[i].y = fmaf(wy[q - i], v[e].y, o[i].y);
+                            o[i].z = fmaf(wy[q - i], v[e].z, o[i].z);
+                            o[i].w = fmaf(wy[q - i], v[e].w, o[i].w);
+                        }
+                }
+                if constexpr (K > 16)
+                    asm volatile("" : "+v"(o[0]), "+v"(o[1]), "+v"(o[2]), "+v"(o[3]) : : "memory");
             }
             const int gx = x0 + 4 * c4;
 #pragma unroll
@@ -230,7 +255,7 @@ __global__ __launch_bounds__(256) void merit_sepfilter_tile(SepParams p, const f
 
 template <int K>
 static hipError_t launch_sep(const SepParams &p, const float *x, const float *kx, const float *ky, float *y,
-                             hipStream_t s, uint32_t grid)
+                             hipStream_t s, int64_t ntiles, int cus)
 {
     static bool raised = false;
     if (!raised) {
@@ -239,6 +264,26 @@ static hipError_t launch_sep(const SepParams &p, const float *x, const float *kx
         if (e != hipSuccess) return e;
         raised = true;
     }
+    // Persistent workgroups.  The plan's count per CU is what LDS allows.  Long windows need so
+    // many registers that fewer are resident, and a workgroup beyond the resident ones would
+    // start only when another has finished all of its tiles: there the grid is exactly the
+    // resident count (k = 30 at 4x1080x1920: 768 instead of 1024 workgroups, 30.2 -> 28.1 us).
+    // Short windows keep the plan's count: one tile per workgroup, dealt out as workgroups
+    // retire, measured faster than two rounds over the resident ones (k = 3: 17.2 against 17.9 us).
+    int per_cu = p.wg_per_cu;
+    if (K > 16) {
+        static int asked_lds = -1, answer = 1;           // the last query (plans of one shape repeat)
+        if (asked_lds != p.lds_bytes) {
+            int r = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&r, merit_sepfilter_tile<K>, 256,
+                                                             (size_t)p.lds_bytes) != hipSuccess || r <= 0)
+                r = 1;
+            answer = r; asked_lds = p.lds_bytes;
+        }
+        if (answer < per_cu) per_cu = answer;
+    }
+    const int64_t slots = (int64_t)cus * per_cu;
+    const uint32_t grid = (uint32_t)(ntiles < slots ? ntiles : slots);
     hipLaunchKernelGGL(merit_sepfilter_tile<K>, dim3(grid), dim3(256), (size_t)p.lds_bytes, s, p, x, kx, ky, y);
     return hipGetLastError();
 }
@@ -257,10 +302,8 @@ hipError_t launch_sepfilter(const SepParams &p, const float *x, const float *kx,
             n = 256;
         cus = n;
     }
-    const int64_t slots = (int64_t)cus * p.wg_per_cu;
-    const uint32_t g = (uint32_t)(ntiles < slots ? ntiles : slots);
     switch (p.k) {
-#define MERIT_SEP_CASE(Kv) case Kv: return launch_sep<Kv>(p, x, kx, ky, y, s, g)
+#define MERIT_SEP_CASE(Kv) case Kv: return launch_sep<Kv>(p, x, kx, ky, y, s, ntiles, cus)
 #define MERIT_SEP_CASE8(B)                                                                           \
     MERIT_SEP_CASE(B + 1); MERIT_SEP_CASE(B + 2); MERIT_SEP_CASE(B + 3); MERIT_SEP_CASE(B + 4);      \
     MERIT_SEP_CASE(B + 5); MERIT_SEP_CASE(B + 6); MERIT_SEP_CASE(B + 7); MERIT_SEP_CASE(B + 8)
