@@ -39,6 +39,18 @@ __device__ __forceinline__ uint32_t wave_min_u32(uint32_t v)
     return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
+// v + (the lanes below in the same group of G = 8 or 16 lanes): the last lane of every
+// group holds the group's sum.  Lanes shifted in from outside a 16-lane row read 0.
+template <int G>
+__device__ __forceinline__ uint32_t group_sum_u32(uint32_t v)
+{
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, true);   // row_shr:1
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, true);   // row_shr:2
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, true);   // row_shr:4
+    if (G == 16) v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, true);   // row_shr:8
+    return v;
+}
+
 // Stage the clamped search window of block (by,bx) as bytes win[wy*pitch + wx],
 // wy,wx in [0, B+2R), four bytes per thread-iteration.
 __device__ __forceinline__ void stage_window(const SadParams &p, const uint8_t *__restrict__ ref,
@@ -227,6 +239,21 @@ __global__ __launch_bounds__(256) void merit_sad_rowscan16(SadParams p, const ui
         }
     }
 
+    // row (lane & 15) of the current block in vector registers, for the split tail below
+    // (requested here, used after the row scan)
+    uint32_t crow[4];
+    {
+        const uint32_t *cp = reinterpret_cast<const uint32_t *>(cur);
+        const int W4 = p.W >> 2;
+        const int row = min(by * 16 + (lane & 15), p.H - 1);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int d = bx * 4 + j;
+            const uint32_t v = cp[row * W4 + min(d, W4 - 1)];
+            crow[j] = d < W4 ? v : (v >> 24) * 0x01010101u;
+        }
+    }
+
     uint32_t best = 0xffffffffu;                   // (sad << 14) | raster index
 #pragma unroll 1
     for (int ch = 0; ch < NCHUNK; ++ch) {
@@ -282,10 +309,14 @@ __global__ __launch_bounds__(256) void merit_sad_rowscan16(SadParams p, const ui
     }
 
     if (NLEFT > 0) {
-        // the last NLEFT columns, one candidate per lane
+        // the last NLEFT columns, one candidate per lane; what does not fill a pass of 64
+        // (one candidate at R = 32) is split sixteen lanes per candidate, a block row each
         constexpr int NCAND = NLEFT * N;
+        constexpr int REM = NCAND % 64;
+        constexpr bool SPLIT = REM > 0 && REM <= 4;
+        constexpr int NFULL = SPLIT ? NCAND - REM : NCAND;
 #pragma unroll 1
-        for (int c0 = 0; c0 < NCAND; c0 += 64) {
+        for (int c0 = 0; c0 < NFULL; c0 += 64) {
             const int cand = min(c0 + lane, NCAND - 1);
             const int dyi = cand / NLEFT;
             const int dxi = (N / 64) * 64 + (cand - dyi * NLEFT);
@@ -302,6 +333,21 @@ __global__ __launch_bounds__(256) void merit_sad_rowscan16(SadParams p, const ui
             }
             const uint32_t key = (a << KEY_SHIFT) | (uint32_t)(dyi * N + dxi);
             best = key < best ? key : best;        // idle lanes recompute the last candidate
+        }
+        if (SPLIT) {
+            const int i = lane & 15;
+            const int cand = min(NFULL + (lane >> 4), NCAND - 1);
+            const int dyi = cand / NLEFT;
+            const int dxi = (N / 64) * 64 + (cand - dyi * NLEFT);
+            const int o = 16 * wv + dxi;
+            uint32_t r4[4];
+            load_aligned16(lds32 + (dyi + i) * pitch4 + (o >> 2), (uint32_t)(o & 3), r4);
+            uint32_t a = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) a = __builtin_amdgcn_sad_u8(crow[j], r4[j], a);
+            a = group_sum_u32<16>(a);
+            const uint32_t key = (a << KEY_SHIFT) | (uint32_t)(dyi * N + dxi);
+            if (i == 15 && NFULL + (lane >> 4) < NCAND) best = key < best ? key : best;
         }
     }
 
@@ -399,6 +445,20 @@ __global__ __launch_bounds__(256) void merit_sad_rowscan_pair(SadParams p, const
         }
     }
 
+    // row (lane & (B-1)) of this half's current block, for the split tail below
+    uint32_t crow[B4];
+    {
+        const uint32_t *cp = reinterpret_cast<const uint32_t *>(cur);
+        const int W4 = p.W >> 2;
+        const int row = min(by * B + (l32 & (B - 1)), p.H - 1);
+        const int d0 = min(bx, p.nbx - 1) * B4;
+#pragma unroll
+        for (int j = 0; j < B4; ++j) {
+            const uint32_t v = cp[row * W4 + min(d0 + j, W4 - 1)];
+            crow[j] = d0 + j < W4 ? v : (v >> 24) * 0x01010101u;
+        }
+    }
+
     uint32_t best = 0xffffffffu;                    // (sad << 14) | raster index
     {
         const int dxi = l32;
@@ -450,9 +510,14 @@ __global__ __launch_bounds__(256) void merit_sad_rowscan_pair(SadParams p, const
     }
 
     if (NLEFT > 0) {
+        // what does not fill a pass of 32 candidates (one candidate at N = 33) is split B
+        // lanes per candidate, a block row each
         constexpr int NCAND = NLEFT * N;
+        constexpr int REM = NCAND % 32;
+        constexpr bool SPLIT = REM > 0 && REM <= 32 / B;
+        constexpr int NFULL = SPLIT ? NCAND - REM : NCAND;
 #pragma unroll 1
-        for (int c0 = 0; c0 < NCAND; c0 += 32) {
+        for (int c0 = 0; c0 < NFULL; c0 += 32) {
             const int cand = min(c0 + l32, NCAND - 1);         // idle lanes recompute the last candidate
             const int dyi = cand / NLEFT;
             const int dxi = NMAIN + (cand - dyi * NLEFT);
@@ -469,6 +534,22 @@ __global__ __launch_bounds__(256) void merit_sad_rowscan_pair(SadParams p, const
             }
             const uint32_t key = (a << KEY_SHIFT) | (uint32_t)(dyi * N + dxi);
             best = key < best ? key : best;
+        }
+        if (SPLIT) {
+            const int i = l32 & (B - 1);
+            const int ci = NFULL + l32 / B;
+            const int cand = min(ci, NCAND - 1);
+            const int dyi = cand / NLEFT;
+            const int dxi = NMAIN + (cand - dyi * NLEFT);
+            const int o = B * bxl + dxi;
+            uint32_t r4[B4];
+            load_aligned_row<B4>(lds32 + (dyi + i) * pitch4 + (o >> 2), (uint32_t)(o & 3), r4);
+            uint32_t a = 0;
+#pragma unroll
+            for (int j = 0; j < B4; ++j) a = __builtin_amdgcn_sad_u8(crow[j], r4[j], a);
+            a = group_sum_u32<B>(a);
+            const uint32_t key = (a << KEY_SHIFT) | (uint32_t)(dyi * N + dxi);
+            if (i == B - 1 && ci < NCAND) best = key < best ? key : best;
         }
     }
 
