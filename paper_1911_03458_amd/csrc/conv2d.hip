@@ -1234,7 +1234,9 @@ __global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const 
 
     const int ntiles = p.N * p.tiles_per_image;
     bool first = true;
-    for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    // consecutive tiles share their halo rows: a contiguous run of each round of tiles per XCD
+    const int lwg = (int)xcd_band_item(blockIdx.x, (int)(gridDim.x >> 3), (int)(gridDim.x & 7));
+    for (int tile = lwg; tile < ntiles; tile += gridDim.x) {
         const int n = (int)fdiv((uint32_t)tile, p.div_tiles);
         const int m0 = (tile - n * p.tiles_per_image) * p.TM;
         const int oyA = (int)fdiv((uint32_t)m0, p.div_ow);

@@ -856,6 +856,25 @@ def test_sepfilter(mb, N, H, W, k, tile):
     assert np.all(err <= _sep_tol(x, kx, ky)), f"max err {err.max()} at {np.unravel_index(err.argmax(), err.shape)}"
 
 
+@pytest.mark.parametrize("k", range(1, 33))
+def test_sepfilter_every_window_length(mb, k):
+    """Every window length is a kernel instantiation of its own (taps and windows unrolled):
+    each is checked on an image of three column tiles, the last ragged, two tiles down."""
+    N, H, W = 2, 101, 136
+    rng = np.random.default_rng(4000 + k)
+    x = rng.uniform(0, 255, (N, H, W)).astype(np.float32)
+    kx = rng.standard_normal(k).astype(np.float32)
+    ky = rng.standard_normal(k).astype(np.float32)
+    plan = mb.merit_plan_sepfilter(N, H, W, k)
+    print("sepfilter k", k, plan.launch_info(), flush=True)
+    buf, y, p = guarded_empty((N, H, W), torch.float32, 777.0)
+    mb.merit_sepfilter(plan, dev(x), dev(kx), dev(ky), y)
+    torch.cuda.synchronize()
+    check_canary(buf, p, 777.0)
+    err = np.abs(y.cpu().numpy().astype(np.float64) - oracle.sepfilter(x, kx, ky).astype(np.float64))
+    assert np.all(err <= _sep_tol(x, kx, ky)), f"k={k}: max err {err.max()} at {np.unravel_index(err.argmax(), err.shape)}"
+
+
 def test_sepfilter_impulse_is_exact(mb):
     """Small-integer taps and one impulse: every product is exact in fp32, so the result must
     equal the oracle bit for bit, and shows the unflipped, -k/2-centred window."""
@@ -932,6 +951,25 @@ def test_bilateral(mb, N, H, W, k, sigma_r):
     ref = oracle.bilateral(x, gx, gy, norm).astype(np.float64)
     err = np.abs(got - ref)
     assert np.all(err <= _bilateral_tol(x, k)), f"max err {err.max()} at {np.unravel_index(err.argmax(), err.shape)}"
+
+
+@pytest.mark.parametrize("k", range(1, 19))
+def test_bilateral_every_window_length(mb, k):
+    """k <= 16 are instantiations of the row kernel, above that the tile kernel takes over."""
+    N, H, W = 1, 37, 132
+    rng = np.random.default_rng(5000 + k)
+    x = (rng.integers(0, 3, size=(N, H, W)) * 80.0 + rng.normal(0, 6.0, size=(N, H, W))).astype(np.float32)
+    gx = np.exp(-0.5 * ((np.arange(k) - k // 2) / max(k / 4.0, 0.5)) ** 2).astype(np.float32)
+    gy = rng.uniform(0.3, 1.0, k).astype(np.float32)
+    norm = -1.0 / (2 * 25.0 * 25.0)
+    plan = mb.merit_plan_bilateral(N, H, W, k)
+    print("bilateral k", k, plan.launch_info(), flush=True)
+    buf, y, p = guarded_empty((N, H, W), torch.float32, 777.0)
+    mb.merit_bilateral(plan, dev(x), dev(gx), dev(gy), norm, y)
+    torch.cuda.synchronize()
+    check_canary(buf, p, 777.0)
+    err = np.abs(y.cpu().numpy().astype(np.float64) - oracle.bilateral(x, gx, gy, norm).astype(np.float64))
+    assert np.all(err <= _bilateral_tol(x, k)), f"k={k}: max err {err.max()}"
 
 
 def test_bilateral_positive_constant(mb):
