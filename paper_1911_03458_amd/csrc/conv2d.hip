@@ -1043,7 +1043,7 @@ __device__ __forceinline__ int wsw(int cc, int chi) { return cc ^ (chi & 7); }
 // in registers to T fragments of 8 channels (needs Cin % 8 == 0)
 template <int T>
 __device__ __forceinline__ void stage_weights_chblock_vec(const ConvParams &p, const uint16_t *__restrict__ w,
-                                                          uint4 *wl, int co_base, int CB, int t0, int nthr)
+                                                          uint4 *wl, int co_base, int CB, int chi0, int t0, int nthr)
 {
     const int half_nchi = p.nchi >> 1;
     const int units = CB * 32 * p.nchi;
@@ -1057,9 +1057,10 @@ __device__ __forceinline__ void stage_weights_chblock_vec(const ConvParams &p, c
             const int col = (int)fdiv((uint32_t)u, p.div_nchi);
             const int chi = u - col * p.nchi;
             const int co = co_base + col;
-            const bool ok = (co < p.Cout) && (chi * 8 + 8 <= p.Cin);
+            const bool ok = (co < p.Cout) && ((chi0 + chi) * 8 + 8 <= p.Cin);
             // branch-free load (a padding unit re-reads unit 0 and is zeroed)
-            const uint4 *g = reinterpret_cast<const uint4 *>(w + (ok ? ((size_t)co * p.Cin + chi * 8) * T : 0));
+            const uint4 *g =
+                reinterpret_cast<const uint4 *>(w + (ok ? ((size_t)co * p.Cin + (chi0 + chi) * 8) * T : 0));
 #pragma unroll
             for (int i = 0; i < T; ++i) {
                 const uint4 v = g[i];
@@ -1094,7 +1095,8 @@ __device__ __forceinline__ void stage_weights_chblock_vec(const ConvParams &p, c
 }
 
 __device__ __forceinline__ void stage_weights_chblock_scalar(const ConvParams &p, const uint16_t *__restrict__ w,
-                                                             uint4 *wl, int co_base, int CB, int t0, int nthr)
+                                                             uint4 *wl, int co_base, int CB, int chi0, int t0,
+                                                             int nthr)
 {
     const int T = p.kh * p.kw;
     const int half_nchi = p.nchi >> 1;
@@ -1109,7 +1111,7 @@ __device__ __forceinline__ void stage_weights_chblock_scalar(const ConvParams &p
         if (co < p.Cout) {
 #pragma unroll
             for (int c = 0; c < 8; ++c) {
-                const int ci = chi * 8 + c;
+                const int ci = (chi0 + chi) * 8 + c;
                 if (ci < p.Cin) d[c >> 1] |= (uint32_t)w[((size_t)co * p.Cin + ci) * T + t] << (16 * (c & 1));
             }
         }
@@ -1120,18 +1122,19 @@ __device__ __forceinline__ void stage_weights_chblock_scalar(const ConvParams &p
     }
 }
 
+// chi0: first channel group of the pass (the groups of a pass are numbered from 0 in LDS)
 __device__ __forceinline__ void stage_weights_chblock(const ConvParams &p, const uint16_t *__restrict__ w,
-                                                      uint4 *wl, int co_base, int CB, int t0, int nthr)
+                                                      uint4 *wl, int co_base, int CB, int chi0, int t0, int nthr)
 {
     const int T = p.kh * p.kw;
-    if (T == 9 && (p.Cin & 7) == 0) stage_weights_chblock_vec<9>(p, w, wl, co_base, CB, t0, nthr);
-    else if (T == 1 && (p.Cin & 7) == 0) stage_weights_chblock_vec<1>(p, w, wl, co_base, CB, t0, nthr);
-    else stage_weights_chblock_scalar(p, w, wl, co_base, CB, t0, nthr);
+    if (T == 9 && (p.Cin & 7) == 0) stage_weights_chblock_vec<9>(p, w, wl, co_base, CB, chi0, t0, nthr);
+    else if (T == 1 && (p.Cin & 7) == 0) stage_weights_chblock_vec<1>(p, w, wl, co_base, CB, chi0, t0, nthr);
+    else stage_weights_chblock_scalar(p, w, wl, co_base, CB, chi0, t0, nthr);
 }
 
-// input rows [yA, yA+RH) of image n as [ci/8][row][col][8 channels]
+// input rows [yA, yA+RH) of image n as [ci/8][row][col][8 channels], channel groups chi0 .. chi0 + nchi - 1
 __device__ __forceinline__ void stage_input_chblock(const ConvParams &p, const uint16_t *__restrict__ x, uint4 *xl,
-                                                    int n, int yA, int RH, int t0, int nthr)
+                                                    int n, int yA, int RH, int chi0, int t0, int nthr)
 {
     // zero the padding columns of the staged rows
     const int npad = p.pitch - p.W;
@@ -1159,10 +1162,11 @@ __device__ __forceinline__ void stage_input_chblock(const ConvParams &p, const u
                 const int r = q - chi * p.RHa;
                 const int gy = yA + r;
                 const bool rowok = r < RH && gy >= 0 && gy < p.H;
-                const uint16_t *src = x + (((size_t)n * p.Cin + chi * 8) * p.H + (rowok ? gy : 0)) * p.W + 8 * x8;
+                const int ch0 = (chi0 + chi) * 8;
+                const uint16_t *src = x + (((size_t)n * p.Cin + ch0) * p.H + (rowok ? gy : 0)) * p.W + 8 * x8;
 #pragma unroll
                 for (int c = 0; c < 8; ++c) {
-                    const bool ok = rowok && (chi * 8 + c < p.Cin);
+                    const bool ok = rowok && (ch0 + c < p.Cin);
                     // branch-free: a padding channel or row re-reads the tensor's first bytes and is zeroed
                     const uint4 t4 = *reinterpret_cast<const uint4 *>(ok ? src + c * chstride : x);
                     v[k][c][0] = ok ? t4.x : 0u; v[k][c][1] = ok ? t4.y : 0u;
@@ -1203,7 +1207,7 @@ __device__ __forceinline__ void stage_input_chblock(const ConvParams &p, const u
             if (gy >= 0 && gy < p.H) {
 #pragma unroll
                 for (int c = 0; c < 8; ++c) {
-                    const int ch = chi * 8 + c;
+                    const int ch = (chi0 + chi) * 8 + c;
                     if (ch < p.Cin)
                         d[c >> 1] |= (uint32_t)x[(((size_t)n * p.Cin + ch) * p.H + gy) * p.W + xg] << (16 * (c & 1));
                 }
@@ -1234,6 +1238,7 @@ __global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const 
 
     const int ntiles = p.N * p.tiles_per_image;
     bool first = true;
+    const bool multi = p.nchunks > 1;
     // consecutive tiles share their halo rows: a contiguous run of each round of tiles per XCD
     const int lwg = (int)xcd_band_item(blockIdx.x, (int)(gridDim.x >> 3), (int)(gridDim.x & 7));
     for (int tile = lwg; tile < ntiles; tile += gridDim.x) {
@@ -1244,19 +1249,6 @@ __global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const 
         const int oyB = (int)fdiv((uint32_t)mlast, p.div_ow);
         const int yA = oyA * p.sh - p.ph;
         const int RH = (oyB - oyA) * p.sh + (p.kh - 1) * p.dh + 1;
-
-        __syncthreads();
-        if (first) {
-            // first tile: half of the wavefronts fetch the weights (once per workgroup) while
-            // the other half fetches the input, so the two global-memory round trips overlap
-            if (wave < 2) stage_weights_chblock(p, w, wl, co_base, CB, tid, 128);
-            else stage_input_chblock(p, x, xl, n, yA, RH, tid - 128, 128);
-            first = false;
-        } else {
-            stage_input_chblock(p, x, xl, n, yA, RH, tid, 256);
-        }
-        if (RES) stage_residual<CB, 4 * PXW * 32, 256>(p, outl, res, n, co_base, m0, tid);
-        __syncthreads();
 
         int pbase[PXW], pcol[PXW];                  // staged row offset and column of tap kx = 0
         const int lim8 = p.pitch & ~7;
@@ -1278,58 +1270,121 @@ __global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const 
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[cb][pb][r] = 0.0f;
 
-        // K loop.  Step s = (chip, ky, kx), kx fastest; a lone wavefront per SIMD issues about one
-        // instruction per 4-5 cycles, so what counts is instructions per step (two MFMAs = 64
-        // cycles).  3x3 windows get the nine steps of a channel-group pair unrolled: weight
-        // fragments at immediate offsets, the three swizzled tap columns computed once per tile.
-        if (p.kh == 3 && p.kw == 3) {
-            int xc[PXW][3];
-#pragma unroll
-            for (int pb = 0; pb < PXW; ++pb)
-#pragma unroll
-                for (int kx = 0; kx < 3; ++kx) xc[pb][kx] = pbase[pb] + xsw(pcol[pb] + kx * p.dw, lim8);
-            for (int chip = 0; chip < half_nchi; ++chip) {
-                const uint4 *wa = wl + (chip * 9 * CB) * 64 + h * 32 + wsw(c32, chip + h * half_nchi);
-#pragma unroll
-                for (int ky = 0; ky < 3; ++ky) {
-                    const int rowoff = (chip * p.RHa + ky * p.dh) * p.pitch;
-#pragma unroll
-                    for (int kx = 0; kx < 3; ++kx) {
-                        Frag a[CB], b[PXW];
-#pragma unroll
-                        for (int cb = 0; cb < CB; ++cb) a[cb].u = wa[((ky * 3 + kx) * CB + cb) * 64];
-#pragma unroll
-                        for (int pb = 0; pb < PXW; ++pb) b[pb].u = xl[xc[pb][kx] + rowoff];
-#pragma unroll
-                        for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-                            for (int pb = 0; pb < PXW; ++pb) acc[cb][pb] = mfma16(a[cb], b[pb], acc[cb][pb]);
+        // Channels go through LDS in passes of p.nchi groups of eight (one pass when everything
+        // fits); the accumulators stay in registers across the passes.
+        for (int ck = 0; ck < p.nchunks; ++ck) {
+            __syncthreads();                           // the previous pass (or tile) has been read
+            const int chi0 = ck * p.nchi;
+            if (first || multi) {
+                // half of the wavefronts fetch the weights (once per workgroup when all channels
+                // fit in one pass) while the other half fetches the input, so the two
+                // global-memory round trips overlap
+                if (wave < 2) stage_weights_chblock(p, w, wl, co_base, CB, chi0, tid, 128);
+                else stage_input_chblock(p, x, xl, n, yA, RH, chi0, tid - 128, 128);
+                first = false;
+            } else {
+                stage_input_chblock(p, x, xl, n, yA, RH, chi0, tid, 256);
+            }
+            if (RES && ck == 0) stage_residual<CB, 4 * PXW * 32, 256>(p, outl, res, n, co_base, m0, tid);
+            __syncthreads();
+
+            // K loop.  Step s = (chip, ky, kx), kx fastest; a lone wavefront per SIMD issues about one
+            // instruction per 4-5 cycles, so what counts is instructions per step (two MFMAs = 64
+            // cycles).  3x3 windows get the nine steps of a channel-group pair unrolled: weight
+            // fragments at immediate offsets, the three swizzled tap columns computed once per tile.
+            if (p.kh == 3 && p.kw == 3) {
+                int xc[PXW][3];
+    #pragma unroll
+                for (int pb = 0; pb < PXW; ++pb)
+    #pragma unroll
+                    for (int kx = 0; kx < 3; ++kx) xc[pb][kx] = pbase[pb] + xsw(pcol[pb] + kx * p.dw, lim8);
+                for (int chip = 0; chip < half_nchi; ++chip) {
+                    const uint4 *wa = wl + (chip * 9 * CB) * 64 + h * 32 + wsw(c32, chip + h * half_nchi);
+    #pragma unroll
+                    for (int ky = 0; ky < 3; ++ky) {
+                        const int rowoff = (chip * p.RHa + ky * p.dh) * p.pitch;
+    #pragma unroll
+                        for (int kx = 0; kx < 3; ++kx) {
+                            Frag a[CB], b[PXW];
+    #pragma unroll
+                            for (int cb = 0; cb < CB; ++cb) a[cb].u = wa[((ky * 3 + kx) * CB + cb) * 64];
+    #pragma unroll
+                            for (int pb = 0; pb < PXW; ++pb) b[pb].u = xl[xc[pb][kx] + rowoff];
+    #pragma unroll
+                            for (int cb = 0; cb < CB; ++cb)
+    #pragma unroll
+                                for (int pb = 0; pb < PXW; ++pb) acc[cb][pb] = mfma16(a[cb], b[pb], acc[cb][pb]);
+                        }
                     }
                 }
-            }
-        } else {
-            int s = 0;
-            for (int chip = 0; chip < half_nchi; ++chip) {
-                const int wslot = h * 32 + wsw(c32, chip + h * half_nchi);
-                for (int ky = 0; ky < p.kh; ++ky) {
-                    const int rowoff = (chip * p.RHa + ky * p.dh) * p.pitch;
-                    for (int kx = 0; kx < p.kw; ++kx, ++s) {
-                        Frag a[CB], b[PXW];
-#pragma unroll
-                        for (int cb = 0; cb < CB; ++cb) a[cb].u = wl[(s * CB + cb) * 64 + wslot];
-#pragma unroll
-                        for (int pb = 0; pb < PXW; ++pb)
-                            b[pb].u = xl[pbase[pb] + rowoff + xsw(pcol[pb] + kx * p.dw, lim8)];
-#pragma unroll
-                        for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-                            for (int pb = 0; pb < PXW; ++pb) acc[cb][pb] = mfma16(a[cb], b[pb], acc[cb][pb]);
+            } else {
+                int s = 0;
+                for (int chip = 0; chip < half_nchi; ++chip) {
+                    const int wslot = h * 32 + wsw(c32, chip + h * half_nchi);
+                    for (int ky = 0; ky < p.kh; ++ky) {
+                        const int rowoff = (chip * p.RHa + ky * p.dh) * p.pitch;
+                        for (int kx = 0; kx < p.kw; ++kx, ++s) {
+                            Frag a[CB], b[PXW];
+    #pragma unroll
+                            for (int cb = 0; cb < CB; ++cb) a[cb].u = wl[(s * CB + cb) * 64 + wslot];
+    #pragma unroll
+                            for (int pb = 0; pb < PXW; ++pb)
+                                b[pb].u = xl[pbase[pb] + rowoff + xsw(pcol[pb] + kx * p.dw, lim8)];
+    #pragma unroll
+                            for (int cb = 0; cb < CB; ++cb)
+    #pragma unroll
+                                for (int pb = 0; pb < PXW; ++pb) acc[cb][pb] = mfma16(a[cb], b[pb], acc[cb][pb]);
+                        }
                     }
                 }
             }
         }
         store_tile<CB, PXW, 4, false>(p, acc, outl, y, n, co_base, m0, tid, RES);
     }
+}
+
+// ---------------------------------------------------------------------------
+// Last resort for shapes neither MFMA kernel takes (a window or a channel count whose
+// operands do not fit the LDS layouts above): the definition itself, one output element per
+// thread, fp16 products (exact in fp32) accumulated in fp32 in the order (ci, ky, kx), then the
+// PostLoop of the other kernels: + residual, clip, one rounding.  A wavefront covers 64
+// adjacent outputs of a row where it can, so the input reads coalesce and the weight reads
+// are one address per wavefront.  tile = 256 consecutive elements of one image's [Cout][OH][OW].
+__global__ __launch_bounds__(256) void merit_conv2d_direct(ConvParams p, const uint16_t *__restrict__ x,
+                                                          const uint16_t *__restrict__ w,
+                                                          const uint16_t *__restrict__ res,
+                                                          uint16_t *__restrict__ y)
+{
+    const uint32_t n = blockIdx.x / (uint32_t)p.tiles_per_image;       // plain divisions: any extent
+    const uint32_t e = (blockIdx.x - n * (uint32_t)p.tiles_per_image) * 256u + threadIdx.x;   // element of the image
+    const uint32_t per_image = (uint32_t)p.Cout * (uint32_t)(p.OH * p.OW);
+    if (e >= per_image) return;
+    const uint32_t q = e / (uint32_t)p.OW;
+    const int ox = (int)(e - q * (uint32_t)p.OW);
+    const uint32_t co = q / (uint32_t)p.OH;
+    const int oy = (int)(q - co * (uint32_t)p.OH);
+    const _Float16 *xh = reinterpret_cast<const _Float16 *>(x) + (size_t)n * p.Cin * p.H * p.W;
+    const _Float16 *wh = reinterpret_cast<const _Float16 *>(w) + (size_t)co * p.Cin * p.kh * p.kw;
+    const int iy0 = oy * p.sh - p.ph, ix0 = ox * p.sw - p.pw;
+    float acc = 0.0f;
+    for (int ci = 0; ci < p.Cin; ++ci) {
+        const _Float16 *xc = xh + (size_t)ci * p.H * p.W;
+        const _Float16 *wc = wh + ci * p.kh * p.kw;
+        for (int ky = 0; ky < p.kh; ++ky) {
+            const int iy = iy0 + ky * p.dh;
+            if (iy < 0 || iy >= p.H) continue;
+            for (int kx = 0; kx < p.kw; ++kx) {
+                const int ix = ix0 + kx * p.dw;
+                if (ix < 0 || ix >= p.W) continue;
+                acc = fmaf((float)xc[iy * p.W + ix], (float)wc[ky * p.kw + kx], acc);
+            }
+        }
+    }
+    const size_t o = (size_t)n * per_image + e;
+    if (p.residual) acc += (float)reinterpret_cast<const _Float16 *>(res)[o];
+    if (p.relu) acc = fmaxf(acc, 0.0f);
+    const _Float16 h = (_Float16)acc;                             // round to nearest even
+    y[o] = __builtin_bit_cast(uint16_t, h);
 }
 
 // ---------------------------------------------------------------------------
@@ -1376,6 +1431,12 @@ hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, cons
 {
     const int64_t ntiles = (int64_t)p.N * p.tiles_per_image;
     if (ntiles == 0) return hipSuccess;
+    if (p.variant == CONV_DIRECT) {                // one workgroup per 256 output elements
+        hipLaunchKernelGGL(merit_conv2d_direct, dim3((uint32_t)ntiles), dim3(256), 0, s, p,
+                           reinterpret_cast<const uint16_t *>(x), reinterpret_cast<const uint16_t *>(w),
+                           reinterpret_cast<const uint16_t *>(r), reinterpret_cast<uint16_t *>(y));
+        return hipGetLastError();
+    }
     // persistent grid: as many workgroups as fit on the chip at once, at most one per tile
     int64_t slots = (int64_t)device_cu_count() * p.wg_per_cu / p.co_groups;
     if (slots < 1) slots = 1;
@@ -1444,6 +1505,7 @@ const char *conv_kernel_name(const ConvParams &p)
 {
     if (p.variant == CONV_PLANAR_SMALLC && p.ws && p.pool) return "merit_conv2d_planar_ws_pool";
     if (p.variant == CONV_PLANAR_SMALLC) return p.ws ? "merit_conv2d_planar_ws" : "merit_conv2d_planar";
+    if (p.variant == CONV_DIRECT) return "merit_conv2d_direct";
     return "merit_conv2d_chblock";
 }
 

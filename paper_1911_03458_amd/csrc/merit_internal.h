@@ -82,7 +82,7 @@ struct SadParams {
 };
 
 // ---- convolution -----------------------------------------------------------
-enum ConvVariant { CONV_PLANAR_SMALLC = 0, CONV_CHBLOCK = 1 };
+enum ConvVariant { CONV_PLANAR_SMALLC = 0, CONV_CHBLOCK = 1, CONV_DIRECT = 2 };
 
 struct ConvParams {
     int N, Cin, H, W, Cout, OH, OW;
@@ -101,7 +101,8 @@ struct ConvParams {
     int padl;              // staged column of input x = 0
     int G, G2;             // planar: (ci,ky) groups and padded-even count
     int S;                 // MFMA K-steps (K = 16 each)
-    int nchi;              // channel-blocked: 8-channel groups incl. zero padding (even)
+    int nchi;              // channel-blocked: 8-channel groups per pass incl. zero padding (even)
+    int nchunks;           // channel-blocked: passes over the channels (1: everything is staged at once)
     int lds_w_bytes;       // weights region
     int lds_x_bytes;       // input region
     int lds_o_offset;      // output staging region: byte offset and size

@@ -436,6 +436,7 @@ merit_status derive_conv(merit_plan *pl)
     auto try_variant = [&](int variant, int pxw, int nw) -> bool {
         ConvParams q = p;
         q.variant = variant;
+        q.nchunks = 1;
         q.PXW = pxw;
         q.NW = nw;
         q.TM = nw * pxw * 32;
@@ -472,13 +473,31 @@ merit_status derive_conv(merit_plan *pl)
             q.lds_o_offset = (int)round_up((int64_t)q.lds_w_bytes + 32 + q.lds_x_bytes, 16);
         } else {
             q.front = 0; q.aligned = 0;
-            q.nchi = (int)(cdiv(Cin, 16) * 2);
             q.padl = (int)pw;
             int64_t pitch = q.padl + W;
             const int64_t reach = (OW - 1) * sw + ew;
             if (reach > pitch) pitch = reach;
             q.pitch = (int)pitch;
             q.G = q.G2 = 0;
+            // Channel groups of 8, an even number (the two halves of a wavefront take one each per
+            // MFMA step).  All of them are staged at once when weights + input rows + output
+            // staging fit in LDS; else the channels go through in passes of the largest even
+            // group count that fits half of it (two workgroups per CU overlap staging and MFMAs),
+            // or all of it if not even one pair fits the half.
+            const int64_t nchi_all = cdiv(Cin, 16) * 2;
+            const int64_t per_pair = kh * kw * q.CB * 64 * 16 + 2 * (int64_t)q.RHa * pitch * 16;
+            const int64_t o_bytes = (int64_t)q.CB * 32 * (q.TM / 2 + 2) * 4;
+            int64_t pairs = nchi_all / 2;
+            if (pairs * per_pair + o_bytes > LDS_LIMIT) {
+                pairs = (LDS_LIMIT / 2 - o_bytes) / per_pair;
+                if (pairs < 1) pairs = (LDS_LIMIT - o_bytes) / per_pair;
+                if (pairs < 1) return false;
+                // equal passes (the last one is padded with zero channels otherwise)
+                const int64_t passes = cdiv(nchi_all / 2, pairs);
+                pairs = cdiv(nchi_all / 2, passes);
+            }
+            q.nchi = (int)(2 * pairs);
+            q.nchunks = (int)cdiv(nchi_all, q.nchi);
             q.S = (int)((q.nchi / 2) * kh * kw);
             q.lds_w_bytes = q.S * q.CB * 64 * 16;
             q.lds_x_bytes = (int)((int64_t)q.nchi * q.RHa * q.pitch * 16);
@@ -577,7 +596,24 @@ merit_status derive_conv(merit_plan *pl)
             ok = want_big ? (try_variant(CONV_CHBLOCK, 2, 4) || try_variant(CONV_CHBLOCK, 1, 4))
                           : (try_variant(CONV_CHBLOCK, 1, 4) || try_variant(CONV_CHBLOCK, 2, 4));
     }
-    if (!ok) return MERIT_ERR_UNSUPPORTED;
+    if (!ok) {
+        // neither MFMA kernel holds this shape's operands in LDS: the one-element-per-thread
+        // kernel takes any shape (not a tile request, which names an MFMA tiling, and not the
+        // fused pooling, which only the wave-specialised kernel does)
+        if (pool || (pl->tile_req[2] > 0 && pl->tile_req[3] > 0)) return MERIT_ERR_UNSUPPORTED;
+        const int64_t per_image = Cout * ohw;
+        if (per_image >= INT_LIMIT || H * W >= INT_LIMIT) return MERIT_ERR_UNSUPPORTED;
+        p.variant = CONV_DIRECT;
+        p.PXW = 1; p.NW = 4; p.TM = 256; p.CB = 1; p.co_groups = 1; p.ws = 0; p.su = 0;
+        p.tiles_per_image = (int)cdiv(per_image, 256);
+        p.rows_out_max = 1; p.RHa = (int)eh; p.pitch = (int)W; p.padl = 0;
+        p.G = p.G2 = p.S = p.nchi = 0; p.nchunks = 1;
+        p.lds_w_bytes = p.lds_x_bytes = p.lds_o_offset = p.lds_o_bytes = p.lds_total = 0;
+        p.front = p.aligned = p.lg_chunks = 0;
+        p.wg_per_cu = 8;
+        p.div_ow = make_fastdiv((uint32_t)OW);
+        p.div_tiles = make_fastdiv((uint32_t)p.tiles_per_image);
+    }
     if ((int64_t)N * p.tiles_per_image >= (1ll << 31)) return MERIT_ERR_UNSUPPORTED;
 
     pl->out_ndim = 4;
@@ -592,6 +628,7 @@ merit_status derive_conv(merit_plan *pl)
         const int64_t nt = (int64_t)N * p.tiles_per_image;
         li.grid[0] = nt < slots ? nt : slots;
         if (pool) li.grid[0] = (int64_t)N * p.NB;          // one workgroup per band, not persistent
+        if (p.variant == CONV_DIRECT) li.grid[0] = nt;     // one workgroup per 256 output elements
     }
     li.grid[1] = p.co_groups; li.grid[2] = 1;
     li.block[0] = p.ws ? 512 : p.NW * 64; li.block[1] = 1; li.block[2] = 1;

@@ -441,3 +441,22 @@ def test_plans_for_extreme_shapes_are_sane_or_refused():
         ok(mb.merit_plan_correlation, *a)
     for a in [(1 << 10, 1024, 112, 112, 3, 3, 1, 1, 1, 1), (1, 1, 3, 8192, 5, 5, 2, 2, 2, 2)]:
         ok(mb.merit_plan_conv2d_depthwise, *a)
+
+
+def test_conv_plans_for_layers_that_do_not_fit_lds_at_once():
+    """Channel passes for many-channel layers; the one-element-per-thread kernel when a wide
+    window on few channels fits neither MFMA layout; the tile request and the fused pooling
+    stay with the MFMA kernels."""
+    for shape in ((1, 512, 14, 14, 512, 3, 3, 1, 1, 1, 1), (1, 96, 27, 27, 256, 5, 5, 1, 1, 2, 2),
+                  (1, 64, 224, 224, 64, 3, 3, 1, 1, 1, 1), (1, 256, 56, 56, 64, 1, 1, 1, 1, 0, 0)):
+        li = mb.merit_plan_conv2d(*shape).launch_info()
+        assert li["kernel"] == "merit_conv2d_chblock" and 0 < li["lds_bytes"] <= 160 * 1024, (shape, li)
+    alex1 = (1, 3, 227, 227, 96, 11, 11, 4, 4, 0, 0)
+    p = mb.merit_plan_conv2d(*alex1)
+    li = p.launch_info()
+    assert li["kernel"] == "merit_conv2d_direct" and li["lds_bytes"] == 0
+    assert p.out_shape() == (1, 96, 55, 55) and li["grid"][0] == -(-96 * 55 * 55 // 256)
+    with pytest.raises(mb.MeritError):
+        p.set_tile((0, 0, 4, 32))
+    with pytest.raises(mb.MeritError):
+        mb.merit_plan_conv2d_pool(1, 3, 224, 224, 64, 11, 11, 2, 2, 5, 5)

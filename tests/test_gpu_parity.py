@@ -440,6 +440,16 @@ CONV_CASES = [
     (1, 20, 9, 11, 10, 2, 3, 1, 1, 0, 1),      # channel-block, scalar staging everywhere
     (1, 32, 8, 8, 96, 1, 1, 1, 1, 0, 0),       # channel-block, 1x1, three channel blocks
     (1, 8, 40, 40, 16, 5, 5, 1, 1, 2, 2),      # channel-block, many tiles per image
+    # layers whose operands do not fit LDS at once: the channels go through in passes
+    (1, 200, 14, 14, 70, 3, 3, 1, 1, 1, 1),    # passes, vector weight staging, three channel blocks
+    (2, 35, 12, 18, 52, 7, 5, 1, 1, 3, 3),     # passes, scalar weight staging, ragged channels
+    (1, 96, 27, 27, 40, 5, 5, 1, 1, 2, 2),     # passes, the 5x5 / 96-channel layer class
+    (1, 520, 9, 16, 64, 1, 1, 1, 1, 0, 0),     # passes, 1x1 over many channels
+    (1, 64, 20, 120, 32, 3, 3, 1, 1, 1, 1),    # passes because the rows are wide
+    (1, 128, 21, 23, 64, 3, 3, 2, 2, 1, 1),    # passes, stride 2, odd sizes
+    # neither MFMA kernel: the one-element-per-thread kernel
+    (1, 3, 67, 67, 48, 11, 11, 4, 4, 5, 5),    # the paper's strided example: x = 4p + a - 5, 11x11 window
+    (2, 5, 30, 41, 7, 9, 12, 2, 3, 4, 6),      # wide window on few channels
 ]
 
 
@@ -620,6 +630,8 @@ RESIDUAL_CASES = [
     (2, 3, 32, 32, 64, 7, 7, 2, 2, 3, 3, 1),    # planar with prefetch
     (2, 3, 17, 19, 40, 7, 7, 2, 2, 3, 3, 0),    # planar, odd sizes
     (40, 3, 64, 64, 64, 7, 7, 2, 2, 3, 3, 1),   # planar, several tiles per workgroup
+    (1, 136, 10, 16, 64, 3, 3, 1, 1, 1, 1, 1),  # channel-block, channels in passes
+    (1, 3, 45, 45, 6, 11, 11, 4, 4, 0, 0, 1),   # one element per thread
 ]
 
 
@@ -701,6 +713,8 @@ DILATED_CASES = [
     (1, 64, 30, 34, 64, 3, 3, 2, 1, 3, 0, 3, 1, 0),   # mixed dilation and stride
     (2, 3, 33, 40, 8, 3, 3, 1, 1, 2, 2, 2, 2, 0),     # few input channels (padded to 16)
     (1, 8, 18, 24, 16, 2, 5, 1, 2, 0, 4, 4, 2, 0),    # even window, wide dilation
+    (1, 144, 20, 40, 32, 3, 3, 1, 1, 2, 2, 2, 2, 1),  # channels in passes
+    (1, 3, 50, 50, 8, 11, 11, 2, 2, 10, 10, 2, 2, 1), # one element per thread, dilated and clipped
 ]
 
 
