@@ -1345,47 +1345,72 @@ __global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const 
 
 // ---------------------------------------------------------------------------
 // Last resort for shapes neither MFMA kernel takes (a window or a channel count whose
-// operands do not fit the LDS layouts above): the definition itself, one output element per
-// thread, fp16 products (exact in fp32) accumulated in fp32 in the order (ci, ky, kx), then the
-// PostLoop of the other kernels: + residual, clip, one rounding.  A wavefront covers 64
-// adjacent outputs of a row where it can, so the input reads coalesce and the weight reads
-// are one address per wavefront.  tile = 256 consecutive elements of one image's [Cout][OH][OW].
+// operands do not fit the LDS layouts above): the definition itself on the vector ALU, fp16
+// products (exact in fp32) accumulated in fp32 in the order (ci, ky, kx), then the PostLoop of
+// the other kernels: + residual, clip, one rounding.  A workgroup owns 256 consecutive pixels
+// of one image (a lane a pixel) and DIRECT_CO output channels: an input element is loaded and
+// converted once for DIRECT_CO multiply-adds, the weights are the same for the whole
+// workgroup (uniform addresses).  Workgroup index = (image, channel block, pixel block),
+// pixel block fastest.
+constexpr int DIRECT_CO = 8;
+
 __global__ __launch_bounds__(256) void merit_conv2d_direct(ConvParams p, const uint16_t *__restrict__ x,
                                                           const uint16_t *__restrict__ w,
                                                           const uint16_t *__restrict__ res,
                                                           uint16_t *__restrict__ y)
 {
-    const uint32_t n = blockIdx.x / (uint32_t)p.tiles_per_image;       // plain divisions: any extent
-    const uint32_t e = (blockIdx.x - n * (uint32_t)p.tiles_per_image) * 256u + threadIdx.x;   // element of the image
-    const uint32_t per_image = (uint32_t)p.Cout * (uint32_t)(p.OH * p.OW);
-    if (e >= per_image) return;
-    const uint32_t q = e / (uint32_t)p.OW;
-    const int ox = (int)(e - q * (uint32_t)p.OW);
-    const uint32_t co = q / (uint32_t)p.OH;
-    const int oy = (int)(q - co * (uint32_t)p.OH);
+    const uint32_t ohw = (uint32_t)(p.OH * p.OW);
+    const uint32_t pblocks = (ohw + 255u) / 256u;                      // plain divisions: any extent
+    const uint32_t q0 = blockIdx.x / pblocks;
+    const uint32_t pb = blockIdx.x - q0 * pblocks;
+    const uint32_t n = q0 / (uint32_t)p.co_groups;
+    const int co0 = (int)(q0 - n * (uint32_t)p.co_groups) * DIRECT_CO;
+    const uint32_t m = pb * 256u + threadIdx.x;                        // pixel of the image
+    const uint32_t mm = min(m, ohw - 1u);                              // idle lanes repeat the last pixel
+    const int oy = (int)(mm / (uint32_t)p.OW);
+    const int ox = (int)(mm - (uint32_t)oy * (uint32_t)p.OW);
     const _Float16 *xh = reinterpret_cast<const _Float16 *>(x) + (size_t)n * p.Cin * p.H * p.W;
-    const _Float16 *wh = reinterpret_cast<const _Float16 *>(w) + (size_t)co * p.Cin * p.kh * p.kw;
+    const _Float16 *wh = reinterpret_cast<const _Float16 *>(w);
+    const int T = p.kh * p.kw;
     const int iy0 = oy * p.sh - p.ph, ix0 = ox * p.sw - p.pw;
-    float acc = 0.0f;
+    // output channels past the last one repeat it (computed, not stored)
+    int wrow[DIRECT_CO];
+#pragma unroll
+    for (int j = 0; j < DIRECT_CO; ++j) wrow[j] = min(co0 + j, p.Cout - 1) * p.Cin * T;
+    float acc[DIRECT_CO];
+#pragma unroll
+    for (int j = 0; j < DIRECT_CO; ++j) acc[j] = 0.0f;
     for (int ci = 0; ci < p.Cin; ++ci) {
         const _Float16 *xc = xh + (size_t)ci * p.H * p.W;
-        const _Float16 *wc = wh + ci * p.kh * p.kw;
         for (int ky = 0; ky < p.kh; ++ky) {
             const int iy = iy0 + ky * p.dh;
-            if (iy < 0 || iy >= p.H) continue;
+            const bool rowok = iy >= 0 && iy < p.H;
+            const _Float16 *xr = xc + (rowok ? iy : 0) * p.W;
+            const int wt = ci * T + ky * p.kw;
             for (int kx = 0; kx < p.kw; ++kx) {
                 const int ix = ix0 + kx * p.dw;
-                if (ix < 0 || ix >= p.W) continue;
-                acc = fmaf((float)xc[iy * p.W + ix], (float)wc[ky * p.kw + kx], acc);
+                const bool ok = rowok && ix >= 0 && ix < p.W;
+                const float v = ok ? (float)xr[ok ? ix : 0] : 0.0f;   // zero padding
+#pragma unroll
+                for (int j = 0; j < DIRECT_CO; ++j) acc[j] = fmaf(v, (float)wh[wrow[j] + wt + kx], acc[j]);
             }
         }
     }
-    const size_t o = (size_t)n * per_image + e;
-    if (p.residual) acc += (float)reinterpret_cast<const _Float16 *>(res)[o];
-    if (p.relu) acc = fmaxf(acc, 0.0f);
-    const _Float16 h = (_Float16)acc;                             // round to nearest even
-    y[o] = __builtin_bit_cast(uint16_t, h);
+    if (m < ohw) {
+#pragma unroll
+        for (int j = 0; j < DIRECT_CO; ++j) {
+            if (co0 + j >= p.Cout) break;
+            const size_t o = ((size_t)n * p.Cout + (co0 + j)) * ohw + m;
+            float a = acc[j];
+            if (p.residual) a += (float)reinterpret_cast<const _Float16 *>(res)[o];
+            if (p.relu) a = fmaxf(a, 0.0f);
+            const _Float16 h = (_Float16)a;                           // round to nearest even
+            y[o] = __builtin_bit_cast(uint16_t, h);
+        }
+    }
 }
+
+int conv_direct_channels() { return DIRECT_CO; }
 
 // ---------------------------------------------------------------------------
 template <typename K>
@@ -1431,7 +1456,7 @@ hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, cons
 {
     const int64_t ntiles = (int64_t)p.N * p.tiles_per_image;
     if (ntiles == 0) return hipSuccess;
-    if (p.variant == CONV_DIRECT) {                // one workgroup per 256 output elements
+    if (p.variant == CONV_DIRECT) {                // one workgroup per 256 pixels x 8 channels
         hipLaunchKernelGGL(merit_conv2d_direct, dim3((uint32_t)ntiles), dim3(256), 0, s, p,
                            reinterpret_cast<const uint16_t *>(x), reinterpret_cast<const uint16_t *>(w),
                            reinterpret_cast<const uint16_t *>(r), reinterpret_cast<uint16_t *>(y));

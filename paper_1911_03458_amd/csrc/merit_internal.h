@@ -216,6 +216,7 @@ hipError_t launch_bilateral(const BilatParams &p, const float *x, const float *g
 
 hipError_t launch_correlation(const CorrParams &p, const void *x1, const void *x2, void *y, hipStream_t s);
 size_t corr_lds_bytes(const CorrParams &p);
+int conv_direct_channels();     // output channels per workgroup of the one-element-per-thread convolution
 
 }  // namespace merit
 

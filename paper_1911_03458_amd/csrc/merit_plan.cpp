@@ -602,10 +602,13 @@ merit_status derive_conv(merit_plan *pl)
         // fused pooling, which only the wave-specialised kernel does)
         if (pool || (pl->tile_req[2] > 0 && pl->tile_req[3] > 0)) return MERIT_ERR_UNSUPPORTED;
         const int64_t per_image = Cout * ohw;
-        if (per_image >= INT_LIMIT || H * W >= INT_LIMIT) return MERIT_ERR_UNSUPPORTED;
+        if (per_image >= INT_LIMIT || H * W >= INT_LIMIT || Cout * Cin * kh * kw >= INT_LIMIT) return MERIT_ERR_UNSUPPORTED;
         p.variant = CONV_DIRECT;
-        p.PXW = 1; p.NW = 4; p.TM = 256; p.CB = 1; p.co_groups = 1; p.ws = 0; p.su = 0;
-        p.tiles_per_image = (int)cdiv(per_image, 256);
+        // a workgroup: 256 pixels x a block of output channels; the channel blocks count as
+        // tiles of the image here (grid.y stays 1)
+        p.PXW = 1; p.NW = 4; p.TM = 256; p.CB = 1; p.ws = 0; p.su = 0;
+        p.co_groups = (int)cdiv(Cout, conv_direct_channels());
+        p.tiles_per_image = (int)(p.co_groups * cdiv(ohw, 256));
         p.rows_out_max = 1; p.RHa = (int)eh; p.pitch = (int)W; p.padl = 0;
         p.G = p.G2 = p.S = p.nchi = 0; p.nchunks = 1;
         p.lds_w_bytes = p.lds_x_bytes = p.lds_o_offset = p.lds_o_bytes = p.lds_total = 0;
@@ -628,9 +631,9 @@ merit_status derive_conv(merit_plan *pl)
         const int64_t nt = (int64_t)N * p.tiles_per_image;
         li.grid[0] = nt < slots ? nt : slots;
         if (pool) li.grid[0] = (int64_t)N * p.NB;          // one workgroup per band, not persistent
-        if (p.variant == CONV_DIRECT) li.grid[0] = nt;     // one workgroup per 256 output elements
+        if (p.variant == CONV_DIRECT) li.grid[0] = nt;     // one workgroup per 256 pixels x 8 channels
     }
-    li.grid[1] = p.co_groups; li.grid[2] = 1;
+    li.grid[1] = p.variant == CONV_DIRECT ? 1 : p.co_groups; li.grid[2] = 1;
     li.block[0] = p.ws ? 512 : p.NW * 64; li.block[1] = 1; li.block[2] = 1;
     li.lds_bytes = (int64_t)conv_lds_bytes(p);
     li.tile[0] = 1; li.tile[1] = p.CB * 32; li.tile[2] = p.rows_out_max; li.tile[3] = OW;
