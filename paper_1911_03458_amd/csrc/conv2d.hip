@@ -1238,7 +1238,129 @@ __global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const 
 
     const int ntiles = p.N * p.tiles_per_image;
     bool first = true;
-    const bool multi = p.nchunks > 1;
+    // consecutive tiles share their halo rows: a contiguous run of each round of tiles per XCD
+    const int lwg = (int)xcd_band_item(blockIdx.x, (int)(gridDim.x >> 3), (int)(gridDim.x & 7));
+    for (int tile = lwg; tile < ntiles; tile += gridDim.x) {
+        const int n = (int)fdiv((uint32_t)tile, p.div_tiles);
+        const int m0 = (tile - n * p.tiles_per_image) * p.TM;
+        const int oyA = (int)fdiv((uint32_t)m0, p.div_ow);
+        const int mlast = min(m0 + p.TM, ohw) - 1;
+        const int oyB = (int)fdiv((uint32_t)mlast, p.div_ow);
+        const int yA = oyA * p.sh - p.ph;
+        const int RH = (oyB - oyA) * p.sh + (p.kh - 1) * p.dh + 1;
+
+        __syncthreads();
+        if (first) {
+            // first tile: half of the wavefronts fetch the weights (once per workgroup) while
+            // the other half fetches the input, so the two global-memory round trips overlap
+            if (wave < 2) stage_weights_chblock(p, w, wl, co_base, CB, 0, tid, 128);
+            else stage_input_chblock(p, x, xl, n, yA, RH, 0, tid - 128, 128);
+            first = false;
+        } else {
+            stage_input_chblock(p, x, xl, n, yA, RH, 0, tid, 256);
+        }
+        if (RES) stage_residual<CB, 4 * PXW * 32, 256>(p, outl, res, n, co_base, m0, tid);
+        __syncthreads();
+
+        int pbase[PXW], pcol[PXW];                  // staged row offset and column of tap kx = 0
+        const int lim8 = p.pitch & ~7;
+#pragma unroll
+        for (int pb = 0; pb < PXW; ++pb) {
+            const int m = m0 + (wave * PXW + pb) * 32 + c32;
+            const int mm = min(m, ohw - 1);
+            const int oy = (int)fdiv((uint32_t)mm, p.div_ow);
+            const int ox = mm - oy * p.OW;
+            pbase[pb] = ((h * half_nchi * p.RHa) + (oy - oyA) * p.sh) * p.pitch;
+            pcol[pb] = (p.padl - p.pw) + ox * p.sw;
+        }
+
+        floatx16 acc[CB][PXW];
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int pb = 0; pb < PXW; ++pb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[cb][pb][r] = 0.0f;
+
+        // K loop.  Step s = (chip, ky, kx), kx fastest; a lone wavefront per SIMD issues about one
+        // instruction per 4-5 cycles, so what counts is instructions per step (two MFMAs = 64
+        // cycles).  3x3 windows get the nine steps of a channel-group pair unrolled: weight
+        // fragments at immediate offsets, the three swizzled tap columns computed once per tile.
+        if (p.kh == 3 && p.kw == 3) {
+            int xc[PXW][3];
+#pragma unroll
+            for (int pb = 0; pb < PXW; ++pb)
+#pragma unroll
+                for (int kx = 0; kx < 3; ++kx) xc[pb][kx] = pbase[pb] + xsw(pcol[pb] + kx * p.dw, lim8);
+            for (int chip = 0; chip < half_nchi; ++chip) {
+                const uint4 *wa = wl + (chip * 9 * CB) * 64 + h * 32 + wsw(c32, chip + h * half_nchi);
+#pragma unroll
+                for (int ky = 0; ky < 3; ++ky) {
+                    const int rowoff = (chip * p.RHa + ky * p.dh) * p.pitch;
+#pragma unroll
+                    for (int kx = 0; kx < 3; ++kx) {
+                        Frag a[CB], b[PXW];
+#pragma unroll
+                        for (int cb = 0; cb < CB; ++cb) a[cb].u = wa[((ky * 3 + kx) * CB + cb) * 64];
+#pragma unroll
+                        for (int pb = 0; pb < PXW; ++pb) b[pb].u = xl[xc[pb][kx] + rowoff];
+#pragma unroll
+                        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                            for (int pb = 0; pb < PXW; ++pb) acc[cb][pb] = mfma16(a[cb], b[pb], acc[cb][pb]);
+                    }
+                }
+            }
+        } else {
+            int s = 0;
+            for (int chip = 0; chip < half_nchi; ++chip) {
+                const int wslot = h * 32 + wsw(c32, chip + h * half_nchi);
+                for (int ky = 0; ky < p.kh; ++ky) {
+                    const int rowoff = (chip * p.RHa + ky * p.dh) * p.pitch;
+                    for (int kx = 0; kx < p.kw; ++kx, ++s) {
+                        Frag a[CB], b[PXW];
+#pragma unroll
+                        for (int cb = 0; cb < CB; ++cb) a[cb].u = wl[(s * CB + cb) * 64 + wslot];
+#pragma unroll
+                        for (int pb = 0; pb < PXW; ++pb)
+                            b[pb].u = xl[pbase[pb] + rowoff + xsw(pcol[pb] + kx * p.dw, lim8)];
+#pragma unroll
+                        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                            for (int pb = 0; pb < PXW; ++pb) acc[cb][pb] = mfma16(a[cb], b[pb], acc[cb][pb]);
+                    }
+                }
+            }
+        }
+        store_tile<CB, PXW, 4, false>(p, acc, outl, y, n, co_base, m0, tid, RES);
+    }
+}
+
+// The same tile and K loop for layers whose weights and input rows do not fit LDS at once: the
+// channels go through in passes of p.nchi groups of eight and the accumulators stay in
+// registers across the passes (a kernel of its own: accumulators that live across the staging
+// code cost the single-pass kernel above 10 % of its speed).
+template <int CB, int PXW, bool RES>
+__global__ __launch_bounds__(256, (CB * PXW == 4 ? 1 : 2)) void merit_conv2d_chpass(ConvParams p, const uint16_t *__restrict__ x,
+                                                           const uint16_t *__restrict__ w,
+                                                           const uint16_t *__restrict__ res,
+                                                           uint16_t *__restrict__ y)
+{
+    touch_kernarg_lines();
+    extern __shared__ __align__(16) uint8_t smem[];
+    uint4 *wl = reinterpret_cast<uint4 *>(smem);
+    uint4 *xl = reinterpret_cast<uint4 *>(smem + p.lds_w_bytes);
+    uint32_t *outl = reinterpret_cast<uint32_t *>(smem + p.lds_o_offset);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6, h = lane >> 5, c32 = lane & 31;
+    const int co_base = blockIdx.y * CB * 32;
+    const int ohw = p.OH * p.OW;
+    const int half_nchi = p.nchi >> 1;
+
+    const int ntiles = p.N * p.tiles_per_image;
+    bool first = true;
+    constexpr bool MULTI = true, multi = true;
     // consecutive tiles share their halo rows: a contiguous run of each round of tiles per XCD
     const int lwg = (int)xcd_band_item(blockIdx.x, (int)(gridDim.x >> 3), (int)(gridDim.x & 7));
     for (int tile = lwg; tile < ntiles; tile += gridDim.x) {
@@ -1263,22 +1385,30 @@ __global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const 
         }
 
         floatx16 acc[CB][PXW];
+        auto clear_acc = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb)
+            for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-            for (int pb = 0; pb < PXW; ++pb)
+                for (int pb = 0; pb < PXW; ++pb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[cb][pb][r] = 0.0f;
+                    for (int r = 0; r < 16; ++r) acc[cb][pb][r] = 0.0f;
+        };
+        if (MULTI) clear_acc();
 
         // Channels go through LDS in passes of p.nchi groups of eight (one pass when everything
         // fits); the accumulators stay in registers across the passes.
-        for (int ck = 0; ck < p.nchunks; ++ck) {
+        const int npass = MULTI ? p.nchunks : 1;
+        for (int ck = 0; ck < npass; ++ck) {
             __syncthreads();                           // the previous pass (or tile) has been read
             const int chi0 = ck * p.nchi;
-            if (first || multi) {
-                // half of the wavefronts fetch the weights (once per workgroup when all channels
-                // fit in one pass) while the other half fetches the input, so the two
-                // global-memory round trips overlap
+            if (multi) {
+                // every pass needs its weights: all wavefronts fetch both (the weights are the
+                // larger part)
+                stage_weights_chblock(p, w, wl, co_base, CB, chi0, tid, 256);
+                stage_input_chblock(p, x, xl, n, yA, RH, chi0, tid, 256);
+            } else if (first) {
+                // half of the wavefronts fetch the weights (once per workgroup) while the other
+                // half fetches the input, so the two global-memory round trips overlap
                 if (wave < 2) stage_weights_chblock(p, w, wl, co_base, CB, chi0, tid, 128);
                 else stage_input_chblock(p, x, xl, n, yA, RH, chi0, tid - 128, 128);
                 first = false;
@@ -1287,6 +1417,7 @@ __global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const 
             }
             if (RES && ck == 0) stage_residual<CB, 4 * PXW * 32, 256>(p, outl, res, n, co_base, m0, tid);
             __syncthreads();
+            if (!MULTI) clear_acc();
 
             // K loop.  Step s = (chip, ky, kx), kx fastest; a lone wavefront per SIMD issues about one
             // instruction per 4-5 cycles, so what counts is instructions per step (two MFMAs = 64
@@ -1516,6 +1647,10 @@ hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, cons
     }
 #define MERIT_CHBLOCK(CBv, PXv)                                                                   \
     do {                                                                                          \
+        if (p.nchunks > 1) {                                                                      \
+            if (p.residual) return launch(merit_conv2d_chpass<CBv, PXv, true>, p, x, w, r, y, s, gx, lds);  \
+            return launch(merit_conv2d_chpass<CBv, PXv, false>, p, x, w, r, y, s, gx, lds);       \
+        }                                                                                         \
         if (p.residual) return launch(merit_conv2d_chblock<CBv, PXv, true>, p, x, w, r, y, s, gx, lds); \
         return launch(merit_conv2d_chblock<CBv, PXv, false>, p, x, w, r, y, s, gx, lds);          \
     } while (0)
@@ -1531,7 +1666,7 @@ const char *conv_kernel_name(const ConvParams &p)
     if (p.variant == CONV_PLANAR_SMALLC && p.ws && p.pool) return "merit_conv2d_planar_ws_pool";
     if (p.variant == CONV_PLANAR_SMALLC) return p.ws ? "merit_conv2d_planar_ws" : "merit_conv2d_planar";
     if (p.variant == CONV_DIRECT) return "merit_conv2d_direct";
-    return "merit_conv2d_chblock";
+    return p.nchunks > 1 ? "merit_conv2d_chpass" : "merit_conv2d_chblock";
 }
 
 }  // namespace merit
