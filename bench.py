@@ -406,6 +406,8 @@ def main():
             bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets, relu=True, pool=True),
             bench_conv(torch, mb, wl, wl.CFG2_CONV3, k, w, args.sets, relu=True, residual=True),
             bench_conv(torch, mb, wl, wl.CFG_DILATED, k, w, args.sets),
+            bench_conv(torch, mb, wl, wl.CFG_CONV256, max(10, k // 2), w, args.sets),
+            bench_conv(torch, mb, wl, wl.CFG_CONV11, max(10, k // 2), w, args.sets),
             bench_corr(torch, mb, wl, wl.CFG_CORRELATION, k, w),
             bench_depthwise(torch, mb, wl, wl.CFG_DEPTHWISE, k, w, args.sets),
             bench_sepfilter(torch, mb, wl, wl.CFG_SEP_K3, k, w, args.sets),

@@ -156,6 +156,10 @@ merit_status merit_plan_destroy(merit_plan *plan);
  * and call merit_plan_create.
  *  conv2d: y[n,co,oy,ox] = sum x[n,ci,oy*sh+ky-ph,ox*sw+kx-pw] * w[co,ci,ky,kx]
  *          (index pattern of Section III-C, Eq. 6: strided, no kernel flip).
+ *          Any channel counts, window, stride and padding within the index limits: the
+ *          planner picks an MFMA kernel (few input channels; all channels staged at once;
+ *          channels in passes) and, where no MFMA layout holds the shape, a vector-ALU kernel
+ *          (merit_launch_info.kernel names the choice).
  *  pool2d: max (is_avg=0) or mean over in-range elements (is_avg=1) of the window.
  *  sad:    frames [H,W] u8, ceil(H/block) x ceil(W/block) blocks of `block` x `block`
  *          pixels (blocks that reach past the frame edge read both frames with

@@ -114,6 +114,14 @@ CFG_ME_720P = SadWorkload("me_1280x720_b8_r16", 720, 1280, 8, 16, 0, "sinusoid")
 # full HD at its real height: 1080 = 67.5 blocks of 16, the last block row reaches past the frame
 CFG_ME_1080P = SadWorkload("me_1920x1080_b16_r32", 1080, 1920, 16, 32, 0, "uniform")
 CFG_DILATED = ConvWorkload("conv_8x32x64x64_co32_k3s1p2_d2", 8, 32, 64, 64, 32, 3, 3, 1, 1, 2, 2, "normal", 2, 2)
+# The paper's strided example (Section III-C, Eq. 6): 48 output channels of 55 x 55 from 3 input
+# channels under an 11 x 11 window, x = 4p + a - 5 (stride 4, padding 5 => a 220 x 220 input);
+# the batch is not given there: 8 here.  Its window is wider than the small-channel MFMA
+# kernel's fragments: the one-element-per-thread kernel takes it.
+CFG_CONV11 = ConvWorkload("conv_8x3x220x220_co48_k11s4p5", 8, 3, 220, 220, 48, 11, 11, 4, 4, 5, 5, "uniform")
+# A layer whose weights and input rows do not fit LDS at once (256 -> 256 channels, 3 x 3 on
+# 56 x 56, the shape class of the deeper layers of the paper's per-layer table): channels in passes.
+CFG_CONV256 = ConvWorkload("conv_8x256x56x56_co256_k3s1p1", 8, 256, 56, 56, 256, 3, 3, 1, 1, 1, 1, "normal")
 
 
 @dataclass(frozen=True)

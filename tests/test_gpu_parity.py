@@ -727,6 +727,26 @@ def test_conv_dilated(mb, case):
     _conv_check(mb, x, w, (sh, sw), (ph, pw), relu=bool(relu), dilation=(dh, dw))
 
 
+def test_conv_channel_passes_and_wide_window_workloads_sampled(mb):
+    """Full-size launches of the two layers beyond the MFMA single-pass kernels; the oracle
+    checks one image of the 256-channel layer and all of the 11 x 11 layer."""
+    c = wl.CFG_CONV256
+    x, w = wl.make_conv_inputs(c)
+    plan = mb.merit_plan_conv2d(c.N, c.Cin, c.H, c.W, c.Cout, c.kh, c.kw, c.sh, c.sw, c.ph, c.pw)
+    assert plan.launch_info()["kernel"] == "merit_conv2d_chpass"
+    y = mb.merit_conv2d(plan, dev(x), dev(w)).cpu().numpy().astype(np.float64)
+    n = 5
+    ref = oracle.conv2d(x[n:n + 1], w, (c.sh, c.sw), (c.ph, c.pw)).astype(np.float64)
+    assert np.all(np.abs(y[n:n + 1] - ref) <= 2e-2 * np.abs(ref) + 1e-3)
+    c = wl.CFG_CONV11
+    x, w = wl.make_conv_inputs(c)
+    plan = mb.merit_plan_conv2d(c.N, c.Cin, c.H, c.W, c.Cout, c.kh, c.kw, c.sh, c.sw, c.ph, c.pw)
+    assert plan.launch_info()["kernel"] == "merit_conv2d_direct" and plan.out_shape() == (8, 48, 55, 55)
+    y = mb.merit_conv2d(plan, dev(x), dev(w)).cpu().numpy().astype(np.float64)
+    ref = oracle.conv2d(x, w, (c.sh, c.sw), (c.ph, c.pw)).astype(np.float64)
+    assert np.all(np.abs(y - ref) <= 2e-2 * np.abs(ref) + 1e-3)
+
+
 def test_conv_dilated_one_hot_tap_shifts_the_input_exactly(mb):
     """x = p + 2a (Section III-C): a one-hot kernel returns the input shifted by twice the tap."""
     rng = np.random.default_rng(6)
