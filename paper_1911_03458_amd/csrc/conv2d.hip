@@ -1336,11 +1336,144 @@ __global__ __launch_bounds__(256) void merit_conv2d_chblock(ConvParams p, const 
     }
 }
 
+// ---- staging of the multi-pass kernel, split into "issue the loads" and "transpose and write
+// to LDS", so that the loads of a pass fly while the previous pass is multiplied.  For layers
+// the vector staging takes (Cin % 8 == 0, W % 8 == 0, T = 9 or 1 taps); the plan keeps a pass
+// within one (T = 9) or two (T = 1) weight units and CP_XU input units per thread: the
+// registers that hold a pass in flight must not push the kernel into spilling (a reload from
+// scratch waits for every load issued before it, the prefetched ones included).
+// weight units (8 channels x T taps of one output channel, 4T registers) per thread
+template <int T> struct CpWu { static constexpr int n = T >= 8 ? 1 : 2; };
+constexpr int CP_XU = 1;      // input units (8 channels x 8 pixels of one row, 32 registers) per thread
+
+template <int T>
+__device__ __forceinline__ void chpipe_issue_w(const ConvParams &p, const uint16_t *__restrict__ w, int co_base,
+                                               int CB, int chi0, int tid, uint32_t (&r)[CpWu<T>::n][4 * T])
+{
+    const int units = CB * 32 * p.nchi;
+#pragma unroll
+    for (int k = 0; k < CpWu<T>::n; ++k) {
+        const int u = min(tid + 256 * k, units - 1);
+        const int col = (int)fdiv((uint32_t)u, p.div_nchi);
+        const int chi = u - col * p.nchi;
+        const int co = co_base + col;
+        const bool ok = (co < p.Cout) && ((chi0 + chi) * 8 + 8 <= p.Cin);
+        // branch-free load (a padding unit re-reads unit 0 and is zeroed)
+        const uint4 *g = reinterpret_cast<const uint4 *>(w + (ok ? ((size_t)co * p.Cin + (chi0 + chi) * 8) * T : 0));
+#pragma unroll
+        for (int i = 0; i < T; ++i) {
+            const uint4 v = g[i];
+            r[k][4 * i + 0] = ok ? v.x : 0u; r[k][4 * i + 1] = ok ? v.y : 0u;
+            r[k][4 * i + 2] = ok ? v.z : 0u; r[k][4 * i + 3] = ok ? v.w : 0u;
+        }
+    }
+}
+
+template <int T>
+__device__ __forceinline__ void chpipe_commit_w(const ConvParams &p, uint4 *wl, int CB, int tid,
+                                                const uint32_t (&r)[CpWu<T>::n][4 * T])
+{
+    const int half_nchi = p.nchi >> 1;
+    const int units = CB * 32 * p.nchi;
+#pragma unroll
+    for (int k = 0; k < CpWu<T>::n; ++k) {
+        const int u = tid + 256 * k;
+        if (u >= units) break;
+        const int col = (int)fdiv((uint32_t)u, p.div_nchi);
+        const int chi = u - col * p.nchi;
+        const int hh = chi >= half_nchi ? 1 : 0;
+        const int chip = chi - hh * half_nchi;
+        const int cb = col >> 5, cc = col & 31;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            uint32_t d[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int e0 = (2 * q) * T + t, e1 = (2 * q + 1) * T + t;   // halves (c=2q,t), (c=2q+1,t)
+                const uint32_t sel =
+                    ((e0 & 1) ? 0x00000302u : 0x00000100u) | ((e1 & 1) ? 0x07060000u : 0x05040000u);
+                d[q] = __builtin_amdgcn_perm(r[k][e1 >> 1], r[k][e0 >> 1], sel);
+            }
+            const int s = chip * T + t;
+            wl[((s * CB + cb) * 2 + hh) * 32 + wsw(cc, chi)] = make_uint4(d[0], d[1], d[2], d[3]);
+        }
+    }
+}
+
+__device__ __forceinline__ void chpipe_issue_x(const ConvParams &p, const uint16_t *__restrict__ x, int n, int yA,
+                                               int RH, int chi0, int tid, uint32_t (&v)[CP_XU][8][4])
+{
+    const int W8 = p.W >> 3;
+    const int nu = p.nchi * p.RHa * W8;
+    const size_t chstride = (size_t)p.H * p.W;
+#pragma unroll
+    for (int k = 0; k < CP_XU; ++k) {
+        const int u = min(tid + 256 * k, nu - 1);
+        const int q = (int)fdiv((uint32_t)u, p.div_w8);
+        const int x8 = u - q * W8;
+        const int chi = (int)fdiv((uint32_t)q, p.div_rha);
+        const int r = q - chi * p.RHa;
+        const int gy = yA + r;
+        const bool rowok = r < RH && gy >= 0 && gy < p.H;
+        const int ch0 = (chi0 + chi) * 8;
+        const uint16_t *src = x + (((size_t)n * p.Cin + ch0) * p.H + (rowok ? gy : 0)) * p.W + 8 * x8;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            const bool ok = rowok && (ch0 + c < p.Cin);
+            // branch-free: a padding channel or row re-reads the tensor's first bytes and is zeroed
+            const uint4 t4 = *reinterpret_cast<const uint4 *>(ok ? src + c * chstride : x);
+            v[k][c][0] = ok ? t4.x : 0u; v[k][c][1] = ok ? t4.y : 0u;
+            v[k][c][2] = ok ? t4.z : 0u; v[k][c][3] = ok ? t4.w : 0u;
+        }
+    }
+}
+
+__device__ __forceinline__ void chpipe_commit_x(const ConvParams &p, uint4 *xl, int tid,
+                                                const uint32_t (&v)[CP_XU][8][4])
+{
+    const int W8 = p.W >> 3;
+    const int nu = p.nchi * p.RHa * W8;
+#pragma unroll
+    for (int k = 0; k < CP_XU; ++k) {
+        const int u = tid + 256 * k;
+        if (u >= nu) break;
+        const int q = (int)fdiv((uint32_t)u, p.div_w8);
+        const int x8 = u - q * W8;
+        const int chi = (int)fdiv((uint32_t)q, p.div_rha);
+        const int r = q - chi * p.RHa;
+        uint4 *dst = xl + (chi * p.RHa + r) * p.pitch;
+        const int col0 = p.padl + 8 * x8;
+#pragma unroll
+        for (int px = 0; px < 8; ++px) {
+            const uint32_t sel = (px & 1) ? 0x07060302u : 0x05040100u;
+            uint32_t d[4];
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq)
+                d[qq] = __builtin_amdgcn_perm(v[k][2 * qq + 1][px >> 1], v[k][2 * qq][px >> 1], sel);
+            dst[xsw(col0 + px, p.pitch & ~7)] = make_uint4(d[0], d[1], d[2], d[3]);
+        }
+    }
+}
+
+// zero the padding columns of the staged rows (they are the same in every pass of a tile)
+__device__ __forceinline__ void chpipe_zero_pad(const ConvParams &p, uint4 *xl, int tid)
+{
+    const int npad = p.pitch - p.W;
+    for (int u = tid; u < p.nchi * p.RHa * npad; u += 256) {
+        const int rowi = u / npad;
+        const int c = u - rowi * npad;
+        const int col = c < p.padl ? c : p.W + c;
+        xl[rowi * p.pitch + xsw(col, p.pitch & ~7)] = make_uint4(0, 0, 0, 0);
+    }
+}
+
 // The same tile and K loop for layers whose weights and input rows do not fit LDS at once: the
 // channels go through in passes of p.nchi groups of eight and the accumulators stay in
 // registers across the passes (a kernel of its own: accumulators that live across the staging
 // code cost the single-pass kernel above 10 % of its speed).
-template <int CB, int PXW, bool RES>
+// T = 9 or 1: the pipelined vector staging above (p.pipe says so); T = 0: any shape, a pass is
+// staged and then multiplied.
+template <int CB, int PXW, bool RES, int T>
 __global__ __launch_bounds__(256, (CB * PXW == 4 ? 1 : 2)) void merit_conv2d_chpass(ConvParams p, const uint16_t *__restrict__ x,
                                                            const uint16_t *__restrict__ w,
                                                            const uint16_t *__restrict__ res,
@@ -1398,10 +1531,24 @@ __global__ __launch_bounds__(256, (CB * PXW == 4 ? 1 : 2)) void merit_conv2d_chp
         // Channels go through LDS in passes of p.nchi groups of eight (one pass when everything
         // fits); the accumulators stay in registers across the passes.
         const int npass = MULTI ? p.nchunks : 1;
+        constexpr int TT = T > 0 ? T : 1;
+        uint32_t wreg[CpWu<TT>::n][4 * TT], xreg[CP_XU][8][4];
+        if constexpr (T > 0) {
+            chpipe_issue_w<TT>(p, w, co_base, CB, 0, tid, wreg);
+            chpipe_issue_x(p, x, n, yA, RH, 0, tid, xreg);
+        }
         for (int ck = 0; ck < npass; ++ck) {
             __syncthreads();                           // the previous pass (or tile) has been read
             const int chi0 = ck * p.nchi;
-            if (multi) {
+            if constexpr (T > 0) {
+                chpipe_commit_w<TT>(p, wl, CB, tid, wreg);
+                chpipe_commit_x(p, xl, tid, xreg);
+                if (ck == 0) chpipe_zero_pad(p, xl, tid);
+                if (ck + 1 < npass) {                  // the next pass's loads fly under this pass's MFMAs
+                    chpipe_issue_w<TT>(p, w, co_base, CB, chi0 + p.nchi, tid, wreg);
+                    chpipe_issue_x(p, x, n, yA, RH, chi0 + p.nchi, tid, xreg);
+                }
+            } else if (multi) {
                 // every pass needs its weights: all wavefronts fetch both (the weights are the
                 // larger part)
                 stage_weights_chblock(p, w, wl, co_base, CB, chi0, tid, 256);
@@ -1648,8 +1795,16 @@ hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, cons
 #define MERIT_CHBLOCK(CBv, PXv)                                                                   \
     do {                                                                                          \
         if (p.nchunks > 1) {                                                                      \
-            if (p.residual) return launch(merit_conv2d_chpass<CBv, PXv, true>, p, x, w, r, y, s, gx, lds);  \
-            return launch(merit_conv2d_chpass<CBv, PXv, false>, p, x, w, r, y, s, gx, lds);       \
+            if (p.pipe == 9) {                                                                    \
+                if (p.residual) return launch(merit_conv2d_chpass<CBv, PXv, true, 9>, p, x, w, r, y, s, gx, lds);  \
+                return launch(merit_conv2d_chpass<CBv, PXv, false, 9>, p, x, w, r, y, s, gx, lds);   \
+            }                                                                                     \
+            if (p.pipe == 1) {                                                                    \
+                if (p.residual) return launch(merit_conv2d_chpass<CBv, PXv, true, 1>, p, x, w, r, y, s, gx, lds);  \
+                return launch(merit_conv2d_chpass<CBv, PXv, false, 1>, p, x, w, r, y, s, gx, lds);   \
+            }                                                                                     \
+            if (p.residual) return launch(merit_conv2d_chpass<CBv, PXv, true, 0>, p, x, w, r, y, s, gx, lds);  \
+            return launch(merit_conv2d_chpass<CBv, PXv, false, 0>, p, x, w, r, y, s, gx, lds);    \
         }                                                                                         \
         if (p.residual) return launch(merit_conv2d_chblock<CBv, PXv, true>, p, x, w, r, y, s, gx, lds); \
         return launch(merit_conv2d_chblock<CBv, PXv, false>, p, x, w, r, y, s, gx, lds);          \

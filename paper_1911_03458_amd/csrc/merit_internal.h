@@ -103,6 +103,7 @@ struct ConvParams {
     int S;                 // MFMA K-steps (K = 16 each)
     int nchi;              // channel-blocked: 8-channel groups per pass incl. zero padding (even)
     int nchunks;           // channel-blocked: passes over the channels (1: everything is staged at once)
+    int pipe;              // multi-pass kernel: 9 or 1 = taps of the pipelined vector staging, 0 = plain staging
     int lds_w_bytes;       // weights region
     int lds_x_bytes;       // input region
     int lds_o_offset;      // output staging region: byte offset and size

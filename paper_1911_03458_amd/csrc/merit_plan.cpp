@@ -436,7 +436,7 @@ merit_status derive_conv(merit_plan *pl)
     auto try_variant = [&](int variant, int pxw, int nw) -> bool {
         ConvParams q = p;
         q.variant = variant;
-        q.nchunks = 1;
+        q.nchunks = 1; q.pipe = 0;
         q.PXW = pxw;
         q.NW = nw;
         q.TM = nw * pxw * 32;
@@ -488,10 +488,23 @@ merit_status derive_conv(merit_plan *pl)
             const int64_t per_pair = kh * kw * q.CB * 64 * 16 + 2 * (int64_t)q.RHa * pitch * 16;
             const int64_t o_bytes = (int64_t)q.CB * 32 * (q.TM / 2 + 2) * 4;
             int64_t pairs = nchi_all / 2;
+            q.pipe = 0;
             if (pairs * per_pair + o_bytes > LDS_LIMIT) {
                 pairs = (LDS_LIMIT / 2 - o_bytes) / per_pair;
                 if (pairs < 1) pairs = (LDS_LIMIT - o_bytes) / per_pair;
                 if (pairs < 1) return false;
+                // Layers the vector staging takes get the pipelined form of the multi-pass
+                // kernel (a pass's loads fly under the previous pass's MFMAs): a pass then is
+                // at most 1 (3x3) or 2 (1x1) weight units (8 channels x all taps of an output
+                // channel) and 1 input unit (8 channels x 8 pixels) per thread.
+                const int64_t T = kh * kw;
+                if ((T == 9 || T == 1) && (Cin % 8) == 0 && (W % 8) == 0) {
+                    int64_t pp = pairs;
+                    const int64_t by_w = (T == 9 ? 256 : 512) / (q.CB * 32 * 2), by_x = 256 / (2 * q.RHa * (W / 8));
+                    if (pp > by_w) pp = by_w;
+                    if (pp > by_x) pp = by_x;
+                    if (pp >= 1) { pairs = pp; q.pipe = (int)T; }
+                }
                 // equal passes (the last one is padded with zero channels otherwise)
                 const int64_t passes = cdiv(nchi_all / 2, pairs);
                 pairs = cdiv(nchi_all / 2, passes);
@@ -610,7 +623,7 @@ merit_status derive_conv(merit_plan *pl)
         p.co_groups = (int)cdiv(Cout, conv_direct_channels());
         p.tiles_per_image = (int)(p.co_groups * cdiv(ohw, 256));
         p.rows_out_max = 1; p.RHa = (int)eh; p.pitch = (int)W; p.padl = 0;
-        p.G = p.G2 = p.S = p.nchi = 0; p.nchunks = 1;
+        p.G = p.G2 = p.S = p.nchi = 0; p.nchunks = 1; p.pipe = 0;
         p.lds_w_bytes = p.lds_x_bytes = p.lds_o_offset = p.lds_o_bytes = p.lds_total = 0;
         p.front = p.aligned = p.lg_chunks = 0;
         p.wg_per_cu = 8;

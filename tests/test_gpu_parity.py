@@ -447,6 +447,12 @@ CONV_CASES = [
     (1, 520, 9, 16, 64, 1, 1, 1, 1, 0, 0),     # passes, 1x1 over many channels
     (1, 64, 20, 120, 32, 3, 3, 1, 1, 1, 1),    # passes because the rows are wide
     (1, 128, 21, 23, 64, 3, 3, 2, 2, 1, 1),    # passes, stride 2, odd sizes
+    # passes on the vector staging paths (3x3 or 1x1, Cin % 8 = 0, W % 8 = 0)
+    (1, 256, 20, 56, 64, 3, 3, 1, 1, 1, 1),    # 3x3 passes, two channel blocks
+    (2, 136, 9, 24, 40, 3, 3, 1, 1, 1, 1),     # last pass padded with zero channels, ragged blocks
+    (1, 128, 24, 24, 64, 3, 3, 2, 2, 1, 1),    # 3x3 passes, stride 2
+    (1, 512, 16, 64, 64, 1, 1, 1, 1, 0, 0),    # 1x1 passes
+    (1, 520, 12, 64, 96, 1, 1, 1, 1, 0, 0),    # 1x1 passes, three channel blocks in two groups
     # neither MFMA kernel: the one-element-per-thread kernel
     (1, 3, 67, 67, 48, 11, 11, 4, 4, 5, 5),    # the paper's strided example: x = 4p + a - 5, 11x11 window
     (2, 5, 30, 41, 7, 9, 12, 2, 3, 4, 6),      # wide window on few channels
@@ -631,6 +637,7 @@ RESIDUAL_CASES = [
     (2, 3, 17, 19, 40, 7, 7, 2, 2, 3, 3, 0),    # planar, odd sizes
     (40, 3, 64, 64, 64, 7, 7, 2, 2, 3, 3, 1),   # planar, several tiles per workgroup
     (1, 136, 10, 16, 64, 3, 3, 1, 1, 1, 1, 1),  # channel-block, channels in passes
+    (1, 256, 12, 56, 64, 3, 3, 1, 1, 1, 1, 1),  # channel-block, passes on the vector staging path
     (1, 3, 45, 45, 6, 11, 11, 4, 4, 0, 0, 1),   # one element per thread
 ]
 
