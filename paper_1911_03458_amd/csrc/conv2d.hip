@@ -1631,6 +1631,7 @@ __global__ __launch_bounds__(256, (CB * PXW == 4 ? 1 : 2)) void merit_conv2d_chp
 // workgroup (uniform addresses).  Workgroup index = (image, channel block, pixel block),
 // pixel block fastest.
 constexpr int DIRECT_CO = 8;
+constexpr int DIRECT_WTAPS = 1024;      // taps of one input channel held in LDS at a time (32 KB)
 
 __global__ __launch_bounds__(256) void merit_conv2d_direct(ConvParams p, const uint16_t *__restrict__ x,
                                                           const uint16_t *__restrict__ w,
@@ -1651,26 +1652,40 @@ __global__ __launch_bounds__(256) void merit_conv2d_direct(ConvParams p, const u
     const _Float16 *wh = reinterpret_cast<const _Float16 *>(w);
     const int T = p.kh * p.kw;
     const int iy0 = oy * p.sh - p.ph, ix0 = ox * p.sw - p.pw;
-    // output channels past the last one repeat it (computed, not stored)
-    int wrow[DIRECT_CO];
-#pragma unroll
-    for (int j = 0; j < DIRECT_CO; ++j) wrow[j] = min(co0 + j, p.Cout - 1) * p.Cin * T;
+    // The weights of the workgroup's DIRECT_CO output channels for one input channel and a chunk
+    // of window rows go to LDS as fp32, [tap][channel]: a tap's 8 weights are two 16-byte
+    // reads of one address for the whole wavefront instead of 8 two-byte global loads.
+    // Output channels past the last one repeat it (computed, not stored).
+    __shared__ __align__(16) float wsh[DIRECT_WTAPS * DIRECT_CO];
+    const int kyc = max(1, min(p.kh, DIRECT_WTAPS / p.kw));          // window rows per chunk (kw <= 64)
     float acc[DIRECT_CO];
 #pragma unroll
     for (int j = 0; j < DIRECT_CO; ++j) acc[j] = 0.0f;
     for (int ci = 0; ci < p.Cin; ++ci) {
         const _Float16 *xc = xh + (size_t)ci * p.H * p.W;
-        for (int ky = 0; ky < p.kh; ++ky) {
-            const int iy = iy0 + ky * p.dh;
-            const bool rowok = iy >= 0 && iy < p.H;
-            const _Float16 *xr = xc + (rowok ? iy : 0) * p.W;
-            const int wt = ci * T + ky * p.kw;
-            for (int kx = 0; kx < p.kw; ++kx) {
-                const int ix = ix0 + kx * p.dw;
-                const bool ok = rowok && ix >= 0 && ix < p.W;
-                const float v = ok ? (float)xr[ok ? ix : 0] : 0.0f;   // zero padding
-#pragma unroll
-                for (int j = 0; j < DIRECT_CO; ++j) acc[j] = fmaf(v, (float)wh[wrow[j] + wt + kx], acc[j]);
+        for (int ky0 = 0; ky0 < p.kh; ky0 += kyc) {
+            const int nky = min(kyc, p.kh - ky0);
+            __syncthreads();                                         // the previous chunk has been read
+            for (int i = (int)threadIdx.x; i < nky * p.kw * DIRECT_CO; i += 256) {
+                const int t = i / DIRECT_CO, j = i - t * DIRECT_CO;
+                wsh[i] = (float)wh[(min(co0 + j, p.Cout - 1) * p.Cin + ci) * T + ky0 * p.kw + t];
+            }
+            __syncthreads();
+            for (int ky = 0; ky < nky; ++ky) {
+                const int iy = iy0 + (ky0 + ky) * p.dh;
+                const bool rowok = iy >= 0 && iy < p.H;
+                const _Float16 *xr = xc + (rowok ? iy : 0) * p.W;
+                const float4 *wt = reinterpret_cast<const float4 *>(wsh + ky * p.kw * DIRECT_CO);
+                for (int kx = 0; kx < p.kw; ++kx) {
+                    const int ix = ix0 + kx * p.dw;
+                    const bool ok = rowok && ix >= 0 && ix < p.W;
+                    const float v = ok ? (float)xr[ok ? ix : 0] : 0.0f;   // zero padding
+                    const float4 w0 = wt[2 * kx], w1 = wt[2 * kx + 1];
+                    acc[0] = fmaf(v, w0.x, acc[0]); acc[1] = fmaf(v, w0.y, acc[1]);
+                    acc[2] = fmaf(v, w0.z, acc[2]); acc[3] = fmaf(v, w0.w, acc[3]);
+                    acc[4] = fmaf(v, w1.x, acc[4]); acc[5] = fmaf(v, w1.y, acc[5]);
+                    acc[6] = fmaf(v, w1.z, acc[6]); acc[7] = fmaf(v, w1.w, acc[7]);
+                }
             }
         }
     }

@@ -624,7 +624,8 @@ merit_status derive_conv(merit_plan *pl)
         p.tiles_per_image = (int)(p.co_groups * cdiv(ohw, 256));
         p.rows_out_max = 1; p.RHa = (int)eh; p.pitch = (int)W; p.padl = 0;
         p.G = p.G2 = p.S = p.nchi = 0; p.nchunks = 1; p.pipe = 0;
-        p.lds_w_bytes = p.lds_x_bytes = p.lds_o_offset = p.lds_o_bytes = p.lds_total = 0;
+        p.lds_w_bytes = p.lds_x_bytes = p.lds_o_offset = p.lds_o_bytes = 0;
+        p.lds_total = 32 * 1024;          // the kernel's own (static) weight buffer
         p.front = p.aligned = p.lg_chunks = 0;
         p.wg_per_cu = 8;
         p.div_ow = make_fastdiv((uint32_t)OW);
