@@ -129,6 +129,16 @@ merit_status derive_pool(merit_plan *pl)
             p.div_ow4 = make_fastdiv((uint32_t)(OW / 4));
         }
     }
+    // one output per plane (global pooling): a wavefront per plane, no staging
+    if (variant == POOL_TILE_GENERIC && OH == 1 && OW == 1 && pl->tile_req[2] <= 0 && pl->tile_req[3] <= 0 &&
+        H * W < INT_LIMIT) {
+        p.variant = variant = POOL_PLANE;
+        p.TH = p.TW = 1; p.tiles_y = p.tiles_x = 1;
+        p.RH = p.RW = p.pitch = 0;
+        const int64_t g = cdiv((int64_t)p.NC, 4);
+        if (g >= (1ll << 31)) return MERIT_ERR_UNSUPPORTED;
+        p.grid = (int)g;
+    }
     if (variant == POOL_TILE_GENERIC) {
         p.variant = POOL_TILE_GENERIC;
         int64_t TW = OW < 64 ? OW : 64;
@@ -150,7 +160,7 @@ merit_status derive_pool(merit_plan *pl)
         p.div_rw = make_fastdiv((uint32_t)RW);
         p.div_tw = make_fastdiv((uint32_t)TW);
     }
-    if (variant != POOL_STREAM_K3S2P1) {
+    if (variant != POOL_STREAM_K3S2P1 && variant != POOL_PLANE) {
         const int64_t g = (int64_t)p.NC * p.tiles_y * p.tiles_x;
         if (g >= (1ll << 31)) return MERIT_ERR_UNSUPPORTED;
         p.grid = (int)g;

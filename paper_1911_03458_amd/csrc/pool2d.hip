@@ -250,6 +250,38 @@ __global__ __launch_bounds__(256) void merit_pool2d_stream_k3s2p1(PoolParams p, 
 }
 
 // ---------------------------------------------------------------------------
+// ---------------------------------------------------------------------------
+// One output per plane (OH = OW = 1: global pooling, the window covers what it can reach of
+// the plane): a wavefront per plane, lanes stride over the in-range window elements, the
+// 64 partial results are folded with six lane exchanges.  No LDS, no barrier.
+// ---------------------------------------------------------------------------
+template <bool AVG>
+__global__ __launch_bounds__(256) void merit_pool2d_plane(PoolParams p, const float *__restrict__ x,
+                                                         float *__restrict__ y)
+{
+    const int lane = threadIdx.x & 63;
+    const int plane = (int)blockIdx.x * 4 + (int)(threadIdx.x >> 6);
+    if (plane >= p.NC) return;                                      // whole wavefronts leave
+    const int y0 = max(-p.ph, 0), y1 = min(-p.ph + p.kh, p.H);      // in-range part of the window
+    const int x0 = max(-p.pw, 0), x1 = min(-p.pw + p.kw, p.W);
+    const int rw = max(x1 - x0, 0), cnt = max(y1 - y0, 0) * rw;
+    const float *xp = x + (size_t)plane * p.H * p.W;
+    float acc = AVG ? 0.0f : -INFINITY;
+    for (int i = lane; i < cnt; i += 64) {
+        const int r = i / rw;
+        const float v = xp[(size_t)(y0 + r) * p.W + x0 + (i - r * rw)];
+        if (AVG) acc += v;
+        else acc = (v > acc) ? v : acc;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float o = __shfl_xor(acc, off);
+        if (AVG) acc += o;
+        else acc = (o > acc) ? o : acc;
+    }
+    if (lane == 0) y[plane] = AVG ? (cnt > 0 ? acc / (float)cnt : 0.0f) : acc;
+}
+
 template <typename K>
 static hipError_t launch(K kernel, const PoolParams &p, const float *x, float *y, hipStream_t s,
                          size_t lds_bytes, uint32_t grid)
@@ -264,6 +296,9 @@ hipError_t launch_pool2d(const PoolParams &p, const float *x, float *y, hipStrea
     const uint32_t grid = (uint32_t)p.grid;
     const size_t lds_bytes = (size_t)p.RH * p.pitch * sizeof(float);
     switch (p.variant) {
+    case POOL_PLANE:
+        return p.is_avg ? launch(merit_pool2d_plane<true>, p, x, y, s, 0, grid)
+                        : launch(merit_pool2d_plane<false>, p, x, y, s, 0, grid);
     case POOL_STREAM_K3S2P1:
         if (p.TH == 4)
             return p.is_avg ? launch(merit_pool2d_stream_k3s2p1<true, 4>, p, x, y, s, 0, grid)
@@ -291,6 +326,7 @@ hipError_t launch_pool2d(const PoolParams &p, const float *x, float *y, hipStrea
 const char *pool_kernel_name(const PoolParams &p)
 {
     switch (p.variant) {
+    case POOL_PLANE: return p.is_avg ? "merit_pool2d_plane<avg>" : "merit_pool2d_plane<max>";
     case POOL_STREAM_K3S2P1: return p.is_avg ? "merit_pool2d_stream_k3s2p1<avg>" : "merit_pool2d_stream_k3s2p1<max>";
     case POOL_ROWS_K3S2P1: return p.is_avg ? "merit_pool2d_rows<3,3,2,2,1,avg>" : "merit_pool2d_rows<3,3,2,2,1,max>";
     case POOL_ROWS_K2S2P0: return p.is_avg ? "merit_pool2d_rows<2,2,2,2,0,avg>" : "merit_pool2d_rows<2,2,2,2,0,max>";

@@ -460,3 +460,12 @@ def test_conv_plans_for_layers_that_do_not_fit_lds_at_once():
         p.set_tile((0, 0, 4, 32))
     with pytest.raises(mb.MeritError):
         mb.merit_plan_conv2d_pool(1, 3, 224, 224, 64, 11, 11, 2, 2, 5, 5)
+
+
+def test_pool_plan_one_output_per_plane():
+    li = mb.merit_plan_pool2d(32, 512, 7, 7, 7, 7, 1, 1, 0, 0, 1).launch_info()
+    assert li["kernel"] == "merit_pool2d_plane<avg>" and li["grid"][0] == 32 * 512 // 4 and li["lds_bytes"] == 0
+    p = mb.merit_plan_pool2d(1, 3, 5, 6, 7, 8, 1, 1, 1, 1, 0)
+    assert p.out_shape() == (1, 3, 1, 1) and p.launch_info()["kernel"] == "merit_pool2d_plane<max>"
+    p.set_tile((0, 0, 1, 1))                               # a tile request names the generic kernel
+    assert p.launch_info()["kernel"] == "merit_pool2d_tile<max>"

@@ -54,6 +54,11 @@ POOL_CASES = [
     (1, 1, 130, 200, 3, 3, 2, 2, 1, 1),    # wide plane, several tiles
     (1, 1, 9, 9, 9, 9, 1, 1, 4, 4),        # window as large as the image
     (1, 2, 4, 4, 2, 2, 2, 2, 1, 1),        # corner windows hold a single element
+    # one output per plane: the wavefront-per-plane kernel
+    (3, 37, 7, 7, 7, 7, 1, 1, 0, 0),       # global pooling of 7x7 planes, planes not a multiple of 4
+    (1, 5, 9, 13, 9, 13, 2, 3, 0, 0),      # 117 elements: two rounds of lanes
+    (2, 6, 5, 6, 7, 8, 1, 1, 1, 1),        # window larger than the plane: padding on every side
+    (1, 4, 1, 1, 1, 1, 1, 1, 0, 0),        # a single element per plane
 ]
 
 
