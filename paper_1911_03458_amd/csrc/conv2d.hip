@@ -57,14 +57,14 @@ __device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, v);
 }
 
-// Touch every 64-byte line of the kernel's argument block (ConvParams + four pointers) with
-// the first scalar loads, so that the later ones, issued where their values are needed, hit
+// Touch every 64-byte line of the kernel's argument block (ConvParams + four pointers = five
+// lines, and the line after them that holds the grid extents) with the first scalar loads, so that the later ones, issued where their values are needed, hit
 // the scalar cache instead of each paying a trip to memory.
 __device__ __forceinline__ void touch_kernarg_lines()
 {
     typedef const uint32_t __attribute__((address_space(4))) *kernarg_ptr;
     kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
-    const uint32_t warm = ka[16] ^ ka[32] ^ ka[48] ^ ka[64];
+    const uint32_t warm = ka[16] ^ ka[32] ^ ka[48] ^ ka[64] ^ ka[80];   // 80: the grid extents after the pointers
     asm volatile("" ::"s"(warm));
 }
 
@@ -1048,7 +1048,7 @@ __device__ __forceinline__ void stage_weights_chblock_vec(const ConvParams &p, c
     const int half_nchi = p.nchi >> 1;
     const int units = CB * 32 * p.nchi;
     // batches of WB units: every load of a batch is issued before the first use
-    constexpr int WB = (T >= 8) ? 4 : 8;
+    constexpr int WB = (T >= 16) ? 1 : (T >= 8) ? 4 : 8;     // 4T registers per unit
     for (int u0 = t0; u0 < units; u0 += nthr * WB) {
         uint32_t src[WB][4 * T];
 #pragma unroll
@@ -1122,13 +1122,17 @@ __device__ __forceinline__ void stage_weights_chblock_scalar(const ConvParams &p
     }
 }
 
-// chi0: first channel group of the pass (the groups of a pass are numbered from 0 in LDS)
+// chi0: first channel group of the pass (the groups of a pass are numbered from 0 in LDS).
+// WIDE adds the vector path for 5x5 windows (100 registers per unit: only the multi-pass
+// kernel takes it; in the single-pass kernel it would cost the second wavefront per SIMD).
+template <bool WIDE = false>
 __device__ __forceinline__ void stage_weights_chblock(const ConvParams &p, const uint16_t *__restrict__ w,
                                                       uint4 *wl, int co_base, int CB, int chi0, int t0, int nthr)
 {
     const int T = p.kh * p.kw;
     if (T == 9 && (p.Cin & 7) == 0) stage_weights_chblock_vec<9>(p, w, wl, co_base, CB, chi0, t0, nthr);
     else if (T == 1 && (p.Cin & 7) == 0) stage_weights_chblock_vec<1>(p, w, wl, co_base, CB, chi0, t0, nthr);
+    else if (WIDE && T == 25 && (p.Cin & 7) == 0) stage_weights_chblock_vec<25>(p, w, wl, co_base, CB, chi0, t0, nthr);
     else stage_weights_chblock_scalar(p, w, wl, co_base, CB, chi0, t0, nthr);
 }
 
@@ -1551,7 +1555,7 @@ __global__ __launch_bounds__(256, (CB * PXW == 4 ? 1 : 2)) void merit_conv2d_chp
             } else if (multi) {
                 // every pass needs its weights: all wavefronts fetch both (the weights are the
                 // larger part)
-                stage_weights_chblock(p, w, wl, co_base, CB, chi0, tid, 256);
+                stage_weights_chblock<true>(p, w, wl, co_base, CB, chi0, tid, 256);
                 stage_input_chblock(p, x, xl, n, yA, RH, chi0, tid, 256);
             } else if (first) {
                 // half of the wavefronts fetch the weights (once per workgroup) while the other

@@ -103,7 +103,6 @@ struct ConvParams {
     int S;                 // MFMA K-steps (K = 16 each)
     int nchi;              // channel-blocked: 8-channel groups per pass incl. zero padding (even)
     int nchunks;           // channel-blocked: passes over the channels (1: everything is staged at once)
-    int pipe;              // multi-pass kernel: 9 or 1 = taps of the pipelined vector staging, 0 = plain staging
     int lds_w_bytes;       // weights region
     int lds_x_bytes;       // input region
     int lds_o_offset;      // output staging region: byte offset and size
@@ -132,6 +131,9 @@ struct ConvParams {
     FastDiv div_tiles;
     FastDiv div_nb;        // fused pooling: bands per image
     FastDiv div_pw8;       // fused pooling: units per pooled row
+    // (sizeof(ConvParams) + the four pointers = 320 bytes = five 64-byte kernel-argument lines; the grid
+    // extents HIP appends start a sixth: touch_kernarg_lines in conv2d.hip covers all six)
+    int pipe;              // multi-pass kernel: 9 or 1 = taps of the pipelined vector staging, 0 = plain staging
 };
 
 // ---- launchers (defined in the .hip files) --------------------------------
