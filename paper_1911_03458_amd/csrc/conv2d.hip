@@ -1471,13 +1471,60 @@ __device__ __forceinline__ void chpipe_zero_pad(const ConvParams &p, uint4 *xl, 
     }
 }
 
+// The same for widths that are not a multiple of 8: a unit is one pixel x 8 channels, eight
+// 2-byte loads (a lane a pixel, so each of the eight is coalesced along the row).
+constexpr int CP_XS = 3;      // such units per thread
+
+__device__ __forceinline__ void chpipe_issue_xs(const ConvParams &p, const uint16_t *__restrict__ x, int n, int yA,
+                                                int RH, int chi0, int tid, uint16_t (&v)[CP_XS][8])
+{
+    const int nu = p.nchi * p.RHa * p.W;
+#pragma unroll
+    for (int k = 0; k < CP_XS; ++k) {
+        const int u = min(tid + 256 * k, nu - 1);
+        const int q = u / p.W;
+        const int xg = u - q * p.W;
+        const int chi = (int)fdiv((uint32_t)q, p.div_rha);
+        const int r = q - chi * p.RHa;
+        const int gy = yA + r;
+        const bool rowok = r < RH && gy >= 0 && gy < p.H;
+        const int ch0 = (chi0 + chi) * 8;
+        const uint16_t *src = x + (((size_t)n * p.Cin + ch0) * p.H + (rowok ? gy : 0)) * p.W + xg;
+        const size_t chstride = (size_t)p.H * p.W;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            const bool ok = rowok && (ch0 + c < p.Cin);
+            const uint16_t t = *(ok ? src + c * chstride : x);        // branch-free; zeroed below
+            v[k][c] = ok ? t : (uint16_t)0;
+        }
+    }
+}
+
+__device__ __forceinline__ void chpipe_commit_xs(const ConvParams &p, uint4 *xl, int tid,
+                                                 const uint16_t (&v)[CP_XS][8])
+{
+    const int nu = p.nchi * p.RHa * p.W;
+#pragma unroll
+    for (int k = 0; k < CP_XS; ++k) {
+        const int u = tid + 256 * k;
+        if (u >= nu) break;
+        const int q = u / p.W;
+        const int xg = u - q * p.W;
+        uint32_t d[4];
+#pragma unroll
+        for (int qq = 0; qq < 4; ++qq) d[qq] = (uint32_t)v[k][2 * qq] | ((uint32_t)v[k][2 * qq + 1] << 16);
+        xl[q * p.pitch + xsw(p.padl + xg, p.pitch & ~7)] = make_uint4(d[0], d[1], d[2], d[3]);
+    }
+}
+
 // The same tile and K loop for layers whose weights and input rows do not fit LDS at once: the
 // channels go through in passes of p.nchi groups of eight and the accumulators stay in
 // registers across the passes (a kernel of its own: accumulators that live across the staging
 // code cost the single-pass kernel above 10 % of its speed).
 // T = 9 or 1: the pipelined vector staging above (p.pipe says so); T = 0: any shape, a pass is
 // staged and then multiplied.
-template <int CB, int PXW, bool RES, int T>
+// XV: the input rows take the 16-byte staging (W % 8 == 0), else the per-pixel one.
+template <int CB, int PXW, bool RES, int T, bool XV = true>
 __global__ __launch_bounds__(256, (CB * PXW == 4 ? 1 : 2)) void merit_conv2d_chpass(ConvParams p, const uint16_t *__restrict__ x,
                                                            const uint16_t *__restrict__ w,
                                                            const uint16_t *__restrict__ res,
@@ -1536,21 +1583,25 @@ __global__ __launch_bounds__(256, (CB * PXW == 4 ? 1 : 2)) void merit_conv2d_chp
         // fits); the accumulators stay in registers across the passes.
         const int npass = MULTI ? p.nchunks : 1;
         constexpr int TT = T > 0 ? T : 1;
-        uint32_t wreg[CpWu<TT>::n][4 * TT], xreg[CP_XU][8][4];
+        uint32_t wreg[CpWu<TT>::n][4 * TT], xreg[XV ? CP_XU : 1][8][4];
+        uint16_t xsreg[XV ? 1 : CP_XS][8];
         if constexpr (T > 0) {
             chpipe_issue_w<TT>(p, w, co_base, CB, 0, tid, wreg);
-            chpipe_issue_x(p, x, n, yA, RH, 0, tid, xreg);
+            if constexpr (XV) chpipe_issue_x(p, x, n, yA, RH, 0, tid, xreg);
+            else chpipe_issue_xs(p, x, n, yA, RH, 0, tid, xsreg);
         }
         for (int ck = 0; ck < npass; ++ck) {
             __syncthreads();                           // the previous pass (or tile) has been read
             const int chi0 = ck * p.nchi;
             if constexpr (T > 0) {
                 chpipe_commit_w<TT>(p, wl, CB, tid, wreg);
-                chpipe_commit_x(p, xl, tid, xreg);
+                if constexpr (XV) chpipe_commit_x(p, xl, tid, xreg);
+                else chpipe_commit_xs(p, xl, tid, xsreg);
                 if (ck == 0) chpipe_zero_pad(p, xl, tid);
                 if (ck + 1 < npass) {                  // the next pass's loads fly under this pass's MFMAs
                     chpipe_issue_w<TT>(p, w, co_base, CB, chi0 + p.nchi, tid, wreg);
-                    chpipe_issue_x(p, x, n, yA, RH, chi0 + p.nchi, tid, xreg);
+                    if constexpr (XV) chpipe_issue_x(p, x, n, yA, RH, chi0 + p.nchi, tid, xreg);
+                    else chpipe_issue_xs(p, x, n, yA, RH, chi0 + p.nchi, tid, xsreg);
                 }
             } else if (multi) {
                 // every pass needs its weights: all wavefronts fetch both (the weights are the
@@ -1814,13 +1865,21 @@ hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, cons
 #define MERIT_CHBLOCK(CBv, PXv)                                                                   \
     do {                                                                                          \
         if (p.nchunks > 1) {                                                                      \
-            if (p.pipe == 9) {                                                                    \
+            if (p.pipe == 9 && (p.W & 7) == 0) {                                                  \
                 if (p.residual) return launch(merit_conv2d_chpass<CBv, PXv, true, 9>, p, x, w, r, y, s, gx, lds);  \
                 return launch(merit_conv2d_chpass<CBv, PXv, false, 9>, p, x, w, r, y, s, gx, lds);   \
             }                                                                                     \
-            if (p.pipe == 1) {                                                                    \
+            if (p.pipe == 1 && (p.W & 7) == 0) {                                                  \
                 if (p.residual) return launch(merit_conv2d_chpass<CBv, PXv, true, 1>, p, x, w, r, y, s, gx, lds);  \
                 return launch(merit_conv2d_chpass<CBv, PXv, false, 1>, p, x, w, r, y, s, gx, lds);   \
+            }                                                                                     \
+            if (p.pipe == 9) {                                                                    \
+                if (p.residual) return launch(merit_conv2d_chpass<CBv, PXv, true, 9, false>, p, x, w, r, y, s, gx, lds);  \
+                return launch(merit_conv2d_chpass<CBv, PXv, false, 9, false>, p, x, w, r, y, s, gx, lds);   \
+            }                                                                                     \
+            if (p.pipe == 1) {                                                                    \
+                if (p.residual) return launch(merit_conv2d_chpass<CBv, PXv, true, 1, false>, p, x, w, r, y, s, gx, lds);  \
+                return launch(merit_conv2d_chpass<CBv, PXv, false, 1, false>, p, x, w, r, y, s, gx, lds);   \
             }                                                                                     \
             if (p.residual) return launch(merit_conv2d_chpass<CBv, PXv, true, 0>, p, x, w, r, y, s, gx, lds);  \
             return launch(merit_conv2d_chpass<CBv, PXv, false, 0>, p, x, w, r, y, s, gx, lds);    \

@@ -503,14 +503,16 @@ merit_status derive_conv(merit_plan *pl)
                 pairs = (LDS_LIMIT / 2 - o_bytes) / per_pair;
                 if (pairs < 1) pairs = (LDS_LIMIT - o_bytes) / per_pair;
                 if (pairs < 1) return false;
-                // Layers the vector staging takes get the pipelined form of the multi-pass
+                // 3x3 and 1x1 layers with Cin % 8 == 0 get the pipelined form of the multi-pass
                 // kernel (a pass's loads fly under the previous pass's MFMAs): a pass then is
                 // at most 1 (3x3) or 2 (1x1) weight units (8 channels x all taps of an output
-                // channel) and 1 input unit (8 channels x 8 pixels) per thread.
+                // channel) and 1 input unit of 8 channels x 8 pixels (3 of 8 x 1 when W % 8 != 0) per thread.
                 const int64_t T = kh * kw;
-                if ((T == 9 || T == 1) && (Cin % 8) == 0 && (W % 8) == 0) {
+                if ((T == 9 || T == 1) && (Cin % 8) == 0) {
                     int64_t pp = pairs;
-                    const int64_t by_w = (T == 9 ? 256 : 512) / (q.CB * 32 * 2), by_x = 256 / (2 * q.RHa * (W / 8));
+                    const int64_t by_w = (T == 9 ? 256 : 512) / (q.CB * 32 * 2);
+                    // input: one 8-pixel unit per thread (W % 8 == 0), else three 1-pixel units
+                    const int64_t by_x = (W % 8) == 0 ? 256 / (2 * q.RHa * (W / 8)) : 768 / (2 * q.RHa * W);
                     if (pp > by_w) pp = by_w;
                     if (pp > by_x) pp = by_x;
                     if (pp >= 1) { pairs = pp; q.pipe = (int)T; }
