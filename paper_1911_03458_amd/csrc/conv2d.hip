@@ -1482,7 +1482,7 @@ __device__ __forceinline__ void chpipe_issue_xs(const ConvParams &p, const uint1
 #pragma unroll
     for (int k = 0; k < CP_XS; ++k) {
         const int u = min(tid + 256 * k, nu - 1);
-        const int q = u / p.W;
+        const int q = (int)fdiv((uint32_t)u, p.div_w);
         const int xg = u - q * p.W;
         const int chi = (int)fdiv((uint32_t)q, p.div_rha);
         const int r = q - chi * p.RHa;
@@ -1508,7 +1508,7 @@ __device__ __forceinline__ void chpipe_commit_xs(const ConvParams &p, uint4 *xl,
     for (int k = 0; k < CP_XS; ++k) {
         const int u = tid + 256 * k;
         if (u >= nu) break;
-        const int q = u / p.W;
+        const int q = (int)fdiv((uint32_t)u, p.div_w);
         const int xg = u - q * p.W;
         uint32_t d[4];
 #pragma unroll

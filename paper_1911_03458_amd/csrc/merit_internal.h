@@ -131,9 +131,10 @@ struct ConvParams {
     FastDiv div_tiles;
     FastDiv div_nb;        // fused pooling: bands per image
     FastDiv div_pw8;       // fused pooling: units per pooled row
-    // (sizeof(ConvParams) + the four pointers = 320 bytes = five 64-byte kernel-argument lines; the grid
-    // extents HIP appends start a sixth: touch_kernarg_lines in conv2d.hip covers all six)
+    // (ConvParams + the four pointers end in the sixth 64-byte kernel-argument line, where the grid
+    // extents HIP appends follow: touch_kernarg_lines in conv2d.hip covers all six)
     int pipe;              // multi-pass kernel: 9 or 1 = taps of the pipelined vector staging, 0 = plain staging
+    FastDiv div_w;         // multi-pass kernel, one-pixel staging units: W
 };
 
 // ---- launchers (defined in the .hip files) --------------------------------

@@ -515,7 +515,7 @@ merit_status derive_conv(merit_plan *pl)
                     const int64_t by_x = (W % 8) == 0 ? 256 / (2 * q.RHa * (W / 8)) : 768 / (2 * q.RHa * W);
                     if (pp > by_w) pp = by_w;
                     if (pp > by_x) pp = by_x;
-                    if (pp >= 1) { pairs = pp; q.pipe = (int)T; }
+                    if (pp >= 1 && fastdiv_ok(768, W)) { pairs = pp; q.pipe = (int)T; q.div_w = make_fastdiv((uint32_t)W); }
                 }
                 // equal passes (the last one is padded with zero channels otherwise)
                 const int64_t passes = cdiv(nchi_all / 2, pairs);
