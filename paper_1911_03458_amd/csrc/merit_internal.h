@@ -44,7 +44,7 @@ __device__ __forceinline__ uint32_t xcd_band_item(uint32_t hw_id, int xq, int xr
 
 // ---- pooling ---------------------------------------------------------------
 enum PoolVariant { POOL_TILE_GENERIC = 0, POOL_ROWS_K3S2P1 = 1, POOL_ROWS_K2S2P0 = 2, POOL_ROWS_K3S1P1 = 3,
-                   POOL_STREAM_K3S2P1 = 4, POOL_PLANE = 5 };
+                   POOL_STREAM_K3S2P1 = 4, POOL_PLANE = 5, POOL_LANES_K3S2 = 6 };
 
 struct PoolParams {
     int NC, H, W, OH, OW;

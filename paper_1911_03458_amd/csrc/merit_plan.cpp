@@ -129,6 +129,25 @@ merit_status derive_pool(merit_plan *pl)
             p.div_ow4 = make_fastdiv((uint32_t)(OW / 4));
         }
     }
+    // 3x3 / stride 2 on a width the 16-byte kernels do not take: a lane per output column
+    if (variant == POOL_TILE_GENERIC && kh == 3 && kw == 3 && sh == 2 && sw == 2 && ph <= 1 && pw <= 1 &&
+        !(OH == 1 && OW == 1) && pl->tile_req[2] <= 0 && pl->tile_req[3] <= 0 && H * W < INT_LIMIT) {
+        int lg_shift = 0;                                   // items per wavefront = 1 << lg_shift
+        while (lg_shift < 2 && (64 >> (lg_shift + 1)) >= OW) ++lg_shift;
+        const int64_t chunks = cdiv(OW, 64), strips = cdiv(OH, 4);
+        const int64_t items = N * C * chunks * strips;
+        if (items < INT_LIMIT && fastdiv_ok(items, chunks) && fastdiv_ok(items, strips)) {
+            p.variant = variant = POOL_LANES_K3S2;
+            p.TH = 4; p.TW = (int)(OW < 64 ? OW : 64);
+            p.tiles_y = (int)strips; p.tiles_x = (int)chunks;
+            p.RH = p.RW = p.pitch = 0;
+            p.lg_shift = lg_shift;
+            p.items = (int)items;
+            p.div_tiles_x = make_fastdiv((uint32_t)chunks);
+            p.div_tiles_y = make_fastdiv((uint32_t)strips);
+            p.grid = (int)cdiv(items, 4 * (1 << lg_shift));
+        }
+    }
     // one output per plane (global pooling): a wavefront per plane, no staging
     if (variant == POOL_TILE_GENERIC && OH == 1 && OW == 1 && pl->tile_req[2] <= 0 && pl->tile_req[3] <= 0 &&
         H * W < INT_LIMIT) {
@@ -160,7 +179,7 @@ merit_status derive_pool(merit_plan *pl)
         p.div_rw = make_fastdiv((uint32_t)RW);
         p.div_tw = make_fastdiv((uint32_t)TW);
     }
-    if (variant != POOL_STREAM_K3S2P1 && variant != POOL_PLANE) {
+    if (variant != POOL_STREAM_K3S2P1 && variant != POOL_PLANE && variant != POOL_LANES_K3S2) {
         const int64_t g = (int64_t)p.NC * p.tiles_y * p.tiles_x;
         if (g >= (1ll << 31)) return MERIT_ERR_UNSUPPORTED;
         p.grid = (int)g;

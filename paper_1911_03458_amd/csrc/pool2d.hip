@@ -282,6 +282,73 @@ __global__ __launch_bounds__(256) void merit_pool2d_plane(PoolParams p, const fl
     if (lane == 0) y[plane] = AVG ? (cnt > 0 ? acc / (float)cnt : 0.0f) : acc;
 }
 
+// ---------------------------------------------------------------------------
+// 3x3 / stride 2 window on any width (padding 0 or 1): a lane per output column, no LDS, no
+// barrier.  A group of 16, 32 or 64 lanes (the smallest that holds a row of outputs, 64-column
+// chunks beyond that) owns LANES_TH output rows of one plane: per input row a lane loads its
+// three columns (neighbouring lanes' loads overlap in one column and coalesce), reduces them,
+// and every row result is used by the one or two output rows it belongs to.  All loads of a
+// strip are issued before the first use.  tiles_x = column chunks, tiles_y = row strips.
+// ---------------------------------------------------------------------------
+constexpr int LANES_TH = 4;
+
+template <bool AVG>
+__global__ __launch_bounds__(256) void merit_pool2d_lanes_k3s2(PoolParams p, const float *__restrict__ x,
+                                                              float *__restrict__ y)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lpi = 64 >> p.lg_shift;                        // lanes per item
+    const int l = lane & (lpi - 1);
+    const int item = (wave << p.lg_shift) + (lane >> (6 - p.lg_shift));
+    const bool live_item = item < p.items;
+    const int it = live_item ? item : 0;
+    const uint32_t q0 = fdiv((uint32_t)it, p.div_tiles_x);
+    const int chunk = it - (int)q0 * p.tiles_x;
+    const uint32_t nc = fdiv(q0, p.div_tiles_y);
+    const int strip = (int)q0 - (int)nc * p.tiles_y;
+    const int ox = chunk * 64 + l;
+    const bool live = live_item && ox < p.OW;
+    const int oy0 = strip * LANES_TH;
+    const int ytop = oy0 * 2 - p.ph, xleft = min(ox, p.OW - 1) * 2 - p.pw;
+    const float fill = AVG ? 0.0f : -INFINITY;
+    const float *xp = x + (size_t)nc * p.H * p.W;
+
+    float v[2 * LANES_TH + 1][3];
+#pragma unroll
+    for (int r = 0; r < 2 * LANES_TH + 1; ++r) {
+        const int gy = ytop + r;
+        const bool rowok = gy >= 0 && gy < p.H;
+        const float *row = xp + (size_t)(rowok ? gy : 0) * p.W;
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+            const int gx = xleft + k;
+            const bool ok = rowok && gx >= 0 && gx < p.W;
+            const float t = row[ok ? gx : 0];                       // branch-free; replaced below
+            v[r][k] = ok ? t : fill;
+        }
+    }
+    float rr[2 * LANES_TH + 1];
+#pragma unroll
+    for (int r = 0; r < 2 * LANES_TH + 1; ++r)
+        rr[r] = AVG ? (v[r][0] + v[r][1]) + v[r][2] : fmaxf(fmaxf(v[r][0], v[r][1]), v[r][2]);
+    float *yp = y + (size_t)nc * p.OH * p.OW;
+#pragma unroll
+    for (int i = 0; i < LANES_TH; ++i) {
+        const int oy = oy0 + i;
+        float o = AVG ? (rr[2 * i] + rr[2 * i + 1]) + rr[2 * i + 2]
+                      : fmaxf(fmaxf(rr[2 * i], rr[2 * i + 1]), rr[2 * i + 2]);
+        if (AVG) {
+            const int wy0 = 2 * oy - p.ph, wx0 = 2 * ox - p.pw;
+            const int cy = min(wy0 + 3, p.H) - max(wy0, 0);
+            const int cx = min(wx0 + 3, p.W) - max(wx0, 0);
+            const int cnt = max(cy, 0) * max(cx, 0);
+            o = cnt > 0 ? o / (float)cnt : 0.0f;
+        }
+        if (live && oy < p.OH) yp[(size_t)oy * p.OW + ox] = o;
+    }
+}
+
 template <typename K>
 static hipError_t launch(K kernel, const PoolParams &p, const float *x, float *y, hipStream_t s,
                          size_t lds_bytes, uint32_t grid)
@@ -296,6 +363,9 @@ hipError_t launch_pool2d(const PoolParams &p, const float *x, float *y, hipStrea
     const uint32_t grid = (uint32_t)p.grid;
     const size_t lds_bytes = (size_t)p.RH * p.pitch * sizeof(float);
     switch (p.variant) {
+    case POOL_LANES_K3S2:
+        return p.is_avg ? launch(merit_pool2d_lanes_k3s2<true>, p, x, y, s, 0, grid)
+                        : launch(merit_pool2d_lanes_k3s2<false>, p, x, y, s, 0, grid);
     case POOL_PLANE:
         return p.is_avg ? launch(merit_pool2d_plane<true>, p, x, y, s, 0, grid)
                         : launch(merit_pool2d_plane<false>, p, x, y, s, 0, grid);
@@ -327,6 +397,7 @@ const char *pool_kernel_name(const PoolParams &p)
 {
     switch (p.variant) {
     case POOL_PLANE: return p.is_avg ? "merit_pool2d_plane<avg>" : "merit_pool2d_plane<max>";
+    case POOL_LANES_K3S2: return p.is_avg ? "merit_pool2d_lanes_k3s2<avg>" : "merit_pool2d_lanes_k3s2<max>";
     case POOL_STREAM_K3S2P1: return p.is_avg ? "merit_pool2d_stream_k3s2p1<avg>" : "merit_pool2d_stream_k3s2p1<max>";
     case POOL_ROWS_K3S2P1: return p.is_avg ? "merit_pool2d_rows<3,3,2,2,1,avg>" : "merit_pool2d_rows<3,3,2,2,1,max>";
     case POOL_ROWS_K2S2P0: return p.is_avg ? "merit_pool2d_rows<2,2,2,2,0,avg>" : "merit_pool2d_rows<2,2,2,2,0,max>";

@@ -469,3 +469,11 @@ def test_pool_plan_one_output_per_plane():
     assert p.out_shape() == (1, 3, 1, 1) and p.launch_info()["kernel"] == "merit_pool2d_plane<max>"
     p.set_tile((0, 0, 1, 1))                               # a tile request names the generic kernel
     assert p.launch_info()["kernel"] == "merit_pool2d_tile<max>"
+
+
+def test_pool_plan_lane_per_column_for_odd_widths():
+    li = mb.merit_plan_pool2d(32, 96, 55, 55, 3, 3, 2, 2, 0, 0, 0).launch_info()
+    assert li["kernel"] == "merit_pool2d_lanes_k3s2<max>" and li["lds_bytes"] == 0
+    assert li["grid"][0] == -(-(32 * 96 * 7) // 8)          # 7 strips of 4 rows, two items per wavefront
+    # the 16-byte kernels keep the shapes they take
+    assert mb.merit_plan_pool2d(16, 64, 112, 112, 3, 3, 2, 2, 1, 1, 0).launch_info()["kernel"].startswith("merit_pool2d_stream")

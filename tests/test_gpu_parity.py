@@ -54,6 +54,12 @@ POOL_CASES = [
     (1, 1, 130, 200, 3, 3, 2, 2, 1, 1),    # wide plane, several tiles
     (1, 1, 9, 9, 9, 9, 1, 1, 4, 4),        # window as large as the image
     (1, 2, 4, 4, 2, 2, 2, 2, 1, 1),        # corner windows hold a single element
+    # 3x3 / stride 2 on widths the 16-byte kernels do not take: a lane per output column
+    (2, 5, 55, 55, 3, 3, 2, 2, 0, 0),      # 27 outputs per row: two items per wavefront
+    (1, 3, 13, 13, 3, 3, 2, 2, 0, 0),      # 6 outputs per row: four items per wavefront
+    (1, 2, 9, 150, 3, 3, 2, 2, 1, 1),      # 75 outputs per row: two column chunks
+    (1, 4, 6, 5, 3, 3, 2, 2, 0, 1),        # mixed padding, tiny plane
+    (3, 7, 27, 27, 3, 3, 2, 2, 0, 0),      # items not a multiple of the wavefront's share
     # one output per plane: the wavefront-per-plane kernel
     (3, 37, 7, 7, 7, 7, 1, 1, 0, 0),       # global pooling of 7x7 planes, planes not a multiple of 4
     (1, 5, 9, 13, 9, 13, 2, 3, 0, 0),      # 117 elements: two rounds of lanes
