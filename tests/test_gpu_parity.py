@@ -1151,3 +1151,68 @@ def test_launches_can_be_captured_in_a_graph(mb):
         assert np.all(np.abs(yavg.cpu().numpy() - ra) <= 1e-5 * np.abs(ra) + 1e-6), rep
         rc = oracle.conv2d(xc, w, (1, 1), (1, 1), relu=True).astype(np.float64)
         assert np.all(np.abs(yc.cpu().numpy().astype(np.float64) - rc) <= 2e-2 * np.abs(rc) + 1e-3), rep
+
+
+def test_more_launches_can_be_captured_in_a_graph(mb):
+    """The same for the kernels with more host-side work in their launchers: the long-window
+    separable filter (its persistent grid is sized by an occupancy query), the multi-pass and
+    the one-element-per-thread convolution, the lane-per-column and per-plane pooling, and the
+    correlation layer.  One eager call each, then capture, then replays with eager work between."""
+    rng = np.random.default_rng(78)
+    sep = mb.merit_plan_sepfilter(1, 70, 136, 30)
+    kx = rng.standard_normal(30).astype(np.float32); ky = rng.standard_normal(30).astype(np.float32)
+    xs = torch.zeros((1, 70, 136), dtype=torch.float32, device="cuda:0"); ys = torch.empty_like(xs)
+    cp = mb.merit_plan_conv2d(1, 136, 10, 16, 40, 3, 3, 1, 1, 1, 1)
+    cd = mb.merit_plan_conv2d(1, 3, 45, 45, 6, 11, 11, 4, 4, 0, 0)
+    assert cp.launch_info()["kernel"] == "merit_conv2d_chpass" and cd.launch_info()["kernel"] == "merit_conv2d_direct"
+    wp = (rng.standard_normal((40, 136, 3, 3)) / 35).astype(np.float16)
+    wd = (rng.standard_normal((6, 3, 11, 11)) / 19).astype(np.float16)
+    xp = torch.zeros((1, 136, 10, 16), dtype=torch.float16, device="cuda:0")
+    xd = torch.zeros((1, 3, 45, 45), dtype=torch.float16, device="cuda:0")
+    yp = torch.empty(cp.out_shape(), dtype=torch.float16, device="cuda:0")
+    yd = torch.empty(cd.out_shape(), dtype=torch.float16, device="cuda:0")
+    pl = mb.merit_plan_pool2d(2, 5, 27, 27, 3, 3, 2, 2, 0, 0, 0)
+    pg = mb.merit_plan_pool2d(2, 5, 27, 27, 27, 27, 1, 1, 0, 0, 1)
+    xq = torch.zeros((2, 5, 27, 27), dtype=torch.float32, device="cuda:0")
+    yl = torch.empty(pl.out_shape(), dtype=torch.float32, device="cuda:0")
+    yg = torch.empty(pg.out_shape(), dtype=torch.float32, device="cuda:0")
+    co = mb.merit_plan_correlation(1, 24, 12, 24, 3, 2)
+    x1 = torch.zeros((1, 24, 12, 24), dtype=torch.float16, device="cuda:0"); x2 = torch.zeros_like(x1)
+    yo = torch.empty(co.out_shape(), dtype=torch.float16, device="cuda:0")
+    dkx, dky, dwp, dwd = dev(kx), dev(ky), dev(wp), dev(wd)
+
+    def launch_all():
+        mb.merit_sepfilter(sep, xs, dkx, dky, ys)
+        mb.merit_conv2d(cp, xp, dwp, yp)
+        mb.merit_conv2d(cd, xd, dwd, yd)
+        mb.merit_pool2d(pl, xq, yl)
+        mb.merit_pool2d(pg, xq, yg)
+        mb.merit_correlation(co, x1, x2, yo)
+
+    launch_all()                                                    # eager first
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        launch_all()
+    for rep in range(2):
+        a = rng.uniform(0, 255, (1, 70, 136)).astype(np.float32)
+        b = rng.standard_normal((1, 136, 10, 16)).astype(np.float16)
+        c = rng.standard_normal((1, 3, 45, 45)).astype(np.float16)
+        d = rng.standard_normal((2, 5, 27, 27)).astype(np.float32)
+        e1 = (rng.standard_normal((1, 24, 12, 24)) / 5).astype(np.float16)
+        e2 = rng.standard_normal((1, 24, 12, 24)).astype(np.float16)
+        for t, v in ((xs, a), (xp, b), (xd, c), (xq, d), (x1, e1), (x2, e2)):
+            t.copy_(torch.from_numpy(v))                            # eager work between replays
+        for t in (ys, yp, yd, yl, yg, yo):
+            t.fill_(-7.0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.all(np.abs(ys.cpu().numpy() - oracle.sepfilter(a, kx, ky)) <= _sep_tol(a, kx, ky)), rep
+        for got, ref in ((yp, oracle.conv2d(b, wp, (1, 1), (1, 1))), (yd, oracle.conv2d(c, wd, (4, 4), (0, 0))),
+                         (yo, oracle.correlation(e1, e2, 3, 2))):
+            gg, rr = got.cpu().numpy().astype(np.float64), ref.astype(np.float64)
+            assert np.all(np.abs(gg - rr) <= 2e-2 * np.abs(rr) + 1e-3), rep
+        assert np.array_equal(yl.cpu().numpy(), oracle.pool2d(d, (3, 3), (2, 2), (0, 0), "max")), rep
+        rg = oracle.pool2d(d, (27, 27), (1, 1), (0, 0), "avg")
+        assert np.all(np.abs(yg.cpu().numpy() - rg) <= 1e-5 * np.abs(rg) + 1e-6), rep
