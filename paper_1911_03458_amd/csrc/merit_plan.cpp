@@ -456,6 +456,10 @@ merit_status derive_conv(merit_plan *pl)
     const int64_t ohw = OH * OW;
     const int64_t ncb = cdiv(Cout, 32);
     p.CB = ncb >= 2 ? 2 : 1;
+    // A grid that would leave more than half of the 256 CUs idle gets 32-channel blocks, i.e. twice
+    // the workgroups (channel-block kernels; 8x128x56x56 -> 128, 3x3 / s2: 112 -> 224 workgroups,
+    // 24.4 -> 14.5 us; with more workgroups than that the 64-channel blocks win: half the input staging).
+    if (ncb >= 2 && Cin >= 8 && !pool && N * cdiv(ohw, 128) * cdiv(ncb, 2) <= 128) p.CB = 1;
     p.co_groups = (int)cdiv(ncb, p.CB);
 
     // try both tile sizes for a variant; prefer 256 pixels when the grid stays large

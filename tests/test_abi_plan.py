@@ -448,7 +448,7 @@ def test_conv_plans_for_layers_that_do_not_fit_lds_at_once():
     window on few channels fits neither MFMA layout; the tile request and the fused pooling
     stay with the MFMA kernels."""
     for shape in ((1, 512, 14, 14, 512, 3, 3, 1, 1, 1, 1), (1, 96, 27, 27, 256, 5, 5, 1, 1, 2, 2),
-                  (1, 64, 224, 224, 64, 3, 3, 1, 1, 1, 1), (1, 256, 56, 56, 64, 1, 1, 1, 1, 0, 0)):
+                  (1, 64, 224, 224, 64, 3, 3, 1, 1, 1, 1), (8, 256, 56, 56, 64, 1, 1, 1, 1, 0, 0)):
         li = mb.merit_plan_conv2d(*shape).launch_info()
         assert li["kernel"] == "merit_conv2d_chpass" and 0 < li["lds_bytes"] <= 160 * 1024, (shape, li)
     alex1 = (1, 3, 227, 227, 96, 11, 11, 4, 4, 0, 0)

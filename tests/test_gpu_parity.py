@@ -464,6 +464,11 @@ CONV_CASES = [
     (1, 128, 24, 24, 64, 3, 3, 2, 2, 1, 1),    # 3x3 passes, stride 2
     (1, 512, 16, 64, 64, 1, 1, 1, 1, 0, 0),    # 1x1 passes
     (1, 520, 12, 64, 96, 1, 1, 1, 1, 0, 0),    # 1x1 passes, three channel blocks in two groups
+    # the same kernels with 64-channel blocks (grids of more than 128 workgroups keep them)
+    (70, 35, 12, 18, 52, 7, 5, 1, 1, 3, 3),    # passes, scalar weight staging
+    (33, 200, 14, 14, 70, 3, 3, 1, 1, 1, 1),   # passes, 3x3, one-pixel input units
+    (17, 256, 20, 56, 64, 3, 3, 1, 1, 1, 1),   # passes, 3x3, 8-pixel input units
+    (20, 520, 12, 64, 96, 1, 1, 1, 1, 0, 0),   # passes, 1x1
     # neither MFMA kernel: the one-element-per-thread kernel
     (1, 3, 67, 67, 48, 11, 11, 4, 4, 5, 5),    # the paper's strided example: x = 4p + a - 5, 11x11 window
     (2, 5, 30, 41, 7, 9, 12, 2, 3, 4, 6),      # wide window on few channels
@@ -649,6 +654,7 @@ RESIDUAL_CASES = [
     (40, 3, 64, 64, 64, 7, 7, 2, 2, 3, 3, 1),   # planar, several tiles per workgroup
     (1, 136, 10, 16, 64, 3, 3, 1, 1, 1, 1, 1),  # channel-block, channels in passes
     (1, 256, 12, 56, 64, 3, 3, 1, 1, 1, 1, 1),  # channel-block, passes on the vector staging path
+    (22, 256, 12, 56, 64, 3, 3, 1, 1, 1, 1, 1), # the same with 64-channel blocks (more than 128 workgroups)
     (1, 3, 45, 45, 6, 11, 11, 4, 4, 0, 0, 1),   # one element per thread
 ]
 
@@ -1162,12 +1168,12 @@ def test_more_launches_can_be_captured_in_a_graph(mb):
     sep = mb.merit_plan_sepfilter(1, 70, 136, 30)
     kx = rng.standard_normal(30).astype(np.float32); ky = rng.standard_normal(30).astype(np.float32)
     xs = torch.zeros((1, 70, 136), dtype=torch.float32, device="cuda:0"); ys = torch.empty_like(xs)
-    cp = mb.merit_plan_conv2d(1, 136, 10, 16, 40, 3, 3, 1, 1, 1, 1)
+    cp = mb.merit_plan_conv2d(1, 264, 10, 16, 40, 3, 3, 1, 1, 1, 1)
     cd = mb.merit_plan_conv2d(1, 3, 45, 45, 6, 11, 11, 4, 4, 0, 0)
     assert cp.launch_info()["kernel"] == "merit_conv2d_chpass" and cd.launch_info()["kernel"] == "merit_conv2d_direct"
-    wp = (rng.standard_normal((40, 136, 3, 3)) / 35).astype(np.float16)
+    wp = (rng.standard_normal((40, 264, 3, 3)) / 49).astype(np.float16)
     wd = (rng.standard_normal((6, 3, 11, 11)) / 19).astype(np.float16)
-    xp = torch.zeros((1, 136, 10, 16), dtype=torch.float16, device="cuda:0")
+    xp = torch.zeros((1, 264, 10, 16), dtype=torch.float16, device="cuda:0")
     xd = torch.zeros((1, 3, 45, 45), dtype=torch.float16, device="cuda:0")
     yp = torch.empty(cp.out_shape(), dtype=torch.float16, device="cuda:0")
     yd = torch.empty(cd.out_shape(), dtype=torch.float16, device="cuda:0")
@@ -1196,7 +1202,7 @@ def test_more_launches_can_be_captured_in_a_graph(mb):
         launch_all()
     for rep in range(2):
         a = rng.uniform(0, 255, (1, 70, 136)).astype(np.float32)
-        b = rng.standard_normal((1, 136, 10, 16)).astype(np.float16)
+        b = rng.standard_normal((1, 264, 10, 16)).astype(np.float16)
         c = rng.standard_normal((1, 3, 45, 45)).astype(np.float16)
         d = rng.standard_normal((2, 5, 27, 27)).astype(np.float32)
         e1 = (rng.standard_normal((1, 24, 12, 24)) / 5).astype(np.float16)
