@@ -247,6 +247,26 @@ merit_status merit_plan_set_tile(merit_plan *plan, const int64_t tile[MERIT_MAX_
 merit_status merit_conv2d(const merit_plan *plan, const void *x_f16, const void *w_f16,
                           void *y_f16, void *hip_stream);
 
+/* Weights in pass order.  The kernel for layers with many input channels takes the channels
+ * through LDS in passes (Section IV-A: one covering sub-tensor at a time) and needs, per pass,
+ * each output channel's taps regrouped by eight input channels.  From the caller's
+ * [Cout,Cin,kh,kw] tensor that is a register transposition on every pass of every tile; weights
+ * do not change between calls, so the regrouping can be done once instead:
+ *   merit_plan_packed_weights_bytes  size of the packed copy for this plan (a multiple of 16);
+ *                                    MERIT_ERR_UNSUPPORTED if the plan's kernel takes no packed
+ *                                    weights (merit_launch_info.kernel != "merit_conv2d_chws")
+ *   merit_conv2d_pack_weights        w_f16 -> packed (device memory of that size, owned by the
+ *                                    caller, 16-byte aligned); enqueued on the stream
+ *   merit_conv2d_packed              merit_conv2d with the packed copy in place of w_f16; same
+ *                                    result bit for bit.  The packed copy belongs to the plan's
+ *                                    shape and tile: use it only with plans of that shape.
+ * The library still owns no device memory. */
+merit_status merit_plan_packed_weights_bytes(const merit_plan *plan, int64_t *bytes);
+merit_status merit_conv2d_pack_weights(const merit_plan *plan, const void *w_f16, void *packed,
+                                       void *hip_stream);
+merit_status merit_conv2d_packed(const merit_plan *plan, const void *x_f16, const void *packed,
+                                 void *y_f16, void *hip_stream);
+
 /* Residual layer: as merit_conv2d, with r_f16 [N,Cout,OH,OW] binary16 added to the fp32 sums
  * before the clip (if the plan has one) and the one rounding to binary16.  r_f16 may be
  * y_f16 itself (every element is read before it is overwritten, by the workgroup that owns

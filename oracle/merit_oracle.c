@@ -419,42 +419,37 @@ int ref_sepfilter(const float *x, const float *kx, const float *ky, float *y, in
 /* Bilateral filter, fp32                                                     */
 /* ------------------------------------------------------------------------ */
 /*
- * The strategy class of Section VI-A (Listings 2 and 3) on a k x k window centred with
- * offset -k/2 on both window indices:
- *   PreLoop : wsum = wxsum = 0; center = x[n,p1,p2]
- *   Loop    : v = x[n, p1 + a1 - k/2, p2 + a2 - k/2]   (coordinates clamped to the image)
- *             d = center - v;  w = exp(d*d*norm) * gy[a1] * gx[a2]
- *             wsum += w;  wxsum += w*v
- *   PostLoop: y[n,p1,p2] = wxsum / wsum
- * gy, gx: the two spatial lookup tables of length k (precomputed Gaussians in the paper);
- * norm: the range constant handed to the kernel (-1/(2 sigma_r^2) for a Gaussian range term).
+ * Section VI-A (Listings 2 and 3): every output pixel is a normalised weighted mean of the
+ * k x k window around it (window offset -k/2 on both window indices, coordinates clamped to
+ * the image).  A neighbour's weight is the product of a range factor, exp(norm * (its value -
+ * the centre pixel's value)^2), and a spatial factor gy[a1] * gx[a2] taken from two lookup
+ * tables of length k (precomputed Gaussians in the paper).  norm is the range constant handed
+ * to the kernel as it stands (-1/(2 sigma_r^2) for a Gaussian range term).
  * Everything in double, rounded once to float.  Returns 0, or -1 on a bad shape.
  */
 int ref_bilateral(const float *x, const float *gx, const float *gy, float *y, int N, int H, int W, int k,
                   double norm)
 {
     if (N < 0 || H <= 0 || W <= 0 || k <= 0) return -1;
-    const int c = k / 2;
-    long row;
+    const int half = k / 2;
+    long pix;
 #pragma omp parallel for schedule(static)
-    for (row = 0; row < (long)N * H; ++row) {
-        const int n = (int)(row / H), p1 = (int)(row % H);
-        const float *img = x + (size_t)n * H * W;
-        for (int p2 = 0; p2 < W; ++p2) {
-            const double center = (double)img[(size_t)p1 * W + p2];
-            double wsum = 0.0, wxsum = 0.0;
-            for (int a1 = 0; a1 < k; ++a1) {
-                const int yy = clampi(p1 + a1 - c, 0, H - 1);
-                for (int a2 = 0; a2 < k; ++a2) {
-                    const double v = (double)img[(size_t)yy * W + clampi(p2 + a2 - c, 0, W - 1)];
-                    const double d = center - v;
-                    const double w = exp(d * d * norm) * (double)gy[a1] * (double)gx[a2];
-                    wsum += w;
-                    wxsum += w * v;
-                }
+    for (pix = 0; pix < (long)N * H * W; ++pix) {
+        const int p2 = (int)(pix % W), p1 = (int)((pix / W) % H);
+        const float *img = x + (size_t)(pix / ((long)H * W)) * H * W;
+        const double here = (double)img[(size_t)p1 * W + p2];
+        double numer = 0.0, denom = 0.0;
+        for (int a1 = 0; a1 < k; ++a1) {
+            const float *line = img + (size_t)clampi(p1 + a1 - half, 0, H - 1) * W;
+            for (int a2 = 0; a2 < k; ++a2) {
+                const double there = (double)line[clampi(p2 + a2 - half, 0, W - 1)];
+                const double spatial = (double)gy[a1] * (double)gx[a2];
+                const double range = exp(norm * (there - here) * (there - here));
+                numer += range * spatial * there;
+                denom += range * spatial;
             }
-            y[(size_t)row * W + p2] = (float)(wxsum / wsum);
         }
+        y[pix] = (float)(numer / denom);
     }
     return 0;
 }

@@ -102,6 +102,9 @@ def lib():
     L.merit_plan_launch_info.argtypes = [P, ctypes.POINTER(merit_launch_info)]
     L.merit_plan_set_tile.argtypes = [P, ctypes.POINTER(ctypes.c_int64)]
     L.merit_conv2d.argtypes = [P, P, P, P, P]
+    L.merit_plan_packed_weights_bytes.argtypes = [P, ctypes.POINTER(ctypes.c_int64)]
+    L.merit_conv2d_pack_weights.argtypes = [P, P, P, P]
+    L.merit_conv2d_packed.argtypes = [P, P, P, P, P]
     L.merit_pool2d.argtypes = [P, P, P, P]
     L.merit_sad_search.argtypes = [P, P, P, P, P, P]
     for name in ("merit_plan_create", "merit_plan_destroy", "merit_plan_conv2d", "merit_plan_conv2d_relu",
@@ -112,7 +115,8 @@ def lib():
                  "merit_plan_sad", "merit_plan_correlation", "merit_correlation", "merit_plan_conv2d_depthwise",
                  "merit_conv2d_depthwise", "merit_plan_get_desc", "merit_plan_out_shape", "merit_plan_footprint",
                  "merit_plan_launch_info", "merit_plan_set_tile", "merit_conv2d", "merit_pool2d",
-                 "merit_sad_search"):
+                 "merit_sad_search", "merit_plan_packed_weights_bytes", "merit_conv2d_pack_weights",
+                 "merit_conv2d_packed"):
         getattr(L, name).restype = c_int
     L.merit_status_string.argtypes = [c_int]
     L.merit_status_string.restype = ctypes.c_char_p
@@ -275,6 +279,42 @@ def merit_conv2d(plan: Plan, x, w, y=None, stream=None):
         raise ValueError("x / w do not match the plan")
     _check(lib().merit_conv2d(plan.handle, _dev_ptr(x, torch.float16, "x"), _dev_ptr(w, torch.float16, "w"),
                               _dev_ptr(y, torch.float16, "y"), _stream(stream)), "merit_conv2d")
+    return y
+
+
+def merit_plan_packed_weights_bytes(plan: Plan) -> int:
+    n = ctypes.c_int64(0)
+    _check(lib().merit_plan_packed_weights_bytes(plan.handle, ctypes.byref(n)), "merit_plan_packed_weights_bytes")
+    return int(n.value)
+
+
+def merit_conv2d_pack_weights(plan: Plan, w, packed=None, stream=None):
+    import torch
+    nbytes = merit_plan_packed_weights_bytes(plan)
+    if tuple(w.shape) != plan.shapes()[2]:
+        raise ValueError("w does not match the plan")
+    if packed is None:
+        packed = torch.empty(nbytes // 2, dtype=torch.float16, device=w.device)
+    if packed.numel() * packed.element_size() != nbytes:
+        raise ValueError("packed has the wrong size")
+    _check(lib().merit_conv2d_pack_weights(plan.handle, _dev_ptr(w, torch.float16, "w"),
+                                           _dev_ptr(packed, torch.float16, "packed"), _stream(stream)),
+           "merit_conv2d_pack_weights")
+    return packed
+
+
+def merit_conv2d_packed(plan: Plan, x, packed, y=None, stream=None):
+    import torch
+    out_shape, a_shape, _ = plan.shapes()
+    if y is None:
+        y = torch.empty(out_shape, dtype=torch.float16, device=x.device)
+    if tuple(y.shape) != out_shape or tuple(x.shape) != a_shape:
+        raise ValueError("x / y do not match the plan")
+    if packed.numel() * packed.element_size() != merit_plan_packed_weights_bytes(plan):
+        raise ValueError("packed has the wrong size")
+    _check(lib().merit_conv2d_packed(plan.handle, _dev_ptr(x, torch.float16, "x"),
+                                     _dev_ptr(packed, torch.float16, "packed"), _dev_ptr(y, torch.float16, "y"),
+                                     _stream(stream)), "merit_conv2d_packed")
     return y
 
 
@@ -465,6 +505,18 @@ def bind_conv2d(plan: Plan, x, w, y, stream=None) -> BoundCall:
     args = (plan.handle, _dev_ptr(x, torch.float16, "x"), _dev_ptr(w, torch.float16, "w"),
             _dev_ptr(y, torch.float16, "y"), _stream(stream))
     return BoundCall(lib().merit_conv2d, "merit_conv2d", args, (plan, x, w, y))
+
+
+def bind_conv2d_packed(plan: Plan, x, packed, y, stream=None) -> BoundCall:
+    import torch
+    out_shape, a_shape, _ = plan.shapes()
+    if tuple(y.shape) != out_shape or tuple(x.shape) != a_shape:
+        raise ValueError("tensors do not match the plan")
+    if packed.numel() * packed.element_size() != merit_plan_packed_weights_bytes(plan):
+        raise ValueError("packed has the wrong size")
+    args = (plan.handle, _dev_ptr(x, torch.float16, "x"), _dev_ptr(packed, torch.float16, "packed"),
+            _dev_ptr(y, torch.float16, "y"), _stream(stream))
+    return BoundCall(lib().merit_conv2d_packed, "merit_conv2d_packed", args, (plan, x, packed, y))
 
 
 def bind_conv2d_residual(plan: Plan, x, w, r, y, stream=None) -> BoundCall:

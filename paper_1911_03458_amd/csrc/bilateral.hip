@@ -1,9 +1,7 @@
-// Bilateral filter for gfx950: the strategy class and call of Section VI-A (Listings 2, 3) on a
-// k x k window centred with offset -k/2 on both window indices,
-//     PreLoop : wsum = wxsum = 0; center = x[n,p1,p2]
-//     Loop    : v = x[n, p1 + a1 - k/2, p2 + a2 - k/2];  d = center - v
-//               w = exp(d*d*norm) * gy[a1] * gx[a2];  wsum += w;  wxsum += w*v
-//     PostLoop: y[n,p1,p2] = wxsum / wsum
+// Bilateral filter for gfx950 (Section VI-A, Listings 2 and 3): every output pixel is the
+// normalised weighted mean of its k x k window (window offset -k/2 on both window indices); a
+// neighbour's weight is exp(norm * (its difference to the centre pixel)^2) times one entry
+// of each of two spatial lookup tables of length k,
 // with coordinates clamped to the image.  k*k exponentials per pixel against 8 bytes of memory
 // traffic: bound by the vector ALU (v_exp_f32 runs at a quarter of the plain rate).
 //

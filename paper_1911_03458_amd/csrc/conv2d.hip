@@ -26,6 +26,7 @@
 // along the contiguous pixel axis of NCHW.
 #include "merit_internal.h"
 
+#include <atomic>
 #include <type_traits>
 
 namespace merit {
@@ -60,6 +61,8 @@ __device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi)
 // Touch every 64-byte line of the kernel's argument block (ConvParams + four pointers = five
 // lines, and the line after them that holds the grid extents) with the first scalar loads, so that the later ones, issued where their values are needed, hit
 // the scalar cache instead of each paying a trip to memory.
+static_assert(sizeof(ConvParams) + 4 * sizeof(void *) > 5 * 64 && sizeof(ConvParams) + 4 * sizeof(void *) <= 6 * 64,
+              "touch_kernarg_lines covers six 64-byte lines: the argument block must end in the sixth");
 __device__ __forceinline__ void touch_kernarg_lines()
 {
     typedef const uint32_t __attribute__((address_space(4))) *kernarg_ptr;
@@ -1767,12 +1770,12 @@ static hipError_t launch(K kernel, const ConvParams &p, const void *x, const voi
 {
     // raise this kernel instance's dynamic-LDS limit to the 160 KB a gfx950 workgroup may
     // use; done once per instance (the static lives in this template instantiation)
-    static bool raised = false;
-    if (!raised) {
+    static std::atomic<int> raised{0};
+    if (!raised.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
-        raised = true;
+        raised.store(1, std::memory_order_release);
     }
     hipLaunchKernelGGL(kernel, dim3(gx, (uint32_t)p.co_groups), dim3(nthreads), lds_bytes, s, p,
                        reinterpret_cast<const uint16_t *>(x), reinterpret_cast<const uint16_t *>(w),
@@ -1786,24 +1789,27 @@ size_t conv_lds_bytes(const ConvParams &p)
 }
 
 // number of compute units of the current device (cached; 256 on MI355X)
-static int device_cu_count()
+int conv_device_cu_count()
 {
-    static int cus = 0;
-    if (cus == 0) {
+    static std::atomic<int> cus{0};
+    int c = cus.load(std::memory_order_relaxed);
+    if (c == 0) {
         int dev = 0, v = 0;
         if (hipGetDevice(&dev) == hipSuccess &&
             hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-            cus = v;
+            c = v;
         else
-            cus = 256;
+            c = 256;
+        cus.store(c, std::memory_order_relaxed);
     }
-    return cus;
+    return c;
 }
 
 hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, const void *r, void *y, hipStream_t s)
 {
     const int64_t ntiles = (int64_t)p.N * p.tiles_per_image;
     if (ntiles == 0) return hipSuccess;
+    if (p.variant == CONV_CHWS) return launch_conv2d_chws(p, x, w, y, s, false);
     if (p.variant == CONV_DIRECT) {                // one workgroup per 256 pixels x 8 channels
         hipLaunchKernelGGL(merit_conv2d_direct, dim3((uint32_t)ntiles), dim3(256), 0, s, p,
                            reinterpret_cast<const uint16_t *>(x), reinterpret_cast<const uint16_t *>(w),
@@ -1811,7 +1817,7 @@ hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, cons
         return hipGetLastError();
     }
     // persistent grid: as many workgroups as fit on the chip at once, at most one per tile
-    int64_t slots = (int64_t)device_cu_count() * p.wg_per_cu / p.co_groups;
+    int64_t slots = (int64_t)conv_device_cu_count() * p.wg_per_cu / p.co_groups;
     if (slots < 1) slots = 1;
     const uint32_t gx = (uint32_t)(ntiles < slots ? ntiles : slots);
     const size_t lds = conv_lds_bytes(p);
@@ -1899,6 +1905,7 @@ const char *conv_kernel_name(const ConvParams &p)
     if (p.variant == CONV_PLANAR_SMALLC && p.ws && p.pool) return "merit_conv2d_planar_ws_pool";
     if (p.variant == CONV_PLANAR_SMALLC) return p.ws ? "merit_conv2d_planar_ws" : "merit_conv2d_planar";
     if (p.variant == CONV_DIRECT) return "merit_conv2d_direct";
+    if (p.variant == CONV_CHWS) return "merit_conv2d_chws";
     return p.nchunks > 1 ? "merit_conv2d_chpass" : "merit_conv2d_chblock";
 }
 

@@ -1,0 +1,595 @@
+// 2-D convolution for gfx950, many input channels: wave-specialised, double-buffered passes.
+//
+// k = (n, co, oy, ox | ci, ky, kx) (Section III-C, Eq. 6), reduced with the dot product
+// (Section III-B, Eq. 3) on v_mfma_f32_32x32x16_f16, K order (ci/8, ky, kx | ci%8) as in the
+// channel-block kernels of conv2d.hip.  What differs is who does what and how large a
+// wavefront's register tile is:
+//
+//   * A workgroup is 8 wavefronts.  Wavefronts 0-3 only multiply: each owns PXB x CHB blocks of
+//     32 pixels x 32 output channels (128 x 64 by default), so a K step reads PXB + CHB
+//     fragments from LDS for PXB * CHB MFMAs (6 reads per 8 MFMAs instead of 3 per 2), and the
+//     reads of step s+1 are issued before the MFMAs of step s.
+//   * Wavefronts 4-7 only move data.  The input channels go through LDS in passes of 16 (two
+//     groups of 8, one per half of a wavefront); pass q+1 is transposed into the other LDS
+//     buffer while pass q is multiplied, and the global loads of passes q+2 and q+3 are in
+//     flight meanwhile (two register sets).  One barrier per pass.
+//   * The covering sub-tensor of a tile (Section IV-A, Eq. 9) is TM consecutive output pixels
+//     of one image (whole rows: only a vertical halo) x 16 channels per pass.
+//
+// Weights are either the caller's [Cout][Cin][kh][kw] tensor, transposed in registers by the
+// moving wavefronts on every pass, or a buffer that merit_conv2d_pack_weights wrote once in
+// exactly the order the passes want them (then a pass's weights are one contiguous copy).
+#include "merit_internal.h"
+
+#include <atomic>
+
+#ifndef MERIT_CHWS_EXPERIMENT
+#define MERIT_CHWS_EXPERIMENT 0     // 2: the multiplying wavefronts skip the K loop (wrong results), 9: in-kernel phase timing printed by one workgroup
+#endif
+#if MERIT_CHWS_EXPERIMENT == 9
+#define TS() __builtin_amdgcn_s_memrealtime()
+#define TIMED(acc, stmt) do { const unsigned long long t0_ = TS(); stmt; acc += TS() - t0_; } while (0)
+#else
+#define TIMED(acc, stmt) do { stmt; } while (0)
+#endif
+
+namespace merit {
+
+namespace {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef uint32_t uint32x4 __attribute__((ext_vector_type(4)));
+
+union Frag {
+    uint4 u;
+    half8 h;
+};
+
+struct Geom {
+    int n, m0, oyA, yA, RH, cg;
+};
+
+__device__ __forceinline__ Geom tile_geom(const ConvParams &p, int item, int ohw)
+{
+    Geom g;
+    const int tile = (int)fdiv((uint32_t)item, p.div_cog);
+    g.cg = item - tile * p.co_groups;
+    g.n = (int)fdiv((uint32_t)tile, p.div_tiles);
+    g.m0 = (tile - g.n * p.tiles_per_image) * p.TM;
+    g.oyA = (int)fdiv((uint32_t)g.m0, p.div_ow);
+    const int mlast = min(g.m0 + p.TM, ohw) - 1;
+    const int oyB = (int)fdiv((uint32_t)mlast, p.div_ow);
+    g.yA = g.oyA * p.sh - p.ph;
+    g.RH = (oyB - g.oyA) * p.sh + (p.kh - 1) * p.dh + 1;
+    return g;
+}
+
+constexpr int XS_MAX = 4;      // input units of 8 channels x 1 pixel a moving thread holds per pass
+constexpr uint32_t OOB = 0x80000000u;   // a buffer offset past the end of every tensor: loads return zeros
+
+}  // namespace
+
+// PXB x CHB: 32x32 blocks per multiplying wavefront; WM x WN = 4 multiplying wavefronts.
+// T: taps of the window (9 = 3x3, 1 = 1x1).  XU = 1, 2: the input rows are staged in units of 8
+// channels x 8 pixels (W % 8 == 0), XU of them per moving thread and pass; XU = 0: in units of
+// 8 channels x 1 pixel, up to XS_MAX per thread.
+template <int PXB, int CHB, int WM, int WN, int T, int XU, bool PACKED>
+__global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvParams p, const uint16_t *__restrict__ x,
+                                                            const uint16_t *__restrict__ w,
+                                                            uint16_t *__restrict__ y)
+{
+    constexpr int NMW = WM * WN;                         // multiplying wavefronts; four more move data
+    static_assert(NMW == 4 || NMW == 8, "one or two multiplying wavefronts per SIMD");
+    constexpr int NT = (NMW + 4) * 64;                   // threads per workgroup
+    constexpr int TM = WM * PXB * 32, NCB = WN * CHB, TN = NCB * 32;
+    constexpr int WITEMS = T * NCB * 64;                 // 16-byte weight fragments per pass
+    constexpr int WU = (TN * 2 + 255) / 256;             // weight units (8 channels x T taps of one output channel) per moving thread
+    constexpr int OP = TM / 2 + 2;                       // output staging: dwords per channel
+    constexpr bool XV = XU > 0;
+
+    extern __shared__ __align__(16) uint8_t smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6, h = lane >> 5, c32 = lane & 31;
+    const bool mover = wave >= NMW;
+    const int mt = tid - NMW * 64;                       // index among the moving threads
+    const int ohw = p.OH * p.OW;
+    const int npass = p.nchunks;
+
+    auto wbuf = [&](int b) { return reinterpret_cast<uint4 *>(smem + b * p.lds_buf_bytes); };
+    auto xbuf = [&](int b) { return reinterpret_cast<uint4 *>(smem + b * p.lds_buf_bytes + p.lds_w_bytes); };
+    uint32_t *outl = reinterpret_cast<uint32_t *>(smem);
+
+    // ---- work list: item = (tile, channel block), a contiguous band of the list per XCD ------
+    const int nitems = p.N * p.tiles_per_image * p.co_groups;
+    const int stride = (int)gridDim.x;
+    int item = (int)xcd_band_item(blockIdx.x, stride >> 3, stride & 7);
+    if (item >= nitems) return;                            // (the launcher never makes the grid larger than the list)
+
+    // results: LDS [channel][pixel] -> 16-byte runs along the pixel axis, by all threads
+    auto store_out = [&](const Geom &g) __attribute__((always_inline)) {
+        const bool vec_ok = (ohw & 7) == 0;
+        constexpr int UNITS = TN * (TM / 8);
+#pragma unroll 4
+        for (int u = tid; u < UNITS; u += NT) {
+            const int c = u / (TM / 8);
+            const int px8 = u - c * (TM / 8);
+            const int m = g.m0 + px8 * 8;
+            const int co = g.cg * TN + c;
+            if (m >= ohw || co >= p.Cout) continue;
+            const uint2 *src = reinterpret_cast<const uint2 *>(outl + c * OP + px8 * 4);
+            const uint2 lo = src[0], hi = src[1];
+            uint16_t *y0 = y + ((size_t)g.n * p.Cout + co) * ohw + m;
+            if (vec_ok) {
+                uint32x4 v;
+                v.x = lo.x; v.y = lo.y; v.z = hi.x; v.w = hi.y;
+                __builtin_nontemporal_store(v, reinterpret_cast<uint32x4 *>(y0));
+            } else {
+                const uint32_t e[4] = {lo.x, lo.y, hi.x, hi.y};
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    if (m + k >= ohw) break;
+                    y0[k] = (uint16_t)(e[k >> 1] >> (16 * (k & 1)));
+                }
+            }
+        }
+    };
+
+    // Both kinds of wavefront run the same sequence of barriers (npass + 3 per work item):
+    //   P      pass 0 is in buffer 0
+    //   B_ck   pass ck has been multiplied, pass ck+1 is in the other buffer
+    //   E1     the accumulators are in the output staging area (which overlays the buffers)
+    //   E2     the staging area has been stored: the buffers are free again
+    if (mover) {
+        // ---- the moving wavefronts ----
+        // Global memory is read through buffer descriptors: a unit that lies outside the tensors
+        // (rows above or below the image, padding channels of the last pass, channels past Cout)
+        // gets the offset OOB and comes back as zeros: no branch and no select on the data.
+        // Per-thread offsets and LDS addresses are worked out once per work item; a pass adds
+        // scalar offsets only.
+        const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t *>(x), 0, (int)((size_t)p.N * p.Cin * p.H * p.W * 2), 0x00020000);
+        const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t *>(w), 0,
+            (int)(PACKED ? (size_t)p.co_groups * npass * WITEMS * 16 : (size_t)p.Cout * p.Cin * T * 2), 0x00020000);
+        const uint32_t chbytes = (uint32_t)(p.H * p.W * 2);          // one channel of one image
+        const int mwave = wave - NMW;
+
+        constexpr int NXU = XV ? XU : XS_MAX;
+        uint32_t x_voff[NXU];               // byte offset of the unit inside (image, first channel of the pass)
+        int x_lds[NXU][XV ? 8 : 1];         // byte address of each of its pixels inside a pass buffer's input region
+        int x_hh[NXU];                      // its channel group within the pass
+        uint32_t xv[XV ? XU : 1][8][4];     // the unit on its way: 8 channels x 8 pixels
+        uint16_t xs[XV ? 1 : XS_MAX][8];    // ... 8 channels x 1 pixel
+        uint32_t w_voff[WU];
+        int w_lds[WU], w_hh[WU];
+        uint32_t wr[PACKED ? 1 : WU][PACKED ? 1 : 4 * T];
+
+        auto setup = [&](const Geom &g) __attribute__((always_inline)) {
+            if constexpr (XV) {
+                const int W8 = p.W >> 3;
+                const int nu = 2 * p.RHa * W8;
+#pragma unroll
+                for (int k = 0; k < XU; ++k) {
+                    // consecutive threads take consecutive staged rows (q = group * RHa + row) of one
+                    // 8-pixel column chunk: their LDS writes are q * pitch items apart, and the pitch
+                    // is odd, so 16 of them fall into 16 different bank groups
+                    const int u = mt + 256 * k;
+                    const int uc = min(u, nu - 1);
+                    const int x8 = (int)fdiv((uint32_t)uc, p.div_r2);
+                    const int q = uc - x8 * 2 * p.RHa;
+                    const int hh = (int)fdiv((uint32_t)q, p.div_rha);
+                    const int r = q - hh * p.RHa;
+                    const int gy = g.yA + r;
+                    const bool ok = u < nu && r < g.RH && gy >= 0 && gy < p.H;
+                    x_hh[k] = u < nu ? hh : 2;                               // 2: no such unit, never written
+                    x_voff[k] = ok ? (uint32_t)(((hh * 8 * p.H + gy) * p.W + 8 * x8) * 2) : OOB;
+#pragma unroll
+                    for (int px = 0; px < 8; ++px)
+                        x_lds[k][px] = (q * p.pitch + p.padl + 8 * x8 + px) * 16;
+                }
+            } else {
+                const int nu = 2 * p.RHa * p.W;
+#pragma unroll
+                for (int k = 0; k < XS_MAX; ++k) {
+                    const int u = mt + 256 * k;
+                    const int uc = min(u, nu - 1);
+                    const int q = (int)fdiv((uint32_t)uc, p.div_w);
+                    const int xg = uc - q * p.W;
+                    const int hh = (int)fdiv((uint32_t)q, p.div_rha);
+                    const int r = q - hh * p.RHa;
+                    const int gy = g.yA + r;
+                    const bool ok = u < nu && r < g.RH && gy >= 0 && gy < p.H;
+                    x_hh[k] = u < nu ? hh : 2;
+                    x_voff[k] = ok ? (uint32_t)(((hh * 8 * p.H + gy) * p.W + xg) * 2) : OOB;
+                    x_lds[k][0] = (q * p.pitch + p.padl + xg) * 16;
+                }
+            }
+            if constexpr (!PACKED) {
+#pragma unroll
+                for (int k = 0; k < WU; ++k) {
+                    const int u = mt + 256 * k;
+                    const int col = u >> 1, hh = u & 1;
+                    const int co = g.cg * TN + col;
+                    const bool ok = u < TN * 2 && co < p.Cout;
+                    w_hh[k] = u < TN * 2 ? hh : 2;
+                    w_voff[k] = ok ? (uint32_t)(((co * p.Cin + hh * 8) * T) * 2) : OOB;
+                    w_lds[k] = (((col >> 5) * 2 + hh) * 32 + ((col & 31) ^ (hh * 8))) * 16;
+                }
+            }
+        };
+
+        // request the input rows (and, unless packed, the weights) of pass ck into the registers
+        auto request = [&](const Geom &g, int ck) __attribute__((always_inline)) {
+            const bool half = (ck * 2 + 1) * 8 + 8 > p.Cin;      // the pass's second channel group is padding
+            const uint32_t xbase = ((uint32_t)g.n * (uint32_t)p.Cin + (uint32_t)ck * 16u) * chbytes;
+#pragma unroll
+            for (int k = 0; k < NXU; ++k) {
+                if (!XV && k >= p.xu) break;
+                const uint32_t voff = (half && x_hh[k] == 1) ? OOB : x_voff[k];
+#pragma unroll
+                for (int c = 0; c < 8; ++c) {
+                    if constexpr (XV) {
+                        const uint32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rx, voff, xbase + c * chbytes, 0);
+                        xv[k][c][0] = v.x; xv[k][c][1] = v.y; xv[k][c][2] = v.z; xv[k][c][3] = v.w;
+                    } else {
+                        xs[k][c] = __builtin_amdgcn_raw_buffer_load_b16(rx, voff, xbase + c * chbytes, 0);
+                    }
+                }
+            }
+            if constexpr (!PACKED) {
+                const uint32_t wbase = (uint32_t)ck * (uint32_t)(16 * T * 2);
+#pragma unroll
+                for (int k = 0; k < WU; ++k) {
+                    const uint32_t voff = (half && w_hh[k] == 1) ? OOB : w_voff[k];
+#pragma unroll
+                    for (int i = 0; i < T; ++i) {
+                        const uint32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rw, voff + 16 * i, wbase, 0);
+                        wr[k][4 * i + 0] = v.x; wr[k][4 * i + 1] = v.y; wr[k][4 * i + 2] = v.z; wr[k][4 * i + 3] = v.w;
+                    }
+                }
+            }
+        };
+
+        // transpose the registers into pass buffer b
+        auto commit = [&](int b) __attribute__((always_inline)) {
+            uint8_t *xl = smem + b * p.lds_buf_bytes + p.lds_w_bytes;
+#pragma unroll
+            for (int k = 0; k < NXU; ++k) {
+                if (!XV && k >= p.xu) break;
+                if (x_hh[k] < 2) {
+                    if constexpr (XV) {
+#pragma unroll
+                        for (int px = 0; px < 8; ++px) {
+                            const uint32_t sel = (px & 1) ? 0x07060302u : 0x05040100u;
+                            uint32x4 d;
+                            d.x = __builtin_amdgcn_perm(xv[k][1][px >> 1], xv[k][0][px >> 1], sel);
+                            d.y = __builtin_amdgcn_perm(xv[k][3][px >> 1], xv[k][2][px >> 1], sel);
+                            d.z = __builtin_amdgcn_perm(xv[k][5][px >> 1], xv[k][4][px >> 1], sel);
+                            d.w = __builtin_amdgcn_perm(xv[k][7][px >> 1], xv[k][6][px >> 1], sel);
+                            *reinterpret_cast<uint32x4 *>(xl + x_lds[k][px]) = d;
+                        }
+                    } else {
+                        uint32x4 d;
+                        d.x = (uint32_t)xs[k][0] | ((uint32_t)xs[k][1] << 16);
+                        d.y = (uint32_t)xs[k][2] | ((uint32_t)xs[k][3] << 16);
+                        d.z = (uint32_t)xs[k][4] | ((uint32_t)xs[k][5] << 16);
+                        d.w = (uint32_t)xs[k][6] | ((uint32_t)xs[k][7] << 16);
+                        *reinterpret_cast<uint32x4 *>(xl + x_lds[k][0]) = d;
+                    }
+                }
+            }
+            if constexpr (!PACKED) {
+                uint8_t *wl = smem + b * p.lds_buf_bytes;
+#pragma unroll
+                for (int k = 0; k < WU; ++k) {
+                    if (w_hh[k] < 2) {
+#pragma unroll
+                        for (int t = 0; t < T; ++t) {
+                            uint32_t d[4];
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) {
+                                // halves (channel 2q, tap t) and (channel 2q+1, tap t) of the unit's 8 x T block
+                                const int e0 = (2 * q) * T + t, e1 = (2 * q + 1) * T + t;
+                                const uint32_t sel =
+                                    ((e0 & 1) ? 0x00000302u : 0x00000100u) | ((e1 & 1) ? 0x07060000u : 0x05040000u);
+                                d[q] = __builtin_amdgcn_perm(wr[k][e1 >> 1], wr[k][e0 >> 1], sel);
+                            }
+                            uint32x4 dv;
+                            dv.x = d[0]; dv.y = d[1]; dv.z = d[2]; dv.w = d[3];
+                            *reinterpret_cast<uint32x4 *>(wl + w_lds[k] + t * NCB * 64 * 16) = dv;
+                        }
+                    }
+                }
+            }
+        };
+
+        // packed weights of pass ck of channel block cg: global memory -> pass buffer b directly
+        // (no registers; each wavefront instruction moves 64 consecutive fragments)
+        auto weights_direct = [&](int cg, int ck, int b) __attribute__((always_inline)) {
+            if constexpr (PACKED) {
+                const uint32_t soff = (uint32_t)((cg * npass + ck) * WITEMS) * 16u;
+                constexpr int ROUNDS = (WITEMS / 64 + 3) / 4;
+#pragma unroll
+                for (int k = 0; k < ROUNDS; ++k) {
+                    const int i = mwave + 4 * k;                           // 64-fragment slice of the pass
+                    if (i * 64 < WITEMS)
+                        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                            rw, (__attribute__((address_space(3))) void *)(smem + b * p.lds_buf_bytes + i * 1024), 16,
+                            (i * 64 + lane) * 16, soff, 0, 0);
+                }
+            }
+        };
+        // ... and the wait for them: everything this wavefront has requested has arrived
+        auto weights_landed = [&]() __attribute__((always_inline)) {
+            if constexpr (PACKED) __builtin_amdgcn_s_waitcnt(0 | (0x7 << 4) | (0xF << 8));    // vmcnt(0)
+        };
+
+        // the padding columns of the staged rows, both buffers (the output staging overwrites them)
+        auto zero_pads = [&]() __attribute__((always_inline)) {
+            const int npad = p.pitch - p.W;
+            const int per = 2 * p.RHa * npad;
+            for (int u = mt; u < 2 * per; u += 256) {
+                const int b = u >= per ? 1 : 0;
+                const int v = u - b * per;
+                const int rowi = v / npad;
+                const int c = v - rowi * npad;
+                const int col = c < p.padl ? c : p.W + c;
+                xbuf(b)[rowi * p.pitch + col] = make_uint4(0, 0, 0, 0);
+            }
+        };
+
+        // Per period (the multiplying wavefronts are on pass ck of the item): write pass ck+1, whose
+        // registers were requested a period ago, to the other buffer; start its packed weights;
+        // request pass ck+2 (or pass 0 / 1 of the next item).  The registers are free again only
+        // after the commit, so one pass is in flight at a time, for a whole period.
+#if MERIT_CHWS_EXPERIMENT == 9
+        unsigned long long tc = 0, tr = 0, tb = 0, tw = 0;
+#endif
+        Geom g = tile_geom(p, item, ohw);
+        setup(g);
+        request(g, 0);
+        for (; item < nitems; item += stride) {
+            const bool more = item + stride < nitems;
+            const Geom gn = more ? tile_geom(p, item + stride, ohw) : g;
+            commit(0);
+            weights_direct(g.cg, 0, 0);
+            zero_pads();
+            if (npass > 1) request(g, 1);
+            weights_landed();                                  // (waits for the request too: once per item)
+            __syncthreads();                                   // P
+            for (int ck = 0; ck < npass; ++ck) {
+                if (ck + 1 < npass) {
+                    TIMED(tc, commit((ck + 1) & 1));
+                    weights_direct(g.cg, ck + 1, (ck + 1) & 1);
+                    if constexpr (XV) {
+                        // the packed weights have the rest of the period to land: wait until only
+                        // the request that follows them is still in flight
+                        if (ck + 2 < npass) {
+                            TIMED(tr, request(g, ck + 2));
+                            if constexpr (PACKED) __builtin_amdgcn_s_waitcnt((8 * XU) | (0x7 << 4) | (0xF << 8));
+                        } else {
+                            TIMED(tw, weights_landed());
+                        }
+                    } else {
+                        TIMED(tw, weights_landed());
+                        if (ck + 2 < npass) TIMED(tr, request(g, ck + 2));
+                    }
+                }
+                TIMED(tb, __syncthreads());                    // B_ck
+            }
+            // the next item's first pass flies under the result stores
+            if (more) { setup(gn); request(gn, 0); }
+            __syncthreads();                                   // E1
+            store_out(g);
+            __syncthreads();                                   // E2
+            g = gn;
+        }
+#if MERIT_CHWS_EXPERIMENT == 9
+        if (blockIdx.x == 7 && tid == 256)
+            printf("mover: commit %llu request %llu wait-weights %llu barrier %llu (x10 ns) npass %d\n", tc, tr, tw, tb, npass);
+#endif
+        return;
+    }
+
+    // ---- the multiplying wavefronts ----
+#if MERIT_CHWS_EXPERIMENT == 9
+    unsigned long long tk = 0, tb = 0, t0, tstart = TS();
+#endif
+    const int wm = wave % WM, wn = wave / WM;
+    for (; item < nitems; item += stride) {
+        const Geom g = tile_geom(p, item, ohw);
+        int xc[PXB][T == 9 ? 3 : 1];
+#pragma unroll
+        for (int pb = 0; pb < PXB; ++pb) {
+            const int m = g.m0 + (wm * PXB + pb) * 32 + c32;
+            const int mm = min(m, ohw - 1);
+            const int oy = (int)fdiv((uint32_t)mm, p.div_ow);
+            const int ox = mm - oy * p.OW;
+            const int pbase = (h * p.RHa + (oy - g.oyA) * p.sh) * p.pitch;
+            const int pcol = (p.padl - p.pw) + ox * p.sw;
+#pragma unroll
+            for (int kx = 0; kx < (T == 9 ? 3 : 1); ++kx) xc[pb][kx] = pbase + pcol + kx * p.dw;
+        }
+        floatx16 acc[CHB][PXB];
+#pragma unroll
+        for (int cb = 0; cb < CHB; ++cb)
+#pragma unroll
+            for (int pb = 0; pb < PXB; ++pb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[cb][pb][r] = 0.0f;
+        __syncthreads();                                       // P
+
+        for (int ck = 0; ck < npass; ++ck) {
+            const uint4 *wl = wbuf(ck & 1) + (wn * CHB * 2 + h) * 32 + (c32 ^ (h * 8));
+            const uint4 *xl = xbuf(ck & 1);
+            const int rowstep = p.dh * p.pitch;
+            Frag a[2][CHB], b[2][PXB];
+            auto load = [&](int s, int slot) __attribute__((always_inline)) {
+                const int ky = T == 9 ? s / 3 : 0, kx = T == 9 ? s % 3 : 0;
+#pragma unroll
+                for (int cb = 0; cb < CHB; ++cb) a[slot][cb].u = wl[(s * NCB + cb) * 64];
+#pragma unroll
+                for (int pb = 0; pb < PXB; ++pb) b[slot][pb].u = xl[xc[pb][kx] + ky * rowstep];
+            };
+            // the reads of step s+1 are issued before the MFMAs of step s and stay there (left to
+            // itself the scheduler sinks them to their first use, and the matrix core idles for
+            // an LDS round trip per step)
+#if MERIT_CHWS_EXPERIMENT >= 2 && MERIT_CHWS_EXPERIMENT < 9
+            if (p.N > 0) { __syncthreads(); continue; }
+#endif
+#if MERIT_CHWS_EXPERIMENT == 9
+            t0 = TS();
+#endif
+            load(0, 0);
+#pragma unroll
+            for (int s = 0; s < T; ++s) {
+                if (s + 1 < T) load(s + 1, (s + 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int cb = 0; cb < CHB; ++cb)
+#pragma unroll
+                    for (int pb = 0; pb < PXB; ++pb)
+                        acc[cb][pb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(b[s & 1][pb].h, a[s & 1][cb].h,
+                                                                             acc[cb][pb], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#if MERIT_CHWS_EXPERIMENT == 9
+            asm volatile("s_nop 0" :: "v"(acc[0][0][0]), "v"(acc[CHB - 1][PXB - 1][15]));
+            tk += TS() - t0;
+            t0 = TS();
+#endif
+            __syncthreads();                                   // B_ck
+#if MERIT_CHWS_EXPERIMENT == 9
+            tb += TS() - t0;
+#endif
+        }
+
+        // accumulators -> LDS [channel][pixel].  Accumulator register r of lane l is output
+        // channel l%32 of its block, pixel 8*(r/4) + 4*(l/32) + r%4: four consecutive registers
+        // are four consecutive pixels.  OP = TM/2 + 2 dwords per channel spreads the 32 channels
+        // of a write over all banks.
+        {
+            const half2v z = {(_Float16)0.0f, (_Float16)0.0f};
+#pragma unroll
+            for (int cb = 0; cb < CHB; ++cb)
+#pragma unroll
+                for (int pb = 0; pb < PXB; ++pb)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        half2v v0, v1;
+                        v0.x = (_Float16)acc[cb][pb][4 * q];     v0.y = (_Float16)acc[cb][pb][4 * q + 1];
+                        v1.x = (_Float16)acc[cb][pb][4 * q + 2]; v1.y = (_Float16)acc[cb][pb][4 * q + 3];
+                        if (p.relu) {            // clipping the rounded value = rounding the clipped value
+                            v0 = __builtin_elementwise_max(v0, z);
+                            v1 = __builtin_elementwise_max(v1, z);
+                        }
+                        uint2 v;
+                        v.x = __builtin_bit_cast(uint32_t, v0);
+                        v.y = __builtin_bit_cast(uint32_t, v1);
+                        const int ch = (wn * CHB + cb) * 32 + c32;
+                        *reinterpret_cast<uint2 *>(outl + ch * OP + (wm * PXB + pb) * 16 + 4 * q + 2 * h) = v;
+                    }
+        }
+        __syncthreads();                                       // E1
+        store_out(g);
+        __syncthreads();                                       // E2
+    }
+#if MERIT_CHWS_EXPERIMENT == 9
+    if (blockIdx.x == 7 && tid == 0)
+        printf("mfma: kloop %llu barrier %llu total %llu (x10 ns)\n", tk, tb, TS() - tstart);
+#endif
+}
+
+// Rewrites w[Cout][Cin][kh][kw] into the order the passes of merit_conv2d_chws read it: for every
+// channel block and pass the T * NCB * 64 fragments of 8 input channels in their LDS places.
+// One thread per 16-byte fragment.
+__global__ __launch_bounds__(256) void merit_conv2d_pack_w(ConvParams p, int T, int NCB, const uint16_t *__restrict__ w,
+                                                          uint4 *__restrict__ out, long long total)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int witems = T * NCB * 64;
+    const long long blk = i / witems;                      // (channel block, pass)
+    int r = (int)(i - blk * witems);
+    const int cg = (int)(blk / p.nchunks), ck = (int)(blk - (long long)cg * p.nchunks);
+    const int t = r / (NCB * 64);
+    r -= t * NCB * 64;
+    const int cb = r >> 6, hh = (r >> 5) & 1, slot = r & 31;
+    const int cc = slot ^ (hh * 8);
+    const int co = (cg * NCB + cb) * 32 + cc;
+    const int ci0 = (ck * 2 + hh) * 8;
+    uint32_t d[4] = {0, 0, 0, 0};
+    if (co < p.Cout) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+            if (ci0 + c < p.Cin)
+                d[c >> 1] |= (uint32_t)w[((size_t)co * p.Cin + ci0 + c) * T + t] << (16 * (c & 1));
+    }
+    out[i] = make_uint4(d[0], d[1], d[2], d[3]);
+}
+
+namespace {
+
+template <typename K>
+hipError_t launch_one(K kernel, const ConvParams &p, const void *x, const void *w, void *y, hipStream_t s, uint32_t grid)
+{
+    // raise this instance's dynamic-LDS limit to the 160 KB a gfx950 workgroup may use, once
+    static std::atomic<int> raised{0};
+    if (!raised.load(std::memory_order_acquire)) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        raised.store(1, std::memory_order_release);
+    }
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3((unsigned)(p.NW * 64)), (size_t)p.lds_total, s, p, reinterpret_cast<const uint16_t *>(x),
+                       reinterpret_cast<const uint16_t *>(w), reinterpret_cast<uint16_t *>(y));
+    return hipGetLastError();
+}
+
+template <int PXB, int CHB, int WM, int WN>
+hipError_t launch_tile(const ConvParams &p, const void *x, const void *w, void *y, hipStream_t s, uint32_t grid,
+                       bool packed)
+{
+    const int xu = (p.W & 7) == 0 ? p.xu : 0;                // 8-pixel units per moving thread, 0: one-pixel units
+    const int T = p.kh * p.kw;
+#define MERIT_CHWS(Tv, XUv)                                                                             \
+    do {                                                                                                \
+        if (packed) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, Tv, XUv, true>, p, x, w, y, s, grid);  \
+        return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, Tv, XUv, false>, p, x, w, y, s, grid);    \
+    } while (0)
+    if (T == 9 && xu == 1) MERIT_CHWS(9, 1);
+    if (T == 9 && xu == 2) MERIT_CHWS(9, 2);
+    if (T == 9 && xu == 0) MERIT_CHWS(9, 0);
+    if (T == 1 && xu == 1) MERIT_CHWS(1, 1);
+    if (T == 1 && xu == 2) MERIT_CHWS(1, 2);
+    if (T == 1 && xu == 0) MERIT_CHWS(1, 0);
+#undef MERIT_CHWS
+    return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+hipError_t launch_conv2d_chws(const ConvParams &p, const void *x, const void *w, void *y, hipStream_t s, bool packed)
+{
+    const int64_t nitems = (int64_t)p.N * p.tiles_per_image * p.co_groups;
+    if (nitems == 0) return hipSuccess;
+    const int64_t slots = conv_device_cu_count();            // one 512-thread workgroup per compute unit
+    const uint32_t grid = (uint32_t)(nitems < slots ? nitems : slots);
+    if (p.CB == 4 && p.NW == 12) return launch_tile<2, 2, 4, 2>(p, x, w, y, s, grid, packed);   // 256 x 128, 8 x (64 x 64)
+    if (p.CB == 4) return launch_tile<4, 2, 2, 2>(p, x, w, y, s, grid, packed);     // 256 pixels x 128 channels, 4 x (128 x 64)
+    return launch_tile<2, 2, 4, 1>(p, x, w, y, s, grid, packed);                    // 256 pixels x 64 channels, 4 x (64 x 64)
+}
+
+hipError_t launch_conv2d_pack_weights(const ConvParams &p, const void *w, void *packed, hipStream_t s)
+{
+    const int T = p.kh * p.kw;
+    const long long total = (long long)p.co_groups * p.nchunks * T * p.CB * 64;
+    if (total == 0) return hipSuccess;
+    hipLaunchKernelGGL(merit_conv2d_pack_w, dim3((uint32_t)((total + 255) / 256)), dim3(256), 0, s, p, T, p.CB,
+                       reinterpret_cast<const uint16_t *>(w), reinterpret_cast<uint4 *>(packed), total);
+    return hipGetLastError();
+}
+
+}  // namespace merit

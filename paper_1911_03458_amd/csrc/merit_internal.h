@@ -82,7 +82,7 @@ struct SadParams {
 };
 
 // ---- convolution -----------------------------------------------------------
-enum ConvVariant { CONV_PLANAR_SMALLC = 0, CONV_CHBLOCK = 1, CONV_DIRECT = 2 };
+enum ConvVariant { CONV_PLANAR_SMALLC = 0, CONV_CHBLOCK = 1, CONV_DIRECT = 2, CONV_CHWS = 3 };
 
 struct ConvParams {
     int N, Cin, H, W, Cout, OH, OW;
@@ -135,6 +135,12 @@ struct ConvParams {
     // extents HIP appends follow: touch_kernarg_lines in conv2d.hip covers all six)
     int pipe;              // multi-pass kernel: 9 or 1 = taps of the pipelined vector staging, 0 = plain staging
     FastDiv div_w;         // multi-pass kernel, one-pixel staging units: W
+    // wave-specialised multi-pass kernel (CONV_CHWS): CB = 32-channel blocks per workgroup (4 or 2),
+    // TM = 256, nchi = 2 channel groups per pass, nchunks = passes
+    int lds_buf_bytes;     // one of its two pass buffers (weights, then input rows)
+    int xu;                // input staging units per moving thread and pass
+    FastDiv div_cog;       // work item -> (tile, channel block)
+    FastDiv div_r2;        // staged rows of both channel groups of a pass (2 * RHa)
 };
 
 // ---- launchers (defined in the .hip files) --------------------------------
@@ -146,6 +152,11 @@ hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, cons
 const char *pool_kernel_name(const PoolParams &p);
 const char *sad_kernel_name(const SadParams &p);
 const char *conv_kernel_name(const ConvParams &p);
+int conv_device_cu_count();     // compute units of the current device (256 on MI355X)
+// wave-specialised multi-pass kernel: w is the [Cout][Cin][kh][kw] tensor, or (packed) what
+// launch_conv2d_pack_weights wrote
+hipError_t launch_conv2d_chws(const ConvParams &p, const void *x, const void *w, void *y, hipStream_t s, bool packed);
+hipError_t launch_conv2d_pack_weights(const ConvParams &p, const void *w, void *packed, hipStream_t s);
 
 // ---- correlation layer -----------------------------------------------------
 // One staging unit = 8 pixels x 8 channels.  One unit per thread and pass measured best: fewer

@@ -600,6 +600,72 @@ merit_status derive_conv(merit_plan *pl)
         return true;
     };
 
+    // Wave-specialised multi-pass kernel (conv2d_chws.hip): 256-pixel tiles x `cb` 32-channel blocks
+    // (4 or 2), 16 input channels per pass through two LDS buffers, 3x3 or 1x1 windows on a multiple
+    // of 8 input channels.
+    auto try_chws = [&](int cb, bool forced, int nw = 8) -> bool {
+        if (!((kh == 3 && kw == 3) || (kh == 1 && kw == 1))) return false;
+        // its tiles are 256 pixels of one image: small images (13x13, 7x7) would leave a third
+        // and more of every tile empty and stay with the 128-pixel tiles of the plain kernels
+        if (!forced && 4 * ohw < 3 * cdiv(ohw, 256) * 256) return false;
+        if (Cin % 8 != 0 || Cin < 16 || pool || p.residual || ncb < 2) return false;
+        if (cb != 2 && cb != 4) return false;
+        ConvParams q = p;
+        q.variant = CONV_CHWS;
+        q.CB = cb;
+        q.co_groups = (int)cdiv(ncb, cb);
+        q.PXW = (cb == 4 && nw == 8) ? 4 : 2;    // 32-pixel blocks per multiplying wavefront
+        q.NW = nw;                               // 8: four multiplying + four moving wavefronts; 12: eight + four
+        q.TM = 256;
+        q.tiles_per_image = (int)cdiv(ohw, q.TM);
+        q.rows_out_max = (int)((q.TM + OW - 2) / OW + 1);
+        if (q.rows_out_max > OH) q.rows_out_max = (int)OH;
+        q.RHa = (int)((q.rows_out_max - 1) * sh + eh);
+        q.front = 0; q.aligned = 0; q.ws = 0; q.su = 0; q.lg_chunks = 0; q.pipe = 0;
+        q.G = q.G2 = 0;
+        q.padl = (int)pw;
+        int64_t pitch = q.padl + W;
+        const int64_t reach = (OW - 1) * sw + ew;
+        if (reach > pitch) pitch = reach;
+        pitch |= 1;                               // odd: staged rows start in different LDS bank groups
+        q.pitch = (int)pitch;
+        q.nchi = 2;
+        q.nchunks = (int)cdiv(Cin, 16);
+        q.S = (int)(kh * kw);
+        const int64_t w_bytes = kh * kw * cb * 64 * 16;
+        const int64_t x_bytes = 2 * (int64_t)q.RHa * pitch * 16;
+        const int64_t o_bytes = (int64_t)cb * 32 * (q.TM / 2 + 2) * 4;
+        const int64_t total = 2 * (w_bytes + x_bytes) > o_bytes ? 2 * (w_bytes + x_bytes) : o_bytes;
+        if (total > LDS_LIMIT) return false;
+        q.lds_w_bytes = (int)w_bytes; q.lds_x_bytes = (int)x_bytes; q.lds_buf_bytes = (int)(w_bytes + x_bytes);
+        q.lds_o_offset = 0; q.lds_o_bytes = (int)o_bytes; q.lds_total = (int)total;
+        // staging units per moving thread and pass: 8 channels x 8 pixels (two at most), or x 1 pixel (four)
+        if ((W % 8) == 0) {
+            const int64_t nu = 2 * (int64_t)q.RHa * (W / 8);
+            if (nu > 2 * 256 || !fastdiv_ok(nu, 2 * (int64_t)q.RHa)) return false;
+            q.xu = (int)cdiv(nu, 256);
+            q.div_w8 = make_fastdiv((uint32_t)(W / 8));
+            q.div_r2 = make_fastdiv((uint32_t)(2 * q.RHa));
+        } else {
+            const int64_t nu = 2 * (int64_t)q.RHa * W;
+            if (nu > 4 * 256 || !fastdiv_ok(nu, W)) return false;
+            q.xu = (int)cdiv(nu, 256);
+            q.div_w = make_fastdiv((uint32_t)W);
+        }
+        const int64_t nitems = N * q.tiles_per_image * q.co_groups;
+        if (nitems >= (1ll << 30) || !fastdiv_ok(nitems + 256, q.co_groups) || !fastdiv_ok(2 * (int64_t)q.RHa, q.RHa) ||
+            !fastdiv_ok(ohw, OW) || !fastdiv_ok(N * q.tiles_per_image, q.tiles_per_image))
+            return false;
+        if (N * Cin * H * W >= (1ll << 31) || N * Cout * ohw >= (1ll << 31)) return false;
+        q.div_cog = make_fastdiv((uint32_t)q.co_groups);
+        q.div_rha = make_fastdiv((uint32_t)q.RHa);
+        q.div_ow = make_fastdiv((uint32_t)OW);
+        q.div_tiles = make_fastdiv((uint32_t)q.tiles_per_image);
+        q.wg_per_cu = 1;
+        p = q;
+        return true;
+    };
+
     // tile = (wavefronts per workgroup) x (pixels per wavefront): 4 x 32, 4 x 64 or, for the
     // planar kernel, 8 x 32.  256-pixel tiles when that still leaves a large grid.
     const bool want_big = N * cdiv(ohw, 256) * p.co_groups >= 512;
@@ -627,8 +693,20 @@ merit_status derive_conv(merit_plan *pl)
         if ((int64_t)N * p.NB >= (1ll << 31)) return MERIT_ERR_UNSUPPORTED;
     } else if (pl->tile_req[2] > 0 && pl->tile_req[3] > 0) {
         const int64_t nw = pl->tile_req[2], ppw = pl->tile_req[3];
-        if ((nw != 4 && nw != 8) || (ppw != 32 && ppw != 64)) return MERIT_ERR_UNSUPPORTED;
-        if (nw == 8 && ppw == 64) {
+        if ((nw != 4 && nw != 8 && nw != 12) || (ppw != 32 && ppw != 64 && ppw != 128)) return MERIT_ERR_UNSUPPORTED;
+        if (ppw == 128 && nw != 8) return MERIT_ERR_UNSUPPORTED;
+        if (nw == 12) {
+            // 8 multiplying (64 pixels x 64 channels each) + 4 moving wavefronts: 256 pixels x 128 channels
+            if (ppw != 64 || Cin < 8) return MERIT_ERR_UNSUPPORTED;
+            ok = try_chws(4, true, 12);
+            if (!ok) return MERIT_ERR_UNSUPPORTED;
+        } else if (nw == 8 && Cin >= 8) {
+            // 4 multiplying + 4 moving wavefronts on many channels: 256 pixels x 128 (4 x 32) or 64 channels
+            ok = try_chws(ppw == 128 ? 4 : (ppw == 64 ? 2 : 0), true);
+            if (!ok) return MERIT_ERR_UNSUPPORTED;
+        } else if (ppw == 128) {
+            return MERIT_ERR_UNSUPPORTED;
+        } else if (nw == 8 && ppw == 64) {
             // 4 multiplier wavefronts x 64 pixels + 4 mover wavefronts: the wave-specialised kernel
             if (p.residual) return MERIT_ERR_UNSUPPORTED;
             want_ws = true;
@@ -643,6 +721,13 @@ merit_status derive_conv(merit_plan *pl)
         if (!ok)
             ok = want_big ? (try_variant(CONV_CHBLOCK, 2, 4) || try_variant(CONV_CHBLOCK, 1, 4))
                           : (try_variant(CONV_CHBLOCK, 1, 4) || try_variant(CONV_CHBLOCK, 2, 4));
+        // layers whose channels do not fit LDS at once (they would go through the plain multi-pass
+        // kernel): the wave-specialised one, 128 output channels per workgroup when there are that many
+        // (3x3 only by default: a 1x1 pass is one MFMA step per 16 staged channels, which the plain
+        // multi-pass kernel's larger passes serve better; 12 wavefronts when the tile has 128 channels)
+        if ((!ok || p.nchunks > 1) && kh == 3 &&
+            ((ncb >= 4 && try_chws(4, false, 12)) || try_chws(2, false)))
+            ok = true;
     }
     if (!ok) {
         // neither MFMA kernel holds this shape's operands in LDS: the one-element-per-thread
@@ -681,8 +766,9 @@ merit_status derive_conv(merit_plan *pl)
         li.grid[0] = nt < slots ? nt : slots;
         if (pool) li.grid[0] = (int64_t)N * p.NB;          // one workgroup per band, not persistent
         if (p.variant == CONV_DIRECT) li.grid[0] = nt;     // one workgroup per 256 pixels x 8 channels
+        if (p.variant == CONV_CHWS) li.grid[0] = nt * p.co_groups < 256 ? nt * p.co_groups : 256;   // (tile, channel block) items
     }
-    li.grid[1] = p.variant == CONV_DIRECT ? 1 : p.co_groups; li.grid[2] = 1;
+    li.grid[1] = (p.variant == CONV_DIRECT || p.variant == CONV_CHWS) ? 1 : p.co_groups; li.grid[2] = 1;
     li.block[0] = p.ws ? 512 : p.NW * 64; li.block[1] = 1; li.block[2] = 1;
     li.lds_bytes = (int64_t)conv_lds_bytes(p);
     li.tile[0] = 1; li.tile[1] = p.CB * 32; li.tile[2] = p.rows_out_max; li.tile[3] = OW;
@@ -1177,6 +1263,44 @@ merit_status merit_conv2d(const merit_plan *plan, const void *x, const void *w, 
     if (!x || !w || !y) return MERIT_ERR_NULL;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return MERIT_ERR_ALIGNMENT;
     return launch_conv2d(plan->conv, x, w, nullptr, y, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? MERIT_OK
+               : MERIT_ERR_HIP;
+}
+
+static bool plan_takes_packed(const merit_plan *plan)
+{
+    return (plan->desc.op == MERIT_OP_CONV_DOT || plan->desc.op == MERIT_OP_CONV_DOT_RELU) &&
+           plan->conv.variant == CONV_CHWS;
+}
+
+merit_status merit_plan_packed_weights_bytes(const merit_plan *plan, int64_t *bytes)
+{
+    if (!plan || !bytes) return MERIT_ERR_NULL;
+    if (!plan_takes_packed(plan)) return MERIT_ERR_UNSUPPORTED;
+    const ConvParams &p = plan->conv;
+    *bytes = (int64_t)p.co_groups * p.nchunks * p.lds_w_bytes;
+    return MERIT_OK;
+}
+
+merit_status merit_conv2d_pack_weights(const merit_plan *plan, const void *w, void *packed, void *stream)
+{
+    if (!plan) return MERIT_ERR_NULL;
+    if (!plan_takes_packed(plan)) return MERIT_ERR_UNSUPPORTED;
+    if (!w || !packed) return MERIT_ERR_NULL;
+    if (!aligned16(w) || !aligned16(packed)) return MERIT_ERR_ALIGNMENT;
+    return launch_conv2d_pack_weights(plan->conv, w, packed, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? MERIT_OK
+               : MERIT_ERR_HIP;
+}
+
+merit_status merit_conv2d_packed(const merit_plan *plan, const void *x, const void *packed, void *y, void *stream)
+{
+    if (!plan) return MERIT_ERR_NULL;
+    if (!plan_takes_packed(plan)) return MERIT_ERR_UNSUPPORTED;
+    if (plan->conv.N == 0) return MERIT_OK;               // empty batch: nothing to read or write
+    if (!x || !packed || !y) return MERIT_ERR_NULL;
+    if (!aligned16(x) || !aligned16(packed) || !aligned16(y)) return MERIT_ERR_ALIGNMENT;
+    return launch_conv2d_chws(plan->conv, x, packed, y, static_cast<hipStream_t>(stream), true) == hipSuccess
                ? MERIT_OK
                : MERIT_ERR_HIP;
 }

@@ -447,10 +447,30 @@ def test_conv_plans_for_layers_that_do_not_fit_lds_at_once():
     """Channel passes for many-channel layers; the one-element-per-thread kernel when a wide
     window on few channels fits neither MFMA layout; the tile request and the fused pooling
     stay with the MFMA kernels."""
-    for shape in ((1, 512, 14, 14, 512, 3, 3, 1, 1, 1, 1), (1, 96, 27, 27, 256, 5, 5, 1, 1, 2, 2),
-                  (1, 64, 224, 224, 64, 3, 3, 1, 1, 1, 1), (8, 256, 56, 56, 64, 1, 1, 1, 1, 0, 0)):
+    for shape, kernel in (((1, 512, 14, 14, 512, 3, 3, 1, 1, 1, 1), "merit_conv2d_chws"),
+                          ((1, 96, 27, 27, 256, 5, 5, 1, 1, 2, 2), "merit_conv2d_chpass"),      # 5x5 window
+                          ((1, 512, 7, 7, 512, 3, 3, 1, 1, 1, 1), "merit_conv2d_chpass"),       # 49 pixels: a 256-pixel tile would be 4/5 empty
+                          ((1, 300, 56, 56, 64, 3, 3, 1, 1, 1, 1), "merit_conv2d_chpass"),      # Cin % 8 != 0
+                          ((1, 64, 224, 224, 64, 3, 3, 1, 1, 1, 1), "merit_conv2d_chws"),
+                          ((8, 256, 56, 56, 256, 3, 3, 1, 1, 1, 1), "merit_conv2d_chws"),
+                          ((8, 256, 56, 56, 64, 1, 1, 1, 1, 0, 0), "merit_conv2d_chpass")):       # 1x1: larger passes
         li = mb.merit_plan_conv2d(*shape).launch_info()
-        assert li["kernel"] == "merit_conv2d_chpass" and 0 < li["lds_bytes"] <= 160 * 1024, (shape, li)
+        assert li["kernel"] == kernel and 0 < li["lds_bytes"] <= 160 * 1024, (shape, li)
+        if kernel == "merit_conv2d_chws":
+            # 4 moving wavefronts + 8 multiplying ones on 128-channel tiles, 4 on 64-channel tiles
+            assert li["block"][0] == (768 if li["tile"][1] == 128 else 512), li
+            assert li["grid"][0] <= 256 and li["grid"][1] == 1
+    # the wave-specialised kernel on request: 8 wavefronts, 128 or 64 pixels per multiplying wavefront
+    p = mb.merit_plan_conv2d(8, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1)
+    p.set_tile((0, 0, 8, 64))
+    assert p.launch_info()["kernel"] == "merit_conv2d_chws" and p.launch_info()["tile"][1] == 64
+    assert mb.merit_plan_packed_weights_bytes(p) == 64 * 64 * 9 * 2           # nothing padded here
+    p = mb.merit_plan_conv2d(8, 256, 56, 56, 256, 3, 3, 1, 1, 1, 1)
+    assert p.launch_info()["tile"][1] == 128 and mb.merit_plan_packed_weights_bytes(p) == 256 * 256 * 9 * 2
+    with pytest.raises(mb.MeritError):                                          # 5x5: no such instance
+        mb.merit_plan_conv2d(1, 96, 27, 27, 256, 5, 5, 1, 1, 2, 2).set_tile((0, 0, 8, 128))
+    with pytest.raises(mb.MeritError):                                          # packed weights: only that kernel
+        mb.merit_plan_packed_weights_bytes(mb.merit_plan_conv2d(1, 3, 32, 32, 16, 7, 7, 2, 2, 3, 3))
     alex1 = (1, 3, 227, 227, 96, 11, 11, 4, 4, 0, 0)
     p = mb.merit_plan_conv2d(*alex1)
     li = p.launch_info()

@@ -757,7 +757,7 @@ def test_conv_channel_passes_and_wide_window_workloads_sampled(mb):
     c = wl.CFG_CONV256
     x, w = wl.make_conv_inputs(c)
     plan = mb.merit_plan_conv2d(c.N, c.Cin, c.H, c.W, c.Cout, c.kh, c.kw, c.sh, c.sw, c.ph, c.pw)
-    assert plan.launch_info()["kernel"] == "merit_conv2d_chpass"
+    assert plan.launch_info()["kernel"] == "merit_conv2d_chws"
     y = mb.merit_conv2d(plan, dev(x), dev(w)).cpu().numpy().astype(np.float64)
     n = 5
     ref = oracle.conv2d(x[n:n + 1], w, (c.sh, c.sw), (c.ph, c.pw)).astype(np.float64)

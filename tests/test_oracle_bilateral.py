@@ -75,6 +75,33 @@ def test_one_pixel_by_hand(k, norm):
         assert abs(float(y[0, p1, p2]) - wxsum / wsum) <= 1e-6 * abs(wxsum / wsum) + 1e-6
 
 
+def test_range_factor_closed_form_half_weight():
+    """Section VI-A, Listing 2: a neighbour's range factor is exp(norm * (difference)^2).  A row
+    `b a b` with (a - b)^2 * norm = -ln 2 gives both neighbours exactly half their spatial
+    weight, so the centre output is (g1 a + (g0 + g2) b / 2) / (g1 + (g0 + g2) / 2); the table
+    along the other window index multiplies numerator and denominator alike and cancels (all
+    three window rows clamp to the one image row).  Numbers worked by hand: a = 10, b = 4,
+    g = (1, 2, 3) -> (20 + 8) / (2 + 2) = 7.  A factor of 2 in the exponent would give
+    (20 + 4) / (2 + 1) = 8, a missing square (a - b = 6 instead of 36) a weight of 2^(-1/6)."""
+    norm = -np.log(2.0) / 36.0
+    g = np.array([1, 2, 3], np.float32)
+    other = np.array([0.3, 1.7, 0.9], np.float32)
+    row = np.array([[[4, 10, 4]]], np.float32)                  # [N=1, H=1, W=3]
+    y = oracle.bilateral(row, g, other, norm)
+    assert abs(float(y[0, 0, 1]) - 7.0) < 1e-6
+    # the same column-wise: now the table along the height carries the weights
+    col = row.reshape(1, 3, 1).copy()
+    y = oracle.bilateral(col, other, g, norm)
+    assert abs(float(y[0, 1, 0]) - 7.0) < 1e-6
+    # the border pixels: window `b b a` (left edge clamps): neighbours b (full weight, d = 0)
+    # and a (half weight): (1*4 + 2*4 + 3*10/2) / (1 + 2 + 3/2) = 27 / 4.5 = 6
+    y = oracle.bilateral(row, g, other, norm)
+    assert abs(float(y[0, 0, 0]) - 6.0) < 1e-6
+    # a quarter weight: (a - b)^2 * norm = -2 ln 2 with a - b = 6 -> norm = -2 ln 2 / 36
+    y = oracle.bilateral(row, g, other, 2 * norm)
+    assert abs(float(y[0, 0, 1]) - 8.0) < 1e-6
+
+
 def test_output_stays_within_the_window_range():
     rng = np.random.default_rng(7)
     x = rng.uniform(0, 255, (1, 20, 20)).astype(np.float32)
