@@ -42,7 +42,8 @@ typedef enum {
     MERIT_ERR_SHAPE,         /* ranges/shapes inconsistent with each other         */
     MERIT_ERR_UNSUPPORTED,   /* a valid transform that no kernel here implements   */
     MERIT_ERR_ALIGNMENT,     /* device pointer not 16-byte aligned                 */
-    MERIT_ERR_HIP            /* the HIP runtime refused the launch                 */
+    MERIT_ERR_HIP,           /* the HIP runtime refused the launch                 */
+    MERIT_ERR_SCRATCH_LIMIT  /* more scratch memory needed than the library's fixed buffer holds */
 } merit_status;
 
 /* Product functions (.) (Section III-B): dot product (Eq. 3); max / mean of the
@@ -266,6 +267,22 @@ merit_status merit_conv2d_pack_weights(const merit_plan *plan, const void *w_f16
                                        void *hip_stream);
 merit_status merit_conv2d_packed(const merit_plan *plan, const void *x_f16, const void *packed,
                                  void *y_f16, void *hip_stream);
+
+/* For callers that cannot allocate device memory -- code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc: merit_conv2d_pack_weights and
+ * merit_conv2d_packed in one call, with the packed copy in a fixed device buffer that lives
+ * inside the library instead of one the caller brings.  The buffer is
+ * MERIT_NOALLOC_SCRATCH_BYTES per GPU, part of the loaded library on every GPU it runs on
+ * until the process ends; a plan whose packed weights are larger is refused with
+ * MERIT_ERR_SCRATCH_LIMIT (nothing launched), a plan whose kernel takes no packed weights with
+ * MERIT_ERR_UNSUPPORTED.  Neither this call nor anything it runs allocates or frees memory.
+ * Every call on a GPU uses that GPU's one buffer and overwrites all of the part it needs:
+ * two calls that overlap in time on one GPU (different streams, different threads) race and
+ * give undefined results; calls on one stream are ordered and safe.  Same result, bit for
+ * bit, as merit_conv2d_packed. */
+#define MERIT_NOALLOC_SCRATCH_BYTES (8 << 20)
+merit_status merit_conv2d_packed_noalloc(const merit_plan *plan, const void *x_f16, const void *w_f16,
+                                         void *y_f16, void *hip_stream);
 
 /* Residual layer: as merit_conv2d, with r_f16 [N,Cout,OH,OW] binary16 added to the fp32 sums
  * before the clip (if the plan has one) and the one rounding to binary16.  r_f16 may be

@@ -18,7 +18,8 @@ MERIT_AXIS_UNUSED = -1
 
 MERIT_OK = 0
 (MERIT_ERR_NULL, MERIT_ERR_INVALID_ARG, MERIT_ERR_SHAPE, MERIT_ERR_UNSUPPORTED,
- MERIT_ERR_ALIGNMENT, MERIT_ERR_HIP) = range(1, 7)
+ MERIT_ERR_ALIGNMENT, MERIT_ERR_HIP, MERIT_ERR_SCRATCH_LIMIT) = range(1, 8)
+MERIT_NOALLOC_SCRATCH_BYTES = 8 << 20
 (MERIT_OP_CONV_DOT, MERIT_OP_POOL_MAX, MERIT_OP_POOL_AVG, MERIT_OP_SAD_ARGMIN, MERIT_OP_CONV_DOT_RELU,
  MERIT_OP_CORR_DOT, MERIT_OP_DWCONV_DOT, MERIT_OP_CONV_DOT_POOLMAX, MERIT_OP_CONV_DOT_RELU_POOLMAX,
  MERIT_OP_CONV_DOT_ADD, MERIT_OP_CONV_DOT_ADD_RELU, MERIT_OP_SEPFILTER_DOT,
@@ -105,6 +106,7 @@ def lib():
     L.merit_plan_packed_weights_bytes.argtypes = [P, ctypes.POINTER(ctypes.c_int64)]
     L.merit_conv2d_pack_weights.argtypes = [P, P, P, P]
     L.merit_conv2d_packed.argtypes = [P, P, P, P, P]
+    L.merit_conv2d_packed_noalloc.argtypes = [P, P, P, P, P]
     L.merit_pool2d.argtypes = [P, P, P, P]
     L.merit_sad_search.argtypes = [P, P, P, P, P, P]
     for name in ("merit_plan_create", "merit_plan_destroy", "merit_plan_conv2d", "merit_plan_conv2d_relu",
@@ -116,7 +118,7 @@ def lib():
                  "merit_conv2d_depthwise", "merit_plan_get_desc", "merit_plan_out_shape", "merit_plan_footprint",
                  "merit_plan_launch_info", "merit_plan_set_tile", "merit_conv2d", "merit_pool2d",
                  "merit_sad_search", "merit_plan_packed_weights_bytes", "merit_conv2d_pack_weights",
-                 "merit_conv2d_packed"):
+                 "merit_conv2d_packed", "merit_conv2d_packed_noalloc"):
         getattr(L, name).restype = c_int
     L.merit_status_string.argtypes = [c_int]
     L.merit_status_string.restype = ctypes.c_char_p
@@ -315,6 +317,18 @@ def merit_conv2d_packed(plan: Plan, x, packed, y=None, stream=None):
     _check(lib().merit_conv2d_packed(plan.handle, _dev_ptr(x, torch.float16, "x"),
                                      _dev_ptr(packed, torch.float16, "packed"), _dev_ptr(y, torch.float16, "y"),
                                      _stream(stream)), "merit_conv2d_packed")
+    return y
+
+
+def merit_conv2d_packed_noalloc(plan: Plan, x, w, y, stream=None):
+    """No allocation anywhere: the caller passes every tensor, the packed weights live in the library."""
+    import torch
+    out_shape, a_shape, b_shape = plan.shapes()
+    if tuple(y.shape) != out_shape or tuple(x.shape) != a_shape or tuple(w.shape) != b_shape:
+        raise ValueError("tensors do not match the plan")
+    _check(lib().merit_conv2d_packed_noalloc(plan.handle, _dev_ptr(x, torch.float16, "x"),
+                                             _dev_ptr(w, torch.float16, "w"), _dev_ptr(y, torch.float16, "y"),
+                                             _stream(stream)), "merit_conv2d_packed_noalloc")
     return y
 
 

@@ -22,6 +22,7 @@
 #include "merit_internal.h"
 
 #include <atomic>
+#include <mutex>
 
 #ifndef MERIT_CHWS_EXPERIMENT
 #define MERIT_CHWS_EXPERIMENT 0     // 2: the multiplying wavefronts skip the K loop (wrong results), 9: in-kernel phase timing printed by one workgroup
@@ -590,6 +591,46 @@ hipError_t launch_conv2d_pack_weights(const ConvParams &p, const void *w, void *
     hipLaunchKernelGGL(merit_conv2d_pack_w, dim3((uint32_t)((total + 255) / 256)), dim3(256), 0, s, p, T, p.CB,
                        reinterpret_cast<const uint16_t *>(w), reinterpret_cast<uint4 *>(packed), total);
     return hipGetLastError();
+}
+
+// ---- the packed copy in a buffer of the library's own, for callers that cannot allocate ----
+// A file-scope device array: every GPU the library runs on holds its own copy at its own
+// address until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; kernels get the address that call returned, per device.
+static __device__ __align__(256) unsigned char scratch[MERIT_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex scratch_mutex;
+void *scratch_ptr[MAX_DEVICES];          // device address of `scratch` on each GPU, once asked for
+
+hipError_t scratch_address(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));      // the current device's copy
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        scratch_ptr[dev] = ptr;
+    }
+    *out = scratch_ptr[dev];
+    return hipSuccess;
+}
+}  // namespace
+
+hipError_t launch_conv2d_chws_noalloc(const ConvParams &p, const void *x, const void *w, void *y, hipStream_t s)
+{
+    void *packed = nullptr;
+    hipError_t e = scratch_address(&packed);
+    if (e != hipSuccess) return e;
+    e = launch_conv2d_pack_weights(p, w, packed, s);            // writes every fragment the passes read
+    if (e != hipSuccess) return e;
+    return launch_conv2d_chws(p, x, packed, y, s, true);
 }
 
 }  // namespace merit

@@ -157,6 +157,9 @@ int conv_device_cu_count();     // compute units of the current device (256 on M
 // launch_conv2d_pack_weights wrote
 hipError_t launch_conv2d_chws(const ConvParams &p, const void *x, const void *w, void *y, hipStream_t s, bool packed);
 hipError_t launch_conv2d_pack_weights(const ConvParams &p, const void *w, void *packed, hipStream_t s);
+// the same two launches with the packed copy in the library's own fixed device buffer
+// (MERIT_NOALLOC_SCRATCH_BYTES; the caller has checked that the plan's packed weights fit)
+hipError_t launch_conv2d_chws_noalloc(const ConvParams &p, const void *x, const void *w, void *y, hipStream_t s);
 
 // ---- correlation layer -----------------------------------------------------
 // One staging unit = 8 pixels x 8 channels.  One unit per thread and pass measured best: fewer

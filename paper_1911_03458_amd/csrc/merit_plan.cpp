@@ -1305,6 +1305,20 @@ merit_status merit_conv2d_packed(const merit_plan *plan, const void *x, const vo
                : MERIT_ERR_HIP;
 }
 
+merit_status merit_conv2d_packed_noalloc(const merit_plan *plan, const void *x, const void *w, void *y, void *stream)
+{
+    if (!plan) return MERIT_ERR_NULL;
+    if (!plan_takes_packed(plan)) return MERIT_ERR_UNSUPPORTED;
+    const ConvParams &p = plan->conv;
+    if ((int64_t)p.co_groups * p.nchunks * p.lds_w_bytes > (int64_t)MERIT_NOALLOC_SCRATCH_BYTES)
+        return MERIT_ERR_SCRATCH_LIMIT;
+    if (p.N == 0) return MERIT_OK;                        // empty batch: nothing to read or write
+    if (!x || !w || !y) return MERIT_ERR_NULL;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return MERIT_ERR_ALIGNMENT;
+    return launch_conv2d_chws_noalloc(p, x, w, y, static_cast<hipStream_t>(stream)) == hipSuccess ? MERIT_OK
+                                                                                                   : MERIT_ERR_HIP;
+}
+
 merit_status merit_conv2d_residual(const merit_plan *plan, const void *x, const void *w, const void *r, void *y,
                                    void *stream)
 {
@@ -1431,6 +1445,7 @@ const char *merit_status_string(merit_status s)
     case MERIT_ERR_UNSUPPORTED: return "transform not supported by any kernel";
     case MERIT_ERR_ALIGNMENT: return "device pointer not 16-byte aligned";
     case MERIT_ERR_HIP: return "HIP launch failed";
+    case MERIT_ERR_SCRATCH_LIMIT: return "needs more scratch memory than the library's fixed buffer holds";
     }
     return "unknown status";
 }

@@ -35,8 +35,8 @@ def test_library_exports_every_declared_symbol():
 
 def test_status_strings():
     L = mb.lib()
-    seen = {L.merit_status_string(i).decode() for i in range(7)}
-    assert len(seen) == 7 and "ok" in seen
+    seen = {L.merit_status_string(i).decode() for i in range(8)}
+    assert len(seen) == 8 and "ok" in seen
 
 
 def test_struct_layout_matches_header_sizes():
