@@ -35,6 +35,18 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitized_check() -> str:
+    """merit_oracle.c + oracle_check.c under AddressSanitizer and UBSan, as an executable."""
+    exe = os.path.join(_HERE, "oracle_check_asan")
+    chk = os.path.join(_HERE, "oracle_check.c")
+    if os.path.exists(exe) and os.path.getmtime(exe) >= max(os.path.getmtime(_SRC), os.path.getmtime(chk)):
+        return exe
+    cmd = ["gcc", "-O1", "-g", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fsanitize=address,undefined",
+           "-fno-sanitize-recover=all", "-static-libasan", "-Wall", "-Wextra", "-o", exe, _SRC, chk, "-lm"]
+    subprocess.run(cmd, check=True)
+    return exe
+
+
 def _load():
     global _lib
     if _lib is not None:

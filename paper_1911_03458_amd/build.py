@@ -59,5 +59,52 @@ def build_library(force: bool = True, extra_flags=()) -> str:
     return LIB_PATH
 
 
+def build_host_check(sanitizer: str = "address,undefined") -> str:
+    """CPU-only build for host robustness checks: the host side of every source (no device code,
+    so it takes seconds) with -fsanitize=<sanitizer>, linked with csrc/host_check.cpp into an
+    executable that exercises the plan code through the C ABI without touching a GPU.
+    `sanitizer` = "address,undefined" or "thread".  Returns the executable's path."""
+    tag = sanitizer.replace(",", "_")
+    objdir = os.path.join(_HERE, "_build", "host_" + tag)
+    os.makedirs(objdir, exist_ok=True)
+    exe = os.path.join(objdir, "host_check")
+    srcs = [os.path.join(CSRC, s) for s in SOURCES] + [os.path.join(CSRC, "host_check.cpp")]
+    if os.path.exists(exe) and all(os.path.getmtime(d) <= os.path.getmtime(exe) for d in srcs + HEADERS):
+        return exe
+    common = [hipcc_path(), "--offload-arch=gfx950", "--cuda-host-only", "-O1", "-g", "-std=c++17",
+              "-fsanitize=" + sanitizer, "-fno-sanitize-recover=all", "-Wno-unused-command-line-argument",
+              "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    objs = [os.path.join(objdir, os.path.splitext(os.path.basename(s))[0] + ".o") for s in srcs]
+
+    def compile_one(job):
+        src, obj = job
+        return subprocess.run(common + ["-c", src, "-o", obj], capture_output=True, text=True)
+
+    with ThreadPoolExecutor(max_workers=min(len(srcs), os.cpu_count() or 1)) as pool:
+        for proc in pool.map(compile_one, zip(srcs, objs)):
+            if proc.returncode != 0:
+                raise RuntimeError("hipcc (host check) failed:\n" + proc.stdout + proc.stderr)
+    # Host-only objects still refer to the device code object they would register at load time
+    # (one symbol per source, named after a hash); there is none in this build: define each as
+    # a few zero bytes, which the HIP runtime declines to load -- nothing here launches a kernel.
+    undef = set()
+    for obj in objs:
+        nm = subprocess.run(["nm", "-u", obj], capture_output=True, text=True)
+        undef |= {ln.split()[-1] for ln in nm.stdout.splitlines() if "__hip_fatbin_" in ln}
+    stub = os.path.join(objdir, "no_device_code.c")
+    with open(stub, "w") as f:
+        for name in sorted(undef):
+            f.write(f"const unsigned long long {name}[8] = {{0}};\n")
+    stub_o = os.path.join(objdir, "no_device_code.o")
+    proc = subprocess.run(["gcc", "-c", stub, "-o", stub_o], capture_output=True, text=True)
+    if proc.returncode != 0:
+        raise RuntimeError("gcc (host check stub) failed:\n" + proc.stdout + proc.stderr)
+    proc = subprocess.run([hipcc_path(), "--offload-arch=gfx950", "-fsanitize=" + sanitizer, "-o", exe] + objs
+                          + [stub_o, "-lpthread"], capture_output=True, text=True)
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc (host check link) failed:\n" + proc.stdout + proc.stderr)
+    return exe
+
+
 if __name__ == "__main__":
     print(build_library())

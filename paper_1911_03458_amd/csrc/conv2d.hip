@@ -1771,12 +1771,7 @@ static hipError_t launch(K kernel, const ConvParams &p, const void *x, const voi
     // raise this kernel instance's dynamic-LDS limit to the 160 KB a gfx950 workgroup may
     // use; done once per instance (the static lives in this template instantiation)
     static std::atomic<int> raised{0};
-    if (!raised.load(std::memory_order_acquire)) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        raised.store(1, std::memory_order_release);
-    }
+    if (hipError_t e = raise_lds_limit_once(reinterpret_cast<const void *>(kernel), raised); e != hipSuccess) return e;
     hipLaunchKernelGGL(kernel, dim3(gx, (uint32_t)p.co_groups), dim3(nthreads), lds_bytes, s, p,
                        reinterpret_cast<const uint16_t *>(x), reinterpret_cast<const uint16_t *>(w),
                        reinterpret_cast<const uint16_t *>(r), reinterpret_cast<uint16_t *>(y));
@@ -1789,7 +1784,7 @@ size_t conv_lds_bytes(const ConvParams &p)
 }
 
 // number of compute units of the current device (cached; 256 on MI355X)
-int conv_device_cu_count()
+int device_cu_count()
 {
     static std::atomic<int> cus{0};
     int c = cus.load(std::memory_order_relaxed);
@@ -1817,7 +1812,7 @@ hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, cons
         return hipGetLastError();
     }
     // persistent grid: as many workgroups as fit on the chip at once, at most one per tile
-    int64_t slots = (int64_t)conv_device_cu_count() * p.wg_per_cu / p.co_groups;
+    int64_t slots = (int64_t)device_cu_count() * p.wg_per_cu / p.co_groups;
     if (slots < 1) slots = 1;
     const uint32_t gx = (uint32_t)(ntiles < slots ? ntiles : slots);
     const size_t lds = conv_lds_bytes(p);

@@ -538,12 +538,7 @@ hipError_t launch_one(K kernel, const ConvParams &p, const void *x, const void *
 {
     // raise this instance's dynamic-LDS limit to the 160 KB a gfx950 workgroup may use, once
     static std::atomic<int> raised{0};
-    if (!raised.load(std::memory_order_acquire)) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        raised.store(1, std::memory_order_release);
-    }
+    if (hipError_t e = raise_lds_limit_once(reinterpret_cast<const void *>(kernel), raised); e != hipSuccess) return e;
     hipLaunchKernelGGL(kernel, dim3(grid), dim3((unsigned)(p.NW * 64)), (size_t)p.lds_total, s, p, reinterpret_cast<const uint16_t *>(x),
                        reinterpret_cast<const uint16_t *>(w), reinterpret_cast<uint16_t *>(y));
     return hipGetLastError();
@@ -576,7 +571,7 @@ hipError_t launch_conv2d_chws(const ConvParams &p, const void *x, const void *w,
 {
     const int64_t nitems = (int64_t)p.N * p.tiles_per_image * p.co_groups;
     if (nitems == 0) return hipSuccess;
-    const int64_t slots = conv_device_cu_count();            // one 512-thread workgroup per compute unit
+    const int64_t slots = device_cu_count();            // one 512-thread workgroup per compute unit
     const uint32_t grid = (uint32_t)(nitems < slots ? nitems : slots);
     if (p.CB == 4 && p.NW == 12) return launch_tile<2, 2, 4, 2>(p, x, w, y, s, grid, packed);   // 256 x 128, 8 x (64 x 64)
     if (p.CB == 4) return launch_tile<4, 2, 2, 2>(p, x, w, y, s, grid, packed);     // 256 pixels x 128 channels, 4 x (128 x 64)

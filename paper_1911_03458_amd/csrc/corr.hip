@@ -218,13 +218,10 @@ template <int NB, int BPW>
 static hipError_t launch_corr(const CorrParams &p, const void *x1, const void *x2, void *y, hipStream_t s,
                               uint32_t grid)
 {
-    static bool raised = false;
-    if (!raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(merit_corr_mfma<NB, BPW>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        raised = true;
-    }
+    static std::atomic<int> raised{0};
+    if (hipError_t e = raise_lds_limit_once(reinterpret_cast<const void *>(merit_corr_mfma<NB, BPW>), raised);
+        e != hipSuccess)
+        return e;
     hipLaunchKernelGGL((merit_corr_mfma<NB, BPW>), dim3(grid), dim3(256), corr_lds_bytes(p), s, p,
                        reinterpret_cast<const uint16_t *>(x1), reinterpret_cast<const uint16_t *>(x2),
                        reinterpret_cast<uint16_t *>(y));

@@ -155,6 +155,15 @@ hipError_t launch_dwconv(const DwParams &p, const void *x, const void *w, void *
     const uint16_t *xs = reinterpret_cast<const uint16_t *>(x);
     const uint16_t *ws = reinterpret_cast<const uint16_t *>(w);
     uint16_t *ys = reinterpret_cast<uint16_t *>(y);
+    if (p.lds_bytes > 64 * 1024) {     // wide rows: more dynamic LDS than a kernel gets by default
+        static std::atomic<int> raised_rows{0}, raised_tile{0};
+        const bool rows = p.variant == DW_ROWS_K3S1P1;
+        if (hipError_t e = raise_lds_limit_once(rows ? reinterpret_cast<const void *>(merit_dwconv_rows_k3s1p1)
+                                                     : reinterpret_cast<const void *>(merit_dwconv_tile),
+                                                rows ? raised_rows : raised_tile);
+            e != hipSuccess)
+            return e;
+    }
     if (p.variant == DW_ROWS_K3S1P1)
         hipLaunchKernelGGL(merit_dwconv_rows_k3s1p1, dim3((uint32_t)grid), dim3(256), (size_t)p.lds_bytes, s, p, xs, ws, ys);
     else

@@ -3,6 +3,7 @@
 #pragma once
 
 #include <stdint.h>
+#include <atomic>
 #include <hip/hip_runtime.h>
 
 #include "merit.h"
@@ -41,6 +42,22 @@ __device__ __forceinline__ uint32_t xcd_band_item(uint32_t hw_id, int xq, int xr
     return xcd * (uint32_t)xq + min(xcd, (uint32_t)xr) + slot;
 }
 #endif
+
+// ---- launcher helpers (host) -------------------------------------------------
+// A kernel instance may use more than 64 KB of dynamic LDS only after its limit has been raised
+// (to the 160 KB a gfx950 workgroup may use).  Once per instance; `done` is the instance's
+// flag (a function-local static of the launcher template).  Safe to call from several threads:
+// the attribute call is idempotent, the flag only saves repeating it.
+inline hipError_t raise_lds_limit_once(const void *kernel, std::atomic<int> &done)
+{
+    if (!done.load(std::memory_order_acquire)) {
+        hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        done.store(1, std::memory_order_release);
+    }
+    return hipSuccess;
+}
+int device_cu_count();          // compute units of the current device (256 on MI355X); cached, thread-safe
 
 // ---- pooling ---------------------------------------------------------------
 enum PoolVariant { POOL_TILE_GENERIC = 0, POOL_ROWS_K3S2P1 = 1, POOL_ROWS_K2S2P0 = 2, POOL_ROWS_K3S1P1 = 3,
@@ -152,7 +169,6 @@ hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, cons
 const char *pool_kernel_name(const PoolParams &p);
 const char *sad_kernel_name(const SadParams &p);
 const char *conv_kernel_name(const ConvParams &p);
-int conv_device_cu_count();     // compute units of the current device (256 on MI355X)
 // wave-specialised multi-pass kernel: w is the [Cout][Cin][kh][kw] tensor, or (packed) what
 // launch_conv2d_pack_weights wrote
 hipError_t launch_conv2d_chws(const ConvParams &p, const void *x, const void *w, void *y, hipStream_t s, bool packed);

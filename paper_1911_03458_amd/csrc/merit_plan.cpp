@@ -1437,7 +1437,7 @@ merit_status merit_correlation(const merit_plan *plan, const void *x1, const voi
 
 const char *merit_status_string(merit_status s)
 {
-    switch (s) {
+    switch ((int)s) {          // a C caller may pass any int
     case MERIT_OK: return "ok";
     case MERIT_ERR_NULL: return "null pointer";
     case MERIT_ERR_INVALID_ARG: return "invalid argument";

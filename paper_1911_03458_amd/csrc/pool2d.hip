@@ -157,7 +157,8 @@ __global__ __launch_bounds__(256) void merit_pool2d_rows(PoolParams p, const flo
             for (int v = 0; v < 4; ++v) {
                 const int wx0 = (4 * q + v) * SW - PW;
                 const int cx = min(wx0 + KW, p.W) - max(wx0, 0);
-                acc[v] = acc[v] / (float)(cy * cx);
+                const int cnt = max(cy, 0) * max(cx, 0);       // 0: the window lies in the padding
+                acc[v] = cnt > 0 ? acc[v] / (float)cnt : 0.0f;
             }
         }
         reinterpret_cast<float4 *>(yp + (size_t)oy * p.OW)[q] = make_float4(acc[0], acc[1], acc[2], acc[3]);
@@ -354,6 +355,10 @@ static hipError_t launch(K kernel, const PoolParams &p, const float *x, float *y
                          size_t lds_bytes, uint32_t grid)
 {
     if (grid == 0) return hipSuccess;
+    if (lds_bytes > 64 * 1024) {       // wide rows: more dynamic LDS than a kernel gets by default
+        static std::atomic<int> raised{0};                  // (one per kernel instance: K is its type)
+        if (hipError_t e = raise_lds_limit_once(reinterpret_cast<const void *>(kernel), raised); e != hipSuccess) return e;
+    }
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), lds_bytes, s, p, x, y);
     return hipGetLastError();
 }

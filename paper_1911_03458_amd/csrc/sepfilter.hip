@@ -257,13 +257,10 @@ template <int K>
 static hipError_t launch_sep(const SepParams &p, const float *x, const float *kx, const float *ky, float *y,
                              hipStream_t s, int64_t ntiles, int cus)
 {
-    static bool raised = false;
-    if (!raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(merit_sepfilter_tile<K>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        raised = true;
-    }
+    static std::atomic<int> raised{0};
+    if (hipError_t e = raise_lds_limit_once(reinterpret_cast<const void *>(merit_sepfilter_tile<K>), raised);
+        e != hipSuccess)
+        return e;
     // Persistent workgroups.  The plan's count per CU is what LDS allows.  Long windows need so
     // many registers that fewer are resident, and a workgroup beyond the resident ones would
     // start only when another has finished all of its tiles: there the grid is exactly the
@@ -272,13 +269,18 @@ static hipError_t launch_sep(const SepParams &p, const float *x, const float *kx
     // retire, measured faster than two rounds over the resident ones (k = 3: 17.2 against 17.9 us).
     int per_cu = p.wg_per_cu;
     if (K > 16) {
-        static int asked_lds = -1, answer = 1;           // the last query (plans of one shape repeat)
-        if (asked_lds != p.lds_bytes) {
+        // the last query and its answer in one atomic word (plans of one shape repeat); two
+        // threads with different shapes at worst repeat the query, neither reads the other's answer
+        static std::atomic<uint64_t> last{0};
+        const uint64_t seen = last.load(std::memory_order_relaxed);
+        int answer = (int)(seen & 0xffffffffu);
+        if ((seen >> 32) != (uint64_t)(uint32_t)p.lds_bytes || answer <= 0) {
             int r = 0;
             if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&r, merit_sepfilter_tile<K>, 256,
                                                              (size_t)p.lds_bytes) != hipSuccess || r <= 0)
                 r = 1;
-            answer = r; asked_lds = p.lds_bytes;
+            answer = r;
+            last.store(((uint64_t)(uint32_t)p.lds_bytes << 32) | (uint32_t)r, std::memory_order_relaxed);
         }
         if (answer < per_cu) per_cu = answer;
     }
@@ -294,14 +296,7 @@ hipError_t launch_sepfilter(const SepParams &p, const float *x, const float *kx,
     const int64_t ntiles = (int64_t)p.N * p.tiles_y * p.tiles_x;
     if (ntiles == 0) return hipSuccess;
     // persistent workgroups, p.wg_per_cu per compute unit (256 on MI355X), at most one per tile
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-            n = 256;
-        cus = n;
-    }
+    const int cus = device_cu_count();
     switch (p.k) {
 #define MERIT_SEP_CASE(Kv) case Kv: return launch_sep<Kv>(p, x, kx, ky, y, s, ntiles, cus)
 #define MERIT_SEP_CASE8(B)                                                                           \

@@ -65,6 +65,12 @@ POOL_CASES = [
     (1, 5, 9, 13, 9, 13, 2, 3, 0, 0),      # 117 elements: two rounds of lanes
     (2, 6, 5, 6, 7, 8, 1, 1, 1, 1),        # window larger than the plane: padding on every side
     (1, 4, 1, 1, 1, 1, 1, 1, 0, 0),        # a single element per plane
+    # padding as large as the window: the first output rows see no input element (mean of nothing = 0)
+    (1, 2, 16, 32, 3, 3, 2, 2, 3, 1),      # row-strip kernel
+    (1, 2, 16, 32, 3, 3, 2, 2, 4, 1),
+    (1, 2, 9, 11, 3, 3, 2, 2, 3, 3),       # generic kernel, rows and columns
+    # rows so wide that a strip needs more than 64 KB of LDS
+    (1, 1, 16, 8192, 3, 3, 2, 2, 1, 1),
 ]
 
 
@@ -304,6 +310,8 @@ DW_CASES = [
     (1, 4, 11, 13, 3, 3, 2, 2, 1, 1, None),      # generic: stride 2, odd sizes
     (2, 3, 17, 10, 5, 3, 1, 2, 2, 0, None),      # generic: rectangular window, mixed stride / padding
     (1, 1, 8, 8, 1, 1, 1, 1, 0, 0, None),        # pointwise scale
+    (1, 1, 40, 1200, 31, 3, 1, 1, 15, 1, None),  # generic: tall window on wide rows, more than 64 KB of LDS
+    (1, 2, 12, 2800, 3, 3, 1, 1, 1, 1, None),    # row kernel, rows so wide that a strip needs more than 64 KB
 ]
 
 
