@@ -99,6 +99,31 @@ def measure_peaks(torch, mb):
     return out
 
 
+CPU_EXTRA = True      # time the oracle beside every extra workload (off with --no-cpu)
+
+
+def oracle_rate(fn, out_elems, sample):
+    """The oracle as it stands on a bounded sample of the workload: output elements per second on
+    all host threads (best of the passes that fit ~0.3 s, at least one) and on one thread (one pass)."""
+    if not CPU_EXTRA:
+        return None
+    import oracle
+    n = oracle.num_threads()
+    fn()                                            # first touch
+    best, reps, t_all = None, 0, time.perf_counter()
+    while reps < 1 or (time.perf_counter() - t_all < 0.3 and reps < 20):
+        t0 = time.perf_counter(); fn(); dt = time.perf_counter() - t0
+        best = dt if best is None else min(best, dt)
+        reps += 1
+    oracle.set_num_threads(1)
+    try:
+        t0 = time.perf_counter(); fn(); one = time.perf_counter() - t0
+    finally:
+        oracle.set_num_threads(n)
+    return {"kind": "oracle", "unit": "output elems/s", "value": out_elems / best, "cores": n,
+            "value_1_thread": out_elems / one, "sample": sample}
+
+
 def bench_pool(torch, mb, wl, steps, warmup, nsets):
     c = wl.CFG1_POOL
     x_host = torch.from_numpy(wl.make_pool_input(c))
@@ -146,8 +171,17 @@ def bench_sad(torch, mb, wl, cfg, steps, warmup):
     alg_bytes = 2 * cfg.H * cfg.W + nby * nbx * 12
     absdiffs = nby * nbx * cfg.n_candidates * cfg.block * cfg.block
     sad_lane_ops = absdiffs / 4                       # v_sad_u8: four pixels per lane-op
+    # oracle sample: the top two block rows (plus the search margin below them) of the frame pair
+    import oracle
+    rows = min(cfg.H, 2 * cfg.block + cfg.search)
+    rows -= rows % cfg.block
+    rows = max(rows, cfg.block)
+    sub_c, sub_r = cur[:rows].copy(), ref[:rows].copy()
+    cpu = oracle_rate(lambda: oracle.sad_search(sub_c, sub_r, cfg.block, cfg.search),
+                      (rows // cfg.block) * nbx, f"blocks of the top {rows} rows of the frame pair (unit: blocks)")
     return {
-        "workload": cfg.name, "kernel": plan.launch_info()["kernel"], "avg_launch_us": t * 1e6,
+        "workload": cfg.name, "kernel": plan.launch_info()["kernel"], "avg_launch_us": t * 1e6, "launches": steps,
+        "cpu_baseline": cpu,
         "blocks_per_s": nby * nbx / t, "candidate_sads_per_s": nby * nbx * cfg.n_candidates / t,
         "achieved_hbm_gbs": alg_bytes / t / 1e9, "hbm_frac": alg_bytes / t / 1e9 / HBM_PEAK_GBS,
         "roofline": {"bound": "alu", "achieved": sad_lane_ops / t / 1e12, "peak": VALU_PEAK_TOPS,
@@ -155,7 +189,8 @@ def bench_sad(torch, mb, wl, cfg, steps, warmup):
     }
 
 
-def bench_conv(torch, mb, wl, cfg, steps, warmup, nsets, relu=False, pool=False, residual=False):
+def bench_conv(torch, mb, wl, cfg, steps, warmup, nsets, relu=False, pool=False, residual=False, packed=False):
+    import numpy as np
     x, w = wl.make_conv_inputs(cfg)
     x0 = torch.from_numpy(x).to("cuda:0")
     dw = torch.from_numpy(w).to("cuda:0")
@@ -171,7 +206,6 @@ def bench_conv(torch, mb, wl, cfg, steps, warmup, nsets, relu=False, pool=False,
     ys = [torch.empty((cfg.N, cfg.Cout, oh, ow), dtype=torch.float16, device="cuda:0") for _ in range(ns)]
     rs = None
     if residual:
-        import numpy as np
         plan = mb.merit_plan_conv2d_residual(cfg.N, cfg.Cin, cfg.H, cfg.W, cfg.Cout, cfg.kh, cfg.kw, cfg.sh, cfg.sw,
                                              cfg.ph, cfg.pw, int(relu))
         r0 = torch.from_numpy(np.random.default_rng(wl.BASE_SEED + 77).standard_normal(
@@ -188,16 +222,31 @@ def bench_conv(torch, mb, wl, cfg, steps, warmup, nsets, relu=False, pool=False,
         plan = make(cfg.N, cfg.Cin, cfg.H, cfg.W, cfg.Cout, cfg.kh, cfg.kw, cfg.sh, cfg.sw, cfg.ph, cfg.pw)
     if residual:
         calls = [mb.bind_conv2d_residual(plan, xs[i], dw, rs[i], ys[i]) for i in range(ns)]
+    elif packed:
+        # the weights regrouped once, outside the timed region (they do not change between calls)
+        pk = mb.merit_conv2d_pack_weights(plan, dw)
+        calls = [mb.bind_conv2d_packed(plan, xs[i], pk, ys[i]) for i in range(ns)]
     else:
         calls = [mb.bind_conv2d(plan, xs[i], dw, ys[i]) for i in range(ns)]
     wall, ev_ms = timed_region(torch, lambda i: calls[i % ns](), steps, warmup)
     t = ev_ms * 1e-3 / steps
     flops = 2.0 * cfg.N * cfg.Cout * cfg.OH * cfg.OW * cfg.Cin * cfg.kh * cfg.kw
+    # oracle sample: one image, the first 8 output channels
+    import oracle
+    xs1, ws8 = x[:1].copy(), w[:8].copy()
+    if pool:
+        ofn = lambda: oracle.conv2d_pool(xs1, ws8, (cfg.sh, cfg.sw), (cfg.ph, cfg.pw), relu=relu)
+    elif residual:
+        r1 = np.zeros((1, 8, cfg.OH, cfg.OW), np.float16)
+        ofn = lambda: oracle.conv2d_residual(xs1, ws8, r1, (cfg.sh, cfg.sw), (cfg.ph, cfg.pw), relu=relu)
+    else:
+        ofn = lambda: oracle.conv2d(xs1, ws8, (cfg.sh, cfg.sw), (cfg.ph, cfg.pw), relu=relu, dilation=(cfg.dh, cfg.dw))
+    cpu = oracle_rate(ofn, 8 * oh * ow, "one image, the first 8 output channels")
     return {
         "workload": cfg.name + (" + residual tensor" if residual else "") + (" + fused ReLU" if relu else "")
-        + (" + fused 3x3/s2/p1 max pooling" if pool else ""),
+        + (" + fused 3x3/s2/p1 max pooling" if pool else "") + (" (weights packed once)" if packed else ""),
         "kernel": plan.launch_info()["kernel"],
-        "avg_launch_us": t * 1e6,
+        "avg_launch_us": t * 1e6, "launches": steps, "cpu_baseline": cpu,
         "out_elems_per_s": cfg.N * cfg.Cout * oh * ow / t,
         "achieved_tflops": flops / t / 1e12, "mfma_frac": flops / t / 1e12 / MFMA_F16_PEAK_TFLOPS,
         "achieved_hbm_gbs": (in_bytes + out_bytes) / t / 1e9,
@@ -222,8 +271,13 @@ def bench_depthwise(torch, mb, wl, cfg, steps, warmup, nsets):
     calls = [mb.bind_conv2d_depthwise(plan, xs[i], dw, ys[i]) for i in range(ns)]
     wall, ev_ms = timed_region(torch, lambda i: calls[i % ns](), steps, warmup)
     t = ev_ms * 1e-3 / steps
+    import oracle
+    x1 = x[:1].copy()
+    cpu = oracle_rate(lambda: oracle.conv2d_depthwise(x1, w, (cfg.sh, cfg.sw), (cfg.ph, cfg.pw)),
+                      n_out // cfg.N, "one image")
     return {
-        "workload": cfg.name, "kernel": plan.launch_info()["kernel"], "avg_launch_us": t * 1e6,
+        "workload": cfg.name, "kernel": plan.launch_info()["kernel"], "avg_launch_us": t * 1e6, "launches": steps,
+        "cpu_baseline": cpu,
         "out_elems_per_s": n_out / t,
         "achieved_hbm_gbs": alg_bytes / t / 1e9, "hbm_frac": alg_bytes / t / 1e9 / HBM_PEAK_GBS,
         "rotating_sets": ns,
@@ -252,8 +306,12 @@ def bench_sepfilter(torch, mb, wl, cfg, steps, warmup, nsets):
     else:
         roof = {"bound": "hbm", "achieved": alg_bytes / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": alg_bytes / t / 1e9 / HBM_PEAK_GBS}
+    import oracle
+    band = x[:1, :256].copy()
+    cpu = oracle_rate(lambda: oracle.sepfilter(band, kx, ky), band.size, "the top 256 rows of one image")
     return {
-        "workload": cfg.name, "kernel": plan.launch_info()["kernel"], "avg_launch_us": t * 1e6,
+        "workload": cfg.name, "kernel": plan.launch_info()["kernel"], "avg_launch_us": t * 1e6, "launches": steps,
+        "cpu_baseline": cpu,
         "out_elems_per_s": cfg.N * cfg.H * cfg.W / t,
         "achieved_hbm_gbs": alg_bytes / t / 1e9, "hbm_frac": alg_bytes / t / 1e9 / HBM_PEAK_GBS,
         "achieved_fp32_tflops": 2 * fmas / t / 1e12,
@@ -271,18 +329,25 @@ def bench_bilateral(torch, mb, wl, cfg, steps, warmup):
     wall, ev_ms = timed_region(torch, lambda i: call(), steps, warmup)
     t = ev_ms * 1e-3 / steps
     taps = float(cfg.N * cfg.H * cfg.W * cfg.k * cfg.k)
-    # per tap: two fused multiply-adds (scaled difference, exponent), add, fused multiply-add and
-    # the exponential, a quarter-rate instruction counted as 4: 8 fp32 vector-ALU slots, priced
-    # against the published fp32 vector peak (157.3 TFLOP/s = 78.6 T slots/s)
-    slots = 8.0 * taps
-    peak = FP32_FMA_PEAK_TOPS
+    # Algorithmic work is taps (one weight and two accumulations per window element); the ceiling
+    # is what the chip's vector ALU could do per tap at the published rates whatever the
+    # instruction recipe: the definition needs one exponential (a transcendental: a quarter of
+    # the fp32 vector rate) and at least 3 plain fp32 operations (the squared difference times
+    # the constant, sum w, sum w*v, as fused multiply-adds), i.e. 4 + 3 = 7 issue slots of the
+    # 78.6 T slots/s (157.3 TFLOP/s fp32 vector = 256 CU x 128 lanes x 2.4 GHz): 11.2 T taps/s.
+    peak_taps = FP32_FMA_PEAK_TOPS / 7.0
     alg_bytes = 2 * x.nbytes
+    import oracle
+    band = x[:, :64].copy()
+    cpu = oracle_rate(lambda: oracle.bilateral(band, g, g, cfg.norm), band.size, "the top 64 rows of the image")
     return {
-        "workload": cfg.name, "kernel": plan.launch_info()["kernel"], "avg_launch_us": t * 1e6,
+        "workload": cfg.name, "kernel": plan.launch_info()["kernel"], "avg_launch_us": t * 1e6, "launches": steps,
+        "cpu_baseline": cpu,
         "out_elems_per_s": cfg.N * cfg.H * cfg.W / t, "taps_per_s": taps / t,
         "achieved_hbm_gbs": alg_bytes / t / 1e9, "hbm_frac": alg_bytes / t / 1e9 / HBM_PEAK_GBS,
-        "roofline": {"bound": "alu", "achieved": slots / t / 1e12, "peak": peak,
-                     "unit": "T slots/s (fp32 vector-ALU issue slots, exp2 = 4)", "frac": slots / t / 1e12 / peak},
+        "roofline": {"bound": "alu", "achieved": taps / t / 1e12, "peak": peak_taps,
+                     "unit": "T taps/s (ceiling: 1 exponential at a quarter rate + 3 fp32 operations per tap "
+                             "at 78.6 T vector operations/s)", "frac": taps / t / 1e12 / peak_taps},
     }
 
 
@@ -297,8 +362,13 @@ def bench_corr(torch, mb, wl, cfg, steps, warmup):
     n = 2 * cfg.search + 1
     alg_bytes = x1.nbytes + x2.nbytes + y.numel() * 2
     flops = 2.0 * cfg.N * cfg.H * cfg.W * n * n * cfg.C          # zero-padded positions included
+    import oracle
+    r1, r2 = x1[:, :, :8].copy(), x2[:, :, :8].copy()
+    cpu = oracle_rate(lambda: oracle.correlation(r1, r2, cfg.search, cfg.stride), cfg.N * 8 * cfg.W * n * n,
+                      "the top 8 rows of the feature maps (as a map of their own)")
     return {
-        "workload": cfg.name, "kernel": plan.launch_info()["kernel"], "avg_launch_us": t * 1e6,
+        "workload": cfg.name, "kernel": plan.launch_info()["kernel"], "avg_launch_us": t * 1e6, "launches": steps,
+        "cpu_baseline": cpu,
         "out_elems_per_s": y.numel() / t, "achieved_tflops": flops / t / 1e12,
         "achieved_hbm_gbs": alg_bytes / t / 1e9, "hbm_frac": alg_bytes / t / 1e9 / HBM_PEAK_GBS,
         "mfma_frac": flops / t / 1e12 / MFMA_F16_PEAK_TFLOPS,
@@ -330,12 +400,28 @@ def cpu_baseline(wl):
                       f"gcc -O2 + OpenMP over (n,c) planes"}
 
 
-# HBM-side bytes per pooling launch from two rocprofv3 --pmc runs of this file (FETCH_SIZE, then
-# WRITE_SIZE, KiB per dispatch), each scaled by what the same counter reads for a plain 256 MiB
-# device copy (--copy-calibration): FETCH_SIZE 26979.7 x 2.000, WRITE_SIZE 12544.2 x 1.000
-# (profiles/pool2d_stream_k3s2p1_max__pool_16x64x112x112_k3s2p1.txt).  A stored measurement:
-# counters cannot be read from inside this process.
-POOL_TRAFFIC_BYTES = 68.09e6
+def pool_traffic_from_profiles():
+    """HBM-side bytes per pooling launch: counters cannot be read from inside this process, so the
+    figure is the one the committed rocprofv3 summaries hold (two --pmc runs of this file,
+    FETCH_SIZE then WRITE_SIZE, each scaled by what the same counter reads for a plain 256 MiB
+    device copy).  Read from the files, mean of the max and the avg kernel; None if a summary
+    is missing or has no counter section (then `traffic` is null rather than stale)."""
+    import re
+    vals, names = [], []
+    for mode in ("max", "avg"):
+        name = f"pool2d_stream_k3s2p1_{mode}__pool_16x64x112x112_k3s2p1.txt"
+        path = os.path.join(ROOT, "profiles", name)
+        try:
+            text = open(path).read()
+        except OSError:
+            return None, None
+        m = re.search(r"scaled: read ([0-9.]+) MB \+ written ([0-9.]+) MB = ([0-9.]+) MB per launch", text)
+        if not m:
+            return None, None
+        vals.append(float(m.group(3)) * 1e6)
+        names.append("profiles/" + name)
+    stamp = time.strftime("%Y-%m-%d", time.gmtime(min(os.path.getmtime(os.path.join(ROOT, n)) for n in names)))
+    return sum(vals) / len(vals), {"files": names, "file_date": stamp}
 
 
 def main():
@@ -370,6 +456,7 @@ def main():
 
     pool = bench_pool(torch, mb, wl, args.steps, args.warmup, args.sets)
     value = pool["out_elems_per_step"] * args.steps / pool["wall_s"]
+    traffic, traffic_src = pool_traffic_from_profiles()
     result = {
         "metric": "pool2d output elems/s (max + avg, cache-cold)",
         "value": value,
@@ -387,32 +474,39 @@ def main():
                    "rotating_buffer_sets": args.sets, "kernel": pool["kernel"],
                    "grid": pool["launch"]["grid"][0], "lds_bytes": pool["launch"]["lds_bytes"]},
         "roofline": {"bound": "hbm", "achieved": pool["achieved_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": pool["achieved_gbs"] / HBM_PEAK_GBS, "traffic": POOL_TRAFFIC_BYTES,
-                     "traffic_unit": "bytes per launch",
+                     "frac": pool["achieved_gbs"] / HBM_PEAK_GBS, "traffic": traffic,
+                     "traffic_unit": "bytes per launch", "traffic_source": traffic_src,
+                     "time_base": "HIP events over the timed region / launches (includes the dispatch gap "
+                                  "between back-to-back launches; rocprofv3's per-kernel duration in profiles/ "
+                                  "is a few percent shorter, the wall-clock ms_per_step a few percent longer)",
                      "avg_launch_us": pool["avg_launch_us"], "alg_bytes_per_launch": pool["alg_bytes_per_launch"],
                      "cache_warm_avg_launch_us": pool["warm_avg_launch_us"]},
     }
+    global CPU_EXTRA
+    CPU_EXTRA = not args.no_cpu
     if not args.no_extra:
-        k = max(20, args.steps // 4)
-        w = max(5, args.warmup // 2)
+        k = max(100, args.steps // 2)        # launches per extra workload, whatever --steps says
+        w = max(10, args.warmup // 2)
+        kl = max(100, k // 2)                # the longer kernels
         result["extra"] = [
             bench_sad(torch, mb, wl, wl.CFG0_ME_SMALL, k, w),
             bench_conv(torch, mb, wl, wl.CFG2_CONV3, k, w, args.sets),
-            bench_sad(torch, mb, wl, wl.CFG3_ME_FHD, max(10, k // 2), w),
+            bench_sad(torch, mb, wl, wl.CFG3_ME_FHD, kl, w),
             bench_sad(torch, mb, wl, wl.CFG_ME_720P, k, w),
-            bench_sad(torch, mb, wl, wl.CFG_ME_1080P, max(10, k // 2), w),
+            bench_sad(torch, mb, wl, wl.CFG_ME_1080P, kl, w),
             bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets),
             bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets, relu=True),
             bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets, relu=True, pool=True),
             bench_conv(torch, mb, wl, wl.CFG2_CONV3, k, w, args.sets, relu=True, residual=True),
             bench_conv(torch, mb, wl, wl.CFG_DILATED, k, w, args.sets),
-            bench_conv(torch, mb, wl, wl.CFG_CONV256, max(10, k // 2), w, args.sets),
-            bench_conv(torch, mb, wl, wl.CFG_CONV11, max(10, k // 2), w, args.sets),
+            bench_conv(torch, mb, wl, wl.CFG_CONV256, kl, w, args.sets),
+            bench_conv(torch, mb, wl, wl.CFG_CONV256, kl, w, args.sets, packed=True),
+            bench_conv(torch, mb, wl, wl.CFG_CONV11, kl, w, args.sets),
             bench_corr(torch, mb, wl, wl.CFG_CORRELATION, k, w),
             bench_depthwise(torch, mb, wl, wl.CFG_DEPTHWISE, k, w, args.sets),
             bench_sepfilter(torch, mb, wl, wl.CFG_SEP_K3, k, w, args.sets),
-            bench_sepfilter(torch, mb, wl, wl.CFG_SEP_K30, max(10, k // 2), w, args.sets),
-            bench_bilateral(torch, mb, wl, wl.CFG_BILATERAL, max(10, k // 2), w),
+            bench_sepfilter(torch, mb, wl, wl.CFG_SEP_K30, kl, w, args.sets),
+            bench_bilateral(torch, mb, wl, wl.CFG_BILATERAL, kl, w),
         ]
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(wl)

@@ -361,7 +361,7 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
             weights_landed();                                  // (waits for the request too: once per item)
             __syncthreads();                                   // P
             for (int ck = 0; ck < npass; ++ck) {
-                if (ck + 1 < npass) {
+                if (MERIT_CHWS_EXPERIMENT != 1 && ck + 1 < npass) {
                     TIMED(tc, commit((ck + 1) & 1));
                     weights_direct(g.cg, ck + 1, (ck + 1) & 1);
                     if constexpr (XV) {
@@ -430,14 +430,20 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
             auto load = [&](int s, int slot) __attribute__((always_inline)) {
                 const int ky = T == 9 ? s / 3 : 0, kx = T == 9 ? s % 3 : 0;
 #pragma unroll
-                for (int cb = 0; cb < CHB; ++cb) a[slot][cb].u = wl[(s * NCB + cb) * 64];
+                for (int cb = 0; cb < CHB; ++cb) {
+                    if (MERIT_CHWS_EXPERIMENT == 4 && s > 0) a[slot][cb] = a[0][cb];
+                    else a[slot][cb].u = wl[(s * NCB + cb) * 64];
+                }
 #pragma unroll
-                for (int pb = 0; pb < PXB; ++pb) b[slot][pb].u = xl[xc[pb][kx] + ky * rowstep];
+                for (int pb = 0; pb < PXB; ++pb) {
+                    if ((MERIT_CHWS_EXPERIMENT == 3 || MERIT_CHWS_EXPERIMENT == 4) && s > 0) b[slot][pb] = b[0][pb];
+                    else b[slot][pb].u = xl[xc[pb][kx] + ky * rowstep];
+                }
             };
             // the reads of step s+1 are issued before the MFMAs of step s and stay there (left to
             // itself the scheduler sinks them to their first use, and the matrix core idles for
             // an LDS round trip per step)
-#if MERIT_CHWS_EXPERIMENT >= 2 && MERIT_CHWS_EXPERIMENT < 9
+#if MERIT_CHWS_EXPERIMENT == 2
             if (p.N > 0) { __syncthreads(); continue; }
 #endif
 #if MERIT_CHWS_EXPERIMENT == 9
