@@ -76,7 +76,9 @@ constexpr uint32_t OOB = 0x80000000u;   // a buffer offset past the end of every
 // T: taps of the window (9 = 3x3, 1 = 1x1).  XU = 1, 2: the input rows are staged in units of 8
 // channels x 8 pixels (W % 8 == 0), XU of them per moving thread and pass; XU = 0: in units of
 // 8 channels x 1 pixel, up to XS_MAX per thread.
-template <int PXB, int CHB, int WM, int WN, int T, int XU, bool PACKED>
+// NG: pairs of 8-channel groups per pass (1: 16 channels, 2: 32 -- small tiles, whose passes would
+// otherwise be shorter than a memory round trip).
+template <int PXB, int CHB, int WM, int WN, int T, int XU, bool PACKED, int NG = 1>
 __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvParams p, const uint16_t *__restrict__ x,
                                                             const uint16_t *__restrict__ w,
                                                             uint16_t *__restrict__ y)
@@ -85,11 +87,25 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
     static_assert(NMW == 4 || NMW == 8, "one or two multiplying wavefronts per SIMD");
     constexpr int NT = (NMW + 4) * 64;                   // threads per workgroup
     constexpr int TM = WM * PXB * 32, NCB = WN * CHB, TN = NCB * 32;
-    constexpr int WITEMS = T * NCB * 64;                 // 16-byte weight fragments per pass
-    constexpr int WU = (TN * 2 + 255) / 256;             // weight units (8 channels x T taps of one output channel) per moving thread
+    constexpr int WITEMS = NG * T * NCB * 64;            // 16-byte weight fragments per pass
+    constexpr int NGRP = 2 * NG;                         // 8-channel groups per pass
+    constexpr int WU = (TN * NGRP + 255) / 256;          // weight units (8 channels x T taps of one output channel) per moving thread
     constexpr int OP = TM / 2 + 2;                       // output staging: dwords per channel
     constexpr bool XV = XU > 0;
 
+    {
+        // The kernel-argument block (ConvParams and three pointers: six 64-byte lines) is read with
+        // scalar loads where the values are first needed; touching every line with the very first
+        // instructions fetches them side by side instead of one memory trip after the other.
+        static_assert(sizeof(ConvParams) + 3 * sizeof(void *) <= 6 * 64, "six lines of kernel arguments");
+        typedef const uint32_t __attribute__((address_space(4))) *kernarg_ptr;
+        kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
+        const uint32_t warm = ka[0] ^ ka[16] ^ ka[32] ^ ka[48] ^ ka[64] ^ ka[80];
+        asm volatile("" ::"s"(warm));
+    }
+#if MERIT_CHWS_EXPERIMENT == 9
+    const unsigned long long tentry = TS();
+#endif
     extern __shared__ __align__(16) uint8_t smem[];
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6, h = lane >> 5, c32 = lane & 31;
@@ -170,7 +186,7 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
         auto setup = [&](const Geom &g) __attribute__((always_inline)) {
             if constexpr (XV) {
                 const int W8 = p.W >> 3;
-                const int nu = 2 * p.RHa * W8;
+                const int nu = NGRP * p.RHa * W8;
 #pragma unroll
                 for (int k = 0; k < XU; ++k) {
                     // consecutive threads take consecutive staged rows (q = group * RHa + row) of one
@@ -179,19 +195,19 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
                     const int u = mt + 256 * k;
                     const int uc = min(u, nu - 1);
                     const int x8 = (int)fdiv((uint32_t)uc, p.div_r2);
-                    const int q = uc - x8 * 2 * p.RHa;
+                    const int q = uc - x8 * NGRP * p.RHa;
                     const int hh = (int)fdiv((uint32_t)q, p.div_rha);
                     const int r = q - hh * p.RHa;
                     const int gy = g.yA + r;
                     const bool ok = u < nu && r < g.RH && gy >= 0 && gy < p.H;
-                    x_hh[k] = u < nu ? hh : 2;                               // 2: no such unit, never written
+                    x_hh[k] = u < nu ? hh : NGRP;                            // NGRP: no such unit, never written
                     x_voff[k] = ok ? (uint32_t)(((hh * 8 * p.H + gy) * p.W + 8 * x8) * 2) : OOB;
 #pragma unroll
                     for (int px = 0; px < 8; ++px)
                         x_lds[k][px] = (q * p.pitch + p.padl + 8 * x8 + px) * 16;
                 }
             } else {
-                const int nu = 2 * p.RHa * p.W;
+                const int nu = NGRP * p.RHa * p.W;
 #pragma unroll
                 for (int k = 0; k < XS_MAX; ++k) {
                     const int u = mt + 256 * k;
@@ -202,7 +218,7 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
                     const int r = q - hh * p.RHa;
                     const int gy = g.yA + r;
                     const bool ok = u < nu && r < g.RH && gy >= 0 && gy < p.H;
-                    x_hh[k] = u < nu ? hh : 2;
+                    x_hh[k] = u < nu ? hh : NGRP;
                     x_voff[k] = ok ? (uint32_t)(((hh * 8 * p.H + gy) * p.W + xg) * 2) : OOB;
                     x_lds[k][0] = (q * p.pitch + p.padl + xg) * 16;
                 }
@@ -210,25 +226,27 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
             if constexpr (!PACKED) {
 #pragma unroll
                 for (int k = 0; k < WU; ++k) {
+                    // unit = (output channel, 8-channel group of the pass); group 2*gp + h belongs to
+                    // lane half h of step block gp
                     const int u = mt + 256 * k;
-                    const int col = u >> 1, hh = u & 1;
+                    const int col = u / NGRP, hh = u % NGRP;
                     const int co = g.cg * TN + col;
-                    const bool ok = u < TN * 2 && co < p.Cout;
-                    w_hh[k] = u < TN * 2 ? hh : 2;
+                    const bool ok = u < TN * NGRP && co < p.Cout;
+                    w_hh[k] = u < TN * NGRP ? hh : NGRP;
                     w_voff[k] = ok ? (uint32_t)(((co * p.Cin + hh * 8) * T) * 2) : OOB;
-                    w_lds[k] = (((col >> 5) * 2 + hh) * 32 + ((col & 31) ^ (hh * 8))) * 16;
+                    w_lds[k] = ((((hh >> 1) * T * NCB + (col >> 5)) * 2 + (hh & 1)) * 32 + ((col & 31) ^ ((hh & 1) * 8))) * 16;
                 }
             }
         };
 
         // request the input rows (and, unless packed, the weights) of pass ck into the registers
         auto request = [&](const Geom &g, int ck) __attribute__((always_inline)) {
-            const bool half = (ck * 2 + 1) * 8 + 8 > p.Cin;      // the pass's second channel group is padding
-            const uint32_t xbase = ((uint32_t)g.n * (uint32_t)p.Cin + (uint32_t)ck * 16u) * chbytes;
+            const int live = (p.Cin >> 3) - ck * NGRP;          // groups of this pass that exist (the rest: padding)
+            const uint32_t xbase = ((uint32_t)g.n * (uint32_t)p.Cin + (uint32_t)(ck * NGRP * 8)) * chbytes;
 #pragma unroll
             for (int k = 0; k < NXU; ++k) {
                 if (!XV && k >= p.xu) break;
-                const uint32_t voff = (half && x_hh[k] == 1) ? OOB : x_voff[k];
+                const uint32_t voff = x_hh[k] >= live ? OOB : x_voff[k];
 #pragma unroll
                 for (int c = 0; c < 8; ++c) {
                     if constexpr (XV) {
@@ -240,10 +258,10 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
                 }
             }
             if constexpr (!PACKED) {
-                const uint32_t wbase = (uint32_t)ck * (uint32_t)(16 * T * 2);
+                const uint32_t wbase = (uint32_t)ck * (uint32_t)(NGRP * 8 * T * 2);
 #pragma unroll
                 for (int k = 0; k < WU; ++k) {
-                    const uint32_t voff = (half && w_hh[k] == 1) ? OOB : w_voff[k];
+                    const uint32_t voff = w_hh[k] >= live ? OOB : w_voff[k];
 #pragma unroll
                     for (int i = 0; i < T; ++i) {
                         const uint32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rw, voff + 16 * i, wbase, 0);
@@ -259,7 +277,7 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
 #pragma unroll
             for (int k = 0; k < NXU; ++k) {
                 if (!XV && k >= p.xu) break;
-                if (x_hh[k] < 2) {
+                if (x_hh[k] < NGRP) {
                     if constexpr (XV) {
 #pragma unroll
                         for (int px = 0; px < 8; ++px) {
@@ -285,7 +303,7 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
                 uint8_t *wl = smem + b * p.lds_buf_bytes;
 #pragma unroll
                 for (int k = 0; k < WU; ++k) {
-                    if (w_hh[k] < 2) {
+                    if (w_hh[k] < NGRP) {
 #pragma unroll
                         for (int t = 0; t < T; ++t) {
                             uint32_t d[4];
@@ -330,7 +348,7 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
         // the padding columns of the staged rows, both buffers (the output staging overwrites them)
         auto zero_pads = [&]() __attribute__((always_inline)) {
             const int npad = p.pitch - p.W;
-            const int per = 2 * p.RHa * npad;
+            const int per = NGRP * p.RHa * npad;
             for (int u = mt; u < 2 * per; u += 256) {
                 const int b = u >= per ? 1 : 0;
                 const int v = u - b * per;
@@ -421,6 +439,9 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[cb][pb][r] = 0.0f;
         __syncthreads();                                       // P
+#if MERIT_CHWS_EXPERIMENT == 9
+        const unsigned long long tfill = TS() - tentry;
+#endif
 
         for (int ck = 0; ck < npass; ++ck) {
             const uint4 *wl = wbuf(ck & 1) + (wn * CHB * 2 + h) * 32 + (c32 ^ (h * 8));
@@ -428,7 +449,9 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
             const int rowstep = p.dh * p.pitch;
             Frag a[2][CHB], b[2][PXB];
             auto load = [&](int s, int slot) __attribute__((always_inline)) {
-                const int ky = T == 9 ? s / 3 : 0, kx = T == 9 ? s % 3 : 0;
+                const int gp = s / T, tap = s % T;               // step = (pair of channel groups, tap)
+                const int ky = T == 9 ? tap / 3 : 0, kx = T == 9 ? tap % 3 : 0;
+                const int xgrp = gp * 2 * p.RHa * p.pitch;
 #pragma unroll
                 for (int cb = 0; cb < CHB; ++cb) {
                     if (MERIT_CHWS_EXPERIMENT == 4 && s > 0) a[slot][cb] = a[0][cb];
@@ -437,7 +460,7 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
 #pragma unroll
                 for (int pb = 0; pb < PXB; ++pb) {
                     if ((MERIT_CHWS_EXPERIMENT == 3 || MERIT_CHWS_EXPERIMENT == 4) && s > 0) b[slot][pb] = b[0][pb];
-                    else b[slot][pb].u = xl[xc[pb][kx] + ky * rowstep];
+                    else b[slot][pb].u = xl[xc[pb][kx] + ky * rowstep + xgrp];
                 }
             };
             // the reads of step s+1 are issued before the MFMAs of step s and stay there (left to
@@ -451,8 +474,8 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
 #endif
             load(0, 0);
 #pragma unroll
-            for (int s = 0; s < T; ++s) {
-                if (s + 1 < T) load(s + 1, (s + 1) & 1);
+            for (int s = 0; s < NG * T; ++s) {
+                if (s + 1 < NG * T) load(s + 1, (s + 1) & 1);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int cb = 0; cb < CHB; ++cb)
@@ -499,9 +522,17 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
                         *reinterpret_cast<uint2 *>(outl + ch * OP + (wm * PXB + pb) * 16 + 4 * q + 2 * h) = v;
                     }
         }
+#if MERIT_CHWS_EXPERIMENT == 9
+        const unsigned long long te0 = TS();
+#endif
         __syncthreads();                                       // E1
         store_out(g);
         __syncthreads();                                       // E2
+#if MERIT_CHWS_EXPERIMENT == 9
+        if (blockIdx.x == 7 && tid == 0)
+            printf("mfma item: entry->first pass %llu, acc->LDS done at %llu, stores issued at %llu (x10 ns since entry)\n",
+                   tfill, te0 - tentry, TS() - tentry);
+#endif
     }
 #if MERIT_CHWS_EXPERIMENT == 9
     if (blockIdx.x == 7 && tid == 0)
@@ -512,21 +543,22 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
 // Rewrites w[Cout][Cin][kh][kw] into the order the passes of merit_conv2d_chws read it: for every
 // channel block and pass the T * NCB * 64 fragments of 8 input channels in their LDS places.
 // One thread per 16-byte fragment.
-__global__ __launch_bounds__(256) void merit_conv2d_pack_w(ConvParams p, int T, int NCB, const uint16_t *__restrict__ w,
+__global__ __launch_bounds__(256) void merit_conv2d_pack_w(ConvParams p, int T, int NCB, int NG, const uint16_t *__restrict__ w,
                                                           uint4 *__restrict__ out, long long total)
 {
     const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
     if (i >= total) return;
-    const int witems = T * NCB * 64;
+    const int witems = NG * T * NCB * 64;
     const long long blk = i / witems;                      // (channel block, pass)
     int r = (int)(i - blk * witems);
     const int cg = (int)(blk / p.nchunks), ck = (int)(blk - (long long)cg * p.nchunks);
-    const int t = r / (NCB * 64);
-    r -= t * NCB * 64;
+    const int s = r / (NCB * 64);                          // step = (pair of channel groups, tap)
+    r -= s * NCB * 64;
+    const int gp = s / T, t = s - gp * T;
     const int cb = r >> 6, hh = (r >> 5) & 1, slot = r & 31;
     const int cc = slot ^ (hh * 8);
     const int co = (cg * NCB + cb) * 32 + cc;
-    const int ci0 = (ck * 2 + hh) * 8;
+    const int ci0 = ((ck * NG + gp) * 2 + hh) * 8;
     uint32_t d[4] = {0, 0, 0, 0};
     if (co < p.Cout) {
 #pragma unroll
@@ -550,7 +582,7 @@ hipError_t launch_one(K kernel, const ConvParams &p, const void *x, const void *
     return hipGetLastError();
 }
 
-template <int PXB, int CHB, int WM, int WN>
+template <int PXB, int CHB, int WM, int WN, int NG = 1>
 hipError_t launch_tile(const ConvParams &p, const void *x, const void *w, void *y, hipStream_t s, uint32_t grid,
                        bool packed)
 {
@@ -558,8 +590,8 @@ hipError_t launch_tile(const ConvParams &p, const void *x, const void *w, void *
     const int T = p.kh * p.kw;
 #define MERIT_CHWS(Tv, XUv)                                                                             \
     do {                                                                                                \
-        if (packed) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, Tv, XUv, true>, p, x, w, y, s, grid);  \
-        return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, Tv, XUv, false>, p, x, w, y, s, grid);    \
+        if (packed) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, Tv, XUv, true, NG>, p, x, w, y, s, grid);  \
+        return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, Tv, XUv, false, NG>, p, x, w, y, s, grid);    \
     } while (0)
     if (T == 9 && xu == 1) MERIT_CHWS(9, 1);
     if (T == 9 && xu == 2) MERIT_CHWS(9, 2);
@@ -581,15 +613,17 @@ hipError_t launch_conv2d_chws(const ConvParams &p, const void *x, const void *w,
     const uint32_t grid = (uint32_t)(nitems < slots ? nitems : slots);
     if (p.CB == 4 && p.NW == 12) return launch_tile<2, 2, 4, 2>(p, x, w, y, s, grid, packed);   // 256 x 128, 8 x (64 x 64)
     if (p.CB == 4) return launch_tile<4, 2, 2, 2>(p, x, w, y, s, grid, packed);     // 256 pixels x 128 channels, 4 x (128 x 64)
+    if (p.TM == 128) return launch_tile<1, 2, 4, 1, 2>(p, x, w, y, s, grid, packed);   // 128 pixels x 64 channels, 4 x (32 x 64), 32 channels per pass
     return launch_tile<2, 2, 4, 1>(p, x, w, y, s, grid, packed);                    // 256 pixels x 64 channels, 4 x (64 x 64)
 }
 
 hipError_t launch_conv2d_pack_weights(const ConvParams &p, const void *w, void *packed, hipStream_t s)
 {
     const int T = p.kh * p.kw;
-    const long long total = (long long)p.co_groups * p.nchunks * T * p.CB * 64;
+    const int NG = p.nchi / 2;
+    const long long total = (long long)p.co_groups * p.nchunks * NG * T * p.CB * 64;
     if (total == 0) return hipSuccess;
-    hipLaunchKernelGGL(merit_conv2d_pack_w, dim3((uint32_t)((total + 255) / 256)), dim3(256), 0, s, p, T, p.CB,
+    hipLaunchKernelGGL(merit_conv2d_pack_w, dim3((uint32_t)((total + 255) / 256)), dim3(256), 0, s, p, T, p.CB, NG,
                        reinterpret_cast<const uint16_t *>(w), reinterpret_cast<uint4 *>(packed), total);
     return hipGetLastError();
 }

@@ -603,20 +603,21 @@ merit_status derive_conv(merit_plan *pl)
     // Wave-specialised multi-pass kernel (conv2d_chws.hip): 256-pixel tiles x `cb` 32-channel blocks
     // (4 or 2), 16 input channels per pass through two LDS buffers, 3x3 or 1x1 windows on a multiple
     // of 8 input channels.
-    auto try_chws = [&](int cb, bool forced, int nw = 8) -> bool {
+    auto try_chws = [&](int cb, bool forced, int nw = 8, int tm = 256) -> bool {
         if (!((kh == 3 && kw == 3) || (kh == 1 && kw == 1))) return false;
         // its tiles are 256 pixels of one image: small images (13x13, 7x7) would leave a third
         // and more of every tile empty and stay with the 128-pixel tiles of the plain kernels
-        if (!forced && 4 * ohw < 3 * cdiv(ohw, 256) * 256) return false;
+        if (!forced && 4 * ohw < 3 * cdiv(ohw, tm) * tm) return false;
         if (Cin % 8 != 0 || Cin < 16 || pool || p.residual || ncb < 2) return false;
         if (cb != 2 && cb != 4) return false;
         ConvParams q = p;
         q.variant = CONV_CHWS;
         q.CB = cb;
         q.co_groups = (int)cdiv(ncb, cb);
-        q.PXW = (cb == 4 && nw == 8) ? 4 : 2;    // 32-pixel blocks per multiplying wavefront
+        q.PXW = tm == 128 ? 1 : ((cb == 4 && nw == 8) ? 4 : 2);    // 32-pixel blocks per multiplying wavefront
         q.NW = nw;                               // 8: four multiplying + four moving wavefronts; 12: eight + four
-        q.TM = 256;
+        q.TM = tm;                               // 256 pixels, or 128 (64-channel tiles on 8 wavefronts only)
+        if (tm != 256 && !(tm == 128 && cb == 2 && nw == 8)) return false;
         q.tiles_per_image = (int)cdiv(ohw, q.TM);
         q.rows_out_max = (int)((q.TM + OW - 2) / OW + 1);
         if (q.rows_out_max > OH) q.rows_out_max = (int)OH;
@@ -629,11 +630,14 @@ merit_status derive_conv(merit_plan *pl)
         if (reach > pitch) pitch = reach;
         pitch |= 1;                               // odd: staged rows start in different LDS bank groups
         q.pitch = (int)pitch;
-        q.nchi = 2;
-        q.nchunks = (int)cdiv(Cin, 16);
-        q.S = (int)(kh * kw);
-        const int64_t w_bytes = kh * kw * cb * 64 * 16;
-        const int64_t x_bytes = 2 * (int64_t)q.RHa * pitch * 16;
+        // 16 input channels per pass; 32 with the small tile, whose passes would otherwise be
+        // shorter than the memory round trip that brings the next one
+        const int64_t ng = tm == 128 ? 2 : 1;
+        q.nchi = (int)(2 * ng);
+        q.nchunks = (int)cdiv(Cin, 16 * ng);
+        q.S = (int)(ng * kh * kw);
+        const int64_t w_bytes = ng * kh * kw * cb * 64 * 16;
+        const int64_t x_bytes = 2 * ng * (int64_t)q.RHa * pitch * 16;
         const int64_t o_bytes = (int64_t)cb * 32 * (q.TM / 2 + 2) * 4;
         const int64_t total = 2 * (w_bytes + x_bytes) > o_bytes ? 2 * (w_bytes + x_bytes) : o_bytes;
         if (total > LDS_LIMIT) return false;
@@ -641,19 +645,19 @@ merit_status derive_conv(merit_plan *pl)
         q.lds_o_offset = 0; q.lds_o_bytes = (int)o_bytes; q.lds_total = (int)total;
         // staging units per moving thread and pass: 8 channels x 8 pixels (two at most), or x 1 pixel (four)
         if ((W % 8) == 0) {
-            const int64_t nu = 2 * (int64_t)q.RHa * (W / 8);
-            if (nu > 2 * 256 || !fastdiv_ok(nu, 2 * (int64_t)q.RHa)) return false;
+            const int64_t nu = 2 * ng * (int64_t)q.RHa * (W / 8);
+            if (nu > 2 * 256 || !fastdiv_ok(nu, 2 * ng * (int64_t)q.RHa)) return false;
             q.xu = (int)cdiv(nu, 256);
             q.div_w8 = make_fastdiv((uint32_t)(W / 8));
-            q.div_r2 = make_fastdiv((uint32_t)(2 * q.RHa));
+            q.div_r2 = make_fastdiv((uint32_t)(2 * ng * q.RHa));
         } else {
-            const int64_t nu = 2 * (int64_t)q.RHa * W;
+            const int64_t nu = 2 * ng * (int64_t)q.RHa * W;
             if (nu > 4 * 256 || !fastdiv_ok(nu, W)) return false;
             q.xu = (int)cdiv(nu, 256);
             q.div_w = make_fastdiv((uint32_t)W);
         }
         const int64_t nitems = N * q.tiles_per_image * q.co_groups;
-        if (nitems >= (1ll << 30) || !fastdiv_ok(nitems + 256, q.co_groups) || !fastdiv_ok(2 * (int64_t)q.RHa, q.RHa) ||
+        if (nitems >= (1ll << 30) || !fastdiv_ok(nitems + 256, q.co_groups) || !fastdiv_ok(2 * ng * (int64_t)q.RHa, q.RHa) ||
             !fastdiv_ok(ohw, OW) || !fastdiv_ok(N * q.tiles_per_image, q.tiles_per_image))
             return false;
         if (N * Cin * H * W >= (1ll << 31) || N * Cout * ohw >= (1ll << 31)) return false;
@@ -702,7 +706,7 @@ merit_status derive_conv(merit_plan *pl)
             if (!ok) return MERIT_ERR_UNSUPPORTED;
         } else if (nw == 8 && Cin >= 8) {
             // 4 multiplying + 4 moving wavefronts on many channels: 256 pixels x 128 (4 x 32) or 64 channels
-            ok = try_chws(ppw == 128 ? 4 : (ppw == 64 ? 2 : 0), true);
+            ok = ppw == 32 ? try_chws(2, true, 8, 128) : try_chws(ppw == 128 ? 4 : 2, true);
             if (!ok) return MERIT_ERR_UNSUPPORTED;
         } else if (ppw == 128) {
             return MERIT_ERR_UNSUPPORTED;
@@ -721,13 +725,19 @@ merit_status derive_conv(merit_plan *pl)
         if (!ok)
             ok = want_big ? (try_variant(CONV_CHBLOCK, 2, 4) || try_variant(CONV_CHBLOCK, 1, 4))
                           : (try_variant(CONV_CHBLOCK, 1, 4) || try_variant(CONV_CHBLOCK, 2, 4));
-        // layers whose channels do not fit LDS at once (they would go through the plain multi-pass
-        // kernel): the wave-specialised one, 128 output channels per workgroup when there are that many
-        // (3x3 only by default: a 1x1 pass is one MFMA step per 16 staged channels, which the plain
-        // multi-pass kernel's larger passes serve better; 12 wavefronts when the tile has 128 channels)
-        if ((!ok || p.nchunks > 1) && kh == 3 &&
-            ((ncb >= 4 && try_chws(4, false, 12)) || try_chws(2, false)))
-            ok = true;
+        // 3x3 layers on at least 32 input channels (a multiple of 8) and at least 64 output channels:
+        // the wave-specialised multi-pass kernel.  Its three tilings, largest first: 256 pixels x 128
+        // channels on 12 wavefronts, 256 x 64 and 128 x 64 (32 channels per pass) on 8.  The largest
+        // one that still gives (nearly) every compute unit a workgroup is taken -- the larger the
+        // tile, the less is staged per multiply-add -- else the smallest.  (1x1 layers stay with the
+        // plain kernels: a 1x1 pass is one MFMA step per 16 staged channels.)
+        if (kh == 3 && kw == 3 && Cin >= 32 && (Cin % 8) == 0 && ncb >= 2) {
+            const int64_t i4 = N * cdiv(ohw, 256) * cdiv(ncb, 4), i2 = N * cdiv(ohw, 256) * cdiv(ncb, 2);
+            const bool took = (ncb >= 4 && i4 >= 192 && try_chws(4, false, 12)) || (i2 >= 192 && try_chws(2, false, 8, 256)) ||
+                              try_chws(2, false, 8, 128) || try_chws(2, false, 8, 256) ||
+                              (ncb >= 4 && try_chws(4, false, 12));
+            if (took) ok = true;
+        }
     }
     if (!ok) {
         // neither MFMA kernel holds this shape's operands in LDS: the one-element-per-thread

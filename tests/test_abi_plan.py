@@ -139,7 +139,10 @@ def test_residual_plan():
     plan.set_tile((0, 0, 4, 64))
     assert plan.launch_info()["kernel"] == "merit_conv2d_planar"
     res = mb.merit_plan_conv2d_residual(8, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1, 1)
-    assert res.launch_info() == mb.merit_plan_conv2d(8, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1).launch_info()
+    assert res.launch_info()["kernel"] == "merit_conv2d_chblock"       # the multi-pass kernels that take the added tensor
+    plain = mb.merit_plan_conv2d(8, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1)
+    plain.set_tile((0, 0, 4, 32))
+    assert res.launch_info() == plain.launch_info()
     assert mb.merit_plan_create(res.desc()).desc().op == mb.MERIT_OP_CONV_DOT_ADD_RELU
 
 
@@ -397,9 +400,13 @@ def test_null_and_misuse_without_gpu():
 
 def test_conv_variant_selection():
     assert mb.merit_plan_conv2d(32, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3).launch_info()["kernel"].startswith("merit_conv2d_planar")
-    assert mb.merit_plan_conv2d(8, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1).launch_info()["kernel"] == "merit_conv2d_chblock"
+    # the 3x3 workload: the wave-specialised kernel on 128-pixel tiles (200 workgroups), 32 channels per pass
     li = mb.merit_plan_conv2d(8, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1).launch_info()
+    assert li["kernel"] == "merit_conv2d_chws" and li["grid"][0] == 200 and li["block"][0] == 512
     assert li["lds_bytes"] <= 160 * 1024
+    # fewer than 32 input channels, or fewer than 64 output channels: the single-pass channel-block kernel
+    assert mb.merit_plan_conv2d(8, 16, 56, 56, 64, 3, 3, 1, 1, 1, 1).launch_info()["kernel"] == "merit_conv2d_chblock"
+    assert mb.merit_plan_conv2d(8, 64, 56, 56, 32, 3, 3, 1, 1, 1, 1).launch_info()["kernel"] == "merit_conv2d_chblock"
 
 
 def test_plans_for_extreme_shapes_are_sane_or_refused():

@@ -59,6 +59,12 @@ CHWS_CASES = [
     ((2, 16, 40, 40, 64, 3, 3, 1, 1, 1, 1), (1, 1), 0, (0, 0, 8, 64)),      # a single pass per item
     ((2, 48, 27, 27, 256, 3, 3, 1, 1, 0, 0), (1, 1), 1, (0, 0, 8, 128)),    # no padding, odd width, three passes
     ((1, 64, 9, 10, 64, 1, 1, 2, 2, 0, 0), (1, 1), 0, (0, 0, 8, 64)),       # 1x1 stride 2, tiny image
+    # 128-pixel tiles, 32 channels per pass (the 3x3 workload's shape class)
+    ((2, 64, 28, 56, 64, 3, 3, 1, 1, 1, 1), (1, 1), 0, (0, 0, 8, 32)),      # two passes
+    ((3, 80, 17, 24, 40, 3, 3, 1, 1, 1, 1), (1, 1), 1, (0, 0, 8, 32)),      # last pass half empty, ragged channel block
+    ((1, 40, 13, 11, 64, 3, 3, 2, 2, 1, 1), (1, 1), 0, (0, 0, 8, 32)),      # one-pixel input units, stride 2, one group of padding
+    ((300, 32, 12, 16, 64, 3, 3, 1, 1, 1, 1), (1, 1), 0, (0, 0, 8, 32)),    # a single pass per item, several items per workgroup
+    ((1, 96, 20, 40, 64, 1, 1, 1, 1, 0, 0), (1, 1), 0, (0, 0, 8, 32)),      # 1x1
 ]
 
 

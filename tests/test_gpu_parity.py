@@ -536,7 +536,8 @@ RELU_CASES = [
     ((300, 3, 32, 32, 64, 7, 7, 2, 2, 3, 3), (0, 0, 8, 64), "merit_conv2d_planar_ws"),
     ((2, 3, 17, 19, 40, 7, 7, 2, 2, 3, 3), None, "merit_conv2d_planar"),
     ((1, 16, 12, 16, 32, 3, 3, 1, 1, 1, 1), None, "merit_conv2d_chblock"),
-    ((2, 64, 28, 28, 64, 3, 3, 1, 1, 1, 1), None, "merit_conv2d_chblock"),
+    ((2, 64, 28, 28, 64, 3, 3, 1, 1, 1, 1), (0, 0, 4, 32), "merit_conv2d_chblock"),
+    ((2, 64, 28, 28, 64, 3, 3, 1, 1, 1, 1), None, "merit_conv2d_chws"),
 ]
 
 
