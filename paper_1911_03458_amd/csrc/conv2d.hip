@@ -36,6 +36,7 @@ typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 typedef uint32_t uint32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t uint32x2 __attribute__((ext_vector_type(2)));
 
 union Frag {
     uint4 u;
@@ -236,10 +237,12 @@ __device__ __forceinline__ void store_tile(const ConvParams &p, floatx16 (&acc)[
 // planar variant
 // LDS: [ weights: CB*G2*32 x 16 B ][ 32 B of zeros ][ input: Cin*RHa*pitch halves ]
 //      [ output staging ]
-// A K-group g = (ci, ky) is one window row: its kw taps occupy slots
-// front .. front+kw-1 of an 8-slot fragment (front = 0 or 1 is chosen so that the
-// fragment starts on an even staged column whenever the column stride is even);
-// unused slots are cleared in the data and zero in the weights.
+// A K-group is one window row (ci, ky), or half of one: its kw taps occupy slots
+// front .. front+kw-1 of one 8-slot fragment (kw + front <= 8) or of two adjacent ones
+// (up to 16: g = 2 (ci, ky) + part, so lanes 0-31 of a step multiply slots 0-7 and lanes
+// 32-63 slots 8-15 of the same row).  front = 0 or 1 is chosen so that the fragment starts
+// on an even staged column whenever the column stride is even; unused slots are cleared
+// in the data and zero in the weights.
 // ---------------------------------------------------------------------------
 template <int CB, int PXW, int NW, bool ALIGNED, bool PREFETCH>
 __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, const uint16_t *__restrict__ x,
@@ -261,53 +264,16 @@ __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, 
     const int P8 = p.pitch >> 3;
     const int ohw = p.OH * p.OW;
 
-    // ---- weights, once per workgroup: unit = (local output channel, group) ----
-    {
-        // batches of WU units: all global loads of a batch are issued before the first LDS
-        // write, so a batch costs one memory round trip
-        constexpr int WU = 6;
-        const int units = CB * 32 * p.G2;
-        for (int u0 = tid; u0 < units; u0 += NT * WU) {
-            uint16_t hv[WU][8];
-            bool ok[WU];
-#pragma unroll
-            for (int k = 0; k < WU; ++k) {
-                const int u = min(u0 + NT * k, units - 1);
-                const int col = (int)fdiv((uint32_t)u, p.div_g2);
-                const int g = u - col * p.G2;
-                const int co = co_base + col;
-                ok[k] = co < p.Cout && g < p.G;
-                const uint16_t *src = w + (ok[k] ? ((size_t)co * p.G + g) * p.kw : 0);
-#pragma unroll
-                for (int t = 0; t < 8; ++t) hv[k][t] = (t < p.kw) ? src[t] : (uint16_t)0;
-            }
-#pragma unroll
-            for (int k = 0; k < WU; ++k) {
-                const int u = u0 + NT * k;
-                if (u >= units) break;
-                const int col = (int)fdiv((uint32_t)u, p.div_g2);
-                const int g = u - col * p.G2;
-                uint32_t d[4] = {0, 0, 0, 0};
-#pragma unroll
-                for (int t = 0; t < 8; ++t)
-                    if (t < p.kw && ok[k]) d[t >> 1] |= (uint32_t)hv[k][t] << (16 * (t & 1));
-                if (p.front) {                             // taps start at slot 1 (kw <= 7)
-                    d[3] = (d[3] << 16) | (d[2] >> 16);
-                    d[2] = (d[2] << 16) | (d[1] >> 16);
-                    d[1] = (d[1] << 16) | (d[0] >> 16);
-                    d[0] = d[0] << 16;
-                }
-                wl[((col >> 5) * p.G2 + g) * 32 + (col & 31)] = make_uint4(d[0], d[1], d[2], d[3]);
-            }
-        }
-        if (tid < 8) reinterpret_cast<uint32_t *>(xz)[tid] = 0;
-    }
+    // a window row wider than one fragment is two groups (slots 0-7 and 8-15)
+    const bool two_parts = p.front + p.kw > 8;
+    const int wrows = p.Cin * p.kh;                       // window rows per output channel
 
-    // masks that clear the slots outside [front, front+kw) of a fragment
+    // masks that clear the slots outside [front, front+kw) of a fragment (of this lane's half
+    // of the window row when it takes two)
     uint32_t kmask[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        const int s0 = 2 * q - p.front, s1 = 2 * q + 1 - p.front;
+        const int s0 = (two_parts ? h * 8 : 0) + 2 * q - p.front, s1 = s0 + 1;
         kmask[q] = ((s0 >= 0 && s0 < p.kw) ? 0x0000ffffu : 0u) | ((s1 >= 0 && s1 < p.kw) ? 0xffff0000u : 0u);
     }
 
@@ -338,15 +304,17 @@ __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, 
     // tile the loads of the NEXT tile are issued before the current tile's results are
     // stored, so their latency hides behind the epilogue.
     const int nu = p.Cin * p.RHa * P8;
-    const bool vec_ok = (p.W & 7) == 0;
-    constexpr int XU = 5;
-    constexpr bool prefetchable = PREFETCH;               // host: W % 8 == 0 and nu <= NT * XU
-    uint4 pre[XU];
-    bool pre_in[XU];
+    const bool vec8 = (p.W & 7) == 0;                     // a unit is one 16-byte load,
+    const bool vec_ok = (p.W & 3) == 0;                   // or two of 8 bytes (rows are 8-byte aligned)
+    // units per thread and batch: 5 when a batch stays in registers across the K loop, else 10 (a
+    // batch is one memory round trip)
+    constexpr int XU = PREFETCH ? 5 : 10;
+    constexpr bool prefetchable = PREFETCH;               // host: W % 8 == 0 and nu <= 5 NT
+    uint32x4 pre[XU];
     // unit u = u0 + NT k -> (channel, staged row, column): independent of the tile, so the
     // prefetch path decomposes once; u_off = (ci*H + r)*W + x relative to row yA of the image
     int u_off[XU], u_row[XU];
-    bool u_colok[XU];
+    bool u_colok[XU], u_col2ok[XU];
     auto decompose = [&](int u0) {
 #pragma unroll
         for (int k = 0; k < XU; ++k) {
@@ -359,25 +327,38 @@ __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, 
             const int xg0 = 8 * c8 - p.padl;
             u_row[k] = r;
             u_colok[k] = u < nu && xg0 >= 0 && xg0 < p.W;
+            u_col2ok[k] = xg0 + 4 < p.W;                  // second half of the unit (W % 8 == 4: the row may end between)
             u_off[k] = (ci * p.H + r) * p.W + xg0;
         }
     };
+    // The image is read through a buffer descriptor: an offset of 2^31 is past its end, so such
+    // a load returns zeros -- padding and rows outside the image need no select on the data (a
+    // select right after a load would make the load wait where it is issued), and the two
+    // widths stay two different instructions (as plain loads behind a uniform branch the
+    // compiler merged them into four 4-byte loads per unit).
     auto issue_loads = [&](const Geom &t) {
-        const uint16_t *img = x + (size_t)t.n * p.Cin * p.H * p.W;
+        const __amdgpu_buffer_rsrc_t rimg = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t *>(x + (size_t)t.n * p.Cin * p.H * p.W), 0, p.Cin * p.H * p.W * 2, 0x00020000);
         const int yaw = t.yA * p.W;
 #pragma unroll
         for (int k = 0; k < XU; ++k) {
             const int gy = t.yA + u_row[k];
-            pre_in[k] = u_colok[k] && u_row[k] < t.RH && gy >= 0 && gy < p.H;
-            const int off = pre_in[k] ? u_off[k] + yaw : 0;           // >= 0 whenever it is used
-            pre[k] = *reinterpret_cast<const uint4 *>(img + off);
+            const bool in = u_colok[k] && u_row[k] < t.RH && gy >= 0 && gy < p.H;
+            const uint32_t off = in ? (uint32_t)(u_off[k] + yaw) * 2u : 0x80000000u;
+            if (PREFETCH || vec8) {
+                pre[k] = __builtin_amdgcn_raw_buffer_load_b128(rimg, off, 0, 0);
+            } else {
+                const uint32x2 a = __builtin_amdgcn_raw_buffer_load_b64(rimg, off, 0, 0);
+                const uint32x2 b = __builtin_amdgcn_raw_buffer_load_b64(rimg, (in && u_col2ok[k]) ? off + 8u : 0x80000000u, 0, 0);
+                pre[k] = uint32x4{a.x, a.y, b.x, b.y};
+            }
         }
     };
     auto commit_loads = [&](int u0) {
 #pragma unroll
         for (int k = 0; k < XU; ++k) {
             const int u = u0 + NT * k;
-            if (u < nu) reinterpret_cast<uint4 *>(xl)[u] = pre_in[k] ? pre[k] : make_uint4(0, 0, 0, 0);
+            if (u < nu) reinterpret_cast<uint32x4 *>(xl)[u] = pre[k];
         }
     };
 
@@ -386,7 +367,8 @@ __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, 
     const uint32_t wrapb = chb - (uint32_t)p.kh * rowb;           // row kh of ci -> row 0 of ci+1
     const bool g_odd = (p.G & 1) != 0;                            // last step: lanes 32-63 have no group
     // which dwords of a fragment hold slots outside [front, front+kw): 1 = first, 2 = last, 3 = any
-    const int mask_mode = (kmask[0] & kmask[1] & kmask[2] & kmask[3]) == 0xffffffffu ? 0
+    // (uniform over the wavefront: with two fragments per row the masks differ between its halves)
+    const int mask_mode = two_parts ? 3 : (kmask[0] & kmask[1] & kmask[2] & kmask[3]) == 0xffffffffu ? 0
                           : ((kmask[1] & kmask[2] & kmask[3]) == 0xffffffffu ? 1
                           : ((kmask[0] & kmask[1] & kmask[2]) == 0xffffffffu ? 2 : 3));
 
@@ -395,15 +377,17 @@ __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, 
     // state the order of memory operations is  loads(t+1), stores(t), [wait loads(t+1)] ...
     // and the wait for the loads does not have to wait for the stores behind them.
     floatx16 acc[CB][PXW];
-    auto tile_body = [&](const Geom &T, const Geom &Tn) {
+    auto tile_body = [&](const Geom &T, const Geom &Tn, bool first) {
         __syncthreads();                                  // previous tile fully consumed
         if (p.residual) stage_residual<CB, NW * PXW * 32, NT>(p, outl, res, T.n, co_base, T.m0, tid);
         if (prefetchable) {
             commit_loads(tid);
         } else if (vec_ok) {
             for (int u0 = tid; u0 < nu; u0 += NT * XU) {
-                decompose(u0);
-                issue_loads(T);
+                if (!first || u0 != tid) {                 // (the first tile's first batch is in flight already)
+                    decompose(u0);
+                    issue_loads(T);
+                }
                 commit_loads(u0);
             }
         } else {
@@ -446,8 +430,10 @@ __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, 
         // g = (ci, ky) is one staged row, two rows further per step, so both halves' LDS offsets
         // are advanced incrementally in scalar registers.  Fragments of step s+1 are fetched
         // while the MFMAs of step s run; the first step starts from a zero accumulator.
-        uint32_t goff[2] = {0u, (p.kh == 1) ? chb : rowb};            // offsets of groups 0 and 1
-        int gky[2] = {0, (p.kh == 1) ? 0 : 1};
+        // (two fragments per row: both halves walk the same rows, 16 bytes apart, one row per step)
+        uint32_t goff[2] = {0u, two_parts ? 16u : ((p.kh == 1) ? chb : rowb)};      // offsets of groups 0 and 1
+        int gky[2] = {0, (two_parts || p.kh == 1) ? 0 : 1};
+        const int rows_per_step = two_parts ? 1 : 2;
         auto kloop = [&](auto mm_tag) {
             constexpr int MM = decltype(mm_tag)::value;
             auto load_frags = [&](int s, Frag (&a)[CB], Frag (&b)[PXW]) {
@@ -476,7 +462,7 @@ __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, 
                 }
 #pragma unroll
                 for (int e = 0; e < 2; ++e) {                         // both halves: two rows on
-                    gky[e] += 2; goff[e] += 2u * rowb;
+                    gky[e] += rows_per_step; goff[e] += (uint32_t)rows_per_step * rowb;
                     if (gky[e] >= p.kh) { gky[e] -= p.kh; goff[e] += wrapb; }
                     if (gky[e] >= p.kh) { gky[e] -= p.kh; goff[e] += wrapb; }
                 }
@@ -521,16 +507,136 @@ __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, 
     int tile = lw;                                        // < ntiles: the grid never exceeds it
     Geom T = geom(tile);
     Geom Tn = geom(min(tile + nwg, ntiles - 1));
-    if (prefetchable) {
+    // the first tile's (first batch of) input loads go out before the weights are fetched: one
+    // memory round trip for both
+    if (prefetchable || vec_ok) {
         decompose(tid);
         issue_loads(T);
     }
-    tile_body(T, Tn);
+
+    // ---- weights, once per workgroup: unit = (local output channel, group) ----
+    const int units = CB * 32 * p.G2;
+    const int nco = min(CB * 32, p.Cout - co_base);
+    const int wtotal = nco * wrows * p.kw;                // halves of this workgroup's block: contiguous
+    const long long wbytes = (long long)p.Cout * wrows * p.kw * 2;
+    if (wtotal * 2 + 64 <= p.lds_total - p.lds_w_bytes - 32 && wbytes < (1ll << 31)) {
+        // The block fits the (not yet used) tile area: it is parked there as it lies in memory, with
+        // 16-byte loads (an offset of 2^31 is past the end of the tensor: zeros), and the fragments are
+        // cut out of LDS -- five dwords around a fragment's 8 slots, shifted by one half if needed.
+        // As 2-byte gathers from global memory the same took three to four times as long.
+        const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t *>(w), 0, (int)wbytes, 0x00020000);
+        const uint32_t base = (uint32_t)co_base * (uint32_t)(wrows * p.kw) * 2u;      // a multiple of 64
+        const int nvec = (wtotal * 2 + 15) >> 4;
+        constexpr int WB = 12;
+        for (int i0 = tid; i0 < nvec; i0 += NT * WB) {
+            uint32x4 v[WB];
+#pragma unroll
+            for (int k = 0; k < WB; ++k) {
+                const int i = i0 + NT * k;
+                v[k] = __builtin_amdgcn_raw_buffer_load_b128(rw, i < nvec ? base + 16u * (uint32_t)i : 0x80000000u, 0, 0);
+            }
+#pragma unroll
+            for (int k = 0; k < WB; ++k) {
+                const int i = i0 + NT * k;
+                if (i < nvec) reinterpret_cast<uint32x4 *>(xl)[i] = v[k];
+            }
+        }
+        __syncthreads();
+        // valid slots of a fragment: [lo, hi) with lo = front - 8 part, hi = lo + kw, as one mask per dword
+        uint32_t wm[2][4];
+#pragma unroll
+        for (int part = 0; part < 2; ++part)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int t0 = part * 8 + 2 * q - p.front, t1 = t0 + 1;
+                wm[part][q] = ((t0 >= 0 && t0 < p.kw) ? 0x0000ffffu : 0u) | ((t1 >= 0 && t1 < p.kw) ? 0xffff0000u : 0u);
+            }
+        const uint32_t *rawd = reinterpret_cast<const uint32_t *>(xl);
+        // A thread keeps its channel and walks the groups: consecutive lanes take consecutive
+        // channels of one group, so their 16-byte writes are adjacent (lanes along the groups would
+        // write 512 bytes apart, all into the same four banks).  Four fragments per batch: every LDS
+        // read of a batch is issued before the first use (a lone wavefront per SIMD cannot hide
+        // the latency otherwise: 3.4 us for the 66 groups of an 11x11 window on 3 channels).
+        constexpr int GSTEP = NT / (CB * 32);               // groups between a thread's units: 4, 8 or 16
+        constexpr int WQ = 4;
+        const int col = tid & (CB * 32 - 1);
+        const int g0 = tid / (CB * 32);
+        const int part = two_parts ? g0 & 1 : 0;           // GSTEP is even: a thread stays in its half of the row
+        const int dstart = (two_parts ? GSTEP / 2 : GSTEP) * p.kw;
+        int start = (col * wrows + (two_parts ? g0 >> 1 : g0)) * p.kw + part * 8 - p.front;        // >= -1: inside LDS
+        int dst = ((col >> 5) * p.G2 + g0) * 32 + (col & 31);
+        for (int g = g0; g < p.G2; g += WQ * GSTEP) {
+            uint32_t d[WQ][5];
+            uint32_t sh[WQ];
+            bool ok[WQ];
+#pragma unroll
+            for (int k = 0; k < WQ; ++k) {
+                ok[k] = col < nco && g + k * GSTEP < p.G;
+                const int st = ok[k] ? start + k * dstart : 0;
+                sh[k] = (uint32_t)(st & 1) * 16u;
+                const uint32_t *r = rawd + (st >> 1);
+#pragma unroll
+                for (int q = 0; q < 5; ++q) d[k][q] = r[q];
+            }
+#pragma unroll
+            for (int k = 0; k < WQ; ++k) {
+                uint32_t o[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    o[q] = ok[k] ? (__builtin_amdgcn_alignbit(d[k][q + 1], d[k][q], sh[k]) & (part ? wm[1][q] : wm[0][q])) : 0u;
+                if (g + k * GSTEP < p.G2) wl[dst + k * GSTEP * 32] = make_uint4(o[0], o[1], o[2], o[3]);
+            }
+            start += WQ * dstart;
+            dst += WQ * GSTEP * 32;
+        }
+        if (tid < 8) reinterpret_cast<uint32_t *>(xz)[tid] = 0;
+    } else {
+        // batches of WU units: all global loads of a batch are issued before the first LDS
+        // write, so a batch costs one memory round trip
+        constexpr int WU = 6;
+        for (int u0 = tid; u0 < units; u0 += NT * WU) {
+            uint16_t hv[WU][8];
+            bool ok[WU];
+#pragma unroll
+            for (int k = 0; k < WU; ++k) {
+                const int u = min(u0 + NT * k, units - 1);
+                const int col = (int)fdiv((uint32_t)u, p.div_g2);
+                const int g = u - col * p.G2;
+                const int co = co_base + col;
+                ok[k] = co < p.Cout && g < p.G;
+                const int row = two_parts ? g >> 1 : g;     // (ci, ky)
+                const int tap0 = (two_parts ? (g & 1) * 8 : 0) - p.front;      // tap in slot 0 of this fragment
+                const uint16_t *src = w + (ok[k] ? ((size_t)co * wrows + row) * p.kw : 0);
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    const int tap = tap0 + t;
+                    hv[k][t] = (tap >= 0 && tap < p.kw) ? src[tap] : (uint16_t)0;
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < WU; ++k) {
+                const int u = u0 + NT * k;
+                if (u >= units) break;
+                const int col = (int)fdiv((uint32_t)u, p.div_g2);
+                const int g = u - col * p.G2;
+                uint32_t d[4] = {0, 0, 0, 0};
+                if (ok[k]) {
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) d[t >> 1] |= (uint32_t)hv[k][t] << (16 * (t & 1));
+                }
+                wl[((col >> 5) * p.G2 + g) * 32 + (col & 31)] = make_uint4(d[0], d[1], d[2], d[3]);
+            }
+        }
+        if (tid < 8) reinterpret_cast<uint32_t *>(xz)[tid] = 0;
+    }
+
+    tile_body(T, Tn, true);
     for (tile += nwg; tile < ntiles; tile += nwg) {
         store_tile<CB, PXW, NW, FULL>(p, acc, outl, y, T.n, co_base, T.m0, tid, p.residual != 0);
         T = Tn;
         Tn = geom(min(tile + nwg, ntiles - 1));
-        tile_body(T, Tn);
+        tile_body(T, Tn, false);
     }
     store_tile<CB, PXW, NW, FULL>(p, acc, outl, y, T.n, co_base, T.m0, tid, p.residual != 0);
 }

@@ -479,19 +479,22 @@ merit_status derive_conv(merit_plan *pl)
         if (pool) q.rows_out_max = 2;
         q.RHa = (int)((q.rows_out_max - 1) * sh + eh);
         if (variant == CONV_PLANAR_SMALLC) {
-            if (kw > 8 || pw > 8 || dilated) return false;       // its fragments are runs of adjacent taps
+            if (kw > 16 || pw > 8 || dilated) return false;      // its fragments are runs of adjacent taps
+            if (Cin * H * W * 2 >= (1ll << 31) || Cout * Cin * kh * kw * 2 >= (1ll << 31)) return false;    // byte offsets into an image / the weights
             q.padl = 8;
             // with an even column stride every window starts on the same column parity; if that
             // parity is odd and a slot is free, start the fragment one column earlier (front = 1)
             // so that it is dword-aligned in LDS and needs no funnel shift
             const bool odd_start = ((q.padl - pw) & 1) != 0;
-            q.front = (sw % 2 == 0 && odd_start && kw <= 7) ? 1 : 0;
+            q.front = (sw % 2 == 0 && odd_start && kw != 8 && kw != 16) ? 1 : 0;
             q.aligned = (sw % 2 == 0 && ((q.padl - pw - q.front) & 1) == 0) ? 1 : 0;
+            // a window row of more than 8 slots is two K-groups (two adjacent fragments)
+            const int64_t parts = (q.front + kw > 8) ? 2 : 1;
             int64_t pitch = q.padl + W;
-            const int64_t reach = q.padl - pw + (OW - 1) * sw + 10;
+            const int64_t reach = q.padl - pw + (OW - 1) * sw + 2 + 8 * parts;
             if (reach > pitch) pitch = reach;
             q.pitch = (int)round_up(pitch, 8);
-            q.G = (int)(Cin * kh);
+            q.G = (int)(Cin * kh * parts);
             q.G2 = (int)round_up(q.G, 2);
             q.S = q.G2 / 2;
             q.nchi = 0;
@@ -571,7 +574,7 @@ merit_status derive_conv(merit_plan *pl)
         // (the kernel fetches a channel's weights in 16-byte vectors: at least one per channel)
         int lgc = 0;
         while ((1 << lgc) < q.pitch / 8) ++lgc;
-        if (variant == CONV_PLANAR_SMALLC && want_ws && pxw == 2 && nw == 4 && (W % 8) == 0 && lgc <= 7 &&
+        if (variant == CONV_PLANAR_SMALLC && want_ws && q.front + kw <= 8 && pxw == 2 && nw == 4 && (W % 8) == 0 && lgc <= 7 &&
             (((int64_t)Cin * q.RHa) << lgc) <= 128 * 10 && (int64_t)q.G * kw >= 8 &&
             (OH * OW) % 8 == 0 && N * Cin * H * W * 2 < (1ll << 31) &&
             N * Cout * OH * OW * 2 / (pool ? 4 : 1) < (1ll << 31)) {

@@ -481,8 +481,15 @@ def test_conv_plans_for_layers_that_do_not_fit_lds_at_once():
     alex1 = (1, 3, 227, 227, 96, 11, 11, 4, 4, 0, 0)
     p = mb.merit_plan_conv2d(*alex1)
     li = p.launch_info()
+    # 11 taps per window row: two 8-slot fragments per row in the few-channel MFMA kernel
+    assert li["kernel"] == "merit_conv2d_planar" and p.out_shape() == (1, 96, 55, 55)
+    p.set_tile((0, 0, 4, 32))
+    assert p.launch_info()["kernel"] == "merit_conv2d_planar"
+    # 17 taps: neither MFMA layout holds the window
+    p = mb.merit_plan_conv2d(1, 3, 227, 227, 96, 11, 17, 4, 4, 0, 0)
+    li = p.launch_info()
     assert li["kernel"] == "merit_conv2d_direct" and li["lds_bytes"] == 32 * 1024
-    assert p.out_shape() == (1, 96, 55, 55) and li["grid"][:2] == (12 * -(-55 * 55 // 256), 1)   # 8 channels x 256 pixels
+    assert p.out_shape() == (1, 96, 55, 53) and li["grid"][:2] == (12 * -(-55 * 53 // 256), 1)   # 8 channels x 256 pixels
     with pytest.raises(mb.MeritError):
         p.set_tile((0, 0, 4, 32))
     with pytest.raises(mb.MeritError):

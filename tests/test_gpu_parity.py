@@ -477,9 +477,17 @@ CONV_CASES = [
     (33, 200, 14, 14, 70, 3, 3, 1, 1, 1, 1),   # passes, 3x3, one-pixel input units
     (17, 256, 20, 56, 64, 3, 3, 1, 1, 1, 1),   # passes, 3x3, 8-pixel input units
     (20, 520, 12, 64, 96, 1, 1, 1, 1, 0, 0),   # passes, 1x1
-    # neither MFMA kernel: the one-element-per-thread kernel
+    # planar, window rows of 9 to 16 taps: two 8-slot fragments per row
     (1, 3, 67, 67, 48, 11, 11, 4, 4, 5, 5),    # the paper's strided example: x = 4p + a - 5, 11x11 window
-    (2, 5, 30, 41, 7, 9, 12, 2, 3, 4, 6),      # wide window on few channels
+    (2, 5, 30, 41, 7, 9, 12, 2, 3, 4, 6),      # odd column stride: funnel-shifted fragments
+    (3, 3, 44, 48, 40, 11, 11, 4, 4, 5, 5),    # W % 8 == 0: vector staging with prefetch, several tiles
+    (2, 1, 20, 64, 33, 1, 16, 1, 2, 0, 8),     # one channel, one window row of 16 taps, widest padding
+    (1, 2, 25, 37, 16, 3, 9, 1, 2, 1, 4),      # 9 taps, even stride, even start: no front slot
+    (1, 4, 23, 31, 20, 2, 15, 2, 2, 1, 7),     # 15 taps + the front slot: all 16 slots
+    (9, 3, 40, 40, 64, 9, 9, 1, 1, 4, 4),      # stride 1, several tiles per workgroup
+    # neither MFMA kernel: the one-element-per-thread kernel
+    (1, 3, 40, 44, 10, 5, 17, 2, 2, 2, 8),     # 17 taps per window row on few channels
+    (2, 5, 30, 41, 7, 9, 12, 2, 3, 4, 9),      # padding wider than the staged left margin
 ]
 
 
@@ -683,7 +691,8 @@ RESIDUAL_CASES = [
     (1, 136, 10, 16, 64, 3, 3, 1, 1, 1, 1, 1),  # channel-block, channels in passes
     (1, 256, 12, 56, 64, 3, 3, 1, 1, 1, 1, 1),  # channel-block, passes on the vector staging path
     (22, 256, 12, 56, 64, 3, 3, 1, 1, 1, 1, 1), # the same with 64-channel blocks (more than 128 workgroups)
-    (1, 3, 45, 45, 6, 11, 11, 4, 4, 0, 0, 1),   # one element per thread
+    (1, 3, 45, 45, 6, 11, 11, 4, 4, 0, 0, 1),   # planar, two fragments per window row
+    (1, 3, 45, 45, 6, 11, 17, 4, 4, 0, 0, 1),   # one element per thread
 ]
 
 
@@ -793,7 +802,7 @@ def test_conv_channel_passes_and_wide_window_workloads_sampled(mb):
     c = wl.CFG_CONV11
     x, w = wl.make_conv_inputs(c)
     plan = mb.merit_plan_conv2d(c.N, c.Cin, c.H, c.W, c.Cout, c.kh, c.kw, c.sh, c.sw, c.ph, c.pw)
-    assert plan.launch_info()["kernel"] == "merit_conv2d_direct" and plan.out_shape() == (8, 48, 55, 55)
+    assert plan.launch_info()["kernel"] == "merit_conv2d_planar" and plan.out_shape() == (8, 48, 55, 55)
     y = mb.merit_conv2d(plan, dev(x), dev(w)).cpu().numpy().astype(np.float64)
     ref = oracle.conv2d(x, w, (c.sh, c.sw), (c.ph, c.pw)).astype(np.float64)
     assert np.all(np.abs(y - ref) <= 2e-2 * np.abs(ref) + 1e-3)
@@ -1215,10 +1224,10 @@ def test_more_launches_can_be_captured_in_a_graph(mb):
     kx = rng.standard_normal(30).astype(np.float32); ky = rng.standard_normal(30).astype(np.float32)
     xs = torch.zeros((1, 70, 136), dtype=torch.float32, device="cuda:0"); ys = torch.empty_like(xs)
     cp = mb.merit_plan_conv2d(1, 264, 10, 16, 40, 3, 3, 1, 1, 1, 1)
-    cd = mb.merit_plan_conv2d(1, 3, 45, 45, 6, 11, 11, 4, 4, 0, 0)
+    cd = mb.merit_plan_conv2d(1, 3, 45, 45, 6, 11, 17, 4, 4, 0, 0)
     assert cp.launch_info()["kernel"] == "merit_conv2d_chpass" and cd.launch_info()["kernel"] == "merit_conv2d_direct"
     wp = (rng.standard_normal((40, 264, 3, 3)) / 49).astype(np.float16)
-    wd = (rng.standard_normal((6, 3, 11, 11)) / 19).astype(np.float16)
+    wd = (rng.standard_normal((6, 3, 11, 17)) / 24).astype(np.float16)
     xp = torch.zeros((1, 264, 10, 16), dtype=torch.float16, device="cuda:0")
     xd = torch.zeros((1, 3, 45, 45), dtype=torch.float16, device="cuda:0")
     yp = torch.empty(cp.out_shape(), dtype=torch.float16, device="cuda:0")
