@@ -250,6 +250,7 @@ __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, 
                                                              const uint16_t *__restrict__ res,
                                                              uint16_t *__restrict__ y)
 {
+    touch_kernarg_lines();
     extern __shared__ __align__(16) uint8_t smem[];
     uint4 *wl = reinterpret_cast<uint4 *>(smem);
     uint8_t *xz = smem + p.lds_w_bytes;                 // 32 zero bytes, then the tile
@@ -436,29 +437,25 @@ __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, 
         const int rows_per_step = two_parts ? 1 : 2;
         auto kloop = [&](auto mm_tag) {
             constexpr int MM = decltype(mm_tag)::value;
-            auto load_frags = [&](int s, Frag (&a)[CB], Frag (&b)[PXW]) {
+            // A fetch only reads LDS; the funnel shift and the masks are applied where the fragment is
+            // used (done right behind the reads they would make the reads wait where they are issued).
+            struct Raw {
+                uint32_t d[ALIGNED ? 4 : 5];
+            };
+            auto load_frags = [&](int s, Frag (&a)[CB], Raw (&r)[PXW]) {
                 const uint32_t off = h ? goff[1] : goff[0];
-                const bool dead = g_odd && h && (s == p.S - 1);       // group 2s+1 == G: no such row
+                // group 2s+1 == G: no such row; s == S: the step after the last one, fetched and never
+                // used (a fetch under a condition would make every wait in the loop a wait for all)
+                const bool dead = (g_odd && h && (s == p.S - 1)) || s >= p.S;
 #pragma unroll
-                for (int cb = 0; cb < CB; ++cb) a[cb].u = wl[cb * p.G2 * 32 + s * 64 + lane];
+                for (int cb = 0; cb < CB; ++cb) a[cb].u = wl[cb * p.G2 * 32 + min(s, p.S - 1) * 64 + lane];
 #pragma unroll
                 for (int pb = 0; pb < PXW; ++pb) {
                     // a dead group reads the zero block (its weights are zero too)
                     const uint32_t addr = dead ? 0u : pbase[pb] + off;
                     const uint32_t *src = reinterpret_cast<const uint32_t *>(xz + addr);
-                    if (ALIGNED) {
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) b[pb].d[q] = src[q];
-                    } else {
-                        uint32_t d[5];
-#pragma unroll
-                        for (int q = 0; q < 5; ++q) d[q] = src[q];
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) b[pb].d[q] = __builtin_amdgcn_alignbit(d[q + 1], d[q], shift[pb]);
-                    }
-                    if (MM == 1 || MM == 3) b[pb].d[0] &= kmask[0];
-                    if (MM == 3) { b[pb].d[1] &= kmask[1]; b[pb].d[2] &= kmask[2]; }
-                    if (MM == 2 || MM == 3) b[pb].d[3] &= kmask[3];
+                    for (int q = 0; q < (ALIGNED ? 4 : 5); ++q) r[pb].d[q] = src[q];
                 }
 #pragma unroll
                 for (int e = 0; e < 2; ++e) {                         // both halves: two rows on
@@ -467,32 +464,43 @@ __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, 
                     if (gky[e] >= p.kh) { gky[e] -= p.kh; goff[e] += wrapb; }
                 }
             };
-            auto mfma_all = [&](Frag (&a)[CB], Frag (&b)[PXW]) {
+            auto mfma_all = [&](Frag (&a)[CB], Raw (&r)[PXW], bool init) {
+                Frag b[PXW];
 #pragma unroll
-                for (int cb = 0; cb < CB; ++cb)
+                for (int pb = 0; pb < PXW; ++pb) {
 #pragma unroll
-                    for (int pb = 0; pb < PXW; ++pb) acc[cb][pb] = mfma16(a[cb], b[pb], acc[cb][pb]);
-            };
-            Frag a0[CB], b0[PXW], a1[CB], b1[PXW];
-            load_frags(0, a0, b0);
-            if (p.S > 1) load_frags(1, a1, b1);
-            {
+                    for (int q = 0; q < 4; ++q)
+                        b[pb].d[q] = ALIGNED ? r[pb].d[q] : __builtin_amdgcn_alignbit(r[pb].d[ALIGNED ? q : q + 1], r[pb].d[q], shift[pb]);
+                    if (MM == 1 || MM == 3) b[pb].d[0] &= kmask[0];
+                    if (MM == 3) { b[pb].d[1] &= kmask[1]; b[pb].d[2] &= kmask[2]; }
+                    if (MM == 2 || MM == 3) b[pb].d[3] &= kmask[3];
+                }
                 floatx16 zero;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) zero[r] = 0.0f;
+                for (int q = 0; q < 16; ++q) zero[q] = 0.0f;
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-                    for (int pb = 0; pb < PXW; ++pb) acc[cb][pb] = mfma16(a0[cb], b0[pb], zero);
-            }
-            int s = 1;                                                // a1/b1 hold step s
+                    for (int pb = 0; pb < PXW; ++pb) acc[cb][pb] = mfma16(a[cb], b[pb], init ? zero : acc[cb][pb]);
+            };
+            Frag a0[CB], a1[CB];
+            Raw r0[PXW], r1[PXW];
+            load_frags(0, a0, r0);
+            load_frags(1, a1, r1);
+            mfma_all(a0, r0, true);                                   // the first step starts from zero
+            int s = 1;                                                // a1/r1 hold step s
+            // (the fences keep the scheduler from sinking a fetch below the MFMAs it is meant to run under)
             for (; s + 2 <= p.S; s += 2) {
-                load_frags(s + 1, a0, b0);
-                mfma_all(a1, b1);
-                if (s + 2 < p.S) load_frags(s + 2, a1, b1);
-                mfma_all(a0, b0);
+                load_frags(s + 1, a0, r0);
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_all(a1, r1, false);
+                __builtin_amdgcn_sched_barrier(0);
+                load_frags(s + 2, a1, r1);
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_all(a0, r0, false);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            if (s < p.S) mfma_all(a1, b1);
+            if (s < p.S) mfma_all(a1, r1, false);
         };
         if (mask_mode == 0) kloop(std::integral_constant<int, 0>{});
         else if (mask_mode == 1) kloop(std::integral_constant<int, 1>{});
@@ -521,20 +529,24 @@ __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, 
     const long long wbytes = (long long)p.Cout * wrows * p.kw * 2;
     if (wtotal * 2 + 64 <= p.lds_total - p.lds_w_bytes - 32 && wbytes < (1ll << 31)) {
         // The block fits the (not yet used) tile area: it is parked there as it lies in memory, with
-        // 16-byte loads (an offset of 2^31 is past the end of the tensor: zeros), and the fragments are
+        // 16-byte loads, and the fragments are
         // cut out of LDS -- five dwords around a fragment's 8 slots, shifted by one half if needed.
         // As 2-byte gathers from global memory the same took three to four times as long.
         const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<uint16_t *>(w), 0, (int)wbytes, 0x00020000);
         const uint32_t base = (uint32_t)co_base * (uint32_t)(wrows * p.kw) * 2u;      // a multiple of 64
-        const int nvec = (wtotal * 2 + 15) >> 4;
+        // whole 16-byte vectors inside the tensor; the last block's last few halves (a load that is
+        // only partly in range returns zeros for all of it) are fetched one by one
+        const int nvec = min((wtotal * 2 + 15) >> 4, (int)((wbytes - (long long)base) >> 4));
+        if (tid < 8 && nvec * 8 + tid < wtotal)
+            reinterpret_cast<uint16_t *>(xl)[nvec * 8 + tid] = w[(size_t)co_base * (size_t)(wrows * p.kw) + nvec * 8 + tid];
         constexpr int WB = 12;
         for (int i0 = tid; i0 < nvec; i0 += NT * WB) {
             uint32x4 v[WB];
 #pragma unroll
             for (int k = 0; k < WB; ++k) {
                 const int i = i0 + NT * k;
-                v[k] = __builtin_amdgcn_raw_buffer_load_b128(rw, i < nvec ? base + 16u * (uint32_t)i : 0x80000000u, 0, 0);
+                v[k] = __builtin_amdgcn_raw_buffer_load_b128(rw, i < nvec ? base + 16u * (uint32_t)i : 0x80000000u, 0, 0);   // (2^31: out of range, no load)
             }
 #pragma unroll
             for (int k = 0; k < WB; ++k) {
@@ -543,15 +555,6 @@ __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, 
             }
         }
         __syncthreads();
-        // valid slots of a fragment: [lo, hi) with lo = front - 8 part, hi = lo + kw, as one mask per dword
-        uint32_t wm[2][4];
-#pragma unroll
-        for (int part = 0; part < 2; ++part)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int t0 = part * 8 + 2 * q - p.front, t1 = t0 + 1;
-                wm[part][q] = ((t0 >= 0 && t0 < p.kw) ? 0x0000ffffu : 0u) | ((t1 >= 0 && t1 < p.kw) ? 0xffff0000u : 0u);
-            }
         const uint32_t *rawd = reinterpret_cast<const uint32_t *>(xl);
         // A thread keeps its channel and walks the groups: consecutive lanes take consecutive
         // channels of one group, so their 16-byte writes are adjacent (lanes along the groups would
@@ -563,6 +566,11 @@ __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, 
         const int col = tid & (CB * 32 - 1);
         const int g0 = tid / (CB * 32);
         const int part = two_parts ? g0 & 1 : 0;           // GSTEP is even: a thread stays in its half of the row
+        // valid slots of this thread's fragments: bit t of `valid` = slot t holds a tap; one mask per dword
+        const uint32_t valid = ((((1u << p.kw) - 1u) << p.front) >> (8 * part)) & 0xffu;
+        uint32_t wm[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) wm[q] = ((valid >> (2 * q)) & 1u) * 0x0000ffffu | ((valid >> (2 * q + 1)) & 1u) * 0xffff0000u;
         const int dstart = (two_parts ? GSTEP / 2 : GSTEP) * p.kw;
         int start = (col * wrows + (two_parts ? g0 >> 1 : g0)) * p.kw + part * 8 - p.front;        // >= -1: inside LDS
         int dst = ((col >> 5) * p.G2 + g0) * 32 + (col & 31);
@@ -582,9 +590,9 @@ __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, 
 #pragma unroll
             for (int k = 0; k < WQ; ++k) {
                 uint32_t o[4];
+                const uint32_t okm = ok[k] ? 0xffffffffu : 0u;      // (no branch: what was read for a unit that is not there is inside LDS)
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    o[q] = ok[k] ? (__builtin_amdgcn_alignbit(d[k][q + 1], d[k][q], sh[k]) & (part ? wm[1][q] : wm[0][q])) : 0u;
+                for (int q = 0; q < 4; ++q) o[q] = __builtin_amdgcn_alignbit(d[k][q + 1], d[k][q], sh[k]) & wm[q] & okm;
                 if (g + k * GSTEP < p.G2) wl[dst + k * GSTEP * 32] = make_uint4(o[0], o[1], o[2], o[3]);
             }
             start += WQ * dstart;

@@ -485,6 +485,7 @@ CONV_CASES = [
     (1, 2, 25, 37, 16, 3, 9, 1, 2, 1, 4),      # 9 taps, even stride, even start: no front slot
     (1, 4, 23, 31, 20, 2, 15, 2, 2, 1, 7),     # 15 taps + the front slot: all 16 slots
     (9, 3, 40, 40, 64, 9, 9, 1, 1, 4, 4),      # stride 1, several tiles per workgroup
+    (1, 1, 22, 17, 53, 1, 7, 3, 3, 0, 1),      # the weight tensor ends in the middle of a 16-byte vector
     # neither MFMA kernel: the one-element-per-thread kernel
     (1, 3, 40, 44, 10, 5, 17, 2, 2, 2, 8),     # 17 taps per window row on few channels
     (2, 5, 30, 41, 7, 9, 12, 2, 3, 4, 9),      # padding wider than the staged left margin
