@@ -498,6 +498,7 @@ def main():
             bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets, relu=True),
             bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets, relu=True, pool=True),
             bench_conv(torch, mb, wl, wl.CFG2_CONV3, k, w, args.sets, relu=True, residual=True),
+            bench_conv(torch, mb, wl, wl.CFG2_CONV3, k, w, args.sets, relu=True, pool=True),
             bench_conv(torch, mb, wl, wl.CFG_DILATED, k, w, args.sets),
             bench_conv(torch, mb, wl, wl.CFG_CONV256, kl, w, args.sets),
             bench_conv(torch, mb, wl, wl.CFG_CONV256, kl, w, args.sets, packed=True),

@@ -2014,7 +2014,7 @@ const char *conv_kernel_name(const ConvParams &p)
     if (p.variant == CONV_PLANAR_SMALLC && p.ws && p.pool) return "merit_conv2d_planar_ws_pool";
     if (p.variant == CONV_PLANAR_SMALLC) return p.ws ? "merit_conv2d_planar_ws" : "merit_conv2d_planar";
     if (p.variant == CONV_DIRECT) return "merit_conv2d_direct";
-    if (p.variant == CONV_CHWS) return "merit_conv2d_chws";
+    if (p.variant == CONV_CHWS) return p.pool ? "merit_conv2d_chws_pool" : "merit_conv2d_chws";
     return p.nchunks > 1 ? "merit_conv2d_chpass" : "merit_conv2d_chblock";
 }
 

@@ -50,6 +50,13 @@ union Frag {
 
 struct Geom {
     int n, m0, oyA, yA, RH, cg;
+    int mend;      // one past the last output pixel of the tile that is used
+    // fused pooling only
+    int pr0;       // first pooled row the tile completes
+    int warm;      // the tile above a band's first pooled row: only its last row is kept
+    int top;       // the tile starts at the image's first row: nothing above it (-inf)
+    int roff;      // row of the tile that is convolution row 2 pr0 (1 when the tile computes the row above it)
+    int par;       // which of the two carry buffers holds the row above the tile
 };
 
 __device__ __forceinline__ Geom tile_geom(const ConvParams &p, int item, int ohw)
@@ -64,6 +71,50 @@ __device__ __forceinline__ Geom tile_geom(const ConvParams &p, int item, int ohw
     const int oyB = (int)fdiv((uint32_t)mlast, p.div_ow);
     g.yA = g.oyA * p.sh - p.ph;
     g.RH = (oyB - g.oyA) * p.sh + (p.kh - 1) * p.dh + 1;
+    g.mend = min(g.m0 + p.TM, ohw);
+    g.pr0 = g.warm = g.top = g.roff = g.par = 0;
+    return g;
+}
+
+// Fused 3x3 / stride 2 / padding 1 max pooling: a work item is (image, band of PB pooled rows,
+// channel block); its tiles are whole convolution rows.  Pooled row r needs rows 2r-1, 2r, 2r+1.
+// Two ways to get row 2r-1 for a tile's first pooled row:
+//   * carried (pool_halo = 0): a tile is rows_out_max (even) rows from the even row 2 pr0 and
+//     completes rows_out_max / 2 pooled rows from its own rows and the last row of the tile before
+//     it, which is kept in LDS.  The first tile of a band below the image's top only produces that
+//     carried row.
+//   * computed (pool_halo = 1): a tile is rows_out_max (odd) rows from row 2 pr0 - 1 and completes
+//     (rows_out_max - 1) / 2 pooled rows on its own; a band is one tile.
+__device__ __forceinline__ int pool_band_tiles(const ConvParams &p, int item)
+{
+    if (p.pool_halo) return 1;
+    const int bu = (int)fdiv((uint32_t)item, p.div_cog);
+    const int n = (int)fdiv((uint32_t)bu, p.div_nb);
+    const int band = bu - n * p.NB;
+    const int rows = min(p.PB, p.PH - band * p.PB);                  // pooled rows of this band
+    const int hp = p.rows_out_max >> 1;
+    return (rows + hp - 1) / hp + (band > 0 ? 1 : 0);
+}
+
+__device__ __forceinline__ Geom pool_geom(const ConvParams &p, int item, int i, int ohw)
+{
+    Geom g;
+    const int bu = (int)fdiv((uint32_t)item, p.div_cog);
+    g.cg = item - bu * p.co_groups;
+    g.n = (int)fdiv((uint32_t)bu, p.div_nb);
+    const int band = bu - g.n * p.NB;
+    const int R = p.rows_out_max, hp = R >> 1;
+    const int lead = (band > 0 && !p.pool_halo) ? 1 : 0;
+    g.pr0 = band * p.PB + (i - lead) * hp;                           // (the warm-up tile: hp rows higher, nothing of it is stored)
+    g.warm = (lead && i == 0) ? 1 : 0;
+    g.top = g.pr0 == 0 ? 1 : 0;
+    g.roff = (p.pool_halo && !g.top) ? 1 : 0;
+    g.oyA = 2 * g.pr0 - g.roff;
+    g.par = i & 1;
+    g.m0 = g.oyA * p.OW;
+    g.mend = min(g.m0 + R * p.OW, ohw);
+    g.yA = g.oyA * p.sh - p.ph;
+    g.RH = (R - 1) * p.sh + (p.kh - 1) * p.dh + 1;
     return g;
 }
 
@@ -78,7 +129,9 @@ constexpr uint32_t OOB = 0x80000000u;   // a buffer offset past the end of every
 // 8 channels x 1 pixel, up to XS_MAX per thread.
 // NG: pairs of 8-channel groups per pass (1: 16 channels, 2: 32 -- small tiles, whose passes would
 // otherwise be shorter than a memory round trip).
-template <int PXB, int CHB, int WM, int WN, int T, int XU, bool PACKED, int NG = 1>
+// POOL: the results are max-pooled (3x3 / stride 2 / padding 1) out of the staging area and only the
+// pooled tensor is written; work items are bands of pooled rows (pool_geom above).
+template <int PXB, int CHB, int WM, int WN, int T, int XU, bool PACKED, int NG = 1, bool POOL = false>
 __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvParams p, const uint16_t *__restrict__ x,
                                                             const uint16_t *__restrict__ w,
                                                             uint16_t *__restrict__ y)
@@ -119,10 +172,26 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
     uint32_t *outl = reinterpret_cast<uint32_t *>(smem);
 
     // ---- work list: item = (tile, channel block), a contiguous band of the list per XCD ------
-    const int nitems = p.N * p.tiles_per_image * p.co_groups;
+    const int nitems = POOL ? p.N * p.NB * p.co_groups : p.N * p.tiles_per_image * p.co_groups;
     const int stride = (int)gridDim.x;
     int item = (int)xcd_band_item(blockIdx.x, stride >> 3, stride & 7);
     if (item >= nitems) return;                            // (the launcher never makes the grid larger than the list)
+    // position = (item, tile of the item); without pooling an item is one tile
+    int ti = 0, ntile = POOL ? pool_band_tiles(p, item) : 1;
+    auto geom_at = [&](int it, int i) __attribute__((always_inline)) {
+        if constexpr (POOL) return pool_geom(p, it, i, ohw);
+        else return tile_geom(p, it, ohw);
+    };
+    auto next_pos = [&](int &it, int &i, int &n) __attribute__((always_inline)) -> bool {
+        if constexpr (POOL) {
+            if (++i < n) return true;
+            i = 0;
+        }
+        it += stride;
+        if (it >= nitems) return false;
+        if constexpr (POOL) n = pool_band_tiles(p, it);
+        return true;
+    };
 
     // results: LDS [channel][pixel] -> 16-byte runs along the pixel axis, by all threads
     auto store_out = [&](const Geom &g) __attribute__((always_inline)) {
@@ -149,6 +218,68 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
                     if (m + k >= ohw) break;
                     y0[k] = (uint16_t)(e[k >> 1] >> (16 * (k & 1)));
                 }
+            }
+        }
+    };
+
+    // Fused pooling, by all threads: unit = (channel, pooled row of the tile, 4 pooled pixels).  The
+    // rows 2r-1, 2r, 2r+1 are 4 dwords (8 convolution pixels) each plus the dword to their left;
+    // row -1 of the tile comes from the carry buffer the previous tile filled (-inf above the
+    // image).  Maximum down the rows, then along the row at stride 2.  Before that the tile's last
+    // row goes to the other carry buffer.  binary16 maxima are exact: the result is bit-equal to
+    // pooling the stored convolution.
+    auto pool_out = [&](const Geom &g) __attribute__((always_inline)) {
+        static_assert((TN & (TN - 1)) == 0, "channel index = low bits of the unit index");
+        constexpr uint32_t NINF = 0xFC00FC00u;
+        const int OW2 = p.OW >> 1;                         // dwords per convolution row
+        const int R = p.rows_out_max, hp = R >> 1;
+        uint32_t *carry = reinterpret_cast<uint32_t *>(smem + p.lds_o_offset);
+        const uint32_t *cin = carry + g.par * (TN * OW2);
+        if (!p.pool_halo) {
+            uint32_t *cnext = carry + (g.par ^ 1) * (TN * OW2);
+            for (int u = tid; u < TN * OW2; u += NT) {
+                const int c = u & (TN - 1), d = u / TN;
+                cnext[c * OW2 + d] = outl[c * OP + (R - 1) * OW2 + d];
+            }
+            if (g.warm) return;
+        }
+        auto pmax = [](uint32_t a, uint32_t b) {
+            return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(half2v, a), __builtin_bit_cast(half2v, b)));
+        };
+        const int units = TN * hp * p.pw8;
+        const bool vec_ok = (p.PW & 3) == 0;
+        for (int u = tid; u < units; u += NT) {
+            const int c = u & (TN - 1), v = u / TN;
+            const int prl = (int)fdiv((uint32_t)v, p.div_pw8);
+            const int j4 = v - prl * p.pw8;
+            const int pr = g.pr0 + prl;
+            const int co = g.cg * TN + c;
+            if (pr >= p.PH || co >= p.Cout) continue;
+            const int rowb = g.roff + 2 * prl;                                  // the tile's row that is convolution row 2r
+            const uint32_t *rb = outl + c * OP + rowb * OW2 + 4 * j4;            // row 2r; row 2r+1 is OW2 further
+            const uint32_t *ra = rowb > 0 ? rb - OW2 : cin + c * OW2 + 4 * j4;   // row 2r-1: the tile's, or the carried one
+            const bool above = rowb > 0 || !g.top;
+            uint32_t vm[4], left;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) vm[q] = pmax(pmax(rb[q], rb[OW2 + q]), above ? ra[q] : NINF);
+            if (j4 > 0) left = pmax(pmax(rb[-1], rb[OW2 - 1]), above ? ra[-1] : NINF);
+            else left = NINF;
+            uint32_t res[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t prev = (k == 0 ? left : vm[k - 1]) >> 16;          // pixel 2k-1 in the low half
+                res[k] = pmax(pmax(vm[k], vm[k] >> 16), prev) & 0xffffu;         // max of pixels 2k-1, 2k, 2k+1
+            }
+            uint16_t *y0 = y + (((size_t)g.n * p.Cout + co) * p.PH + pr) * p.PW + 4 * j4;
+            if (vec_ok) {
+                uint2 o;
+                o.x = res[0] | (res[1] << 16);
+                o.y = res[2] | (res[3] << 16);
+                *reinterpret_cast<uint2 *>(y0) = o;
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    if (4 * j4 + k < p.PW) y0[k] = (uint16_t)res[k];
             }
         }
     };
@@ -366,12 +497,13 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
 #if MERIT_CHWS_EXPERIMENT == 9
         unsigned long long tc = 0, tr = 0, tb = 0, tw = 0;
 #endif
-        Geom g = tile_geom(p, item, ohw);
+        Geom g = geom_at(item, 0);
         setup(g);
         request(g, 0);
-        for (; item < nitems; item += stride) {
-            const bool more = item + stride < nitems;
-            const Geom gn = more ? tile_geom(p, item + stride, ohw) : g;
+        for (;;) {
+            int item2 = item, ti2 = ti, ntile2 = ntile;
+            const bool more = next_pos(item2, ti2, ntile2);
+            const Geom gn = more ? geom_at(item2, ti2) : g;
             commit(0);
             weights_direct(g.cg, 0, 0);
             zero_pads();
@@ -401,9 +533,11 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
             // the next item's first pass flies under the result stores
             if (more) { setup(gn); request(gn, 0); }
             __syncthreads();                                   // E1
-            store_out(g);
+            if constexpr (POOL) pool_out(g);
+            else store_out(g);
             __syncthreads();                                   // E2
-            g = gn;
+            if (!more) break;
+            g = gn; item = item2; ti = ti2; ntile = ntile2;
         }
 #if MERIT_CHWS_EXPERIMENT == 9
         if (blockIdx.x == 7 && tid == 256)
@@ -417,13 +551,13 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
     unsigned long long tk = 0, tb = 0, t0, tstart = TS();
 #endif
     const int wm = wave % WM, wn = wave / WM;
-    for (; item < nitems; item += stride) {
-        const Geom g = tile_geom(p, item, ohw);
+    for (bool more = true; more; more = next_pos(item, ti, ntile)) {
+        const Geom g = geom_at(item, ti);
         int xc[PXB][T == 9 ? 3 : 1];
 #pragma unroll
         for (int pb = 0; pb < PXB; ++pb) {
             const int m = g.m0 + (wm * PXB + pb) * 32 + c32;
-            const int mm = min(m, ohw - 1);
+            const int mm = min(m, g.mend - 1);                 // (pixels past the tile's end: computed, never stored)
             const int oy = (int)fdiv((uint32_t)mm, p.div_ow);
             const int ox = mm - oy * p.OW;
             const int pbase = (h * p.RHa + (oy - g.oyA) * p.sh) * p.pitch;
@@ -526,7 +660,8 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
         const unsigned long long te0 = TS();
 #endif
         __syncthreads();                                       // E1
-        store_out(g);
+        if constexpr (POOL) pool_out(g);
+        else store_out(g);
         __syncthreads();                                       // E2
 #if MERIT_CHWS_EXPERIMENT == 9
         if (blockIdx.x == 7 && tid == 0)
@@ -582,12 +717,22 @@ hipError_t launch_one(K kernel, const ConvParams &p, const void *x, const void *
     return hipGetLastError();
 }
 
-template <int PXB, int CHB, int WM, int WN, int NG = 1>
+template <int PXB, int CHB, int WM, int WN, int NG = 1, bool POOLS = false>
 hipError_t launch_tile(const ConvParams &p, const void *x, const void *w, void *y, hipStream_t s, uint32_t grid,
                        bool packed)
 {
     const int xu = (p.W & 7) == 0 ? p.xu : 0;                // 8-pixel units per moving thread, 0: one-pixel units
     const int T = p.kh * p.kw;
+    if (p.pool) {
+        // fused pooling: 3x3 windows on the caller's weights; not the 128-channel tiling on 8 wavefronts
+        if constexpr (POOLS) {
+            if (T != 9 || packed) return hipErrorInvalidValue;
+            if (xu == 1) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 1, false, NG, true>, p, x, w, y, s, grid);
+            if (xu == 2) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 2, false, NG, true>, p, x, w, y, s, grid);
+            return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 0, false, NG, true>, p, x, w, y, s, grid);
+        }
+        return hipErrorInvalidValue;
+    }
 #define MERIT_CHWS(Tv, XUv)                                                                             \
     do {                                                                                                \
         if (packed) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, Tv, XUv, true, NG>, p, x, w, y, s, grid);  \
@@ -607,14 +752,14 @@ hipError_t launch_tile(const ConvParams &p, const void *x, const void *w, void *
 
 hipError_t launch_conv2d_chws(const ConvParams &p, const void *x, const void *w, void *y, hipStream_t s, bool packed)
 {
-    const int64_t nitems = (int64_t)p.N * p.tiles_per_image * p.co_groups;
+    const int64_t nitems = p.pool ? (int64_t)p.N * p.NB * p.co_groups : (int64_t)p.N * p.tiles_per_image * p.co_groups;
     if (nitems == 0) return hipSuccess;
     const int64_t slots = device_cu_count();            // one 512-thread workgroup per compute unit
     const uint32_t grid = (uint32_t)(nitems < slots ? nitems : slots);
-    if (p.CB == 4 && p.NW == 12) return launch_tile<2, 2, 4, 2>(p, x, w, y, s, grid, packed);   // 256 x 128, 8 x (64 x 64)
+    if (p.CB == 4 && p.NW == 12) return launch_tile<2, 2, 4, 2, 1, true>(p, x, w, y, s, grid, packed);   // 256 x 128, 8 x (64 x 64)
     if (p.CB == 4) return launch_tile<4, 2, 2, 2>(p, x, w, y, s, grid, packed);     // 256 pixels x 128 channels, 4 x (128 x 64)
-    if (p.TM == 128) return launch_tile<1, 2, 4, 1, 2>(p, x, w, y, s, grid, packed);   // 128 pixels x 64 channels, 4 x (32 x 64), 32 channels per pass
-    return launch_tile<2, 2, 4, 1>(p, x, w, y, s, grid, packed);                    // 256 pixels x 64 channels, 4 x (64 x 64)
+    if (p.TM == 128) return launch_tile<1, 2, 4, 1, 2, true>(p, x, w, y, s, grid, packed);   // 128 pixels x 64 channels, 4 x (32 x 64), 32 channels per pass
+    return launch_tile<2, 2, 4, 1, 1, true>(p, x, w, y, s, grid, packed);           // 256 pixels x 64 channels, 4 x (64 x 64)
 }
 
 hipError_t launch_conv2d_pack_weights(const ConvParams &p, const void *w, void *packed, hipStream_t s)

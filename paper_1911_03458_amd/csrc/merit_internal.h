@@ -158,6 +158,8 @@ struct ConvParams {
     int xu;                // input staging units per moving thread and pass
     FastDiv div_cog;       // work item -> (tile, channel block)
     FastDiv div_r2;        // staged rows of both channel groups of a pass (2 * RHa)
+    int pool_halo;         // fused pooling there: 1 = a tile computes the row above its first pooled row itself
+                           // (rows_out_max odd), 0 = that row is carried from the tile before it (rows_out_max even)
 };
 
 // ---- launchers (defined in the .hip files) --------------------------------

@@ -447,9 +447,9 @@ merit_status derive_conv(merit_plan *pl)
     p.residual = (d.op == MERIT_OP_CONV_DOT_ADD || d.op == MERIT_OP_CONV_DOT_ADD_RELU) ? 1 : 0;
     const bool pool = d.op == MERIT_OP_CONV_DOT_POOLMAX || d.op == MERIT_OP_CONV_DOT_RELU_POOLMAX;
     p.pool = pool ? 1 : 0;
-    p.PH = p.PW = p.PB = p.NB = p.pw8 = 0;
-    // fused pooling: a workgroup's 256-pixel tile is two whole output rows, pooled 8 columns at a time
-    if (pool && (OH % 2 != 0 || OW % 16 != 0 || 2 * OW > 256)) return MERIT_ERR_UNSUPPORTED;
+    p.PH = p.PW = p.PB = p.NB = p.pw8 = 0; p.pool_halo = 0;
+    // fused pooling: a workgroup's tile is an even number of whole output rows (at least two)
+    if (pool && (OH % 2 != 0 || OW % 2 != 0 || 2 * OW > 256)) return MERIT_ERR_UNSUPPORTED;
     p.OH = (int)OH; p.OW = (int)OW; p.kh = (int)kh; p.kw = (int)kw; p.sh = (int)sh; p.sw = (int)sw;
     p.ph = (int)ph; p.pw = (int)pw; p.dh = (int)dh; p.dw = (int)dw;
 
@@ -606,13 +606,15 @@ merit_status derive_conv(merit_plan *pl)
     // Wave-specialised multi-pass kernel (conv2d_chws.hip): 256-pixel tiles x `cb` 32-channel blocks
     // (4 or 2), 16 input channels per pass through two LDS buffers, 3x3 or 1x1 windows on a multiple
     // of 8 input channels.
-    auto try_chws = [&](int cb, bool forced, int nw = 8, int tm = 256) -> bool {
+    auto try_chws = [&](int cb, bool forced, int nw = 8, int tm = 256, bool halo = false) -> bool {
         if (!((kh == 3 && kw == 3) || (kh == 1 && kw == 1))) return false;
         // its tiles are 256 pixels of one image: small images (13x13, 7x7) would leave a third
         // and more of every tile empty and stay with the 128-pixel tiles of the plain kernels
-        if (!forced && 4 * ohw < 3 * cdiv(ohw, tm) * tm) return false;
-        if (Cin % 8 != 0 || Cin < 16 || pool || p.residual || ncb < 2) return false;
+        if (!forced && !pool && 4 * ohw < 3 * cdiv(ohw, tm) * tm) return false;
+        if (Cin % 8 != 0 || Cin < 16 || p.residual || ncb < 2) return false;
         if (cb != 2 && cb != 4) return false;
+        // fused pooling: 3x3 windows, the 64-channel tilings and the 128-channel one on 12 wavefronts; a tile is whole rows
+        if (pool && (kh != 3 || !((cb == 2 && nw == 8) || (cb == 4 && nw == 12)) || (halo ? 3 : 2) * OW > tm)) return false;
         ConvParams q = p;
         q.variant = CONV_CHWS;
         q.CB = cb;
@@ -624,6 +626,28 @@ merit_status derive_conv(merit_plan *pl)
         q.tiles_per_image = (int)cdiv(ohw, q.TM);
         q.rows_out_max = (int)((q.TM + OW - 2) / OW + 1);
         if (q.rows_out_max > OH) q.rows_out_max = (int)OH;
+        if (pool) {
+            // R whole rows per tile.  Carried row above (R even, R / 2 pooled rows per tile): bands of PB
+            // pooled rows, a multiple of R / 2, about one band per compute unit (every band below the
+            // first computes a tile more).  Computed row above (R odd, (R - 1) / 2 pooled rows): a
+            // band is one tile.
+            int64_t R = q.TM / OW;
+            if (halo) { if (R % 2 == 0) --R; if (R > OH + 1) R = OH + 1; }
+            else { R &= ~1ll; if (R > OH) R = OH; }
+            const int64_t hp = R / 2;
+            q.rows_out_max = (int)R;
+            q.pool_halo = halo ? 1 : 0;
+            q.PH = (int)(OH / 2); q.PW = (int)(OW / 2);
+            int64_t nb = 256 / (N * q.co_groups);
+            if (nb < 1) nb = 1;
+            int64_t pb = halo ? hp : round_up(cdiv(q.PH, nb), hp);
+            q.PB = (int)pb;
+            q.NB = (int)cdiv(q.PH, pb);
+            q.pw8 = (int)cdiv(q.PW, 4);                       // units of 4 pooled pixels per pooled row
+            if (!fastdiv_ok(N * q.NB, q.NB) || !fastdiv_ok((hp + 1) * q.pw8, q.pw8)) return false;
+            q.div_nb = make_fastdiv((uint32_t)q.NB);
+            q.div_pw8 = make_fastdiv((uint32_t)q.pw8);
+        }
         q.RHa = (int)((q.rows_out_max - 1) * sh + eh);
         q.front = 0; q.aligned = 0; q.ws = 0; q.su = 0; q.lg_chunks = 0; q.pipe = 0;
         q.G = q.G2 = 0;
@@ -646,6 +670,13 @@ merit_status derive_conv(merit_plan *pl)
         if (total > LDS_LIMIT) return false;
         q.lds_w_bytes = (int)w_bytes; q.lds_x_bytes = (int)x_bytes; q.lds_buf_bytes = (int)(w_bytes + x_bytes);
         q.lds_o_offset = 0; q.lds_o_bytes = (int)o_bytes; q.lds_total = (int)total;
+        if (pool) {
+            // two carry buffers (the last row of a tile, every channel) behind the pass buffers / staging area
+            const int64_t carry = 2 * (int64_t)cb * 32 * (OW / 2) * 4 + 16;
+            q.lds_o_offset = (int)round_up(total, 16);
+            q.lds_total = (int)(q.lds_o_offset + carry);
+            if (q.lds_total > LDS_LIMIT) return false;
+        }
         // staging units per moving thread and pass: 8 channels x 8 pixels (two at most), or x 1 pixel (four)
         if ((W % 8) == 0) {
             const int64_t nu = 2 * ng * (int64_t)q.RHa * (W / 8);
@@ -659,7 +690,7 @@ merit_status derive_conv(merit_plan *pl)
             q.xu = (int)cdiv(nu, 256);
             q.div_w = make_fastdiv((uint32_t)W);
         }
-        const int64_t nitems = N * q.tiles_per_image * q.co_groups;
+        const int64_t nitems = pool ? N * q.NB * q.co_groups : N * q.tiles_per_image * q.co_groups;
         if (nitems >= (1ll << 30) || !fastdiv_ok(nitems + 256, q.co_groups) || !fastdiv_ok(2 * ng * (int64_t)q.RHa, q.RHa) ||
             !fastdiv_ok(ohw, OW) || !fastdiv_ok(N * q.tiles_per_image, q.tiles_per_image))
             return false;
@@ -677,12 +708,43 @@ merit_status derive_conv(merit_plan *pl)
     // planar kernel, 8 x 32.  256-pixel tiles when that still leaves a large grid.
     const bool want_big = N * cdiv(ohw, 256) * p.co_groups >= 512;
     bool ok = false;
-    if (pool) {
-        // only the wave-specialised kernel pools; a tile request must name it (8 x 64) or nothing
+    if (pool && Cin >= 8) {
+        // many input channels: the wave-specialised multi-pass kernel pools out of its staging area.
+        // A tile request names one of its tilings: 8 x 64 (256 pixels x 64 channels), 8 x 32 (128 x 64),
+        // 12 x 64 (256 x 128).
+        const bool req = pl->tile_req[2] > 0 && pl->tile_req[3] > 0;
+        const int64_t rw = pl->tile_req[2], rp = pl->tile_req[3];
+        if (req && !((rw == 8 && (rp == 64 || rp == 32)) || (rw == 12 && rp == 64))) return MERIT_ERR_UNSUPPORTED;
+        // Six candidates: 256 x 64, 128 x 64 or 256 x 128 tiles, the row above a tile's first pooled
+        // row carried from the tile before or computed by the tile itself.  Estimated time = rounds of
+        // the grid x tiles per workgroup x cost of a tile (256 x 64: 1, 128 x 64: 0.6, 256 x 128: 1.6; from timings).
+        int best_tm = 0, best_cb = 0; bool best_halo = false; double best = 0.0;
+        for (int cand = 0; cand < 6; ++cand) {
+            const int shape = cand >> 1;                       // 0: 256 x 64, 1: 128 x 64, 2: 256 x 128
+            const int tm = shape == 1 ? 128 : 256, cb = shape == 2 ? 4 : 2, nw = shape == 2 ? 12 : 8;
+            const bool halo = (cand & 1) != 0;
+            if (req && !(rw == nw && rp == (shape == 1 ? 32 : 64))) continue;
+            if (cb == 4 && ncb < 4) continue;
+            const ConvParams saved = p;
+            const bool fits = try_chws(cb, true, nw, tm, halo);
+            const ConvParams q = p;
+            p = saved;
+            if (!fits) continue;
+            const int64_t items = N * q.NB * q.co_groups;
+            const int64_t hp = q.rows_out_max / 2;
+            const int64_t per_item = cdiv(q.PB, hp) + (halo || q.NB == 1 ? 0 : 1);
+            const double cost = (double)cdiv(items, 256) * (double)per_item * (shape == 0 ? 1.0 : (shape == 1 ? 0.6 : 1.6));
+            if (!best_tm || cost < best) { best_tm = tm; best_cb = cb; best_halo = halo; best = cost; }
+        }
+        ok = best_tm != 0 && try_chws(best_cb, true, best_cb == 4 ? 12 : 8, best_tm, best_halo);
+        if (!ok) return MERIT_ERR_UNSUPPORTED;
+    } else if (pool) {
+        // few input channels: the wave-specialised planar kernel pools; a tile request must name it (8 x 64) or nothing
         if (pl->tile_req[2] > 0 && pl->tile_req[3] > 0 && (pl->tile_req[2] != 8 || pl->tile_req[3] != 64))
             return MERIT_ERR_UNSUPPORTED;
+        if (OW % 16 != 0) return MERIT_ERR_UNSUPPORTED;    // it pools 8 columns at a time
         want_ws = true;
-        ok = Cin < 8 && try_variant(CONV_PLANAR_SMALLC, 2, 4) && p.ws;
+        ok = try_variant(CONV_PLANAR_SMALLC, 2, 4) && p.ws;
         if (!ok) return MERIT_ERR_UNSUPPORTED;
         p.PH = (int)(OH / 2); p.PW = (int)(OW / 2); p.pw8 = p.PW / 8;
         // bands of pooled rows: about one workgroup per compute unit, but at least 4 rows per
@@ -780,13 +842,18 @@ merit_status derive_conv(merit_plan *pl)
         if (pool) li.grid[0] = (int64_t)N * p.NB;          // one workgroup per band, not persistent
         if (p.variant == CONV_DIRECT) li.grid[0] = nt;     // one workgroup per 256 pixels x 8 channels
         if (p.variant == CONV_CHWS) li.grid[0] = nt * p.co_groups < 256 ? nt * p.co_groups : 256;   // (tile, channel block) items
+        if (p.variant == CONV_CHWS && pool) {                                                       // (band, channel block) items
+            const int64_t nb = (int64_t)N * p.NB * p.co_groups;
+            li.grid[0] = nb < 256 ? nb : 256;
+        }
     }
     li.grid[1] = (p.variant == CONV_DIRECT || p.variant == CONV_CHWS) ? 1 : p.co_groups; li.grid[2] = 1;
     li.block[0] = p.ws ? 512 : p.NW * 64; li.block[1] = 1; li.block[2] = 1;
     li.lds_bytes = (int64_t)conv_lds_bytes(p);
     li.tile[0] = 1; li.tile[1] = p.CB * 32; li.tile[2] = p.rows_out_max; li.tile[3] = OW;
     li.tile[4] = Cin; li.tile[5] = kh; li.tile[6] = kw;
-    if (pool) li.tile[2] = 2 * (p.PB + 1);                 // convolution rows a band computes
+    // convolution rows a band computes: its own and the row pair (few-channel kernel) or tile above
+    if (pool) li.tile[2] = p.variant == CONV_CHWS ? ((p.pool_halo || p.NB == 1) ? p.rows_out_max * (int)cdiv(p.PB, p.rows_out_max / 2) : 2 * p.PB + p.rows_out_max) : 2 * (p.PB + 1);
     return MERIT_OK;
 }
 

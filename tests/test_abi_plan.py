@@ -117,10 +117,46 @@ def test_fused_pooling_plan():
     for bad in ((2, 3, 62, 62, 8, 7, 7, 2, 2, 3, 3),        # 31 x 31 result: odd height
                 (2, 3, 64, 48, 8, 7, 7, 2, 2, 3, 3),        # 24 columns: not a multiple of 16
                 (2, 3, 32, 256, 8, 3, 3, 1, 1, 1, 1),       # a row pair does not fit a tile
-                (2, 16, 32, 32, 8, 3, 3, 1, 1, 1, 1)):      # many input channels: other kernel family
+                (2, 16, 32, 32, 8, 3, 3, 1, 1, 1, 1),       # many input channels, fewer than 33 output channels
+                (2, 16, 32, 32, 64, 5, 5, 1, 1, 2, 2),      # many input channels: 3x3 windows only
+                (2, 16, 31, 33, 64, 3, 3, 1, 1, 1, 1),      # odd result
+                (2, 64, 8, 224, 64, 3, 3, 1, 1, 1, 1)):     # a row pair does not fit the largest tile
         with pytest.raises(mb.MeritError) as e:
             mb.merit_plan_conv2d_pool(*bad, 1)
         assert e.value.status == mb.MERIT_ERR_UNSUPPORTED
+
+
+def test_fused_pooling_plan_many_channels():
+    """The same fusion on the wave-specialised multi-pass kernel (3x3 layers with at least 16
+    input and 33 output channels): work items are bands of pooled rows, tiles whole rows."""
+    plan = mb.merit_plan_conv2d_pool(8, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1, 1)
+    assert plan.desc().op == mb.MERIT_OP_CONV_DOT_RELU_POOLMAX and plan.out_shape() == (8, 64, 28, 28)
+    li = plan.launch_info()
+    # 256-pixel tiles of 3 rows = the row above + 1 pooled row; 8 images x 28 tiles
+    assert li["kernel"] == "merit_conv2d_chws_pool" and li["block"][0] == 512 and li["tile"][1] == 64
+    assert li["grid"][:2] == (224, 1) and li["tile"][2] == 3 and li["lds_bytes"] <= 160 * 1024
+    plan.set_tile((0, 0, 8, 32))       # 128-pixel tiles: 2 rows, the row above carried from the tile before; a band below the top computes that tile too
+    li = plan.launch_info()
+    assert li["kernel"] == "merit_conv2d_chws_pool" and li["grid"][0] == 8 * 28 and li["tile"][2] == 4
+    plan.set_tile((0, 0, 8, 64))
+    assert plan.launch_info()["tile"][2] == 3
+    with pytest.raises(mb.MeritError):
+        plan.set_tile((0, 0, 12, 64))
+    with pytest.raises(mb.MeritError):
+        mb.merit_plan_packed_weights_bytes(plan)           # the pooling kernel reads the caller's weights
+    # many images: bands of 2 pooled rows, 4-row tiles with the row above carried
+    many = mb.merit_plan_conv2d_pool(32, 16, 24, 56, 64, 3, 3, 1, 1, 1, 1, 1)
+    many.set_tile((0, 0, 8, 64))
+    li = many.launch_info()
+    assert li["grid"][0] == 32 * 6 and li["tile"][2] == 2 * 2 + 4
+    wide = mb.merit_plan_conv2d_pool(8, 128, 112, 112, 128, 3, 3, 1, 1, 1, 1, 0)
+    li = wide.launch_info()
+    # 128 output channels: 256 x 128 tiles on 12 wavefronts; two rows of 112 per tile, 8 images x 28 bands of 2 pooled rows
+    assert li["kernel"] == "merit_conv2d_chws_pool" and li["block"][0] == 768 and li["tile"][1] == 128
+    assert li["grid"][0] == 224 and li["tile"][2] == 6 and li["lds_bytes"] <= 160 * 1024
+    assert wide.out_shape() == (8, 128, 56, 56)
+    wide.set_tile((0, 0, 8, 64))                           # 64-channel tiles on request
+    assert wide.launch_info()["tile"][1] == 64 and wide.launch_info()["block"][0] == 512
 
 
 def test_residual_plan():

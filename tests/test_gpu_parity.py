@@ -617,22 +617,43 @@ POOLFUSE_CASES = [
     (1, 2, 8, 16, 8, 3, 3, 1, 1, 1, 1, 1),      # smallest: one unit per pooled row
 ]
 
+# the same fusion on many input channels: the wave-specialised multi-pass kernel pools its staging area
+POOLFUSE_CHWS_CASES = [
+    # N Cin H   W  Cout kh kw sh sw ph pw relu, tile request
+    (8, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1, 1, None),       # the 56x56 / 64-channel layer: 3-row tiles (the row above computed), one pooled row each
+    (2, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1, 0, (0, 0, 8, 64)),  # the same tiling on request; no clipping
+    (1, 16, 12, 20, 64, 3, 3, 1, 1, 1, 1, 0, None),       # W % 8 != 0: one-pixel staging; 10 pooled columns: 2-byte stores
+    (2, 32, 28, 28, 96, 3, 3, 1, 1, 1, 1, 1, None),       # 14 pooled columns, second channel block half empty
+    (1, 64, 16, 112, 64, 3, 3, 1, 1, 1, 1, 1, None),      # widest rows the 256-pixel tile takes two of
+    (3, 24, 36, 40, 64, 3, 3, 1, 1, 1, 1, 0, (0, 0, 8, 64)),  # 6 rows per tile, padded last pass (24 channels)
+    (1, 16, 48, 48, 64, 3, 3, 2, 2, 1, 1, 1, None),       # stride-2 convolution below the pooling
+    (150, 16, 16, 16, 64, 3, 3, 1, 1, 1, 1, 1, None),     # more bands than compute units: several items per workgroup
+    (1, 40, 8, 8, 70, 3, 3, 1, 1, 1, 1, 0, None),         # smallest image here: whole image in one tile, ragged channels
+    (2, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1, 1, (0, 0, 8, 32)),  # 128-pixel tiles: the row above carried, a warm-up tile per band
+    (2, 32, 28, 56, 160, 3, 3, 1, 1, 1, 1, 1, (0, 0, 12, 64)),  # 128-channel tiles on 12 wavefronts (second block: 32 channels), the row above computed
+    (1, 32, 16, 112, 128, 3, 3, 1, 1, 1, 1, 0, (0, 0, 12, 64)),  # the same tiling, two rows of 112: the row above carried
+    (32, 16, 24, 56, 64, 3, 3, 1, 1, 1, 1, 1, (0, 0, 8, 64)),  # many images: 256-pixel tiles of 4 rows, carried row, 6 bands per image
+]
+
 
 def _window_max_abs(a):
     """max |a| over the 3x3 / stride 2 / padding 1 window of every pooled position."""
     return oracle.pool2d(np.abs(a).astype(np.float32), (3, 3), (2, 2), (1, 1), "max").astype(np.float64)
 
 
-@pytest.mark.parametrize("case", POOLFUSE_CASES)
+@pytest.mark.parametrize("case", POOLFUSE_CASES + POOLFUSE_CHWS_CASES)
 def test_conv_pool_fused(mb, case):
-    N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, relu = case
-    rng = np.random.default_rng(abs(hash(case)) % 2 ** 31)
+    N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, relu = case[:12]
+    tile = case[12] if len(case) > 12 else None
+    rng = np.random.default_rng(abs(hash(case[:12])) % 2 ** 31)
     x = rng.standard_normal((N, Cin, H, W)).astype(np.float16)
     w = (rng.standard_normal((Cout, Cin, kh, kw)) / np.sqrt(Cin * kh * kw)).astype(np.float16)
     plan = mb.merit_plan_conv2d_pool(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, relu)
+    if tile is not None:
+        plan.set_tile(tile)
     info = plan.launch_info()
     print("conv+pool", case, info, flush=True)
-    assert info["kernel"] == "merit_conv2d_planar_ws_pool"
+    assert info["kernel"] == ("merit_conv2d_planar_ws_pool" if Cin < 8 else "merit_conv2d_chws_pool")
     buf, y, p = guarded_empty(plan.out_shape(), torch.float16, 777.0)
     mb.merit_conv2d(plan, dev(x), dev(w), y)
     torch.cuda.synchronize()
@@ -647,8 +668,14 @@ def test_conv_pool_fused(mb, case):
     err = np.abs(got - ref)
     assert np.all(err <= tol), f"max excess {np.max(err - tol)} at {np.unravel_index(np.argmax(err - tol), err.shape)}"
     # (2) exactly the pooled maximum of what the unfused kernel rounds to
+    # (the unfused plan on the same kernel family: the same order of summation.  The single-pass kernel,
+    # which the planner prefers for fewer than 32 input channels, rounds a few sums per 10^4 the other way.)
     make = mb.merit_plan_conv2d_relu if relu else mb.merit_plan_conv2d
-    plain = mb.merit_conv2d(make(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw), dev(x), dev(w)).cpu().numpy()
+    unfused = make(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw)
+    if Cin >= 8:
+        unfused.set_tile((0, 0, 8, 64))
+        assert unfused.launch_info()["kernel"] == "merit_conv2d_chws"
+    plain = mb.merit_conv2d(unfused, dev(x), dev(w)).cpu().numpy()
     exact = oracle.pool2d(plain.astype(np.float32), (3, 3), (2, 2), (1, 1), "max").astype(np.float64)
     assert np.array_equal(got, exact)
 
