@@ -181,9 +181,10 @@ merit_status merit_plan_conv2d_dilated(int N, int Cin, int H, int W, int Cout, i
 /* Convolution, optional clipping (relu != 0), then max pooling with a 3x3 window, stride 2,
  * padding 1 (-inf outside) of the binary16 convolution result, as one kernel: the convolution
  * output never reaches memory (the fused "CONV+Pool" layers of the per-layer table in
- * Section VI-C).  Output [N,Cout,OH/2,OW/2].  Built on the kernel for few input channels:
- * Cin < 8, W % 8 == 0, OH even, OW % 16 == 0 and OW <= 128; anything else is
- * MERIT_ERR_UNSUPPORTED (run merit_conv2d and merit_pool2d one after the other). */
+ * Section VI-C).  Output [N,Cout,OH/2,OW/2].  Two kernel families take it: few input
+ * channels (Cin < 8, window rows of at most 8 taps, W % 8 == 0, OH even, OW % 16 == 0, OW <= 128)
+ * and 3x3 windows on many (Cin % 8 == 0, Cin >= 16, Cout >= 33, OH and OW even, OW <= 128);
+ * anything else is MERIT_ERR_UNSUPPORTED (run the two operations one after the other). */
 merit_status merit_plan_conv2d_pool(int N, int Cin, int H, int W, int Cout, int kh, int kw,
                                     int sh, int sw, int ph, int pw, int relu, merit_plan **out);
 /* Residual layer (Section III-B, remark after Listing 1): y = x (*) w + r, or
@@ -227,10 +228,15 @@ merit_status merit_plan_launch_info(const merit_plan *plan, merit_launch_info *o
  * passes tile sizes next to the ranges (Section VI-A, Listing 3).  Entries <= 0
  * keep the library's choice.  Honoured entries: pooling tile[2] = output rows
  * (and tile[3] = output columns when the generic kernel is used); convolution
- * tile[2] = wavefronts per workgroup (4, or 8 for few input channels) and
- * tile[3] = consecutive output pixels per multiplying wavefront (32 or 64),
- * where 8 x 64 means 4 multiplying + 4 data-moving wavefronts (256 pixels per
- * workgroup) and every other pair tile[2]*tile[3] pixels; block matching
+ * tile[2] = wavefronts per workgroup and tile[3] = consecutive output pixels per
+ * multiplying wavefront.  4 x 32, 4 x 64 and (fewer than 8 input channels) 8 x 32:
+ * every wavefront stages, multiplies and stores, tile[2]*tile[3] pixels per
+ * workgroup.  8 x 64: 4 multiplying + 4 data-moving wavefronts, 256 pixels per
+ * workgroup (x 64 output channels).  On 8 and more input channels (3x3 and 1x1
+ * windows, Cin % 8 == 0) also 8 x 128 (256 pixels x 128 channels), 8 x 32 (128
+ * pixels x 64 channels, 32 input channels per pass) and 12 x 64 (8 multiplying +
+ * 4 moving wavefronts, 256 pixels x 128 channels); a fused-pooling plan on many
+ * channels takes 8 x 64, 8 x 32 and 12 x 64.  Block matching
  * tile[1] = blocks per workgroup (1, 4 or 8; a value the shape has no kernel for
  * keeps the library's choice); separable filter tile[1] = staged rows per workgroup
  * at most (output rows = that minus k - 1, rounded down to a multiple of 4).  On error
