@@ -24,16 +24,6 @@
 #include <atomic>
 #include <mutex>
 
-#ifndef MERIT_CHWS_EXPERIMENT
-#define MERIT_CHWS_EXPERIMENT 0     // 2: the multiplying wavefronts skip the K loop (wrong results), 9: in-kernel phase timing printed by one workgroup
-#endif
-#if MERIT_CHWS_EXPERIMENT == 9
-#define TS() __builtin_amdgcn_s_memrealtime()
-#define TIMED(acc, stmt) do { const unsigned long long t0_ = TS(); stmt; acc += TS() - t0_; } while (0)
-#else
-#define TIMED(acc, stmt) do { stmt; } while (0)
-#endif
-
 namespace merit {
 
 namespace {
@@ -156,9 +146,6 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
         const uint32_t warm = ka[0] ^ ka[16] ^ ka[32] ^ ka[48] ^ ka[64] ^ ka[80];
         asm volatile("" ::"s"(warm));
     }
-#if MERIT_CHWS_EXPERIMENT == 9
-    const unsigned long long tentry = TS();
-#endif
     extern __shared__ __align__(16) uint8_t smem[];
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6, h = lane >> 5, c32 = lane & 31;
@@ -494,9 +481,6 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
         // registers were requested a period ago, to the other buffer; start its packed weights;
         // request pass ck+2 (or pass 0 / 1 of the next item).  The registers are free again only
         // after the commit, so one pass is in flight at a time, for a whole period.
-#if MERIT_CHWS_EXPERIMENT == 9
-        unsigned long long tc = 0, tr = 0, tb = 0, tw = 0;
-#endif
         Geom g = geom_at(item, 0);
         setup(g);
         request(g, 0);
@@ -511,24 +495,24 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
             weights_landed();                                  // (waits for the request too: once per item)
             __syncthreads();                                   // P
             for (int ck = 0; ck < npass; ++ck) {
-                if (MERIT_CHWS_EXPERIMENT != 1 && ck + 1 < npass) {
-                    TIMED(tc, commit((ck + 1) & 1));
+                if (ck + 1 < npass) {
+                    commit((ck + 1) & 1);
                     weights_direct(g.cg, ck + 1, (ck + 1) & 1);
                     if constexpr (XV) {
                         // the packed weights have the rest of the period to land: wait until only
                         // the request that follows them is still in flight
                         if (ck + 2 < npass) {
-                            TIMED(tr, request(g, ck + 2));
+                            request(g, ck + 2);
                             if constexpr (PACKED) __builtin_amdgcn_s_waitcnt((8 * XU) | (0x7 << 4) | (0xF << 8));
                         } else {
-                            TIMED(tw, weights_landed());
+                            weights_landed();
                         }
                     } else {
-                        TIMED(tw, weights_landed());
-                        if (ck + 2 < npass) TIMED(tr, request(g, ck + 2));
+                        weights_landed();
+                        if (ck + 2 < npass) request(g, ck + 2);
                     }
                 }
-                TIMED(tb, __syncthreads());                    // B_ck
+                __syncthreads();                    // B_ck
             }
             // the next item's first pass flies under the result stores
             if (more) { setup(gn); request(gn, 0); }
@@ -539,17 +523,10 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
             if (!more) break;
             g = gn; item = item2; ti = ti2; ntile = ntile2;
         }
-#if MERIT_CHWS_EXPERIMENT == 9
-        if (blockIdx.x == 7 && tid == 256)
-            printf("mover: commit %llu request %llu wait-weights %llu barrier %llu (x10 ns) npass %d\n", tc, tr, tw, tb, npass);
-#endif
         return;
     }
 
     // ---- the multiplying wavefronts ----
-#if MERIT_CHWS_EXPERIMENT == 9
-    unsigned long long tk = 0, tb = 0, t0, tstart = TS();
-#endif
     const int wm = wave % WM, wn = wave / WM;
     for (bool more = true; more; more = next_pos(item, ti, ntile)) {
         const Geom g = geom_at(item, ti);
@@ -573,9 +550,6 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[cb][pb][r] = 0.0f;
         __syncthreads();                                       // P
-#if MERIT_CHWS_EXPERIMENT == 9
-        const unsigned long long tfill = TS() - tentry;
-#endif
 
         for (int ck = 0; ck < npass; ++ck) {
             const uint4 *wl = wbuf(ck & 1) + (wn * CHB * 2 + h) * 32 + (c32 ^ (h * 8));
@@ -587,25 +561,13 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
                 const int ky = T == 9 ? tap / 3 : 0, kx = T == 9 ? tap % 3 : 0;
                 const int xgrp = gp * 2 * p.RHa * p.pitch;
 #pragma unroll
-                for (int cb = 0; cb < CHB; ++cb) {
-                    if (MERIT_CHWS_EXPERIMENT == 4 && s > 0) a[slot][cb] = a[0][cb];
-                    else a[slot][cb].u = wl[(s * NCB + cb) * 64];
-                }
+                for (int cb = 0; cb < CHB; ++cb) a[slot][cb].u = wl[(s * NCB + cb) * 64];
 #pragma unroll
-                for (int pb = 0; pb < PXB; ++pb) {
-                    if ((MERIT_CHWS_EXPERIMENT == 3 || MERIT_CHWS_EXPERIMENT == 4) && s > 0) b[slot][pb] = b[0][pb];
-                    else b[slot][pb].u = xl[xc[pb][kx] + ky * rowstep + xgrp];
-                }
+                for (int pb = 0; pb < PXB; ++pb) b[slot][pb].u = xl[xc[pb][kx] + ky * rowstep + xgrp];
             };
             // the reads of step s+1 are issued before the MFMAs of step s and stay there (left to
             // itself the scheduler sinks them to their first use, and the matrix core idles for
             // an LDS round trip per step)
-#if MERIT_CHWS_EXPERIMENT == 2
-            if (p.N > 0) { __syncthreads(); continue; }
-#endif
-#if MERIT_CHWS_EXPERIMENT == 9
-            t0 = TS();
-#endif
             load(0, 0);
 #pragma unroll
             for (int s = 0; s < NG * T; ++s) {
@@ -619,15 +581,7 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
                                                                              acc[cb][pb], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
-#if MERIT_CHWS_EXPERIMENT == 9
-            asm volatile("s_nop 0" :: "v"(acc[0][0][0]), "v"(acc[CHB - 1][PXB - 1][15]));
-            tk += TS() - t0;
-            t0 = TS();
-#endif
             __syncthreads();                                   // B_ck
-#if MERIT_CHWS_EXPERIMENT == 9
-            tb += TS() - t0;
-#endif
         }
 
         // accumulators -> LDS [channel][pixel].  Accumulator register r of lane l is output
@@ -656,23 +610,11 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
                         *reinterpret_cast<uint2 *>(outl + ch * OP + (wm * PXB + pb) * 16 + 4 * q + 2 * h) = v;
                     }
         }
-#if MERIT_CHWS_EXPERIMENT == 9
-        const unsigned long long te0 = TS();
-#endif
         __syncthreads();                                       // E1
         if constexpr (POOL) pool_out(g);
         else store_out(g);
         __syncthreads();                                       // E2
-#if MERIT_CHWS_EXPERIMENT == 9
-        if (blockIdx.x == 7 && tid == 0)
-            printf("mfma item: entry->first pass %llu, acc->LDS done at %llu, stores issued at %llu (x10 ns since entry)\n",
-                   tfill, te0 - tentry, TS() - tentry);
-#endif
     }
-#if MERIT_CHWS_EXPERIMENT == 9
-    if (blockIdx.x == 7 && tid == 0)
-        printf("mfma: kloop %llu barrier %llu total %llu (x10 ns)\n", tk, tb, TS() - tstart);
-#endif
 }
 
 // Rewrites w[Cout][Cin][kh][kw] into the order the passes of merit_conv2d_chws read it: for every
