@@ -252,6 +252,12 @@ def bench_conv(torch, mb, wl, cfg, steps, warmup, nsets, relu=False, pool=False,
         "achieved_hbm_gbs": (in_bytes + out_bytes) / t / 1e9,
         "hbm_frac": (in_bytes + out_bytes) / t / 1e9 / HBM_PEAK_GBS,
         "rotating_sets": ns,
+        # the roof that binds this layer: whichever of its MFMA time and its HBM time at peak is longer
+        "roofline": ({"bound": "mfma", "achieved": flops / t / 1e12, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                      "frac": flops / t / 1e12 / MFMA_F16_PEAK_TFLOPS}
+                     if flops / (MFMA_F16_PEAK_TFLOPS * 1e12) >= (in_bytes + out_bytes) / (HBM_PEAK_GBS * 1e9) else
+                     {"bound": "hbm", "achieved": (in_bytes + out_bytes) / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                      "frac": (in_bytes + out_bytes) / t / 1e9 / HBM_PEAK_GBS}),
     }
 
 
