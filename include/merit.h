@@ -110,7 +110,7 @@ typedef struct {
  * range[] lists the extents of k = (p, a): n_par parallel indices first, then
  * n_acc accumulation indices (the NDRange of Section III-C, Eq. 6).
  *
- * Accepted patterns (anything else: MERIT_ERR_UNSUPPORTED)
+ * Patterns with a specialised kernel
  *   CONV_DOT   F16 ZERO     k=(n,co,oy,ox | ci,ky,kx)  a = x[N,Cin,H,W], b = w[Cout,Cin,kh,kw]
  *   CONV_DOT_RELU           same
  *   POOL_MAX   F32 NEG_INF  k=(n,c,oy,ox | ky,kx)      a = x[N,C,H,W],   b unused (ndim 0)
@@ -122,7 +122,18 @@ typedef struct {
  *                                                      b = x2[N,C,H,W] at (p1+(p3-R)*sd, p2+(p4-R)*sd)
  * with output extents equal to floor((I + 2*pad - e)/s) + 1, e = (k-1)*d + 1.  The
  * strides d of the window indices ky, kx must be 1 for pooling; for the CONV ops they are
- * the dilation (Section III-C, the example after Eq. 6), up to 16. */
+ * the dilation (Section III-C, the example after Eq. 6), up to 16.
+ *
+ * Any other descriptor of a dot product (CONV_DOT, CONV_DOT_RELU, DWCONV_DOT, CORR_DOT: F16,
+ * padding ZERO or CLAMP, two operands) or of a single-operand reduction (POOL_MAX: F32, any
+ * padding rule; POOL_AVG: F32, EXCLUDE, ZERO or CLAMP) runs on one kernel that evaluates Eq. 5
+ * as it reads, a thread per row of M(A), M(B): any number of indices up to MERIT_MAX_INDEX with at
+ * most MERIT_MAX_DIMS parallel ones, any axis, stride (negative too) and offset per index,
+ * ranges of at least 1 for the accumulation indices.  Its output is the dense tensor of the
+ * parallel ranges; it goes through the entry point of the descriptor's operation (merit_conv2d
+ * for CONV_DOT / CONV_DOT_RELU with a = x, b = w).  launch_info().kernel names it
+ * ("merit_generic<dot|max|mean>"); it takes no tile request.  Everything else is
+ * MERIT_ERR_UNSUPPORTED. */
 typedef struct {
     merit_op      op;
     merit_dtype   dtype;

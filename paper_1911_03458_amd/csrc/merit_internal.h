@@ -256,6 +256,30 @@ int conv_direct_channels();     // output channels per workgroup of the one-elem
 
 }  // namespace merit
 
+// ---- any descriptor: the definition, one thread per row ------------------------
+namespace merit {
+struct GenericOperand {
+    int ndim;
+    int shape[MERIT_MAX_DIMS];
+    long long pitch[MERIT_MAX_DIMS];      // elements between neighbours along each axis (dense, row-major)
+    int axis[MERIT_MAX_INDEX];            // d_j, -1: the index does not move this operand
+    int stride[MERIT_MAX_INDEX];          // s_j
+    int offset[MERIT_MAX_INDEX];          // o_j
+};
+struct GenericParams {
+    int mode;                             // 0 dot product (binary16), 1 maximum, 2 mean (fp32)
+    int pad;                              // merit_pad
+    int relu;
+    int n_par, n_acc;
+    int range[MERIT_MAX_INDEX];
+    long long rows;                       // product of the parallel ranges = output elements
+    long long acc;                        // product of the accumulation ranges
+    GenericOperand a, b;
+};
+hipError_t launch_generic(const GenericParams &p, const void *a, const void *b, void *y, hipStream_t s);
+const char *generic_kernel_name(const GenericParams &p);
+}  // namespace merit
+
 struct merit_plan {
     merit_plan_desc desc;
     int64_t tile_req[MERIT_MAX_INDEX];   // caller's tile override, 0 = library default
@@ -268,5 +292,7 @@ struct merit_plan {
     merit::DwParams dw;
     merit::SepParams sep;
     merit::BilatParams bil;
+    int generic;                          // 1: no specialised kernel took the descriptor; `gen` runs it
+    merit::GenericParams gen;
     merit_launch_info info;
 };

@@ -1007,6 +1007,97 @@ merit_status derive_corr(merit_plan *pl)
     return MERIT_OK;
 }
 
+// ------------------------------------------------ any descriptor (Eq. 1, Eq. 5) ---
+// What none of the patterns above recognises still is a ranged inner product: the definition
+// kernel (generic.hip) runs it, one thread per row.  Operations: the dot products (CONV_DOT,
+// CONV_DOT_RELU, DWCONV_DOT, CORR_DOT: binary16, zero or clamp padding, two operands) and the
+// single-operand reductions (POOL_MAX: any padding rule; POOL_AVG: exclude, zero or clamp; fp32).
+// The output is the dense tensor of the parallel ranges, so there are at most MERIT_MAX_DIMS of them.
+merit_status derive_generic(merit_plan *pl)
+{
+    const merit_plan_desc &d = pl->desc;
+    GenericParams &g = pl->gen;
+    std::memset(&g, 0, sizeof(g));
+    switch (d.op) {
+    case MERIT_OP_CONV_DOT:
+    case MERIT_OP_CONV_DOT_RELU:
+    case MERIT_OP_DWCONV_DOT:
+    case MERIT_OP_CORR_DOT:
+        if (d.dtype != MERIT_F16 || (d.pad != MERIT_PAD_ZERO && d.pad != MERIT_PAD_CLAMP) || d.b.ndim < 1)
+            return MERIT_ERR_UNSUPPORTED;
+        g.mode = 0;
+        g.relu = d.op == MERIT_OP_CONV_DOT_RELU ? 1 : 0;
+        break;
+    case MERIT_OP_POOL_MAX:
+        if (d.dtype != MERIT_F32) return MERIT_ERR_UNSUPPORTED;
+        g.mode = 1;
+        break;
+    case MERIT_OP_POOL_AVG:
+        if (d.dtype != MERIT_F32 || d.pad == MERIT_PAD_NEG_INF) return MERIT_ERR_UNSUPPORTED;
+        g.mode = 2;
+        break;
+    default: return MERIT_ERR_UNSUPPORTED;
+    }
+    if (d.n_par > MERIT_MAX_DIMS) return MERIT_ERR_UNSUPPORTED;
+    g.pad = (int)d.pad;
+    g.n_par = d.n_par; g.n_acc = d.n_acc;
+    const int nidx = d.n_par + d.n_acc;
+    int64_t rows = 1, acc = 1;
+    for (int j = 0; j < nidx; ++j) {
+        const int64_t r = d.range[j];
+        if (r >= INT_LIMIT) return MERIT_ERR_UNSUPPORTED;
+        if (j >= d.n_par && r < 1) return MERIT_ERR_INVALID_ARG;     // an empty reduction has no value
+        g.range[j] = (int)r;
+        if (j < d.n_par) { rows *= r; if (rows >= (1ll << 38)) return MERIT_ERR_UNSUPPORTED; }
+        else { acc *= r; if (acc >= (1ll << 40)) return MERIT_ERR_UNSUPPORTED; }
+    }
+    g.rows = rows; g.acc = acc;
+    auto operand = [&](const merit_operand &o, GenericOperand &q) -> merit_status {
+        q.ndim = o.ndim;
+        int64_t elems = 1;
+        for (int i = o.ndim - 1; i >= 0; --i) {
+            if (o.shape[i] < 1 || o.shape[i] >= (1ll << 31)) return MERIT_ERR_INVALID_ARG;
+            q.shape[i] = (int)o.shape[i];
+            q.pitch[i] = elems;
+            elems *= o.shape[i];
+            if (elems >= (1ll << 40)) return MERIT_ERR_UNSUPPORTED;
+        }
+        // every coordinate any k can produce stays a small integer
+        int64_t lo[MERIT_MAX_DIMS] = {0}, hi[MERIT_MAX_DIMS] = {0};
+        for (int j = 0; j < nidx; ++j) {
+            q.axis[j] = o.axis[j];
+            if (o.stride[j] <= -INT_LIMIT || o.stride[j] >= INT_LIMIT || o.offset[j] <= -INT_LIMIT || o.offset[j] >= INT_LIMIT)
+                return MERIT_ERR_UNSUPPORTED;
+            q.stride[j] = (int)o.stride[j]; q.offset[j] = (int)o.offset[j];
+            if (o.axis[j] < 0) continue;
+            const int64_t travel = (d.range[j] > 0 ? d.range[j] - 1 : 0) * o.stride[j];
+            lo[o.axis[j]] += o.offset[j] + (travel < 0 ? travel : 0);
+            hi[o.axis[j]] += o.offset[j] + (travel > 0 ? travel : 0);
+            if (lo[o.axis[j]] <= -INT_LIMIT || hi[o.axis[j]] >= INT_LIMIT) return MERIT_ERR_UNSUPPORTED;
+        }
+        return MERIT_OK;
+    };
+    if (merit_status st = operand(d.a, g.a); st != MERIT_OK) return st;
+    if (g.mode == 0) {
+        if (merit_status st = operand(d.b, g.b); st != MERIT_OK) return st;
+    } else {
+        for (int j = 0; j < MERIT_MAX_INDEX; ++j) g.b.axis[j] = -1;
+    }
+    pl->generic = 1;
+    pl->out_ndim = d.n_par;
+    for (int j = 0; j < d.n_par; ++j) pl->out_shape[j] = d.range[j];
+    merit_launch_info &li = pl->info;
+    std::memset(&li, 0, sizeof(li));
+    li.kernel = generic_kernel_name(g);
+    li.grid[0] = cdiv(rows, 256); li.grid[1] = 1; li.grid[2] = 1;
+    li.block[0] = 256; li.block[1] = 1; li.block[2] = 1;
+    li.lds_bytes = 0;
+    // a workgroup: 256 consecutive rows (the last parallel index fastest), the whole accumulation range
+    for (int j = 0; j < nidx; ++j) li.tile[j] = j < d.n_par ? 1 : d.range[j];
+    li.tile[d.n_par - 1] = d.range[d.n_par - 1] < 256 ? d.range[d.n_par - 1] : 256;
+    return MERIT_OK;
+}
+
 bool aligned16(const void *ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15u) == 0; }
 
 }  // namespace
@@ -1051,6 +1142,11 @@ merit_status merit_plan_create(const merit_plan_desc *desc, merit_plan **out)
     case MERIT_OP_SEPFILTER_DOT: st = derive_sep(pl); break;
     case MERIT_OP_BILATERAL: st = derive_bilateral(pl); break;
     default: st = derive_sad(pl); break;
+    }
+    // no specialised kernel for this descriptor: the definition kernel takes what it can
+    if (st == MERIT_ERR_UNSUPPORTED) {
+        const merit_status sg = derive_generic(pl);
+        if (sg != MERIT_ERR_UNSUPPORTED) st = sg;
     }
     if (st != MERIT_OK) {
         delete pl;
@@ -1266,6 +1362,11 @@ merit_status merit_plan_sad(int H, int W, int block, int range, merit_plan **out
 merit_status merit_plan_set_tile(merit_plan *plan, const int64_t tile[MERIT_MAX_INDEX])
 {
     if (!plan || !tile) return MERIT_ERR_NULL;
+    if (plan->generic) {                                   // the definition kernel has one shape: nothing to choose
+        for (int j = 0; j < MERIT_MAX_INDEX; ++j)
+            if (tile[j] > 0) return MERIT_ERR_UNSUPPORTED;
+        return MERIT_OK;
+    }
     merit_plan trial = *plan;
     for (int j = 0; j < MERIT_MAX_INDEX; ++j) trial.tile_req[j] = tile[j];
     merit_status st;
@@ -1333,12 +1434,22 @@ merit_status merit_plan_launch_info(const merit_plan *plan, merit_launch_info *o
     return MERIT_OK;
 }
 
+// a plan on the definition kernel: the same pointer rules as everywhere
+static merit_status run_generic(const merit_plan *plan, const void *a, const void *b, void *y, void *stream)
+{
+    if (plan->gen.rows == 0) return MERIT_OK;             // an empty parallel range: nothing to read or write
+    if (!a || !b || !y) return MERIT_ERR_NULL;
+    if (!aligned16(a) || !aligned16(b) || !aligned16(y)) return MERIT_ERR_ALIGNMENT;
+    return launch_generic(plan->gen, a, b, y, static_cast<hipStream_t>(stream)) == hipSuccess ? MERIT_OK : MERIT_ERR_HIP;
+}
+
 merit_status merit_conv2d(const merit_plan *plan, const void *x, const void *w, void *y, void *stream)
 {
     if (!plan) return MERIT_ERR_NULL;
     if (plan->desc.op != MERIT_OP_CONV_DOT && plan->desc.op != MERIT_OP_CONV_DOT_RELU &&
         plan->desc.op != MERIT_OP_CONV_DOT_POOLMAX && plan->desc.op != MERIT_OP_CONV_DOT_RELU_POOLMAX)
         return MERIT_ERR_INVALID_ARG;
+    if (plan->generic) return run_generic(plan, x, w, y, stream);
     if (plan->conv.N == 0) return MERIT_OK;               // empty batch: nothing to read or write
     if (!x || !w || !y) return MERIT_ERR_NULL;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return MERIT_ERR_ALIGNMENT;
@@ -1417,6 +1528,7 @@ merit_status merit_pool2d(const merit_plan *plan, const void *x, void *y, void *
 {
     if (!plan) return MERIT_ERR_NULL;
     if (plan->desc.op != MERIT_OP_POOL_MAX && plan->desc.op != MERIT_OP_POOL_AVG) return MERIT_ERR_INVALID_ARG;
+    if (plan->generic) return run_generic(plan, x, x, y, stream);
     if (plan->pool.NC == 0) return MERIT_OK;              // empty batch: nothing to read or write
     if (!x || !y) return MERIT_ERR_NULL;
     if (!aligned16(x) || !aligned16(y)) return MERIT_ERR_ALIGNMENT;
@@ -1472,6 +1584,7 @@ merit_status merit_conv2d_depthwise(const merit_plan *plan, const void *x, const
 {
     if (!plan) return MERIT_ERR_NULL;
     if (plan->desc.op != MERIT_OP_DWCONV_DOT) return MERIT_ERR_INVALID_ARG;
+    if (plan->generic) return run_generic(plan, x, w, y, stream);
     if (plan->dw.NC == 0) return MERIT_OK;                // empty batch: nothing to read or write
     if (!x || !w || !y) return MERIT_ERR_NULL;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return MERIT_ERR_ALIGNMENT;
@@ -1508,6 +1621,7 @@ merit_status merit_correlation(const merit_plan *plan, const void *x1, const voi
 {
     if (!plan) return MERIT_ERR_NULL;
     if (plan->desc.op != MERIT_OP_CORR_DOT) return MERIT_ERR_INVALID_ARG;
+    if (plan->generic) return run_generic(plan, x1, x2, y, stream);
     if (plan->corr.N == 0) return MERIT_OK;               // empty batch: nothing to read or write
     if (!x1 || !x2 || !y) return MERIT_ERR_NULL;
     if (!aligned16(x1) || !aligned16(x2) || !aligned16(y)) return MERIT_ERR_ALIGNMENT;

@@ -73,7 +73,9 @@ def test_relu_plan_differs_only_in_the_product_function():
     assert a.launch_info() == b.launch_info()
     # the generic constructor accepts the same descriptor
     assert mb.merit_plan_create(db).desc().op == mb.MERIT_OP_CONV_DOT_RELU
-    db.pad = mb.MERIT_PAD_CLAMP
+    db.pad = mb.MERIT_PAD_CLAMP                      # border replication: no specialised kernel, the definition kernel
+    assert mb.merit_plan_create(db).launch_info()["kernel"] == "merit_generic<dot>"
+    db.pad = mb.MERIT_PAD_NEG_INF                    # not a rule a dot product can have
     with pytest.raises(mb.MeritError):
         mb.merit_plan_create(db)
 
@@ -267,13 +269,14 @@ def test_correlation_plan_is_eq8():
     li = plan.launch_info()
     assert li["kernel"] == "merit_corr_mfma" and li["grid"][0] == 64 * 11 and li["lds_bytes"] <= 160 * 1024
     assert mb.merit_plan_create(d).out_shape() == (1, 64, 64, 11, 11)
-    d.b.offset[3] = -9                                              # not centred: no kernel
-    with pytest.raises(mb.MeritError) as e:
-        mb.merit_plan_create(d)
-    assert e.value.status == mb.MERIT_ERR_UNSUPPORTED
-    with pytest.raises(mb.MeritError) as e:
-        mb.merit_plan_correlation(1, 8, 16, 20, 2, 1)               # W not a multiple of 8
-    assert e.value.status == mb.MERIT_ERR_UNSUPPORTED
+    d.b.offset[3] = -9                                              # not centred: the definition kernel
+    off = mb.merit_plan_create(d)
+    assert off.launch_info()["kernel"] == "merit_generic<dot>" and off.out_shape() == (1, 64, 64, 11, 11)
+    odd = mb.merit_plan_correlation(1, 8, 16, 20, 2, 1)             # W not a multiple of 8: the same
+    assert odd.launch_info()["kernel"] == "merit_generic<dot>" and odd.out_shape() == (1, 16, 20, 5, 5)
+    assert odd.launch_info()["grid"][0] == -(-16 * 20 * 25 // 256) and odd.launch_info()["lds_bytes"] == 0
+    with pytest.raises(mb.MeritError):
+        odd.set_tile((0, 4))                                        # nothing to choose there
     L = mb.lib()
     assert L.merit_correlation(plan.handle, None, 16, 16, None) == mb.MERIT_ERR_NULL
     assert L.merit_conv2d(plan.handle, 16, 16, 16, None) == mb.MERIT_ERR_INVALID_ARG
@@ -385,7 +388,10 @@ def test_generic_descriptor_patterns():
     d.a.stride[5] = 1
     d.range[2] = 16
     dp = mb.merit_plan_pool2d(1, 1, 16, 16, 3, 3, 2, 2, 1, 1, 0).desc()
-    dp.a.stride[4] = 2                               # pooling windows are not dilated here
+    dp.a.stride[4] = 2                               # a dilated pooling window: none of the pooling kernels, ...
+    gp = mb.merit_plan_create(dp)                    # ... but still a ranged maximum: the definition kernel
+    assert gp.launch_info()["kernel"] == "merit_generic<max>" and gp.out_shape() == (1, 1, 8, 8)
+    dp.dtype = mb.MERIT_F16
     with pytest.raises(mb.MeritError) as e:
         mb.merit_plan_create(dp)
     assert e.value.status == mb.MERIT_ERR_UNSUPPORTED
@@ -394,7 +400,7 @@ def test_generic_descriptor_patterns():
         mb.merit_plan_create(d)
     assert e.value.status == mb.MERIT_ERR_SHAPE
     d.range[2] = 16
-    d.pad = mb.MERIT_PAD_CLAMP                       # wrong padding rule for a dot product
+    d.pad = mb.MERIT_PAD_EXCLUDE                     # wrong padding rule for a dot product
     with pytest.raises(mb.MeritError) as e:
         mb.merit_plan_create(d)
     assert e.value.status == mb.MERIT_ERR_UNSUPPORTED
