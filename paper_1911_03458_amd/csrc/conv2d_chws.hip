@@ -296,7 +296,7 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
         int x_lds[NXU][XV ? 8 : 1];         // byte address of each of its pixels inside a pass buffer's input region
         int x_hh[NXU];                      // its channel group within the pass
         uint32_t xv[XV ? XU : 1][8][4];     // the unit on its way: 8 channels x 8 pixels
-        uint16_t xs[XV ? 1 : XS_MAX][8];    // ... 8 channels x 1 pixel
+        uint32_t xs[XV ? 1 : XS_MAX][8];    // ... 8 channels x 1 pixel (a register each: see commit)
         uint32_t w_voff[WU];
         int w_lds[WU], w_hh[WU];
         uint32_t wr[PACKED ? 1 : WU][PACKED ? 1 : 4 * T];
@@ -360,7 +360,10 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
         // request the input rows (and, unless packed, the weights) of pass ck into the registers
         auto request = [&](const Geom &g, int ck) __attribute__((always_inline)) {
             const int live = (p.Cin >> 3) - ck * NGRP;          // groups of this pass that exist (the rest: padding)
-            const uint32_t xbase = ((uint32_t)g.n * (uint32_t)p.Cin + (uint32_t)(ck * NGRP * 8)) * chbytes;
+            // (the same for the whole wavefront: said explicitly, or the 2-byte loads below each get a
+            // loop over the distinct values of a vector register)
+            const uint32_t xbase = (uint32_t)__builtin_amdgcn_readfirstlane(
+                (int)(((uint32_t)g.n * (uint32_t)p.Cin + (uint32_t)(ck * NGRP * 8)) * chbytes));
 #pragma unroll
             for (int k = 0; k < NXU; ++k) {
                 if (!XV && k >= p.xu) break;
@@ -408,6 +411,10 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
                             *reinterpret_cast<uint32x4 *>(xl + x_lds[k][px]) = d;
                         }
                     } else {
+                        // the eight loads of a unit stay eight registers until here: packed in pairs
+                        // where they are requested, every pair would wait for its own memory round trip
+#pragma unroll
+                        for (int c = 0; c < 8; ++c) asm volatile("" : "+v"(xs[k][c]));
                         uint32x4 d;
                         d.x = (uint32_t)xs[k][0] | ((uint32_t)xs[k][1] << 16);
                         d.y = (uint32_t)xs[k][2] | ((uint32_t)xs[k][3] << 16);

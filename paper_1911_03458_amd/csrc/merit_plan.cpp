@@ -790,18 +790,27 @@ merit_status derive_conv(merit_plan *pl)
         if (!ok)
             ok = want_big ? (try_variant(CONV_CHBLOCK, 2, 4) || try_variant(CONV_CHBLOCK, 1, 4))
                           : (try_variant(CONV_CHBLOCK, 1, 4) || try_variant(CONV_CHBLOCK, 2, 4));
-        // 3x3 layers on at least 32 input channels (a multiple of 8) and at least 64 output channels:
-        // the wave-specialised multi-pass kernel.  Its three tilings, largest first: 256 pixels x 128
-        // channels on 12 wavefronts, 256 x 64 and 128 x 64 (32 channels per pass) on 8.  The largest
-        // one that still gives (nearly) every compute unit a workgroup is taken -- the larger the
-        // tile, the less is staged per multiply-add -- else the smallest.  (1x1 layers stay with the
+        // 3x3 layers on at least 32 input channels (a multiple of 8) and at least 33 output channels:
+        // the wave-specialised multi-pass kernel.  Its tilings: 256 pixels x 128 channels on 12
+        // wavefronts, 256 x 64 and 128 x 64 (32 channels per pass) on 8.  The one with the lowest
+        // estimate rounds of the grid x cost of a tile (1.6, 1, 0.6 from timings) is taken, the larger
+        // tile on a tie: few large tiles while they still fill the chip, else more small ones --
+        // also for images far smaller than a tile (13x13 on 256-pixel tiles: 32 us, against 98 us on
+        // the plain multi-pass kernel; 7x7 on 128-pixel tiles: 28 against 88).  (1x1 layers stay with the
         // plain kernels: a 1x1 pass is one MFMA step per 16 staged channels.)
         if (kh == 3 && kw == 3 && Cin >= 32 && (Cin % 8) == 0 && ncb >= 2) {
-            const int64_t i4 = N * cdiv(ohw, 256) * cdiv(ncb, 4), i2 = N * cdiv(ohw, 256) * cdiv(ncb, 2);
-            const bool took = (ncb >= 4 && i4 >= 192 && try_chws(4, false, 12)) || (i2 >= 192 && try_chws(2, false, 8, 256)) ||
-                              try_chws(2, false, 8, 128) || try_chws(2, false, 8, 256) ||
-                              (ncb >= 4 && try_chws(4, false, 12));
-            if (took) ok = true;
+            int best = -1; double best_cost = 0.0;
+            for (int shape = 0; shape < 3; ++shape) {          // 0: 256 x 128 on 12 wavefronts, 1: 256 x 64, 2: 128 x 64
+                if (shape == 0 && ncb < 4) continue;
+                const int64_t tm = shape == 2 ? 128 : 256;
+                const int64_t items = N * cdiv(ohw, tm) * cdiv(ncb, shape == 0 ? 4 : 2);
+                const double cost = (double)cdiv(items, 256) * (shape == 0 ? 1.6 : (shape == 1 ? 1.0 : 0.6));
+                const ConvParams saved = p;
+                const bool fits = try_chws(shape == 0 ? 4 : 2, true, shape == 0 ? 12 : 8, (int)tm);
+                p = saved;
+                if (fits && (best < 0 || cost < best_cost)) { best = shape; best_cost = cost; }
+            }
+            if (best >= 0 && try_chws(best == 0 ? 4 : 2, true, best == 0 ? 12 : 8, best == 2 ? 128 : 256)) ok = true;
         }
     }
     if (!ok) {

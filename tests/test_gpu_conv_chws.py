@@ -159,6 +159,21 @@ def test_chws_many_channel_workload_four_images(mb):
         assert np.all(np.abs(y[n:n + 1] - ref) <= 2e-2 * np.abs(ref) + 1e-3)
 
 
+def test_chws_512_channel_layer_on_28x28(mb):
+    """512 -> 512 at 28x28, batch 8 (a width that is not a multiple of 8: one-pixel staging units, 32
+    passes): the planner's own choice at full size; the oracle checks every output of two images."""
+    N, C, H, W = 8, 512, 28, 28
+    rng = np.random.default_rng(512)
+    x = rng.standard_normal((N, C, H, W)).astype(np.float16)
+    w = (rng.standard_normal((C, C, 3, 3)) / np.sqrt(C * 9)).astype(np.float16)
+    plan = mb.merit_plan_conv2d(N, C, H, W, C, 3, 3, 1, 1, 1, 1)
+    assert plan.launch_info()["kernel"] == "merit_conv2d_chws"
+    y = mb.merit_conv2d(plan, dev(x), dev(w)).cpu().numpy().astype(np.float64)
+    for n in (0, 5):
+        ref = oracle.conv2d(x[n:n + 1], w, (1, 1), (1, 1)).astype(np.float64)
+        assert np.all(np.abs(y[n:n + 1] - ref) <= 2e-2 * np.abs(ref) + 1e-3)
+
+
 def test_packed_entry_points_refuse_other_plans(mb):
     plan = mb.merit_plan_conv2d(1, 3, 32, 32, 16, 7, 7, 2, 2, 3, 3)
     with pytest.raises(mb.MeritError) as e:

@@ -1251,10 +1251,10 @@ def test_more_launches_can_be_captured_in_a_graph(mb):
     sep = mb.merit_plan_sepfilter(1, 70, 136, 30)
     kx = rng.standard_normal(30).astype(np.float32); ky = rng.standard_normal(30).astype(np.float32)
     xs = torch.zeros((1, 70, 136), dtype=torch.float32, device="cuda:0"); ys = torch.empty_like(xs)
-    cp = mb.merit_plan_conv2d(1, 264, 10, 16, 40, 3, 3, 1, 1, 1, 1)
+    cp = mb.merit_plan_conv2d(1, 264, 10, 16, 40, 5, 5, 1, 1, 2, 2)
     cd = mb.merit_plan_conv2d(1, 3, 45, 45, 6, 11, 17, 4, 4, 0, 0)
     assert cp.launch_info()["kernel"] == "merit_conv2d_chpass" and cd.launch_info()["kernel"] == "merit_conv2d_direct"
-    wp = (rng.standard_normal((40, 264, 3, 3)) / 49).astype(np.float16)
+    wp = (rng.standard_normal((40, 264, 5, 5)) / 81).astype(np.float16)
     wd = (rng.standard_normal((6, 3, 11, 17)) / 24).astype(np.float16)
     xp = torch.zeros((1, 264, 10, 16), dtype=torch.float16, device="cuda:0")
     xd = torch.zeros((1, 3, 45, 45), dtype=torch.float16, device="cuda:0")
@@ -1298,7 +1298,7 @@ def test_more_launches_can_be_captured_in_a_graph(mb):
         g.replay()
         torch.cuda.synchronize()
         assert np.all(np.abs(ys.cpu().numpy() - oracle.sepfilter(a, kx, ky)) <= _sep_tol(a, kx, ky)), rep
-        for got, ref in ((yp, oracle.conv2d(b, wp, (1, 1), (1, 1))), (yd, oracle.conv2d(c, wd, (4, 4), (0, 0))),
+        for got, ref in ((yp, oracle.conv2d(b, wp, (1, 1), (2, 2))), (yd, oracle.conv2d(c, wd, (4, 4), (0, 0))),
                          (yo, oracle.correlation(e1, e2, 3, 2))):
             gg, rr = got.cpu().numpy().astype(np.float64), ref.astype(np.float64)
             assert np.all(np.abs(gg - rr) <= 2e-2 * np.abs(rr) + 1e-3), rep
