@@ -1918,7 +1918,7 @@ hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, cons
 {
     const int64_t ntiles = (int64_t)p.N * p.tiles_per_image;
     if (ntiles == 0) return hipSuccess;
-    if (p.variant == CONV_CHWS) return launch_conv2d_chws(p, x, w, y, s, false);
+    if (p.variant == CONV_CHWS) return launch_conv2d_chws(p, x, w, r, y, s, false);
     if (p.variant == CONV_DIRECT) {                // one workgroup per 256 pixels x 8 channels
         hipLaunchKernelGGL(merit_conv2d_direct, dim3((uint32_t)ntiles), dim3(256), 0, s, p,
                            reinterpret_cast<const uint16_t *>(x), reinterpret_cast<const uint16_t *>(w),

@@ -32,6 +32,7 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef uint32_t uint32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t uint32x2 __attribute__((ext_vector_type(2)));
 
 union Frag {
     uint4 u;
@@ -121,10 +122,11 @@ constexpr uint32_t OOB = 0x80000000u;   // a buffer offset past the end of every
 // otherwise be shorter than a memory round trip).
 // POOL: the results are max-pooled (3x3 / stride 2 / padding 1) out of the staging area and only the
 // pooled tensor is written; work items are bands of pooled rows (pool_geom above).
-template <int PXB, int CHB, int WM, int WN, int T, int XU, bool PACKED, int NG = 1, bool POOL = false>
+// RES: a tensor of the output's shape is added to the fp32 sums before the clip and the rounding.
+template <int PXB, int CHB, int WM, int WN, int T, int XU, bool PACKED, int NG = 1, bool POOL = false, bool RES = false>
 __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvParams p, const uint16_t *__restrict__ x,
                                                             const uint16_t *__restrict__ w,
-                                                            uint16_t *__restrict__ y)
+                                                            const uint16_t *res, uint16_t *y)
 {
     constexpr int NMW = WM * WN;                         // multiplying wavefronts; four more move data
     static_assert(NMW == 4 || NMW == 8, "one or two multiplying wavefronts per SIMD");
@@ -140,7 +142,7 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
         // The kernel-argument block (ConvParams and three pointers: six 64-byte lines) is read with
         // scalar loads where the values are first needed; touching every line with the very first
         // instructions fetches them side by side instead of one memory trip after the other.
-        static_assert(sizeof(ConvParams) + 3 * sizeof(void *) <= 6 * 64, "six lines of kernel arguments");
+        static_assert(sizeof(ConvParams) + 4 * sizeof(void *) <= 6 * 64, "six lines of kernel arguments");
         typedef const uint32_t __attribute__((address_space(4))) *kernarg_ptr;
         kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
         const uint32_t warm = ka[0] ^ ka[16] ^ ka[32] ^ ka[48] ^ ka[64] ^ ka[80];
@@ -558,7 +560,39 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
                 for (int r = 0; r < 16; ++r) acc[cb][pb][r] = 0.0f;
         __syncthreads();                                       // P
 
+        // Residual layer: the added tensor is read in the accumulators' own layout -- a lane's four
+        // consecutive pixels of one channel are 8 bytes -- and requested before the last pass, so
+        // the loads (64 cache lines per instruction: lanes are channels) land under its MFMAs.
+        uint32_t rres[RES ? CHB : 1][RES ? PXB : 1][4][2];
+        auto request_residual = [&]() __attribute__((always_inline)) {
+            if constexpr (!RES) return;
+            const __amdgpu_buffer_rsrc_t rr = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<uint16_t *>(res), 0, (int)((size_t)p.N * p.Cout * ohw * 2), 0x00020000);
+            const bool vec = (ohw & 3) == 0;
+#pragma unroll
+            for (int cb = 0; cb < CHB; ++cb) {
+                const int co = g.cg * TN + (wn * CHB + cb) * 32 + c32;
+#pragma unroll
+                for (int pb = 0; pb < PXB; ++pb)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int m = g.m0 + (wm * PXB + pb) * 32 + 8 * q + 4 * h;
+                        const uint32_t off = (uint32_t)((((size_t)g.n * p.Cout + co) * ohw + m) * 2);
+                        if (vec) {
+                            const uint32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rr, (co < p.Cout && m < ohw) ? off : OOB, 0, 0);
+                            rres[cb][pb][q][0] = v.x; rres[cb][pb][q][1] = v.y;
+                        } else {
+                            uint32_t e[4];
+#pragma unroll
+                            for (int k = 0; k < 4; ++k)
+                                e[k] = __builtin_amdgcn_raw_buffer_load_b16(rr, (co < p.Cout && m + k < ohw) ? off + 2 * k : OOB, 0, 0);
+                            rres[cb][pb][q][0] = e[0] | (e[1] << 16); rres[cb][pb][q][1] = e[2] | (e[3] << 16);
+                        }
+                    }
+            }
+        };
         for (int ck = 0; ck < npass; ++ck) {
+            if constexpr (RES) { if (ck == npass - 1) request_residual(); }
             const uint4 *wl = wbuf(ck & 1) + (wn * CHB * 2 + h) * 32 + (c32 ^ (h * 8));
             const uint4 *xl = xbuf(ck & 1);
             const int rowstep = p.dh * p.pitch;
@@ -603,6 +637,12 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
                 for (int pb = 0; pb < PXB; ++pb)
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
+                        if constexpr (RES) {     // added to the fp32 sums: one rounding
+                            const half2v r0 = __builtin_bit_cast(half2v, rres[cb][pb][q][0]);
+                            const half2v r1 = __builtin_bit_cast(half2v, rres[cb][pb][q][1]);
+                            acc[cb][pb][4 * q] += (float)r0.x;     acc[cb][pb][4 * q + 1] += (float)r0.y;
+                            acc[cb][pb][4 * q + 2] += (float)r1.x; acc[cb][pb][4 * q + 3] += (float)r1.y;
+                        }
                         half2v v0, v1;
                         v0.x = (_Float16)acc[cb][pb][4 * q];     v0.y = (_Float16)acc[cb][pb][4 * q + 1];
                         v1.x = (_Float16)acc[cb][pb][4 * q + 2]; v1.y = (_Float16)acc[cb][pb][4 * q + 3];
@@ -656,36 +696,49 @@ __global__ __launch_bounds__(256) void merit_conv2d_pack_w(ConvParams p, int T, 
 namespace {
 
 template <typename K>
-hipError_t launch_one(K kernel, const ConvParams &p, const void *x, const void *w, void *y, hipStream_t s, uint32_t grid)
+hipError_t launch_one(K kernel, const ConvParams &p, const void *x, const void *w, const void *res, void *y, hipStream_t s,
+                      uint32_t grid)
 {
     // raise this instance's dynamic-LDS limit to the 160 KB a gfx950 workgroup may use, once
     static std::atomic<int> raised{0};
     if (hipError_t e = raise_lds_limit_once(reinterpret_cast<const void *>(kernel), raised); e != hipSuccess) return e;
     hipLaunchKernelGGL(kernel, dim3(grid), dim3((unsigned)(p.NW * 64)), (size_t)p.lds_total, s, p, reinterpret_cast<const uint16_t *>(x),
-                       reinterpret_cast<const uint16_t *>(w), reinterpret_cast<uint16_t *>(y));
+                       reinterpret_cast<const uint16_t *>(w), reinterpret_cast<const uint16_t *>(res),
+                       reinterpret_cast<uint16_t *>(y));
     return hipGetLastError();
 }
 
 template <int PXB, int CHB, int WM, int WN, int NG = 1, bool POOLS = false>
-hipError_t launch_tile(const ConvParams &p, const void *x, const void *w, void *y, hipStream_t s, uint32_t grid,
-                       bool packed)
+hipError_t launch_tile(const ConvParams &p, const void *x, const void *w, const void *res, void *y, hipStream_t s,
+                       uint32_t grid, bool packed)
 {
     const int xu = (p.W & 7) == 0 ? p.xu : 0;                // 8-pixel units per moving thread, 0: one-pixel units
     const int T = p.kh * p.kw;
+    if (p.residual) {
+        // residual layer: 3x3 windows on the caller's weights, the two 64-channel tilings (on the
+        // others the 32 registers of the added tensor would spill)
+        if constexpr (POOLS && WN == 1) {
+            if (T != 9 || packed || p.pool) return hipErrorInvalidValue;
+            if (xu == 1) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 1, false, NG, false, true>, p, x, w, res, y, s, grid);
+            if (xu == 2) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 2, false, NG, false, true>, p, x, w, res, y, s, grid);
+            return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 0, false, NG, false, true>, p, x, w, res, y, s, grid);
+        }
+        return hipErrorInvalidValue;
+    }
     if (p.pool) {
         // fused pooling: 3x3 windows on the caller's weights; not the 128-channel tiling on 8 wavefronts
         if constexpr (POOLS) {
             if (T != 9 || packed) return hipErrorInvalidValue;
-            if (xu == 1) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 1, false, NG, true>, p, x, w, y, s, grid);
-            if (xu == 2) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 2, false, NG, true>, p, x, w, y, s, grid);
-            return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 0, false, NG, true>, p, x, w, y, s, grid);
+            if (xu == 1) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 1, false, NG, true>, p, x, w, res, y, s, grid);
+            if (xu == 2) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 2, false, NG, true>, p, x, w, res, y, s, grid);
+            return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 0, false, NG, true>, p, x, w, res, y, s, grid);
         }
         return hipErrorInvalidValue;
     }
 #define MERIT_CHWS(Tv, XUv)                                                                             \
     do {                                                                                                \
-        if (packed) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, Tv, XUv, true, NG>, p, x, w, y, s, grid);  \
-        return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, Tv, XUv, false, NG>, p, x, w, y, s, grid);    \
+        if (packed) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, Tv, XUv, true, NG>, p, x, w, res, y, s, grid);  \
+        return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, Tv, XUv, false, NG>, p, x, w, res, y, s, grid);    \
     } while (0)
     if (T == 9 && xu == 1) MERIT_CHWS(9, 1);
     if (T == 9 && xu == 2) MERIT_CHWS(9, 2);
@@ -699,16 +752,18 @@ hipError_t launch_tile(const ConvParams &p, const void *x, const void *w, void *
 
 }  // namespace
 
-hipError_t launch_conv2d_chws(const ConvParams &p, const void *x, const void *w, void *y, hipStream_t s, bool packed)
+hipError_t launch_conv2d_chws(const ConvParams &p, const void *x, const void *w, const void *res, void *y, hipStream_t s,
+                              bool packed)
 {
+    if ((p.residual != 0) != (res != nullptr)) return hipErrorInvalidValue;
     const int64_t nitems = p.pool ? (int64_t)p.N * p.NB * p.co_groups : (int64_t)p.N * p.tiles_per_image * p.co_groups;
     if (nitems == 0) return hipSuccess;
     const int64_t slots = device_cu_count();            // one 512-thread workgroup per compute unit
     const uint32_t grid = (uint32_t)(nitems < slots ? nitems : slots);
-    if (p.CB == 4 && p.NW == 12) return launch_tile<2, 2, 4, 2, 1, true>(p, x, w, y, s, grid, packed);   // 256 x 128, 8 x (64 x 64)
-    if (p.CB == 4) return launch_tile<4, 2, 2, 2>(p, x, w, y, s, grid, packed);     // 256 pixels x 128 channels, 4 x (128 x 64)
-    if (p.TM == 128) return launch_tile<1, 2, 4, 1, 2, true>(p, x, w, y, s, grid, packed);   // 128 pixels x 64 channels, 4 x (32 x 64), 32 channels per pass
-    return launch_tile<2, 2, 4, 1, 1, true>(p, x, w, y, s, grid, packed);           // 256 pixels x 64 channels, 4 x (64 x 64)
+    if (p.CB == 4 && p.NW == 12) return launch_tile<2, 2, 4, 2, 1, true>(p, x, w, res, y, s, grid, packed);   // 256 x 128, 8 x (64 x 64)
+    if (p.CB == 4) return launch_tile<4, 2, 2, 2>(p, x, w, res, y, s, grid, packed);     // 256 pixels x 128 channels, 4 x (128 x 64)
+    if (p.TM == 128) return launch_tile<1, 2, 4, 1, 2, true>(p, x, w, res, y, s, grid, packed);   // 128 pixels x 64 channels, 4 x (32 x 64), 32 channels per pass
+    return launch_tile<2, 2, 4, 1, 1, true>(p, x, w, res, y, s, grid, packed);           // 256 pixels x 64 channels, 4 x (64 x 64)
 }
 
 hipError_t launch_conv2d_pack_weights(const ConvParams &p, const void *w, void *packed, hipStream_t s)
@@ -759,7 +814,7 @@ hipError_t launch_conv2d_chws_noalloc(const ConvParams &p, const void *x, const 
     if (e != hipSuccess) return e;
     e = launch_conv2d_pack_weights(p, w, packed, s);            // writes every fragment the passes read
     if (e != hipSuccess) return e;
-    return launch_conv2d_chws(p, x, packed, y, s, true);
+    return launch_conv2d_chws(p, x, packed, nullptr, y, s, true);
 }
 
 }  // namespace merit

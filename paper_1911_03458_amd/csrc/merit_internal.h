@@ -173,7 +173,8 @@ const char *sad_kernel_name(const SadParams &p);
 const char *conv_kernel_name(const ConvParams &p);
 // wave-specialised multi-pass kernel: w is the [Cout][Cin][kh][kw] tensor, or (packed) what
 // launch_conv2d_pack_weights wrote
-hipError_t launch_conv2d_chws(const ConvParams &p, const void *x, const void *w, void *y, hipStream_t s, bool packed);
+hipError_t launch_conv2d_chws(const ConvParams &p, const void *x, const void *w, const void *res, void *y, hipStream_t s,
+                              bool packed);
 hipError_t launch_conv2d_pack_weights(const ConvParams &p, const void *w, void *packed, hipStream_t s);
 // the same two launches with the packed copy in the library's own fixed device buffer
 // (MERIT_NOALLOC_SCRATCH_BYTES; the caller has checked that the plan's packed weights fit)

@@ -611,7 +611,9 @@ merit_status derive_conv(merit_plan *pl)
         // its tiles are 256 pixels of one image: small images (13x13, 7x7) would leave a third
         // and more of every tile empty and stay with the 128-pixel tiles of the plain kernels
         if (!forced && !pool && 4 * ohw < 3 * cdiv(ohw, tm) * tm) return false;
-        if (Cin % 8 != 0 || Cin < 16 || p.residual || ncb < 2) return false;
+        if (Cin % 8 != 0 || Cin < 16 || (pool && p.residual) || ncb < 2) return false;
+        // residual layer: 3x3 windows, the 64-channel tilings on 8 wavefronts
+        if (p.residual && (kh != 3 || cb != 2 || nw != 8)) return false;
         if (cb != 2 && cb != 4) return false;
         // fused pooling: 3x3 windows, the 64-channel tilings and the 128-channel one on 12 wavefronts; a tile is whole rows
         if (pool && (kh != 3 || !((cb == 2 && nw == 8) || (cb == 4 && nw == 12)) || (halo ? 3 : 2) * OW > tm)) return false;
@@ -1500,7 +1502,7 @@ merit_status merit_conv2d_packed(const merit_plan *plan, const void *x, const vo
     if (plan->conv.N == 0) return MERIT_OK;               // empty batch: nothing to read or write
     if (!x || !packed || !y) return MERIT_ERR_NULL;
     if (!aligned16(x) || !aligned16(packed) || !aligned16(y)) return MERIT_ERR_ALIGNMENT;
-    return launch_conv2d_chws(plan->conv, x, packed, y, static_cast<hipStream_t>(stream), true) == hipSuccess
+    return launch_conv2d_chws(plan->conv, x, packed, nullptr, y, static_cast<hipStream_t>(stream), true) == hipSuccess
                ? MERIT_OK
                : MERIT_ERR_HIP;
 }

@@ -163,7 +163,7 @@ def test_fused_pooling_plan_many_channels():
 
 def test_residual_plan():
     """The residual layer keeps the convolution's descriptor; only the multiply-and-store kernels
-    take the added tensor, so the planner never picks the wave-specialised one."""
+    take the added tensor; of the wave-specialised ones only the many-channel kernel does."""
     args = (32, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3)
     plan = mb.merit_plan_conv2d_residual(*args, 1)
     conv = mb.merit_plan_conv2d(*args)
@@ -176,12 +176,21 @@ def test_residual_plan():
         plan.set_tile((0, 0, 8, 64))
     plan.set_tile((0, 0, 4, 64))
     assert plan.launch_info()["kernel"] == "merit_conv2d_planar"
+    # many channels, 3x3: the wave-specialised multi-pass kernel adds the tensor in its accumulators' layout
     res = mb.merit_plan_conv2d_residual(8, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1, 1)
-    assert res.launch_info()["kernel"] == "merit_conv2d_chblock"       # the multi-pass kernels that take the added tensor
     plain = mb.merit_plan_conv2d(8, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1)
-    plain.set_tile((0, 0, 4, 32))
-    assert res.launch_info() == plain.launch_info()
+    assert res.launch_info()["kernel"] == "merit_conv2d_chws" and res.launch_info() == plain.launch_info()
     assert mb.merit_plan_create(res.desc()).desc().op == mb.MERIT_OP_CONV_DOT_ADD_RELU
+    res.set_tile((0, 0, 4, 32))                                       # the plain kernel on request
+    assert res.launch_info()["kernel"] == "merit_conv2d_chblock"
+    with pytest.raises(mb.MeritError):
+        res.set_tile((0, 0, 12, 64))                                  # not the 128-channel tilings
+    # 256 channels: the 64-channel tiles (the plain plan takes 128-channel ones)
+    big = mb.merit_plan_conv2d_residual(8, 256, 56, 56, 256, 3, 3, 1, 1, 1, 1, 0).launch_info()
+    assert big["kernel"] == "merit_conv2d_chws" and big["tile"][1] == 64 and big["block"][0] == 512
+    # other windows: the plain kernels
+    assert mb.merit_plan_conv2d_residual(1, 64, 28, 28, 64, 5, 5, 1, 1, 2, 2, 1).launch_info()["kernel"] in (
+        "merit_conv2d_chblock", "merit_conv2d_chpass")
 
 
 def test_sepfilter_plan():

@@ -710,17 +710,22 @@ def test_conv_pool_fused_7x7_workload(mb):
 
 RESIDUAL_CASES = [
     # N Cin H   W  Cout kh kw sh sw ph pw relu   (one per kernel and staging path)
-    (2, 64, 28, 28, 64, 3, 3, 1, 1, 1, 1, 1),   # channel-block, the residual block's shape class
+    (2, 64, 28, 28, 64, 3, 3, 1, 1, 1, 1, 1),   # the residual block's shape class
     (1, 16, 12, 16, 40, 3, 3, 1, 1, 1, 1, 0),   # channel-block, ragged channels, no clip
     (1, 20, 9, 11, 10, 2, 3, 1, 1, 0, 1, 1),    # channel-block, OH*OW % 8 != 0: scalar staging of r
     (2, 3, 32, 32, 64, 7, 7, 2, 2, 3, 3, 1),    # planar with prefetch
     (2, 3, 17, 19, 40, 7, 7, 2, 2, 3, 3, 0),    # planar, odd sizes
     (40, 3, 64, 64, 64, 7, 7, 2, 2, 3, 3, 1),   # planar, several tiles per workgroup
-    (1, 136, 10, 16, 64, 3, 3, 1, 1, 1, 1, 1),  # channel-block, channels in passes
-    (1, 256, 12, 56, 64, 3, 3, 1, 1, 1, 1, 1),  # channel-block, passes on the vector staging path
+    (1, 136, 10, 16, 64, 3, 3, 1, 1, 1, 1, 1),  # channels in passes, the last one half empty
+    (1, 256, 12, 56, 64, 3, 3, 1, 1, 1, 1, 1),  # passes on the vector staging path
     (22, 256, 12, 56, 64, 3, 3, 1, 1, 1, 1, 1), # the same with 64-channel blocks (more than 128 workgroups)
     (1, 3, 45, 45, 6, 11, 11, 4, 4, 0, 0, 1),   # planar, two fragments per window row
     (1, 3, 45, 45, 6, 11, 17, 4, 4, 0, 0, 1),   # one element per thread
+    # the wave-specialised multi-pass kernel (3x3, at least 32 input channels): r read in the accumulators' layout
+    (1, 32, 9, 11, 70, 3, 3, 1, 1, 1, 1, 1),    # 99 output pixels: 2-byte loads of r; ragged channel block; one-pixel staging
+    (3, 96, 20, 24, 128, 3, 3, 1, 1, 1, 1, 0),  # two channel blocks, several tiles per image, no clip
+    (300, 32, 8, 8, 64, 3, 3, 1, 1, 1, 1, 1),   # more work items than workgroups
+    (2, 64, 30, 32, 64, 3, 3, 2, 2, 1, 1, 1),   # stride 2
 ]
 
 
@@ -759,6 +764,14 @@ def test_conv_residual(mb, case):
     _residual_check(mb, case)
 
 
+@pytest.mark.parametrize("case", [c for c in RESIDUAL_CASES if c[1] >= 32 and c[5] == 3])
+@pytest.mark.parametrize("tile", [(0, 0, 4, 32), (0, 0, 8, 64), (0, 0, 8, 32)])
+def test_conv_residual_many_channels_every_kernel(mb, case, tile):
+    """The many-channel cases on the plain kernels (4 x 32: single- or multi-pass) and on both
+    64-channel tilings of the wave-specialised kernel."""
+    _residual_check(mb, case, tile=tile)
+
+
 def test_conv_residual_in_place_and_big_tiles(mb):
     _residual_check(mb, RESIDUAL_CASES[0], in_place=True)
     _residual_check(mb, RESIDUAL_CASES[0], tile=(0, 0, 4, 64))
@@ -780,6 +793,19 @@ def test_conv_residual_single_rounding(mb):
     y = mb.merit_conv2d_residual(plan, dev(x), dev(w), dev(r)).cpu().numpy().astype(np.float64)
     assert np.all(y[0, :, :4] == 2050.0) and np.all(y[0, :, 4:] == 1.0)
     assert np.array_equal(y, oracle.conv2d_residual(x, w, r).astype(np.float64))
+    # the same on the wave-specialised multi-pass kernel: a 3x3 window whose centre tap does it
+    Cin = 32
+    x = np.zeros((1, Cin, 8, 8), np.float16)
+    x[0, 0], x[0, 1] = 2048.0, 1.0
+    w = np.zeros((64, Cin, 3, 3), np.float16)
+    w[:, 0, 1, 1], w[:, 1, 1, 1] = 1.0, 1.0
+    plan = mb.merit_plan_conv2d_residual(1, Cin, 8, 8, 64, 3, 3, 1, 1, 1, 1, 0)
+    assert plan.launch_info()["kernel"] == "merit_conv2d_chws"
+    r = np.ones(plan.out_shape(), np.float16)
+    r[0, :, 4:] = -2048.0
+    y = mb.merit_conv2d_residual(plan, dev(x), dev(w), dev(r)).cpu().numpy().astype(np.float64)
+    assert np.all(y[0, :, :4] == 2050.0) and np.all(y[0, :, 4:] == 1.0)
+    assert np.array_equal(y, oracle.conv2d_residual(x, w, r, (1, 1), (1, 1)).astype(np.float64))
 
 
 def test_conv_residual_3x3_workload(mb):
@@ -787,7 +813,7 @@ def test_conv_residual_3x3_workload(mb):
     c = wl.CFG2_CONV3
     x, w = wl.make_conv_inputs(c)
     plan = mb.merit_plan_conv2d_residual(c.N, c.Cin, c.H, c.W, c.Cout, c.kh, c.kw, c.sh, c.sw, c.ph, c.pw, 1)
-    assert plan.launch_info()["kernel"] == "merit_conv2d_chblock"
+    assert plan.launch_info()["kernel"] == "merit_conv2d_chws"
     r = np.random.default_rng(wl.BASE_SEED + 77).standard_normal(plan.out_shape()).astype(np.float16)
     y = mb.merit_conv2d_residual(plan, dev(x), dev(w), dev(r)).cpu().numpy().astype(np.float64)
     ref = oracle.conv2d_residual(x, w, r, (c.sh, c.sw), (c.ph, c.pw), relu=True).astype(np.float64)
