@@ -798,9 +798,10 @@ merit_status derive_conv(merit_plan *pl)
         // estimate rounds of the grid x cost of a tile (1.6, 1, 0.6 from timings) is taken, the larger
         // tile on a tie: few large tiles while they still fill the chip, else more small ones --
         // also for images far smaller than a tile (13x13 on 256-pixel tiles: 32 us, against 98 us on
-        // the plain multi-pass kernel; 7x7 on 128-pixel tiles: 28 against 88).  (1x1 layers stay with the
-        // plain kernels: a 1x1 pass is one MFMA step per 16 staged channels.)
-        if (kh == 3 && kw == 3 && Cin >= 32 && (Cin % 8) == 0 && ncb >= 2) {
+        // the plain multi-pass kernel; 7x7 on 128-pixel tiles: 28 against 88).  1x1 layers the same
+        // (256 -> 64 on 56x56: 8.1 against 11.9 us, 1024 -> 256 on 14x14: 27 against 51); with a residual
+        // tensor they stay on the plain kernels.
+        if (((kh == 3 && kw == 3) || (kh == 1 && kw == 1 && !p.residual)) && Cin >= 32 && (Cin % 8) == 0 && ncb >= 2) {
             int best = -1; double best_cost = 0.0;
             for (int shape = 0; shape < 3; ++shape) {          // 0: 256 x 128 on 12 wavefronts, 1: 256 x 64, 2: 128 x 64
                 if (shape == 0 && ncb < 4) continue;

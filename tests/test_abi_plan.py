@@ -511,7 +511,8 @@ def test_conv_plans_for_layers_that_do_not_fit_lds_at_once():
                           ((1, 300, 56, 56, 64, 3, 3, 1, 1, 1, 1), "merit_conv2d_chpass"),      # Cin % 8 != 0
                           ((1, 64, 224, 224, 64, 3, 3, 1, 1, 1, 1), "merit_conv2d_chws"),
                           ((8, 256, 56, 56, 256, 3, 3, 1, 1, 1, 1), "merit_conv2d_chws"),
-                          ((8, 256, 56, 56, 64, 1, 1, 1, 1, 0, 0), "merit_conv2d_chpass")):       # 1x1: larger passes
+                          ((8, 256, 56, 56, 64, 1, 1, 1, 1, 0, 0), "merit_conv2d_chws"),         # 1x1
+                          ((8, 260, 56, 56, 64, 1, 1, 1, 1, 0, 0), "merit_conv2d_chpass")):       # 1x1, Cin % 8 != 0: larger passes
         li = mb.merit_plan_conv2d(*shape).launch_info()
         assert li["kernel"] == kernel and 0 < li["lds_bytes"] <= 160 * 1024, (shape, li)
         if kernel == "merit_conv2d_chws":
