@@ -85,6 +85,8 @@ def measure_peaks(torch, mb):
     sink = torch.empty(wgs * 256, dtype=torch.int32, device="cuda:0")
     kinds = [("mfma_f16", mb.MERIT_PROBE_MFMA_F16, 32768.0 / 1e12, MFMA_F16_PEAK_TFLOPS, "TFLOP/s",
               "v_mfma_f32_32x32x16_f16, 8 independent accumulators per wavefront"),
+             ("mfma_f16_random_operands", mb.MERIT_PROBE_MFMA_F16_RANDOM, 32768.0 / 1e12, MFMA_F16_PEAK_TFLOPS, "TFLOP/s",
+              "the same loop on hashed binary16 operands (random sign and mantissa), four operand pairs in turn"),
              ("fma_f32", mb.MERIT_PROBE_FMA_F32, 64.0 / 1e12, FP32_FMA_PEAK_TOPS, "T lane-ops/s",
               "v_fma_f32 (not packed), 8 independent chains per lane; data sheet = 157.3 TFLOP/s fp32 vector"),
              ("sad_u8", mb.MERIT_PROBE_SAD_U8, 64.0 / 1e12, VALU_PEAK_TOPS, "T lane-ops/s",
@@ -92,7 +94,7 @@ def measure_peaks(torch, mb):
              ("exp2_f32", mb.MERIT_PROBE_EXP2_F32, 64.0 / 1e12, FP32_FMA_PEAK_TOPS / 4, "T lane-ops/s",
               "v_exp_f32, 8 independent chains per lane; data-sheet figure = a quarter of the fp32 rate")]
     for name, which, per_instr, sheet, unit, what in kinds:
-        it = iters // 4 if which == mb.MERIT_PROBE_MFMA_F16 else iters
+        it = iters // 4 if which in (mb.MERIT_PROBE_MFMA_F16, mb.MERIT_PROBE_MFMA_F16_RANDOM) else iters
         wall, ms = timed_region(torch, lambda i: mb.merit_probe_alu(which, wgs, it, sink), 10, 2)
         instrs = wgs * 4 * it * 8
         out[name] = {"measured": instrs * per_instr / (ms * 1e-3 / 10), "datasheet": sheet, "unit": unit, "what": what}

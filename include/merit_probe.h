@@ -24,7 +24,10 @@ enum {
     MERIT_PROBE_MFMA_F16 = 0, /* v_mfma_f32_32x32x16_f16: 32768 flop per wavefront instruction */
     MERIT_PROBE_FMA_F32 = 1,  /* v_fma_f32 (not packed): 1 lane-op per lane                    */
     MERIT_PROBE_SAD_U8 = 2,   /* v_sad_u8: 1 lane-op (4 pixel differences) per lane            */
-    MERIT_PROBE_EXP2_F32 = 3  /* v_exp_f32: 1 lane-op per lane                                 */
+    MERIT_PROBE_EXP2_F32 = 3, /* v_exp_f32: 1 lane-op per lane                                 */
+    MERIT_PROBE_MFMA_F16_RANDOM = 4 /* the MFMA loop on random binary16 operands (sign, mantissa and a few
+                                 * exponents hashed per lane, four operand pairs in turn): what the matrix
+                                 * cores sustain on data like a layer's, where the clock follows the power */
 };
 
 /* Runs `workgroups` workgroups of 256 threads; every wavefront issues iters x 8 instructions

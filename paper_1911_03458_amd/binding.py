@@ -456,7 +456,7 @@ def bind_bilateral(plan: Plan, x, gx, gy, norm, y, stream=None) -> BoundCall:
                      (plan, x, gx, gy, y))
 
 
-(MERIT_PROBE_MFMA_F16, MERIT_PROBE_FMA_F32, MERIT_PROBE_SAD_U8, MERIT_PROBE_EXP2_F32) = range(4)
+(MERIT_PROBE_MFMA_F16, MERIT_PROBE_FMA_F32, MERIT_PROBE_SAD_U8, MERIT_PROBE_EXP2_F32, MERIT_PROBE_MFMA_F16_RANDOM) = range(5)
 
 
 def merit_probe_copy(src, dst, stream=None):

@@ -46,6 +46,36 @@ __global__ __launch_bounds__(256) void merit_probe_alu_kernel(int iters, uint32_
 #pragma unroll
         for (int c = 0; c < 8; ++c) s += acc[c][0] + acc[c][15];
         out = __builtin_bit_cast(uint32_t, s);
+    } else if (WHICH == MERIT_PROBE_MFMA_F16_RANDOM) {
+        // the same instruction stream on operands like a layer's: four operand pairs of hashed
+        // binary16 values (random sign and mantissa, magnitudes 1/8 .. 1) taken in turn, so that
+        // the multipliers see different bits every instruction
+        floatx16 acc[8];
+        half8 a[4], b[4];
+        uint32_t hsh = seed | 1u;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                hsh = hsh * 1664525u + 1013904223u;
+                const uint16_t ba = (uint16_t)(((hsh >> 16) & 0x83ffu) | (uint16_t)((12 + ((hsh >> 28) & 3)) << 10));
+                hsh = hsh * 1664525u + 1013904223u;
+                const uint16_t bb = (uint16_t)(((hsh >> 16) & 0x83ffu) | (uint16_t)((12 + ((hsh >> 28) & 3)) << 10));
+                a[k][j] = __builtin_bit_cast(_Float16, ba);
+                b[k][j] = __builtin_bit_cast(_Float16, bb);
+            }
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[c][r] = 0.0f;
+        for (int i = 0; i < iters; ++i) {
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[c & 3], b[(c + (c >> 2)) & 3], acc[c], 0, 0, 0);
+        }
+        float s = 0.0f;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) s += acc[c][0] + acc[c][15];
+        out = __builtin_bit_cast(uint32_t, s);
     } else if (WHICH == MERIT_PROBE_FMA_F32) {
         float acc[8];
         const float m = 1.0f + (float)(seed & 7) * 1e-7f, d = (float)(seed & 3) * 1e-3f;
@@ -106,7 +136,7 @@ merit_status merit_probe_copy(const void *src, void *dst, size_t bytes, void *st
 
 merit_status merit_probe_alu(int which, int workgroups, int iters, void *sink, void *stream)
 {
-    if (which < 0 || which > 3 || workgroups < 0 || iters < 0 || workgroups > (1 << 20)) return MERIT_ERR_INVALID_ARG;
+    if (which < 0 || which > 4 || workgroups < 0 || iters < 0 || workgroups > (1 << 20)) return MERIT_ERR_INVALID_ARG;
     if (workgroups == 0) return MERIT_OK;
     if (!sink) return MERIT_ERR_NULL;
     if ((uintptr_t)sink & 3) return MERIT_ERR_ALIGNMENT;
@@ -120,6 +150,8 @@ merit_status merit_probe_alu(int which, int workgroups, int iters, void *sink, v
         hipLaunchKernelGGL(merit::merit_probe_alu_kernel<MERIT_PROBE_FMA_F32>, g, b, 0, s, iters, out); break;
     case MERIT_PROBE_SAD_U8:
         hipLaunchKernelGGL(merit::merit_probe_alu_kernel<MERIT_PROBE_SAD_U8>, g, b, 0, s, iters, out); break;
+    case MERIT_PROBE_MFMA_F16_RANDOM:
+        hipLaunchKernelGGL(merit::merit_probe_alu_kernel<MERIT_PROBE_MFMA_F16_RANDOM>, g, b, 0, s, iters, out); break;
     default:
         hipLaunchKernelGGL(merit::merit_probe_alu_kernel<MERIT_PROBE_EXP2_F32>, g, b, 0, s, iters, out); break;
     }
