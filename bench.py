@@ -493,9 +493,9 @@ def main():
     global CPU_EXTRA
     CPU_EXTRA = not args.no_cpu
     if not args.no_extra:
-        k = max(100, args.steps // 2)        # launches per extra workload, whatever --steps says
-        w = max(10, args.warmup // 2)
-        kl = max(100, k // 2)                # the longer kernels
+        k = max(200, args.steps)             # launches per extra workload, whatever --steps says
+        w = max(20, args.warmup)
+        kl = k
         result["extra"] = [
             bench_sad(torch, mb, wl, wl.CFG0_ME_SMALL, k, w),
             bench_conv(torch, mb, wl, wl.CFG2_CONV3, k, w, args.sets),
