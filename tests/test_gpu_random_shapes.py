@@ -155,3 +155,72 @@ def test_random_shapes(seed):
             tol = (2e-5 + 1.2e-7 * k * k) * float(x.max() - x.min()) + 1e-30
             report("bil", case, canary(buf, pad) and err <= tol, "err %.2e tol %.2e" % (err, tol))
     assert not failures, failures
+
+
+@pytest.mark.parametrize("seed", [1103, 458])
+def test_random_layer_shapes(seed):
+    """Layers with many channels (the shapes the wave-specialised convolution kernels take):
+    3x3 and 1x1 windows on 32..256 input channels, any output-channel count and ragged image
+    extents, through every way a convolution can be called: plain, clipped, with an added
+    tensor, with the fused 3x3 / stride 2 / padding 1 max pooling, with weights packed once,
+    and through the entry point that allocates nothing."""
+    rng = np.random.default_rng(seed)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+    failures, kernels = [], set()
+
+    def ri(a, b):
+        return int(rng.integers(a, b + 1))
+
+    for it in range(26):
+        N, Cin, Cout = ri(1, 3), 8 * ri(4, 32), ri(33, 256)
+        if rng.random() < 0.5: Cout = 32 * ri(2, 8)
+        H, W = ri(4, 36), ri(4, 36)
+        if rng.random() < 0.3: H = W = int(rng.choice([7, 14, 28, 56])); N = 1
+        k = 3 if rng.random() < 0.7 else 1
+        s = 1 if rng.random() < 0.8 else 2
+        pd = ri(0, 1) if k == 3 else 0
+        if H + 2 * pd < k or W + 2 * pd < k: continue
+        mode = str(rng.choice(["plain", "relu", "residual", "pool", "packed", "noalloc"]))
+        relu = int(mode in ("relu", "pool") or (mode == "residual" and rng.random() < 0.5))
+        case = (mode, N, Cin, H, W, Cout, k, s, pd, relu)
+        print(it, case, flush=True)
+        x = rng.standard_normal((N, Cin, H, W)).astype(np.float16)
+        w = (rng.standard_normal((Cout, Cin, k, k)) / np.sqrt(Cin * k * k)).astype(np.float16)
+        try:
+            if mode == "residual": plan = mb.merit_plan_conv2d_residual(N, Cin, H, W, Cout, k, k, s, s, pd, pd, relu)
+            elif mode == "pool": plan = mb.merit_plan_conv2d_pool(N, Cin, H, W, Cout, k, k, s, s, pd, pd, relu)
+            else: plan = mb.merit_plan_conv2d_dilated(N, Cin, H, W, Cout, k, k, s, s, pd, pd, 1, 1, relu)
+        except mb.MeritError as e:
+            print("   plan refused:", e, flush=True)
+            assert mode == "pool", case                     # only the fused pooling has shape conditions
+            continue
+        buf, y, pad = _guard(plan.out_shape(), torch.float16)
+        try:
+            if mode == "residual":
+                r = rng.standard_normal(plan.out_shape()).astype(np.float16)
+                mb.merit_conv2d_residual(plan, dev(x), dev(w), dev(r), y)
+                ref = oracle.conv2d_residual(x, w, r, (s, s), (pd, pd), bool(relu))
+            elif mode == "pool":
+                mb.merit_conv2d(plan, dev(x), dev(w), y)
+                ref = oracle.conv2d_pool(x, w, (s, s), (pd, pd), bool(relu))
+            elif mode == "packed":
+                packed = mb.merit_conv2d_pack_weights(plan, dev(w))
+                mb.merit_conv2d_packed(plan, dev(x), packed, y)
+                ref = oracle.conv2d(x, w, (s, s), (pd, pd), bool(relu))
+            elif mode == "noalloc":
+                mb.merit_conv2d_packed_noalloc(plan, dev(x), dev(w), y)
+                ref = oracle.conv2d(x, w, (s, s), (pd, pd), bool(relu))
+            else:
+                mb.merit_conv2d(plan, dev(x), dev(w), y)
+                ref = oracle.conv2d(x, w, (s, s), (pd, pd), bool(relu))
+        except mb.MeritError as e:
+            print("   call refused:", e, flush=True)
+            assert mode in ("packed", "noalloc"), case      # packing is for the multi-pass kernels only
+            continue
+        torch.cuda.synchronize()
+        kernels.add(plan.launch_info()["kernel"])
+        got = y.cpu().numpy().astype(np.float64); ref = ref.astype(np.float64)
+        if not (_canary(buf, pad) and got.shape == ref.shape and np.all(np.abs(got - ref) <= 2e-2 * np.abs(ref) + 1e-3)):
+            failures.append((case, plan.launch_info()["kernel"]))
+    assert not failures, failures
+    assert any("chws" in k for k in kernels), kernels
