@@ -223,3 +223,64 @@ def test_empty_and_misuse(mb):
     with pytest.raises(mb.MeritError) as e:
         mb.merit_plan_create(d)
     assert e.value.status == mb.MERIT_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("seed", [35, 81])
+def test_random_descriptors(mb, seed):
+    """Descriptors nobody designed: 1-4 parallel and 1-3 accumulation indices, each moving along
+    any axis of a 1- to 4-axis operand (or none) with a stride in -2..3 and an offset in -3..3,
+    several indices on one axis, every padding rule each product function has.  Expected values
+    are Eq. 5 taken literally (M(A), M(B) materialised, rows reduced); whichever kernel the plan
+    chose must agree with it."""
+    rng = np.random.default_rng(seed)
+
+    def ri(a, b):
+        return int(rng.integers(a, b + 1))
+
+    def operand(J):
+        shape = tuple(ri(1, 7) for _ in range(ri(1, 4)))
+        axis = tuple(ri(-1, len(shape) - 1) for _ in range(J))
+        return shape, lit.Transform(axis, tuple(ri(-2, 3) for _ in range(J)), tuple(ri(-3, 3) for _ in range(J)))
+
+    kernels = set()
+    for it in range(60):
+        n_par, n_acc = ri(1, 4), ri(1, 3)
+        J = n_par + n_acc
+        ranges = tuple(ri(1, 5) for _ in range(J))
+        mode = str(rng.choice(["dot", "dot_relu", "max", "avg"]))
+        sa, ta = operand(J)
+        if mode in ("dot", "dot_relu"):
+            pad = str(rng.choice(["zero", "clamp"]))
+            sb, tb = operand(J)
+            A = rng.standard_normal(sa).astype(np.float16)
+            B = (rng.standard_normal(sb) / 4).astype(np.float16)
+            op = mb.MERIT_OP_CONV_DOT_RELU if mode == "dot_relu" else mb.MERIT_OP_CONV_DOT
+            d = make_desc(mb, op, mb.MERIT_F16, pad, ranges, n_par, ta, sa, tb, sb)
+            print(it, mode, pad, ranges, n_par, sa, ta, sb, tb, flush=True)
+            plan = mb.merit_plan_create(d)
+            kernels.add(plan.launch_info()["kernel"])
+            assert plan.out_shape() == ranges[:n_par]
+            y = mb.merit_conv2d(plan, dev(A), dev(B)).cpu().numpy()
+            check_dot(y, literal_dot(A, B, ranges, n_par, ta, tb, pad, relu=(mode == "dot_relu")))
+        else:
+            pad = str(rng.choice(["ninf", "clamp", "zero"] if mode == "max" else ["exclude", "zero", "clamp"]))
+            A = rng.standard_normal(sa).astype(np.float32)
+            op = mb.MERIT_OP_POOL_MAX if mode == "max" else mb.MERIT_OP_POOL_AVG
+            d = make_desc(mb, op, mb.MERIT_F32, pad, ranges, n_par, ta, sa)
+            print(it, mode, pad, ranges, n_par, sa, ta, flush=True)
+            plan = mb.merit_plan_create(d)
+            kernels.add(plan.launch_info()["kernel"])
+            y = mb.merit_pool2d(plan, dev(A)).cpu().numpy().astype(np.float64)
+            M, inside = lit.transform(A.astype(np.float64), ranges, ta, n_par, pad)
+            if mode == "max":
+                ref = M.max(axis=1).reshape(ranges[:n_par])
+                assert np.array_equal(y, ref)
+            else:
+                if pad == "exclude":
+                    cnt = inside.sum(axis=1)
+                    ref = np.where(cnt > 0, M.sum(axis=1) / np.maximum(cnt, 1), 0.0)
+                else:
+                    ref = M.mean(axis=1)
+                ref = ref.reshape(ranges[:n_par])
+                assert y.shape == ref.shape and np.all(np.abs(y - ref) <= 1e-5 * np.abs(ref) + 1e-6)
+    assert {"merit_generic<dot>", "merit_generic<max>", "merit_generic<mean>"} <= kernels, kernels
