@@ -43,6 +43,8 @@ def parse_args():
     ap.add_argument("--sets", type=int, default=8, help="rotating buffer sets for cache-cold timing")
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--extra-only", default=None, help="run only the other workloads whose name contains this")
+    ap.add_argument("--extra-skip", default=None, help="skip the other workloads whose name contains this")
     ap.add_argument("--peaks", action="store_true",
                     help="only run the peak probes (streaming copy, MFMA / FMA / SAD / exp2 instruction "
                          "loops) and print the measured-achievable peaks beside the data-sheet ones")
@@ -496,27 +498,32 @@ def main():
         k = max(200, args.steps)             # launches per extra workload, whatever --steps says
         w = max(20, args.warmup)
         kl = k
-        result["extra"] = [
-            bench_sad(torch, mb, wl, wl.CFG0_ME_SMALL, k, w),
-            bench_conv(torch, mb, wl, wl.CFG2_CONV3, k, w, args.sets),
-            bench_sad(torch, mb, wl, wl.CFG3_ME_FHD, kl, w),
-            bench_sad(torch, mb, wl, wl.CFG_ME_720P, k, w),
-            bench_sad(torch, mb, wl, wl.CFG_ME_1080P, kl, w),
-            bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets),
-            bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets, relu=True),
-            bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets, relu=True, pool=True),
-            bench_conv(torch, mb, wl, wl.CFG2_CONV3, k, w, args.sets, relu=True, residual=True),
-            bench_conv(torch, mb, wl, wl.CFG2_CONV3, k, w, args.sets, relu=True, pool=True),
-            bench_conv(torch, mb, wl, wl.CFG_DILATED, k, w, args.sets),
-            bench_conv(torch, mb, wl, wl.CFG_CONV256, kl, w, args.sets),
-            bench_conv(torch, mb, wl, wl.CFG_CONV256, kl, w, args.sets, packed=True),
-            bench_conv(torch, mb, wl, wl.CFG_CONV11, kl, w, args.sets),
-            bench_corr(torch, mb, wl, wl.CFG_CORRELATION, k, w),
-            bench_depthwise(torch, mb, wl, wl.CFG_DEPTHWISE, k, w, args.sets),
-            bench_sepfilter(torch, mb, wl, wl.CFG_SEP_K3, k, w, args.sets),
-            bench_sepfilter(torch, mb, wl, wl.CFG_SEP_K30, kl, w, args.sets),
-            bench_bilateral(torch, mb, wl, wl.CFG_BILATERAL, kl, w),
+        extras = [
+            (wl.CFG0_ME_SMALL.name, lambda: bench_sad(torch, mb, wl, wl.CFG0_ME_SMALL, k, w)),
+            (wl.CFG2_CONV3.name, lambda: bench_conv(torch, mb, wl, wl.CFG2_CONV3, k, w, args.sets)),
+            (wl.CFG3_ME_FHD.name, lambda: bench_sad(torch, mb, wl, wl.CFG3_ME_FHD, kl, w)),
+            (wl.CFG_ME_720P.name, lambda: bench_sad(torch, mb, wl, wl.CFG_ME_720P, k, w)),
+            (wl.CFG_ME_1080P.name, lambda: bench_sad(torch, mb, wl, wl.CFG_ME_1080P, kl, w)),
+            (wl.CFG4_CONV7.name, lambda: bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets)),
+            (wl.CFG4_CONV7.name, lambda: bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets, relu=True)),
+            (wl.CFG4_CONV7.name, lambda: bench_conv(torch, mb, wl, wl.CFG4_CONV7, k, w, args.sets, relu=True, pool=True)),
+            (wl.CFG2_CONV3.name, lambda: bench_conv(torch, mb, wl, wl.CFG2_CONV3, k, w, args.sets, relu=True, residual=True)),
+            (wl.CFG2_CONV3.name, lambda: bench_conv(torch, mb, wl, wl.CFG2_CONV3, k, w, args.sets, relu=True, pool=True)),
+            (wl.CFG_DILATED.name, lambda: bench_conv(torch, mb, wl, wl.CFG_DILATED, k, w, args.sets)),
+            (wl.CFG_CONV256.name, lambda: bench_conv(torch, mb, wl, wl.CFG_CONV256, kl, w, args.sets)),
+            (wl.CFG_CONV256.name, lambda: bench_conv(torch, mb, wl, wl.CFG_CONV256, kl, w, args.sets, packed=True)),
+            (wl.CFG_CONV256_B64.name, lambda: bench_conv(torch, mb, wl, wl.CFG_CONV256_B64, kl, w, 3)),
+            (wl.CFG_CONV11.name, lambda: bench_conv(torch, mb, wl, wl.CFG_CONV11, kl, w, args.sets)),
+            (wl.CFG_CORRELATION.name, lambda: bench_corr(torch, mb, wl, wl.CFG_CORRELATION, k, w)),
+            (wl.CFG_DEPTHWISE.name, lambda: bench_depthwise(torch, mb, wl, wl.CFG_DEPTHWISE, k, w, args.sets)),
+            (wl.CFG_SEP_K3.name, lambda: bench_sepfilter(torch, mb, wl, wl.CFG_SEP_K3, k, w, args.sets)),
+            (wl.CFG_SEP_K30.name, lambda: bench_sepfilter(torch, mb, wl, wl.CFG_SEP_K30, kl, w, args.sets)),
+            (wl.CFG_BILATERAL.name, lambda: bench_bilateral(torch, mb, wl, wl.CFG_BILATERAL, kl, w)),
         ]
+        # --extra-only / --extra-skip: substrings of a workload's name (for profiling one launch shape alone)
+        result["extra"] = [run() for name, run in extras
+                           if (args.extra_only is None or args.extra_only in name)
+                           and (args.extra_skip is None or args.extra_skip not in name)]
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(result))

@@ -122,6 +122,9 @@ CFG_CONV11 = ConvWorkload("conv_8x3x220x220_co48_k11s4p5", 8, 3, 220, 220, 48, 1
 # A layer whose weights and input rows do not fit LDS at once (256 -> 256 channels, 3 x 3 on
 # 56 x 56, the shape class of the deeper layers of the paper's per-layer table): channels in passes.
 CFG_CONV256 = ConvWorkload("conv_8x256x56x56_co256_k3s1p1", 8, 256, 56, 56, 256, 3, 3, 1, 1, 1, 1, "normal")
+# The same layer on a batch of 64: 200 704 pixels = 784 tiles of 256, three rounds of the 256 CUs,
+# so that the launch and the pipeline fill of the first tile weigh a third as much.
+CFG_CONV256_B64 = ConvWorkload("conv_64x256x56x56_co256_k3s1p1", 64, 256, 56, 56, 256, 3, 3, 1, 1, 1, 1, "normal")
 
 
 @dataclass(frozen=True)

@@ -174,6 +174,21 @@ def test_chws_512_channel_layer_on_28x28(mb):
         assert np.all(np.abs(y[n:n + 1] - ref) <= 2e-2 * np.abs(ref) + 1e-3)
 
 
+def test_chws_many_channel_workload_on_a_batch_of_64(mb):
+    """The 256 -> 256 layer on 64 images (the bench's larger launch: three rounds of tiles per CU);
+    the oracle checks every output of the first, a middle and the last image."""
+    from paper_1911_03458_amd import workloads as wl
+    c = wl.CFG_CONV256_B64
+    x, w = wl.make_conv_inputs(c)
+    plan = mb.merit_plan_conv2d(c.N, c.Cin, c.H, c.W, c.Cout, c.kh, c.kw, c.sh, c.sw, c.ph, c.pw)
+    assert plan.launch_info()["kernel"] == "merit_conv2d_chws"
+    y = mb.merit_conv2d(plan, dev(x), dev(w))
+    for n in (0, 37, 63):
+        ref = oracle.conv2d(x[n:n + 1], w, (1, 1), (1, 1)).astype(np.float64)
+        got = y[n:n + 1].cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(got - ref) <= 2e-2 * np.abs(ref) + 1e-3), n
+
+
 def test_packed_entry_points_refuse_other_plans(mb):
     plan = mb.merit_plan_conv2d(1, 3, 32, 32, 16, 7, 7, 2, 2, 3, 3)
     with pytest.raises(mb.MeritError) as e:
