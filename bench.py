@@ -454,6 +454,7 @@ def pool_traffic_from_profiles():
 
 
 def main():
+    global CPU_EXTRA, WARM_MS
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -468,6 +469,7 @@ def main():
     torch.cuda.set_device(0)
 
     if args.peaks:
+        WARM_MS = args.extra_warm_ms             # the probes too are timed at settled clocks
         print(json.dumps({"peaks": measure_peaks(torch, mb)}))
         return
 
@@ -511,7 +513,6 @@ def main():
                      "avg_launch_us": pool["avg_launch_us"], "alg_bytes_per_launch": pool["alg_bytes_per_launch"],
                      "cache_warm_avg_launch_us": pool["warm_avg_launch_us"]},
     }
-    global CPU_EXTRA, WARM_MS
     CPU_EXTRA = not args.no_cpu
     WARM_MS = args.extra_warm_ms                 # the headline above keeps exactly --warmup launches
     if not args.no_extra:
