@@ -542,6 +542,8 @@ def main():
             (wl.CFG_BILATERAL.name, lambda: bench_bilateral(torch, mb, wl, wl.CFG_BILATERAL, kl, w)),
         ]
         # --extra-only / --extra-skip: substrings of a workload's name (for profiling one launch shape alone)
+        result["extra_timing"] = ("each workload below: at least %g ms of untimed launches (settled clocks), then %d timed "
+                                  "launches between two HIP events" % (args.extra_warm_ms, k))
         result["extra"] = [run() for name, run in extras
                            if (args.extra_only is None or args.extra_only in name)
                            and (args.extra_skip is None or args.extra_skip not in name)]
