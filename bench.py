@@ -254,17 +254,19 @@ def bench_conv(torch, mb, wl, cfg, steps, warmup, nsets, relu=False, pool=False,
     wall, ev_ms = timed_region(torch, lambda i: calls[i % ns](), steps, warmup)
     t = ev_ms * 1e-3 / steps
     flops = 2.0 * cfg.N * cfg.Cout * cfg.OH * cfg.OW * cfg.Cin * cfg.kh * cfg.kw
-    # oracle sample: one image, the first 8 output channels
+    # oracle sample: one image, one output channel per host thread (the oracle's parallel loop is over
+    # (image, output channel)), at least 8
     import oracle
-    xs1, ws8 = x[:1].copy(), w[:8].copy()
+    nco = min(cfg.Cout, max(8, oracle.num_threads()))
+    xs1, ws8 = x[:1].copy(), w[:nco].copy()
     if pool:
         ofn = lambda: oracle.conv2d_pool(xs1, ws8, (cfg.sh, cfg.sw), (cfg.ph, cfg.pw), relu=relu)
     elif residual:
-        r1 = np.zeros((1, 8, cfg.OH, cfg.OW), np.float16)
+        r1 = np.zeros((1, nco, cfg.OH, cfg.OW), np.float16)
         ofn = lambda: oracle.conv2d_residual(xs1, ws8, r1, (cfg.sh, cfg.sw), (cfg.ph, cfg.pw), relu=relu)
     else:
         ofn = lambda: oracle.conv2d(xs1, ws8, (cfg.sh, cfg.sw), (cfg.ph, cfg.pw), relu=relu, dilation=(cfg.dh, cfg.dw))
-    cpu = oracle_rate(ofn, 8 * oh * ow, "one image, the first 8 output channels")
+    cpu = oracle_rate(ofn, nco * oh * ow, "one image, the first %d output channels" % nco)
     return {
         "workload": cfg.name + (" + residual tensor" if residual else "") + (" + fused ReLU" if relu else "")
         + (" + fused 3x3/s2/p1 max pooling" if pool else "") + (" (weights packed once)" if packed else ""),
@@ -392,9 +394,10 @@ def bench_corr(torch, mb, wl, cfg, steps, warmup):
     alg_bytes = x1.nbytes + x2.nbytes + y.numel() * 2
     flops = 2.0 * cfg.N * cfg.H * cfg.W * n * n * cfg.C          # zero-padded positions included
     import oracle
-    r1, r2 = x1[:, :, :8].copy(), x2[:, :, :8].copy()
-    cpu = oracle_rate(lambda: oracle.correlation(r1, r2, cfg.search, cfg.stride), cfg.N * 8 * cfg.W * n * n,
-                      "the top 8 rows of the feature maps (as a map of their own)")
+    nr = min(cfg.H, max(8, oracle.num_threads()))  # the oracle's parallel loop is over (image, row)
+    r1, r2 = x1[:, :, :nr].copy(), x2[:, :, :nr].copy()
+    cpu = oracle_rate(lambda: oracle.correlation(r1, r2, cfg.search, cfg.stride), cfg.N * nr * cfg.W * n * n,
+                      "the top %d rows of the feature maps (as a map of their own)" % nr)
     return {
         "workload": cfg.name, "kernel": plan.launch_info()["kernel"], "avg_launch_us": t * 1e6, "launches": steps,
         "cpu_baseline": cpu,
