@@ -536,6 +536,7 @@ def main():
             (wl.CFG_DILATED.name, lambda: bench_conv(torch, mb, wl, wl.CFG_DILATED, k, w, args.sets)),
             (wl.CFG_CONV256.name, lambda: bench_conv(torch, mb, wl, wl.CFG_CONV256, kl, w, args.sets)),
             (wl.CFG_CONV256.name, lambda: bench_conv(torch, mb, wl, wl.CFG_CONV256, kl, w, args.sets, packed=True)),
+            (wl.CFG_CONV256.name, lambda: bench_conv(torch, mb, wl, wl.CFG_CONV256, kl, w, args.sets, relu=True, pool=True)),
             (wl.CFG_CONV256_B64.name, lambda: bench_conv(torch, mb, wl, wl.CFG_CONV256_B64, kl, w, 3)),
             (wl.CFG_CONV11.name, lambda: bench_conv(torch, mb, wl, wl.CFG_CONV11, kl, w, args.sets)),
             (wl.CFG_CORRELATION.name, lambda: bench_corr(torch, mb, wl, wl.CFG_CORRELATION, k, w)),

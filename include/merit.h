@@ -16,7 +16,10 @@
  *     16-byte aligned (else MERIT_ERR_ALIGNMENT).  Nothing is copied or kept.
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Work is enqueued and the call returns; the library never synchronises and
- *     never allocates device memory.
+ *     never allocates device memory -- with one exception, a convolution +
+ *     pooling plan that runs as two launches (see merit_plan_conv2d_pool), which
+ *     takes a stream-ordered temporary (hipMallocAsync / hipFreeAsync in the
+ *     caller's stream).
  *   - A plan is immutable host memory; it may be shared between threads and
  *     streams.  Plans are created and destroyed without touching the GPU.
  *   - Every function returns a merit_status; on any error nothing was launched.
@@ -195,7 +198,15 @@ merit_status merit_plan_conv2d_dilated(int N, int Cin, int H, int W, int Cout, i
  * Section VI-C).  Output [N,Cout,OH/2,OW/2].  Two kernel families take it: few input
  * channels (Cin < 8, window rows of at most 8 taps, W % 8 == 0, OH even, OW % 16 == 0, OW <= 128)
  * and 3x3 windows on many (Cin % 8 == 0, Cin >= 16, Cout >= 33, OH and OW even, OW <= 128);
- * anything else is MERIT_ERR_UNSUPPORTED (run the two operations one after the other). */
+ * anything else is MERIT_ERR_UNSUPPORTED (run the two operations one after the other).
+ * On many channels the planner compares two forms.  One kernel: work items are bands of pooled
+ * rows, and every band below an image's first recomputes the convolution rows above it, which
+ * a compute-bound layer on few images cannot hide (256 -> 256 channels on 56x56, 8 images: 1.8
+ * times the plain convolution).  Two launches: the plain convolution into a temporary of its
+ * result's size, taken from and returned to the stream's memory pool inside the call, then a
+ * binary16 pooling kernel over it (the same values: maxima are exact).  merit_plan_launch_info
+ * names the form ("merit_conv2d_chws_pool" or "merit_conv2d_chws+merit_maxpool_f16"); a tile
+ * request (merit_plan_set_tile: 8 x 64, 8 x 32, 12 x 64) always selects the one-kernel form. */
 merit_status merit_plan_conv2d_pool(int N, int Cin, int H, int W, int Cout, int kh, int kw,
                                     int sh, int sw, int ph, int pw, int relu, merit_plan **out);
 /* Residual layer (Section III-B, remark after Listing 1): y = x (*) w + r, or

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libmerit.so")
 
-SOURCES = ["merit_plan.cpp", "pool2d.hip", "sad_search.hip", "conv2d.hip", "conv2d_chws.hip", "generic.hip", "corr.hip", "dwconv.hip", "sepfilter.hip", "bilateral.hip", "probe.hip"]
+SOURCES = ["merit_plan.cpp", "pool2d.hip", "sad_search.hip", "conv2d.hip", "conv2d_chws.hip", "maxpool_f16.hip", "generic.hip", "corr.hip", "dwconv.hip", "sepfilter.hip", "bilateral.hip", "probe.hip"]
 HEADERS = [os.path.join(CSRC, "merit_internal.h"), os.path.join(ROOT, "include", "merit.h"),
            os.path.join(ROOT, "include", "merit_probe.h")]
 

@@ -176,6 +176,9 @@ const char *conv_kernel_name(const ConvParams &p);
 hipError_t launch_conv2d_chws(const ConvParams &p, const void *x, const void *w, const void *res, void *y, hipStream_t s,
                               bool packed);
 hipError_t launch_conv2d_pack_weights(const ConvParams &p, const void *w, void *packed, hipStream_t s);
+// 3x3 / stride 2 / padding 1 max pooling of a binary16 tensor [planes][OH][OW] (OH, OW even): the
+// second pass of a convolution + pooling plan that runs as two launches (csrc/maxpool_f16.hip)
+hipError_t launch_maxpool_f16(const void *c, void *y, int64_t planes, int OH, int OW, hipStream_t s);
 // the same two launches with the packed copy in the library's own fixed device buffer
 // (MERIT_NOALLOC_SCRATCH_BYTES; the caller has checked that the plan's packed weights fit)
 hipError_t launch_conv2d_chws_noalloc(const ConvParams &p, const void *x, const void *w, void *y, hipStream_t s);
@@ -296,4 +299,11 @@ struct merit_plan {
     int generic;                          // 1: no specialised kernel took the descriptor; `gen` runs it
     merit::GenericParams gen;
     merit_launch_info info;
+    // convolution plans on the wave-specialised multi-pass kernel: the planner's estimate for the
+    // chosen tiling, in units of one 256-pixel x 64-channel tile
+    double est_units;
+    // convolution + pooling plans that run as two launches (the plain convolution into a
+    // stream-ordered temporary, then the binary16 pooling kernel): `conv2` is the plain convolution
+    int two_pass;
+    merit::ConvParams conv2;
 };

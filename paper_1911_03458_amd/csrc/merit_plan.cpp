@@ -710,6 +710,8 @@ merit_status derive_conv(merit_plan *pl)
     // planar kernel, 8 x 32.  256-pixel tiles when that still leaves a large grid.
     const bool want_big = N * cdiv(ohw, 256) * p.co_groups >= 512;
     bool ok = false;
+    pl->est_units = 0.0;
+    pl->two_pass = 0;
     if (pool && Cin >= 8) {
         // many input channels: the wave-specialised multi-pass kernel pools out of its staging area.
         // A tile request names one of its tilings: 8 x 64 (256 pixels x 64 channels), 8 x 32 (128 x 64),
@@ -740,6 +742,7 @@ merit_status derive_conv(merit_plan *pl)
         }
         ok = best_tm != 0 && try_chws(best_cb, true, best_cb == 4 ? 12 : 8, best_tm, best_halo);
         if (!ok) return MERIT_ERR_UNSUPPORTED;
+        pl->est_units = best;
     } else if (pool) {
         // few input channels: the wave-specialised planar kernel pools; a tile request must name it (8 x 64) or nothing
         if (pl->tile_req[2] > 0 && pl->tile_req[3] > 0 && (pl->tile_req[2] != 8 || pl->tile_req[3] != 64))
@@ -813,7 +816,10 @@ merit_status derive_conv(merit_plan *pl)
                 p = saved;
                 if (fits && (best < 0 || cost < best_cost)) { best = shape; best_cost = cost; }
             }
-            if (best >= 0 && try_chws(best == 0 ? 4 : 2, true, best == 0 ? 12 : 8, best == 2 ? 128 : 256)) ok = true;
+            if (best >= 0 && try_chws(best == 0 ? 4 : 2, true, best == 0 ? 12 : 8, best == 2 ? 128 : 256)) {
+                ok = true;
+                pl->est_units = best_cost;
+            }
         }
     }
     if (!ok) {
@@ -866,6 +872,39 @@ merit_status derive_conv(merit_plan *pl)
     li.tile[4] = Cin; li.tile[5] = kh; li.tile[6] = kw;
     // convolution rows a band computes: its own and the row pair (few-channel kernel) or tile above
     if (pool) li.tile[2] = p.variant == CONV_CHWS ? ((p.pool_halo || p.NB == 1) ? p.rows_out_max * (int)cdiv(p.PB, p.rows_out_max / 2) : 2 * p.PB + p.rows_out_max) : 2 * (p.PB + 1);
+
+    // Convolution + pooling on many channels: pooling inside the kernel costs MFMA time (a band of
+    // pooled rows below the first recomputes the tile above it, tiles are whole rows, the 128-channel
+    // tiling rarely fits), which a compute-bound layer cannot hide.  When the estimate for the
+    // plain convolution plus one pass of the binary16 pooling kernel over its result is clearly
+    // lower, the plan runs as those two launches (the result is the same: the maxima are exact).
+    // Estimates in microseconds: a launch 4, a 256 x 64 tile 1.5 + 0.058 Cin kh kw / 9 (from
+    // timings on 64 .. 512 channels), the pooling pass 3.5 (it cannot start before the convolution
+    // has drained) + 1.25 x the convolution's result at 2.9 TB/s (measured: + 9 us for 12.8 MB,
+    // + 3.4 us for 1.6 MB).  A tile request names a fused tiling and keeps the plan fused.
+    if (pool && p.variant == CONV_CHWS && !(pl->tile_req[2] > 0 && pl->tile_req[3] > 0) && pl->est_units > 0.0) {
+        merit_plan *plain = new (std::nothrow) merit_plan(*pl);
+        if (plain) {
+            plain->desc.op = p.relu ? MERIT_OP_CONV_DOT_RELU : MERIT_OP_CONV_DOT;
+            if (derive_conv(plain) == MERIT_OK && plain->conv.variant == CONV_CHWS && plain->est_units > 0.0) {
+                const double unit = 1.5 + 0.058 * (double)Cin * (double)(kh * kw) / 9.0;
+                const double conv_bytes = (double)N * (double)Cout * (double)ohw * 2.0;
+                const double t_fused = 4.0 + pl->est_units * unit;
+                const double t_two = 4.0 + plain->est_units * unit + 3.5 + 1.25 * conv_bytes / 2.9e6;
+                // (a launch that leaves most of the chip idle is short: the second launch and the
+                // temporary's allocation calls would then cost more host time than the GPU saves)
+                if (t_two < 0.9 * t_fused && plain->info.grid[0] >= 128) {
+                    pl->two_pass = 1;
+                    pl->conv2 = plain->conv;
+                    const int64_t keep2 = li.tile[2];
+                    li = plain->info;
+                    li.tile[2] = keep2;
+                    li.kernel = "merit_conv2d_chws+merit_maxpool_f16";
+                }
+            }
+            delete plain;
+        }
+    }
     return MERIT_OK;
 }
 
@@ -1465,6 +1504,20 @@ merit_status merit_conv2d(const merit_plan *plan, const void *x, const void *w, 
     if (plan->conv.N == 0) return MERIT_OK;               // empty batch: nothing to read or write
     if (!x || !w || !y) return MERIT_ERR_NULL;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return MERIT_ERR_ALIGNMENT;
+    if (plan->two_pass) {
+        // the plain convolution into the plan's buffer on this device, then the pooling kernel
+        // The convolution's result lives in a stream-ordered temporary: allocated and released in
+        // the caller's stream, so calls on different streams never share it and the plan stays
+        // immutable.  (The pool that serves it keeps the memory for the next call.)
+        const ConvParams &q = plan->conv2;
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        void *mid = nullptr;
+        if (hipMallocAsync(&mid, (size_t)q.N * q.Cout * q.OH * q.OW * 2, s) != hipSuccess || !mid) return MERIT_ERR_HIP;
+        hipError_t e = launch_conv2d(q, x, w, nullptr, mid, s);
+        if (e == hipSuccess) e = launch_maxpool_f16(mid, y, (int64_t)q.N * q.Cout, q.OH, q.OW, s);
+        const hipError_t ef = hipFreeAsync(mid, s);
+        return (e == hipSuccess && ef == hipSuccess) ? MERIT_OK : MERIT_ERR_HIP;
+    }
     return launch_conv2d(plan->conv, x, w, nullptr, y, static_cast<hipStream_t>(stream)) == hipSuccess
                ? MERIT_OK
                : MERIT_ERR_HIP;

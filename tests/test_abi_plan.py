@@ -128,6 +128,25 @@ def test_fused_pooling_plan():
         assert e.value.status == mb.MERIT_ERR_UNSUPPORTED
 
 
+def test_pooling_plan_in_two_launches_where_fusion_would_cost_more():
+    """Compute-bound layers on few images (256 -> 256 on 56x56, batch 8): the plan runs the plain
+    convolution and then the binary16 pooling kernel; a tile request names a fused tiling and keeps
+    the plan fused, an empty request gives the choice back to the planner."""
+    plan = mb.merit_plan_conv2d_pool(8, 256, 56, 56, 256, 3, 3, 1, 1, 1, 1, 1)
+    assert plan.out_shape() == (8, 256, 28, 28)
+    li = plan.launch_info()
+    assert li["kernel"] == "merit_conv2d_chws+merit_maxpool_f16" and li["block"][0] == 768 and li["tile"][1] == 128
+    plan.set_tile((0, 0, 8, 64))
+    assert plan.launch_info()["kernel"] == "merit_conv2d_chws_pool"
+    plan.set_tile((0,) * 12)
+    assert plan.launch_info()["kernel"] == "merit_conv2d_chws+merit_maxpool_f16"
+    # memory-bound and small layers, launches that leave most of the chip idle, and launches with enough
+    # images to fill the chip with long bands stay fused
+    for shape in ((8, 64, 56, 56, 64), (8, 256, 28, 28, 512), (1, 256, 56, 56, 256), (32, 256, 56, 56, 256), (8, 128, 112, 112, 128)):
+        N, Cin, H, W, Cout = shape
+        assert mb.merit_plan_conv2d_pool(N, Cin, H, W, Cout, 3, 3, 1, 1, 1, 1, 1).launch_info()["kernel"] == "merit_conv2d_chws_pool"
+
+
 def test_fused_pooling_plan_many_channels():
     """The same fusion on the wave-specialised multi-pass kernel (3x3 layers with at least 16
     input and 33 output channels): work items are bands of pooled rows, tiles whole rows."""

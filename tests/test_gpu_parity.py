@@ -624,7 +624,7 @@ POOLFUSE_CHWS_CASES = [
     (2, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1, 0, (0, 0, 8, 64)),  # the same tiling on request; no clipping
     (1, 16, 12, 20, 64, 3, 3, 1, 1, 1, 1, 0, None),       # W % 8 != 0: one-pixel staging; 10 pooled columns: 2-byte stores
     (2, 32, 28, 28, 96, 3, 3, 1, 1, 1, 1, 1, None),       # 14 pooled columns, second channel block half empty
-    (1, 64, 16, 112, 64, 3, 3, 1, 1, 1, 1, 1, None),      # widest rows the 256-pixel tile takes two of
+    (1, 64, 16, 112, 64, 3, 3, 1, 1, 1, 1, 1, (0, 0, 8, 64)),  # widest rows the 256-pixel tile takes two of (on request: the planner would take two launches here)
     (3, 24, 36, 40, 64, 3, 3, 1, 1, 1, 1, 0, (0, 0, 8, 64)),  # 6 rows per tile, padded last pass (24 channels)
     (1, 16, 48, 48, 64, 3, 3, 2, 2, 1, 1, 1, None),       # stride-2 convolution below the pooling
     (150, 16, 16, 16, 64, 3, 3, 1, 1, 1, 1, 1, None),     # more bands than compute units: several items per workgroup
@@ -678,6 +678,45 @@ def test_conv_pool_fused(mb, case):
     plain = mb.merit_conv2d(unfused, dev(x), dev(w)).cpu().numpy()
     exact = oracle.pool2d(plain.astype(np.float32), (3, 3), (2, 2), (1, 1), "max").astype(np.float64)
     assert np.array_equal(got, exact)
+
+
+TWO_LAUNCH_POOL_CASES = [
+    # N  Cin  H   W  Cout relu  (shapes for which the planner takes the plain convolution + the pooling kernel)
+    (4, 128, 36, 56, 256, 1),      # 16-byte pooling loads (OW % 8 == 0), even pooled row count
+    (4, 256, 36, 28, 256, 0),      # 8-byte loads (OW % 4 == 0), no clipping
+    (4, 256, 38, 56, 256, 1),      # odd number of pooled rows: a plane's last thread row makes one pooled row
+    (4, 256, 36, 26, 256, 1),      # OW % 4 == 2: two pooled pixels per thread, odd pooled width
+]
+
+
+@pytest.mark.parametrize("case", TWO_LAUNCH_POOL_CASES)
+def test_conv_pool_in_two_launches(mb, case):
+    """Convolution + pooling plans the planner runs as two launches (compute-bound layers on few
+    images): against the oracle, exactly equal to the fused kernel's result on request, and the
+    second call reuses the plan's buffer."""
+    N, Cin, H, W, Cout, relu = case
+    rng = np.random.default_rng(abs(hash(case)) % 2 ** 31)
+    x = rng.standard_normal((N, Cin, H, W)).astype(np.float16)
+    w = (rng.standard_normal((Cout, Cin, 3, 3)) / np.sqrt(Cin * 9)).astype(np.float16)
+    plan = mb.merit_plan_conv2d_pool(N, Cin, H, W, Cout, 3, 3, 1, 1, 1, 1, relu)
+    assert plan.launch_info()["kernel"] == "merit_conv2d_chws+merit_maxpool_f16", plan.launch_info()
+    buf, y, p = guarded_empty(plan.out_shape(), torch.float16, 777.0)
+    mb.merit_conv2d(plan, dev(x), dev(w), y)
+    torch.cuda.synchronize()
+    check_canary(buf, p, 777.0)
+    got = y.cpu().numpy().astype(np.float64)
+    conv_ref = oracle.conv2d(x, w, (1, 1), (1, 1), relu=bool(relu))
+    ref = oracle.conv2d_pool(x, w, (1, 1), (1, 1), relu=bool(relu)).astype(np.float64)
+    assert got.shape == ref.shape
+    assert np.all(np.abs(got - ref) <= 2e-2 * _window_max_abs(conv_ref) + 1e-3)
+    fused = mb.merit_plan_conv2d_pool(N, Cin, H, W, Cout, 3, 3, 1, 1, 1, 1, relu)
+    fused.set_tile((0, 0, 8, 64))
+    assert fused.launch_info()["kernel"] == "merit_conv2d_chws_pool"
+    assert torch.equal(mb.merit_conv2d(fused, dev(x), dev(w)), y)
+    # a second input through the same plan (its buffer is reused)
+    x2 = rng.standard_normal((N, Cin, H, W)).astype(np.float16)
+    y2 = mb.merit_conv2d(plan, dev(x2), dev(w))
+    assert torch.equal(mb.merit_conv2d(fused, dev(x2), dev(w)), y2)
 
 
 def test_conv_pool_fused_7x7_workload(mb):
