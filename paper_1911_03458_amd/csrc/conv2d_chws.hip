@@ -56,13 +56,13 @@ __device__ __forceinline__ Geom tile_geom(const ConvParams &p, int item, int ohw
     const int tile = (int)fdiv((uint32_t)item, p.div_cog);
     g.cg = item - tile * p.co_groups;
     g.n = (int)fdiv((uint32_t)tile, p.div_tiles);
-    g.m0 = (tile - g.n * p.tiles_per_image) * p.TM;
+    g.m0 = (tile - g.n * p.tiles_per_image) * p.tile_px;
     g.oyA = (int)fdiv((uint32_t)g.m0, p.div_ow);
-    const int mlast = min(g.m0 + p.TM, ohw) - 1;
+    const int mlast = min(g.m0 + p.tile_px, ohw) - 1;
     const int oyB = (int)fdiv((uint32_t)mlast, p.div_ow);
     g.yA = g.oyA * p.sh - p.ph;
     g.RH = (oyB - g.oyA) * p.sh + (p.kh - 1) * p.dh + 1;
-    g.mend = min(g.m0 + p.TM, ohw);
+    g.mend = min(g.m0 + p.tile_px, ohw);
     g.pr0 = g.warm = g.top = g.roff = g.par = 0;
     return g;
 }
@@ -192,7 +192,7 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
             const int px8 = u - c * (TM / 8);
             const int m = g.m0 + px8 * 8;
             const int co = g.cg * TN + c;
-            if (m >= ohw || co >= p.Cout) continue;
+            if (m >= g.mend || co >= p.Cout) continue;       // (a tile of whole rows ends before the 256th pixel)
             const uint2 *src = reinterpret_cast<const uint2 *>(outl + c * OP + px8 * 4);
             const uint2 lo = src[0], hi = src[1];
             uint16_t *y0 = y + ((size_t)g.n * p.Cout + co) * ohw + m;
@@ -204,7 +204,7 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
                 const uint32_t e[4] = {lo.x, lo.y, hi.x, hi.y};
 #pragma unroll
                 for (int k = 0; k < 8; ++k) {
-                    if (m + k >= ohw) break;
+                    if (m + k >= g.mend) break;
                     y0[k] = (uint16_t)(e[k >> 1] >> (16 * (k & 1)));
                 }
             }

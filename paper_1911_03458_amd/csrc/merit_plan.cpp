@@ -476,6 +476,7 @@ merit_status derive_conv(merit_plan *pl)
         q.tiles_per_image = (int)cdiv(ohw, q.TM);
         q.rows_out_max = (int)((q.TM + OW - 2) / OW + 1);
         if (q.rows_out_max > OH) q.rows_out_max = (int)OH;
+        q.tile_px = q.TM;
         if (pool) q.rows_out_max = 2;
         q.RHa = (int)((q.rows_out_max - 1) * sh + eh);
         if (variant == CONV_PLANAR_SMALLC) {
@@ -628,6 +629,27 @@ merit_status derive_conv(merit_plan *pl)
         q.tiles_per_image = (int)cdiv(ohw, q.TM);
         q.rows_out_max = (int)((q.TM + OW - 2) / OW + 1);
         if (q.rows_out_max > OH) q.rows_out_max = (int)OH;
+        q.tile_px = q.TM;
+        if (!pool && tm == 256) {
+            // A tile of TM consecutive pixels starts anywhere in a row, so its covering sub-tensor
+            // (Section IV-A, Eq. 9) is rows_out_max whole rows + the window's: on a 224-wide image
+            // 5 staged rows for 1.14 rows of results.  Tiles of whole rows (R rows, R OW <= TM, the
+            // rest of the MFMA tile idle) stage R - 1 + kh rows: taken when at least 80 % of the
+            // tile is used and a fifth less input is staged over the image (224-wide: 51.8 -> 45.5 us for
+            // 64 -> 64 channels; 112-wide: 3-5 % faster; 56-wide, a fifth less: no gain, not taken;
+            // nor on the 128-pixel tiles of small launches, where the extra workgroups cost more).
+            int64_t R = q.TM / OW;
+            if (R > OH) R = OH;
+            if (R >= 1 && (R * OW) % 8 == 0 && R * OW * 10 >= (int64_t)q.TM * 8) {
+                const int64_t stage_lin = (int64_t)q.tiles_per_image * ((q.rows_out_max - 1) * sh + eh);
+                const int64_t stage_row = cdiv(OH, R) * ((R - 1) * sh + eh);
+                if (stage_row * 100 <= stage_lin * 80) {
+                    q.tile_px = (int)(R * OW);
+                    q.tiles_per_image = (int)cdiv(OH, R);
+                    q.rows_out_max = (int)R;
+                }
+            }
+        }
         if (pool) {
             // R whole rows per tile.  Carried row above (R even, R / 2 pooled rows per tile): bands of PB
             // pooled rows, a multiple of R / 2, about one band per compute unit (every band below the
@@ -809,10 +831,10 @@ merit_status derive_conv(merit_plan *pl)
             for (int shape = 0; shape < 3; ++shape) {          // 0: 256 x 128 on 12 wavefronts, 1: 256 x 64, 2: 128 x 64
                 if (shape == 0 && ncb < 4) continue;
                 const int64_t tm = shape == 2 ? 128 : 256;
-                const int64_t items = N * cdiv(ohw, tm) * cdiv(ncb, shape == 0 ? 4 : 2);
-                const double cost = (double)cdiv(items, 256) * (shape == 0 ? 1.6 : (shape == 1 ? 1.0 : 0.6));
                 const ConvParams saved = p;
                 const bool fits = try_chws(shape == 0 ? 4 : 2, true, shape == 0 ? 12 : 8, (int)tm);
+                const int64_t items = N * (int64_t)p.tiles_per_image * p.co_groups;     // (of the trial, if it fits)
+                const double cost = (double)cdiv(items, 256) * (shape == 0 ? 1.6 : (shape == 1 ? 1.0 : 0.6));
                 p = saved;
                 if (fits && (best < 0 || cost < best_cost)) { best = shape; best_cost = cost; }
             }

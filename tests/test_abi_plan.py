@@ -128,6 +128,18 @@ def test_fused_pooling_plan():
         assert e.value.status == mb.MERIT_ERR_UNSUPPORTED
 
 
+def test_wide_images_get_tiles_of_whole_rows():
+    """64 -> 64 on 224x224: a 256-pixel run would start anywhere in a row and stage 5 rows for
+    1.14 rows of results; a tile of one whole row (224 pixels) stages 3.  56-wide layers keep the
+    runs (a fifth less staging does not pay for the idle eighth of the tile)."""
+    wide = mb.merit_plan_conv2d(8, 64, 224, 224, 64, 3, 3, 1, 1, 1, 1).launch_info()
+    assert wide["kernel"] == "merit_conv2d_chws" and wide["tile"][2] == 1 and wide["tile"][3] == 224
+    mid = mb.merit_plan_conv2d(8, 128, 112, 112, 128, 3, 3, 1, 1, 1, 1).launch_info()
+    assert mid["kernel"] == "merit_conv2d_chws" and mid["tile"][2] == 2
+    narrow = mb.merit_plan_conv2d(8, 256, 56, 56, 256, 3, 3, 1, 1, 1, 1).launch_info()
+    assert narrow["tile"][2] == 6 and narrow["grid"][0] == 208
+
+
 def test_pooling_plan_in_two_launches_where_fusion_would_cost_more():
     """Compute-bound layers on few images (256 -> 256 on 56x56, batch 8): the plan runs the plain
     convolution and then the binary16 pooling kernel; a tile request names a fused tiling and keeps

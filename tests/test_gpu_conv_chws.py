@@ -59,6 +59,11 @@ CHWS_CASES = [
     ((2, 16, 40, 40, 64, 3, 3, 1, 1, 1, 1), (1, 1), 0, (0, 0, 8, 64)),      # a single pass per item
     ((2, 48, 27, 27, 256, 3, 3, 1, 1, 0, 0), (1, 1), 1, (0, 0, 8, 128)),    # no padding, odd width, three passes
     ((1, 64, 9, 10, 64, 1, 1, 2, 2, 0, 0), (1, 1), 0, (0, 0, 8, 64)),       # 1x1 stride 2, tiny image
+    # tiles of whole rows (wide images: two rows of 112, one of 224 in a 256-pixel tile)
+    ((1, 32, 21, 112, 70, 3, 3, 1, 1, 1, 1), (1, 1), 0, (0, 0, 8, 64)),     # odd row count: the last tile is one row; ragged channels
+    ((1, 64, 9, 112, 64, 1, 1, 1, 1, 0, 0), (1, 1), 1, (0, 0, 8, 64)),      # 1x1
+    ((1, 32, 24, 224, 64, 3, 3, 2, 2, 1, 1), (1, 1), 0, (0, 0, 8, 64)),     # stride 2 from 224 columns to 112
+    ((2, 48, 10, 112, 160, 3, 3, 1, 1, 1, 1), (1, 1), 1, (0, 0, 12, 64)),   # 128-channel tiles on 12 wavefronts
     # 128-pixel tiles, 32 channels per pass (the 3x3 workload's shape class)
     ((2, 64, 28, 56, 64, 3, 3, 1, 1, 1, 1), (1, 1), 0, (0, 0, 8, 32)),      # two passes
     ((3, 80, 17, 24, 40, 3, 3, 1, 1, 1, 1), (1, 1), 1, (0, 0, 8, 32)),      # last pass half empty, ragged channel block
@@ -187,6 +192,27 @@ def test_chws_many_channel_workload_on_a_batch_of_64(mb):
         ref = oracle.conv2d(x[n:n + 1], w, (1, 1), (1, 1)).astype(np.float64)
         got = y[n:n + 1].cpu().numpy().astype(np.float64)
         assert np.all(np.abs(got - ref) <= 2e-2 * np.abs(ref) + 1e-3), n
+
+
+def test_chws_whole_row_tiles_with_an_added_tensor(mb):
+    """Tiles of two whole rows of 112 (224 of the 256 pixels used) on the residual instance: the
+    added tensor is read per tile, the pixels past a tile's end are never stored."""
+    N, Cin, H, W, Cout = 1, 32, 11, 112, 64
+    rng = np.random.default_rng(112)
+    x = rng.standard_normal((N, Cin, H, W)).astype(np.float16)
+    w = (rng.standard_normal((Cout, Cin, 3, 3)) / np.sqrt(Cin * 9)).astype(np.float16)
+    r = rng.standard_normal((N, Cout, H, W)).astype(np.float16)
+    plan = mb.merit_plan_conv2d_residual(N, Cin, H, W, Cout, 3, 3, 1, 1, 1, 1, 1)
+    plan.set_tile((0, 0, 8, 64))
+    li = plan.launch_info()
+    assert li["kernel"] == "merit_conv2d_chws" and li["tile"][2] == 2 and li["grid"][0] == 6
+    buf, y, pad = guarded(plan.out_shape())
+    mb.merit_conv2d_residual(plan, dev(x), dev(w), dev(r), y)
+    torch.cuda.synchronize()
+    assert canary_ok(buf, pad)
+    ref = oracle.conv2d_residual(x, w, r, (1, 1), (1, 1), True).astype(np.float64)
+    got = y.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - ref) <= 2e-2 * np.abs(ref) + 1e-3)
 
 
 def test_packed_entry_points_refuse_other_plans(mb):
