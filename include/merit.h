@@ -254,8 +254,8 @@ merit_status merit_plan_launch_info(const merit_plan *plan, merit_launch_info *o
  * multiplying wavefront.  4 x 32, 4 x 64 and (fewer than 8 input channels) 8 x 32:
  * every wavefront stages, multiplies and stores, tile[2]*tile[3] pixels per
  * workgroup.  8 x 64: 4 multiplying + 4 data-moving wavefronts, 256 pixels per
- * workgroup (x 64 output channels).  On 8 and more input channels (3x3 and 1x1
- * windows, Cin % 8 == 0) also 8 x 128 (256 pixels x 128 channels), 8 x 32 (128
+ * workgroup (x 64 output channels).  On 8 and more input channels (3x3, 1x1 and --
+ * 8 x 64 only -- 5x5 windows, Cin % 8 == 0) also 8 x 128 (256 pixels x 128 channels), 8 x 32 (128
  * pixels x 64 channels, 32 input channels per pass) and 12 x 64 (8 multiplying +
  * 4 moving wavefronts, 256 pixels x 128 channels); a fused-pooling plan on many
  * channels takes 8 x 64, 8 x 32 and 12 x 64.  Block matching

@@ -115,7 +115,7 @@ constexpr uint32_t OOB = 0x80000000u;   // a buffer offset past the end of every
 }  // namespace
 
 // PXB x CHB: 32x32 blocks per multiplying wavefront; WM x WN = 4 multiplying wavefronts.
-// T: taps of the window (9 = 3x3, 1 = 1x1).  XU = 1, 2: the input rows are staged in units of 8
+// T: taps of the window (25 = 5x5, 9 = 3x3, 1 = 1x1).  XU = 1, 2: the input rows are staged in units of 8
 // channels x 8 pixels (W % 8 == 0), XU of them per moving thread and pass; XU = 0: in units of
 // 8 channels x 1 pixel, up to XS_MAX per thread.
 // NG: pairs of 8-channel groups per pass (1: 16 channels, 2: 32 -- small tiles, whose passes would
@@ -539,7 +539,8 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
     const int wm = wave % WM, wn = wave / WM;
     for (bool more = true; more; more = next_pos(item, ti, ntile)) {
         const Geom g = geom_at(item, ti);
-        int xc[PXB][T == 9 ? 3 : 1];
+        constexpr int KW = T == 25 ? 5 : (T == 9 ? 3 : 1);   // the window is square: T = KW * KW taps
+        int xc[PXB][KW];
 #pragma unroll
         for (int pb = 0; pb < PXB; ++pb) {
             const int m = g.m0 + (wm * PXB + pb) * 32 + c32;
@@ -549,7 +550,7 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
             const int pbase = (h * p.RHa + (oy - g.oyA) * p.sh) * p.pitch;
             const int pcol = (p.padl - p.pw) + ox * p.sw;
 #pragma unroll
-            for (int kx = 0; kx < (T == 9 ? 3 : 1); ++kx) xc[pb][kx] = pbase + pcol + kx * p.dw;
+            for (int kx = 0; kx < KW; ++kx) xc[pb][kx] = pbase + pcol + kx * p.dw;
         }
         floatx16 acc[CHB][PXB];
 #pragma unroll
@@ -599,7 +600,7 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
             Frag a[2][CHB], b[2][PXB];
             auto load = [&](int s, int slot) __attribute__((always_inline)) {
                 const int gp = s / T, tap = s % T;               // step = (pair of channel groups, tap)
-                const int ky = T == 9 ? tap / 3 : 0, kx = T == 9 ? tap % 3 : 0;
+                const int ky = tap / KW, kx = tap % KW;
                 const int xgrp = gp * 2 * p.RHa * p.pitch;
 #pragma unroll
                 for (int cb = 0; cb < CHB; ++cb) a[slot][cb].u = wl[(s * NCB + cb) * 64];
@@ -746,6 +747,12 @@ hipError_t launch_tile(const ConvParams &p, const void *x, const void *w, const 
     if (T == 1 && xu == 1) MERIT_CHWS(1, 1);
     if (T == 1 && xu == 2) MERIT_CHWS(1, 2);
     if (T == 1 && xu == 0) MERIT_CHWS(1, 0);
+    // 5x5 windows: the 256-pixel x 64-channel tiling only (a pass's 25 x 2 x 64 weight fragments are 51 KB)
+    if constexpr (PXB == 2 && CHB == 2 && WM == 4 && WN == 1 && NG == 1) {
+        if (T == 25 && xu == 1) MERIT_CHWS(25, 1);
+        if (T == 25 && xu == 2) MERIT_CHWS(25, 2);
+        if (T == 25 && xu == 0) MERIT_CHWS(25, 0);
+    }
 #undef MERIT_CHWS
     return hipErrorInvalidValue;
 }

@@ -605,10 +605,13 @@ merit_status derive_conv(merit_plan *pl)
     };
 
     // Wave-specialised multi-pass kernel (conv2d_chws.hip): 256-pixel tiles x `cb` 32-channel blocks
-    // (4 or 2), 16 input channels per pass through two LDS buffers, 3x3 or 1x1 windows on a multiple
+    // (4 or 2), 16 input channels per pass through two LDS buffers, 3x3, 1x1 or 5x5 windows on a multiple
     // of 8 input channels.
     auto try_chws = [&](int cb, bool forced, int nw = 8, int tm = 256, bool halo = false) -> bool {
-        if (!((kh == 3 && kw == 3) || (kh == 1 && kw == 1))) return false;
+        const bool k5 = kh == 5 && kw == 5;
+        if (!((kh == 3 && kw == 3) || (kh == 1 && kw == 1) || k5)) return false;
+        // 5x5 windows: the 256 x 64 tiling on 8 wavefronts, no added tensor, no pooling
+        if (k5 && (cb != 2 || nw != 8 || tm != 256 || pool || p.residual)) return false;
         // its tiles are 256 pixels of one image: small images (13x13, 7x7) would leave a third
         // and more of every tile empty and stay with the 128-pixel tiles of the plain kernels
         if (!forced && !pool && 4 * ohw < 3 * cdiv(ohw, tm) * tm) return false;
@@ -826,7 +829,7 @@ merit_status derive_conv(merit_plan *pl)
         // the plain multi-pass kernel; 7x7 on 128-pixel tiles: 28 against 88).  1x1 layers the same
         // (256 -> 64 on 56x56: 8.1 against 11.9 us, 1024 -> 256 on 14x14: 27 against 51); with a residual
         // tensor they stay on the plain kernels.
-        if (((kh == 3 && kw == 3) || (kh == 1 && kw == 1 && !p.residual)) && Cin >= 32 && (Cin % 8) == 0 && ncb >= 2) {
+        if (((kh == 3 && kw == 3) || ((kh == 1 && kw == 1 || kh == 5 && kw == 5) && !p.residual)) && Cin >= 32 && (Cin % 8) == 0 && ncb >= 2) {
             int best = -1; double best_cost = 0.0;
             for (int shape = 0; shape < 3; ++shape) {          // 0: 256 x 128 on 12 wavefronts, 1: 256 x 64, 2: 128 x 64
                 if (shape == 0 && ncb < 4) continue;

@@ -537,7 +537,9 @@ def test_conv_plans_for_layers_that_do_not_fit_lds_at_once():
     window on few channels fits neither MFMA layout; the tile request and the fused pooling
     stay with the MFMA kernels."""
     for shape, kernel in (((1, 512, 14, 14, 512, 3, 3, 1, 1, 1, 1), "merit_conv2d_chws"),
-                          ((1, 96, 27, 27, 256, 5, 5, 1, 1, 2, 2), "merit_conv2d_chpass"),      # 5x5 window
+                          ((1, 96, 27, 27, 256, 5, 5, 1, 1, 2, 2), "merit_conv2d_chws"),        # 5x5 window on a multiple of 8 channels
+                              ((1, 100, 27, 27, 256, 5, 5, 1, 1, 2, 2), "merit_conv2d_chpass"),     # 5x5, Cin % 8 != 0
+                              ((1, 96, 27, 27, 256, 7, 7, 1, 1, 3, 3), "merit_conv2d_chpass"),      # 7x7 window on many channels
                           ((1, 512, 7, 7, 512, 3, 3, 1, 1, 1, 1), "merit_conv2d_chws"),         # 49 pixels on a 128-pixel tile: still the faster kernel
                           ((1, 300, 56, 56, 64, 3, 3, 1, 1, 1, 1), "merit_conv2d_chpass"),      # Cin % 8 != 0
                           ((1, 64, 224, 224, 64, 3, 3, 1, 1, 1, 1), "merit_conv2d_chws"),

@@ -64,6 +64,12 @@ CHWS_CASES = [
     ((1, 64, 9, 112, 64, 1, 1, 1, 1, 0, 0), (1, 1), 1, (0, 0, 8, 64)),      # 1x1
     ((1, 32, 24, 224, 64, 3, 3, 2, 2, 1, 1), (1, 1), 0, (0, 0, 8, 64)),     # stride 2 from 224 columns to 112
     ((2, 48, 10, 112, 160, 3, 3, 1, 1, 1, 1), (1, 1), 1, (0, 0, 12, 64)),   # 128-channel tiles on 12 wavefronts
+    # 5x5 windows (256 x 64 tiles; a pass's weights are 25 x 2 x 64 fragments)
+    ((2, 96, 27, 27, 256, 5, 5, 1, 1, 2, 2), (1, 1), 1, None),              # the 5x5 layer of the per-layer table: one-pixel units, 6 passes
+    ((1, 32, 24, 56, 64, 5, 5, 1, 1, 2, 2), (1, 1), 0, None),               # 8-pixel input units, two passes
+    ((1, 40, 24, 32, 70, 5, 5, 2, 2, 2, 2), (1, 1), 0, (0, 0, 8, 64)),      # stride 2, last pass half empty, ragged channels
+    ((1, 32, 30, 40, 64, 5, 5, 1, 1, 4, 4), (2, 2), 1, (0, 0, 8, 64)),      # dilated 5x5 window
+    ((1, 64, 12, 16, 96, 5, 5, 1, 1, 0, 0), (1, 1), 0, (0, 0, 8, 64)),      # no padding
     # 128-pixel tiles, 32 channels per pass (the 3x3 workload's shape class)
     ((2, 64, 28, 56, 64, 3, 3, 1, 1, 1, 1), (1, 1), 0, (0, 0, 8, 32)),      # two passes
     ((3, 80, 17, 24, 40, 3, 3, 1, 1, 1, 1), (1, 1), 1, (0, 0, 8, 32)),      # last pass half empty, ragged channel block
