@@ -160,7 +160,7 @@ def test_random_shapes(seed):
 @pytest.mark.parametrize("seed", [1103, 458])
 def test_random_layer_shapes(seed):
     """Layers with many channels (the shapes the wave-specialised convolution kernels take):
-    3x3 and 1x1 windows on 32..256 input channels, any output-channel count and ragged image
+    3x3, 1x1 and 5x5 windows on 32..256 input channels, any output-channel count and ragged image
     extents, through every way a convolution can be called: plain, clipped, with an added
     tensor, with the fused 3x3 / stride 2 / padding 1 max pooling, with weights packed once,
     and through the entry point that allocates nothing."""
@@ -176,9 +176,9 @@ def test_random_layer_shapes(seed):
         if rng.random() < 0.5: Cout = 32 * ri(2, 8)
         H, W = ri(4, 36), ri(4, 36)
         if rng.random() < 0.3: H = W = int(rng.choice([7, 14, 28, 56])); N = 1
-        k = 3 if rng.random() < 0.7 else 1
+        k = int(rng.choice([3, 3, 3, 3, 3, 3, 1, 1, 5, 5]))
         s = 1 if rng.random() < 0.8 else 2
-        pd = ri(0, 1) if k == 3 else 0
+        pd = ri(0, k // 2)
         if H + 2 * pd < k or W + 2 * pd < k: continue
         mode = str(rng.choice(["plain", "relu", "residual", "pool", "packed", "noalloc"]))
         relu = int(mode in ("relu", "pool") or (mode == "residual" and rng.random() < 0.5))
