@@ -769,6 +769,7 @@ hipError_t launch_conv2d_chws(const ConvParams &p, const void *x, const void *w,
     const uint32_t grid = (uint32_t)(nitems < slots ? nitems : slots);
     if (p.CB == 4 && p.NW == 12) return launch_tile<2, 2, 4, 2, 1, true>(p, x, w, res, y, s, grid, packed);   // 256 x 128, 8 x (64 x 64)
     if (p.CB == 4) return launch_tile<4, 2, 2, 2>(p, x, w, res, y, s, grid, packed);     // 256 pixels x 128 channels, 4 x (128 x 64)
+    if (p.TM == 128 && p.CB == 1) return launch_tile<1, 1, 4, 1, 2, false>(p, x, w, res, y, s, grid, packed);   // 128 pixels x 32 channels, 4 x (32 x 32)
     if (p.TM == 128) return launch_tile<1, 2, 4, 1, 2, true>(p, x, w, res, y, s, grid, packed);   // 128 pixels x 64 channels, 4 x (32 x 64), 32 channels per pass
     return launch_tile<2, 2, 4, 1, 1, true>(p, x, w, res, y, s, grid, packed);           // 256 pixels x 64 channels, 4 x (64 x 64)
 }

@@ -618,7 +618,10 @@ merit_status derive_conv(merit_plan *pl)
         if (Cin % 8 != 0 || Cin < 16 || (pool && p.residual) || ncb < 2) return false;
         // residual layer: 3x3 windows, the 64-channel tilings on 8 wavefronts
         if (p.residual && (kh != 3 || cb != 2 || nw != 8)) return false;
-        if (cb != 2 && cb != 4) return false;
+        if (cb != 1 && cb != 2 && cb != 4) return false;
+        // 32-channel tiles: 128 pixels on 8 wavefronts, 3x3 and 1x1 windows, no added tensor, no pooling (for launches
+        // that would otherwise leave half the chip idle)
+        if (cb == 1 && (nw != 8 || tm != 128 || pool || p.residual || k5)) return false;
         // fused pooling: 3x3 windows, the 64-channel tilings and the 128-channel one on 12 wavefronts; a tile is whole rows
         if (pool && (kh != 3 || !((cb == 2 && nw == 8) || (cb == 4 && nw == 12)) || (halo ? 3 : 2) * OW > tm)) return false;
         ConvParams q = p;
@@ -627,8 +630,8 @@ merit_status derive_conv(merit_plan *pl)
         q.co_groups = (int)cdiv(ncb, cb);
         q.PXW = tm == 128 ? 1 : ((cb == 4 && nw == 8) ? 4 : 2);    // 32-pixel blocks per multiplying wavefront
         q.NW = nw;                               // 8: four multiplying + four moving wavefronts; 12: eight + four
-        q.TM = tm;                               // 256 pixels, or 128 (64-channel tiles on 8 wavefronts only)
-        if (tm != 256 && !(tm == 128 && cb == 2 && nw == 8)) return false;
+        q.TM = tm;                               // 256 pixels, or 128 (64- and 32-channel tiles on 8 wavefronts only)
+        if (tm != 256 && !(tm == 128 && (cb == 2 || cb == 1) && nw == 8)) return false;
         q.tiles_per_image = (int)cdiv(ohw, q.TM);
         q.rows_out_max = (int)((q.TM + OW - 2) / OW + 1);
         if (q.rows_out_max > OH) q.rows_out_max = (int)OH;
@@ -831,17 +834,18 @@ merit_status derive_conv(merit_plan *pl)
         // tensor they stay on the plain kernels.
         if (((kh == 3 && kw == 3) || ((kh == 1 && kw == 1 || kh == 5 && kw == 5) && !p.residual)) && Cin >= 32 && (Cin % 8) == 0 && ncb >= 2) {
             int best = -1; double best_cost = 0.0;
-            for (int shape = 0; shape < 3; ++shape) {          // 0: 256 x 128 on 12 wavefronts, 1: 256 x 64, 2: 128 x 64
+            for (int shape = 0; shape < 4; ++shape) {          // 0: 256 x 128 on 12 wavefronts, 1: 256 x 64, 2: 128 x 64, 3: 128 x 32
                 if (shape == 0 && ncb < 4) continue;
-                const int64_t tm = shape == 2 ? 128 : 256;
+                const int64_t tm = shape >= 2 ? 128 : 256;
+                const int cbs = shape == 0 ? 4 : (shape == 3 ? 1 : 2);
                 const ConvParams saved = p;
-                const bool fits = try_chws(shape == 0 ? 4 : 2, true, shape == 0 ? 12 : 8, (int)tm);
+                const bool fits = try_chws(cbs, true, shape == 0 ? 12 : 8, (int)tm);
                 const int64_t items = N * (int64_t)p.tiles_per_image * p.co_groups;     // (of the trial, if it fits)
-                const double cost = (double)cdiv(items, 256) * (shape == 0 ? 1.6 : (shape == 1 ? 1.0 : 0.6));
+                const double cost = (double)cdiv(items, 256) * (shape == 0 ? 1.6 : (shape == 1 ? 1.0 : (shape == 2 ? 0.6 : 0.42)));
                 p = saved;
                 if (fits && (best < 0 || cost < best_cost)) { best = shape; best_cost = cost; }
             }
-            if (best >= 0 && try_chws(best == 0 ? 4 : 2, true, best == 0 ? 12 : 8, best == 2 ? 128 : 256)) {
+            if (best >= 0 && try_chws(best == 0 ? 4 : (best == 3 ? 1 : 2), true, best == 0 ? 12 : 8, best >= 2 ? 128 : 256)) {
                 ok = true;
                 pl->est_units = best_cost;
             }
@@ -916,9 +920,9 @@ merit_status derive_conv(merit_plan *pl)
                 const double conv_bytes = (double)N * (double)Cout * (double)ohw * 2.0;
                 const double t_fused = 4.0 + pl->est_units * unit;
                 const double t_two = 4.0 + plain->est_units * unit + 3.5 + 1.25 * conv_bytes / 2.9e6;
-                // (a launch that leaves most of the chip idle is short: the second launch and the
-                // temporary's allocation calls would then cost more host time than the GPU saves)
-                if (t_two < 0.9 * t_fused && plain->info.grid[0] >= 128) {
+                // (on a short launch the second launch and the temporary's allocation calls cost
+                // more host time than the GPU saves: the convolution alone must be estimated at 12 us)
+                if (t_two < 0.9 * t_fused && plain->est_units * unit >= 12.0) {
                     pl->two_pass = 1;
                     pl->conv2 = plain->conv;
                     const int64_t keep2 = li.tile[2];

@@ -128,6 +128,21 @@ def test_fused_pooling_plan():
         assert e.value.status == mb.MERIT_ERR_UNSUPPORTED
 
 
+def test_small_launches_get_32_channel_tiles():
+    """A launch whose 128-pixel x 64-channel tiles would leave half the chip idle takes 128 x 32
+    tiles (twice the work items, each 0.7 of the time); with enough items for every compute unit
+    the 64-channel tiles stay."""
+    small = mb.merit_plan_conv2d(8, 512, 14, 14, 512, 3, 3, 1, 1, 1, 1).launch_info()
+    assert small["kernel"] == "merit_conv2d_chws" and small["tile"][1] == 32 and small["grid"][0] == 256
+    one = mb.merit_plan_conv2d(1, 256, 56, 56, 256, 3, 3, 1, 1, 1, 1).launch_info()
+    assert one["tile"][1] == 32 and one["grid"][0] == 200
+    full = mb.merit_plan_conv2d(8, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1).launch_info()
+    assert full["tile"][1] == 64 and full["grid"][0] == 200
+    # an added tensor keeps the 64-channel tiles (the residual instance)
+    res = mb.merit_plan_conv2d_residual(1, 256, 56, 56, 256, 3, 3, 1, 1, 1, 1, 1).launch_info()
+    assert res["kernel"] == "merit_conv2d_chws" and res["tile"][1] == 64
+
+
 def test_wide_images_get_tiles_of_whole_rows():
     """64 -> 64 on 224x224: a 256-pixel run would start anywhere in a row and stage 5 rows for
     1.14 rows of results; a tile of one whole row (224 pixels) stages 3.  56-wide layers keep the

@@ -682,10 +682,10 @@ def test_conv_pool_fused(mb, case):
 
 TWO_LAUNCH_POOL_CASES = [
     # N  Cin  H   W  Cout relu  (shapes for which the planner takes the plain convolution + the pooling kernel)
-    (4, 128, 36, 56, 256, 1),      # 16-byte pooling loads (OW % 8 == 0), even pooled row count
-    (4, 256, 36, 28, 256, 0),      # 8-byte loads (OW % 4 == 0), no clipping
+    (4, 256, 40, 56, 256, 1),      # 16-byte pooling loads (OW % 8 == 0), even pooled row count
+    (4, 256, 36, 52, 256, 0),      # 8-byte loads (OW % 4 == 0), no clipping
     (4, 256, 38, 56, 256, 1),      # odd number of pooled rows: a plane's last thread row makes one pooled row
-    (4, 256, 36, 26, 256, 1),      # OW % 4 == 2: two pooled pixels per thread, odd pooled width
+    (4, 256, 36, 54, 256, 1),      # OW % 4 == 2: two pooled pixels per thread, odd pooled width
 ]
 
 
