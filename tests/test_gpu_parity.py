@@ -1316,12 +1316,12 @@ def test_more_launches_can_be_captured_in_a_graph(mb):
     sep = mb.merit_plan_sepfilter(1, 70, 136, 30)
     kx = rng.standard_normal(30).astype(np.float32); ky = rng.standard_normal(30).astype(np.float32)
     xs = torch.zeros((1, 70, 136), dtype=torch.float32, device="cuda:0"); ys = torch.empty_like(xs)
-    cp = mb.merit_plan_conv2d(1, 264, 10, 16, 40, 5, 5, 1, 1, 2, 2)
+    cp = mb.merit_plan_conv2d(1, 260, 10, 16, 40, 5, 5, 1, 1, 2, 2)
     cd = mb.merit_plan_conv2d(1, 3, 45, 45, 6, 11, 17, 4, 4, 0, 0)
     assert cp.launch_info()["kernel"] == "merit_conv2d_chpass" and cd.launch_info()["kernel"] == "merit_conv2d_direct"
-    wp = (rng.standard_normal((40, 264, 5, 5)) / 81).astype(np.float16)
+    wp = (rng.standard_normal((40, 260, 5, 5)) / 81).astype(np.float16)
     wd = (rng.standard_normal((6, 3, 11, 17)) / 24).astype(np.float16)
-    xp = torch.zeros((1, 264, 10, 16), dtype=torch.float16, device="cuda:0")
+    xp = torch.zeros((1, 260, 10, 16), dtype=torch.float16, device="cuda:0")
     xd = torch.zeros((1, 3, 45, 45), dtype=torch.float16, device="cuda:0")
     yp = torch.empty(cp.out_shape(), dtype=torch.float16, device="cuda:0")
     yd = torch.empty(cd.out_shape(), dtype=torch.float16, device="cuda:0")
@@ -1350,7 +1350,7 @@ def test_more_launches_can_be_captured_in_a_graph(mb):
         launch_all()
     for rep in range(2):
         a = rng.uniform(0, 255, (1, 70, 136)).astype(np.float32)
-        b = rng.standard_normal((1, 264, 10, 16)).astype(np.float16)
+        b = rng.standard_normal((1, 260, 10, 16)).astype(np.float16)
         c = rng.standard_normal((1, 3, 45, 45)).astype(np.float16)
         d = rng.standard_normal((2, 5, 27, 27)).astype(np.float32)
         e1 = (rng.standard_normal((1, 24, 12, 24)) / 5).astype(np.float16)
