@@ -716,10 +716,15 @@ hipError_t launch_tile(const ConvParams &p, const void *x, const void *w, const 
     const int xu = (p.W & 7) == 0 ? p.xu : 0;                // 8-pixel units per moving thread, 0: one-pixel units
     const int T = p.kh * p.kw;
     if (p.residual) {
-        // residual layer: 3x3 windows on the caller's weights, the two 64-channel tilings (on the
+        // residual layer: 3x3 and 1x1 windows on the caller's weights, the two 64-channel tilings (on the
         // others the 32 registers of the added tensor would spill)
         if constexpr (POOLS && WN == 1) {
-            if (T != 9 || packed || p.pool) return hipErrorInvalidValue;
+            if ((T != 9 && T != 1) || packed || p.pool) return hipErrorInvalidValue;
+            if (T == 1) {
+                if (xu == 1) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 1, 1, false, NG, false, true>, p, x, w, res, y, s, grid);
+                if (xu == 2) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 1, 2, false, NG, false, true>, p, x, w, res, y, s, grid);
+                return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 1, 0, false, NG, false, true>, p, x, w, res, y, s, grid);
+            }
             if (xu == 1) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 1, false, NG, false, true>, p, x, w, res, y, s, grid);
             if (xu == 2) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 2, false, NG, false, true>, p, x, w, res, y, s, grid);
             return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 0, false, NG, false, true>, p, x, w, res, y, s, grid);

@@ -616,8 +616,8 @@ merit_status derive_conv(merit_plan *pl)
         // and more of every tile empty and stay with the 128-pixel tiles of the plain kernels
         if (!forced && !pool && 4 * ohw < 3 * cdiv(ohw, tm) * tm) return false;
         if (Cin % 8 != 0 || Cin < 16 || (pool && p.residual) || ncb < 2) return false;
-        // residual layer: 3x3 windows, the 64-channel tilings on 8 wavefronts
-        if (p.residual && (kh != 3 || cb != 2 || nw != 8)) return false;
+        // residual layer: 3x3 and 1x1 windows, the 64-channel tilings on 8 wavefronts
+        if (p.residual && (!(kh == 3 || kh == 1) || cb != 2 || nw != 8)) return false;
         if (cb != 1 && cb != 2 && cb != 4) return false;
         // 32-channel tiles: 128 pixels on 8 wavefronts, 3x3 and 1x1 windows, no added tensor, no pooling (for launches
         // that would otherwise leave half the chip idle)
@@ -831,8 +831,9 @@ merit_status derive_conv(merit_plan *pl)
         // also for images far smaller than a tile (13x13 on 256-pixel tiles: 32 us, against 98 us on
         // the plain multi-pass kernel; 7x7 on 128-pixel tiles: 28 against 88).  1x1 layers the same
         // (256 -> 64 on 56x56: 8.1 against 11.9 us, 1024 -> 256 on 14x14: 27 against 51); with a residual
-        // tensor they stay on the plain kernels.
-        if (((kh == 3 && kw == 3) || ((kh == 1 && kw == 1 || kh == 5 && kw == 5) && !p.residual)) && Cin >= 32 && (Cin % 8) == 0 && ncb >= 2) {
+        // tensor from 128 input channels on (128 -> 512 on 28x28: 11.7 against 36 us; 64 -> 256 on 56x56 is
+        // a single short pass and stays on the single-pass kernel: 12.7 against 14.0).
+        if (((kh == 3 && kw == 3) || (kh == 1 && kw == 1 && (!p.residual || Cin >= 128)) || (kh == 5 && kw == 5 && !p.residual)) && Cin >= 32 && (Cin % 8) == 0 && ncb >= 2) {
             int best = -1; double best_cost = 0.0;
             for (int shape = 0; shape < 4; ++shape) {          // 0: 256 x 128 on 12 wavefronts, 1: 256 x 64, 2: 128 x 64, 3: 128 x 32
                 if (shape == 0 && ncb < 4) continue;

@@ -221,6 +221,26 @@ def test_chws_whole_row_tiles_with_an_added_tensor(mb):
     assert np.all(np.abs(got - ref) <= 2e-2 * np.abs(ref) + 1e-3)
 
 
+@pytest.mark.parametrize("shape", [(2, 128, 28, 28, 512), (1, 256, 14, 14, 1000), (3, 136, 9, 20, 70)])
+def test_chws_1x1_layer_with_an_added_tensor(mb, shape):
+    """1x1 windows with an added tensor and clipping (the closing layer of a bottleneck block) on the
+    residual instance: the planner's own choice from 128 input channels on."""
+    N, Cin, H, W, Cout = shape
+    rng = np.random.default_rng(Cin + Cout)
+    x = rng.standard_normal((N, Cin, H, W)).astype(np.float16)
+    w = (rng.standard_normal((Cout, Cin, 1, 1)) / np.sqrt(Cin)).astype(np.float16)
+    r = rng.standard_normal((N, Cout, H, W)).astype(np.float16)
+    plan = mb.merit_plan_conv2d_residual(N, Cin, H, W, Cout, 1, 1, 1, 1, 0, 0, 1)
+    assert plan.launch_info()["kernel"] == "merit_conv2d_chws", plan.launch_info()
+    buf, y, pad = guarded(plan.out_shape())
+    mb.merit_conv2d_residual(plan, dev(x), dev(w), dev(r), y)
+    torch.cuda.synchronize()
+    assert canary_ok(buf, pad)
+    ref = oracle.conv2d_residual(x, w, r, (1, 1), (0, 0), True).astype(np.float64)
+    got = y.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - ref) <= 2e-2 * np.abs(ref) + 1e-3)
+
+
 def test_packed_entry_points_refuse_other_plans(mb):
     plan = mb.merit_plan_conv2d(1, 3, 32, 32, 16, 7, 7, 2, 2, 3, 3)
     with pytest.raises(mb.MeritError) as e:
