@@ -109,7 +109,7 @@ __device__ __forceinline__ Geom pool_geom(const ConvParams &p, int item, int i, 
     return g;
 }
 
-constexpr int XS_MAX = 4;      // input units of 8 channels x 1 pixel a moving thread holds per pass
+constexpr int XS_MAX = 8;      // input units of 8 channels x 1 pixel a moving thread holds per pass (4 beside 8 multiplying wavefronts -- 168 registers -- and for 5x5 windows)
 constexpr uint32_t OOB = 0x80000000u;   // a buffer offset past the end of every tensor: loads return zeros
 
 }  // namespace
@@ -136,7 +136,8 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
     constexpr int NGRP = 2 * NG;                         // 8-channel groups per pass
     constexpr int WU = (TN * NGRP + 255) / 256;          // weight units (8 channels x T taps of one output channel) per moving thread
     constexpr int OP = TM / 2 + 2;                       // output staging: dwords per channel
-    constexpr bool XV = XU > 0;
+    constexpr bool XV = XU == 1 || XU == 2;              // 8-pixel input units, XU per moving thread
+    constexpr bool XQ = XU == 4;                         // 4-pixel input units (W % 4 == 0)
 
     {
         // The kernel-argument block (ConvParams and three pointers: six 64-byte lines) is read with
@@ -293,12 +294,15 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
         const uint32_t chbytes = (uint32_t)(p.H * p.W * 2);          // one channel of one image
         const int mwave = wave - NMW;
 
-        constexpr int NXU = XV ? XU : XS_MAX;
+        constexpr int XSM = (NMW == 4 && T != 25) ? XS_MAX : 4;       // (5x5: 100 registers of weights on their way)
+        constexpr int XQM = NMW == 4 ? 4 : 2;                // 4-pixel units per moving thread, at most
+        constexpr int NXU = XV ? XU : (XQ ? XQM : XSM);
         uint32_t x_voff[NXU];               // byte offset of the unit inside (image, first channel of the pass)
-        int x_lds[NXU][XV ? 8 : 1];         // byte address of each of its pixels inside a pass buffer's input region
+        int x_lds[NXU][XV ? 8 : (XQ ? 4 : 1)];         // byte address of each of its pixels inside a pass buffer's input region
         int x_hh[NXU];                      // its channel group within the pass
         uint32_t xv[XV ? XU : 1][8][4];     // the unit on its way: 8 channels x 8 pixels
-        uint32_t xs[XV ? 1 : XS_MAX][8];    // ... 8 channels x 1 pixel (a register each: see commit)
+        uint32_t xs[(XV || XQ) ? 1 : XSM][8];    // ... 8 channels x 1 pixel (a register each: see commit)
+        uint32_t xq[XQ ? XQM : 1][8][2];         // ... 8 channels x 4 pixels
         uint32_t w_voff[WU];
         int w_lds[WU], w_hh[WU];
         uint32_t wr[PACKED ? 1 : WU][PACKED ? 1 : 4 * T];
@@ -326,10 +330,29 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
                     for (int px = 0; px < 8; ++px)
                         x_lds[k][px] = (q * p.pitch + p.padl + 8 * x8 + px) * 16;
                 }
+            } else if constexpr (XQ) {
+                const int W4 = p.W >> 2;
+                const int nu = NGRP * p.RHa * W4;
+#pragma unroll
+                for (int k = 0; k < XQM; ++k) {
+                    const int u = mt + 256 * k;
+                    const int uc = min(u, nu - 1);
+                    const int x4 = (int)fdiv((uint32_t)uc, p.div_r2);
+                    const int q = uc - x4 * NGRP * p.RHa;
+                    const int hh = (int)fdiv((uint32_t)q, p.div_rha);
+                    const int r = q - hh * p.RHa;
+                    const int gy = g.yA + r;
+                    const bool ok = u < nu && r < g.RH && gy >= 0 && gy < p.H;
+                    x_hh[k] = u < nu ? hh : NGRP;
+                    x_voff[k] = ok ? (uint32_t)(((hh * 8 * p.H + gy) * p.W + 4 * x4) * 2) : OOB;
+#pragma unroll
+                    for (int px = 0; px < 4; ++px)
+                        x_lds[k][px] = (q * p.pitch + p.padl + 4 * x4 + px) * 16;
+                }
             } else {
                 const int nu = NGRP * p.RHa * p.W;
 #pragma unroll
-                for (int k = 0; k < XS_MAX; ++k) {
+                for (int k = 0; k < XSM; ++k) {
                     const int u = mt + 256 * k;
                     const int uc = min(u, nu - 1);
                     const int q = (int)fdiv((uint32_t)uc, p.div_w);
@@ -375,6 +398,9 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
                     if constexpr (XV) {
                         const uint32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rx, voff, xbase + c * chbytes, 0);
                         xv[k][c][0] = v.x; xv[k][c][1] = v.y; xv[k][c][2] = v.z; xv[k][c][3] = v.w;
+                    } else if constexpr (XQ) {
+                        const uint32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rx, voff, xbase + c * chbytes, 0);
+                        xq[k][c][0] = v.x; xq[k][c][1] = v.y;
                     } else {
                         xs[k][c] = __builtin_amdgcn_raw_buffer_load_b16(rx, voff, xbase + c * chbytes, 0);
                     }
@@ -410,6 +436,17 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
                             d.y = __builtin_amdgcn_perm(xv[k][3][px >> 1], xv[k][2][px >> 1], sel);
                             d.z = __builtin_amdgcn_perm(xv[k][5][px >> 1], xv[k][4][px >> 1], sel);
                             d.w = __builtin_amdgcn_perm(xv[k][7][px >> 1], xv[k][6][px >> 1], sel);
+                            *reinterpret_cast<uint32x4 *>(xl + x_lds[k][px]) = d;
+                        }
+                    } else if constexpr (XQ) {
+#pragma unroll
+                        for (int px = 0; px < 4; ++px) {
+                            const uint32_t sel = (px & 1) ? 0x07060302u : 0x05040100u;
+                            uint32x4 d;
+                            d.x = __builtin_amdgcn_perm(xq[k][1][px >> 1], xq[k][0][px >> 1], sel);
+                            d.y = __builtin_amdgcn_perm(xq[k][3][px >> 1], xq[k][2][px >> 1], sel);
+                            d.z = __builtin_amdgcn_perm(xq[k][5][px >> 1], xq[k][4][px >> 1], sel);
+                            d.w = __builtin_amdgcn_perm(xq[k][7][px >> 1], xq[k][6][px >> 1], sel);
                             *reinterpret_cast<uint32x4 *>(xl + x_lds[k][px]) = d;
                         }
                     } else {
@@ -713,7 +750,8 @@ template <int PXB, int CHB, int WM, int WN, int NG = 1, bool POOLS = false>
 hipError_t launch_tile(const ConvParams &p, const void *x, const void *w, const void *res, void *y, hipStream_t s,
                        uint32_t grid, bool packed)
 {
-    const int xu = (p.W & 7) == 0 ? p.xu : 0;                // 8-pixel units per moving thread, 0: one-pixel units
+    // 8-pixel units per moving thread (1, 2); 4: four-pixel units (W % 4 == 0, 3x3 and 1x1 windows); 0: one-pixel units
+    const int xu = (p.W & 7) == 0 ? p.xu : (p.xq ? 4 : 0);
     const int T = p.kh * p.kw;
     if (p.residual) {
         // residual layer: 3x3 and 1x1 windows on the caller's weights, the two 64-channel tilings (on the
@@ -723,10 +761,12 @@ hipError_t launch_tile(const ConvParams &p, const void *x, const void *w, const 
             if (T == 1) {
                 if (xu == 1) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 1, 1, false, NG, false, true>, p, x, w, res, y, s, grid);
                 if (xu == 2) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 1, 2, false, NG, false, true>, p, x, w, res, y, s, grid);
+                if (xu == 4) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 1, 4, false, NG, false, true>, p, x, w, res, y, s, grid);
                 return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 1, 0, false, NG, false, true>, p, x, w, res, y, s, grid);
             }
             if (xu == 1) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 1, false, NG, false, true>, p, x, w, res, y, s, grid);
             if (xu == 2) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 2, false, NG, false, true>, p, x, w, res, y, s, grid);
+            if (xu == 4) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 4, false, NG, false, true>, p, x, w, res, y, s, grid);
             return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 0, false, NG, false, true>, p, x, w, res, y, s, grid);
         }
         return hipErrorInvalidValue;
@@ -737,6 +777,7 @@ hipError_t launch_tile(const ConvParams &p, const void *x, const void *w, const 
             if (T != 9 || packed) return hipErrorInvalidValue;
             if (xu == 1) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 1, false, NG, true>, p, x, w, res, y, s, grid);
             if (xu == 2) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 2, false, NG, true>, p, x, w, res, y, s, grid);
+            if (xu == 4) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 4, false, NG, true>, p, x, w, res, y, s, grid);
             return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 0, false, NG, true>, p, x, w, res, y, s, grid);
         }
         return hipErrorInvalidValue;
@@ -749,9 +790,11 @@ hipError_t launch_tile(const ConvParams &p, const void *x, const void *w, const 
     if (T == 9 && xu == 1) MERIT_CHWS(9, 1);
     if (T == 9 && xu == 2) MERIT_CHWS(9, 2);
     if (T == 9 && xu == 0) MERIT_CHWS(9, 0);
+    if (T == 9 && xu == 4) MERIT_CHWS(9, 4);
     if (T == 1 && xu == 1) MERIT_CHWS(1, 1);
     if (T == 1 && xu == 2) MERIT_CHWS(1, 2);
     if (T == 1 && xu == 0) MERIT_CHWS(1, 0);
+    if (T == 1 && xu == 4) MERIT_CHWS(1, 4);
     // 5x5 windows: the 256-pixel x 64-channel tiling only (a pass's 25 x 2 x 64 weight fragments are 51 KB)
     if constexpr (PXB == 2 && CHB == 2 && WM == 4 && WN == 1 && NG == 1) {
         if (T == 25 && xu == 1) MERIT_CHWS(25, 1);

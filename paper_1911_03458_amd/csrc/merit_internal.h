@@ -159,6 +159,7 @@ struct ConvParams {
     FastDiv div_cog;       // work item -> (tile, channel block)
     FastDiv div_r2;        // staged rows of both channel groups of a pass (2 * RHa)
     int pool_halo;         // fused pooling there: 1 = a tile computes the row above its first pooled row itself
+    int xq;                // multi-pass kernel: 1 = the input rows are staged in units of 8 channels x 4 pixels
     int tile_px;           // multi-pass kernel without pooling: output pixels from one tile's start to the next (TM, or whole rows: rows * OW <= TM)
                            // (rows_out_max odd), 0 = that row is carried from the tile before it (rows_out_max even)
 };

@@ -636,6 +636,7 @@ merit_status derive_conv(merit_plan *pl)
         q.rows_out_max = (int)((q.TM + OW - 2) / OW + 1);
         if (q.rows_out_max > OH) q.rows_out_max = (int)OH;
         q.tile_px = q.TM;
+        q.xq = 0;
         if (!pool && tm == 256) {
             // A tile of TM consecutive pixels starts anywhere in a row, so its covering sub-tensor
             // (Section IV-A, Eq. 9) is rows_out_max whole rows + the window's: on a 224-wide image
@@ -707,16 +708,23 @@ merit_status derive_conv(merit_plan *pl)
             q.lds_total = (int)(q.lds_o_offset + carry);
             if (q.lds_total > LDS_LIMIT) return false;
         }
-        // staging units per moving thread and pass: 8 channels x 8 pixels (two at most), or x 1 pixel (four)
+        // staging units per moving thread and pass: 8 channels x 8 pixels (two at most), or x 1 pixel (eight; four on 12 wavefronts and for 5x5 windows)
         if ((W % 8) == 0) {
             const int64_t nu = 2 * ng * (int64_t)q.RHa * (W / 8);
             if (nu > 2 * 256 || !fastdiv_ok(nu, 2 * ng * (int64_t)q.RHa)) return false;
             q.xu = (int)cdiv(nu, 256);
             q.div_w8 = make_fastdiv((uint32_t)(W / 8));
             q.div_r2 = make_fastdiv((uint32_t)(2 * ng * q.RHa));
+        } else if ((W % 4) == 0 && !k5) {
+            // 8 channels x 4 pixels: four units per moving thread, two on 12 wavefronts
+            const int64_t nu = 2 * ng * (int64_t)q.RHa * (W / 4);
+            if (nu > (nw == 8 ? 4 : 2) * 256 || !fastdiv_ok(nu, 2 * ng * (int64_t)q.RHa)) return false;
+            q.xu = (int)cdiv(nu, 256);
+            q.xq = 1;
+            q.div_r2 = make_fastdiv((uint32_t)(2 * ng * q.RHa));
         } else {
             const int64_t nu = 2 * ng * (int64_t)q.RHa * W;
-            if (nu > 4 * 256 || !fastdiv_ok(nu, W)) return false;
+            if (nu > ((nw == 8 && !k5) ? 8 : 4) * 256 || !fastdiv_ok(nu, W)) return false;
             q.xu = (int)cdiv(nu, 256);
             q.div_w = make_fastdiv((uint32_t)W);
         }
