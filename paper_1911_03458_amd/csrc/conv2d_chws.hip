@@ -119,7 +119,7 @@ constexpr uint32_t OOB = 0x80000000u;   // a buffer offset past the end of every
 // channels x 8 pixels (W % 8 == 0), XU of them per moving thread and pass; XU = 0: in units of
 // 8 channels x 1 pixel, up to XS_MAX per thread.
 // NG: pairs of 8-channel groups per pass (1: 16 channels, 2: 32 -- small tiles, whose passes would
-// otherwise be shorter than a memory round trip).
+// otherwise be shorter than a memory round trip; 4: 64 -- 1x1 windows on many channels).
 // POOL: the results are max-pooled (3x3 / stride 2 / padding 1) out of the staging area and only the
 // pooled tensor is written; work items are bands of pooled rows (pool_geom above).
 // RES: a tensor of the output's shape is added to the fp32 sums before the clip and the rounding.
@@ -764,16 +764,18 @@ hipError_t launch_tile(const ConvParams &p, const void *x, const void *w, const 
                 if (xu == 4) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 1, 4, false, NG, false, true>, p, x, w, res, y, s, grid);
                 return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 1, 0, false, NG, false, true>, p, x, w, res, y, s, grid);
             }
-            if (xu == 1) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 1, false, NG, false, true>, p, x, w, res, y, s, grid);
-            if (xu == 2) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 2, false, NG, false, true>, p, x, w, res, y, s, grid);
-            if (xu == 4) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 4, false, NG, false, true>, p, x, w, res, y, s, grid);
-            return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 0, false, NG, false, true>, p, x, w, res, y, s, grid);
+            if constexpr (NG != 4) {        // (64 channels per pass: 1x1 windows only)
+                if (xu == 1) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 1, false, NG, false, true>, p, x, w, res, y, s, grid);
+                if (xu == 2) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 2, false, NG, false, true>, p, x, w, res, y, s, grid);
+                if (xu == 4) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 4, false, NG, false, true>, p, x, w, res, y, s, grid);
+                return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 0, false, NG, false, true>, p, x, w, res, y, s, grid);
+            }
         }
         return hipErrorInvalidValue;
     }
     if (p.pool) {
         // fused pooling: 3x3 windows on the caller's weights; not the 128-channel tiling on 8 wavefronts
-        if constexpr (POOLS) {
+        if constexpr (POOLS && NG != 4) {
             if (T != 9 || packed) return hipErrorInvalidValue;
             if (xu == 1) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 1, false, NG, true>, p, x, w, res, y, s, grid);
             if (xu == 2) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, 9, 2, false, NG, true>, p, x, w, res, y, s, grid);
@@ -787,10 +789,12 @@ hipError_t launch_tile(const ConvParams &p, const void *x, const void *w, const 
         if (packed) return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, Tv, XUv, true, NG>, p, x, w, res, y, s, grid);  \
         return launch_one(merit_conv2d_chws<PXB, CHB, WM, WN, Tv, XUv, false, NG>, p, x, w, res, y, s, grid);    \
     } while (0)
-    if (T == 9 && xu == 1) MERIT_CHWS(9, 1);
-    if (T == 9 && xu == 2) MERIT_CHWS(9, 2);
-    if (T == 9 && xu == 0) MERIT_CHWS(9, 0);
-    if (T == 9 && xu == 4) MERIT_CHWS(9, 4);
+    if constexpr (NG != 4) {
+        if (T == 9 && xu == 1) MERIT_CHWS(9, 1);
+        if (T == 9 && xu == 2) MERIT_CHWS(9, 2);
+        if (T == 9 && xu == 0) MERIT_CHWS(9, 0);
+        if (T == 9 && xu == 4) MERIT_CHWS(9, 4);
+    }
     if (T == 1 && xu == 1) MERIT_CHWS(1, 1);
     if (T == 1 && xu == 2) MERIT_CHWS(1, 2);
     if (T == 1 && xu == 0) MERIT_CHWS(1, 0);
@@ -815,6 +819,15 @@ hipError_t launch_conv2d_chws(const ConvParams &p, const void *x, const void *w,
     if (nitems == 0) return hipSuccess;
     const int64_t slots = device_cu_count();            // one 512-thread workgroup per compute unit
     const uint32_t grid = (uint32_t)(nitems < slots ? nitems : slots);
+    if (p.nchi == 8) {
+        // 1x1 windows on 128 and more channels: 64 channels per pass on every tiling (a pass of 16 or 32
+        // channels x one tap is a few MFMAs per wavefront: shorter than the barrier and the memory round trip)
+        if (p.CB == 4 && p.NW == 12) return launch_tile<2, 2, 4, 2, 4, false>(p, x, w, res, y, s, grid, packed);
+        if (p.CB == 4) return launch_tile<4, 2, 2, 2, 4, false>(p, x, w, res, y, s, grid, packed);
+        if (p.TM == 128 && p.CB == 1) return launch_tile<1, 1, 4, 1, 4, false>(p, x, w, res, y, s, grid, packed);
+        if (p.TM == 128) return launch_tile<1, 2, 4, 1, 4, true>(p, x, w, res, y, s, grid, packed);
+        return launch_tile<2, 2, 4, 1, 4, true>(p, x, w, res, y, s, grid, packed);
+    }
     if (p.CB == 4 && p.NW == 12) return launch_tile<2, 2, 4, 2, 1, true>(p, x, w, res, y, s, grid, packed);   // 256 x 128, 8 x (64 x 64)
     if (p.CB == 4) return launch_tile<4, 2, 2, 2>(p, x, w, res, y, s, grid, packed);     // 256 pixels x 128 channels, 4 x (128 x 64)
     if (p.TM == 128 && p.CB == 1) return launch_tile<1, 1, 4, 1, 2, false>(p, x, w, res, y, s, grid, packed);   // 128 pixels x 32 channels, 4 x (32 x 32)

@@ -690,7 +690,15 @@ merit_status derive_conv(merit_plan *pl)
         q.pitch = (int)pitch;
         // 16 input channels per pass; 32 with the small tile, whose passes would otherwise be
         // shorter than the memory round trip that brings the next one
-        const int64_t ng = tm == 128 ? 2 : 1;
+        int64_t ng = tm == 128 ? 2 : 1;
+        if (kh == 1 && kw == 1 && Cin >= 128 && !pool) {
+            // 1x1 windows: a pass is one tap; 64 channels per pass where its rows and staging units fit
+            const int64_t g = 4, xb = 2 * g * (int64_t)q.RHa * pitch * 16, wb = g * cb * 64 * 16;
+            const int64_t rows = 2 * g * (int64_t)q.RHa;
+            const int64_t nu = (W % 8) == 0 ? rows * (W / 8) : ((W % 4) == 0 ? rows * (W / 4) : rows * W);
+            const int64_t cap = ((W % 8) == 0 ? 2 : ((W % 4) == 0 ? (nw == 8 ? 4 : 2) : (nw == 8 ? 8 : 4))) * 256;
+            if (2 * (wb + xb) <= LDS_LIMIT && nu <= cap) ng = g;
+        }
         q.nchi = (int)(2 * ng);
         q.nchunks = (int)cdiv(Cin, 16 * ng);
         q.S = (int)(ng * kh * kw);
