@@ -19,7 +19,9 @@
  *     never allocates device memory -- with one exception, a convolution +
  *     pooling plan that runs as two launches (see merit_plan_conv2d_pool), which
  *     takes a stream-ordered temporary (hipMallocAsync / hipFreeAsync in the
- *     caller's stream).
+ *     caller's stream) and, at its first launch on a device, raises the release
+ *     threshold of that device's default memory pool so that the pool keeps the
+ *     memory across synchronisations.
  *   - A plan is immutable host memory; it may be shared between threads and
  *     streams.  Plans are created and destroyed without touching the GPU.
  *   - Every function returns a merit_status; on any error nothing was launched.
