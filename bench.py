@@ -538,6 +538,8 @@ def main():
             (wl.CFG_CONV256.name, lambda: bench_conv(torch, mb, wl, wl.CFG_CONV256, kl, w, args.sets, packed=True)),
             (wl.CFG_CONV256.name, lambda: bench_conv(torch, mb, wl, wl.CFG_CONV256, kl, w, args.sets, relu=True, pool=True)),
             (wl.CFG_CONV256_B64.name, lambda: bench_conv(torch, mb, wl, wl.CFG_CONV256_B64, kl, w, 3)),
+            (wl.CFG_CONV5X5.name, lambda: bench_conv(torch, mb, wl, wl.CFG_CONV5X5, kl, w, args.sets)),
+            (wl.CFG_CONV14.name, lambda: bench_conv(torch, mb, wl, wl.CFG_CONV14, kl, w, args.sets)),
             (wl.CFG_CONV11.name, lambda: bench_conv(torch, mb, wl, wl.CFG_CONV11, kl, w, args.sets)),
             (wl.CFG_CORRELATION.name, lambda: bench_corr(torch, mb, wl, wl.CFG_CORRELATION, k, w)),
             (wl.CFG_DEPTHWISE.name, lambda: bench_depthwise(torch, mb, wl, wl.CFG_DEPTHWISE, k, w, args.sets)),

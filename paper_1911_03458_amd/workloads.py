@@ -124,6 +124,10 @@ CFG_CONV11 = ConvWorkload("conv_8x3x220x220_co48_k11s4p5", 8, 3, 220, 220, 48, 1
 CFG_CONV256 = ConvWorkload("conv_8x256x56x56_co256_k3s1p1", 8, 256, 56, 56, 256, 3, 3, 1, 1, 1, 1, "normal")
 # The same layer on a batch of 64: 200 704 pixels = 784 tiles of 256, three rounds of the 256 CUs,
 # so that the launch and the pipeline fill of the first tile weigh a third as much.
+# The 5x5 layer of the paper's per-layer table (Section VI-C; 96 -> 256 channels on 27x27) and one of its
+# 3x3 layers on small images (512 -> 512 on 14x14): few pixels, many channels.
+CFG_CONV5X5 = ConvWorkload("conv_8x96x27x27_co256_k5s1p2", 8, 96, 27, 27, 256, 5, 5, 1, 1, 2, 2, "normal")
+CFG_CONV14 = ConvWorkload("conv_8x512x14x14_co512_k3s1p1", 8, 512, 14, 14, 512, 3, 3, 1, 1, 1, 1, "normal")
 CFG_CONV256_B64 = ConvWorkload("conv_64x256x56x56_co256_k3s1p1", 64, 256, 56, 56, 256, 3, 3, 1, 1, 1, 1, "normal")
 
 
