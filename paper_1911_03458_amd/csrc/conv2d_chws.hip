@@ -61,7 +61,7 @@ __device__ __forceinline__ Geom tile_geom(const ConvParams &p, int item, int ohw
     const int mlast = min(g.m0 + p.tile_px, ohw) - 1;
     const int oyB = (int)fdiv((uint32_t)mlast, p.div_ow);
     g.yA = g.oyA * p.sh - p.ph;
-    g.RH = (oyB - g.oyA) * p.sh + (p.kh - 1) * p.dh + 1;
+    g.RH = p.row_skip ? oyB - g.oyA + 1 : (oyB - g.oyA) * p.sh + (p.kh - 1) * p.dh + 1;
     g.mend = min(g.m0 + p.tile_px, ohw);
     g.pr0 = g.warm = g.top = g.roff = g.par = 0;
     return g;
@@ -307,6 +307,7 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
         int w_lds[WU], w_hh[WU];
         uint32_t wr[PACKED ? 1 : WU][PACKED ? 1 : 4 * T];
 
+        const int rstep = p.row_skip ? p.sh : 1;        // image rows between staged rows
         auto setup = [&](const Geom &g) __attribute__((always_inline)) {
             if constexpr (XV) {
                 const int W8 = p.W >> 3;
@@ -322,7 +323,7 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
                     const int q = uc - x8 * NGRP * p.RHa;
                     const int hh = (int)fdiv((uint32_t)q, p.div_rha);
                     const int r = q - hh * p.RHa;
-                    const int gy = g.yA + r;
+                    const int gy = g.yA + r * rstep;
                     const bool ok = u < nu && r < g.RH && gy >= 0 && gy < p.H;
                     x_hh[k] = u < nu ? hh : NGRP;                            // NGRP: no such unit, never written
                     x_voff[k] = ok ? (uint32_t)(((hh * 8 * p.H + gy) * p.W + 8 * x8) * 2) : OOB;
@@ -341,7 +342,7 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
                     const int q = uc - x4 * NGRP * p.RHa;
                     const int hh = (int)fdiv((uint32_t)q, p.div_rha);
                     const int r = q - hh * p.RHa;
-                    const int gy = g.yA + r;
+                    const int gy = g.yA + r * rstep;
                     const bool ok = u < nu && r < g.RH && gy >= 0 && gy < p.H;
                     x_hh[k] = u < nu ? hh : NGRP;
                     x_voff[k] = ok ? (uint32_t)(((hh * 8 * p.H + gy) * p.W + 4 * x4) * 2) : OOB;
@@ -359,7 +360,7 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
                     const int xg = uc - q * p.W;
                     const int hh = (int)fdiv((uint32_t)q, p.div_rha);
                     const int r = q - hh * p.RHa;
-                    const int gy = g.yA + r;
+                    const int gy = g.yA + r * rstep;
                     const bool ok = u < nu && r < g.RH && gy >= 0 && gy < p.H;
                     x_hh[k] = u < nu ? hh : NGRP;
                     x_voff[k] = ok ? (uint32_t)(((hh * 8 * p.H + gy) * p.W + xg) * 2) : OOB;
@@ -584,7 +585,7 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
             const int mm = min(m, g.mend - 1);                 // (pixels past the tile's end: computed, never stored)
             const int oy = (int)fdiv((uint32_t)mm, p.div_ow);
             const int ox = mm - oy * p.OW;
-            const int pbase = (h * p.RHa + (oy - g.oyA) * p.sh) * p.pitch;
+            const int pbase = (h * p.RHa + (oy - g.oyA) * (p.row_skip ? 1 : p.sh)) * p.pitch;
             const int pcol = (p.padl - p.pw) + ox * p.sw;
 #pragma unroll
             for (int kx = 0; kx < KW; ++kx) xc[pb][kx] = pbase + pcol + kx * p.dw;

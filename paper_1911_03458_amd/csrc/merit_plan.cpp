@@ -681,6 +681,9 @@ merit_status derive_conv(merit_plan *pl)
             q.div_pw8 = make_fastdiv((uint32_t)q.pw8);
         }
         q.RHa = (int)((q.rows_out_max - 1) * sh + eh);
+        // a window one row high with a row stride uses every sh-th image row: only those are staged
+        q.row_skip = (kh == 1 && sh > 1 && !pool) ? 1 : 0;
+        if (q.row_skip) q.RHa = q.rows_out_max;
         q.front = 0; q.aligned = 0; q.ws = 0; q.su = 0; q.lg_chunks = 0; q.pipe = 0;
         q.G = q.G2 = 0;
         q.padl = (int)pw;

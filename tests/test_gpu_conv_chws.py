@@ -59,6 +59,8 @@ CHWS_CASES = [
     ((2, 16, 40, 40, 64, 3, 3, 1, 1, 1, 1), (1, 1), 0, (0, 0, 8, 64)),      # a single pass per item
     ((2, 48, 27, 27, 256, 3, 3, 1, 1, 0, 0), (1, 1), 1, (0, 0, 8, 128)),    # no padding, odd width, three passes
     ((1, 64, 9, 10, 64, 1, 1, 2, 2, 0, 0), (1, 1), 0, (0, 0, 8, 64)),       # 1x1 stride 2, tiny image
+    ((2, 128, 15, 28, 96, 1, 1, 2, 2, 0, 0), (1, 1), 1, None),              # 1x1 stride 2: only every second row is staged; 64 channels per pass
+    ((1, 256, 30, 56, 128, 1, 1, 3, 3, 0, 0), (1, 1), 0, None),             # 1x1 stride 3
     # tiles of whole rows (wide images: two rows of 112, one of 224 in a 256-pixel tile)
     ((1, 32, 21, 112, 70, 3, 3, 1, 1, 1, 1), (1, 1), 0, (0, 0, 8, 64)),     # odd row count: the last tile is one row; ragged channels
     ((1, 64, 9, 112, 64, 1, 1, 1, 1, 0, 0), (1, 1), 1, (0, 0, 8, 64)),      # 1x1
