@@ -837,7 +837,10 @@ merit_status derive_conv(merit_plan *pl)
         } else if (Cin < 8) ok = try_variant(CONV_PLANAR_SMALLC, (int)(ppw / 32), (int)nw);
         if (!ok && nw == 4) ok = try_variant(CONV_CHBLOCK, (int)(ppw / 32), 4);
     } else {
-        if (Cin < 8)
+        // window rows of 9 to 16 taps with more 128-pixel tiles than compute units: 256-pixel tiles on 8
+        // wavefronts (8 x 3 x 227 x 227 -> 96, 11x11 / s4: 30.8 -> 20.9 us; 4 wavefronts x 64 pixels: 23.8)
+        if (Cin < 8 && kw > 8 && N * cdiv(ohw, 128) * p.co_groups > 256) ok = try_variant(CONV_PLANAR_SMALLC, 1, 8);
+        if (!ok && Cin < 8)
             ok = want_big ? (try_variant(CONV_PLANAR_SMALLC, 2, 4) || try_variant(CONV_PLANAR_SMALLC, 1, 4))
                           : (try_variant(CONV_PLANAR_SMALLC, 1, 4) || try_variant(CONV_PLANAR_SMALLC, 2, 4));
         if (!ok)

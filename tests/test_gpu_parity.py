@@ -486,6 +486,7 @@ CONV_CASES = [
     (1, 4, 23, 31, 20, 2, 15, 2, 2, 1, 7),     # 15 taps + the front slot: all 16 slots
     (9, 3, 40, 40, 64, 9, 9, 1, 1, 4, 4),      # stride 1, several tiles per workgroup
     (1, 1, 22, 17, 53, 1, 7, 3, 3, 0, 1),      # the weight tensor ends in the middle of a 16-byte vector
+    (9, 2, 150, 131, 144, 9, 9, 3, 3, 2, 3),   # more 128-pixel tiles than compute units: 256-pixel tiles on 8 wavefronts
     # neither MFMA kernel: the one-element-per-thread kernel
     (1, 3, 40, 44, 10, 5, 17, 2, 2, 2, 8),     # 17 taps per window row on few channels
     (2, 5, 30, 41, 7, 9, 12, 2, 3, 4, 9),      # padding wider than the staged left margin
@@ -515,6 +516,18 @@ def test_conv_tile_override_few_channels(mb, tile):
     x = rng.standard_normal((2, 3, 40, 48)).astype(np.float16)
     w = (rng.standard_normal((40, 3, 7, 7)) / 12).astype(np.float16)
     _conv_check(mb, x, w, (2, 2), (3, 3), tile)
+
+
+@pytest.mark.parametrize("tile", [None, (0, 0, 8, 32), (0, 0, 4, 64)])
+def test_conv_two_fragment_rows_tilings(mb, tile):
+    # window rows of 11 taps (two 8-slot fragments) on every tiling of the planar kernel; the planner
+    # itself takes 8 wavefronts when the layer has more 128-pixel tiles than the chip has compute units
+    big = mb.merit_plan_conv2d(9, 2, 150, 131, 144, 9, 9, 3, 3, 2, 3).launch_info()
+    assert big["kernel"] == "merit_conv2d_planar" and big["block"][0] == 512
+    rng = np.random.default_rng(17)
+    x = rng.standard_normal((3, 3, 75, 83)).astype(np.float16)
+    w = (rng.standard_normal((56, 3, 11, 11)) / 19).astype(np.float16)
+    _conv_check(mb, x, w, (4, 4), (2, 0), tile)
 
 
 WS_CASES = [
