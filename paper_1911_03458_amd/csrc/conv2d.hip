@@ -150,6 +150,73 @@ __device__ __forceinline__ void lds_to_global(const ConvParams &p, const uint32_
     const int ohw = p.OH * p.OW;
     const bool vec_ok = (ohw & 7) == 0;
     constexpr int UNITS = CB * 32 * (TM / 8);
+    if (!FULL && !vec_ok) {
+        // A channel's run of the tile starts at any element of the output: the 16-byte units lie on
+        // the output's own 16-byte grid (y itself is 16-byte aligned: the entry points check it; one
+        // more unit per channel than the tile has, as the run may straddle), a whole unit is five
+        // dwords of the staging row shifted down by one half where its first pixel is odd, and the
+        // run's two ends are stored element by element in a pass of their own (in the same loop every
+        // wavefront would take both branches).  As 2-byte stores, 16 bytes apart between lanes, a
+        // 53 MB output took 63 us.
+        constexpr int UPC = TM / 8 + 1;
+        const int cnt = min(TM, ohw - m0);
+        const int nch = min(CB * 32, p.Cout - co_base);
+        const size_t a0 = ((size_t)n * p.Cout + co_base) * ohw + m0;
+        // (the LDS reads of two units per thread go out together, clamped to the area where a unit
+        // is not stored: half the round trips, and few enough registers)
+        constexpr int UB = 2;
+#pragma unroll 1
+        for (int u0 = t; u0 < nch * UPC; u0 += NT * UB) {
+            uint32_t d[UB][5];
+            int pxs[UB];
+            uint32_t coff[UB];                                   // c * ohw (below 2^32: 63 planes of the output)
+#pragma unroll
+            for (int i = 0; i < UB; ++i) {
+                const int u = u0 + NT * i;
+                const int c = min(u / UPC, nch - 1);
+                const int j = u - (u / UPC) * UPC;
+                coff[i] = (uint32_t)c * (uint32_t)ohw;
+                const int px0 = 8 * j - (int)((a0 + coff[i]) & 7);   // tile pixel of the unit's first element
+                pxs[i] = (u < nch * UPC && px0 >= 0 && px0 + 8 <= cnt) ? px0 : -1;
+                const uint32_t *src = outl + c * OP + (max(pxs[i], 0) >> 1);   // (the fifth dword: at most the row's padding)
+#pragma unroll
+                for (int q = 0; q < 5; ++q) d[i][q] = src[q];
+            }
+#pragma unroll
+            for (int i = 0; i < UB; ++i) {
+                if (pxs[i] < 0) continue;
+                const uint32_t sh = (uint32_t)(pxs[i] & 1) * 16u;
+                uint32x4 v;
+                v.x = __builtin_amdgcn_alignbit(d[i][1], d[i][0], sh);
+                v.y = __builtin_amdgcn_alignbit(d[i][2], d[i][1], sh);
+                v.z = __builtin_amdgcn_alignbit(d[i][3], d[i][2], sh);
+                v.w = __builtin_amdgcn_alignbit(d[i][4], d[i][3], sh);
+                __builtin_nontemporal_store(v, reinterpret_cast<uint32x4 *>(y + a0 + coff[i] + pxs[i]));
+            }
+        }
+        // the up to 7 elements before a channel's first whole unit and after its last: 16 lanes per channel
+        constexpr int EB = 2;
+#pragma unroll 1
+        for (int e0 = t; e0 < nch * 16; e0 += NT * EB) {
+            uint16_t ev[EB];
+            int epx[EB];
+            uint32_t eoff[EB];
+#pragma unroll
+            for (int i = 0; i < EB; ++i) {
+                const int e = e0 + NT * i;
+                const int c = min(e >> 4, nch - 1), k = e & 7;
+                eoff[i] = (uint32_t)c * (uint32_t)ohw;
+                const int head = min(cnt, (8 - (int)((a0 + eoff[i]) & 7)) & 7);
+                const int px = (e & 8) ? head + ((cnt - head) & ~7) + k : (k < head ? k : cnt);
+                epx[i] = (e < nch * 16 && px < cnt) ? px : -1;
+                ev[i] = reinterpret_cast<const uint16_t *>(outl + c * OP)[max(epx[i], 0)];
+            }
+#pragma unroll
+            for (int i = 0; i < EB; ++i)
+                if (epx[i] >= 0) y[a0 + eoff[i] + epx[i]] = ev[i];
+        }
+        return;
+    }
 #pragma unroll
     for (int u = t; u < UNITS; u += NT) {
         const int c = u / (TM / 8);
@@ -162,19 +229,10 @@ __device__ __forceinline__ void lds_to_global(const ConvParams &p, const uint32_
         const uint2 *src = reinterpret_cast<const uint2 *>(outl + c * OP + px8 * 4);   // 8-byte aligned
         const uint2 a = src[0], b = src[1];
         uint16_t *y0 = y + ((size_t)n * p.Cout + co) * ohw + m;
-        if (FULL || vec_ok) {
-            // streaming store: written once, not read again here
-            uint32x4 v;
-            v.x = a.x; v.y = a.y; v.z = b.x; v.w = b.y;
-            __builtin_nontemporal_store(v, reinterpret_cast<uint32x4 *>(y0));
-        } else {
-            const uint32_t e[4] = {a.x, a.y, b.x, b.y};
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                if (m + k >= ohw) break;
-                y0[k] = (uint16_t)(e[k >> 1] >> (16 * (k & 1)));
-            }
-        }
+        // streaming store: written once, not read again here
+        uint32x4 v;
+        v.x = a.x; v.y = a.y; v.z = b.x; v.w = b.y;
+        __builtin_nontemporal_store(v, reinterpret_cast<uint32x4 *>(y0));
     }
 }
 
@@ -307,6 +365,9 @@ __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, 
     const int nu = p.Cin * p.RHa * P8;
     const bool vec8 = (p.W & 7) == 0;                     // a unit is one 16-byte load,
     const bool vec_ok = (p.W & 3) == 0;                   // or two of 8 bytes (rows are 8-byte aligned)
+    // any other width: 4-byte-aligned loads through one descriptor over the whole tensor (offsets below 2^31)
+    const long long xbytes = (long long)p.N * p.Cin * p.H * p.W * 2;
+    const bool dw_ok = !vec_ok && xbytes < (1ll << 31);   // (x is 16-byte aligned: the entry points check it)
     // units per thread and batch: 5 when a batch stays in registers across the K loop, else 10 (a
     // batch is one memory round trip)
     constexpr int XU = PREFETCH ? 5 : 10;
@@ -390,6 +451,60 @@ __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, 
                     issue_loads(T);
                 }
                 commit_loads(u0);
+            }
+        } else if (dw_ok) {
+            // Rows start at any element: a unit is the 20 bytes from the 4-byte boundary at or below its
+            // first element (a 16- and a 4-byte load, UB units in flight per thread), shifted down by one
+            // half where it starts odd; what lies past the row's end belongs to the next row and is cleared.
+            // (padl == 8: a unit is all padding or starts inside its row.)
+            constexpr int UB = 4;
+            const __amdgpu_buffer_rsrc_t rall = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(x), 0, (int)xbytes, 0x00020000);
+            const int ebase = T.n * p.Cin * p.H * p.W;
+            for (int u0 = tid; u0 < nu; u0 += NT * UB) {
+                uint32x4 ra[UB];
+                uint32_t rb[UB], sh[UB];
+                int left[UB], el[UB];                      // elements of the unit inside the row (<= 0: none), first element
+                bool whole[UB];                            // both loads lie inside the tensor
+#pragma unroll
+                for (int k = 0; k < UB; ++k) {
+                    const int u = min(u0 + NT * k, nu - 1);
+                    const int q = (int)fdiv((uint32_t)u, p.div_pitch8);
+                    const int c8 = u - q * P8;
+                    const int ci = (int)fdiv((uint32_t)q, p.div_rha);
+                    const int r = q - ci * p.RHa;
+                    const int gy = T.yA + r;
+                    const int xg0 = 8 * c8 - p.padl;
+                    const bool in = r < T.RH && gy >= 0 && gy < p.H && xg0 >= 0 && xg0 < p.W;
+                    el[k] = ebase + (ci * p.H + gy) * p.W + xg0;
+                    left[k] = in ? p.W - xg0 : 0;
+                    const uint32_t off = (uint32_t)(el[k] & ~1) * 2u;
+                    whole[k] = in && (long long)off + 20 <= xbytes;
+                    sh[k] = (uint32_t)(el[k] & 1) * 16u;
+                    ra[k] = __builtin_amdgcn_raw_buffer_load_b128(rall, whole[k] ? off : 0x80000000u, 0, 0);
+                    rb[k] = __builtin_amdgcn_raw_buffer_load_b32(rall, whole[k] ? off + 16u : 0x80000000u, 0, 0);
+                }
+#pragma unroll
+                for (int k = 0; k < UB; ++k) {
+                    const int u = u0 + NT * k;
+                    if (u >= nu) break;
+                    uint32_t d[4];
+                    if (left[k] > 0 && !whole[k]) {        // the tensor's last few elements: one by one
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) d[q] = 0;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (e < left[k]) d[e >> 1] |= (uint32_t)x[el[k] + e] << (16 * (e & 1));
+                    } else {
+                        d[0] = __builtin_amdgcn_alignbit(ra[k].y, ra[k].x, sh[k]);
+                        d[1] = __builtin_amdgcn_alignbit(ra[k].z, ra[k].y, sh[k]);
+                        d[2] = __builtin_amdgcn_alignbit(ra[k].w, ra[k].z, sh[k]);
+                        d[3] = __builtin_amdgcn_alignbit(rb[k], ra[k].w, sh[k]);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            d[q] &= (2 * q < left[k] ? 0x0000ffffu : 0u) | (2 * q + 1 < left[k] ? 0xffff0000u : 0u);
+                    }
+                    reinterpret_cast<uint4 *>(xl)[u] = make_uint4(d[0], d[1], d[2], d[3]);
+                }
             }
         } else {
             for (int u = tid; u < nu; u += NT) {

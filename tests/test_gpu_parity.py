@@ -487,6 +487,9 @@ CONV_CASES = [
     (9, 3, 40, 40, 64, 9, 9, 1, 1, 4, 4),      # stride 1, several tiles per workgroup
     (1, 1, 22, 17, 53, 1, 7, 3, 3, 0, 1),      # the weight tensor ends in the middle of a 16-byte vector
     (9, 2, 150, 131, 144, 9, 9, 3, 3, 2, 3),   # more 128-pixel tiles than compute units: 256-pixel tiles on 8 wavefronts
+    (2, 3, 29, 30, 37, 7, 7, 2, 2, 3, 3),      # W % 4 == 2, 225 pixels per output plane: every alignment of a plane's start
+    (3, 3, 30, 29, 37, 5, 5, 1, 1, 1, 1),      # odd W, 756 pixels per plane (8-byte aligned planes), several tiles
+    (5, 1, 19, 23, 9, 3, 3, 1, 1, 0, 0),       # planes of 357 pixels on 9 channels: runs shorter than a unit's reach at the ends
     # neither MFMA kernel: the one-element-per-thread kernel
     (1, 3, 40, 44, 10, 5, 17, 2, 2, 2, 8),     # 17 taps per window row on few channels
     (2, 5, 30, 41, 7, 9, 12, 2, 3, 4, 9),      # padding wider than the staged left margin
