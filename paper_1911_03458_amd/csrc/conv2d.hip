@@ -818,7 +818,7 @@ __device__ __forceinline__ uint32x4 row_max3_s2(uint32_t left, const uint32_t (&
     return r;
 }
 
-template <int CB, bool ALIGNED, int SU, bool POOL>
+template <int CB, bool ALIGNED, int SU, bool POOL, bool UNAL = false>
 __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, const uint16_t *__restrict__ x,
                                                                 const uint16_t *__restrict__ w,
                                                                 const uint16_t *__restrict__ /* no residual layer here */,
@@ -976,6 +976,19 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
             u_lds[k] = (qc * P8 + min(ld_c8, P8 - 1)) * 16;
         }
     }
+    // UNAL (rows that start on any element: W % 8 != 0): a unit is the 20 bytes from the 4-byte
+    // boundary at or below its first element, one 16- and one 4-byte load, shifted down by a half
+    // where it starts odd; what lies past the row's end (the next row's first pixels) is cleared.
+    // A load only partly in range returns zeros for all of it, so the unit whose 20 bytes would
+    // cross the tensor's end (at most one per thread) is fetched element by element when it is written.
+    uint32_t pre4[UNAL ? XU : 1], u_sh[UNAL ? XU : 1];
+    uint32_t cmask[4];                                    // the halves of this thread's column chunk inside the row
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        cmask[q] = (ld_xg0 + 2 * q < p.W ? 0x0000ffffu : 0u) | (ld_xg0 + 2 * q + 1 < p.W ? 0xffff0000u : 0u);
+    const uint32_t xbytes = (uint32_t)((size_t)p.N * p.Cin * p.H * p.W * 2);
+    uint32_t tail_voff = OOB;
+    int tail_lds = 0;
     auto issue_loads = [&](const Geom &g) {
         const uint32_t soff = (uint32_t)g.n * (uint32_t)(p.Cin * p.H * p.W * 2);
         const int yaw2 = g.yA * p.W * 2;
@@ -983,14 +996,51 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
         for (int k = 0; k < XU; ++k) {
             const uint32_t gy = (uint32_t)(g.yA + u_row[k]);
             const int ok = (int)ld_colok & (int)(u_row[k] < g.RH) & (int)(gy < (uint32_t)p.H);
-            const uint32_t voff = ok ? (uint32_t)(u_off2[k] + yaw2) : OOB;
-            pre[k] = __builtin_amdgcn_raw_buffer_load_b128(rx, voff, soff, 0);
+            if constexpr (UNAL) {
+                const uint32_t ab = soff + (uint32_t)(u_off2[k] + yaw2);      // first element, from the tensor's start
+                const uint32_t al = ab & ~3u;
+                const bool whole = al + 20u <= xbytes;
+                u_sh[k] = (ab & 2u) * 8u;
+                pre[k] = __builtin_amdgcn_raw_buffer_load_b128(rx, (ok && whole) ? al : OOB, 0, 0);
+                pre4[k] = __builtin_amdgcn_raw_buffer_load_b32(rx, (ok && whole) ? al + 16u : OOB, 0, 0);
+                if (ok && !whole && u_live[k]) {
+                    tail_voff = ab;
+                    tail_lds = u_lds[k];
+                }
+            } else {
+                const uint32_t voff = ok ? (uint32_t)(u_off2[k] + yaw2) : OOB;
+                pre[k] = __builtin_amdgcn_raw_buffer_load_b128(rx, voff, soff, 0);
+            }
         }
     };
     auto commit_loads = [&](uint8_t *xl) {
 #pragma unroll
-        for (int k = 0; k < XU; ++k)
-            if (u_live[k]) *reinterpret_cast<uint32x4 *>(xl + u_lds[k]) = pre[k];
+        for (int k = 0; k < XU; ++k) {
+            if constexpr (UNAL) {
+                uint32x4 d;
+                d.x = __builtin_amdgcn_alignbit(pre[k].y, pre[k].x, u_sh[k]) & cmask[0];
+                d.y = __builtin_amdgcn_alignbit(pre[k].z, pre[k].y, u_sh[k]) & cmask[1];
+                d.z = __builtin_amdgcn_alignbit(pre[k].w, pre[k].z, u_sh[k]) & cmask[2];
+                d.w = __builtin_amdgcn_alignbit(pre4[k], pre[k].w, u_sh[k]) & cmask[3];
+                if (u_live[k]) *reinterpret_cast<uint32x4 *>(xl + u_lds[k]) = d;
+            } else {
+                if (u_live[k]) *reinterpret_cast<uint32x4 *>(xl + u_lds[k]) = pre[k];
+            }
+        }
+        if constexpr (UNAL) {
+            if (tail_voff != OOB) {
+                uint32_t d[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t hv = __builtin_amdgcn_raw_buffer_load_b16(rx, ld_xg0 + e < p.W ? tail_voff + 2u * e : OOB, 0, 0);
+                    d[e >> 1] |= (hv & 0xffffu) << (16 * (e & 1));
+                }
+                uint32x4 dv;
+                dv.x = d[0]; dv.y = d[1]; dv.z = d[2]; dv.w = d[3];
+                *reinterpret_cast<uint32x4 *>(xl + tail_lds) = dv;
+                tail_voff = OOB;
+            }
+        }
     };
     // results: thread t stores 8 pixels of channels t/32 + 4k, k = 0 .. CB*8-1
     constexpr int OPW = TM / 2 + 2;                       // out staging pitch in dwords
@@ -1017,6 +1067,53 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
             // streaming them keeps the L2 from collecting dirty lines that the end of the
             // kernel then has to write back all at once
             __builtin_amdgcn_raw_buffer_store_b128(v, ry, voff, 0, 3);
+        }
+    };
+
+    // UNAL, output planes that start on any element (OH*OW % 8 != 0): the 16-byte units lie on the
+    // output's own 16-byte grid -- lane j of a channel stores the unit that starts `head + 8j` pixels
+    // into the channel's run (five dwords of the staging row, shifted down by a half where that pixel
+    // is odd) if all of it is inside the run, and the up to 7 + 7 elements at the run's two ends go
+    // out as 2-byte stores, 16 lanes per channel.
+    auto store_tile_ws_grid = [&](int i) {
+        const Geom P = geom(i);
+        const uint32_t *src0 = reinterpret_cast<const uint32_t *>(outl0 + (i & 1) * ostride);
+        const uint32_t a0 = (uint32_t)(((size_t)P.n * p.Cout + co_base) * ohw + P.m0);      // element index (bytes < 2^31)
+        const int cnt = min(TM, ohw - P.m0);
+        const int j = t & 31;
+#pragma unroll
+        for (int k = 0; k < CB * 8; ++k) {
+            const int c = st_c0 + 4 * k;
+            const uint32_t a = a0 + (uint32_t)(c * ohw);
+            const int px0 = (int)((8u - (a & 7u)) & 7u) + 8 * j;
+            const int pxr = max(min(px0, cnt - 8), 0);         // (a unit that is not stored reads inside the row all the same)
+            const int d0 = pxr >> 1;
+            const uint32_t *r = src0 + c * OPW + (d0 & ~1);     // 8-byte aligned
+            const uint2 A = *reinterpret_cast<const uint2 *>(r);
+            const uint2 B = *reinterpret_cast<const uint2 *>(r + 2);
+            const uint2 C = *reinterpret_cast<const uint2 *>(r + 4);
+            const bool odd = (d0 & 1) != 0;
+            const uint32_t w0 = odd ? A.y : A.x, w1 = odd ? B.x : A.y, w2 = odd ? B.y : B.x, w3 = odd ? C.x : B.y,
+                           w4 = odd ? C.y : C.x;
+            const uint32_t sh = (uint32_t)(pxr & 1) * 16u;
+            uint32x4 v;
+            v.x = __builtin_amdgcn_alignbit(w1, w0, sh);
+            v.y = __builtin_amdgcn_alignbit(w2, w1, sh);
+            v.z = __builtin_amdgcn_alignbit(w3, w2, sh);
+            v.w = __builtin_amdgcn_alignbit(w4, w3, sh);
+            const uint32_t voff = (4 * k < st_nc && px0 + 8 <= cnt) ? (a + (uint32_t)px0) * 2u : OOB;
+            __builtin_amdgcn_raw_buffer_store_b128(v, ry, voff, 0, 3);
+        }
+        const int ec0 = t >> 4, kq = t & 7;
+#pragma unroll
+        for (int k = 0; k < CB * 4; ++k) {
+            const int c = ec0 + 8 * k;
+            const uint32_t a = a0 + (uint32_t)(c * ohw);
+            const int head = min(cnt, (int)((8u - (a & 7u)) & 7u));
+            const int px = (t & 8) ? head + ((cnt - head) & ~7) + kq : (kq < head ? kq : cnt);
+            const uint16_t hv = reinterpret_cast<const uint16_t *>(src0 + c * OPW)[min(px, TM - 1)];
+            const uint32_t voff = (c < p.Cout - co_base && px < cnt) ? (a + (uint32_t)px) * 2u : OOB;
+            __builtin_amdgcn_raw_buffer_store_b16(hv, ry, voff, 0, 3);
         }
     };
 
@@ -1245,6 +1342,12 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
             __syncthreads();
         }
         pool_tile_ws(K - 1);
+    } else if (UNAL && (ohw & 7) != 0) {
+        for (int i = 1; i < K; ++i) {
+            store_tile_ws_grid(i - 1);
+            __syncthreads();
+        }
+        store_tile_ws_grid(K - 1);
     } else {
         for (int i = 1; i < K; ++i) {
             store_tile_ws(i - 1);
@@ -2052,6 +2155,10 @@ hipError_t launch_conv2d(const ConvParams &p, const void *x, const void *w, cons
             const uint32_t gp = (uint32_t)((int64_t)p.N * p.NB);                                           \
             if (p.aligned) return launch(merit_conv2d_planar_ws<CBv, true, SUv, true>, p, x, w, r, y, s, gp, lds, 512);  \
             return launch(merit_conv2d_planar_ws<CBv, false, SUv, true>, p, x, w, r, y, s, gp, lds, 512);     \
+        }                                                                                                  \
+        if (p.unal) {                                                                                      \
+            if (p.aligned) return launch(merit_conv2d_planar_ws<CBv, true, SUv, false, true>, p, x, w, r, y, s, gx, lds, 512); \
+            return launch(merit_conv2d_planar_ws<CBv, false, SUv, false, true>, p, x, w, r, y, s, gx, lds, 512); \
         }                                                                                                  \
         if (p.aligned) return launch(merit_conv2d_planar_ws<CBv, true, SUv, false>, p, x, w, r, y, s, gx, lds, 512); \
         return launch(merit_conv2d_planar_ws<CBv, false, SUv, false>, p, x, w, r, y, s, gx, lds, 512);        \

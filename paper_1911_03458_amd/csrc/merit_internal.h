@@ -160,6 +160,7 @@ struct ConvParams {
     FastDiv div_r2;        // staged rows of both channel groups of a pass (2 * RHa)
     int pool_halo;         // fused pooling there: 1 = a tile computes the row above its first pooled row itself
     int xq;                // multi-pass kernel: 1 = the input rows are staged in units of 8 channels x 4 pixels
+    int unal;              // wave-specialised few-channel kernel: 1 = image rows or output planes start on any element (W % 8 != 0 or OH*OW % 8 != 0)
     int row_skip;          // multi-pass kernel, windows one row high with a row stride: 1 = only the image rows that are used are staged
     int tile_px;           // multi-pass kernel without pooling: output pixels from one tile's start to the next (TM, or whole rows: rows * OW <= TM)
                            // (rows_out_max odd), 0 = that row is carried from the tile before it (rows_out_max even)

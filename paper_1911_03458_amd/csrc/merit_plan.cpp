@@ -576,9 +576,13 @@ merit_status derive_conv(merit_plan *pl)
         // (the kernel fetches a channel's weights in 16-byte vectors: at least one per channel)
         int lgc = 0;
         while ((1 << lgc) < q.pitch / 8) ++lgc;
-        if (variant == CONV_PLANAR_SMALLC && want_ws && q.front + kw <= 8 && pxw == 2 && nw == 4 && (W % 8) == 0 && lgc <= 7 &&
+        // (rows or output planes that start on any element: funnel-shifted staging and stores on the
+        // output's 16-byte grid, not with the fused pooling)
+        const int unal = ((W % 8) != 0 || (OH * OW) % 8 != 0) ? 1 : 0;
+        q.unal = 0;
+        if (variant == CONV_PLANAR_SMALLC && want_ws && q.front + kw <= 8 && pxw == 2 && nw == 4 && (!unal || !pool) && lgc <= 7 &&
             (((int64_t)Cin * q.RHa) << lgc) <= 128 * 10 && (int64_t)q.G * kw >= 8 &&
-            (OH * OW) % 8 == 0 && N * Cin * H * W * 2 < (1ll << 31) &&
+            N * Cin * H * W * 2 < (1ll << 31) &&
             N * Cout * OH * OW * 2 / (pool ? 4 : 1) < (1ll << 31)) {
             static const int steps[] = {4, 6, 8, 11, 12};
             int su = 0;
@@ -587,6 +591,7 @@ merit_status derive_conv(merit_plan *pl)
             const int64_t o_off = (int64_t)q.lds_w_bytes + 32 + 2 * (int64_t)q.lds_x_bytes;
             if (su && o_off + 2 * (int64_t)q.lds_o_bytes <= LDS_LIMIT) {
                 q.ws = 1;
+                q.unal = unal;
                 q.su = su;
                 q.lg_chunks = lgc;
                 q.lds_o_offset = (int)o_off;
@@ -684,7 +689,7 @@ merit_status derive_conv(merit_plan *pl)
         // a window one row high with a row stride uses every sh-th image row: only those are staged
         q.row_skip = (kh == 1 && sh > 1 && !pool) ? 1 : 0;
         if (q.row_skip) q.RHa = q.rows_out_max;
-        q.front = 0; q.aligned = 0; q.ws = 0; q.su = 0; q.lg_chunks = 0; q.pipe = 0;
+        q.front = 0; q.aligned = 0; q.ws = 0; q.su = 0; q.lg_chunks = 0; q.pipe = 0; q.unal = 0;
         q.G = q.G2 = 0;
         q.padl = (int)pw;
         int64_t pitch = q.padl + W;

@@ -544,6 +544,30 @@ WS_CASES = [
 ]
 
 
+WS_UNALIGNED_CASES = [
+    # the same kernel where image rows or output planes start on any element
+    (1, 3, 61, 67, 40, 7, 7, 2, 2, 3, 3),      # odd width, odd element count (the tensor's last unit crosses its end), planes of 1054 pixels
+    (3, 3, 61, 67, 40, 7, 7, 2, 2, 3, 3),      # every parity of an image's start
+    (2, 3, 40, 48, 33, 3, 3, 1, 1, 0, 0),      # W % 8 == 0, planes of 1748 pixels: only the stores are off the grid
+    (2, 3, 34, 36, 33, 5, 5, 1, 1, 2, 2),      # W % 8 == 4, planes of 1224 pixels: only the rows are
+    (300, 3, 31, 33, 64, 7, 7, 2, 2, 3, 3),    # 600 tiles on 256 workgroups: both LDS buffers reused
+    (2, 1, 37, 45, 9, 3, 3, 1, 1, 1, 1),       # one channel, 9 output channels, planes of 1665 pixels
+    (5, 2, 23, 19, 70, 4, 4, 1, 1, 0, 0),      # planes of 320 pixels behind an odd width; three 32-channel blocks in two groups
+]
+
+
+@pytest.mark.parametrize("case", WS_UNALIGNED_CASES)
+def test_conv_wave_specialised_unaligned(mb, case):
+    N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw = case
+    rng = np.random.default_rng(abs(hash(case)) % 2 ** 31)
+    x = rng.standard_normal((N, Cin, H, W)).astype(np.float16)
+    w = (rng.standard_normal((Cout, Cin, kh, kw)) / np.sqrt(Cin * kh * kw)).astype(np.float16)
+    plan = mb.merit_plan_conv2d(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw)
+    plan.set_tile((0, 0, 8, 64))
+    assert plan.launch_info()["kernel"] == "merit_conv2d_planar_ws"
+    _conv_check(mb, x, w, (sh, sw), (ph, pw), (0, 0, 8, 64))
+
+
 @pytest.mark.parametrize("case", WS_CASES)
 def test_conv_wave_specialised(mb, case):
     N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw = case
