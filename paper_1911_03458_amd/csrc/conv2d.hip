@@ -933,7 +933,7 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
         const int tile = lw + min(i, K - 1) * nwg;
         Geom g;
         g.n = (int)fdiv((uint32_t)tile, p.div_tiles);
-        g.m0 = (tile - g.n * p.tiles_per_image) * p.TM;
+        g.m0 = (tile - g.n * p.tiles_per_image) * (UNAL ? p.tile_px : p.TM);
         g.oyA = (int)fdiv((uint32_t)g.m0, p.div_ow);
         const int mlast = min(g.m0 + p.TM, ohw) - 1;
         const int oyB = (int)fdiv((uint32_t)mlast, p.div_ow);
@@ -1070,16 +1070,22 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
         }
     };
 
-    // UNAL, output planes that start on any element (OH*OW % 8 != 0): the 16-byte units lie on the
-    // output's own 16-byte grid -- lane j of a channel stores the unit that starts `head + 8j` pixels
-    // into the channel's run (five dwords of the staging row, shifted down by a half where that pixel
-    // is odd) if all of it is inside the run, and the up to 7 + 7 elements at the run's two ends go
-    // out as 2-byte stores, 16 lanes per channel.
+    // UNAL, output planes that start on any element (OH*OW % 8 != 0): the 16-byte store units lie on
+    // the output's own 16-byte grid.  Tiles advance by TM - 8 pixels and compute TM, so every unit of a
+    // channel's plane lies inside the tile that owns its first pixel (the first TM - 8 of a tile; the
+    // plane's last tile owns the rest): lane j of a channel stores the unit that starts `head + 8j`
+    // pixels into the tile's run -- five dwords of the staging row, shifted down by a half where that
+    // pixel is odd.  Only a plane's first and last tile have elements outside every unit (up to 7 each,
+    // shared 16-byte units with the neighbouring planes): 2-byte stores, 16 lanes per channel.  (With
+    // tiles that end where the next begins every tile had such ends: 2.5 million 2-byte stores into
+    // lines that other workgroups write, 36 us instead of 25 on a 91 MB output.)
     auto store_tile_ws_grid = [&](int i) {
         const Geom P = geom(i);
         const uint32_t *src0 = reinterpret_cast<const uint32_t *>(outl0 + (i & 1) * ostride);
         const uint32_t a0 = (uint32_t)(((size_t)P.n * p.Cout + co_base) * ohw + P.m0);      // element index (bytes < 2^31)
         const int cnt = min(TM, ohw - P.m0);
+        const bool last = P.m0 + TM >= ohw;
+        const int own = last ? cnt - 7 : TM - 8;               // a unit is stored if it starts below this pixel of the tile
         const int j = t & 31;
 #pragma unroll
         for (int k = 0; k < CB * 8; ++k) {
@@ -1101,19 +1107,23 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
             v.y = __builtin_amdgcn_alignbit(w2, w1, sh);
             v.z = __builtin_amdgcn_alignbit(w3, w2, sh);
             v.w = __builtin_amdgcn_alignbit(w4, w3, sh);
-            const uint32_t voff = (4 * k < st_nc && px0 + 8 <= cnt) ? (a + (uint32_t)px0) * 2u : OOB;
+            const uint32_t voff = (4 * k < st_nc && px0 < own) ? (a + (uint32_t)px0) * 2u : OOB;
             __builtin_amdgcn_raw_buffer_store_b128(v, ry, voff, 0, 3);
         }
-        const int ec0 = t >> 4, kq = t & 7;
+        if (P.m0 == 0 || last) {
+            const int ec0 = t >> 4, kq = t & 7;
 #pragma unroll
-        for (int k = 0; k < CB * 4; ++k) {
-            const int c = ec0 + 8 * k;
-            const uint32_t a = a0 + (uint32_t)(c * ohw);
-            const int head = min(cnt, (int)((8u - (a & 7u)) & 7u));
-            const int px = (t & 8) ? head + ((cnt - head) & ~7) + kq : (kq < head ? kq : cnt);
-            const uint16_t hv = reinterpret_cast<const uint16_t *>(src0 + c * OPW)[min(px, TM - 1)];
-            const uint32_t voff = (c < p.Cout - co_base && px < cnt) ? (a + (uint32_t)px) * 2u : OOB;
-            __builtin_amdgcn_raw_buffer_store_b16(hv, ry, voff, 0, 3);
+            for (int k = 0; k < CB * 4; ++k) {
+                const int c = ec0 + 8 * k;
+                const uint32_t a = a0 + (uint32_t)(c * ohw);
+                const int head = min(cnt, (int)((8u - (a & 7u)) & 7u));
+                // lanes 0-7 of a channel: the pixels before the first unit of the plane's first tile;
+                // lanes 8-15: the pixels behind the last unit of its last tile
+                const int px = (t & 8) ? (last ? head + ((cnt - head) & ~7) + kq : cnt) : ((P.m0 == 0 && kq < head) ? kq : cnt);
+                const uint16_t hv = reinterpret_cast<const uint16_t *>(src0 + c * OPW)[min(px, TM - 1)];
+                const uint32_t voff = (c < p.Cout - co_base && px < cnt) ? (a + (uint32_t)px) * 2u : OOB;
+                __builtin_amdgcn_raw_buffer_store_b16(hv, ry, voff, 0, 3);
+            }
         }
     };
 

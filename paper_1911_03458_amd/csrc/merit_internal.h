@@ -162,7 +162,8 @@ struct ConvParams {
     int xq;                // multi-pass kernel: 1 = the input rows are staged in units of 8 channels x 4 pixels
     int unal;              // wave-specialised few-channel kernel: 1 = image rows or output planes start on any element (W % 8 != 0 or OH*OW % 8 != 0)
     int row_skip;          // multi-pass kernel, windows one row high with a row stride: 1 = only the image rows that are used are staged
-    int tile_px;           // multi-pass kernel without pooling: output pixels from one tile's start to the next (TM, or whole rows: rows * OW <= TM)
+    int tile_px;           // output pixels from one tile's start to the next: TM; multi-pass kernel with whole-row tiles: rows * OW <= TM;
+                           // wave-specialised few-channel kernel on output planes off the 16-byte grid: TM - 8 (tiles overlap by 8 pixels)
                            // (rows_out_max odd), 0 = that row is carried from the tile before it (rows_out_max even)
 };
 

@@ -592,6 +592,12 @@ merit_status derive_conv(merit_plan *pl)
             if (su && o_off + 2 * (int64_t)q.lds_o_bytes <= LDS_LIMIT) {
                 q.ws = 1;
                 q.unal = unal;
+                // output planes off the 16-byte grid: tiles advance by 248 pixels and compute 256, so that
+                // every 16-byte unit of a plane lies inside the tile that owns its first pixel
+                if (unal && (OH * OW) % 8 != 0) {
+                    q.tile_px = q.TM - 8;
+                    q.tiles_per_image = (int)std::max<int64_t>(1, cdiv(ohw - 8, q.tile_px));
+                }
                 q.su = su;
                 q.lg_chunks = lgc;
                 q.lds_o_offset = (int)o_off;
