@@ -224,3 +224,69 @@ def test_random_layer_shapes(seed):
             failures.append((case, plan.launch_info()["kernel"]))
     assert not failures, failures
     assert any("chws" in k for k in kernels), kernels
+
+
+@pytest.mark.parametrize("seed", [3, 227])
+def test_random_few_channel_layers(seed):
+    """First layers: 1..7 input channels on images of 20..130 pixels a side with any width (odd,
+    even, a multiple of 8 or not), window rows of up to 16 taps, strides up to 4 -- several tiles per
+    image, so the few-channel MFMA kernels' staging of rows that start on any element and their
+    stores into output planes off the 16-byte grid are met in every alignment; plain, clipped, with
+    an added tensor and (where the shape allows) with the fused pooling."""
+    rng = np.random.default_rng(seed)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+    failures, kernels = [], set()
+
+    def ri(a, b):
+        return int(rng.integers(a, b + 1))
+
+    for it in range(30):
+        N, Cin, Cout = ri(1, 6), ri(1, 7), ri(1, 100)
+        H, W = ri(20, 130), ri(20, 130)
+        kh, kw = ri(1, 7), ri(1, 7)
+        if rng.random() < 0.25: kh, kw = ri(7, 11), ri(9, 16)
+        sh, sw = ri(1, 4), ri(1, 4)
+        if rng.random() < 0.5: sh = sw = ri(1, 2)
+        ph, pw = ri(0, kh // 2), ri(0, min(kw // 2, 8))
+        OH, OW = (H + 2 * ph - kh) // sh + 1, (W + 2 * pw - kw) // sw + 1
+        while N > 1 and N * Cout * OH * OW * Cin * kh * kw > 4e8: N -= 1
+        mode = str(rng.choice(["plain", "relu", "residual", "pool"], p=[0.4, 0.3, 0.15, 0.15]))
+        relu = int(mode in ("relu", "pool") or (mode == "residual" and rng.random() < 0.5))
+        case = (mode, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, relu)
+        print(it, case, flush=True)
+        x = rng.standard_normal((N, Cin, H, W)).astype(np.float16)
+        w = (rng.standard_normal((Cout, Cin, kh, kw)) / np.sqrt(Cin * kh * kw)).astype(np.float16)
+        try:
+            if mode == "residual": plan = mb.merit_plan_conv2d_residual(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, relu)
+            elif mode == "pool": plan = mb.merit_plan_conv2d_pool(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, relu)
+            else: plan = mb.merit_plan_conv2d_dilated(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, 1, 1, relu)
+        except mb.MeritError as e:
+            print("   plan refused:", e, flush=True)
+            assert mode == "pool", case                     # only the fused pooling has shape conditions
+            continue
+        if mode in ("plain", "relu") and rng.random() < 0.6:
+            # the wave-specialised kernel, which the planner itself takes on grids of 512 tiles and more
+            try:
+                plan.set_tile((0, 0, 8, 64))
+            except mb.MeritError:
+                pass
+        buf, y, pad = _guard(plan.out_shape(), torch.float16)
+        if mode == "residual":
+            r = rng.standard_normal(plan.out_shape()).astype(np.float16)
+            mb.merit_conv2d_residual(plan, dev(x), dev(w), dev(r), y)
+            ref = oracle.conv2d_residual(x, w, r, (sh, sw), (ph, pw), bool(relu))
+        elif mode == "pool":
+            mb.merit_conv2d(plan, dev(x), dev(w), y)
+            ref = oracle.conv2d_pool(x, w, (sh, sw), (ph, pw), bool(relu))
+        else:
+            mb.merit_conv2d(plan, dev(x), dev(w), y)
+            ref = oracle.conv2d(x, w, (sh, sw), (ph, pw), bool(relu))
+        torch.cuda.synchronize()
+        li = plan.launch_info()
+        kernels.add(li["kernel"])
+        print("   ", li["kernel"], li["grid"], flush=True)
+        got = y.cpu().numpy().astype(np.float64); ref = ref.astype(np.float64)
+        if not (_canary(buf, pad) and got.shape == ref.shape and np.all(np.abs(got - ref) <= 2e-2 * np.abs(ref) + 1e-3)):
+            failures.append((case, li["kernel"]))
+    assert not failures, failures
+    assert "merit_conv2d_planar_ws" in kernels and "merit_conv2d_planar" in kernels, kernels
