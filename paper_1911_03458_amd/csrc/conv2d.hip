@@ -155,11 +155,16 @@ __device__ __forceinline__ void lds_to_global(const ConvParams &p, const uint32_
         // the output's own 16-byte grid (y itself is 16-byte aligned: the entry points check it; one
         // more unit per channel than the tile has, as the run may straddle), a whole unit is five
         // dwords of the staging row shifted down by one half where its first pixel is odd, and the
-        // run's two ends are stored element by element in a pass of their own (in the same loop every
-        // wavefront would take both branches).  As 2-byte stores, 16 bytes apart between lanes, a
-        // 53 MB output took 63 us.
+        // elements outside every whole unit are stored one by one in a pass of their own (in the same
+        // loop every wavefront would take both branches).  As 2-byte stores, 16 bytes apart between
+        // lanes, a 53 MB output took 63 us.
+        // Tiles that advance by TM - 8 pixels (p.tile_px; they compute TM) own the units that start in
+        // their first TM - 8 pixels, the plane's last tile the rest: only a plane's first and last tile
+        // then have elements outside every unit.  Tiles that advance by TM have up to 7 at either end.
         constexpr int UPC = TM / 8 + 1;
         const int cnt = min(TM, ohw - m0);
+        const bool last = m0 + TM >= ohw, overlap = p.tile_px != TM;
+        const int own = (last || !overlap) ? cnt - 7 : p.tile_px;    // a unit is stored if it starts below this pixel
         const int nch = min(CB * 32, p.Cout - co_base);
         const size_t a0 = ((size_t)n * p.Cout + co_base) * ohw + m0;
         // (the LDS reads of two units per thread go out together, clamped to the area where a unit
@@ -177,7 +182,7 @@ __device__ __forceinline__ void lds_to_global(const ConvParams &p, const uint32_
                 const int j = u - (u / UPC) * UPC;
                 coff[i] = (uint32_t)c * (uint32_t)ohw;
                 const int px0 = 8 * j - (int)((a0 + coff[i]) & 7);   // tile pixel of the unit's first element
-                pxs[i] = (u < nch * UPC && px0 >= 0 && px0 + 8 <= cnt) ? px0 : -1;
+                pxs[i] = (u < nch * UPC && px0 >= 0 && px0 < own) ? px0 : -1;
                 const uint32_t *src = outl + c * OP + (max(pxs[i], 0) >> 1);   // (the fifth dword: at most the row's padding)
 #pragma unroll
                 for (int q = 0; q < 5; ++q) d[i][q] = src[q];
@@ -195,6 +200,8 @@ __device__ __forceinline__ void lds_to_global(const ConvParams &p, const uint32_
             }
         }
         // the up to 7 elements before a channel's first whole unit and after its last: 16 lanes per channel
+        const bool heads = m0 == 0 || !overlap, tails = last || !overlap;
+        if (!heads && !tails) return;
         constexpr int EB = 2;
 #pragma unroll 1
         for (int e0 = t; e0 < nch * 16; e0 += NT * EB) {
@@ -207,7 +214,7 @@ __device__ __forceinline__ void lds_to_global(const ConvParams &p, const uint32_
                 const int c = min(e >> 4, nch - 1), k = e & 7;
                 eoff[i] = (uint32_t)c * (uint32_t)ohw;
                 const int head = min(cnt, (8 - (int)((a0 + eoff[i]) & 7)) & 7);
-                const int px = (e & 8) ? head + ((cnt - head) & ~7) + k : (k < head ? k : cnt);
+                const int px = (e & 8) ? (tails ? head + ((cnt - head) & ~7) + k : cnt) : ((heads && k < head) ? k : cnt);
                 epx[i] = (e < nch * 16 && px < cnt) ? px : -1;
                 ev[i] = reinterpret_cast<const uint16_t *>(outl + c * OP)[max(epx[i], 0)];
             }
@@ -349,7 +356,7 @@ __global__ __launch_bounds__(NW * 64, 2) void merit_conv2d_planar(ConvParams p, 
     auto geom = [&](int tile) {
         Geom t;
         t.n = (int)fdiv((uint32_t)tile, p.div_tiles);
-        t.m0 = (tile - t.n * p.tiles_per_image) * p.TM;
+        t.m0 = (tile - t.n * p.tiles_per_image) * p.tile_px;     // (TM, or TM - 8 where output planes lie off the 16-byte grid)
         t.oyA = (int)fdiv((uint32_t)t.m0, p.div_ow);
         const int mlast = min(t.m0 + p.TM, ohw) - 1;
         const int oyB = (int)fdiv((uint32_t)mlast, p.div_ow);
@@ -1077,15 +1084,17 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
     // pixels into the tile's run -- five dwords of the staging row, shifted down by a half where that
     // pixel is odd.  Only a plane's first and last tile have elements outside every unit (up to 7 each,
     // shared 16-byte units with the neighbouring planes): 2-byte stores, 16 lanes per channel.  (With
-    // tiles that end where the next begins every tile had such ends: 2.5 million 2-byte stores into
-    // lines that other workgroups write, 36 us instead of 25 on a 91 MB output.)
+    // tiles that end where the next begins -- p.tile_px == TM, taken where the extra tiles would cost the
+    // grid another round -- every tile has such ends: 2.5 million 2-byte stores into lines that other
+    // workgroups write, 36 us instead of 31 on a 91 MB output.)
     auto store_tile_ws_grid = [&](int i) {
         const Geom P = geom(i);
         const uint32_t *src0 = reinterpret_cast<const uint32_t *>(outl0 + (i & 1) * ostride);
         const uint32_t a0 = (uint32_t)(((size_t)P.n * p.Cout + co_base) * ohw + P.m0);      // element index (bytes < 2^31)
         const int cnt = min(TM, ohw - P.m0);
-        const bool last = P.m0 + TM >= ohw;
-        const int own = last ? cnt - 7 : TM - 8;               // a unit is stored if it starts below this pixel of the tile
+        const bool last = P.m0 + TM >= ohw, overlap = p.tile_px != TM;
+        const int own = (last || !overlap) ? cnt - 7 : TM - 8;  // a unit is stored if it starts below this pixel of the tile
+        const bool heads = P.m0 == 0 || !overlap, tails = last || !overlap;
         const int j = t & 31;
 #pragma unroll
         for (int k = 0; k < CB * 8; ++k) {
@@ -1110,7 +1119,7 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
             const uint32_t voff = (4 * k < st_nc && px0 < own) ? (a + (uint32_t)px0) * 2u : OOB;
             __builtin_amdgcn_raw_buffer_store_b128(v, ry, voff, 0, 3);
         }
-        if (P.m0 == 0 || last) {
+        if (heads || tails) {
             const int ec0 = t >> 4, kq = t & 7;
 #pragma unroll
             for (int k = 0; k < CB * 4; ++k) {
@@ -1119,7 +1128,7 @@ __global__ __launch_bounds__(512, 1) void merit_conv2d_planar_ws(ConvParams p, c
                 const int head = min(cnt, (int)((8u - (a & 7u)) & 7u));
                 // lanes 0-7 of a channel: the pixels before the first unit of the plane's first tile;
                 // lanes 8-15: the pixels behind the last unit of its last tile
-                const int px = (t & 8) ? (last ? head + ((cnt - head) & ~7) + kq : cnt) : ((P.m0 == 0 && kq < head) ? kq : cnt);
+                const int px = (t & 8) ? (tails ? head + ((cnt - head) & ~7) + kq : cnt) : ((heads && kq < head) ? kq : cnt);
                 const uint16_t hv = reinterpret_cast<const uint16_t *>(src0 + c * OPW)[min(px, TM - 1)];
                 const uint32_t voff = (c < p.Cout - co_base && px < cnt) ? (a + (uint32_t)px) * 2u : OOB;
                 __builtin_amdgcn_raw_buffer_store_b16(hv, ry, voff, 0, 3);

@@ -594,14 +594,31 @@ merit_status derive_conv(merit_plan *pl)
                 q.unal = unal;
                 // output planes off the 16-byte grid: tiles advance by 248 pixels and compute 256, so that
                 // every 16-byte unit of a plane lies inside the tile that owns its first pixel
+                // (unless the extra tiles cost the persistent grid, one workgroup per compute unit, a round that
+                // outweighs the 12 % or so that such a tile's stores gain)
                 if (unal && (OH * OW) % 8 != 0) {
-                    q.tile_px = q.TM - 8;
-                    q.tiles_per_image = (int)std::max<int64_t>(1, cdiv(ohw - 8, q.tile_px));
+                    const int64_t t_ov = std::max<int64_t>(1, cdiv(ohw - 8, q.TM - 8));
+                    const int64_t slots = std::max<int64_t>(1, 256 / q.co_groups);
+                    if (0.88 * (double)cdiv(N * t_ov, slots) <= (double)cdiv(N * q.tiles_per_image, slots)) {
+                        q.tile_px = q.TM - 8;
+                        q.tiles_per_image = (int)t_ov;
+                    }
                 }
                 q.su = su;
                 q.lg_chunks = lgc;
                 q.lds_o_offset = (int)o_off;
                 q.lds_total = (int)(o_off + 2 * (int64_t)q.lds_o_bytes);
+            }
+        }
+        // the few-channel kernel without wave specialisation on output planes off the 16-byte grid: the same
+        // overlapping tiles (a tile's run of a channel then has no elements outside every 16-byte store unit)
+        if (variant == CONV_PLANAR_SMALLC && !q.ws && !pool && (OH * OW) % 8 != 0) {
+            const int64_t t_ov = std::max<int64_t>(1, cdiv(ohw - 8, q.TM - 8));
+            const int64_t wgs = std::min<int64_t>(3, LDS_LIMIT / (int64_t)conv_lds_bytes(q));
+            const int64_t slots = std::max<int64_t>(1, 256 * wgs / q.co_groups);
+            if (0.88 * (double)cdiv(N * t_ov, slots) <= (double)cdiv(N * q.tiles_per_image, slots)) {
+                q.tile_px = q.TM - 8;
+                q.tiles_per_image = (int)t_ov;
             }
         }
         if ((int64_t)conv_lds_bytes(q) > LDS_LIMIT) return false;

@@ -553,6 +553,7 @@ WS_UNALIGNED_CASES = [
     (300, 3, 31, 33, 64, 7, 7, 2, 2, 3, 3),    # 600 tiles on 256 workgroups: both LDS buffers reused
     (2, 1, 37, 45, 9, 3, 3, 1, 1, 1, 1),       # one channel, 9 output channels, planes of 1665 pixels
     (5, 2, 23, 19, 70, 4, 4, 1, 1, 0, 0),      # planes of 320 pixels behind an odd width; three 32-channel blocks in two groups
+    (64, 3, 32, 36, 16, 3, 3, 1, 1, 0, 0),     # planes of 1020 pixels, 256 tiles: overlapping tiles would need a second round, so every tile has loose ends
 ]
 
 
