@@ -161,67 +161,11 @@ __device__ __forceinline__ void lds_to_global(const ConvParams &p, const uint32_
         // Tiles that advance by TM - 8 pixels (p.tile_px; they compute TM) own the units that start in
         // their first TM - 8 pixels, the plane's last tile the rest: only a plane's first and last tile
         // then have elements outside every unit.  Tiles that advance by TM have up to 7 at either end.
-        constexpr int UPC = TM / 8 + 1;
         const int cnt = min(TM, ohw - m0);
         const bool last = m0 + TM >= ohw, overlap = p.tile_px != TM;
         const int own = (last || !overlap) ? cnt - 7 : p.tile_px;    // a unit is stored if it starts below this pixel
-        const int nch = min(CB * 32, p.Cout - co_base);
-        const size_t a0 = ((size_t)n * p.Cout + co_base) * ohw + m0;
-        // (the LDS reads of two units per thread go out together, clamped to the area where a unit
-        // is not stored: half the round trips, and few enough registers)
-        constexpr int UB = 2;
-#pragma unroll 1
-        for (int u0 = t; u0 < nch * UPC; u0 += NT * UB) {
-            uint32_t d[UB][5];
-            int pxs[UB];
-            uint32_t coff[UB];                                   // c * ohw (below 2^32: 63 planes of the output)
-#pragma unroll
-            for (int i = 0; i < UB; ++i) {
-                const int u = u0 + NT * i;
-                const int c = min(u / UPC, nch - 1);
-                const int j = u - (u / UPC) * UPC;
-                coff[i] = (uint32_t)c * (uint32_t)ohw;
-                const int px0 = 8 * j - (int)((a0 + coff[i]) & 7);   // tile pixel of the unit's first element
-                pxs[i] = (u < nch * UPC && px0 >= 0 && px0 < own) ? px0 : -1;
-                const uint32_t *src = outl + c * OP + (max(pxs[i], 0) >> 1);   // (the fifth dword: at most the row's padding)
-#pragma unroll
-                for (int q = 0; q < 5; ++q) d[i][q] = src[q];
-            }
-#pragma unroll
-            for (int i = 0; i < UB; ++i) {
-                if (pxs[i] < 0) continue;
-                const uint32_t sh = (uint32_t)(pxs[i] & 1) * 16u;
-                uint32x4 v;
-                v.x = __builtin_amdgcn_alignbit(d[i][1], d[i][0], sh);
-                v.y = __builtin_amdgcn_alignbit(d[i][2], d[i][1], sh);
-                v.z = __builtin_amdgcn_alignbit(d[i][3], d[i][2], sh);
-                v.w = __builtin_amdgcn_alignbit(d[i][4], d[i][3], sh);
-                __builtin_nontemporal_store(v, reinterpret_cast<uint32x4 *>(y + a0 + coff[i] + pxs[i]));
-            }
-        }
-        // the up to 7 elements before a channel's first whole unit and after its last: 16 lanes per channel
-        const bool heads = m0 == 0 || !overlap, tails = last || !overlap;
-        if (!heads && !tails) return;
-        constexpr int EB = 2;
-#pragma unroll 1
-        for (int e0 = t; e0 < nch * 16; e0 += NT * EB) {
-            uint16_t ev[EB];
-            int epx[EB];
-            uint32_t eoff[EB];
-#pragma unroll
-            for (int i = 0; i < EB; ++i) {
-                const int e = e0 + NT * i;
-                const int c = min(e >> 4, nch - 1), k = e & 7;
-                eoff[i] = (uint32_t)c * (uint32_t)ohw;
-                const int head = min(cnt, (8 - (int)((a0 + eoff[i]) & 7)) & 7);
-                const int px = (e & 8) ? (tails ? head + ((cnt - head) & ~7) + k : cnt) : ((heads && k < head) ? k : cnt);
-                epx[i] = (e < nch * 16 && px < cnt) ? px : -1;
-                ev[i] = reinterpret_cast<const uint16_t *>(outl + c * OP)[max(epx[i], 0)];
-            }
-#pragma unroll
-            for (int i = 0; i < EB; ++i)
-                if (epx[i] >= 0) y[a0 + eoff[i] + epx[i]] = ev[i];
-        }
+        store_runs_on_grid<TM, NT>(outl, y, ((size_t)n * p.Cout + co_base) * ohw + m0, ohw, cnt, min(CB * 32, p.Cout - co_base),
+                                   own, m0 == 0 || !overlap, last || !overlap, t);
         return;
     }
 #pragma unroll

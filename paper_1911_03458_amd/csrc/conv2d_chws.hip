@@ -185,8 +185,13 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
 
     // results: LDS [channel][pixel] -> 16-byte runs along the pixel axis, by all threads
     auto store_out = [&](const Geom &g) __attribute__((always_inline)) {
-        const bool vec_ok = (ohw & 7) == 0;
         constexpr int UNITS = TN * (TM / 8);
+        if ((ohw & 7) != 0) {                                // 13x13, 27x27, 7x7: planes off the 16-byte grid
+            const int cnt = g.mend - g.m0;
+            store_runs_on_grid<TM, NT>(outl, y, ((size_t)g.n * p.Cout + g.cg * TN) * ohw + g.m0, ohw, cnt,
+                                       min(TN, p.Cout - g.cg * TN), cnt - 7, true, true, tid);
+            return;
+        }
 #pragma unroll 4
         for (int u = tid; u < UNITS; u += NT) {
             const int c = u / (TM / 8);
@@ -197,18 +202,9 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
             const uint2 *src = reinterpret_cast<const uint2 *>(outl + c * OP + px8 * 4);
             const uint2 lo = src[0], hi = src[1];
             uint16_t *y0 = y + ((size_t)g.n * p.Cout + co) * ohw + m;
-            if (vec_ok) {
-                uint32x4 v;
-                v.x = lo.x; v.y = lo.y; v.z = hi.x; v.w = hi.y;
-                __builtin_nontemporal_store(v, reinterpret_cast<uint32x4 *>(y0));
-            } else {
-                const uint32_t e[4] = {lo.x, lo.y, hi.x, hi.y};
-#pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    if (m + k >= g.mend) break;
-                    y0[k] = (uint16_t)(e[k >> 1] >> (16 * (k & 1)));
-                }
-            }
+            uint32x4 v;
+            v.x = lo.x; v.y = lo.y; v.z = hi.x; v.w = hi.y;
+            __builtin_nontemporal_store(v, reinterpret_cast<uint32x4 *>(y0));
         }
     };
 

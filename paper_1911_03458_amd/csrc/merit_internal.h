@@ -41,6 +41,78 @@ __device__ __forceinline__ uint32_t xcd_band_item(uint32_t hw_id, int xq, int xr
     const uint32_t xcd = hw_id & 7u, slot = hw_id >> 3;
     return xcd * (uint32_t)xq + min(xcd, (uint32_t)xr) + slot;
 }
+
+// Results of a convolution tile, LDS staging -> global, where a channel's run of the tile starts on
+// any element of the output (OH*OW % 8 != 0; y itself is 16-byte aligned).  outl: [channel][TM / 2 + 2]
+// dwords, two pixels each; a0: element index in y of channel 0's first pixel, channel c `ohw` elements
+// further; cnt: pixels of the run (<= TM); nch: channels; t: thread of NT.  The 16-byte store units lie
+// on the output's own 16-byte grid (one more per channel than the tile has, as the run may straddle):
+// a unit that starts at tile pixel 0 <= px0 < own is five dwords of the staging row, shifted down by a
+// half where px0 is odd (own <= cnt - 7: every stored unit is whole).  The up to 7 pixels before the
+// first unit (`heads`) and behind the last (`tails`) go out as 2-byte stores in a pass of their own, 16
+// lanes per channel (in one loop every wavefront would take both branches).  Tiles that abut pass
+// own = cnt - 7 and both flags; tiles that overlap by 8 pixels pass own = TM - 8 and no flag, but for a
+// plane's first tile (heads) and last tile (own = cnt - 7, tails).
+template <int TM, int NT>
+__device__ __forceinline__ void store_runs_on_grid(const uint32_t *outl, uint16_t *__restrict__ y, size_t a0, int ohw,
+                                                   int cnt, int nch, int own, bool heads, bool tails, int t)
+{
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    constexpr int OP = TM / 2 + 2, UPC = TM / 8 + 1;
+    // (the LDS reads of two units per thread go out together, clamped to the area where a unit
+    // is not stored: half the round trips, and few enough registers)
+    constexpr int UB = 2;
+#pragma unroll 1
+    for (int u0 = t; u0 < nch * UPC; u0 += NT * UB) {
+        uint32_t d[UB][5];
+        int pxs[UB];
+        uint32_t coff[UB];                                   // c * ohw (below 2^32: a tile's channels)
+#pragma unroll
+        for (int i = 0; i < UB; ++i) {
+            const int u = u0 + NT * i;
+            const int c = min(u / UPC, nch - 1);
+            const int j = u - (u / UPC) * UPC;
+            coff[i] = (uint32_t)c * (uint32_t)ohw;
+            const int px0 = 8 * j - (int)((a0 + coff[i]) & 7);   // tile pixel of the unit's first element
+            pxs[i] = (u < nch * UPC && px0 >= 0 && px0 < own) ? px0 : -1;
+            const uint32_t *src = outl + c * OP + (max(pxs[i], 0) >> 1);   // (the fifth dword: at most the row's padding)
+#pragma unroll
+            for (int q = 0; q < 5; ++q) d[i][q] = src[q];
+        }
+#pragma unroll
+        for (int i = 0; i < UB; ++i) {
+            if (pxs[i] < 0) continue;
+            const uint32_t sh = (uint32_t)(pxs[i] & 1) * 16u;
+            u32x4 v;
+            v.x = __builtin_amdgcn_alignbit(d[i][1], d[i][0], sh);
+            v.y = __builtin_amdgcn_alignbit(d[i][2], d[i][1], sh);
+            v.z = __builtin_amdgcn_alignbit(d[i][3], d[i][2], sh);
+            v.w = __builtin_amdgcn_alignbit(d[i][4], d[i][3], sh);
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(y + a0 + coff[i] + pxs[i]));
+        }
+    }
+    if (!heads && !tails) return;
+    constexpr int EB = 2;
+#pragma unroll 1
+    for (int e0 = t; e0 < nch * 16; e0 += NT * EB) {
+        uint16_t ev[EB];
+        int epx[EB];
+        uint32_t eoff[EB];
+#pragma unroll
+        for (int i = 0; i < EB; ++i) {
+            const int e = e0 + NT * i;
+            const int c = min(e >> 4, nch - 1), k = e & 7;
+            eoff[i] = (uint32_t)c * (uint32_t)ohw;
+            const int head = min(cnt, (8 - (int)((a0 + eoff[i]) & 7)) & 7);
+            const int px = (e & 8) ? (tails ? head + ((cnt - head) & ~7) + k : cnt) : ((heads && k < head) ? k : cnt);
+            epx[i] = (e < nch * 16 && px < cnt) ? px : -1;
+            ev[i] = reinterpret_cast<const uint16_t *>(outl + c * OP)[max(epx[i], 0)];
+        }
+#pragma unroll
+        for (int i = 0; i < EB; ++i)
+            if (epx[i] >= 0) y[a0 + eoff[i] + epx[i]] = ev[i];
+    }
+}
 #endif
 
 // ---- launcher helpers (host) -------------------------------------------------
