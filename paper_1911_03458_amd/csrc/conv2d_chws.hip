@@ -138,6 +138,7 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
     constexpr int OP = TM / 2 + 2;                       // output staging: dwords per channel
     constexpr bool XV = XU == 1 || XU == 2;              // 8-pixel input units, XU per moving thread
     constexpr bool XQ = XU == 4;                         // 4-pixel input units (W % 4 == 0)
+    constexpr bool XD = XU == 3;                         // 2-pixel input units (W % 4 == 2: rows start on 4-byte boundaries)
 
     {
         // The kernel-argument block (ConvParams and three pointers: six 64-byte lines) is read with
@@ -292,13 +293,15 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
 
         constexpr int XSM = (NMW == 4 && T != 25) ? XS_MAX : 4;       // (5x5: 100 registers of weights on their way)
         constexpr int XQM = NMW == 4 ? 4 : 2;                // 4-pixel units per moving thread, at most
-        constexpr int NXU = XV ? XU : (XQ ? XQM : XSM);
+        constexpr int XDM = XSM;                             // 2-pixel units per moving thread, at most
+        constexpr int NXU = XV ? XU : (XQ ? XQM : (XD ? XDM : XSM));
         uint32_t x_voff[NXU];               // byte offset of the unit inside (image, first channel of the pass)
-        int x_lds[NXU][XV ? 8 : (XQ ? 4 : 1)];         // byte address of each of its pixels inside a pass buffer's input region
+        int x_lds[NXU][XV ? 8 : (XQ ? 4 : (XD ? 2 : 1))];   // byte address of each of its pixels inside a pass buffer's input region
         int x_hh[NXU];                      // its channel group within the pass
         uint32_t xv[XV ? XU : 1][8][4];     // the unit on its way: 8 channels x 8 pixels
-        uint32_t xs[(XV || XQ) ? 1 : XSM][8];    // ... 8 channels x 1 pixel (a register each: see commit)
+        uint32_t xs[(XV || XQ || XD) ? 1 : XSM][8];    // ... 8 channels x 1 pixel (a register each: see commit)
         uint32_t xq[XQ ? XQM : 1][8][2];         // ... 8 channels x 4 pixels
+        uint32_t xd[XD ? XDM : 1][8];            // ... 8 channels x 2 pixels
         uint32_t w_voff[WU];
         int w_lds[WU], w_hh[WU];
         uint32_t wr[PACKED ? 1 : WU][PACKED ? 1 : 4 * T];
@@ -345,6 +348,25 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
 #pragma unroll
                     for (int px = 0; px < 4; ++px)
                         x_lds[k][px] = (q * p.pitch + p.padl + 4 * x4 + px) * 16;
+                }
+            } else if constexpr (XD) {
+                const int W2 = p.W >> 1;
+                const int nu = NGRP * p.RHa * W2;
+#pragma unroll
+                for (int k = 0; k < XDM; ++k) {
+                    const int u = mt + 256 * k;
+                    const int uc = min(u, nu - 1);
+                    const int x2 = (int)fdiv((uint32_t)uc, p.div_r2);
+                    const int q = uc - x2 * NGRP * p.RHa;
+                    const int hh = (int)fdiv((uint32_t)q, p.div_rha);
+                    const int r = q - hh * p.RHa;
+                    const int gy = g.yA + r * rstep;
+                    const bool ok = u < nu && r < g.RH && gy >= 0 && gy < p.H;
+                    x_hh[k] = u < nu ? hh : NGRP;
+                    x_voff[k] = ok ? (uint32_t)(((hh * 8 * p.H + gy) * p.W + 2 * x2) * 2) : OOB;
+#pragma unroll
+                    for (int px = 0; px < 2; ++px)
+                        x_lds[k][px] = (q * p.pitch + p.padl + 2 * x2 + px) * 16;
                 }
             } else {
                 const int nu = NGRP * p.RHa * p.W;
@@ -398,6 +420,8 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
                     } else if constexpr (XQ) {
                         const uint32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rx, voff, xbase + c * chbytes, 0);
                         xq[k][c][0] = v.x; xq[k][c][1] = v.y;
+                    } else if constexpr (XD) {
+                        xd[k][c] = __builtin_amdgcn_raw_buffer_load_b32(rx, voff, xbase + c * chbytes, 0);
                     } else {
                         xs[k][c] = __builtin_amdgcn_raw_buffer_load_b16(rx, voff, xbase + c * chbytes, 0);
                     }
@@ -444,6 +468,17 @@ __global__ __launch_bounds__((WM * WN + 4) * 64, 1) void merit_conv2d_chws(ConvP
                             d.y = __builtin_amdgcn_perm(xq[k][3][px >> 1], xq[k][2][px >> 1], sel);
                             d.z = __builtin_amdgcn_perm(xq[k][5][px >> 1], xq[k][4][px >> 1], sel);
                             d.w = __builtin_amdgcn_perm(xq[k][7][px >> 1], xq[k][6][px >> 1], sel);
+                            *reinterpret_cast<uint32x4 *>(xl + x_lds[k][px]) = d;
+                        }
+                    } else if constexpr (XD) {
+#pragma unroll
+                        for (int px = 0; px < 2; ++px) {
+                            const uint32_t sel = px ? 0x07060302u : 0x05040100u;
+                            uint32x4 d;
+                            d.x = __builtin_amdgcn_perm(xd[k][1], xd[k][0], sel);
+                            d.y = __builtin_amdgcn_perm(xd[k][3], xd[k][2], sel);
+                            d.z = __builtin_amdgcn_perm(xd[k][5], xd[k][4], sel);
+                            d.w = __builtin_amdgcn_perm(xd[k][7], xd[k][6], sel);
                             *reinterpret_cast<uint32x4 *>(xl + x_lds[k][px]) = d;
                         }
                     } else {
@@ -747,8 +782,9 @@ template <int PXB, int CHB, int WM, int WN, int NG = 1, bool POOLS = false>
 hipError_t launch_tile(const ConvParams &p, const void *x, const void *w, const void *res, void *y, hipStream_t s,
                        uint32_t grid, bool packed)
 {
-    // 8-pixel units per moving thread (1, 2); 4: four-pixel units (W % 4 == 0, 3x3 and 1x1 windows); 0: one-pixel units
-    const int xu = (p.W & 7) == 0 ? p.xu : (p.xq ? 4 : 0);
+    // 8-pixel units per moving thread (1, 2); 4: four-pixel units (W % 4 == 0, 3x3 and 1x1 windows); 3: two-pixel units
+    // (W % 4 == 2, the same windows, no added tensor, no pooling); 0: one-pixel units
+    const int xu = (p.W & 7) == 0 ? p.xu : (p.xq == 1 ? 4 : (p.xq == 2 ? 3 : 0));
     const int T = p.kh * p.kw;
     if (p.residual) {
         // residual layer: 3x3 and 1x1 windows on the caller's weights, the two 64-channel tilings (on the
@@ -791,11 +827,13 @@ hipError_t launch_tile(const ConvParams &p, const void *x, const void *w, const 
         if (T == 9 && xu == 2) MERIT_CHWS(9, 2);
         if (T == 9 && xu == 0) MERIT_CHWS(9, 0);
         if (T == 9 && xu == 4) MERIT_CHWS(9, 4);
+        if (T == 9 && xu == 3) MERIT_CHWS(9, 3);
     }
     if (T == 1 && xu == 1) MERIT_CHWS(1, 1);
     if (T == 1 && xu == 2) MERIT_CHWS(1, 2);
     if (T == 1 && xu == 0) MERIT_CHWS(1, 0);
     if (T == 1 && xu == 4) MERIT_CHWS(1, 4);
+    if (T == 1 && xu == 3) MERIT_CHWS(1, 3);
     // 5x5 windows: the 256-pixel x 64-channel tiling only (a pass's 25 x 2 x 64 weight fragments are 51 KB)
     if constexpr (PXB == 2 && CHB == 2 && WM == 4 && WN == 1 && NG == 1) {
         if (T == 25 && xu == 1) MERIT_CHWS(25, 1);

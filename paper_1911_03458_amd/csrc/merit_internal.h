@@ -231,7 +231,7 @@ struct ConvParams {
     FastDiv div_cog;       // work item -> (tile, channel block)
     FastDiv div_r2;        // staged rows of both channel groups of a pass (2 * RHa)
     int pool_halo;         // fused pooling there: 1 = a tile computes the row above its first pooled row itself
-    int xq;                // multi-pass kernel: 1 = the input rows are staged in units of 8 channels x 4 pixels
+    int xq;                // multi-pass kernel: the input rows are staged in units of 8 channels x 4 pixels (1) or x 2 pixels (2)
     int unal;              // wave-specialised few-channel kernel: 1 = image rows or output planes start on any element (W % 8 != 0 or OH*OW % 8 != 0)
     int row_skip;          // multi-pass kernel, windows one row high with a row stride: 1 = only the image rows that are used are staged
     int tile_px;           // output pixels from one tile's start to the next: TM; multi-pass kernel with whole-row tiles: rows * OW <= TM;

@@ -762,6 +762,13 @@ merit_status derive_conv(merit_plan *pl)
             q.xu = (int)cdiv(nu, 256);
             q.xq = 1;
             q.div_r2 = make_fastdiv((uint32_t)(2 * ng * q.RHa));
+        } else if ((W % 2) == 0 && !k5 && !pool && !p.residual && 2 * ng * (int64_t)q.RHa * (W / 2) <= (nw == 8 ? 8 : 4) * 256 &&
+                   fastdiv_ok(2 * ng * (int64_t)q.RHa * (W / 2), 2 * ng * (int64_t)q.RHa)) {
+            // 8 channels x 2 pixels (rows of an even width start on 4-byte boundaries: 14x14 layers), eight units
+            // per moving thread, four on 12 wavefronts
+            q.xu = (int)cdiv(2 * ng * (int64_t)q.RHa * (W / 2), 256);
+            q.xq = 2;
+            q.div_r2 = make_fastdiv((uint32_t)(2 * ng * q.RHa));
         } else {
             const int64_t nu = 2 * ng * (int64_t)q.RHa * W;
             if (nu > ((nw == 8 && !k5) ? 8 : 4) * 256 || !fastdiv_ok(nu, W)) return false;

@@ -78,6 +78,14 @@ CHWS_CASES = [
     ((1, 40, 13, 11, 64, 3, 3, 2, 2, 1, 1), (1, 1), 0, (0, 0, 8, 32)),      # one-pixel input units, stride 2, one group of padding
     ((300, 32, 12, 16, 64, 3, 3, 1, 1, 1, 1), (1, 1), 0, (0, 0, 8, 32)),    # a single pass per item, several items per workgroup
     ((1, 96, 20, 40, 64, 1, 1, 1, 1, 0, 0), (1, 1), 0, (0, 0, 8, 32)),      # 1x1
+    # two-pixel input units (W % 4 == 2: rows start on 4-byte boundaries)
+    ((2, 128, 14, 14, 40, 3, 3, 1, 1, 1, 1), (1, 1), 0, None),              # the 14x14 layers' shape class, ragged channel block
+    ((1, 200, 13, 14, 64, 3, 3, 1, 1, 1, 1), (1, 1), 1, None),              # last pass half empty, odd height
+    ((3, 64, 14, 14, 96, 1, 1, 1, 1, 0, 0), (1, 1), 0, None),               # 1x1
+    ((2, 96, 30, 30, 64, 3, 3, 2, 2, 1, 1), (1, 1), 0, None),               # stride 2 from 30 to 15 columns
+    ((2, 64, 20, 42, 128, 3, 3, 1, 1, 2, 2), (2, 2), 1, (0, 0, 8, 64)),     # 256-pixel tiles, dilated
+    ((1, 48, 12, 22, 256, 3, 3, 1, 1, 1, 1), (1, 1), 0, (0, 0, 12, 64)),    # 8 multiplying wavefronts: four units per moving thread
+    ((1, 128, 14, 14, 256, 1, 1, 2, 2, 0, 0), (1, 1), 0, None),             # 1x1 stride 2: every second row staged
 ]
 
 
