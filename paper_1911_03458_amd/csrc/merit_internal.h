@@ -133,7 +133,7 @@ int device_cu_count();          // compute units of the current device (256 on M
 
 // ---- pooling ---------------------------------------------------------------
 enum PoolVariant { POOL_TILE_GENERIC = 0, POOL_ROWS_K3S2P1 = 1, POOL_ROWS_K2S2P0 = 2, POOL_ROWS_K3S1P1 = 3,
-                   POOL_STREAM_K3S2P1 = 4, POOL_PLANE = 5, POOL_LANES_K3S2 = 6 };
+                   POOL_STREAM_K3S2P1 = 4, POOL_PLANE = 5, POOL_LANES_K3S2 = 6, POOL_LANES2_K3S2 = 7 };
 
 struct PoolParams {
     int NC, H, W, OH, OW;

@@ -350,6 +350,108 @@ __global__ __launch_bounds__(256) void merit_pool2d_lanes_k3s2(PoolParams p, con
     }
 }
 
+// ---------------------------------------------------------------------------
+// Stride-2 windows on any width of 8 and more -- 3x3 with padding 0 or 1 (K = 3), 2x2 without padding
+// (K = 2): a lane per TWO adjacent output columns, whose input columns 4j - pw .. 4j - pw + 3 are one
+// 16-byte load per input row (fp32 rows start on any 4-byte boundary, which is all a 16-byte global
+// load needs; K = 3 adds a 4-byte load for the fifth column) instead of six 4-byte loads.  The
+// 16-byte load is moved inside the row where the lane's columns cross an edge (start clamped to
+// [0, W - 4]) and the lane's columns are picked out of it by the distance d it was moved (-1 at the
+// left edge with padding, 1..3 at the right edge; a column that is not among the four is outside the
+// row: fill).  d and the validity of the fifth column are the same for every row of the strip.
+// A group of 4, 8, 16, 32 or 64 lanes (the smallest that holds a row of outputs, 128-column chunks
+// beyond that) owns LANES_TH output rows of one plane.  No LDS, no barrier; all loads of a strip are
+// issued before the first use.
+// ---------------------------------------------------------------------------
+typedef float float4u __attribute__((ext_vector_type(4), aligned(4)));
+
+template <bool AVG, int K>
+__global__ __launch_bounds__(256) void merit_pool2d_lanes2_s2(PoolParams p, const float *__restrict__ x,
+                                                             float *__restrict__ y)
+{
+    constexpr int ROWS = K == 3 ? 2 * LANES_TH + 1 : 2 * LANES_TH;
+    const int lane = threadIdx.x & 63;
+    const int wave = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lpi = 64 >> p.lg_shift;                        // lanes per item
+    const int l = lane & (lpi - 1);
+    const int item = (wave << p.lg_shift) + (lane >> (6 - p.lg_shift));
+    const bool live_item = item < p.items;
+    const int it = live_item ? item : 0;
+    const uint32_t q0 = fdiv((uint32_t)it, p.div_tiles_x);
+    const int chunk = it - (int)q0 * p.tiles_x;
+    const uint32_t nc = fdiv(q0, p.div_tiles_y);
+    const int strip = (int)q0 - (int)nc * p.tiles_y;
+    const int ox = chunk * 128 + 2 * l;                      // the lane's first output column
+    const int oy0 = strip * LANES_TH;
+    const int ytop = oy0 * 2 - p.ph;
+    const int c0 = min(2 * ox - p.pw, p.W);                  // first of the lane's input columns (>= -1)
+    const int s0 = min(max(c0, 0), p.W - 4);                 // start of the 16-byte load, inside the row
+    const int d = c0 - s0;                                   // -1 .. 4
+    const int c4 = c0 + 4;
+    const bool ok4 = c4 < p.W;
+    const int s4 = min(c4, p.W - 1);
+    const float fill = AVG ? 0.0f : -INFINITY;
+    const float *xp = x + (size_t)nc * p.H * p.W;
+
+    float4u a[ROWS];
+    float e[K == 3 ? ROWS : 1];
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        const int gy = ytop + r;
+        const bool rowok = gy >= 0 && gy < p.H;
+        const float *row = xp + (size_t)(rowok ? gy : 0) * p.W;
+        a[r] = *reinterpret_cast<const float4u *>(row + s0);
+        if constexpr (K == 3) e[r] = row[s4];
+    }
+    float ra[ROWS], rb[ROWS];
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        const int gy = ytop + r;
+        const bool rowok = gy >= 0 && gy < p.H;
+        float v[5];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int k = i + d;
+            const float t = k == 0 ? a[r].x : (k == 1 ? a[r].y : (k == 2 ? a[r].z : a[r].w));
+            v[i] = (rowok && k >= 0 && k <= 3) ? t : fill;
+        }
+        if constexpr (K == 3) {
+            v[4] = (rowok && ok4) ? e[r] : fill;
+            ra[r] = AVG ? (v[0] + v[1]) + v[2] : fmaxf(fmaxf(v[0], v[1]), v[2]);
+            rb[r] = AVG ? (v[2] + v[3]) + v[4] : fmaxf(fmaxf(v[2], v[3]), v[4]);
+        } else {
+            ra[r] = AVG ? v[0] + v[1] : fmaxf(v[0], v[1]);
+            rb[r] = AVG ? v[2] + v[3] : fmaxf(v[2], v[3]);
+        }
+    }
+    float *yp = y + (size_t)nc * p.OH * p.OW;
+#pragma unroll
+    for (int i = 0; i < LANES_TH; ++i) {
+        const int oy = oy0 + i;
+        float oa, ob;
+        if constexpr (K == 3) {
+            oa = AVG ? (ra[2 * i] + ra[2 * i + 1]) + ra[2 * i + 2] : fmaxf(fmaxf(ra[2 * i], ra[2 * i + 1]), ra[2 * i + 2]);
+            ob = AVG ? (rb[2 * i] + rb[2 * i + 1]) + rb[2 * i + 2] : fmaxf(fmaxf(rb[2 * i], rb[2 * i + 1]), rb[2 * i + 2]);
+        } else {
+            oa = AVG ? ra[2 * i] + ra[2 * i + 1] : fmaxf(ra[2 * i], ra[2 * i + 1]);
+            ob = AVG ? rb[2 * i] + rb[2 * i + 1] : fmaxf(rb[2 * i], rb[2 * i + 1]);
+        }
+        if (AVG) {
+            const int wy0 = 2 * oy - p.ph;
+            const int cy = max(min(wy0 + K, p.H) - max(wy0, 0), 0);
+            const int xa = 2 * ox - p.pw, xb = xa + 2;
+            const int ca = cy * max(min(xa + K, p.W) - max(xa, 0), 0);
+            const int cb = cy * max(min(xb + K, p.W) - max(xb, 0), 0);
+            oa = ca > 0 ? oa / (float)ca : 0.0f;
+            ob = cb > 0 ? ob / (float)cb : 0.0f;
+        }
+        if (live_item && oy < p.OH) {
+            if (ox < p.OW) yp[(size_t)oy * p.OW + ox] = oa;
+            if (ox + 1 < p.OW) yp[(size_t)oy * p.OW + ox + 1] = ob;
+        }
+    }
+}
+
 template <typename K>
 static hipError_t launch(K kernel, const PoolParams &p, const float *x, float *y, hipStream_t s,
                          size_t lds_bytes, uint32_t grid)
@@ -371,6 +473,12 @@ hipError_t launch_pool2d(const PoolParams &p, const float *x, float *y, hipStrea
     case POOL_LANES_K3S2:
         return p.is_avg ? launch(merit_pool2d_lanes_k3s2<true>, p, x, y, s, 0, grid)
                         : launch(merit_pool2d_lanes_k3s2<false>, p, x, y, s, 0, grid);
+    case POOL_LANES2_K3S2:
+        if (p.kh == 2)
+            return p.is_avg ? launch(merit_pool2d_lanes2_s2<true, 2>, p, x, y, s, 0, grid)
+                            : launch(merit_pool2d_lanes2_s2<false, 2>, p, x, y, s, 0, grid);
+        return p.is_avg ? launch(merit_pool2d_lanes2_s2<true, 3>, p, x, y, s, 0, grid)
+                        : launch(merit_pool2d_lanes2_s2<false, 3>, p, x, y, s, 0, grid);
     case POOL_PLANE:
         return p.is_avg ? launch(merit_pool2d_plane<true>, p, x, y, s, 0, grid)
                         : launch(merit_pool2d_plane<false>, p, x, y, s, 0, grid);
@@ -403,6 +511,9 @@ const char *pool_kernel_name(const PoolParams &p)
     switch (p.variant) {
     case POOL_PLANE: return p.is_avg ? "merit_pool2d_plane<avg>" : "merit_pool2d_plane<max>";
     case POOL_LANES_K3S2: return p.is_avg ? "merit_pool2d_lanes_k3s2<avg>" : "merit_pool2d_lanes_k3s2<max>";
+    case POOL_LANES2_K3S2:
+        if (p.kh == 2) return p.is_avg ? "merit_pool2d_lanes2_s2<avg,2>" : "merit_pool2d_lanes2_s2<max,2>";
+        return p.is_avg ? "merit_pool2d_lanes2_s2<avg,3>" : "merit_pool2d_lanes2_s2<max,3>";
     case POOL_STREAM_K3S2P1: return p.is_avg ? "merit_pool2d_stream_k3s2p1<avg>" : "merit_pool2d_stream_k3s2p1<max>";
     case POOL_ROWS_K3S2P1: return p.is_avg ? "merit_pool2d_rows<3,3,2,2,1,avg>" : "merit_pool2d_rows<3,3,2,2,1,max>";
     case POOL_ROWS_K2S2P0: return p.is_avg ? "merit_pool2d_rows<2,2,2,2,0,avg>" : "merit_pool2d_rows<2,2,2,2,0,max>";

@@ -607,7 +607,17 @@ def test_pool_plan_one_output_per_plane():
 
 def test_pool_plan_lane_per_column_for_odd_widths():
     li = mb.merit_plan_pool2d(32, 96, 55, 55, 3, 3, 2, 2, 0, 0, 0).launch_info()
-    assert li["kernel"] == "merit_pool2d_lanes_k3s2<max>" and li["lds_bytes"] == 0
-    assert li["grid"][0] == -(-(32 * 96 * 7) // 8)          # 7 strips of 4 rows, two items per wavefront
+    assert li["kernel"] == "merit_pool2d_lanes2_s2<max,3>" and li["lds_bytes"] == 0    # two output columns per lane
+    assert li["grid"][0] == -(-(32 * 96 * 7) // 16)         # 7 strips of 4 rows, 27 columns on 16 lanes: four items per wavefront
+    li = mb.merit_plan_pool2d(2, 3, 27, 27, 3, 3, 2, 2, 0, 0, 1).launch_info()         # 13 columns on 8 lanes: eight items per wavefront
+    assert li["kernel"] == "merit_pool2d_lanes2_s2<avg,3>" and li["grid"][0] == -(-(2 * 3 * 4) // 32)
+    li = mb.merit_plan_pool2d(2, 3, 9, 7, 3, 3, 2, 2, 1, 1, 1).launch_info()           # narrower than 8: a lane per column
+    assert li["kernel"] == "merit_pool2d_lanes_k3s2<avg>"
+    li = mb.merit_plan_pool2d(2, 3, 40, 301, 3, 3, 2, 2, 0, 0, 0).launch_info()        # 150 output columns: two chunks of 128
+    assert li["kernel"] == "merit_pool2d_lanes2_s2<max,3>" and li["grid"][0] == -(-(2 * 3 * 2 * 5) // 4)
+    # 2x2 / stride 2 where the output rows are not whole 16-byte vectors (28 -> 14, 14 -> 7)
+    li = mb.merit_plan_pool2d(8, 512, 28, 28, 2, 2, 2, 2, 0, 0, 0).launch_info()
+    assert li["kernel"] == "merit_pool2d_lanes2_s2<max,2>" and li["grid"][0] == -(-(8 * 512 * 4) // 32)
+    assert mb.merit_plan_pool2d(8, 64, 224, 224, 2, 2, 2, 2, 0, 0, 0).launch_info()["kernel"].startswith("merit_pool2d_rows")
     # the 16-byte kernels keep the shapes they take
     assert mb.merit_plan_pool2d(16, 64, 112, 112, 3, 3, 2, 2, 1, 1, 0).launch_info()["kernel"].startswith("merit_pool2d_stream")

@@ -60,6 +60,22 @@ POOL_CASES = [
     (1, 2, 9, 150, 3, 3, 2, 2, 1, 1),      # 75 outputs per row: two column chunks
     (1, 4, 6, 5, 3, 3, 2, 2, 0, 1),        # mixed padding, tiny plane
     (3, 7, 27, 27, 3, 3, 2, 2, 0, 0),      # items not a multiple of the wavefront's share
+    # ... two output columns per lane (W >= 8): the lane's columns picked out of a 16-byte load moved inside the row
+    (2, 3, 30, 301, 3, 3, 2, 2, 1, 1),     # 151 outputs per row: two chunks of 128, left padding, the last pair half outside
+    (1, 3, 21, 147, 3, 3, 2, 2, 0, 0),     # 73 outputs per row on 64 lanes
+    (2, 2, 17, 71, 3, 3, 2, 2, 0, 1),      # 36 outputs per row: the last lane's second column is outside
+    (3, 1, 10, 35, 3, 3, 2, 2, 1, 1),      # 18 outputs per row: the narrowest rows the kernel takes, 9 of 16 lanes
+    (1, 2, 11, 38, 3, 3, 2, 2, 1, 0),      # mixed padding
+    (1, 2, 12, 42, 3, 3, 2, 2, 0, 0),      # even width the 16-byte kernels do not take (OW % 4 != 0)
+    (3, 1, 10, 9, 3, 3, 2, 2, 1, 1),       # 9 columns on groups of 4 lanes: every lane's load is moved
+    (1, 2, 11, 8, 3, 3, 2, 2, 1, 0),       # the narrowest plane the kernel takes
+    # ... and 2x2 / stride 2 where the output rows are not whole 16-byte vectors
+    # (launches of 512 workgroups and more)
+    (8, 600, 28, 28, 2, 2, 2, 2, 0, 0),    # 14 outputs per row on 8 lanes
+    (40, 500, 14, 14, 2, 2, 2, 2, 0, 0),   # 7 outputs: the last lane's second column is outside the output
+    (66, 300, 15, 15, 2, 2, 2, 2, 0, 0),   # odd extents: the last row and column are not used
+    (9, 130, 9, 262, 2, 2, 2, 2, 0, 0),    # 131 outputs: two chunks
+    (64, 257, 10, 9, 2, 2, 2, 2, 0, 0),    # 9 columns: the second lane's load is moved
     # one output per plane: the wavefront-per-plane kernel
     (3, 37, 7, 7, 7, 7, 1, 1, 0, 0),       # global pooling of 7x7 planes, planes not a multiple of 4
     (1, 5, 9, 13, 9, 13, 2, 3, 0, 0),      # 117 elements: two rounds of lanes
