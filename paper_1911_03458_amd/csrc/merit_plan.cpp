@@ -162,7 +162,14 @@ merit_status derive_pool(merit_plan *pl)
         p.variant = variant = POOL_PLANE;
         p.TH = p.TW = 1; p.tiles_y = p.tiles_x = 1;
         p.RH = p.RW = p.pitch = 0;
-        const int64_t g = cdiv((int64_t)p.NC, 4);
+        // lanes per plane: about four in-range window elements each, 4 to 64
+        const int64_t y0 = std::max<int64_t>(-ph, 0), y1 = std::min<int64_t>(-ph + kh, H);
+        const int64_t x0 = std::max<int64_t>(-pw, 0), x1 = std::min<int64_t>(-pw + kw, W);
+        const int64_t rw = std::max<int64_t>(x1 - x0, 1), cnt = std::max<int64_t>(y1 - y0, 0) * rw;
+        int lg = 0;                                         // planes per wavefront = 1 << lg
+        while (lg < 4 && (64 >> (lg + 1)) * 4 >= cnt) ++lg;
+        p.lg_shift = lg;
+        const int64_t g = cdiv((int64_t)p.NC, 4 << lg);
         if (g >= (1ll << 31)) return MERIT_ERR_UNSUPPORTED;
         p.grid = (int)g;
     }

@@ -598,7 +598,9 @@ def test_conv_plans_for_layers_that_do_not_fit_lds_at_once():
 
 def test_pool_plan_one_output_per_plane():
     li = mb.merit_plan_pool2d(32, 512, 7, 7, 7, 7, 1, 1, 0, 0, 1).launch_info()
-    assert li["kernel"] == "merit_pool2d_plane<avg>" and li["grid"][0] == 32 * 512 // 4 and li["lds_bytes"] == 0
+    # 49 elements per plane: 16 lanes each, four planes per wavefront, sixteen per workgroup
+    assert li["kernel"] == "merit_pool2d_plane<avg>" and li["grid"][0] == 32 * 512 // 16 and li["lds_bytes"] == 0
+    assert mb.merit_plan_pool2d(2, 10, 40, 40, 40, 40, 1, 1, 0, 0, 0).launch_info()["grid"][0] == 5     # 1600 elements: a wavefront per plane
     p = mb.merit_plan_pool2d(1, 3, 5, 6, 7, 8, 1, 1, 1, 1, 0)
     assert p.out_shape() == (1, 3, 1, 1) and p.launch_info()["kernel"] == "merit_pool2d_plane<max>"
     p.set_tile((0, 0, 1, 1))                               # a tile request names the generic kernel
