@@ -181,6 +181,34 @@ def bench_pool(torch, mb, wl, steps, warmup, nsets):
     }
 
 
+def bench_pool_extra(torch, mb, wl, c, steps, warmup, nsets):
+    """One more pooling shape as an extra line: max pooling only, rotating buffers."""
+    x = wl.make_pool_input(c)
+    x0 = torch.from_numpy(x).to("cuda:0")
+    plan = mb.merit_plan_pool2d(c.N, c.C, c.H, c.W, c.kh, c.kw, c.sh, c.sw, c.ph, c.pw, 0)
+    out_shape = plan.out_shape()
+    n_out = 1
+    for e in out_shape:
+        n_out *= int(e)
+    alg_bytes = x.nbytes + n_out * 4
+    xs = [x0] + [x0.roll(i, dims=0).contiguous() for i in range(1, nsets)]
+    ys = [torch.empty(out_shape, dtype=torch.float32, device="cuda:0") for _ in range(nsets)]
+    calls = [mb.bind_pool2d(plan, xs[i], ys[i]) for i in range(nsets)]
+    wall, ev_ms = timed_region(torch, lambda i: calls[i % nsets](), steps, warmup)
+    t = ev_ms * 1e-3 / steps
+    import oracle
+    cpu = oracle_rate(lambda: oracle.pool2d(x, (c.kh, c.kw), (c.sh, c.sw), (c.ph, c.pw), "max"), n_out, "full batch, max")
+    return {
+        "workload": c.name + " (max)", "kernel": plan.launch_info()["kernel"], "avg_launch_us": t * 1e6, "launches": steps,
+        "cpu_baseline": cpu,
+        "out_elems_per_s": n_out / t,
+        "achieved_hbm_gbs": alg_bytes / t / 1e9, "hbm_frac": alg_bytes / t / 1e9 / HBM_PEAK_GBS,
+        "rotating_sets": nsets,
+        "roofline": {"bound": "hbm", "achieved": alg_bytes / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": alg_bytes / t / 1e9 / HBM_PEAK_GBS},
+    }
+
+
 def bench_sad(torch, mb, wl, cfg, steps, warmup):
     cur, ref, _ = wl.make_sad_frames(cfg)
     dcur, dref = torch.from_numpy(cur).to("cuda:0"), torch.from_numpy(ref).to("cuda:0")
@@ -524,6 +552,7 @@ def main():
         kl = k
         extras = [
             (wl.CFG0_ME_SMALL.name, lambda: bench_sad(torch, mb, wl, wl.CFG0_ME_SMALL, k, w)),
+            (wl.CFG_POOL_ODD.name, lambda: bench_pool_extra(torch, mb, wl, wl.CFG_POOL_ODD, k, w, args.sets)),
             (wl.CFG2_CONV3.name, lambda: bench_conv(torch, mb, wl, wl.CFG2_CONV3, k, w, args.sets)),
             (wl.CFG3_ME_FHD.name, lambda: bench_sad(torch, mb, wl, wl.CFG3_ME_FHD, kl, w)),
             (wl.CFG_ME_720P.name, lambda: bench_sad(torch, mb, wl, wl.CFG_ME_720P, k, w)),

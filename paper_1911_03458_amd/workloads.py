@@ -100,6 +100,9 @@ class ConvWorkload:
 
 CFG0_ME_SMALL = SadWorkload("me_64x64_b8_r4", 64, 64, 8, 4, 3, "uniform")
 CFG1_POOL = PoolWorkload("pool_16x64x112x112_k3s2p1", 16, 64, 112, 112, 3, 3, 2, 2, 1, 1)
+# an odd width and no padding: the first pooling layer of AlexNet (55 x 55 -> 27 x 27), which the 16-byte
+# row kernels do not take
+CFG_POOL_ODD = PoolWorkload("pool_32x96x55x55_k3s2p0", 32, 96, 55, 55, 3, 3, 2, 2, 0, 0)
 CFG2_CONV3 = ConvWorkload("conv_8x64x56x56_co64_k3s1p1", 8, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1, "normal")
 CFG3_ME_FHD = SadWorkload("me_1920x1088_b16_r32", 1088, 1920, 16, 32, 0, "sinusoid")
 CFG4_CONV7 = ConvWorkload("conv_32x3x224x224_co64_k7s2p3", 32, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3, "uniform")
