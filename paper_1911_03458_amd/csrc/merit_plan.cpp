@@ -133,20 +133,24 @@ merit_status derive_pool(merit_plan *pl)
     // 3x3 / stride 2 (padding 0 or 1) and 2x2 / stride 2 (no padding) on a width the 16-byte kernels do not
     // take: a lane per two output columns, whose input columns are one 16-byte load (W >= 8), in groups of
     // 4 to 64 lanes; 3x3 on narrower planes: a lane per output column
+    // (3x3 at stride 1, the pooling branch of an inception module on 35, 17 and 7 columns: the same kernel, 8 output rows
+    // per group, any width of 4 and more)
     const bool k3 = kh == 3 && kw == 3 && ph <= 1 && pw <= 1, k2 = kh == 2 && kw == 2 && ph == 0 && pw == 0 && W >= 8;
-    if (variant == POOL_TILE_GENERIC && (k3 || k2) && sh == 2 && sw == 2 &&
+    const bool s1 = k3 && sh == 1 && sw == 1 && W >= 4;
+    if (variant == POOL_TILE_GENERIC && (((k3 || k2) && sh == 2 && sw == 2) || s1) &&
         !(OH == 1 && OW == 1) && pl->tile_req[2] <= 0 && pl->tile_req[3] <= 0 && H * W < INT_LIMIT) {
-        const bool two = W >= 8;
+        const bool two = W >= 8 || s1;
+        const int64_t th = s1 ? 8 : 4;
         const int64_t cols = two ? 128 : 64;                // output columns of a full group of 64 lanes
         int lg_shift = 0;                                   // items per wavefront = 1 << lg_shift
         while (lg_shift < (two ? 4 : 2) && (cols >> (lg_shift + 1)) >= OW) ++lg_shift;
-        const int64_t chunks = cdiv(OW, cols), strips = cdiv(OH, 4);
+        const int64_t chunks = cdiv(OW, cols), strips = cdiv(OH, th);
         const int64_t items = N * C * chunks * strips;
         // (2x2 windows on small launches stay on the tile kernel: 8 x 512 x 14 x 14 is 128 workgroups here, 6.1 us against 5.5)
         if (items < INT_LIMIT && fastdiv_ok(items, chunks) && fastdiv_ok(items, strips) &&
-            (k3 || cdiv(items, 4 * (1 << lg_shift)) >= 512)) {
+            (k3 || s1 || cdiv(items, 4 * (1 << lg_shift)) >= 512)) {
             p.variant = variant = two ? POOL_LANES2_K3S2 : POOL_LANES_K3S2;
-            p.TH = 4; p.TW = (int)(OW < cols ? OW : cols);
+            p.TH = (int)th; p.TW = (int)(OW < cols ? OW : cols);
             p.tiles_y = (int)strips; p.tiles_x = (int)chunks;
             p.RH = p.RW = p.pitch = 0;
             p.lg_shift = lg_shift;

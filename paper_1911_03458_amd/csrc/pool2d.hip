@@ -378,16 +378,21 @@ __global__ __launch_bounds__(256) void merit_pool2d_lanes_k3s2(PoolParams p, con
 // left edge with padding, 1..3 at the right edge; a column that is not among the four is outside the
 // row: fill).  d and the validity of the fifth column are the same for every row of the strip.
 // A group of 4, 8, 16, 32 or 64 lanes (the smallest that holds a row of outputs, 128-column chunks
-// beyond that) owns LANES_TH output rows of one plane.  No LDS, no barrier; all loads of a strip are
+// beyond that) owns LANES_TH output rows of one plane.  The same for 3x3 windows at stride 1 (S = 1).  No LDS, no barrier; all loads of a strip are
 // issued before the first use.
 // ---------------------------------------------------------------------------
 typedef float float4u __attribute__((ext_vector_type(4), aligned(4)));
 
-template <bool AVG, int K>
+template <bool AVG, int K, int S = 2>
 __global__ __launch_bounds__(256) void merit_pool2d_lanes2_s2(PoolParams p, const float *__restrict__ x,
                                                              float *__restrict__ y)
 {
-    constexpr int ROWS = K == 3 ? 2 * LANES_TH + 1 : 2 * LANES_TH;
+    // S = 1 (3x3 windows, padding 0 or 1; any width of 4 and more): the two outputs' columns ox - pw ..
+    // ox - pw + 3 are the 16-byte load alone; 8 output rows per group from 10 input rows
+    static_assert(S == 2 || K == 3, "stride 1: 3x3 windows");
+    constexpr int TH = S == 1 ? 8 : LANES_TH;
+    constexpr int ROWS = S == 1 ? TH + 2 : (K == 3 ? 2 * TH + 1 : 2 * TH);
+    constexpr bool FIFTH = K == 3 && S == 2;
     const int lane = threadIdx.x & 63;
     const int wave = blockIdx.x * 4 + (threadIdx.x >> 6);
     const int lpi = 64 >> p.lg_shift;                        // lanes per item
@@ -400,9 +405,9 @@ __global__ __launch_bounds__(256) void merit_pool2d_lanes2_s2(PoolParams p, cons
     const uint32_t nc = fdiv(q0, p.div_tiles_y);
     const int strip = (int)q0 - (int)nc * p.tiles_y;
     const int ox = chunk * 128 + 2 * l;                      // the lane's first output column
-    const int oy0 = strip * LANES_TH;
-    const int ytop = oy0 * 2 - p.ph;
-    const int c0 = min(2 * ox - p.pw, p.W);                  // first of the lane's input columns (>= -1)
+    const int oy0 = strip * TH;
+    const int ytop = oy0 * S - p.ph;
+    const int c0 = min(S * ox - p.pw, p.W);                  // first of the lane's input columns (>= -1)
     const int s0 = min(max(c0, 0), p.W - 4);                 // start of the 16-byte load, inside the row
     const int d = c0 - s0;                                   // -1 .. 4
     const int c4 = c0 + 4;
@@ -412,14 +417,14 @@ __global__ __launch_bounds__(256) void merit_pool2d_lanes2_s2(PoolParams p, cons
     const float *xp = x + (size_t)nc * p.H * p.W;
 
     float4u a[ROWS];
-    float e[K == 3 ? ROWS : 1];
+    float e[FIFTH ? ROWS : 1];
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
         const int gy = ytop + r;
         const bool rowok = gy >= 0 && gy < p.H;
         const float *row = xp + (size_t)(rowok ? gy : 0) * p.W;
         a[r] = *reinterpret_cast<const float4u *>(row + s0);
-        if constexpr (K == 3) e[r] = row[s4];
+        if constexpr (FIFTH) e[r] = row[s4];
     }
     float ra[ROWS], rb[ROWS];
 #pragma unroll
@@ -433,10 +438,13 @@ __global__ __launch_bounds__(256) void merit_pool2d_lanes2_s2(PoolParams p, cons
             const float t = k == 0 ? a[r].x : (k == 1 ? a[r].y : (k == 2 ? a[r].z : a[r].w));
             v[i] = (rowok && k >= 0 && k <= 3) ? t : fill;
         }
-        if constexpr (K == 3) {
+        if constexpr (FIFTH) {
             v[4] = (rowok && ok4) ? e[r] : fill;
             ra[r] = AVG ? (v[0] + v[1]) + v[2] : fmaxf(fmaxf(v[0], v[1]), v[2]);
             rb[r] = AVG ? (v[2] + v[3]) + v[4] : fmaxf(fmaxf(v[2], v[3]), v[4]);
+        } else if constexpr (S == 1) {
+            ra[r] = AVG ? (v[0] + v[1]) + v[2] : fmaxf(fmaxf(v[0], v[1]), v[2]);
+            rb[r] = AVG ? (v[1] + v[2]) + v[3] : fmaxf(fmaxf(v[1], v[2]), v[3]);
         } else {
             ra[r] = AVG ? v[0] + v[1] : fmaxf(v[0], v[1]);
             rb[r] = AVG ? v[2] + v[3] : fmaxf(v[2], v[3]);
@@ -444,20 +452,21 @@ __global__ __launch_bounds__(256) void merit_pool2d_lanes2_s2(PoolParams p, cons
     }
     float *yp = y + (size_t)nc * p.OH * p.OW;
 #pragma unroll
-    for (int i = 0; i < LANES_TH; ++i) {
+    for (int i = 0; i < TH; ++i) {
         const int oy = oy0 + i;
+        const int r0 = S * i;
         float oa, ob;
         if constexpr (K == 3) {
-            oa = AVG ? (ra[2 * i] + ra[2 * i + 1]) + ra[2 * i + 2] : fmaxf(fmaxf(ra[2 * i], ra[2 * i + 1]), ra[2 * i + 2]);
-            ob = AVG ? (rb[2 * i] + rb[2 * i + 1]) + rb[2 * i + 2] : fmaxf(fmaxf(rb[2 * i], rb[2 * i + 1]), rb[2 * i + 2]);
+            oa = AVG ? (ra[r0] + ra[r0 + 1]) + ra[r0 + 2] : fmaxf(fmaxf(ra[r0], ra[r0 + 1]), ra[r0 + 2]);
+            ob = AVG ? (rb[r0] + rb[r0 + 1]) + rb[r0 + 2] : fmaxf(fmaxf(rb[r0], rb[r0 + 1]), rb[r0 + 2]);
         } else {
-            oa = AVG ? ra[2 * i] + ra[2 * i + 1] : fmaxf(ra[2 * i], ra[2 * i + 1]);
-            ob = AVG ? rb[2 * i] + rb[2 * i + 1] : fmaxf(rb[2 * i], rb[2 * i + 1]);
+            oa = AVG ? ra[r0] + ra[r0 + 1] : fmaxf(ra[r0], ra[r0 + 1]);
+            ob = AVG ? rb[r0] + rb[r0 + 1] : fmaxf(rb[r0], rb[r0 + 1]);
         }
         if (AVG) {
-            const int wy0 = 2 * oy - p.ph;
+            const int wy0 = S * oy - p.ph;
             const int cy = max(min(wy0 + K, p.H) - max(wy0, 0), 0);
-            const int xa = 2 * ox - p.pw, xb = xa + 2;
+            const int xa = S * ox - p.pw, xb = xa + S;
             const int ca = cy * max(min(xa + K, p.W) - max(xa, 0), 0);
             const int cb = cy * max(min(xb + K, p.W) - max(xb, 0), 0);
             oa = ca > 0 ? oa / (float)ca : 0.0f;
@@ -492,6 +501,9 @@ hipError_t launch_pool2d(const PoolParams &p, const float *x, float *y, hipStrea
         return p.is_avg ? launch(merit_pool2d_lanes_k3s2<true>, p, x, y, s, 0, grid)
                         : launch(merit_pool2d_lanes_k3s2<false>, p, x, y, s, 0, grid);
     case POOL_LANES2_K3S2:
+        if (p.sh == 1)
+            return p.is_avg ? launch(merit_pool2d_lanes2_s2<true, 3, 1>, p, x, y, s, 0, grid)
+                            : launch(merit_pool2d_lanes2_s2<false, 3, 1>, p, x, y, s, 0, grid);
         if (p.kh == 2)
             return p.is_avg ? launch(merit_pool2d_lanes2_s2<true, 2>, p, x, y, s, 0, grid)
                             : launch(merit_pool2d_lanes2_s2<false, 2>, p, x, y, s, 0, grid);
@@ -530,6 +542,7 @@ const char *pool_kernel_name(const PoolParams &p)
     case POOL_PLANE: return p.is_avg ? "merit_pool2d_plane<avg>" : "merit_pool2d_plane<max>";
     case POOL_LANES_K3S2: return p.is_avg ? "merit_pool2d_lanes_k3s2<avg>" : "merit_pool2d_lanes_k3s2<max>";
     case POOL_LANES2_K3S2:
+        if (p.sh == 1) return p.is_avg ? "merit_pool2d_lanes2_s2<avg,3,1>" : "merit_pool2d_lanes2_s2<max,3,1>";
         if (p.kh == 2) return p.is_avg ? "merit_pool2d_lanes2_s2<avg,2>" : "merit_pool2d_lanes2_s2<max,2>";
         return p.is_avg ? "merit_pool2d_lanes2_s2<avg,3>" : "merit_pool2d_lanes2_s2<max,3>";
     case POOL_STREAM_K3S2P1: return p.is_avg ? "merit_pool2d_stream_k3s2p1<avg>" : "merit_pool2d_stream_k3s2p1<max>";

@@ -617,6 +617,10 @@ def test_pool_plan_lane_per_column_for_odd_widths():
     assert li["kernel"] == "merit_pool2d_lanes_k3s2<avg>"
     li = mb.merit_plan_pool2d(2, 3, 40, 301, 3, 3, 2, 2, 0, 0, 0).launch_info()        # 150 output columns: two chunks of 128
     assert li["kernel"] == "merit_pool2d_lanes2_s2<max,3>" and li["grid"][0] == -(-(2 * 3 * 2 * 5) // 4)
+    # 3x3 / stride 1 on widths the row kernel does not take (the pooling branch of an inception module)
+    li = mb.merit_plan_pool2d(32, 288, 35, 35, 3, 3, 1, 1, 1, 1, 1).launch_info()
+    assert li["kernel"] == "merit_pool2d_lanes2_s2<avg,3,1>" and li["grid"][0] == -(-(32 * 288 * 5) // 8)   # 5 strips of 8 rows, 32 lanes each
+    assert mb.merit_plan_pool2d(32, 192, 28, 28, 3, 3, 1, 1, 1, 1, 0).launch_info()["kernel"].startswith("merit_pool2d_rows")
     # 2x2 / stride 2 where the output rows are not whole 16-byte vectors (28 -> 14, 14 -> 7)
     li = mb.merit_plan_pool2d(8, 512, 28, 28, 2, 2, 2, 2, 0, 0, 0).launch_info()
     assert li["kernel"] == "merit_pool2d_lanes2_s2<max,2>" and li["grid"][0] == -(-(8 * 512 * 4) // 32)

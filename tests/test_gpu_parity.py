@@ -70,6 +70,14 @@ POOL_CASES = [
     (3, 1, 10, 9, 3, 3, 2, 2, 1, 1),       # 9 columns on groups of 4 lanes: every lane's load is moved
     (1, 2, 11, 8, 3, 3, 2, 2, 1, 0),       # the narrowest plane the kernel takes
     # ... and 2x2 / stride 2 where the output rows are not whole 16-byte vectors
+    # ... and 3x3 at stride 1 (8 output rows per group; any width of 4 and more)
+    (2, 5, 35, 35, 3, 3, 1, 1, 1, 1),      # 35 outputs per row on 32 lanes, five strips with a ragged last one
+    (3, 7, 17, 17, 3, 3, 1, 1, 1, 1),      # 17 outputs on 16 lanes
+    (2, 9, 7, 7, 3, 3, 1, 1, 1, 1),        # 7 outputs on 4 lanes: sixteen items per wavefront
+    (1, 3, 9, 5, 3, 3, 1, 1, 0, 1),        # mixed padding, 5 columns
+    (1, 2, 21, 150, 3, 3, 1, 1, 1, 1),     # two chunks of 128 outputs
+    (2, 3, 10, 4, 3, 3, 1, 1, 1, 1),       # the narrowest plane the kernel takes
+    (1, 2, 12, 13, 3, 3, 1, 1, 0, 0),      # no padding: 11 outputs from 13 columns
     # (launches of 512 workgroups and more)
     (8, 600, 28, 28, 2, 2, 2, 2, 0, 0),    # 14 outputs per row on 8 lanes
     (40, 500, 14, 14, 2, 2, 2, 2, 0, 0),   # 7 outputs: the last lane's second column is outside the output
