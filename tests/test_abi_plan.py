@@ -620,7 +620,8 @@ def test_pool_plan_lane_per_column_for_odd_widths():
     # 3x3 / stride 1 on widths the row kernel does not take (the pooling branch of an inception module)
     li = mb.merit_plan_pool2d(32, 288, 35, 35, 3, 3, 1, 1, 1, 1, 1).launch_info()
     assert li["kernel"] == "merit_pool2d_lanes2_s2<avg,3,1>" and li["grid"][0] == -(-(32 * 288 * 5) // 8)   # 5 strips of 8 rows, 32 lanes each
-    assert mb.merit_plan_pool2d(32, 192, 28, 28, 3, 3, 1, 1, 1, 1, 0).launch_info()["kernel"].startswith("merit_pool2d_rows")
+    assert mb.merit_plan_pool2d(32, 192, 28, 28, 3, 3, 1, 1, 1, 1, 0).launch_info()["kernel"] == "merit_pool2d_lanes2_s2<max,3,1>"
+    assert mb.merit_plan_pool2d(32, 192, 28, 28, 3, 3, 1, 1, 1, 1, 0).set_tile((0, 0, 7)).launch_info()["kernel"].startswith("merit_pool2d_rows<3,3,1,1,1")
     # 2x2 / stride 2 where the output rows are not whole 16-byte vectors (28 -> 14, 14 -> 7)
     li = mb.merit_plan_pool2d(8, 512, 28, 28, 2, 2, 2, 2, 0, 0, 0).launch_info()
     assert li["kernel"] == "merit_pool2d_lanes2_s2<max,2>" and li["grid"][0] == -(-(8 * 512 * 4) // 32)

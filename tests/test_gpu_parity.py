@@ -134,6 +134,23 @@ def test_pool_tile_override(mb, th):
             assert bool(np.all(np.abs(got - ref) <= 1e-5 * np.abs(ref) + 1e-6))
 
 
+@pytest.mark.parametrize("th", [4, 9])
+def test_pool_stride_1_row_strips_on_request(mb, th):
+    # 3x3 / stride 1 / padding 1: the planner takes the two-columns-per-lane kernel; a strip height asks for the row-strip one
+    rng = np.random.default_rng(40 + th)
+    x = rng.standard_normal((2, 3, 20, 24)).astype(np.float32)
+    for is_avg, mode in ((0, "max"), (1, "avg")):
+        assert mb.merit_plan_pool2d(2, 3, 20, 24, 3, 3, 1, 1, 1, 1, is_avg).launch_info()["kernel"].startswith("merit_pool2d_lanes2_s2")
+        plan = mb.merit_plan_pool2d(2, 3, 20, 24, 3, 3, 1, 1, 1, 1, is_avg).set_tile((0, 0, th))
+        assert plan.launch_info()["kernel"].startswith("merit_pool2d_rows<3,3,1,1,1")
+        got = mb.merit_pool2d(plan, dev(x)).cpu().numpy()
+        ref = oracle.pool2d(x, (3, 3), (1, 1), (1, 1), mode)
+        if mode == "max":
+            assert np.array_equal(got, ref)
+        else:
+            assert bool(np.all(np.abs(got - ref) <= 1e-5 * np.abs(ref) + 1e-6))
+
+
 @pytest.mark.parametrize("mode", ["max", "avg"])
 def test_pool_full_workload(mb, mode):
     c = wl.CFG1_POOL
